@@ -1,0 +1,114 @@
+/*
+ * longconv — batched causal long convolution for AMD Instinct MI355X (gfx950).
+ *
+ *     y[b,h,t] = sum_{s=0..t} k[h,s] * u[b,h,t-s] + D[h] * u[b,h,t]      0 <= t < N
+ *
+ * (paper Eq. 1 and Algorithm 1 line 4: convolution along the sequence axis, skip
+ * term per head), computed as the FFT convolution of Eq. 2 on the sequence zero
+ * padded to 2N, with the FFT factored into small dense DFT blocks (Section 3.2,
+ * "Butterfly Decomposition"; twiddles as in Appendix C.1), the whole chain
+ * FFT -> pointwise multiply -> inverse FFT fused in one kernel (Section 3.2,
+ * "Kernel Fusion"), the kernel spectrum precomputed once per head (Algorithm 2
+ * lines 1-2) and a multi-pass decomposition for sequences that do not fit on chip
+ * (Section 3.2 "Three-Pass Algorithm", Eq. 3).  The backward pass (not described
+ * in the paper) is the exact adjoint:
+ *
+ *     du[b,h,s] = sum_{t>=s} k[h,t-s] * dy[b,h,t] + D[h] * dy[b,h,s]
+ *     dk[h,s]   = sum_b sum_{t>=s} dy[b,h,t] * u[b,h,t-s]
+ *     dD[h]     = sum_b sum_t dy[b,h,t] * u[b,h,t]
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless stated otherwise.  Tensors are
+ *     dense, row-major, N fastest: u, y, dy, du are [B,H,N] in the I/O dtype;
+ *     k, dk are [H,N] float32; D, dD are [H] float32.  Base pointers must be
+ *     16-byte aligned.  Outputs must not alias inputs.
+ *   - N must be a power of two with 256 <= N <= 131072; B >= 1; H >= 1.
+ *   - The caller owns every buffer.  The library allocates no per-call device
+ *     memory, frees nothing, never synchronises the stream and enqueues work only
+ *     on `stream` (a hipStream_t passed as void*; NULL is the default stream).
+ *     The only library-owned state is one immutable twiddle table per device,
+ *     filled by longconv_init() (or lazily by the first call on that device,
+ *     which then synchronises `stream` once).
+ *   - Return value: LONGCONV_OK or an error code; argument validation happens
+ *     before anything is launched.  No exceptions, no aborts.
+ *   - fp16/bf16 I/O computes with fp16 matrix-core operands and fp32 accumulation;
+ *     |values| of u, dy and of the transformed data must stay inside fp16 range
+ *     (unit-variance activations up to N = 131072 are).  fp32 I/O computes in fp32.
+ */
+#ifndef LONGCONV_H
+#define LONGCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LONGCONV_F32 = 0, LONGCONV_F16 = 1, LONGCONV_BF16 = 2 } longconv_dtype_t;
+
+typedef enum {
+    LONGCONV_OK = 0,
+    LONGCONV_ERR_NULL = 1,       /* a required pointer is NULL */
+    LONGCONV_ERR_SHAPE = 2,      /* B or H < 1, N not a power of two or out of range */
+    LONGCONV_ERR_DTYPE = 3,      /* dtype not one of longconv_dtype_t */
+    LONGCONV_ERR_ALIGN = 4,      /* a pointer is not 16-byte aligned */
+    LONGCONV_ERR_WORKSPACE = 5,  /* workspace NULL or smaller than longconv_workspace_bytes() */
+    LONGCONV_ERR_HIP = 6         /* a HIP call failed; see longconv_last_hip_error() */
+} longconv_status_t;
+
+/* Fill the per-device constant tables for the current device.  Optional: the
+ * first compute call on a device does it (and synchronises its stream once).
+ * Call it explicitly before capturing a HIP graph. */
+int longconv_init(void);
+
+/* Size in bytes of the spectrum cache for H heads of length N (0 on bad args).
+ * The cache holds, per head, the 2N-point spectrum of [k[h,:], 0_N] plus D[h]
+ * (the skip term is a delta kernel of height D[h]), pre-scaled and stored in the
+ * permuted order the fused transform produces (Algorithm 2 lines 1-2: the
+ * spectrum is computed once and stored already permuted, so no permutation ever
+ * touches u).  Layout is private to the library and depends on (N, io). */
+size_t longconv_kspec_bytes(int64_t H, int64_t N, int io);
+
+/* Scratch bytes a call needs (0 on bad args).  `backward` = 0 for longconv_fwd,
+ * 1 for longconv_bwd.  The figure includes room for an on-the-fly spectrum, so it
+ * is valid whether or not a cached spectrum is passed. */
+size_t longconv_workspace_bytes(int64_t B, int64_t H, int64_t N, int io, int backward);
+
+/* Kernel-spectrum precompute (Algorithm 2 lines 1-2; Appendix D.1: the spectrum is
+ * shared by all inputs of a batch).  k [H,N] f32, D [H] f32 -> kspec
+ * (longconv_kspec_bytes).  Valid until k or D change.  Needs a workspace of
+ * longconv_workspace_bytes(1,H,N,io,0) bytes. */
+int longconv_kspec_compute(const float* k, const float* D, void* kspec, int64_t H, int64_t N, int io,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Forward (Eq. 1 via Eq. 2, fused; Algorithm 1 line 4).  kspec may be NULL: the
+ * spectrum is then computed into the workspace by this call (k and D are read
+ * only in that case; with a cached spectrum they may be NULL). */
+int longconv_fwd(const void* u, const float* k, const float* D, const void* kspec, void* y,
+                 int64_t B, int64_t H, int64_t N, int io,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward: du, dk, dD as defined above.  Any of the three output pointers may be
+ * NULL to skip that gradient.  dk and dD are overwritten (not accumulated) and are
+ * summed over b in a fixed order (bitwise repeatable).  kspec as in longconv_fwd
+ * (only needed for du). */
+int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, const void* kspec,
+                 void* du, float* dk, float* dD,
+                 int64_t B, int64_t H, int64_t N, int io,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static text for a status code. */
+const char* longconv_status_string(int status);
+
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char* longconv_last_hip_error(void);
+
+/* Human-readable description of the plan chosen for (N, io): engine, factorisation
+ * of 2N, number of passes.  Returns a pointer to a thread-local buffer. */
+const char* longconv_plan_string(int64_t N, int io);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LONGCONV_H */

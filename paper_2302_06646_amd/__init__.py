@@ -1,0 +1,154 @@
+"""Thin Python binding of liblongconv (argument marshalling only).
+
+Every step of the path — spectrum precompute, FFT stages, pointwise product,
+inverse, truncation, skip term, gradients — runs inside the HIP kernels of
+``liblongconv.so``; PyTorch is used here only to own device memory and to name
+the stream.  There is no CPU fallback: if the library is missing, importing
+the functions raises.
+
+Functions mirror the C ABI of ``include/longconv.h``:
+    longconv_init, longconv_kspec_bytes, longconv_workspace_bytes,
+    longconv_kspec_compute, longconv_fwd, longconv_bwd, longconv_plan_string
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+F32, F16, BF16 = 0, 1, 2
+_TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
+_CODE = {v: k for k, v in _TORCH_DTYPE.items()}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblongconv.so")
+_lib = None
+
+EXPORTS = ("longconv_init", "longconv_kspec_bytes", "longconv_workspace_bytes",
+           "longconv_kspec_compute", "longconv_fwd", "longconv_bwd", "longconv_status_string",
+           "longconv_last_hip_error", "longconv_plan_string")
+
+
+class LongconvError(RuntimeError):
+    pass
+
+
+def lib():
+    """Load liblongconv.so (built by ``python -m paper_2302_06646_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise LongconvError(f"{LIB_PATH} not found: build it with "
+                                "`python -m paper_2302_06646_amd.build` (no fallback path exists)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, sz, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int
+        L.longconv_init.restype = ci
+        L.longconv_kspec_bytes.restype = sz
+        L.longconv_kspec_bytes.argtypes = [i64, i64, ci]
+        L.longconv_workspace_bytes.restype = sz
+        L.longconv_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
+        L.longconv_kspec_compute.restype = ci
+        L.longconv_kspec_compute.argtypes = [vp, vp, vp, i64, i64, ci, vp, sz, vp]
+        L.longconv_fwd.restype = ci
+        L.longconv_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, sz, vp]
+        L.longconv_bwd.restype = ci
+        L.longconv_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, sz, vp]
+        L.longconv_status_string.restype = ctypes.c_char_p
+        L.longconv_status_string.argtypes = [ci]
+        L.longconv_last_hip_error.restype = ctypes.c_char_p
+        L.longconv_plan_string.restype = ctypes.c_char_p
+        L.longconv_plan_string.argtypes = [i64, ci]
+        _lib = L
+    return _lib
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        L = lib()
+        msg = L.longconv_status_string(status).decode()
+        hip = L.longconv_last_hip_error().decode()
+        raise LongconvError(f"{what}: {msg}" + (f" [{hip}]" if status == 6 and hip else ""))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _need(t, name, dtype, shape):
+    if t is None:
+        return
+    if not t.is_cuda or not t.is_contiguous():
+        raise LongconvError(f"{name} must be a contiguous device tensor")
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise LongconvError(f"{name}: expected {dtype} {tuple(shape)}, got {t.dtype} {tuple(t.shape)}")
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    return _CODE[t.dtype]
+
+
+def longconv_init() -> None:
+    _check(lib().longconv_init(), "longconv_init")
+
+
+def longconv_kspec_bytes(H: int, N: int, io: int) -> int:
+    return int(lib().longconv_kspec_bytes(H, N, io))
+
+
+def longconv_workspace_bytes(B: int, H: int, N: int, io: int, backward: bool) -> int:
+    return int(lib().longconv_workspace_bytes(B, H, N, io, 1 if backward else 0))
+
+
+def longconv_plan_string(N: int, io: int) -> str:
+    return lib().longconv_plan_string(N, io).decode()
+
+
+def new_workspace(B, H, N, io, backward, device="cuda"):
+    """Allocate a workspace tensor of the size the library asks for (caller-owned)."""
+    n = longconv_workspace_bytes(B, H, N, io, backward)
+    if n == 0:
+        raise LongconvError("bad shape or dtype")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def new_kspec(H, N, io, device="cuda"):
+    n = longconv_kspec_bytes(H, N, io)
+    if n == 0:
+        raise LongconvError("bad shape or dtype")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def longconv_kspec_compute(k, D, kspec, io: int, workspace, stream=None) -> None:
+    H, N = k.shape
+    _need(k, "k", torch.float32, (H, N)); _need(D, "D", torch.float32, (H,))
+    _check(lib().longconv_kspec_compute(_ptr(k), _ptr(D), _ptr(kspec), H, N, io, _ptr(workspace),
+                                        0 if workspace is None else workspace.numel(), _stream(stream)),
+           "longconv_kspec_compute")
+
+
+def longconv_fwd(u, k, D, y, workspace, kspec=None, stream=None) -> None:
+    """y <- (u * k)[:N] + D u.  All tensors caller-allocated on the device."""
+    B, H, N = u.shape
+    io = dtype_code(u)
+    _need(u, "u", _TORCH_DTYPE[io], (B, H, N)); _need(y, "y", _TORCH_DTYPE[io], (B, H, N))
+    _need(k, "k", torch.float32, (H, N)); _need(D, "D", torch.float32, (H,))
+    _check(lib().longconv_fwd(_ptr(u), _ptr(k), _ptr(D), _ptr(kspec), _ptr(y), B, H, N, io,
+                              _ptr(workspace), workspace.numel(), _stream(stream)), "longconv_fwd")
+
+
+def longconv_bwd(dy, u, k, D, du, dk, dD, workspace, kspec=None, stream=None) -> None:
+    """du, dk, dD <- adjoints (any of the three may be None to skip it)."""
+    B, H, N = dy.shape
+    io = dtype_code(dy)
+    _need(dy, "dy", _TORCH_DTYPE[io], (B, H, N)); _need(u, "u", _TORCH_DTYPE[io], (B, H, N))
+    _need(du, "du", _TORCH_DTYPE[io], (B, H, N))
+    _need(k, "k", torch.float32, (H, N)); _need(D, "D", torch.float32, (H,))
+    _need(dk, "dk", torch.float32, (H, N)); _need(dD, "dD", torch.float32, (H,))
+    _check(lib().longconv_bwd(_ptr(dy), _ptr(u), _ptr(k), _ptr(D), _ptr(kspec), _ptr(du), _ptr(dk), _ptr(dD),
+                              B, H, N, io, _ptr(workspace), workspace.numel(), _stream(stream)), "longconv_bwd")

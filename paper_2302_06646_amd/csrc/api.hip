@@ -1,0 +1,334 @@
+// C-ABI layer of liblongconv: argument validation, planning, workspace carving, dispatch.
+// Every step of the path runs in the kernels of engine_valu.hip / engine_mfma.hip /
+// multipass.hip; nothing here computes on the host.
+#include <atomic>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+
+#include "engines.hpp"
+
+namespace lc {
+
+// One immutable table per device: exp(-2 pi i j / 2^18), j < 2^17 (Appendix C.1 twiddles).
+static __device__ float2 g_tw[TW_L / 2];
+
+__global__ void fill_tw_kernel(float2* tw)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= TW_L / 2) return;
+    double s, c;
+    sincospi(-2.0 * (double)j / (double)TW_L, &s, &c);
+    tw[j] = make_float2((float)c, (float)s);
+}
+
+static thread_local char t_hip_err[256] = "";
+static hipError_t note(hipError_t e, const char* what)
+{
+    if (e != hipSuccess) snprintf(t_hip_err, sizeof(t_hip_err), "%s: %s", what, hipGetErrorString(e));
+    return e;
+}
+
+constexpr int MAX_DEV = 64;
+static std::mutex g_init_mu;
+static const float2* g_tw_ptr[MAX_DEV] = {nullptr};
+
+// Returns the device's table pointer, filling the table on first use (then syncs `st` once).
+static hipError_t get_tables(const float2** out, hipStream_t st, bool sync_device)
+{
+    int dev = 0;
+    hipError_t e = note(hipGetDevice(&dev), "hipGetDevice");
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEV) return note(hipErrorInvalidDevice, "device index");
+    std::lock_guard<std::mutex> g(g_init_mu);
+    if (!g_tw_ptr[dev]) {
+        float2* p = nullptr;
+        e = note(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(g_tw)), "hipGetSymbolAddress");
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(fill_tw_kernel, dim3(TW_L / 2 / 256), dim3(256), 0, st, p);
+        e = note(hipGetLastError(), "fill_tw_kernel");
+        if (e != hipSuccess) return e;
+        e = note(sync_device ? hipDeviceSynchronize() : hipStreamSynchronize(st), "table sync");
+        if (e != hipSuccess) return e;
+        g_tw_ptr[dev] = p;
+    }
+    *out = g_tw_ptr[dev];
+    return hipSuccess;
+}
+
+static int ilog2(int64_t x)
+{
+    int l = 0;
+    while ((int64_t(1) << l) < x) ++l;
+    return l;
+}
+
+static int env_int(const char* name, int dflt)
+{
+    const char* v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+}
+
+// Plan for (N, io).  fp32 I/O runs the fp32 vector-ALU engine; fp16/bf16 I/O runs the fp16
+// matrix-core engine.  Environment overrides (experiments and tests only):
+//   LONGCONV_ENGINE=valu|mfma      force the engine
+//   LONGCONV_INNER_LOG2=<n>        cap the on-chip transform length at 2^n (forces multi-pass)
+Plan make_plan(int64_t N, int io)
+{
+    Plan pl{};
+    pl.log2L = ilog2(2 * N);
+    pl.engine = (io == LONGCONV_F32) ? ENGINE_VALU : ENGINE_MFMA;
+    if (const char* e = getenv("LONGCONV_ENGINE")) {
+        if (!strcmp(e, "valu")) pl.engine = ENGINE_VALU;
+        if (!strcmp(e, "mfma")) pl.engine = ENGINE_MFMA;
+    }
+    int cap = pl.engine == ENGINE_VALU ? VALU_INNER_MAX_LOG2 : MFMA_INNER_MAX_LOG2;
+    const int forced = env_int("LONGCONV_INNER_LOG2", 0);
+    if (forced >= 8 && forced < cap) cap = forced;
+    pl.log2L2 = pl.log2L < cap ? pl.log2L : cap;
+    pl.log2R = pl.log2L - pl.log2L2;
+    if (pl.log2R > 5) { pl.log2R = 5; pl.log2L2 = pl.log2L - 5; }   // not reachable for supported N
+    const float invL = 1.0f / (float)(int64_t(1) << pl.log2L);
+    if (pl.engine == ENGINE_VALU) {
+        pl.order.ndig = 0;
+        if (pl.log2R) pl.order.bits[pl.order.ndig++] = (unsigned char)pl.log2R;
+        for (int i = 0; i < pl.log2L2; ++i) pl.order.bits[pl.order.ndig++] = 1;
+        pl.kscale = invL;
+        pl.dkscale = invL;
+    } else {
+        mfma_fill_plan(pl);
+    }
+    return pl;
+}
+
+static size_t cw_bytes(const Plan& pl) { return pl.engine == ENGINE_VALU ? sizeof(float2) : sizeof(__half2); }
+static size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
+
+struct WsLayout {
+    size_t kspec, kscratch, ws1, ws2, wsA, dpart, total;
+    int nblk;
+};
+
+static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool backward)
+{
+    WsLayout w{};
+    const size_t L = size_t(1) << pl.log2L;
+    const size_t npairs = (size_t)((B + 1) / 2);
+    size_t off = 0;
+    w.kspec = off; off += up256((size_t)H * L * sizeof(float2));
+    w.kscratch = off; if (pl.log2L > VALU_KSPEC_MAX_LOG2) off += up256((size_t)H * L * sizeof(float2));
+    w.ws1 = off; if (pl.log2R) off += up256((size_t)H * npairs * L * cw_bytes(pl));
+    w.ws2 = off; if (pl.log2R && backward) off += up256((size_t)H * npairs * L * cw_bytes(pl));
+    w.wsA = off; if (pl.log2R && backward) off += up256((size_t)H * L * cw_bytes(pl));
+    w.nblk = (int)(npairs * ((size_t(1) << pl.log2L2) / 256));
+    w.dpart = off; if (pl.log2R && backward) off += up256((size_t)H * w.nblk * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+static bool pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
+static int check_shape(int64_t B, int64_t H, int64_t N, int io)
+{
+    if (io != LONGCONV_F32 && io != LONGCONV_F16 && io != LONGCONV_BF16) return LONGCONV_ERR_DTYPE;
+    if (B < 1 || H < 1 || !pow2(N) || N < 256 || N > 131072) return LONGCONV_ERR_SHAPE;
+    if (B > (int64_t(1) << 24) || H > 65535) return LONGCONV_ERR_SHAPE;
+    return LONGCONV_OK;
+}
+static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Spectrum of all heads into `kspec` (storage order and scale of plan `pl`).
+static hipError_t run_kspec(const float* k, const float* D, float2* kspec, float2* kscratch, int64_t H,
+                            int64_t N, const Plan& pl, const float2* tw, hipStream_t st)
+{
+    const int lg2 = pl.log2L < VALU_KSPEC_MAX_LOG2 ? pl.log2L : VALU_KSPEC_MAX_LOG2;
+    const int lgR = pl.log2L - lg2;
+    if (lgR == 0) return valu_kspec(k, nullptr, D, kspec, H, N, 0, lg2, pl.order, pl.kscale, tw, st);
+    Problem pk{1, H, N, LONGCONV_F32, 1};
+    hipError_t e = outer_fwd(k, nullptr, kscratch, nullptr, nullptr, pk, lgR, lg2, 1.0f, false, tw, st);
+    if (e != hipSuccess) return e;
+    return valu_kspec(nullptr, kscratch, D, kspec, H, N, lgR, lg2, pl.order, pl.kscale, tw, st);
+}
+
+// y = conv(in, spectrum) (or correlation when conj): all passes of the plan.
+static hipError_t run_conv(const void* in, const float2* kspec, void* out, void* ws1, bool conj,
+                           const Problem& pr, const Plan& pl, const float2* tw, hipStream_t st,
+                           bool ws1_ready)
+{
+    hipError_t e;
+    const bool f16ws = pl.engine == ENGINE_MFMA;
+    if (pl.log2R && !ws1_ready) {
+        e = outer_fwd(in, nullptr, ws1, nullptr, nullptr, pr, pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st);
+        if (e != hipSuccess) return e;
+    }
+    if (pl.engine == ENGINE_VALU)
+        e = valu_conv(in, kspec, out, (float2*)ws1, conj, pr, pl, tw, st);
+    else
+        e = mfma_conv(in, kspec, out, (__half2*)ws1, conj, pr, pl, tw, st);
+    if (e != hipSuccess) return e;
+    if (pl.log2R) e = outer_inv(ws1, out, pr, pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st);
+    return e;
+}
+
+}  // namespace lc
+
+using namespace lc;
+
+extern "C" {
+
+int longconv_init(void)
+{
+    const float2* tw;
+    return get_tables(&tw, nullptr, true) == hipSuccess ? LONGCONV_OK : LONGCONV_ERR_HIP;
+}
+
+size_t longconv_kspec_bytes(int64_t H, int64_t N, int io)
+{
+    if (check_shape(1, H, N, io) != LONGCONV_OK) return 0;
+    return (size_t)H * (size_t)(2 * N) * sizeof(float2);
+}
+
+size_t longconv_workspace_bytes(int64_t B, int64_t H, int64_t N, int io, int backward)
+{
+    if (check_shape(B, H, N, io) != LONGCONV_OK) return 0;
+    const Plan pl = make_plan(N, io);
+    return carve(B, H, N, pl, backward != 0).total;
+}
+
+int longconv_kspec_compute(const float* k, const float* D, void* kspec, int64_t H, int64_t N, int io,
+                           void* workspace, size_t workspace_bytes, void* stream)
+{
+    int s = check_shape(1, H, N, io);
+    if (s != LONGCONV_OK) return s;
+    if (!k || !D || !kspec) return LONGCONV_ERR_NULL;
+    if (misaligned(k) || misaligned(kspec) || misaligned(workspace)) return LONGCONV_ERR_ALIGN;
+    const Plan pl = make_plan(N, io);
+    const WsLayout w = carve(1, H, N, pl, false);
+    const size_t need = w.ws1 - w.kscratch;   // only the producer scratch is used here
+    if (need && (!workspace || workspace_bytes < w.kscratch + need)) return LONGCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const float2* tw;
+    if (get_tables(&tw, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    float2* scratch = need ? (float2*)((char*)workspace + w.kscratch) : nullptr;
+    if (note(run_kspec(k, D, (float2*)kspec, scratch, H, N, pl, tw, st), "kspec") != hipSuccess)
+        return LONGCONV_ERR_HIP;
+    return LONGCONV_OK;
+}
+
+int longconv_fwd(const void* u, const float* k, const float* D, const void* kspec, void* y, int64_t B,
+                 int64_t H, int64_t N, int io, void* workspace, size_t workspace_bytes, void* stream)
+{
+    int s = check_shape(B, H, N, io);
+    if (s != LONGCONV_OK) return s;
+    if (!u || !y || (!kspec && (!k || !D))) return LONGCONV_ERR_NULL;
+    if (misaligned(u) || misaligned(y) || misaligned(k) || misaligned(kspec) || misaligned(workspace))
+        return LONGCONV_ERR_ALIGN;
+    const Plan pl = make_plan(N, io);
+    const WsLayout w = carve(B, H, N, pl, false);
+    if (!workspace || workspace_bytes < w.total) return LONGCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const float2* tw;
+    if (get_tables(&tw, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    char* base = (char*)workspace;
+    const float2* ks = (const float2*)kspec;
+    if (!ks) {
+        if (note(run_kspec(k, D, (float2*)(base + w.kspec), (float2*)(base + w.kscratch), H, N, pl, tw, st),
+                 "kspec") != hipSuccess)
+            return LONGCONV_ERR_HIP;
+        ks = (const float2*)(base + w.kspec);
+    }
+    Problem pr{B, H, N, io, (int)((B + 1) / 2)};
+    if (note(run_conv(u, ks, y, base + w.ws1, false, pr, pl, tw, st, false), "fwd") != hipSuccess)
+        return LONGCONV_ERR_HIP;
+    return LONGCONV_OK;
+}
+
+int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, const void* kspec, void* du,
+                 float* dk, float* dD, int64_t B, int64_t H, int64_t N, int io, void* workspace,
+                 size_t workspace_bytes, void* stream)
+{
+    int s = check_shape(B, H, N, io);
+    if (s != LONGCONV_OK) return s;
+    const bool want_dkD = dk || dD;
+    if (!dy || (want_dkD && !u) || (du && !kspec && (!k || !D))) return LONGCONV_ERR_NULL;
+    if (misaligned(dy) || misaligned(u) || misaligned(k) || misaligned(kspec) || misaligned(du) ||
+        misaligned(dk) || misaligned(workspace))
+        return LONGCONV_ERR_ALIGN;
+    const Plan pl = make_plan(N, io);
+    const WsLayout w = carve(B, H, N, pl, true);
+    if (!workspace || workspace_bytes < w.total) return LONGCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const float2* tw;
+    if (get_tables(&tw, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    char* base = (char*)workspace;
+    Problem pr{B, H, N, io, (int)((B + 1) / 2)};
+    const bool f16ws = pl.engine == ENGINE_MFMA;
+    bool dy_ready = false;   // multi-pass: pass A of dy already in ws1
+
+    if (want_dkD) {
+        hipError_t e = hipSuccess;
+        if (pl.log2R) {
+            // pass A for u (-> ws2) and dy (-> ws1) in one launch, with the dD partial sums
+            e = outer_fwd(dy, u, base + w.ws1, base + w.ws2, dD ? (float*)(base + w.dpart) : nullptr, pr,
+                          pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st);
+            dy_ready = true;
+            if (e == hipSuccess && dD) e = reduce_dD((const float*)(base + w.dpart), dD, H, w.nblk, st);
+        }
+        if (e == hipSuccess && (dk || !pl.log2R)) {
+            if (pl.engine == ENGINE_VALU)
+                e = valu_dk(dy, u, dk, dD, (const float2*)(base + w.ws2), (const float2*)(base + w.ws1),
+                            (float2*)(base + w.wsA), pr, pl, tw, st);
+            else
+                e = mfma_dk(dy, u, dk, dD, (const __half2*)(base + w.ws2), (const __half2*)(base + w.ws1),
+                            (__half2*)(base + w.wsA), pr, pl, tw, st);
+            if (e == hipSuccess && pl.log2R && dk) {
+                Problem pk{1, H, N, LONGCONV_F32, 1};   // heads as single rows, real part only
+                e = outer_inv(base + w.wsA, dk, pk, pl.log2R, pl.log2L2, pl.dkscale, f16ws, tw, st);
+            }
+        }
+        if (note(e, "bwd dk/dD") != hipSuccess) return LONGCONV_ERR_HIP;
+    }
+    if (du) {
+        const float2* ks = (const float2*)kspec;
+        if (!ks) {
+            if (note(run_kspec(k, D, (float2*)(base + w.kspec), (float2*)(base + w.kscratch), H, N, pl, tw, st),
+                     "kspec") != hipSuccess)
+                return LONGCONV_ERR_HIP;
+            ks = (const float2*)(base + w.kspec);
+        }
+        if (note(run_conv(dy, ks, du, base + w.ws1, true, pr, pl, tw, st, dy_ready), "bwd du") != hipSuccess)
+            return LONGCONV_ERR_HIP;
+    }
+    return LONGCONV_OK;
+}
+
+const char* longconv_status_string(int status)
+{
+    switch (status) {
+        case LONGCONV_OK: return "ok";
+        case LONGCONV_ERR_NULL: return "a required pointer is NULL";
+        case LONGCONV_ERR_SHAPE: return "bad shape: need B,H >= 1 and N a power of two in [256, 131072]";
+        case LONGCONV_ERR_DTYPE: return "unsupported dtype";
+        case LONGCONV_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case LONGCONV_ERR_WORKSPACE: return "workspace missing or too small";
+        case LONGCONV_ERR_HIP: return "HIP call failed";
+        default: return "unknown status";
+    }
+}
+
+const char* longconv_last_hip_error(void) { return t_hip_err; }
+
+const char* longconv_plan_string(int64_t N, int io)
+{
+    static thread_local char buf[256];
+    if (check_shape(1, 1, N, io) != LONGCONV_OK) { snprintf(buf, sizeof(buf), "invalid"); return buf; }
+    const Plan pl = make_plan(N, io);
+    int n = snprintf(buf, sizeof(buf), "engine=%s L=2^%d outer_radix=%d inner=2^%d passes=%d digits=",
+                     pl.engine == ENGINE_VALU ? "valu-fp32" : "mfma-fp16", pl.log2L, 1 << pl.log2R, pl.log2L2,
+                     pl.log2R ? 3 : 1);
+    for (int i = 0; i < pl.order.ndig && n < (int)sizeof(buf) - 4; ++i)
+        n += snprintf(buf + n, sizeof(buf) - n, "%s%d", i ? "x" : "", 1 << pl.order.bits[i]);
+    return buf;
+}
+
+}  // extern "C"

@@ -1,0 +1,124 @@
+// Shared device/host helpers for the longconv HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "../../include/longconv.h"
+
+namespace lc {
+
+// ---------------------------------------------------------------------------------
+// Twiddle table: g_tw[j] = exp(-2*pi*i*j / TW_L), j < TW_L/2, float32 rounded from
+// float64 (Appendix C.1: M_{j,k} = exp(-2 pi i jk/N)).  One copy per device, filled
+// once at init and handed to every kernel as a pointer argument.  Any root of unity of order dividing TW_L is a strided read.
+// ---------------------------------------------------------------------------------
+constexpr int TW_LOG2 = 18;
+constexpr int TW_L = 1 << TW_LOG2;
+
+// exp(-2*pi*i*idx/TW_L) for any idx in [0, TW_L)
+__device__ __forceinline__ float2 tw_full(const float2* __restrict__ tw, uint32_t idx)
+{
+    float2 w = tw[idx & (TW_L / 2 - 1)];
+    if (idx & (TW_L / 2)) { w.x = -w.x; w.y = -w.y; }
+    return w;
+}
+
+__device__ __forceinline__ float2 cmul(float2 a, float2 b)
+{
+    return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+// a * conj(b)
+__device__ __forceinline__ float2 cmulc(float2 a, float2 b)
+{
+    return make_float2(a.x * b.x + a.y * b.y, a.y * b.x - a.x * b.y);
+}
+__device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(a.x + b.x, a.y + b.y); }
+__device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
+
+// ---------------------------------------------------------------------------------
+// I/O element types.  ld/st convert to/from float with round-to-nearest-even.
+// ---------------------------------------------------------------------------------
+struct IoF32 {
+    using T = float;
+    static __device__ __forceinline__ float ld(const T* p, size_t i) { return p[i]; }
+    static __device__ __forceinline__ void st(T* p, size_t i, float v) { p[i] = v; }
+};
+struct IoF16 {
+    using T = __half;
+    static __device__ __forceinline__ float ld(const T* p, size_t i) { return __half2float(p[i]); }
+    static __device__ __forceinline__ void st(T* p, size_t i, float v) { p[i] = __float2half_rn(v); }
+};
+struct IoBF16 {
+    using T = uint16_t;
+    static __device__ __forceinline__ float ld(const T* p, size_t i)
+    {
+        return __uint_as_float(((uint32_t)p[i]) << 16);
+    }
+    static __device__ __forceinline__ void st(T* p, size_t i, float v)
+    {
+        uint32_t b = __float_as_uint(v);
+        if ((b & 0x7fffffffu) > 0x7f800000u) { p[i] = (uint16_t)((b >> 16) | 0x40); return; }  // NaN
+        b += 0x7fffu + ((b >> 16) & 1u);
+        p[i] = (uint16_t)(b >> 16);
+    }
+};
+
+// Complex workspace element types used between passes.
+struct CwF32 {
+    using T = float2;
+    static __device__ __forceinline__ float2 ld(const T* p, size_t i) { return p[i]; }
+    static __device__ __forceinline__ void st(T* p, size_t i, float2 v) { p[i] = v; }
+};
+struct CwF16 {
+    using T = __half2;
+    static __device__ __forceinline__ float2 ld(const T* p, size_t i) { return __half22float2(p[i]); }
+    static __device__ __forceinline__ void st(T* p, size_t i, float2 v) { p[i] = __float22half2_rn(v); }
+};
+
+// ---------------------------------------------------------------------------------
+// Storage order of a spectrum.  A transform of length L = r_0 * r_1 * ... * r_{S-1}
+// done decimation-in-frequency and in place leaves frequency
+//     f = k_0 + r_0 * (k_1 + r_1 * (k_2 + ...))
+// at position ((k_0 * r_1 + k_1) * r_2 + k_2) ...  (digit reversal).  The kernel
+// spectrum is stored in that same order (Algorithm 2 line 2), so the pointwise
+// product needs no permutation.  All radices are powers of two: bits[s] = log2 r_s.
+// ---------------------------------------------------------------------------------
+struct SpecOrder {
+    int ndig;
+    unsigned char bits[20];
+};
+
+__host__ __device__ inline uint32_t spec_pos(uint32_t f, const SpecOrder& o)
+{
+    uint32_t pos = 0;
+    for (int s = 0; s < o.ndig; ++s) {
+        const uint32_t b = o.bits[s];
+        pos = (pos << b) | (f & ((1u << b) - 1u));
+        f >>= b;
+    }
+    return pos;
+}
+
+enum Engine { ENGINE_VALU = 0, ENGINE_MFMA = 1 };
+
+// Host-side plan: how 2N is factored and which kernels run.
+struct Plan {
+    int engine;      // ENGINE_VALU (fp32 arithmetic) or ENGINE_MFMA (fp16 matrix cores)
+    int log2L;       // L = 2N
+    int log2R;       // outer radix of the multi-pass split (0 = single fused pass)
+    int log2L2;      // inner (on-chip) transform length
+    SpecOrder order; // storage order of the spectrum: outer digit first, then inner digits
+    float kscale;    // factor folded into the stored spectrum (includes 1/L)
+    float dkscale;   // factor applied to the inverse transform of the dk accumulator
+};
+
+Plan make_plan(int64_t N, int io);
+
+// Row addressing: element (b,h,n) of a [B,H,N] tensor.
+__device__ __forceinline__ size_t row_off(int64_t b, int64_t h, int64_t H, int64_t N)
+{
+    return ((size_t)b * H + h) * (size_t)N;
+}
+
+}  // namespace lc

@@ -1,0 +1,53 @@
+// Internal launch interfaces between the C-ABI layer and the kernel files.
+#pragma once
+#include "common.hpp"
+
+namespace lc {
+
+struct Problem {
+    int64_t B, H, N;
+    int io;          // longconv_dtype_t of u, y, dy, du
+    int npairs;      // ceil(B/2): two batch rows of one head are transformed as re + i*im
+};
+
+// ---- outer passes of the multi-pass split (multipass.hip) ------------------------
+// Pass A: ws[(h*npairs+p)*L + k1*L2 + n2] = scale * w_L^(n2*k1) * sum_{n1<R/2} w_R^(n1*k1) z[n1*L2+n2],
+// z = row(2p) + i*row(2p+1) of `in` (I/O dtype `io`; rows beyond B read as zero).
+// If in2/ws2 are given the same is done for a second tensor in the same launch and, if
+// dD_part != NULL, per-block partial sums of in*in2 are written for the dD reduction.
+hipError_t outer_fwd(const void* in, const void* in2, void* ws, void* ws2, float* dD_part,
+                     const Problem& pr, int log2R, int log2L2, float scale, bool ws_f16,
+                     const float2* tw, hipStream_t st);
+int outer_fwd_blocks_per_head(const Problem& pr, int log2L2);
+// Pass C: rows of `out` <- scale * sum_{k1} conj(w_R^(n1*k1) w_L^(n2*k1)) ws[...], n1 < R/2 only
+// (truncation to the first N samples); re -> row 2p, im -> row 2p+1.
+hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
+                     bool ws_f16, const float2* tw, hipStream_t st);
+// dD[h] = sum of the per-block partials written by outer_fwd.
+hipError_t reduce_dD(const float* part, float* dD, int64_t H, int nblk, hipStream_t st);
+
+// ---- fp32 VALU engine (engine_valu.hip) --------------------------------------------
+// Spectrum of one head (or of one chunk of the multi-pass split) in fp32, scattered to the
+// consumer's storage order.  Used for every dtype: the spectrum is always computed in fp32.
+// Handles inner lengths up to 2^14; longer transforms go through outer_fwd first.
+hipError_t valu_kspec(const float* k, const float2* ws, const float* D, float2* kspec, int64_t H,
+                      int64_t N, int log2R, int log2L2, const SpecOrder& consumer, float scale,
+                      const float2* tw, hipStream_t st);
+constexpr int VALU_KSPEC_MAX_LOG2 = 14;
+constexpr int VALU_INNER_MAX_LOG2 = 13;
+hipError_t valu_conv(const void* in, const float2* kspec, void* out, float2* ws, bool conj,
+                     const Problem& pr, const Plan& pl, const float2* tw, hipStream_t st);
+hipError_t valu_dk(const void* dy, const void* u, float* dk, float* dD, const float2* ws_u,
+                   const float2* ws_dy, float2* ws_A, const Problem& pr, const Plan& pl, const float2* tw,
+                   hipStream_t st);
+
+// ---- fp16 MFMA engine (engine_mfma.hip) ---------------------------------------------
+constexpr int MFMA_INNER_MAX_LOG2 = 15;
+void mfma_fill_plan(Plan& pl);
+hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj,
+                     const Problem& pr, const Plan& pl, const float2* tw, hipStream_t st);
+hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u,
+                   const __half2* ws_dy, __half2* ws_A, const Problem& pr, const Plan& pl, const float2* tw,
+                   hipStream_t st);
+
+}  // namespace lc

@@ -1,0 +1,220 @@
+// Outer passes of the multi-pass split for transforms too long for one compute unit
+// (Section 3.2 "Three-Pass Algorithm", Eq. 3 and Algorithm 2; Butterfly matrix of Appendix C.1).
+//
+// L = R * L2.  With time index n = n1*L2 + n2 and frequency f = k1 + R*k2,
+//   pass A : t[k1][n2] = w_L^(n2*k1) * sum_{n1} w_R^(n1*k1) z[n1*L2 + n2]      (this file)
+//   pass B : R independent length-L2 FFT convolutions, chunk k1 with spectrum slice k1
+//   pass C : y[n1*L2 + n2] = sum_{k1} conj(w_R^(n1*k1) * w_L^(n2*k1)) v[k1][n2] (this file)
+// Pass A/C are the products with the paper's Butterfly matrix B (blocks D_{j,k}[tau] =
+// exp(-2 i pi k (j l + tau)/N), 0-based) and its conjugate; each thread owns one column n2, so
+// every read and write is a unit-stride run of L2 elements per (n1 or k1) slice and the data is
+// touched once per pass (the access pattern of Appendix D.1's single-read/single-write argument).
+// Zero padding and truncation are free here: z is non-zero only for n1 < R/2 and only outputs
+// with n1 < R/2 are kept.  Two real rows travel as one complex sequence (re + i*im).
+#include "engines.hpp"
+
+namespace lc {
+namespace {
+
+constexpr int OB = 256;   // threads per block = columns per block
+
+template <class IO, class CW, int LOG2R, bool TWO>
+__global__ void outer_fwd_kernel(const typename IO::T* __restrict__ in, const typename IO::T* __restrict__ in2,
+                                 typename CW::T* __restrict__ ws, typename CW::T* __restrict__ ws2,
+                                 float* __restrict__ dD_part, int64_t B, int64_t H, int64_t N, int npairs,
+                                 int log2L2, float scale, const float2* __restrict__ tw)
+{
+    constexpr int R = 1 << LOG2R, RH = R / 2;
+    __shared__ float red[OB / 64];
+    const int L2 = 1 << log2L2;
+    const int log2L = log2L2 + LOG2R;
+    const int n2 = blockIdx.x * OB + threadIdx.x;
+    const int pairidx = blockIdx.y;
+    const int h = pairidx / npairs, p = pairidx % npairs;
+    const bool has_b = (2 * p + 1) < B;
+    const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
+    float2 z[RH], z2[RH];
+    float dsum = 0.f;
+#pragma unroll
+    for (int n1 = 0; n1 < RH; ++n1) {
+        const size_t n = (size_t)n1 * L2 + n2;
+        z[n1] = make_float2(IO::ld(in, oa + n), has_b ? IO::ld(in, ob + n) : 0.f);
+        if (TWO) {
+            z2[n1] = make_float2(IO::ld(in2, oa + n), has_b ? IO::ld(in2, ob + n) : 0.f);
+            dsum += z[n1].x * z2[n1].x + z[n1].y * z2[n1].y;
+        }
+    }
+    const size_t base = (size_t)pairidx << log2L;
+#pragma unroll 1
+    for (int k1 = 0; k1 < R; ++k1) {
+        float2 t = make_float2(0.f, 0.f), t2 = t;
+#pragma unroll
+        for (int n1 = 0; n1 < RH; ++n1) {
+            const float2 w = tw_full(tw, (uint32_t)((n1 * k1) & (R - 1)) << (TW_LOG2 - LOG2R));
+            t = cadd(t, cmul(z[n1], w));
+            if (TWO) t2 = cadd(t2, cmul(z2[n1], w));
+        }
+        const float2 wl = tw_full(tw, ((uint32_t)n2 * (uint32_t)k1) << (TW_LOG2 - log2L));
+        t = cmul(t, wl);
+        CW::st(ws, base + (size_t)k1 * L2 + n2, make_float2(t.x * scale, t.y * scale));
+        if (TWO) {
+            t2 = cmul(t2, wl);
+            CW::st(ws2, base + (size_t)k1 * L2 + n2, make_float2(t2.x * scale, t2.y * scale));
+        }
+    }
+    if (TWO && dD_part) {
+        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = dsum;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+            for (int w = 0; w < OB / 64; ++w) t += red[w];
+            dD_part[(size_t)pairidx * gridDim.x + blockIdx.x] = t;
+        }
+    }
+}
+
+template <class IO, class CW, int LOG2R>
+__global__ void outer_inv_kernel(const typename CW::T* __restrict__ ws, typename IO::T* __restrict__ out,
+                                 int64_t B, int64_t H, int64_t N, int npairs, int log2L2, float scale,
+                                 const float2* __restrict__ tw)
+{
+    constexpr int R = 1 << LOG2R, RH = R / 2;
+    const int L2 = 1 << log2L2;
+    const int log2L = log2L2 + LOG2R;
+    const int n2 = blockIdx.x * OB + threadIdx.x;
+    const int pairidx = blockIdx.y;
+    const int h = pairidx / npairs, p = pairidx % npairs;
+    const bool has_b = (2 * p + 1) < B;
+    const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
+    const size_t base = (size_t)pairidx << log2L;
+    float2 v[R];
+#pragma unroll
+    for (int k1 = 0; k1 < R; ++k1) {
+        const float2 wl = tw_full(tw, ((uint32_t)n2 * (uint32_t)k1) << (TW_LOG2 - log2L));
+        v[k1] = cmulc(CW::ld(ws, base + (size_t)k1 * L2 + n2), wl);
+    }
+#pragma unroll 1
+    for (int n1 = 0; n1 < RH; ++n1) {
+        float2 t = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int k1 = 0; k1 < R; ++k1) {
+            const float2 w = tw_full(tw, (uint32_t)((n1 * k1) & (R - 1)) << (TW_LOG2 - LOG2R));
+            t = cadd(t, cmulc(v[k1], w));
+        }
+        const size_t n = (size_t)n1 * L2 + n2;
+        IO::st(out, oa + n, t.x * scale);
+        if (has_b) IO::st(out, ob + n, t.y * scale);
+    }
+}
+
+__global__ void reduce_dD_kernel(const float* __restrict__ part, float* __restrict__ dD, int64_t H, int nblk)
+{
+    const int64_t h = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (h >= H) return;
+    float t = 0.f;
+    for (int i = 0; i < nblk; ++i) t += part[(size_t)h * nblk + i];
+    dD[h] = t;
+}
+
+template <class IO, class CW, int LOG2R>
+hipError_t fwd_launch(const void* in, const void* in2, void* ws, void* ws2, float* dD_part, const Problem& pr,
+                      int log2L2, float scale, const float2* tw, hipStream_t st)
+{
+    using T = typename IO::T;
+    using C = typename CW::T;
+    dim3 grid((1u << log2L2) / OB, (unsigned)(pr.npairs * pr.H));
+    if (in2)
+        hipLaunchKernelGGL((outer_fwd_kernel<IO, CW, LOG2R, true>), grid, dim3(OB), 0, st, (const T*)in,
+                           (const T*)in2, (C*)ws, (C*)ws2, dD_part, pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw);
+    else
+        hipLaunchKernelGGL((outer_fwd_kernel<IO, CW, LOG2R, false>), grid, dim3(OB), 0, st, (const T*)in,
+                           (const T*)nullptr, (C*)ws, (C*)nullptr, (float*)nullptr, pr.B, pr.H, pr.N, pr.npairs,
+                           log2L2, scale, tw);
+    return hipGetLastError();
+}
+
+template <class IO, class CW, int LOG2R>
+hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, float scale, const float2* tw,
+                      hipStream_t st)
+{
+    using T = typename IO::T;
+    using C = typename CW::T;
+    dim3 grid((1u << log2L2) / OB, (unsigned)(pr.npairs * pr.H));
+    hipLaunchKernelGGL((outer_inv_kernel<IO, CW, LOG2R>), grid, dim3(OB), 0, st, (const C*)ws, (T*)out, pr.B,
+                       pr.H, pr.N, pr.npairs, log2L2, scale, tw);
+    return hipGetLastError();
+}
+
+#define LC_R_SWITCH(CALL)                    \
+    switch (log2R) {                         \
+        case 1: return CALL(1);              \
+        case 2: return CALL(2);              \
+        case 3: return CALL(3);              \
+        case 4: return CALL(4);              \
+        case 5: return CALL(5);              \
+        default: return hipErrorInvalidValue; \
+    }
+
+template <class IO, class CW>
+hipError_t fwd_r(const void* in, const void* in2, void* ws, void* ws2, float* dD_part, const Problem& pr,
+                 int log2R, int log2L2, float scale, const float2* tw, hipStream_t st)
+{
+#define CALL(LR) fwd_launch<IO, CW, LR>(in, in2, ws, ws2, dD_part, pr, log2L2, scale, tw, st)
+    LC_R_SWITCH(CALL)
+#undef CALL
+}
+template <class IO, class CW>
+hipError_t inv_r(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
+                 const float2* tw, hipStream_t st)
+{
+#define CALL(LR) inv_launch<IO, CW, LR>(ws, out, pr, log2L2, scale, tw, st)
+    LC_R_SWITCH(CALL)
+#undef CALL
+}
+
+}  // namespace
+
+int outer_fwd_blocks_per_head(const Problem& pr, int log2L2) { return pr.npairs * ((1 << log2L2) / OB); }
+
+hipError_t outer_fwd(const void* in, const void* in2, void* ws, void* ws2, float* dD_part, const Problem& pr,
+                     int log2R, int log2L2, float scale, bool ws_f16, const float2* tw, hipStream_t st)
+{
+    if ((1 << log2L2) < OB) return hipErrorInvalidValue;
+#define GO(IO, CW) return fwd_r<IO, CW>(in, in2, ws, ws2, dD_part, pr, log2R, log2L2, scale, tw, st)
+    if (ws_f16) {
+        if (pr.io == LONGCONV_F32) GO(IoF32, CwF16);
+        if (pr.io == LONGCONV_F16) GO(IoF16, CwF16);
+        GO(IoBF16, CwF16);
+    } else {
+        if (pr.io == LONGCONV_F32) GO(IoF32, CwF32);
+        if (pr.io == LONGCONV_F16) GO(IoF16, CwF32);
+        GO(IoBF16, CwF32);
+    }
+#undef GO
+}
+
+hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
+                     bool ws_f16, const float2* tw, hipStream_t st)
+{
+    if ((1 << log2L2) < OB) return hipErrorInvalidValue;
+#define GO(IO, CW) return inv_r<IO, CW>(ws, out, pr, log2R, log2L2, scale, tw, st)
+    if (ws_f16) {
+        if (pr.io == LONGCONV_F32) GO(IoF32, CwF16);
+        if (pr.io == LONGCONV_F16) GO(IoF16, CwF16);
+        GO(IoBF16, CwF16);
+    } else {
+        if (pr.io == LONGCONV_F32) GO(IoF32, CwF32);
+        if (pr.io == LONGCONV_F16) GO(IoF16, CwF32);
+        GO(IoBF16, CwF32);
+    }
+#undef GO
+}
+
+hipError_t reduce_dD(const float* part, float* dD, int64_t H, int nblk, hipStream_t st)
+{
+    hipLaunchKernelGGL(reduce_dD_kernel, dim3((unsigned)((H + 127) / 128)), dim3(128), 0, st, part, dD, H, nblk);
+    return hipGetLastError();
+}
+
+}  // namespace lc

@@ -1,0 +1,77 @@
+"""Host-side checks of the C-ABI library: it loads, exports every declared symbol, sizes and
+error paths behave.  No kernel is launched here (argument validation precedes any HIP call)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2302_06646_amd as lc
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "longconv.h")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(longconv_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = lc.lib()
+    names = _declared()
+    assert set(names) == set(lc.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_sizes_and_plan():
+    assert lc.longconv_kspec_bytes(4, 1024, lc.F32) == 4 * 2048 * 8
+    assert lc.longconv_kspec_bytes(4, 1000, lc.F32) == 0           # not a power of two
+    assert lc.longconv_kspec_bytes(4, 128, lc.F32) == 0            # too short
+    assert lc.longconv_kspec_bytes(4, 262144, lc.F16) == 0         # too long
+    assert lc.longconv_workspace_bytes(2, 4, 1024, 7, False) == 0  # bad dtype
+    for N in (256, 1024, 16384, 65536, 131072):
+        for io in (lc.F32, lc.F16, lc.BF16):
+            f = lc.longconv_workspace_bytes(3, 5, N, io, False)
+            b = lc.longconv_workspace_bytes(3, 5, N, io, True)
+            assert f >= lc.longconv_kspec_bytes(5, N, io) and b >= f
+            assert "engine=" in lc.longconv_plan_string(N, io)
+    assert "valu" in lc.longconv_plan_string(1024, lc.F32)
+    assert "mfma" in lc.longconv_plan_string(1024, lc.BF16)
+    assert "passes=3" in lc.longconv_plan_string(131072, lc.F16)
+    assert lc.longconv_plan_string(100, lc.F32) == "invalid"
+
+
+def test_error_codes_before_any_launch():
+    L = lc.lib()
+    a = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1004)
+    ws = ctypes.c_void_p(0x2000)
+    big = 1 << 40
+    f = L.longconv_fwd
+    assert f(None, a, a, None, a, 2, 4, 1024, 0, ws, big, None) == 1            # NULL u
+    assert f(a, None, a, None, a, 2, 4, 1024, 0, ws, big, None) == 1            # no k and no kspec
+    assert f(a, a, a, None, a, 0, 4, 1024, 0, ws, big, None) == 2               # B < 1
+    assert f(a, a, a, None, a, 2, 4, 1000, 0, ws, big, None) == 2               # N not a power of two
+    assert f(a, a, a, None, a, 2, 4, 1024, 9, ws, big, None) == 3               # dtype
+    assert f(odd, a, a, None, a, 2, 4, 1024, 0, ws, big, None) == 4             # alignment
+    assert f(a, a, a, None, a, 2, 4, 1024, 0, ws, 16, None) == 5                # workspace too small
+    assert f(a, a, a, None, a, 2, 4, 1024, 0, None, big, None) == 5             # workspace missing
+    b = L.longconv_bwd
+    assert b(None, a, a, a, None, a, a, a, 2, 4, 1024, 0, ws, big, None) == 1   # NULL dy
+    assert b(a, None, a, a, None, a, a, a, 2, 4, 1024, 0, ws, big, None) == 1   # dk wanted, no u
+    assert b(a, a, a, a, None, a, a, a, 2, 4, 2048 + 1, 0, ws, big, None) == 2
+    assert b(a, a, a, a, None, a, a, a, 2, 4, 1024, 0, ws, 8, None) == 5
+    k = L.longconv_kspec_compute
+    assert k(None, a, a, 4, 1024, 0, ws, big, None) == 1
+    assert k(a, a, a, 4, 3, 0, ws, big, None) == 2
+    for code in range(8):
+        assert L.longconv_status_string(code)
+
+
+def test_binding_fails_loudly_without_library(monkeypatch):
+    monkeypatch.setattr(lc, "_lib", None)
+    monkeypatch.setattr(lc, "LIB_PATH", "/nonexistent/liblongconv.so")
+    with pytest.raises(lc.LongconvError):
+        lc.lib()
