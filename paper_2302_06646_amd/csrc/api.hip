@@ -81,7 +81,7 @@ Plan make_plan(int64_t N, int io)
     pl.engine = (io == LONGCONV_F32) ? ENGINE_VALU : ENGINE_MFMA;
     if (const char* e = getenv("LONGCONV_ENGINE")) {
         if (!strcmp(e, "valu")) pl.engine = ENGINE_VALU;
-        if (!strcmp(e, "mfma")) pl.engine = ENGINE_MFMA;
+        if (!strcmp(e, "mfma") && io != LONGCONV_F32) pl.engine = ENGINE_MFMA;
     }
     int cap = pl.engine == ENGINE_VALU ? VALU_INNER_MAX_LOG2 : MFMA_INNER_MAX_LOG2;
     const int forced = env_int("LONGCONV_INNER_LOG2", 0);
@@ -122,7 +122,8 @@ static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool back
     w.ws2 = off; if (pl.log2R && backward) off += up256((size_t)H * npairs * L * cw_bytes(pl));
     w.wsA = off; if (pl.log2R && backward) off += up256((size_t)H * L * cw_bytes(pl));
     w.nblk = (int)(npairs * ((size_t(1) << pl.log2L2) / 256));
-    w.dpart = off; if (pl.log2R && backward) off += up256((size_t)H * w.nblk * sizeof(float));
+    const size_t npart = (size_t)w.nblk > (size_t(1) << pl.log2R) ? (size_t)w.nblk : (size_t(1) << pl.log2R);
+    w.dpart = off; if (pl.log2R && backward) off += up256((size_t)H * npart * sizeof(float));
     w.total = off;
     return w;
 }
@@ -267,24 +268,32 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
 
     if (want_dkD) {
         hipError_t e = hipSuccess;
-        if (pl.log2R) {
-            // pass A for u (-> ws2) and dy (-> ws1) in one launch, with the dD partial sums
-            e = outer_fwd(dy, u, base + w.ws1, base + w.ws2, dD ? (float*)(base + w.dpart) : nullptr, pr,
-                          pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st);
-            dy_ready = true;
-            if (e == hipSuccess && dD) e = reduce_dD((const float*)(base + w.dpart), dD, H, w.nblk, st);
-        }
-        if (e == hipSuccess && (dk || !pl.log2R)) {
-            if (pl.engine == ENGINE_VALU)
+        float* dpart = (float*)(base + w.dpart);
+        if (pl.engine == ENGINE_VALU) {
+            if (pl.log2R) {
+                // pass A for u (-> ws2) and dy (-> ws1) in one launch, with the dD partial sums
+                e = outer_fwd(dy, u, base + w.ws1, base + w.ws2, dD ? dpart : nullptr, pr, pl.log2R, pl.log2L2,
+                              1.0f, false, tw, st);
+                dy_ready = true;
+                if (e == hipSuccess && dD) e = reduce_dD(dpart, dD, H, w.nblk, st);
+            }
+            if (e == hipSuccess && (dk || !pl.log2R))
                 e = valu_dk(dy, u, dk, dD, (const float2*)(base + w.ws2), (const float2*)(base + w.ws1),
                             (float2*)(base + w.wsA), pr, pl, tw, st);
-            else
-                e = mfma_dk(dy, u, dk, dD, (const __half2*)(base + w.ws2), (const __half2*)(base + w.ws1),
-                            (__half2*)(base + w.wsA), pr, pl, tw, st);
-            if (e == hipSuccess && pl.log2R && dk) {
-                Problem pk{1, H, N, LONGCONV_F32, 1};   // heads as single rows, real part only
-                e = outer_inv(base + w.wsA, dk, pk, pl.log2R, pl.log2L2, pl.dkscale, f16ws, tw, st);
+        } else {
+            if (pl.log2R) {
+                e = outer_fwd(dy, u, base + w.ws1, base + w.ws2, nullptr, pr, pl.log2R, pl.log2L2, 1.0f, true,
+                              tw, st);
+                dy_ready = true;
             }
+            if (e == hipSuccess)
+                e = mfma_dk(dy, u, dk, dD, (const __half2*)(base + w.ws2), (const __half2*)(base + w.ws1),
+                            (__half2*)(base + w.wsA), dD ? dpart : nullptr, pr, pl, tw, st);
+            if (e == hipSuccess && pl.log2R && dD) e = reduce_dD(dpart, dD, H, 1 << pl.log2R, st);
+        }
+        if (e == hipSuccess && pl.log2R && dk) {
+            Problem pk{1, H, N, LONGCONV_F32, 1};   // heads as single rows, real part only
+            e = outer_inv(base + w.wsA, dk, pk, pl.log2R, pl.log2L2, pl.dkscale, f16ws, tw, st);
         }
         if (note(e, "bwd dk/dD") != hipSuccess) return LONGCONV_ERR_HIP;
     }
