@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the long-convolution hot path on one MI355X.
+
+One "step" = one pass of the whole path over one batch of synthetic input, as a training
+step would run it (the kernel changes every step, so its spectrum is recomputed):
+
+    kernel-spectrum precompute  ->  forward  ->  backward (dk, dD)  ->  backward (du)
+
+Inputs are resident in HBM before the timed region.  Each step uses the next of several
+distinct buffer sets (more than the 256 MB last-level cache in total) so that reads come from
+HBM rather than from cache.  Prints ONE JSON line (see README for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4a|...] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+CACHE_BYTES = 256 << 20        # last-level (Infinity) cache
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Sets:
+    """Device buffers for one workload: `nsets` rotating copies of the big tensors."""
+
+    def __init__(self, w: wl.Workload, lc, torch, min_total=2 * CACHE_BYTES + (64 << 20)):
+        self.w = w
+        td = {wl.F32: torch.float32, wl.F16: torch.float16, wl.BF16: torch.bfloat16}[w.dtype]
+        per_set = 4 * w.B * w.H * w.N * wl.DTYPE_BYTES[w.dtype]
+        self.nsets = max(2, int(np.ceil(min_total / per_set)))
+        g = torch.Generator(device="cuda").manual_seed(20230213 * 10 + w.wid)
+        shape = (w.B, w.H, w.N)
+        self.u = [torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(td) for _ in range(self.nsets)]
+        self.dy = [torch.randn(shape, generator=g, device="cuda", dtype=torch.float32).to(td) for _ in range(self.nsets)]
+        self.y = [torch.empty(shape, device="cuda", dtype=td) for _ in range(self.nsets)]
+        self.du = [torch.empty(shape, device="cuda", dtype=td) for _ in range(self.nsets)]
+        # kernel and skip term: the seeded host generator (distribution matters for nothing but realism)
+        inp = wl.generate(w, B=1)
+        self.k = torch.from_numpy(inp.k).cuda()
+        self.D = torch.from_numpy(inp.D).cuda()
+        self.dk = torch.empty_like(self.k)
+        self.dD = torch.empty_like(self.D)
+        self.kspec = lc.new_kspec(w.H, w.N, w.dtype)
+        self.ws = lc.new_workspace(w.B, w.H, w.N, w.dtype, True)
+
+
+def run_workload(key, steps, warmup, lc, torch):
+    w = wl.WORKLOADS[key]
+    S = Sets(w, lc, torch)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = [[ev() for _ in range(5)] for _ in range(steps)]
+
+    def step(i, m=None):
+        j = i % S.nsets
+        if m: m[0].record()
+        lc.longconv_kspec_compute(S.k, S.D, S.kspec, w.dtype, S.ws)
+        if m: m[1].record()
+        lc.longconv_fwd(S.u[j], S.k, S.D, S.y[j], S.ws, kspec=S.kspec)
+        if m: m[2].record()
+        lc.longconv_bwd(S.dy[j], S.u[j], S.k, S.D, None, S.dk, S.dD, S.ws, kspec=S.kspec)
+        if m: m[3].record()
+        lc.longconv_bwd(S.dy[j], S.u[j], S.k, S.D, S.du[j], None, None, S.ws, kspec=S.kspec)
+        if m: m[4].record()
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i, marks[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    seg = np.array([[m[a].elapsed_time(m[a + 1]) for a in range(4)] for m in marks])   # ms
+    seg_avg = seg.mean(axis=0)
+    fwd_b, bwd_b = wl.algorithmic_bytes(w.B, w.H, w.N, w.dtype)
+    s = wl.DTYPE_BYTES[w.dtype]
+    E = w.B * w.H * w.N
+    small = w.H * w.N * 4 + w.H * 4
+    # algorithmic bytes charged to each launch group; they sum to fwd_b + bwd_b
+    seg_bytes = {"kspec": 0, "fwd": fwd_b, "bwd_dk_dD": E * s + small, "bwd_du": 2 * E * s + small}
+    names = list(seg_bytes)
+    res = {
+        "workload": w.name, "B": w.B, "H": w.H, "N": w.N, "io": wl.DTYPE_NAMES[w.dtype],
+        "plan": lc.longconv_plan_string(w.N, w.dtype), "buffer_sets": S.nsets,
+        "ms_per_step": float(seg_avg.sum()), "wall_ms_per_step": wall_ms,
+        "bytes_per_step": fwd_b + bwd_b,
+        "GBps": (fwd_b + bwd_b) / (seg_avg.sum() * 1e-3) / 1e9,
+        "segments": {n: {"ms": float(seg_avg[i]), "ms_min": float(seg[:, i].min()),
+                         "GBps": (seg_bytes[n] / (seg_avg[i] * 1e-3) / 1e9) if seg_bytes[n] else None}
+                     for i, n in enumerate(names)},
+    }
+    ff, bf = wl.algorithmic_flops(w.B, w.H, w.N)
+    res["TFLOPs_algorithmic"] = (ff + bf) / (seg_avg.sum() * 1e-3) / 1e12
+    res["frac_hbm"] = res["GBps"] / HBM_PEAK_GBS
+    del S
+    torch.cuda.empty_cache()
+    return res, seg_bytes
+
+
+def cpu_baseline(key):
+    """The float64 oracle, as it stands, on the host cores: whole workload if it is a few seconds of
+    work, otherwise all batch rows of a subset of heads (cost is linear in heads)."""
+    import oracle
+    w = wl.WORKLOADS[key]
+    macs_per_head = 3 * w.B * w.N * w.N / 2          # fwd + du + dk
+    budget = 15.0 * 10e9                             # about 15 s at ~10 GMAC/s
+    heads = int(max(1, min(w.H, budget // macs_per_head)))
+    inp = wl.generate(w, H=heads)
+    k64, D64 = inp.k.astype(np.float64), inp.D.astype(np.float64)
+    t0 = time.perf_counter()
+    oracle.longconv_fwd(inp.u, k64, D64)
+    oracle.longconv_bwd(inp.dy, inp.u, k64, D64)
+    dt = time.perf_counter() - t0
+    fwd_b, bwd_b = wl.algorithmic_bytes(w.B, heads, w.N, w.dtype)
+    return {"value": (fwd_b + bwd_b) / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{heads} of {w.H} heads, all {w.B} batch rows, fwd+bwd, {dt:.2f} s "
+                      f"(float64 direct O(N^2) sums; scales linearly in heads)",
+            "ms_per_step_scaled": dt * 1e3 * w.H / heads}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="2", choices=list(wl.WORKLOADS))
+    ap.add_argument("--also", default="3,4a", help="comma list of further workloads reported under 'targets'")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+
+    import torch
+    import paper_2302_06646_amd as lc
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    lc.longconv_init()
+
+    res, seg_bytes = run_workload(a.workload, a.steps, a.warmup, lc, torch)
+    log(json.dumps(res, indent=1))
+    # dominant kernel = the launch group with the largest share of the step
+    dom = max(("fwd", "bwd_dk_dD", "bwd_du"), key=lambda n: res["segments"][n]["ms"])
+    dom_gbps = res["segments"][dom]["GBps"]
+    out = {
+        "metric": "long-conv fwd+bwd ms, effective GB/s and % HBM roofline at BxHxN",
+        "value": res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": res["workload"], "B": res["B"], "H": res["H"], "N": res["N"], "io": res["io"],
+                   "step": "kspec+fwd+bwd(dk,dD)+bwd(du)", "plan": res["plan"], "buffer_sets": res["buffer_sets"]},
+        "pct_hbm_roofline": 100.0 * res["frac_hbm"],
+        "TFLOPs_algorithmic": res["TFLOPs_algorithmic"],
+        "segments_ms": {n: v["ms"] for n, v in res["segments"].items()},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": dom_gbps / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": seg_bytes[dom]},
+    }
+    targets = []
+    for key in [k for k in a.also.split(",") if k and k != a.workload]:
+        r, _ = run_workload(key, max(10, a.steps // 2), max(3, a.warmup // 2), lc, torch)
+        log(json.dumps(r, indent=1))
+        targets.append({"workload": r["workload"], "ms_per_step": r["ms_per_step"], "GBps": r["GBps"],
+                        "pct_hbm_roofline": 100 * r["frac_hbm"],
+                        "fwd_ms": r["segments"]["fwd"]["ms"],
+                        "fwd_pct_hbm_roofline": 100 * r["segments"]["fwd"]["GBps"] / HBM_PEAK_GBS})
+    out["targets"] = targets
+    if not a.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(a.workload)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
