@@ -23,6 +23,21 @@ __global__ void fill_tw_kernel(float2* tw)
     tw[j] = make_float2((float)c, (float)s);
 }
 
+static __device__ float2 g_stw[STW_TOTAL];
+
+__global__ void fill_stw_kernel(float2* stw)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= STW_TOTAL) return;
+    const int lgLs = 31 - __clz(i + 32);           // table holding entry i
+    const int q = i + 32 - (1 << lgLs);
+    const int lgM = lgLs - 4;
+    const int d = q >> lgM, suf = q & ((1 << lgM) - 1);
+    double s, c;
+    sincospi(-2.0 * (double)(d * suf) / (double)(1 << lgLs), &s, &c);
+    stw[i] = make_float2((float)c, (float)s);
+}
+
 static thread_local char t_hip_err[256] = "";
 static hipError_t note(hipError_t e, const char* what)
 {
@@ -32,28 +47,32 @@ static hipError_t note(hipError_t e, const char* what)
 
 constexpr int MAX_DEV = 64;
 static std::mutex g_init_mu;
-static const float2* g_tw_ptr[MAX_DEV] = {nullptr};
+static Tables g_tab[MAX_DEV] = {};
 
 // Returns the device's table pointer, filling the table on first use (then syncs `st` once).
-static hipError_t get_tables(const float2** out, hipStream_t st, bool sync_device)
+static hipError_t get_tables(Tables* out, hipStream_t st, bool sync_device)
 {
     int dev = 0;
     hipError_t e = note(hipGetDevice(&dev), "hipGetDevice");
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= MAX_DEV) return note(hipErrorInvalidDevice, "device index");
     std::lock_guard<std::mutex> g(g_init_mu);
-    if (!g_tw_ptr[dev]) {
-        float2* p = nullptr;
+    if (!g_tab[dev].tw) {
+        float2 *p = nullptr, *q = nullptr;
         e = note(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(g_tw)), "hipGetSymbolAddress");
         if (e != hipSuccess) return e;
+        e = note(hipGetSymbolAddress((void**)&q, HIP_SYMBOL(g_stw)), "hipGetSymbolAddress");
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL(fill_tw_kernel, dim3(TW_L / 2 / 256), dim3(256), 0, st, p);
-        e = note(hipGetLastError(), "fill_tw_kernel");
+        hipLaunchKernelGGL(fill_stw_kernel, dim3((STW_TOTAL + 255) / 256), dim3(256), 0, st, q);
+        e = note(hipGetLastError(), "fill tables");
         if (e != hipSuccess) return e;
         e = note(sync_device ? hipDeviceSynchronize() : hipStreamSynchronize(st), "table sync");
         if (e != hipSuccess) return e;
-        g_tw_ptr[dev] = p;
+        g_tab[dev].stw = q;
+        g_tab[dev].tw = p;
     }
-    *out = g_tw_ptr[dev];
+    *out = g_tab[dev];
     return hipSuccess;
 }
 
@@ -153,10 +172,11 @@ static hipError_t run_kspec(const float* k, const float* D, float2* kspec, float
 
 // y = conv(in, spectrum) (or correlation when conj): all passes of the plan.
 static hipError_t run_conv(const void* in, const float2* kspec, void* out, void* ws1, bool conj,
-                           const Problem& pr, const Plan& pl, const float2* tw, hipStream_t st,
+                           const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st,
                            bool ws1_ready)
 {
     hipError_t e;
+    const float2* tw = tb.tw;
     const bool f16ws = pl.engine == ENGINE_MFMA;
     if (pl.log2R && !ws1_ready) {
         e = outer_fwd(in, nullptr, ws1, nullptr, nullptr, pr, pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st);
@@ -165,7 +185,7 @@ static hipError_t run_conv(const void* in, const float2* kspec, void* out, void*
     if (pl.engine == ENGINE_VALU)
         e = valu_conv(in, kspec, out, (float2*)ws1, conj, pr, pl, tw, st);
     else
-        e = mfma_conv(in, kspec, out, (__half2*)ws1, conj, pr, pl, tw, st);
+        e = mfma_conv(in, kspec, out, (__half2*)ws1, conj, pr, pl, tb, st);
     if (e != hipSuccess) return e;
     if (pl.log2R) e = outer_inv(ws1, out, pr, pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st);
     return e;
@@ -179,8 +199,8 @@ extern "C" {
 
 int longconv_init(void)
 {
-    const float2* tw;
-    return get_tables(&tw, nullptr, true) == hipSuccess ? LONGCONV_OK : LONGCONV_ERR_HIP;
+    Tables tb;
+    return get_tables(&tb, nullptr, true) == hipSuccess ? LONGCONV_OK : LONGCONV_ERR_HIP;
 }
 
 size_t longconv_kspec_bytes(int64_t H, int64_t N, int io)
@@ -208,8 +228,9 @@ int longconv_kspec_compute(const float* k, const float* D, void* kspec, int64_t 
     const size_t need = w.ws1 - w.kscratch;   // only the producer scratch is used here
     if (need && (!workspace || workspace_bytes < w.kscratch + need)) return LONGCONV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    const float2* tw;
-    if (get_tables(&tw, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    Tables tb;
+    if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    const float2* tw = tb.tw;
     float2* scratch = need ? (float2*)((char*)workspace + w.kscratch) : nullptr;
     if (note(run_kspec(k, D, (float2*)kspec, scratch, H, N, pl, tw, st), "kspec") != hipSuccess)
         return LONGCONV_ERR_HIP;
@@ -228,8 +249,9 @@ int longconv_fwd(const void* u, const float* k, const float* D, const void* kspe
     const WsLayout w = carve(B, H, N, pl, false);
     if (!workspace || workspace_bytes < w.total) return LONGCONV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    const float2* tw;
-    if (get_tables(&tw, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    Tables tb;
+    if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    const float2* tw = tb.tw;
     char* base = (char*)workspace;
     const float2* ks = (const float2*)kspec;
     if (!ks) {
@@ -239,7 +261,7 @@ int longconv_fwd(const void* u, const float* k, const float* D, const void* kspe
         ks = (const float2*)(base + w.kspec);
     }
     Problem pr{B, H, N, io, (int)((B + 1) / 2)};
-    if (note(run_conv(u, ks, y, base + w.ws1, false, pr, pl, tw, st, false), "fwd") != hipSuccess)
+    if (note(run_conv(u, ks, y, base + w.ws1, false, pr, pl, tb, st, false), "fwd") != hipSuccess)
         return LONGCONV_ERR_HIP;
     return LONGCONV_OK;
 }
@@ -259,8 +281,9 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
     const WsLayout w = carve(B, H, N, pl, true);
     if (!workspace || workspace_bytes < w.total) return LONGCONV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    const float2* tw;
-    if (get_tables(&tw, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    Tables tb;
+    if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    const float2* tw = tb.tw;
     char* base = (char*)workspace;
     Problem pr{B, H, N, io, (int)((B + 1) / 2)};
     const bool f16ws = pl.engine == ENGINE_MFMA;
@@ -288,7 +311,7 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
             }
             if (e == hipSuccess)
                 e = mfma_dk(dy, u, dk, dD, (const __half2*)(base + w.ws2), (const __half2*)(base + w.ws1),
-                            (__half2*)(base + w.wsA), dD ? dpart : nullptr, pr, pl, tw, st);
+                            (__half2*)(base + w.wsA), dD ? dpart : nullptr, pr, pl, tb, st);
             if (e == hipSuccess && pl.log2R && dD) e = reduce_dD(dpart, dD, H, 1 << pl.log2R, st);
         }
         if (e == hipSuccess && pl.log2R && dk) {
@@ -305,7 +328,7 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
                 return LONGCONV_ERR_HIP;
             ks = (const float2*)(base + w.kspec);
         }
-        if (note(run_conv(dy, ks, du, base + w.ws1, true, pr, pl, tw, st, dy_ready), "bwd du") != hipSuccess)
+        if (note(run_conv(dy, ks, du, base + w.ws1, true, pr, pl, tb, st, dy_ready), "bwd du") != hipSuccess)
             return LONGCONV_ERR_HIP;
     }
     return LONGCONV_OK;

@@ -16,6 +16,19 @@ namespace lc {
 constexpr int TW_LOG2 = 18;
 constexpr int TW_L = 1 << TW_LOG2;
 
+// Stage twiddle tables in position order: for a radix-16 stage of stride M = 2^lgM (span
+// Ls = 16 M) the factor at position p is w_Ls^(d * suf) with d = (p / M) mod 16 and
+// suf = p mod M; it depends on p mod Ls only.  Table for lgLs = lgM + 4 in [5, 15] starts at
+// entry 2^lgLs - 32 of one array of STW_TOTAL entries; neighbouring positions are neighbouring
+// entries, so a wave's loads are unit-stride runs.
+constexpr int STW_TOTAL = (1 << 16) - 32;
+__host__ __device__ constexpr int stw_offset(int lgLs) { return (1 << lgLs) - 32; }
+
+struct Tables {
+    const float2* tw;    // g_tw
+    const float2* stw;   // stage twiddles
+};
+
 // exp(-2*pi*i*idx/TW_L) for any idx in [0, TW_L)
 __device__ __forceinline__ float2 tw_full(const float2* __restrict__ tw, uint32_t idx)
 {

@@ -87,11 +87,9 @@ __device__ __forceinline__ h2 pack(float re, float im)
 
 // Twiddle of the forward stage whose stride is 2^lgM, for position p:
 // w_{2^(lgM+4)}^(d * suf), d = digit of that stage at p, suf = p mod 2^lgM.
-__device__ __forceinline__ float2 stage_twiddle(const float2* __restrict__ tw, int p, int lgM)
+__device__ __forceinline__ float2 stage_twiddle(const float2* __restrict__ stw, int p, int lgM)
 {
-    const uint32_t d = ((uint32_t)p >> lgM) & 15u;
-    const uint32_t suf = (uint32_t)p & ((1u << lgM) - 1u);
-    return tw_full(tw, (d * suf) << (TW_LOG2 - 4 - lgM));
+    return stw[stw_offset(lgM + 4) + (p & ((16 << lgM) - 1))];
 }
 
 // Position of (column gamma, slot sigma) for a stage of stride 2^lgM.
@@ -262,7 +260,7 @@ template <int LG, class IO, int NW>
 __global__ void __launch_bounds__(NW * 64)
 conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
             typename IO::T* __restrict__ out, __half2* __restrict__ ws, int conj, int64_t B, int64_t H,
-            int64_t N, int log2R, const float2* __restrict__ tw)
+            int64_t N, int log2R, const float2* __restrict__ tw, const float2* __restrict__ stw)
 {
     extern __shared__ uint4 smem_raw[];
     h2* s = reinterpret_cast<h2*>(smem_raw);
@@ -282,7 +280,7 @@ conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ ks
     else
         copy_chunk_in(s, chunk, L2, tid, NW * 64);
     __syncthreads();
-    forward_outer_stages<LG, NW>(s, F16, tw, wave, lane);
+    forward_outer_stages<LG, NW>(s, F16, stw, wave, lane);
 
     // last forward stage -> pointwise product -> first inverse stage, in registers
     const float4* ks = reinterpret_cast<const float4*>(kspec + (size_t)h * L + (size_t)k1 * L2);
@@ -306,13 +304,13 @@ conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ ks
         H8U o;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float2 w = stage_twiddle(tw, pb + j, LB);
+            const float2 w = stage_twiddle(stw, pb + j, LB);
             const float2 r = cmulc(make_float2(yr[j], yi[j]), w);
             o.c[j] = pack(r.x, r.y);
         }
         *reinterpret_cast<uint4*>(&s[phys(pb)]) = o.u;
     }
-    inverse_outer_stages<LG, NW, 0>(s, I16, tw, wave, lane);
+    inverse_outer_stages<LG, NW, 0>(s, I16, stw, wave, lane);
     __syncthreads();
     if (log2R == 0)
         store_pair<IO>(s, out + row_off(2 * p, h, H, N), out + row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N),
@@ -334,7 +332,7 @@ __global__ void __launch_bounds__(NW * 64)
 dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u, float* __restrict__ dk,
           float* __restrict__ dD, const __half2* __restrict__ ws_u, const __half2* __restrict__ ws_dy,
           __half2* __restrict__ ws_A, float* __restrict__ dD_part, int64_t B, int64_t H, int64_t N, int npairs,
-          int log2R, float dkscale, const float2* __restrict__ tw)
+          int log2R, float dkscale, const float2* __restrict__ tw, const float2* __restrict__ stw)
 {
     extern __shared__ uint4 smem_raw[];
     __shared__ float red[NW];
@@ -362,7 +360,7 @@ dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restric
         if (log2R == 0) load_pair<IO>(s, u + oa, u + ob, has_b, (int)N, tid, NW * 64);
         else copy_chunk_in(s, ws_u + coff, L2, tid, NW * 64);
         __syncthreads();
-        forward_outer_stages<LG, NW>(s, F16, tw, wave, lane);
+        forward_outer_stages<LG, NW>(s, F16, stw, wave, lane);
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             const int pb = last_base(wave + i * NW, lane);
@@ -378,7 +376,7 @@ dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restric
         if (log2R == 0) load_pair<IO>(s, dy + oa, dy + ob, has_b, (int)N, tid, NW * 64);
         else copy_chunk_in(s, ws_dy + coff, L2, tid, NW * 64);
         __syncthreads();
-        forward_outer_stages<LG, NW>(s, F16, tw, wave, lane);
+        forward_outer_stages<LG, NW>(s, F16, stw, wave, lane);
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             const int pb = last_base(wave + i * NW, lane);
@@ -429,7 +427,7 @@ dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restric
         H8U o;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float2 w = stage_twiddle(tw, pb + j, LB);
+            const float2 w = stage_twiddle(stw, pb + j, LB);
             const float2 r = cmulc(make_float2(yr[j], yi[j]), w);
             o.c[j] = pack(r.x, r.y);
         }
@@ -437,7 +435,7 @@ dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restric
     }
     if (log2R == 0) {
         // all inverse stages but the outermost through LDS; the outermost writes dk from registers
-        inverse_outer_stages<LG, NW, 1>(s, I16, tw, wave, lane);
+        inverse_outer_stages<LG, NW, 1>(s, I16, stw, wave, lane);
         __syncthreads();
         constexpr int lgM = LG - 4;
         const int c = lane & 15, g = lane >> 4;
@@ -457,7 +455,7 @@ dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restric
             }
         }
     } else {
-        inverse_outer_stages<LG, NW, 0>(s, I16, tw, wave, lane);
+        inverse_outer_stages<LG, NW, 0>(s, I16, stw, wave, lane);
         __syncthreads();
         copy_chunk_out(s, ws_A + (size_t)h * L + (size_t)k1 * L2, L2, tid, NW * 64);
     }
@@ -475,7 +473,7 @@ constexpr int dk_waves(int lg) { return lg <= 8 ? 1 : lg == 9 ? 2 : lg == 10 ? 4
 
 template <int LG, class IO>
 hipError_t conv_go(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
-                   const Plan& pl, const float2* tw, hipStream_t st)
+                   const Plan& pl, const Tables& tb, hipStream_t st)
 {
     constexpr int NW = conv_waves(LG);
     using T = typename IO::T;
@@ -484,13 +482,13 @@ hipError_t conv_go(const void* in, const float2* kspec, void* out, __half2* ws, 
     if (e != hipSuccess) return e;
     dim3 grid(pr.npairs, (unsigned)pr.H, 1u << pl.log2R);
     hipLaunchKernelGGL((conv_kernel<LG, IO, NW>), grid, dim3(NW * 64), lds, st, (const T*)in, kspec, (T*)out, ws,
-                       conj ? 1 : 0, pr.B, pr.H, pr.N, pl.log2R, tw);
+                       conj ? 1 : 0, pr.B, pr.H, pr.N, pl.log2R, tb.tw, tb.stw);
     return hipGetLastError();
 }
 
 template <int LG, class IO>
 hipError_t dk_go(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
-                 __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl, const float2* tw, hipStream_t st)
+                 __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
 {
     constexpr int NW = dk_waves(LG);
     using T = typename IO::T;
@@ -499,7 +497,7 @@ hipError_t dk_go(const void* dy, const void* u, float* dk, float* dD, const __ha
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)pr.H, 1u << pl.log2R);
     hipLaunchKernelGGL((dk_kernel<LG, IO, NW>), grid, dim3(NW * 64), lds, st, (const T*)dy, (const T*)u, dk, dD,
-                       ws_u, ws_dy, ws_A, dD_part, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, pl.dkscale, tw);
+                       ws_u, ws_dy, ws_A, dD_part, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, pl.dkscale, tb.tw, tb.stw);
     return hipGetLastError();
 }
 
@@ -534,22 +532,22 @@ void mfma_fill_plan(Plan& pl)
 }
 
 hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
-                     const Plan& pl, const float2* tw, hipStream_t st)
+                     const Plan& pl, const Tables& tb, hipStream_t st)
 {
-    if (pr.io == LONGCONV_F16) { LC_LG_SWITCH(conv_go, IoF16, in, kspec, out, ws, conj, pr, pl, tw, st) }
-    if (pr.io == LONGCONV_BF16) { LC_LG_SWITCH(conv_go, IoBF16, in, kspec, out, ws, conj, pr, pl, tw, st) }
+    if (pr.io == LONGCONV_F16) { LC_LG_SWITCH(conv_go, IoF16, in, kspec, out, ws, conj, pr, pl, tb, st) }
+    if (pr.io == LONGCONV_BF16) { LC_LG_SWITCH(conv_go, IoBF16, in, kspec, out, ws, conj, pr, pl, tb, st) }
     return hipErrorInvalidValue;
 }
 
 hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
-                   __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl, const float2* tw,
+                   __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl, const Tables& tb,
                    hipStream_t st)
 {
     if (pr.io == LONGCONV_F16) {
-        LC_LG_SWITCH(dk_go, IoF16, dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, pr, pl, tw, st)
+        LC_LG_SWITCH(dk_go, IoF16, dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, pr, pl, tb, st)
     }
     if (pr.io == LONGCONV_BF16) {
-        LC_LG_SWITCH(dk_go, IoBF16, dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, pr, pl, tw, st)
+        LC_LG_SWITCH(dk_go, IoBF16, dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, pr, pl, tb, st)
     }
     return hipErrorInvalidValue;
 }

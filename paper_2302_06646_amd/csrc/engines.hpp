@@ -45,10 +45,10 @@ hipError_t valu_dk(const void* dy, const void* u, float* dk, float* dD, const fl
 constexpr int MFMA_INNER_MAX_LOG2 = 15;
 void mfma_fill_plan(Plan& pl);
 hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj,
-                     const Problem& pr, const Plan& pl, const float2* tw, hipStream_t st);
+                     const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st);
 // Multi-pass: dD_part[h*R + k1] receives chunk k1's share of dD[h] (sum them with reduce_dD).
 hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u,
                    const __half2* ws_dy, __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl,
-                   const float2* tw, hipStream_t st);
+                   const Tables& tb, hipStream_t st);
 
 }  // namespace lc
