@@ -67,6 +67,8 @@ static hipError_t get_tables(Tables* out, hipStream_t st, bool sync_device)
         hipLaunchKernelGGL(fill_stw_kernel, dim3((STW_TOTAL + 255) / 256), dim3(256), 0, st, q);
         e = note(hipGetLastError(), "fill tables");
         if (e != hipSuccess) return e;
+        e = note(wave_fill_tables(&g_tab[dev].wtab, st), "fill wave tables");
+        if (e != hipSuccess) return e;
         e = note(sync_device ? hipDeviceSynchronize() : hipStreamSynchronize(st), "table sync");
         if (e != hipSuccess) return e;
         g_tab[dev].stw = q;
@@ -111,6 +113,7 @@ Plan make_plan(int64_t N, int io)
     const float invL = 1.0f / (float)(int64_t(1) << pl.log2L);
     if (pl.engine == ENGINE_VALU) {
         pl.order.ndig = 0;
+        pl.order.wave_lg = 0;
         if (pl.log2R) pl.order.bits[pl.order.ndig++] = (unsigned char)pl.log2R;
         for (int i = 0; i < pl.log2L2; ++i) pl.order.bits[pl.order.ndig++] = 1;
         pl.kscale = invL;
@@ -360,6 +363,7 @@ const char* longconv_plan_string(int64_t N, int io)
                      pl.log2R ? 3 : 1);
     for (int i = 0; i < pl.order.ndig && n < (int)sizeof(buf) - 4; ++i)
         n += snprintf(buf + n, sizeof(buf) - n, "%s%d", i ? "x" : "", 1 << pl.order.bits[i]);
+    if (pl.order.wave_lg) snprintf(buf + n, sizeof(buf) - n, " fwd_kernel=wave");
     return buf;
 }
 

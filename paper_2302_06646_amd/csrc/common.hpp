@@ -27,6 +27,7 @@ __host__ __device__ constexpr int stw_offset(int lgLs) { return (1 << lgLs) - 32
 struct Tables {
     const float2* tw;    // g_tw
     const float2* stw;   // stage twiddles
+    const void* wtab;    // lane-ordered constants of the wave-autonomous kernels
 };
 
 // exp(-2*pi*i*idx/TW_L) for any idx in [0, TW_L)
@@ -100,10 +101,26 @@ struct CwF16 {
 struct SpecOrder {
     int ndig;
     unsigned char bits[20];
+    int wave_lg;   // != 0: lane order of the wave-autonomous kernels for L = 2^wave_lg instead
 };
+
+// Storage position of frequency f = k_a + 16 k_b + 256 k_c in the spectrum consumed by the
+// wave-autonomous kernels (L = 2^LG = 256 * 2^cb): the lane order of their middle phase,
+// idx = (tile*64 + lane)*4 + reg, so that each lane reads its four values as one 32-byte run.
+__host__ __device__ inline uint32_t wave_spec_pos(uint32_t f, int LG)
+{
+    const int cb = LG - 8;
+    const uint32_t ka = f & 15u, kb = (f >> 4) & 15u, kc = f >> 8;
+    const uint32_t c2 = ((ka & 3u) << 2) | (kb & 3u);
+    const uint32_t q4 = ((ka >> 2) << 2) | (kb >> 2);
+    const uint32_t e = q4 & ((1u << (4 - cb)) - 1u), t2 = q4 >> (4 - cb);
+    const uint32_t sig = (e << cb) | kc;
+    return ((t2 * 64u + (sig >> 2) * 16u + c2) << 2) | (sig & 3u);
+}
 
 __host__ __device__ inline uint32_t spec_pos(uint32_t f, const SpecOrder& o)
 {
+    if (o.wave_lg) return wave_spec_pos(f, o.wave_lg);
     uint32_t pos = 0;
     for (int s = 0; s < o.ndig; ++s) {
         const uint32_t b = o.bits[s];

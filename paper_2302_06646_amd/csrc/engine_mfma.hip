@@ -21,6 +21,9 @@
 // product with the spectrum -> first inverse stage  never leaves registers.
 // Each stage matrix carries a power-of-two scale (1/4 per radix-16 stage) so the data keeps
 // unit magnitude in fp16; the net factor is folded into the stored spectrum.
+#include <cstdlib>
+#include <cstring>
+
 #include "engines.hpp"
 
 namespace lc {
@@ -257,7 +260,7 @@ __device__ __forceinline__ void inverse_outer_stages(h2* s, const Mats& I16, con
 //   multi pass : chunk k1 of the pair's complex workspace, in place (Eq. 3 middle factor).
 // -------------------------------------------------------------------------------------
 template <int LG, class IO, int NW>
-__global__ void __launch_bounds__(NW * 64)
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
             typename IO::T* __restrict__ out, __half2* __restrict__ ws, int conj, int64_t B, int64_t H,
             int64_t N, int log2R, const float2* __restrict__ tw, const float2* __restrict__ stw)
@@ -328,7 +331,7 @@ conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ ks
 // the fp32 accumulators.  TPW = tiles per wave in the last stage.
 // -------------------------------------------------------------------------------------
 template <int LG, class IO, int NW>
-__global__ void __launch_bounds__(NW * 64)
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u, float* __restrict__ dk,
           float* __restrict__ dD, const __half2* __restrict__ ws_u, const __half2* __restrict__ ws_dy,
           __half2* __restrict__ ws_A, float* __restrict__ dD_part, int64_t B, int64_t H, int64_t N, int npairs,
@@ -520,6 +523,10 @@ hipError_t dk_go(const void* dy, const void* u, float* dk, float* dD, const __ha
 void mfma_fill_plan(Plan& pl)
 {
     pl.order.ndig = 0;
+    pl.order.wave_lg = 0;
+    const char* kv = getenv("LONGCONV_MFMA_KERNEL");   // "coop" forces the workgroup-cooperative kernel
+    if (pl.log2R == 0 && pl.log2L2 >= WAVE_MIN_LOG2 && pl.log2L2 <= WAVE_MAX_LOG2 && !(kv && !strcmp(kv, "coop")))
+        pl.order.wave_lg = pl.log2L2;
     if (pl.log2R) pl.order.bits[pl.order.ndig++] = (unsigned char)pl.log2R;
     const int S = n_stages(pl.log2L2);
     for (int i = 0; i < S - 1; ++i) pl.order.bits[pl.order.ndig++] = 4;
@@ -534,6 +541,7 @@ void mfma_fill_plan(Plan& pl)
 hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
                      const Plan& pl, const Tables& tb, hipStream_t st)
 {
+    if (pl.order.wave_lg) return wave_conv(in, kspec, out, conj, pr, pl, tb, st);
     if (pr.io == LONGCONV_F16) { LC_LG_SWITCH(conv_go, IoF16, in, kspec, out, ws, conj, pr, pl, tb, st) }
     if (pr.io == LONGCONV_BF16) { LC_LG_SWITCH(conv_go, IoBF16, in, kspec, out, ws, conj, pr, pl, tb, st) }
     return hipErrorInvalidValue;

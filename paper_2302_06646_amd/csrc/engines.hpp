@@ -51,4 +51,10 @@ hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __
                    const __half2* ws_dy, __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl,
                    const Tables& tb, hipStream_t st);
 
+// ---- wave-autonomous matrix-core kernels for 512 <= L <= 4096 (engine_wave.hip) ----------
+constexpr int WAVE_MIN_LOG2 = 9, WAVE_MAX_LOG2 = 12;
+hipError_t wave_fill_tables(const void** tab_out, hipStream_t st);
+hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
+                     const Plan& pl, const Tables& tb, hipStream_t st);
+
 }  // namespace lc
