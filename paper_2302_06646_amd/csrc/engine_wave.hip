@@ -1,6 +1,5 @@
-// Wave-autonomous fused convolution for 512 <= L = 2N <= 4096 (one wavefront owns whole row
-// pairs; no workgroup barriers between waves, no twiddle work on the vector ALU beyond one
-// complex multiply per point per transform).
+// Wave-autonomous fused convolution for 512 <= L = 2N <= 4096: one wavefront owns whole row
+// pairs, the waves of a workgroup only share read-only constant tables held in LDS.
 //
 // L = 16 * 16 * TC, TC = 2^cb in {2,4,8,16}.  Time index n = d_a*16*TC + d_b*TC + d_c, frequency
 // f = k_a + 16*k_b + 256*k_c (Section 3.2 "Butterfly Decomposition" applied twice; twiddles as in
@@ -10,61 +9,93 @@
 // index in X).  Chaining "A-role, then B-role" therefore contracts two digits with the data
 // never leaving registers:
 //   phase 1 (tile = d_c): [A-role F16 over d_a] * w_L^(k_a*(d_b*TC+d_c)) [B-role over d_b]
-//                         -> LDS
+//                         -> LDS exchange buffer
 //   phase 2 (tile = 16 columns of (k_a,k_b)): [F_TC over d_c] * spectrum [F_TC^-1 over k_c]
 //                         -> LDS (in place)
 //   phase 3 (tile = d_c): [A-role F16^-1 over k_b] * conj(w_L^(k_a*(n_b*TC+d_c)))
 //                         [B-role F16^-1 over k_a] -> global, first N samples only.
 // The twiddle w_{16 TC}^(k_b*d_c) between the d_b and d_c stages depends only on the output row
 // k_b and on the tile (d_c), so it is folded into per-tile DFT matrices (row scaling in phase 1,
-// column scaling of the inverse in phase 3) and costs no vector-ALU work.  All constants
-// (twiddles in lane order, per-tile matrices) come from tables built once at init.
-// Each wave handles PB row pairs of one head in lockstep so that one table/spectrum load serves
-// PB tiles.
+// column scaling of the inverse in phase 3) and costs no vector-ALU work.  The only twiddle
+// multiplies left on the vector ALU are the two w_L factors, one per transform.  All constants
+// (twiddles in lane order as fp16, per-tile matrices) are copied once per workgroup from a global
+// table into LDS; workgroups are persistent (each wave loops over several groups of PB row
+// pairs) so that the copy is amortised.
 #include "engines.hpp"
 
 namespace lc {
 
-// ---- constant tables -----------------------------------------------------------------
-// For LG in [9,12], at byte offset wave_tab_offset(LG):
-//   T0f : float2[L]   idx (t*64+lane)*4+j : w_L^(k_a*(d_b*TC+t)),  k_a = lane%16, d_b = 4*(lane/16)+j
-//   T0i : float2[L]   idx (t*64+lane)*4+j : conj(w_L^(k_a*(n_b*TC+t))), n_b = lane%16, k_a = 4*(lane/16)+j
-//   Gf  : half[TC][2][64][8]  A operands (re-out, im-out) of (1/4) diag(w_{16TC}^(k_b t)) F16
-//   Gi  : half[TC][2][64][8]  B operands of (1/4) diag(conj w_{16TC}^(k_b t)) conj(F16), indexed [k_b][n_b]
-__host__ __device__ constexpr size_t wave_tab_bytes(int LG)
-{
-    return (size_t(16) << LG) + (size_t(4096) << (LG - 8));
-}
+template <int LG>
+struct WC {
+    static constexpr int cb = LG - 8, TC = 1 << cb, L = 1 << LG;
+    static constexpr int PITCH = 4 * TC + 1;          // 16-byte chunks per k_a row (+1 spreads banks)
+    static constexpr int PAIR_WORDS = 16 * PITCH * 4; // LDS words of one row pair's exchange buffer
+    static constexpr int TG = TC < 8 ? TC : 8;        // tiles per global load/store group
+    static constexpr int NWD = TG / 2;                // 32-bit words per (row, reg) per group
+    // constant table, in uint4 (16-byte) units; same layout in global memory and in LDS
+    static constexpr int T0F = 0;                     // [TC][64]      4 x fp16 complex per lane
+    static constexpr int T0I = TC * 64;               // [TC][64]
+    static constexpr int GF = 2 * TC * 64;            // [TC][2][64]   MFMA operand (8 x fp16) per lane
+    static constexpr int GI = GF + TC * 128;          // [TC][2][64]
+    static constexpr int PM = GI + TC * 128;          // [8][64] plain operands: F16, conj F16, F_TC, conj F_TC (re, im each)
+    static constexpr int TAB_U4 = PM + 8 * 64;        // = TC * 384 + 512
+};
+
+// byte offset of the table for LG in [9,12] inside the global array
 __host__ __device__ constexpr size_t wave_tab_offset(int LG)
 {
     size_t o = 0;
-    for (int l = 9; l < LG; ++l) o += wave_tab_bytes(l);
+    for (int l = 9; l < LG; ++l) o += ((size_t)(1 << (l - 8)) * 384 + 512) * 16;
     return o;
 }
 constexpr size_t WAVE_TAB_TOTAL = wave_tab_offset(13);
 
 __device__ unsigned char g_wave_tab[WAVE_TAB_TOTAL] __attribute__((aligned(256)));
 
+// Table entries, one thread per (t, lane, j):
+//   T0f : w_L^(k_a*(d_b*TC+t)),        k_a = lane%16, d_b = 4*(lane/16)+j
+//   T0i : conj(w_L^(k_a*(n_b*TC+t))),  n_b = lane%16, k_a = 4*(lane/16)+j
+//   Gf  : A operands (re-out, im-out) of (1/4) diag_{k_b}(w_{16TC}^(k_b t)) F16      [k_b][d_b]
+//   Gi  : B operands of (1/4) diag_{k_b}(conj w_{16TC}^(k_b t)) conj(F16)             [k_b][n_b]
 __global__ void fill_wave_tab_kernel(unsigned char* tab, int LG)
 {
     const int cb = LG - 8, TC = 1 << cb, L = 1 << LG;
-    unsigned char* base = tab + wave_tab_offset(LG);
-    float2* T0f = reinterpret_cast<float2*>(base);
-    float2* T0i = T0f + L;
-    _Float16* Gf = reinterpret_cast<_Float16*>(T0i + L);
-    _Float16* Gi = Gf + (size_t)TC * 2 * 64 * 8;
+    _Float16* base = reinterpret_cast<_Float16*>(tab + wave_tab_offset(LG));
+    _Float16* T0f = base;
+    _Float16* T0i = base + (size_t)TC * 64 * 8;
+    _Float16* Gf = base + (size_t)2 * TC * 64 * 8;
+    _Float16* Gi = Gf + (size_t)TC * 128 * 8;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= L) return;
     const int j = i & 3, lane = (i >> 2) & 63, t = i >> 8;
     const int x = lane & 15, y = 4 * (lane >> 4) + j;
     double s, c;
+    if (t == 0) {
+        // plain operands (I_{16/r} (x) F_r) * 2^-shift for r = 16 and r = TC, forward and conjugate;
+        // symmetric matrices, so each serves as A or as B operand.  Lane index m = x, slot sig = y.
+        _Float16* PM = Gi + (size_t)TC * 128 * 8;
+        for (int which = 0; which < 4; ++which) {
+            const int b = which < 2 ? 4 : cb, r = 1 << b;
+            const bool inv = which & 1;
+            const int sh = b == 4 ? 2 : (b >= 2 ? 1 : 0);
+            float re = 0.f, im = 0.f;
+            if ((x >> b) == (y >> b)) {
+                sincospi((inv ? 2.0 : -2.0) * (double)(((x & (r - 1)) * (y & (r - 1))) & (r - 1)) / (double)r, &s, &c);
+                re = (float)c / (float)(1 << sh); im = (float)s / (float)(1 << sh);
+            }
+            _Float16* o_re = PM + (((size_t)which * 2 + 0) * 64 + lane) * 8;
+            _Float16* o_im = PM + (((size_t)which * 2 + 1) * 64 + lane) * 8;
+            o_re[2 * j] = (_Float16)re; o_re[2 * j + 1] = (_Float16)(-im);
+            o_im[2 * j] = (_Float16)im; o_im[2 * j + 1] = (_Float16)re;
+        }
+    }
     sincospi(-2.0 * (double)((x * (y * TC + t)) & (L - 1)) / (double)L, &s, &c);   // k_a = x, d_b = y
-    T0f[i] = make_float2((float)c, (float)s);
+    T0f[((size_t)t * 64 + lane) * 8 + 2 * j] = (_Float16)c;
+    T0f[((size_t)t * 64 + lane) * 8 + 2 * j + 1] = (_Float16)s;
     sincospi(+2.0 * (double)((y * (x * TC + t)) & (L - 1)) / (double)L, &s, &c);   // k_a = y, n_b = x
-    T0i[i] = make_float2((float)c, (float)s);
-    // matrices: entry (t, lane, q=j): slot sig = 4*(lane/16)+q, other index m = lane%16
-    const int m = x, sig = y;
-    // forward: G[k_b = m][d_b = sig] = 1/4 * w_16^(m*sig) * w_{16TC}^(m*t)
+    T0i[((size_t)t * 64 + lane) * 8 + 2 * j] = (_Float16)c;
+    T0i[((size_t)t * 64 + lane) * 8 + 2 * j + 1] = (_Float16)s;
+    const int m = x, sig = y;   // operand lane index m, slot sig
     sincospi(-2.0 * ((double)((m * sig) & 15) / 16.0 + (double)(m * t) / (double)(16 * TC)), &s, &c);
     {
         const float re = 0.25f * (float)c, im = 0.25f * (float)s;
@@ -73,7 +104,6 @@ __global__ void fill_wave_tab_kernel(unsigned char* tab, int LG)
         o_re[2 * j] = (_Float16)re; o_re[2 * j + 1] = (_Float16)(-im);
         o_im[2 * j] = (_Float16)im; o_im[2 * j + 1] = (_Float16)re;
     }
-    // inverse (B operand, lane index n_b = m, slot k_b = sig): M[k_b][n_b] = 1/4 conj(w_16^(sig*m) w_{16TC}^(sig*t))
     sincospi(+2.0 * ((double)((m * sig) & 15) / 16.0 + (double)(sig * t) / (double)(16 * TC)), &s, &c);
     {
         const float re = 0.25f * (float)c, im = 0.25f * (float)s;
@@ -127,42 +157,36 @@ __device__ __forceinline__ uint32_t pack_bf2(float a, float b)
     cv.h = __builtin_convertvector(v, bf2);
     return cv.u;
 }
-// two bf16 in a word -> two fp16 in a word
 __device__ __forceinline__ uint32_t bf2_to_h2(uint32_t w)
 {
     return pack_h2(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
 }
-
-// plain (I_{16/r} (x) F_r) * 2^-shift operands; symmetric, so valid as A or as B operand
-__device__ Mats plain_mats(int b, bool inverse, const float2* __restrict__ tw, int lane)
+// (yr + i yi) * w in packed fp16 (one convert, v_pk_mul_f16, v_pk_fma_f16); result as fp16 complex
+__device__ __forceinline__ uint32_t cmul_pack(float yr, float yi, h2 w)
 {
-    const int r = 1 << b;
-    const int m = lane & 15, g = lane >> 4;
-    const int sh = b == 4 ? 2 : (b >= 2 ? 1 : 0);
-    const float sc = 1.0f / (float)(1 << sh);
-    Mats A;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int sig = 4 * g + q;
-        float2 w = make_float2(0.f, 0.f);
-        if ((m >> b) == (sig >> b)) {
-            w = tw_full(tw, (uint32_t)(((m & (r - 1)) * (sig & (r - 1))) & (r - 1)) << (TW_LOG2 - b));
-            if (inverse) w.y = -w.y;
-        }
-        A.re[2 * q] = (_Float16)(w.x * sc);
-        A.re[2 * q + 1] = (_Float16)(-w.y * sc);
-        A.im[2 * q] = (_Float16)(w.y * sc);
-        A.im[2 * q + 1] = (_Float16)(w.x * sc);
-    }
-    return A;
+    const f2 v = {yr, yi};
+    const h2 y = __builtin_convertvector(v, h2);
+    const h2 yx = {y[0], y[0]}, yy = {y[1], y[1]};
+    const h2 ws = {-w[1], w[0]};
+    union { h2 h; uint32_t u; } cv;
+    cv.h = __builtin_elementwise_fma(yy, ws, yx * w);
+    return cv.u;
 }
 
 #define MFMA(a, b, acc) __builtin_amdgcn_mfma_f32_16x16x32_f16((a), (b), (acc), 0, 0, 0)
 
+// LDS traffic between the lanes of one wave: hardware keeps a wave's LDS operations in order,
+// the fence only stops the compiler from moving accesses across the phase boundary.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <class IO> struct IsBf { static constexpr bool v = false; };
 template <> struct IsBf<IoBF16> { static constexpr bool v = true; };
 
-// load NB bytes (4, 8 or 16) from p (aligned to NB) into words
 template <int NW_>
 __device__ __forceinline__ void load_words(const void* p, uint32_t* w)
 {
@@ -178,218 +202,336 @@ __device__ __forceinline__ void store_words(void* p, const uint32_t* w)
     else { *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]); }
 }
 
-// -------------------------------------------------------------------------------------
-// Fused convolution, PB row pairs of one head per wave.  grid = (ceil(npairs/PB), H), block = 64.
-// -------------------------------------------------------------------------------------
-template <int LG, class IO, int PB>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2)))
-wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
-             typename IO::T* __restrict__ out, int conj, int64_t B, int64_t H, int64_t N,
-             const float2* __restrict__ tw, const unsigned char* __restrict__ wtab)
-{
-    constexpr int cb = LG - 8, TC = 1 << cb, L = 1 << LG;
-    constexpr int PITCH = 4 * TC + 1;             // 16-byte chunks per k_a row (+1: bank spread)
-    constexpr int PAIR_WORDS = 16 * PITCH * 4;    // LDS words per row pair
-    constexpr int TG = TC < 8 ? TC : 8;           // tiles handled per global load group
-    constexpr int NWD = TG / 2;                   // 32-bit words per (row, j) per group
-    extern __shared__ uint32_t lds[];
-    const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
-    const int h = blockIdx.y, p0 = blockIdx.x * PB;
-    using T = typename IO::T;
+// Raw input words of one tile group (TG tiles) for PB row pairs: per (pair, reg j) the TG
+// consecutive samples n0 .. n0+TG-1 of row a and of row b (I/O dtype, two per word).
+template <int LG, int PB>
+struct InRegs {
+    uint32_t wa[PB][4][WC<LG>::NWD], wb[PB][4][WC<LG>::NWD];
+};
 
-    const unsigned char* tb = wtab + wave_tab_offset(LG);
-    const float4* T0f = reinterpret_cast<const float4*>(tb);
-    const float4* T0i = reinterpret_cast<const float4*>(tb + (size_t(8) << LG));
-    const uint4* Gf = reinterpret_cast<const uint4*>(tb + (size_t(16) << LG));
-    const uint4* Gi = Gf + TC * 2 * 64;
-
-    const Mats F16 = plain_mats(4, false, tw, lane), I16 = plain_mats(4, true, tw, lane);
-    const Mats FL = plain_mats(cb, false, tw, lane), IL = plain_mats(cb, true, tw, lane);
-    const f4 zero = {0.f, 0.f, 0.f, 0.f};
-
+template <int PB>
+struct Rows {
     bool row_a[PB], row_b[PB];
-    const T* pa[PB];
-    const T* pb_[PB];
-#pragma unroll
-    for (int q = 0; q < PB; ++q) {
-        const int64_t b0 = 2 * (int64_t)(p0 + q);
-        row_a[q] = b0 < B;
-        row_b[q] = b0 + 1 < B;
-        pa[q] = in + row_off(row_a[q] ? b0 : 0, h, H, N);
-        pb_[q] = in + row_off(row_b[q] ? b0 + 1 : 0, h, H, N);
-    }
+    size_t oa[PB], ob[PB];
+};
 
-    // ---------------- phase 1 ----------------
-    const int w1 = (c * PITCH + g * TC) * 4;      // word address of this lane's phase-1/3 chunk, tile 0
+template <int LG, class IO, int PB>
+__device__ __forceinline__ void load_inputs(InRegs<LG, PB>& r, const typename IO::T* in, const Rows<PB>& R, int tg,
+                                            int lane)
+{
+    using C = WC<LG>;
+    const int c = lane & 15, g = lane >> 4;
 #pragma unroll
-    for (int tg = 0; tg < TC; tg += TG) {
-        uint32_t wa[PB][4][NWD], wb[PB][4][NWD];
+    for (int q = 0; q < PB; ++q)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + tg;
+#pragma unroll
+            for (int i = 0; i < C::NWD; ++i) r.wa[q][j][i] = r.wb[q][j][i] = 0u;
+            if (g < 2) {     // samples at and above N are the zero padding
+                if (R.row_a[q]) load_words<C::NWD>(in + R.oa[q] + n0, r.wa[q][j]);
+                if (R.row_b[q]) load_words<C::NWD>(in + R.ob[q] + n0, r.wb[q][j]);
+            }
+        }
+}
+
+// Phase 1 on one tile group: two chained DFT stages -> exchange buffer `xb`.  NT tiles x PB pairs
+// are advanced together, stage by stage, so that independent MFMA / ALU / LDS work overlaps.
+template <int LG, class IO, int PB>
+__device__ __forceinline__ void phase1_group(InRegs<LG, PB>& r, int tg, uint32_t* xb, const uint4* tab,
+                                             const Mats& F16, int lane)
+{
+    using C = WC<LG>;
+    constexpr int NT = (4 / PB) < C::TG ? (4 / PB) : C::TG;   // tiles advanced together (x PB pairs)
+    const int c = lane & 15, g = lane >> 4;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+    if (IsBf<IO>::v) {
 #pragma unroll
         for (int q = 0; q < PB; ++q)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int n0 = (4 * g + j) * 16 * TC + c * TC + tg;
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int i = 0; i < NWD; ++i) wa[q][j][i] = wb[q][j][i] = 0u;
-                if (g < 2) {     // samples at and above N are the zero padding
-                    if (row_a[q]) load_words<NWD>(pa[q] + n0, wa[q][j]);
-                    if (row_b[q]) load_words<NWD>(pb_[q] + n0, wb[q][j]);
-                    if (IsBf<IO>::v) {
-#pragma unroll
-                        for (int i = 0; i < NWD; ++i) {
-                            wa[q][j][i] = bf2_to_h2(wa[q][j][i]);
-                            wb[q][j][i] = bf2_to_h2(wb[q][j][i]);
-                        }
-                    }
+                for (int i = 0; i < C::NWD; ++i) {
+                    r.wa[q][j][i] = bf2_to_h2(r.wa[q][j][i]);
+                    r.wb[q][j][i] = bf2_to_h2(r.wb[q][j][i]);
                 }
-            }
+    }
 #pragma unroll
-        for (int tt = 0; tt < TG; ++tt) {
-            const int t = tg + tt;
-            const float4 t01 = T0f[(t * 64 + lane) * 2], t23 = T0f[(t * 64 + lane) * 2 + 1];
-            const float2 w0[4] = {make_float2(t01.x, t01.y), make_float2(t01.z, t01.w),
-                                  make_float2(t23.x, t23.y), make_float2(t23.z, t23.w)};
-            H8U gr, gi;
-            gr.u = Gf[(t * 2 + 0) * 64 + lane];
-            gi.u = Gf[(t * 2 + 1) * 64 + lane];
+    for (int tb = 0; tb < C::TG; tb += NT) {
+        H8U w0[NT], gr[NT], gi[NT];
+        f4 yr[NT][PB], yi[NT][PB];
+#pragma unroll
+        for (int k = 0; k < NT; ++k) {
+            const int t = tg + tb + k;
+            w0[k].u = tab[C::T0F + t * 64 + lane];
+            gr[k].u = tab[C::GF + (t * 2 + 0) * 64 + lane];
+            gi[k].u = tab[C::GF + (t * 2 + 1) * 64 + lane];
+        }
+#pragma unroll
+        for (int k = 0; k < NT; ++k)
 #pragma unroll
             for (int q = 0; q < PB; ++q) {
+                const int tt = tb + k;
                 H8U x;
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    x.w[j] = (tt & 1) ? __builtin_amdgcn_perm(wb[q][j][tt >> 1], wa[q][j][tt >> 1], 0x07060302u)
-                                      : __builtin_amdgcn_perm(wb[q][j][tt >> 1], wa[q][j][tt >> 1], 0x05040100u);
-                const f4 yr = MFMA(x.v, F16.re, zero), yi = MFMA(x.v, F16.im, zero);   // A-role over d_a
+                    x.w[j] = (tt & 1) ? __builtin_amdgcn_perm(r.wb[q][j][tt >> 1], r.wa[q][j][tt >> 1], 0x07060302u)
+                                      : __builtin_amdgcn_perm(r.wb[q][j][tt >> 1], r.wa[q][j][tt >> 1], 0x05040100u);
+                yr[k][q] = MFMA(x.v, F16.re, zero);   // A-role over d_a
+                yi[k][q] = MFMA(x.v, F16.im, zero);
+            }
+        f4 zr[NT][PB], zi[NT][PB];
+#pragma unroll
+        for (int k = 0; k < NT; ++k)
+#pragma unroll
+            for (int q = 0; q < PB; ++q) {
                 H8U u;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float2 v = cmul(make_float2(yr[j], yi[j]), w0[j]);
-                    u.w[j] = pack_h2(v.x, v.y);
-                }
-                const f4 zr = MFMA(gr.v, u.v, zero), zi = MFMA(gi.v, u.v, zero);       // B-role over d_b
+                for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][q][j], yi[k][q][j], w0[k].c[j]);
+                zr[k][q] = MFMA(gr[k].v, u.v, zero);   // B-role over d_b
+                zi[k][q] = MFMA(gi[k].v, u.v, zero);
+            }
+#pragma unroll
+        for (int k = 0; k < NT; ++k)
+#pragma unroll
+            for (int q = 0; q < PB; ++q) {
                 uint4 o;
-                o.x = pack_h2(zr[0], zi[0]); o.y = pack_h2(zr[1], zi[1]);
-                o.z = pack_h2(zr[2], zi[2]); o.w = pack_h2(zr[3], zi[3]);
-                *reinterpret_cast<uint4*>(&lds[q * PAIR_WORDS + w1 + 4 * t]) = o;
+                o.x = pack_h2(zr[k][q][0], zi[k][q][0]); o.y = pack_h2(zr[k][q][1], zi[k][q][1]);
+                o.z = pack_h2(zr[k][q][2], zi[k][q][2]); o.w = pack_h2(zr[k][q][3], zi[k][q][3]);
+                *reinterpret_cast<uint4*>(&xb[q * C::PAIR_WORDS + w1 + 4 * (tg + tb + k)]) = o;
             }
-        }
-    }
-    __syncthreads();
-
-    // ---------------- phase 2 ----------------
-    const float4* ks = reinterpret_cast<const float4*>(kspec + (size_t)h * L);
-    const float csign = conj ? -1.f : 1.f;
-#pragma unroll
-    for (int t2 = 0; t2 < TC; ++t2) {
-        int ad[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int sig = 4 * g + j;
-            const int dc = sig & (TC - 1), e = sig >> cb;
-            const int q4 = (t2 << (4 - cb)) | e;
-            const int ka = ((q4 >> 2) << 2) | (c >> 2), kbh = q4 & 3;
-            ad[j] = (ka * PITCH + kbh * TC + dc) * 4 + (c & 3);
-        }
-        const float4 k01 = ks[(t2 * 64 + lane) * 2], k23 = ks[(t2 * 64 + lane) * 2 + 1];
-        const float2 kk[4] = {make_float2(k01.x, k01.y * csign), make_float2(k01.z, k01.w * csign),
-                              make_float2(k23.x, k23.y * csign), make_float2(k23.z, k23.w * csign)};
-#pragma unroll
-        for (int q = 0; q < PB; ++q) {
-            H8U x;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) x.w[j] = lds[q * PAIR_WORDS + ad[j]];
-            const f4 yr = MFMA(FL.re, x.v, zero), yi = MFMA(FL.im, x.v, zero);
-            H8U m;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float2 v = cmul(make_float2(yr[j], yi[j]), kk[j]);
-                m.w[j] = pack_h2(v.x, v.y);
-            }
-            const f4 zr = MFMA(IL.re, m.v, zero), zi = MFMA(IL.im, m.v, zero);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) lds[q * PAIR_WORDS + ad[j]] = pack_h2(zr[j], zi[j]);
-        }
-    }
-    __syncthreads();
-
-    // ---------------- phase 3 ----------------
-    T* ya[PB];
-    T* yb[PB];
-#pragma unroll
-    for (int q = 0; q < PB; ++q) {
-        const int64_t b0 = 2 * (int64_t)(p0 + q);
-        ya[q] = out + row_off(row_a[q] ? b0 : 0, h, H, N);
-        yb[q] = out + row_off(row_b[q] ? b0 + 1 : 0, h, H, N);
-    }
-#pragma unroll
-    for (int tg = 0; tg < TC; tg += TG) {
-        uint32_t oa[PB][4][NWD], ob[PB][4][NWD];
-#pragma unroll
-        for (int tt = 0; tt < TG; tt += 2) {
-            f4 r[2][PB], s[2][PB];
-#pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                const int t = tg + tt + k;
-                const float4 t01 = T0i[(t * 64 + lane) * 2], t23 = T0i[(t * 64 + lane) * 2 + 1];
-                const float2 w0[4] = {make_float2(t01.x, t01.y), make_float2(t01.z, t01.w),
-                                      make_float2(t23.x, t23.y), make_float2(t23.z, t23.w)};
-                H8U gr, gi;
-                gr.u = Gi[(t * 2 + 0) * 64 + lane];
-                gi.u = Gi[(t * 2 + 1) * 64 + lane];
-#pragma unroll
-                for (int q = 0; q < PB; ++q) {
-                    H8U x;
-                    x.u = *reinterpret_cast<const uint4*>(&lds[q * PAIR_WORDS + w1 + 4 * t]);
-                    const f4 yr = MFMA(x.v, gr.v, zero), yi = MFMA(x.v, gi.v, zero);   // A-role over k_b
-                    H8U u;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float2 v = cmul(make_float2(yr[j], yi[j]), w0[j]);
-                        u.w[j] = pack_h2(v.x, v.y);
-                    }
-                    r[k][q] = MFMA(I16.re, u.v, zero);                                   // B-role over k_a
-                    s[k][q] = MFMA(I16.im, u.v, zero);
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < PB; ++q)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (IsBf<IO>::v) {
-                        oa[q][j][tt >> 1] = pack_bf2(r[0][q][j], r[1][q][j]);
-                        ob[q][j][tt >> 1] = pack_bf2(s[0][q][j], s[1][q][j]);
-                    } else {
-                        oa[q][j][tt >> 1] = pack_h2(r[0][q][j], r[1][q][j]);
-                        ob[q][j][tt >> 1] = pack_h2(s[0][q][j], s[1][q][j]);
-                    }
-                }
-        }
-        if (g < 2) {     // n_a < 8: the first N samples
-#pragma unroll
-            for (int q = 0; q < PB; ++q)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int n0 = (4 * g + j) * 16 * TC + c * TC + tg;
-                    if (row_a[q]) store_words<NWD>(ya[q] + n0, oa[q][j]);
-                    if (row_b[q]) store_words<NWD>(yb[q] + n0, ob[q][j]);
-                }
-        }
     }
 }
 
-template <int LG, class IO, int PB>
+// word address (within a pair's exchange buffer) of phase-2 tile t2, register j, for this lane
+template <int LG>
+__device__ __forceinline__ int phase2_addr(int t2, int j, int lane)
+{
+    using C = WC<LG>;
+    const int c = lane & 15, g = lane >> 4;
+    const int sig = 4 * g + j;
+    const int dc = sig & (C::TC - 1), e = sig >> C::cb;
+    const int q4 = (t2 << (4 - C::cb)) | e;
+    const int ka = ((q4 >> 2) << 2) | (c >> 2), kbh = q4 & 3;
+    return (ka * C::PITCH + kbh * C::TC + dc) * 4 + (c & 3);
+}
+
+// -------------------------------------------------------------------------------------
+// Fused convolution.  Each wave processes `gpw` consecutive groups of PB row pairs (groups are
+// numbered head-major).  block = NWV waves.
+// -------------------------------------------------------------------------------------
+template <int LG, class IO, int PB, int NWV>
+__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
+wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
+             typename IO::T* __restrict__ out, int conj, int64_t B, int64_t H, int64_t N, int gph,
+             int total_groups, int gpw, const unsigned char* __restrict__ wtab)
+{
+    using C = WC<LG>;
+    constexpr int NT = (4 / PB) < C::TG ? (4 / PB) : C::TG;   // tiles advanced together (x PB pairs)
+    extern __shared__ uint4 lds4[];
+    uint32_t* lds = reinterpret_cast<uint32_t*>(lds4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+
+    auto rows_of = [&](int group, Rows<PB>& R, int& h) {
+        h = group / gph;
+        const int p0 = (group - h * gph) * PB;
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const int64_t b0 = 2 * (int64_t)(p0 + q);
+            R.row_a[q] = b0 < B;
+            R.row_b[q] = b0 + 1 < B;
+            R.oa[q] = row_off(R.row_a[q] ? b0 : 0, h, H, N);
+            R.ob[q] = row_off(R.row_b[q] ? b0 + 1 : 0, h, H, N);
+        }
+    };
+    // first group's rows start travelling before anything else
+    const int group0 = (blockIdx.x * NWV + wave) * gpw;
+    InRegs<LG, PB> inr;
+    Rows<PB> R;
+    int h = 0;
+    if (group0 < total_groups) {
+        rows_of(group0, R, h);
+        load_inputs<LG, IO, PB>(inr, in, R, 0, lane);
+    }
+    {   // constant tables: global -> LDS, once per workgroup
+        const uint4* gt = reinterpret_cast<const uint4*>(wtab + wave_tab_offset(LG));
+        for (int i = tid; i < C::TAB_U4; i += NWV * 64) lds4[i] = gt[i];
+    }
+    __syncthreads();
+    const uint4* tab = lds4;
+    Mats F16, I16, FL, IL;
+    {
+        H8U m;
+        m.u = tab[C::PM + 0 * 64 + lane]; F16.re = m.v;
+        m.u = tab[C::PM + 1 * 64 + lane]; F16.im = m.v;
+        m.u = tab[C::PM + 2 * 64 + lane]; I16.re = m.v;
+        m.u = tab[C::PM + 3 * 64 + lane]; I16.im = m.v;
+        m.u = tab[C::PM + 4 * 64 + lane]; FL.re = m.v;
+        m.u = tab[C::PM + 5 * 64 + lane]; FL.im = m.v;
+        m.u = tab[C::PM + 6 * 64 + lane]; IL.re = m.v;
+        m.u = tab[C::PM + 7 * 64 + lane]; IL.im = m.v;
+    }
+    uint32_t* xb = lds + C::TAB_U4 * 4 + wave * (PB * C::PAIR_WORDS);
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    const float csign = conj ? -1.f : 1.f;
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+
+    for (int gi_ = 0; gi_ < gpw; ++gi_) {
+        const int group = group0 + gi_;
+        if (group >= total_groups) break;
+        const Rows<PB> Rc = R;
+        const int hcur = h;
+
+        // ---------------- phase 1 ----------------
+#pragma unroll
+        for (int tg = 0; tg < C::TC; tg += C::TG) {
+            if (tg > 0) load_inputs<LG, IO, PB>(inr, in, Rc, tg, lane);
+            phase1_group<LG, IO, PB>(inr, tg, xb, tab, F16, lane);
+        }
+        // the next group's rows start travelling now and land while phases 2 and 3 run
+        if (gi_ + 1 < gpw && group + 1 < total_groups) {
+            rows_of(group + 1, R, h);
+            load_inputs<LG, IO, PB>(inr, in, R, 0, lane);
+        }
+        wave_lds_fence();
+
+        // ---------------- phase 2 ----------------
+        const float4* ks = reinterpret_cast<const float4*>(kspec + (size_t)hcur * C::L);
+#pragma unroll
+        for (int tb = 0; tb < C::TC; tb += NT) {
+            int ad[NT][4];
+            float2 kk[NT][4];
+            f4 yr[NT][PB], yi[NT][PB];
+#pragma unroll
+            for (int k = 0; k < NT; ++k) {
+                const int t2 = tb + k;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) ad[k][j] = phase2_addr<LG>(t2, j, lane);
+                const float4 k01 = ks[(t2 * 64 + lane) * 2], k23 = ks[(t2 * 64 + lane) * 2 + 1];
+                kk[k][0] = make_float2(k01.x, k01.y * csign); kk[k][1] = make_float2(k01.z, k01.w * csign);
+                kk[k][2] = make_float2(k23.x, k23.y * csign); kk[k][3] = make_float2(k23.z, k23.w * csign);
+            }
+#pragma unroll
+            for (int k = 0; k < NT; ++k)
+#pragma unroll
+                for (int q = 0; q < PB; ++q) {
+                    H8U x;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) x.w[j] = xb[q * C::PAIR_WORDS + ad[k][j]];
+                    yr[k][q] = MFMA(FL.re, x.v, zero);
+                    yi[k][q] = MFMA(FL.im, x.v, zero);
+                }
+            f4 zr[NT][PB], zi[NT][PB];
+#pragma unroll
+            for (int k = 0; k < NT; ++k)
+#pragma unroll
+                for (int q = 0; q < PB; ++q) {
+                    H8U m;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float2 v = cmul(make_float2(yr[k][q][j], yi[k][q][j]), kk[k][j]);
+                        m.w[j] = pack_h2(v.x, v.y);
+                    }
+                    zr[k][q] = MFMA(IL.re, m.v, zero);
+                    zi[k][q] = MFMA(IL.im, m.v, zero);
+                }
+#pragma unroll
+            for (int k = 0; k < NT; ++k)
+#pragma unroll
+                for (int q = 0; q < PB; ++q)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        xb[q * C::PAIR_WORDS + ad[k][j]] = pack_h2(zr[k][q][j], zi[k][q][j]);
+        }
+        wave_lds_fence();
+
+        // ---------------- phase 3 ----------------
+#pragma unroll
+        for (int tg = 0; tg < C::TC; tg += C::TG) {
+            uint32_t oa[PB][4][C::NWD], ob[PB][4][C::NWD];
+#pragma unroll
+            for (int tb = 0; tb < C::TG; tb += NT) {
+                H8U w0[NT], gr[NT], gi[NT];
+                f4 yr[NT][PB], yi[NT][PB], r[NT][PB], s[NT][PB];
+#pragma unroll
+                for (int k = 0; k < NT; ++k) {
+                    const int t = tg + tb + k;
+                    w0[k].u = tab[C::T0I + t * 64 + lane];
+                    gr[k].u = tab[C::GI + (t * 2 + 0) * 64 + lane];
+                    gi[k].u = tab[C::GI + (t * 2 + 1) * 64 + lane];
+                }
+#pragma unroll
+                for (int k = 0; k < NT; ++k)
+#pragma unroll
+                    for (int q = 0; q < PB; ++q) {
+                        H8U x;
+                        x.u = *reinterpret_cast<const uint4*>(&xb[q * C::PAIR_WORDS + w1 + 4 * (tg + tb + k)]);
+                        yr[k][q] = MFMA(x.v, gr[k].v, zero);   // A-role over k_b
+                        yi[k][q] = MFMA(x.v, gi[k].v, zero);
+                    }
+#pragma unroll
+                for (int k = 0; k < NT; ++k)
+#pragma unroll
+                    for (int q = 0; q < PB; ++q) {
+                        H8U u;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][q][j], yi[k][q][j], w0[k].c[j]);
+                        r[k][q] = MFMA(I16.re, u.v, zero);     // B-role over k_a
+                        s[k][q] = MFMA(I16.im, u.v, zero);
+                    }
+#pragma unroll
+                for (int k = 0; k < NT; k += 2)
+#pragma unroll
+                    for (int q = 0; q < PB; ++q)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            if (IsBf<IO>::v) {
+                                oa[q][j][(tb + k) >> 1] = pack_bf2(r[k][q][j], r[k + 1][q][j]);
+                                ob[q][j][(tb + k) >> 1] = pack_bf2(s[k][q][j], s[k + 1][q][j]);
+                            } else {
+                                oa[q][j][(tb + k) >> 1] = pack_h2(r[k][q][j], r[k + 1][q][j]);
+                                ob[q][j][(tb + k) >> 1] = pack_h2(s[k][q][j], s[k + 1][q][j]);
+                            }
+                        }
+            }
+            if (g < 2) {     // n_a < 8: the first N samples
+#pragma unroll
+                for (int q = 0; q < PB; ++q)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + tg;
+                        if (Rc.row_a[q]) store_words<C::NWD>(out + Rc.oa[q] + n0, oa[q][j]);
+                        if (Rc.row_b[q]) store_words<C::NWD>(out + Rc.ob[q] + n0, ob[q][j]);
+                    }
+            }
+        }
+        wave_lds_fence();
+    }
+}
+
+template <int LG, class IO, int PB, int NWV>
 hipError_t wconv_go(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
                     const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
-    constexpr int TC = 1 << (LG - 8);
-    const size_t lds = (size_t)PB * 16 * (4 * TC + 1) * 16;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wconv_kernel<LG, IO, PB>),
+    using C = WC<LG>;
+    const size_t lds = (size_t)C::TAB_U4 * 16 + (size_t)NWV * PB * C::PAIR_WORDS * 4;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wconv_kernel<LG, IO, PB, NWV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    dim3 grid((pr.npairs + PB - 1) / PB, (unsigned)pr.H);
-    hipLaunchKernelGGL((wconv_kernel<LG, IO, PB>), grid, dim3(64), lds, st, (const T*)in, kspec, (T*)out,
-                       conj ? 1 : 0, pr.B, pr.H, pr.N, tb.tw, (const unsigned char*)tb.wtab);
+    const int gph = (pr.npairs + PB - 1) / PB;
+    const long total = (long)gph * pr.H;
+    // persistent workgroups: as many as fit on the 256 compute units at once, equal shares
+    long fit = (long)(160 * 1024) / (long)lds;
+    fit = fit < 1 ? 1 : (fit > 4 ? 4 : fit);
+    long gpw = (total + 256 * fit * NWV - 1) / (256 * fit * NWV);
+    if (gpw < 1) gpw = 1;
+    const long nblk = (total + gpw * NWV - 1) / (gpw * NWV);
+    hipLaunchKernelGGL((wconv_kernel<LG, IO, PB, NWV>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st,
+                       (const T*)in, kspec, (T*)out, conj ? 1 : 0, pr.B, pr.H, pr.N, gph, (int)total, (int)gpw,
+                       (const unsigned char*)tb.wtab);
     return hipGetLastError();
 }
 
@@ -397,12 +539,11 @@ template <class IO>
 hipError_t wconv_io(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr, const Plan& pl,
                     const Tables& tb, hipStream_t st)
 {
-    constexpr int PB = 2;
     switch (pl.log2L2) {
-        case 9: return wconv_go<9, IO, PB>(in, kspec, out, conj, pr, tb, st);
-        case 10: return wconv_go<10, IO, PB>(in, kspec, out, conj, pr, tb, st);
-        case 11: return wconv_go<11, IO, PB>(in, kspec, out, conj, pr, tb, st);
-        case 12: return wconv_go<12, IO, PB>(in, kspec, out, conj, pr, tb, st);
+        case 9: return wconv_go<9, IO, 2, 8>(in, kspec, out, conj, pr, tb, st);
+        case 10: return wconv_go<10, IO, 2, 8>(in, kspec, out, conj, pr, tb, st);
+        case 11: return wconv_go<11, IO, 1, 12>(in, kspec, out, conj, pr, tb, st);
+        case 12: return wconv_go<12, IO, 1, 3>(in, kspec, out, conj, pr, tb, st);
         default: return hipErrorInvalidValue;
     }
 }
