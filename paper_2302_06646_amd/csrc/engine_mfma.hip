@@ -551,6 +551,8 @@ hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __
                    __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl, const Tables& tb,
                    hipStream_t st)
 {
+    // L = 4096 keeps the cooperative kernel: its accumulators do not fit one wave's registers
+    if (pl.order.wave_lg && pl.log2L2 <= 11) return wave_dk(dy, u, dk, dD, pr, pl, tb, st);
     if (pr.io == LONGCONV_F16) {
         LC_LG_SWITCH(dk_go, IoF16, dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, pr, pl, tb, st)
     }

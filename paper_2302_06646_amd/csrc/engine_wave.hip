@@ -511,6 +511,207 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
     }
 }
 
+// -------------------------------------------------------------------------------------
+// dk and dD for one head per workgroup pass (workgroups loop over heads).  Each wave transforms
+// some of the head's row pairs: Z = transform of the u pair (kept as fp16 in registers), W =
+// transform of the dy pair, A += conj(Z) W in fp32 registers, in the lane order of phase 2.  The
+// waves' partial A are summed through LDS in a fixed binary tree (bitwise repeatable), wave 0
+// runs the inverse of phase 2 on the total, and all waves share phase 3, whose real part is
+// dk (the cross terms between the two rows of a pair are purely imaginary).  dD is the lag-0
+// correlation, sum_f Re(A_f) / L (Parseval), taken from the fp32 total.
+// -------------------------------------------------------------------------------------
+template <int LG, class IO, int NWV>
+__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
+wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u, float* __restrict__ dk,
+           float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs, float dkscale, float dDscale,
+           const unsigned char* __restrict__ wtab)
+{
+    using C = WC<LG>;
+    using T = typename IO::T;
+    extern __shared__ uint4 lds4[];
+    uint32_t* lds = reinterpret_cast<uint32_t*>(lds4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    {
+        const uint4* gt = reinterpret_cast<const uint4*>(wtab + wave_tab_offset(LG));
+        for (int i = tid; i < C::TAB_U4; i += NWV * 64) lds4[i] = gt[i];
+    }
+    __syncthreads();
+    const uint4* tab = lds4;
+    Mats F16, I16, FL, IL;
+    {
+        H8U m;
+        m.u = tab[C::PM + 0 * 64 + lane]; F16.re = m.v;
+        m.u = tab[C::PM + 1 * 64 + lane]; F16.im = m.v;
+        m.u = tab[C::PM + 2 * 64 + lane]; I16.re = m.v;
+        m.u = tab[C::PM + 3 * 64 + lane]; I16.im = m.v;
+        m.u = tab[C::PM + 4 * 64 + lane]; FL.re = m.v;
+        m.u = tab[C::PM + 5 * 64 + lane]; FL.im = m.v;
+        m.u = tab[C::PM + 6 * 64 + lane]; IL.re = m.v;
+        m.u = tab[C::PM + 7 * 64 + lane]; IL.im = m.v;
+    }
+    uint32_t* xall = lds + C::TAB_U4 * 4;                 // NWV exchange buffers, reused for the reduction
+    uint32_t* xb = xall + wave * C::PAIR_WORDS;
+    float2* red = reinterpret_cast<float2*>(xall);        // slot s: red[(s*TC*4 + i)*64 + lane]
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+
+    for (int h = blockIdx.x; h < H; h += gridDim.x) {
+        float2 acc[C::TC][4];
+#pragma unroll
+        for (int t = 0; t < C::TC; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[t][j] = make_float2(0.f, 0.f);
+
+        for (int p = wave; p < npairs; p += NWV) {
+            Rows<1> R;
+            const int64_t b0 = 2 * (int64_t)p;
+            R.row_a[0] = true;
+            R.row_b[0] = b0 + 1 < B;
+            R.oa[0] = row_off(b0, h, H, N);
+            R.ob[0] = row_off(R.row_b[0] ? b0 + 1 : b0, h, H, N);
+            uint32_t z[C::TC][4];
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {     // 0: u pair -> Z, 1: dy pair -> W
+                const T* src = pass == 0 ? u : dy;
+                InRegs<LG, 1> inr;
+#pragma unroll
+                for (int tg = 0; tg < C::TC; tg += C::TG) {
+                    load_inputs<LG, IO, 1>(inr, src, R, tg, lane);
+                    phase1_group<LG, IO, 1>(inr, tg, xb, tab, F16, lane);
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (int t2 = 0; t2 < C::TC; ++t2) {
+                    H8U x;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) x.w[j] = xb[phase2_addr<LG>(t2, j, lane)];
+                    const f4 yr = MFMA(FL.re, x.v, zero), yi = MFMA(FL.im, x.v, zero);
+                    if (pass == 0) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) z[t2][j] = pack_h2(yr[j], yi[j]);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            union { uint32_t u; h2 h; } cv;
+                            cv.u = z[t2][j];
+                            const float zr = (float)cv.h[0], zi = (float)cv.h[1];
+                            acc[t2][j].x += zr * yr[j] + zi * yi[j];      // conj(Z) * W
+                            acc[t2][j].y += zr * yi[j] - zi * yr[j];
+                        }
+                    }
+                }
+                wave_lds_fence();
+            }
+        }
+
+        // ---- sum the waves' partial A in a fixed tree through LDS
+        __syncthreads();
+#pragma unroll
+        for (int active = NWV; active > 1; active >>= 1) {
+            const int half = active >> 1;
+            if (wave >= half && wave < active) {
+                float2* dst = red + (size_t)(wave - half) * C::TC * 4 * 64;
+#pragma unroll
+                for (int t = 0; t < C::TC; ++t)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) dst[(t * 4 + j) * 64 + lane] = acc[t][j];
+            }
+            __syncthreads();
+            if (wave < half) {
+                const float2* srcp = red + (size_t)wave * C::TC * 4 * 64;
+#pragma unroll
+                for (int t = 0; t < C::TC; ++t)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float2 v = srcp[(t * 4 + j) * 64 + lane];
+                        acc[t][j].x += v.x; acc[t][j].y += v.y;
+                    }
+            }
+            __syncthreads();
+        }
+        // ---- wave 0: dD, then inverse of phase 2 into exchange buffer 0
+        if (wave == 0) {
+            if (dD) {
+                float dsum = 0.f;
+#pragma unroll
+                for (int t = 0; t < C::TC; ++t)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) dsum += acc[t][j].x;
+                for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+                if (lane == 0) dD[h] = dsum * dDscale;
+            }
+            if (dk) {
+#pragma unroll
+                for (int t2 = 0; t2 < C::TC; ++t2) {
+                    H8U m;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(acc[t2][j].x, acc[t2][j].y);
+                    const f4 zr = MFMA(IL.re, m.v, zero), zi = MFMA(IL.im, m.v, zero);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) xall[phase2_addr<LG>(t2, j, lane)] = pack_h2(zr[j], zi[j]);
+                }
+            }
+        }
+        __syncthreads();
+        // ---- phase 3 shared by the waves: tile t -> real part -> dk
+        if (dk) {
+            for (int t = wave; t < C::TC; t += NWV) {
+                H8U w0, gr, gi, x;
+                w0.u = tab[C::T0I + t * 64 + lane];
+                gr.u = tab[C::GI + (t * 2 + 0) * 64 + lane];
+                gi.u = tab[C::GI + (t * 2 + 1) * 64 + lane];
+                x.u = *reinterpret_cast<const uint4*>(&xall[w1 + 4 * t]);
+                const f4 yr = MFMA(x.v, gr.v, zero), yi = MFMA(x.v, gi.v, zero);
+                H8U uu;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) uu.w[j] = cmul_pack(yr[j], yi[j], w0.c[j]);
+                const f4 r = MFMA(I16.re, uu.v, zero);
+                if (g < 2) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        dk[(size_t)h * N + (4 * g + j) * 16 * C::TC + c * C::TC + t] = r[j] * dkscale;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int LG, class IO, int NWV>
+hipError_t wdk_go(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
+                  const Tables& tb, hipStream_t st)
+{
+    using T = typename IO::T;
+    using C = WC<LG>;
+    const size_t lds = (size_t)C::TAB_U4 * 16 + (size_t)NWV * C::PAIR_WORDS * 4;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wdk_kernel<LG, IO, NWV>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    long fit = (long)(160 * 1024) / (long)lds;
+    fit = fit < 1 ? 1 : (fit > 4 ? 4 : fit);
+    const long nblk = pr.H < 256 * fit ? pr.H : 256 * fit;
+    // forward chains scale by c = 2^-shift each: A carries c^2, dk's inverse chain another c
+    int shift = 4 + (C::cb == 4 ? 2 : (C::cb >= 2 ? 1 : 0));
+    const float dDscale = pl.dkscale / (float)(1 << shift);
+    hipLaunchKernelGGL((wdk_kernel<LG, IO, NWV>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st, (const T*)dy,
+                       (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, pl.dkscale, dDscale,
+                       (const unsigned char*)tb.wtab);
+    return hipGetLastError();
+}
+
+template <class IO>
+hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
+                  const Tables& tb, hipStream_t st)
+{
+    switch (pl.log2L2) {
+        case 9: return wdk_go<9, IO, 8>(dy, u, dk, dD, pr, pl, tb, st);
+        case 10: return wdk_go<10, IO, 8>(dy, u, dk, dD, pr, pl, tb, st);
+        case 11: return wdk_go<11, IO, 8>(dy, u, dk, dD, pr, pl, tb, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 template <int LG, class IO, int PB, int NWV>
 hipError_t wconv_go(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
                     const Tables& tb, hipStream_t st)
@@ -555,6 +756,14 @@ hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, 
 {
     if (pr.io == LONGCONV_F16) return wconv_io<IoF16>(in, kspec, out, conj, pr, pl, tb, st);
     if (pr.io == LONGCONV_BF16) return wconv_io<IoBF16>(in, kspec, out, conj, pr, pl, tb, st);
+    return hipErrorInvalidValue;
+}
+
+hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
+                   const Tables& tb, hipStream_t st)
+{
+    if (pr.io == LONGCONV_F16) return wdk_io<IoF16>(dy, u, dk, dD, pr, pl, tb, st);
+    if (pr.io == LONGCONV_BF16) return wdk_io<IoBF16>(dy, u, dk, dD, pr, pl, tb, st);
     return hipErrorInvalidValue;
 }
 

@@ -56,5 +56,7 @@ constexpr int WAVE_MIN_LOG2 = 9, WAVE_MAX_LOG2 = 12;
 hipError_t wave_fill_tables(const void** tab_out, hipStream_t st);
 hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
                      const Plan& pl, const Tables& tb, hipStream_t st);
+hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
+                   const Tables& tb, hipStream_t st);
 
 }  // namespace lc
