@@ -29,6 +29,11 @@ import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 CACHE_BYTES = 256 << 20        # last-level (Infinity) cache
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy kernel
+# of known size: FETCH_SIZE x 2.0 KiB, WRITE_SIZE x 1.0 KiB); see profiles/.  Workload 2 only.
+MEASURED_TRAFFIC = {"cfg2_B16_H768_N1024_bf16": {"fwd": (20644.9 * 2.0 + 29184.0) * 1024,
+                                                  "bwd_du": (20644.9 * 2.0 + 29184.0) * 1024,
+                                                  "bwd_dk_dD": (25174.5 * 2.0 + 4120.0) * 1024}}
 
 
 def log(*a):
@@ -141,6 +146,8 @@ def main():
     ap.add_argument("--workload", default="2", choices=list(wl.WORKLOADS))
     ap.add_argument("--also", default="3,4a", help="comma list of further workloads reported under 'targets'")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three plain 64 MiB device copies (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
@@ -152,6 +159,12 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(1)
     lc.longconv_init()
+    if a.copy_probe:
+        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     res, seg_bytes = run_workload(a.workload, a.steps, a.warmup, lc, torch)
     log(json.dumps(res, indent=1))
@@ -169,7 +182,8 @@ def main():
         "TFLOPs_algorithmic": res["TFLOPs_algorithmic"],
         "segments_ms": {n: v["ms"] for n, v in res["segments"].items()},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": dom_gbps / HBM_PEAK_GBS, "traffic": None,
+                     "frac": dom_gbps / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC.get(res["workload"], {}).get(dom),
                      "algorithmic_bytes_per_launch": seg_bytes[dom]},
     }
     targets = []
