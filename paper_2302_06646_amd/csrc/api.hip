@@ -69,6 +69,8 @@ static hipError_t get_tables(Tables* out, hipStream_t st, bool sync_device)
         if (e != hipSuccess) return e;
         e = note(wave_fill_tables(&g_tab[dev].wtab, st), "fill wave tables");
         if (e != hipSuccess) return e;
+        e = note(coop_fill_tables(&g_tab[dev].ctab, st), "fill coop tables");
+        if (e != hipSuccess) return e;
         e = note(sync_device ? hipDeviceSynchronize() : hipStreamSynchronize(st), "table sync");
         if (e != hipSuccess) return e;
         g_tab[dev].stw = q;
@@ -114,6 +116,8 @@ Plan make_plan(int64_t N, int io)
     if (pl.engine == ENGINE_VALU) {
         pl.order.ndig = 0;
         pl.order.wave_lg = 0;
+        pl.order.coop_lg = 0;
+        pl.order.outer_bits = 0;
         if (pl.log2R) pl.order.bits[pl.order.ndig++] = (unsigned char)pl.log2R;
         for (int i = 0; i < pl.log2L2; ++i) pl.order.bits[pl.order.ndig++] = 1;
         pl.kscale = invL;
@@ -128,7 +132,7 @@ static size_t cw_bytes(const Plan& pl) { return pl.engine == ENGINE_VALU ? sizeo
 static size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 
 struct WsLayout {
-    size_t kspec, kscratch, ws1, ws2, wsA, dpart, total;
+    size_t kspec, kscratch, ws1, ws2, wsA, dpart, zbuf, total;
     int nblk;
 };
 
@@ -146,6 +150,7 @@ static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool back
     w.nblk = (int)(npairs * ((size_t(1) << pl.log2L2) / 256));
     const size_t npart = (size_t)w.nblk > (size_t(1) << pl.log2R) ? (size_t)w.nblk : (size_t(1) << pl.log2R);
     w.dpart = off; if (pl.log2R && backward) off += up256((size_t)H * npart * sizeof(float));
+    w.zbuf = off; if (backward && pl.order.coop_lg) off += up256((size_t)H * L * sizeof(__half2));
     w.total = off;
     return w;
 }
@@ -314,7 +319,7 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
             }
             if (e == hipSuccess)
                 e = mfma_dk(dy, u, dk, dD, (const __half2*)(base + w.ws2), (const __half2*)(base + w.ws1),
-                            (__half2*)(base + w.wsA), dD ? dpart : nullptr, pr, pl, tb, st);
+                            (__half2*)(base + w.wsA), dD ? dpart : nullptr, base + w.zbuf, pr, pl, tb, st);
             if (e == hipSuccess && pl.log2R && dD) e = reduce_dD(dpart, dD, H, 1 << pl.log2R, st);
         }
         if (e == hipSuccess && pl.log2R && dk) {
@@ -363,7 +368,8 @@ const char* longconv_plan_string(int64_t N, int io)
                      pl.log2R ? 3 : 1);
     for (int i = 0; i < pl.order.ndig && n < (int)sizeof(buf) - 4; ++i)
         n += snprintf(buf + n, sizeof(buf) - n, "%s%d", i ? "x" : "", 1 << pl.order.bits[i]);
-    if (pl.order.wave_lg) snprintf(buf + n, sizeof(buf) - n, " fwd_kernel=wave");
+    if (pl.order.wave_lg) snprintf(buf + n, sizeof(buf) - n, " kernel=wave");
+    if (pl.order.coop_lg) snprintf(buf + n, sizeof(buf) - n, " kernel=chained");
     return buf;
 }
 

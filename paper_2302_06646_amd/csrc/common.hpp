@@ -28,6 +28,7 @@ struct Tables {
     const float2* tw;    // g_tw
     const float2* stw;   // stage twiddles
     const void* wtab;    // lane-ordered constants of the wave-autonomous kernels
+    const void* ctab;    // lane-ordered constants of the cooperative chained kernels
 };
 
 // exp(-2*pi*i*idx/TW_L) for any idx in [0, TW_L)
@@ -102,6 +103,8 @@ struct SpecOrder {
     int ndig;
     unsigned char bits[20];
     int wave_lg;   // != 0: lane order of the wave-autonomous kernels for L = 2^wave_lg instead
+    int coop_lg;   // != 0: outer digit (outer_bits wide), then lane order of the cooperative chained
+    int outer_bits;  //       kernels for an inner length 2^coop_lg
 };
 
 // Storage position of frequency f = k_a + 16 k_b + 256 k_c in the spectrum consumed by the
@@ -118,9 +121,22 @@ __host__ __device__ inline uint32_t wave_spec_pos(uint32_t f, int LG)
     return ((t2 * 64u + (sig >> 2) * 16u + c2) << 2) | (sig & 3u);
 }
 
+// Same for the cooperative chained kernels, f = k_a + 16 k_b + 256 k_c + 4096 k_e, L = 2^LG = 4096 * 2^te.
+__host__ __device__ inline uint32_t coop_spec_pos(uint32_t f, int LG)
+{
+    const int te = LG - 12;
+    const uint32_t ka = f & 15u, kb = (f >> 4) & 15u, kc = (f >> 8) & 15u, ke = f >> 12;
+    const uint32_t e = kb & ((1u << (4 - te)) - 1u), kbh = kb >> (4 - te);
+    const uint32_t t2 = (ka << te) | kbh;
+    const uint32_t xo = (e << te) | ke;
+    return ((t2 * 64u + (xo >> 2) * 16u + kc) << 2) | (xo & 3u);
+}
+
 __host__ __device__ inline uint32_t spec_pos(uint32_t f, const SpecOrder& o)
 {
     if (o.wave_lg) return wave_spec_pos(f, o.wave_lg);
+    if (o.coop_lg)
+        return ((f & ((1u << o.outer_bits) - 1u)) << o.coop_lg) | coop_spec_pos(f >> o.outer_bits, o.coop_lg);
     uint32_t pos = 0;
     for (int s = 0; s < o.ndig; ++s) {
         const uint32_t b = o.bits[s];

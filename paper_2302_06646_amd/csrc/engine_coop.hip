@@ -1,0 +1,636 @@
+// Workgroup-cooperative chained kernels for 8192 <= L2 <= 32768 (one row pair, or one chunk of
+// the multi-pass split, per workgroup at a time; the pair lives in LDS only between phases).
+//
+// L2 = 16 * 16 * 16 * TE, TE = 2^te in {2,4,8}; TC = 16*TE.  Time index
+// n = d_a*16*TC + d_b*TC + d_c*TE + d_e, frequency f = k_a + 16 k_b + 256 k_c + 4096 k_e
+// (Section 3.2 "Butterfly Decomposition", applied three times; twiddles of Appendix C.1).
+// As in the wave-autonomous kernels an "A-role" MFMA (data as A operand) contracts the slot index
+// and transposes the tile, a "B-role" MFMA contracts it in place, so two digits are contracted
+// per trip through registers and the row crosses LDS only twice per transform pair:
+//   phase 1 (tile t = d_c*TE+d_e): global -> [A: F16 over d_a] * w_L^(k_a(d_b TC + t))
+//                                  -> [B: F16 over d_b] * w_{16TC}^(k_b t) -> LDS
+//   phase 2 (tile = (k_a, high bits of k_b)): LDS -> [A: F16 over d_c] * w_TC^(k_c d_e)
+//            -> [B: F_TE over d_e] * spectrum -> [A: F_TE^-1] * conj -> [B: F16^-1 over k_c] -> LDS
+//   phase 3 (tile t): LDS * conj(w_{16TC}) -> [A: F16^-1 over k_b] * conj(w_L) -> [B: F16^-1 over k_a]
+//                                  -> global (first half only when the input was zero padded)
+// Each wave owns groups of 8 consecutive tiles in every phase; workgroup barriers separate
+// the phases.  The w_L twiddles come from a lane-ordered global table (fp16, one 16-byte load per
+// lane and tile), the w_{16TC} ones from a small table in LDS, the w_TC ones are per-lane constants.
+#include "engines.hpp"
+#include "mfma_util.hpp"
+
+namespace lc {
+
+template <int LG>
+struct CC {
+    static constexpr int cb = LG - 8, TC = 1 << cb, te = cb - 4, TE = 1 << te, L = 1 << LG;
+    static constexpr int PITCH = 4 * TC + 1;           // 16-byte chunks per k_a row
+    static constexpr int XWORDS = 16 * PITCH * 4;      // exchange buffer, 32-bit words
+    static constexpr int NW = TC / 8 > 8 ? 8 : TC / 8; // waves per workgroup
+    static constexpr int NG = TC / (8 * NW);           // groups of 8 tiles per wave and phase
+    // constant table in uint4 units (global): lane-ordered w_L twiddles, then the w_{16TC} table
+    static constexpr int T0F = 0;                      // [TC][64]
+    static constexpr int T0I = TC * 64;                // [TC][64]
+    static constexpr int T1F = 2 * TC * 64;            // [TC][4]   (t, lane/16): four fp16 complex
+    static constexpr int T1I = T1F + TC * 4;           // [TC][4]
+    static constexpr int TAB_U4 = T1I + TC * 4;
+};
+
+__host__ __device__ constexpr size_t coop_tab_offset(int LG)
+{
+    size_t o = 0;
+    for (int l = 13; l < LG; ++l) o += ((size_t)(1 << (l - 8)) * 136) * 16;
+    return o;
+}
+constexpr size_t COOP_TAB_TOTAL = coop_tab_offset(16);
+
+__device__ unsigned char g_coop_tab[COOP_TAB_TOTAL] __attribute__((aligned(256)));
+
+// T0F : w_L^(k_a (d_b TC + t)),       k_a = lane%16, d_b = 4 (lane/16) + j
+// T0I : conj w_L^(k_a (n_b TC + t)),  n_b = lane%16, k_a = 4 (lane/16) + j
+// T1F : w_{16TC}^(k_b t), T1I its conjugate, k_b = 4 g + j
+__global__ void fill_coop_tab_kernel(unsigned char* tab, int LG)
+{
+    const int cb = LG - 8, TC = 1 << cb, L = 1 << LG;
+    _Float16* base = reinterpret_cast<_Float16*>(tab + coop_tab_offset(LG));
+    _Float16* T0f = base;
+    _Float16* T0i = base + (size_t)TC * 64 * 8;
+    _Float16* T1f = base + (size_t)2 * TC * 64 * 8;
+    _Float16* T1i = T1f + (size_t)TC * 4 * 8;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= L) return;
+    const int j = i & 3, lane = (i >> 2) & 63, t = i >> 8;
+    const int x = lane & 15, y = 4 * (lane >> 4) + j;
+    double s, c;
+    sincospi(-2.0 * (double)((x * (y * TC + t)) & (L - 1)) / (double)L, &s, &c);
+    T0f[((size_t)t * 64 + lane) * 8 + 2 * j] = (_Float16)c;
+    T0f[((size_t)t * 64 + lane) * 8 + 2 * j + 1] = (_Float16)s;
+    sincospi(+2.0 * (double)((y * (x * TC + t)) & (L - 1)) / (double)L, &s, &c);
+    T0i[((size_t)t * 64 + lane) * 8 + 2 * j] = (_Float16)c;
+    T0i[((size_t)t * 64 + lane) * 8 + 2 * j + 1] = (_Float16)s;
+    if (x == 0) {
+        const int g = lane >> 4;
+        sincospi(-2.0 * (double)((y * t) & (16 * TC - 1)) / (double)(16 * TC), &s, &c);
+        T1f[((size_t)t * 4 + g) * 8 + 2 * j] = (_Float16)c;
+        T1f[((size_t)t * 4 + g) * 8 + 2 * j + 1] = (_Float16)s;
+        T1i[((size_t)t * 4 + g) * 8 + 2 * j] = (_Float16)c;
+        T1i[((size_t)t * 4 + g) * 8 + 2 * j + 1] = (_Float16)(-s);
+    }
+}
+
+hipError_t coop_fill_tables(const void** tab_out, hipStream_t st)
+{
+    unsigned char* p = nullptr;
+    hipError_t e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(g_coop_tab));
+    if (e != hipSuccess) return e;
+    for (int LG = 13; LG <= 15; ++LG)
+        hipLaunchKernelGGL(fill_coop_tab_kernel, dim3((1 << LG) / 256), dim3(256), 0, st, p, LG);
+    *tab_out = p;
+    return hipGetLastError();
+}
+
+namespace {
+
+using namespace mu;
+
+// fp16 complex times fp16 complex, packed (v_pk_mul_f16 + v_pk_fma_f16)
+__device__ __forceinline__ uint32_t cmul_h2(uint32_t yu, h2 w)
+{
+    union { uint32_t u; h2 h; } a, r;
+    a.u = yu;
+    const h2 yx = {a.h[0], a.h[0]}, yy = {a.h[1], a.h[1]};
+    const h2 ws = {-w[1], w[0]};
+    r.h = __builtin_elementwise_fma(yy, ws, yx * w);
+    return r.u;
+}
+
+template <int LG>
+struct Consts {
+    Mats F16, I16, FL, IL;
+    h2 t2f[4], t2i[4];
+};
+
+template <int LG>
+__device__ __forceinline__ void make_consts(Consts<LG>& K, const float2* __restrict__ tw, int lane)
+{
+    using C = CC<LG>;
+    K.F16 = plain_mats(4, false, tw, lane);
+    K.I16 = plain_mats(4, true, tw, lane);
+    K.FL = plain_mats(C::te, false, tw, lane);
+    K.IL = plain_mats(C::te, true, tw, lane);
+    const int x = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        // forward: lane k_c = x, row (e, d_e) = 4g+j ; inverse: lane (e, d_e) = x, row k_c = 4g+j
+        const int de_f = (4 * g + j) & (C::TE - 1), de_i = x & (C::TE - 1);
+        const float2 wf = tw_full(tw, (uint32_t)((x * de_f) & (C::TC - 1)) << (TW_LOG2 - C::cb));
+        const float2 wi = tw_full(tw, (uint32_t)(((4 * g + j) * de_i) & (C::TC - 1)) << (TW_LOG2 - C::cb));
+        K.t2f[j] = h2{(_Float16)wf.x, (_Float16)wf.y};
+        K.t2i[j] = h2{(_Float16)wi.x, (_Float16)(-wi.y)};
+    }
+}
+
+// ---- phase 1 for the 8 tiles t0..t0+7 of one wave ------------------------------------
+// REAL: rows a, b of I/O elements (zero above N = L/2).  CPLX: chunk of L fp16 complex values.
+template <int LG, class IO, bool CPLX>
+__device__ __forceinline__ void phase1(const typename IO::T* ra, const typename IO::T* rb, bool has_b,
+                                       const __half2* chunk, uint32_t* xb, const uint4* gtab, const uint4* t1f,
+                                       const Consts<LG>& K, int t0, int lane)
+{
+    using C = CC<LG>;
+    const int c = lane & 15, g = lane >> 4;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    uint32_t w[4][8];       // CPLX: [j][tile] complex words; REAL: [j][0..3] row a pairs, [j][4..7] row b pairs
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
+        if (CPLX) {
+            load_words<4>(chunk + n0, &w[j][0]);
+            load_words<4>(chunk + n0 + 4, &w[j][4]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[j][i] = 0u;
+            if (g < 2) {
+                load_words<4>(ra + n0, &w[j][0]);
+                if (has_b) load_words<4>(rb + n0, &w[j][4]);
+                if (IsBf<IO>::v) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) w[j][i] = bf2_to_h2(w[j][i]);
+                }
+            }
+        }
+    }
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+#pragma unroll
+    for (int tb = 0; tb < 8; tb += 2) {
+        H8U tw0[2], tw1[2];
+        f4 yr[2], yi[2], zr[2], zi[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int t = t0 + tb + k;
+            tw0[k].u = gtab[C::T0F + t * 64 + lane];
+            tw1[k].u = t1f[t * 4 + g];
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int tt = tb + k;
+            H8U x;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (CPLX) x.w[j] = w[j][tt];
+                else x.w[j] = (tt & 1) ? __builtin_amdgcn_perm(w[j][4 + (tt >> 1)], w[j][tt >> 1], 0x07060302u)
+                                       : __builtin_amdgcn_perm(w[j][4 + (tt >> 1)], w[j][tt >> 1], 0x05040100u);
+            }
+            yr[k] = MFMA(x.v, K.F16.re, zero);
+            yi[k] = MFMA(x.v, K.F16.im, zero);
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            H8U u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][j], yi[k][j], tw0[k].c[j]);
+            zr[k] = MFMA(K.F16.re, u.v, zero);
+            zi[k] = MFMA(K.F16.im, u.v, zero);
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            uint4 o;
+            o.x = cmul_pack(zr[k][0], zi[k][0], tw1[k].c[0]);
+            o.y = cmul_pack(zr[k][1], zi[k][1], tw1[k].c[1]);
+            o.z = cmul_pack(zr[k][2], zi[k][2], tw1[k].c[2]);
+            o.w = cmul_pack(zr[k][3], zi[k][3], tw1[k].c[3]);
+            *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
+        }
+    }
+}
+
+// word address of (tile t2, reg 0) for this lane in phase 2; reg j adds j*TE*4 words
+template <int LG>
+__device__ __forceinline__ int phase2_base(int t2, int lane)
+{
+    using C = CC<LG>;
+    const int x = lane & 15, g = lane >> 4;
+    const int de = x & (C::TE - 1), e = x >> C::te;
+    const int ka = t2 >> C::te, kb = ((t2 & (C::TE - 1)) << (4 - C::te)) | e;
+    const int t = (4 * g) * C::TE + de;
+    return (ka * C::PITCH + (kb >> 2) * C::TC + t) * 4 + (kb & 3);
+}
+
+// forward half of phase 2 on one tile: LDS -> [A: F16 over d_c] * w_TC -> [B: F_TE over d_e]
+template <int LG>
+__device__ __forceinline__ void phase2_fwd(const uint32_t* xb, int base, const Consts<LG>& K, f4& zr, f4& zi)
+{
+    using C = CC<LG>;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    H8U x;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) x.w[j] = xb[base + j * C::TE * 4];
+    const f4 yr = MFMA(x.v, K.F16.re, zero), yi = MFMA(x.v, K.F16.im, zero);
+    H8U u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[j], yi[j], K.t2f[j]);
+    zr = MFMA(K.FL.re, u.v, zero);
+    zi = MFMA(K.FL.im, u.v, zero);
+}
+
+// inverse half of phase 2 on one tile: (already multiplied) spectrum values m -> LDS
+template <int LG>
+__device__ __forceinline__ void phase2_inv(uint32_t* xb, int base, const Consts<LG>& K, const H8U& m)
+{
+    using C = CC<LG>;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    const f4 yr = MFMA(m.v, K.IL.re, zero), yi = MFMA(m.v, K.IL.im, zero);
+    H8U u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[j], yi[j], K.t2i[j]);
+    const f4 vr = MFMA(K.I16.re, u.v, zero), vi = MFMA(K.I16.im, u.v, zero);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) xb[base + j * C::TE * 4] = pack_h2(vr[j], vi[j]);
+}
+
+// phase 3 on two tiles t, t+1: returns real parts r[k] and imaginary parts s[k] of the time samples
+template <int LG>
+__device__ __forceinline__ void phase3_two(const uint32_t* xb, const uint4* gtab, const uint4* t1i,
+                                           const Consts<LG>& K, int t, int lane, f4 (&r)[2], f4 (&s)[2])
+{
+    using C = CC<LG>;
+    const int c = lane & 15, g = lane >> 4;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+    H8U tw0[2], tw1[2], x[2];
+    f4 yr[2], yi[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        tw0[k].u = gtab[C::T0I + (t + k) * 64 + lane];
+        tw1[k].u = t1i[(t + k) * 4 + g];
+        x[k].u = *reinterpret_cast<const uint4*>(&xb[w1 + 4 * (t + k)]);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[k].w[j] = cmul_h2(x[k].w[j], tw1[k].c[j]);
+        yr[k] = MFMA(x[k].v, K.I16.re, zero);
+        yi[k] = MFMA(x[k].v, K.I16.im, zero);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        H8U u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][j], yi[k][j], tw0[k].c[j]);
+        r[k] = MFMA(K.I16.re, u.v, zero);
+        s[k] = MFMA(K.I16.im, u.v, zero);
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// Fused convolution.  grid = (pair slots, H, R); a workgroup loops over the pairs p = blockIdx.x,
+// blockIdx.x + gridDim.x, ... of head h (chunk k1 of each in the multi-pass split).
+// -------------------------------------------------------------------------------------
+template <int LG, class IO, bool CPLX>
+__global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
+                 typename IO::T* __restrict__ out, __half2* __restrict__ ws, int conj, int64_t B, int64_t H,
+                 int64_t N, int npairs, int log2R, const float2* __restrict__ tw,
+                 const unsigned char* __restrict__ ctab)
+{
+    using C = CC<LG>;
+    using T = typename IO::T;
+    extern __shared__ uint4 lds4[];
+    uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
+    uint4* t1f = lds4 + C::XWORDS / 4;
+    uint4* t1i = t1f + C::TC * 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int h = blockIdx.y, k1 = blockIdx.z;
+    const int64_t Ltot = (int64_t)C::L << log2R;
+    const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
+    for (int i = tid; i < C::TC * 8; i += C::NW * 64) t1f[i] = gtab[C::T1F + i];
+    Consts<LG> K;
+    make_consts<LG>(K, tw, lane);
+    const float csign = conj ? -1.f : 1.f;
+    const float4* ks = reinterpret_cast<const float4*>(kspec + (size_t)h * Ltot + (size_t)k1 * C::L);
+    __syncthreads();
+
+    for (int p = blockIdx.x; p < npairs; p += gridDim.x) {
+        // table and spectrum loads stay inside the loop (hoisting them costs more registers than a wave has)
+        asm volatile("" : "+s"(gtab), "+s"(ks));
+        const bool has_b = (2 * p + 1) < B;
+        const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
+        __half2* chunk = ws + ((size_t)h * npairs + p) * Ltot + (size_t)k1 * C::L;
+
+#pragma unroll
+        for (int gi = 0; gi < C::NG; ++gi) {
+            phase1<LG, IO, CPLX>(in + oa, in + ob, has_b, chunk, xb, gtab, t1f, K, (gi * C::NW + wave) * 8, lane);
+            __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds register pressure
+        }
+        __syncthreads();
+
+        // ---- phase 2: two tiles in flight
+#pragma unroll
+        for (int gi = 0; gi < C::NG; ++gi)
+#pragma unroll
+        for (int tb = 0; tb < 8; tb += 2) {
+            const int t0 = (gi * C::NW + wave) * 8;
+            int base[2];
+            f4 zr[2], zi[2];
+            float4 k01[2], k23[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int t2 = t0 + tb + k;
+                base[k] = phase2_base<LG>(t2, lane);
+                k01[k] = ks[(t2 * 64 + lane) * 2];
+                k23[k] = ks[(t2 * 64 + lane) * 2 + 1];
+            }
+#pragma unroll
+            for (int k = 0; k < 2; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const float2 kk[4] = {make_float2(k01[k].x, k01[k].y * csign), make_float2(k01[k].z, k01[k].w * csign),
+                                      make_float2(k23[k].x, k23[k].y * csign), make_float2(k23[k].z, k23[k].w * csign)};
+                H8U m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float2 v = cmul(make_float2(zr[k][j], zi[k][j]), kk[j]);
+                    m.w[j] = pack_h2(v.x, v.y);
+                }
+                phase2_inv<LG>(xb, base[k], K, m);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+
+        // ---- phase 3
+#pragma unroll
+        for (int gi = 0; gi < C::NG; ++gi) {
+        const int t0 = (gi * C::NW + wave) * 8;
+        uint32_t ow[4][8];     // REAL: [j][0..3] row a, [4..7] row b; CPLX: [j][tile]
+#pragma unroll
+        for (int tb = 0; tb < 8; tb += 2) {
+            f4 r[2], s[2];
+            phase3_two<LG>(xb, gtab, t1i, K, t0 + tb, lane, r, s);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (CPLX) {
+                    ow[j][tb] = pack_h2(r[0][j], s[0][j]);
+                    ow[j][tb + 1] = pack_h2(r[1][j], s[1][j]);
+                } else if (IsBf<IO>::v) {
+                    ow[j][tb >> 1] = pack_bf2(r[0][j], r[1][j]);
+                    ow[j][4 + (tb >> 1)] = pack_bf2(s[0][j], s[1][j]);
+                } else {
+                    ow[j][tb >> 1] = pack_h2(r[0][j], r[1][j]);
+                    ow[j][4 + (tb >> 1)] = pack_h2(s[0][j], s[1][j]);
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
+            if (CPLX) {
+                store_words<4>(chunk + n0, &ow[j][0]);
+                store_words<4>(chunk + n0 + 4, &ow[j][4]);
+            } else if (g < 2) {
+                store_words<4>(out + oa + n0, &ow[j][0]);
+                if (has_b) store_words<4>(out + ob + n0, &ow[j][4]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// dk and dD: one workgroup per (head, chunk) loops over all row pairs of the head in order.
+// Z (u pair) is kept as fp16, A += conj(Z) W accumulates in fp32 registers in the lane order
+// of phase 2; then the inverse half of phase 2 and phase 3 give dk (real part).
+// -------------------------------------------------------------------------------------
+template <int LG, class IO, bool CPLX>
+__global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u, float* __restrict__ dk,
+               float* __restrict__ dD, const __half2* __restrict__ ws_u, const __half2* __restrict__ ws_dy,
+               __half2* __restrict__ ws_A, float* __restrict__ dD_part, uint4* __restrict__ zbuf, int64_t B,
+               int64_t H, int64_t N,
+               int npairs, int log2R, float dkscale, float dDscale, const float2* __restrict__ tw,
+               const unsigned char* __restrict__ ctab)
+{
+    using C = CC<LG>;
+    using T = typename IO::T;
+    extern __shared__ uint4 lds4[];
+    __shared__ float red[C::NW];
+    uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
+    uint4* t1f = lds4 + C::XWORDS / 4;
+    uint4* t1i = t1f + C::TC * 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int h = blockIdx.x, k1 = blockIdx.y;
+    const int64_t Ltot = (int64_t)C::L << log2R;
+    const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
+    for (int i = tid; i < C::TC * 8; i += C::NW * 64) t1f[i] = gtab[C::T1F + i];
+    Consts<LG> K;
+    make_consts<LG>(K, tw, lane);
+    __syncthreads();
+    // Z of the current pair is parked in global scratch (lane order, 16 bytes per lane and tile)
+    uint4* zb = zbuf + ((size_t)h * gridDim.y + k1) * (C::TC * 64) + lane;
+
+    float2 acc[C::NG * 8][4];
+#pragma unroll
+    for (int i = 0; i < C::NG * 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = make_float2(0.f, 0.f);
+
+    for (int p = 0; p < npairs; ++p) {
+        asm volatile("" : "+s"(gtab));
+        const bool has_b = (2 * p + 1) < B;
+        const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
+        const size_t coff = ((size_t)h * npairs + p) * Ltot + (size_t)k1 * C::L;
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            asm volatile("" : "+s"(gtab));
+            const T* src = pass == 0 ? u : dy;
+            const __half2* csrc = pass == 0 ? ws_u : ws_dy;
+#pragma unroll
+            for (int gi = 0; gi < C::NG; ++gi) {
+                phase1<LG, IO, CPLX>(src + oa, src + ob, has_b, csrc + coff, xb, gtab, t1f, K,
+                                     (gi * C::NW + wave) * 8, lane);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int gi = 0; gi < C::NG; ++gi)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int t2 = (gi * C::NW + wave) * 8 + i;
+                    f4 zr, zi;
+                    phase2_fwd<LG>(xb, phase2_base<LG>(t2, lane), K, zr, zi);
+                    if (pass == 0) {
+                        zb[(size_t)t2 * 64] = make_uint4(pack_h2(zr[0], zi[0]), pack_h2(zr[1], zi[1]),
+                                                         pack_h2(zr[2], zi[2]), pack_h2(zr[3], zi[3]));
+                    } else {
+                        H8U z;
+                        z.u = zb[(size_t)t2 * 64];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float a = (float)z.c[j][0], b = (float)z.c[j][1];
+                            acc[gi * 8 + i][j].x += a * zr[j] + b * zi[j];
+                            acc[gi * 8 + i][j].y += a * zi[j] - b * zr[j];
+                        }
+                    }
+                    if (i & 1) __builtin_amdgcn_sched_barrier(0);
+                }
+            __syncthreads();
+        }
+    }
+
+    if (dD || dD_part) {
+        float dsum = 0.f;
+#pragma unroll
+        for (int i = 0; i < C::NG * 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dsum += acc[i][j].x;
+        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+        if (lane == 0) red[wave] = dsum;
+        __syncthreads();
+        if (tid == 0) {
+            float t = 0.f;
+            for (int w = 0; w < C::NW; ++w) t += red[w];
+            if (log2R == 0) { if (dD) dD[h] = t * dDscale; }
+            else dD_part[(size_t)h * gridDim.y + k1] = t * dDscale;
+        }
+    }
+    if (!dk) return;
+
+#pragma unroll
+    for (int gi = 0; gi < C::NG; ++gi)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        H8U m;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(acc[gi * 8 + i][j].x, acc[gi * 8 + i][j].y);
+        phase2_inv<LG>(xb, phase2_base<LG>((gi * C::NW + wave) * 8 + i, lane), K, m);
+    }
+    __syncthreads();
+    __half2* achunk = ws_A + (size_t)h * Ltot + (size_t)k1 * C::L;
+#pragma unroll
+    for (int gi = 0; gi < C::NG; ++gi)
+#pragma unroll
+    for (int tb = 0; tb < 8; tb += 2) {
+        const int t0 = (gi * C::NW + wave) * 8;
+        f4 r[2], s[2];
+        phase3_two<LG>(xb, gtab, t1i, K, t0 + tb, lane, r, s);
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int n = (4 * g + j) * 16 * C::TC + c * C::TC + t0 + tb + k;
+                if (CPLX) {
+                    union { uint32_t u; __half2 hh; } cv;
+                    cv.u = pack_h2(r[k][j], s[k][j]);
+                    achunk[n] = cv.hh;
+                } else if (g < 2) {
+                    dk[(size_t)h * N + n] = r[k][j] * dkscale;
+                }
+            }
+    }
+}
+
+template <int LG>
+size_t coop_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16; }
+
+template <int LG, class IO>
+hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
+                        const Plan& pl, const Tables& tb, hipStream_t st)
+{
+    using T = typename IO::T;
+    const size_t lds = coop_lds_bytes<LG>();
+    const int R = 1 << pl.log2R;
+    long gx = (512 + pr.H * R - 1) / (pr.H * R);
+    if (gx < 1) gx = 1;
+    if (gx > pr.npairs) gx = pr.npairs;
+    dim3 grid((unsigned)gx, (unsigned)pr.H, (unsigned)R);
+    hipError_t e;
+    if (pl.log2R == 0) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, IO, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((coop_conv_kernel<LG, IO, false>), grid, dim3(CC<LG>::NW * 64), lds, st, (const T*)in,
+                           kspec, (T*)out, ws, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, tb.tw,
+                           (const unsigned char*)tb.ctab);
+    } else {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, IO, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((coop_conv_kernel<LG, IO, true>), grid, dim3(CC<LG>::NW * 64), lds, st, (const T*)in,
+                           kspec, (T*)out, ws, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, tb.tw,
+                           (const unsigned char*)tb.ctab);
+    }
+    return hipGetLastError();
+}
+
+template <int LG, class IO>
+hipError_t coop_dk_go(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
+                      __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl,
+                      const Tables& tb, hipStream_t st)
+{
+    using T = typename IO::T;
+    using C = CC<LG>;
+    const size_t lds = coop_lds_bytes<LG>();
+    dim3 grid((unsigned)pr.H, 1u << pl.log2R);
+    const int shift = 6 + (C::te >= 2 ? 1 : 0);      // three radix-16 stages (1/4 each) and F_TE
+    const float dDscale = pl.dkscale / (float)(1 << shift);
+    hipError_t e;
+    if (pl.log2R == 0) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_dk_kernel<LG, IO, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((coop_dk_kernel<LG, IO, false>), grid, dim3(C::NW * 64), lds, st, (const T*)dy, (const T*)u,
+                           dk, dD, ws_u, ws_dy, ws_A, dD_part, (uint4*)zbuf, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, pl.dkscale,
+                           dDscale, tb.tw, (const unsigned char*)tb.ctab);
+    } else {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_dk_kernel<LG, IO, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((coop_dk_kernel<LG, IO, true>), grid, dim3(C::NW * 64), lds, st, (const T*)dy, (const T*)u,
+                           dk, dD, ws_u, ws_dy, ws_A, dD_part, (uint4*)zbuf, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, pl.dkscale,
+                           dDscale, tb.tw, (const unsigned char*)tb.ctab);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
+                     const Plan& pl, const Tables& tb, hipStream_t st)
+{
+#define GO(LG, IO) return coop_conv_go<LG, IO>(in, kspec, out, ws, conj, pr, pl, tb, st)
+    if (pr.io == LONGCONV_F16) {
+        if (pl.log2L2 == 13) GO(13, IoF16);
+        if (pl.log2L2 == 14) GO(14, IoF16);
+        if (pl.log2L2 == 15) GO(15, IoF16);
+    } else if (pr.io == LONGCONV_BF16) {
+        if (pl.log2L2 == 13) GO(13, IoBF16);
+        if (pl.log2L2 == 14) GO(14, IoBF16);
+        if (pl.log2L2 == 15) GO(15, IoBF16);
+    }
+#undef GO
+    return hipErrorInvalidValue;
+}
+
+hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
+                   __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl, const Tables& tb,
+                   hipStream_t st)
+{
+#define GO(LG, IO) return coop_dk_go<LG, IO>(dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, zbuf, pr, pl, tb, st)
+    if (pr.io == LONGCONV_F16) {
+        if (pl.log2L2 == 13) GO(13, IoF16);
+        if (pl.log2L2 == 14) GO(14, IoF16);
+        if (pl.log2L2 == 15) GO(15, IoF16);
+    } else if (pr.io == LONGCONV_BF16) {
+        if (pl.log2L2 == 13) GO(13, IoBF16);
+        if (pl.log2L2 == 14) GO(14, IoBF16);
+        if (pl.log2L2 == 15) GO(15, IoBF16);
+    }
+#undef GO
+    return hipErrorInvalidValue;
+}
+
+}  // namespace lc

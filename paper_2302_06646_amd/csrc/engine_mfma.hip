@@ -524,9 +524,13 @@ void mfma_fill_plan(Plan& pl)
 {
     pl.order.ndig = 0;
     pl.order.wave_lg = 0;
-    const char* kv = getenv("LONGCONV_MFMA_KERNEL");   // "coop" forces the workgroup-cooperative kernel
-    if (pl.log2R == 0 && pl.log2L2 >= WAVE_MIN_LOG2 && pl.log2L2 <= WAVE_MAX_LOG2 && !(kv && !strcmp(kv, "coop")))
+    pl.order.coop_lg = 0;
+    pl.order.outer_bits = pl.log2R;
+    const char* kv = getenv("LONGCONV_MFMA_KERNEL");   // "staged" forces the in-place staged kernel everywhere
+    const bool staged = kv && !strcmp(kv, "staged");
+    if (!staged && pl.log2R == 0 && pl.log2L2 >= WAVE_MIN_LOG2 && pl.log2L2 <= WAVE_MAX_LOG2)
         pl.order.wave_lg = pl.log2L2;
+    if (!staged && pl.log2L2 >= COOP_MIN_LOG2 && pl.log2L2 <= COOP_MAX_LOG2) pl.order.coop_lg = pl.log2L2;
     if (pl.log2R) pl.order.bits[pl.order.ndig++] = (unsigned char)pl.log2R;
     const int S = n_stages(pl.log2L2);
     for (int i = 0; i < S - 1; ++i) pl.order.bits[pl.order.ndig++] = 4;
@@ -542,17 +546,19 @@ hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws
                      const Plan& pl, const Tables& tb, hipStream_t st)
 {
     if (pl.order.wave_lg) return wave_conv(in, kspec, out, conj, pr, pl, tb, st);
+    if (pl.order.coop_lg) return coop_conv(in, kspec, out, ws, conj, pr, pl, tb, st);
     if (pr.io == LONGCONV_F16) { LC_LG_SWITCH(conv_go, IoF16, in, kspec, out, ws, conj, pr, pl, tb, st) }
     if (pr.io == LONGCONV_BF16) { LC_LG_SWITCH(conv_go, IoBF16, in, kspec, out, ws, conj, pr, pl, tb, st) }
     return hipErrorInvalidValue;
 }
 
 hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
-                   __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl, const Tables& tb,
+                   __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl, const Tables& tb,
                    hipStream_t st)
 {
     // L = 4096 keeps the cooperative kernel: its accumulators do not fit one wave's registers
     if (pl.order.wave_lg && pl.log2L2 <= 11) return wave_dk(dy, u, dk, dD, pr, pl, tb, st);
+    if (pl.order.coop_lg) return coop_dk(dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, zbuf, pr, pl, tb, st);
     if (pr.io == LONGCONV_F16) {
         LC_LG_SWITCH(dk_go, IoF16, dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, pr, pl, tb, st)
     }

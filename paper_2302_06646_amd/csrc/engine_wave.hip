@@ -22,6 +22,7 @@
 // table into LDS; workgroups are persistent (each wave loops over several groups of PB row
 // pairs) so that the copy is amortised.
 #include "engines.hpp"
+#include "mfma_util.hpp"
 
 namespace lc {
 
@@ -127,80 +128,7 @@ hipError_t wave_fill_tables(const void** tab_out, hipStream_t st)
 
 namespace {
 
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef float f2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
-
-union H8U {
-    h8 v;
-    h2 c[4];
-    uint32_t w[4];
-    uint4 u;
-};
-struct Mats {
-    h8 re, im;
-};
-
-__device__ __forceinline__ uint32_t pack_h2(float a, float b)
-{
-    const f2 v = {a, b};
-    union { h2 h; uint32_t u; } cv;
-    cv.h = __builtin_convertvector(v, h2);
-    return cv.u;
-}
-__device__ __forceinline__ uint32_t pack_bf2(float a, float b)
-{
-    const f2 v = {a, b};
-    union { bf2 h; uint32_t u; } cv;
-    cv.h = __builtin_convertvector(v, bf2);
-    return cv.u;
-}
-__device__ __forceinline__ uint32_t bf2_to_h2(uint32_t w)
-{
-    return pack_h2(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
-}
-// (yr + i yi) * w in packed fp16 (one convert, v_pk_mul_f16, v_pk_fma_f16); result as fp16 complex
-__device__ __forceinline__ uint32_t cmul_pack(float yr, float yi, h2 w)
-{
-    const f2 v = {yr, yi};
-    const h2 y = __builtin_convertvector(v, h2);
-    const h2 yx = {y[0], y[0]}, yy = {y[1], y[1]};
-    const h2 ws = {-w[1], w[0]};
-    union { h2 h; uint32_t u; } cv;
-    cv.h = __builtin_elementwise_fma(yy, ws, yx * w);
-    return cv.u;
-}
-
-#define MFMA(a, b, acc) __builtin_amdgcn_mfma_f32_16x16x32_f16((a), (b), (acc), 0, 0, 0)
-
-// LDS traffic between the lanes of one wave: hardware keeps a wave's LDS operations in order,
-// the fence only stops the compiler from moving accesses across the phase boundary.
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-template <class IO> struct IsBf { static constexpr bool v = false; };
-template <> struct IsBf<IoBF16> { static constexpr bool v = true; };
-
-template <int NW_>
-__device__ __forceinline__ void load_words(const void* p, uint32_t* w)
-{
-    if constexpr (NW_ == 1) { w[0] = *reinterpret_cast<const uint32_t*>(p); }
-    else if constexpr (NW_ == 2) { const uint2 v = *reinterpret_cast<const uint2*>(p); w[0] = v.x; w[1] = v.y; }
-    else { const uint4 v = *reinterpret_cast<const uint4*>(p); w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w; }
-}
-template <int NW_>
-__device__ __forceinline__ void store_words(void* p, const uint32_t* w)
-{
-    if constexpr (NW_ == 1) { *reinterpret_cast<uint32_t*>(p) = w[0]; }
-    else if constexpr (NW_ == 2) { *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]); }
-    else { *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]); }
-}
+using namespace mu;
 
 // Raw input words of one tile group (TG tiles) for PB row pairs: per (pair, reg j) the TG
 // consecutive samples n0 .. n0+TG-1 of row a and of row b (I/O dtype, two per word).

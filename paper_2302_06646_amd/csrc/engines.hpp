@@ -48,8 +48,8 @@ hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws
                      const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st);
 // Multi-pass: dD_part[h*R + k1] receives chunk k1's share of dD[h] (sum them with reduce_dD).
 hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u,
-                   const __half2* ws_dy, __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl,
-                   const Tables& tb, hipStream_t st);
+                   const __half2* ws_dy, __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr,
+                   const Plan& pl, const Tables& tb, hipStream_t st);
 
 // ---- wave-autonomous matrix-core kernels for 512 <= L <= 4096 (engine_wave.hip) ----------
 constexpr int WAVE_MIN_LOG2 = 9, WAVE_MAX_LOG2 = 12;
@@ -58,5 +58,15 @@ hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, 
                      const Plan& pl, const Tables& tb, hipStream_t st);
 hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
                    const Tables& tb, hipStream_t st);
+
+// ---- cooperative chained matrix-core kernels for 2^13 <= L2 <= 2^15 (engine_coop.hip) --------
+constexpr int COOP_MIN_LOG2 = 13, COOP_MAX_LOG2 = 15;
+hipError_t coop_fill_tables(const void** tab_out, hipStream_t st);
+hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
+                     const Plan& pl, const Tables& tb, hipStream_t st);
+// zbuf: H * 2N * 4 bytes of scratch (transform of the current u pair, parked between the two transforms)
+hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
+                   __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl, const Tables& tb,
+                   hipStream_t st);
 
 }  // namespace lc
