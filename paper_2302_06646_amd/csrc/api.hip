@@ -132,7 +132,7 @@ static size_t cw_bytes(const Plan& pl) { return pl.engine == ENGINE_VALU ? sizeo
 static size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 
 struct WsLayout {
-    size_t kspec, kscratch, ws1, ws2, wsA, dpart, zbuf, total;
+    size_t kspec, kscratch, hscale, ws1, ws2, wsA, dpart, zbuf, total;
     int nblk;
 };
 
@@ -144,6 +144,7 @@ static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool back
     size_t off = 0;
     w.kspec = off; off += up256((size_t)H * L * sizeof(float2));
     w.kscratch = off; if (pl.log2L > VALU_KSPEC_MAX_LOG2) off += up256((size_t)H * L * sizeof(float2));
+    w.hscale = off; off += up256((size_t)H * sizeof(float));
     w.ws1 = off; if (pl.log2R) off += up256((size_t)H * npairs * L * cw_bytes(pl));
     w.ws2 = off; if (pl.log2R && backward) off += up256((size_t)H * npairs * L * cw_bytes(pl));
     w.wsA = off; if (pl.log2R && backward) off += up256((size_t)H * L * cw_bytes(pl));
@@ -166,9 +167,22 @@ static int check_shape(int64_t B, int64_t H, int64_t N, int io)
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // Spectrum of all heads into `kspec` (storage order and scale of plan `pl`).
-static hipError_t run_kspec(const float* k, const float* D, float2* kspec, float2* kscratch, int64_t H,
-                            int64_t N, const Plan& pl, const float2* tw, hipStream_t st)
+static hipError_t run_kspec(const float* k, const float* D, float2* kspec, float2* kscratch, float* hscale,
+                            int64_t H, int64_t N, const Plan& pl, const Tables& tb, hipStream_t st)
 {
+    const float2* tw = tb.tw;
+    if (pl.engine == ENGINE_MFMA && (pl.order.wave_lg || pl.order.coop_lg)) {
+        // matrix-core route: per-head power-of-two pre-scale, (pass A,) forward half of the fused kernel
+        hipError_t e = head_max(k, hscale, H, N, st);
+        if (e != hipSuccess) return e;
+        if (pl.order.wave_lg) return wave_kspec(k, D, hscale, kspec, H, N, pl, tb, st);
+        if (pl.log2R) {
+            Problem pk{1, H, N, LONGCONV_F32, 1};
+            e = outer_fwd(k, nullptr, kscratch, nullptr, nullptr, pk, pl.log2R, pl.log2L2, 1.0f, true, tw, st, hscale);
+            if (e != hipSuccess) return e;
+        }
+        return coop_kspec(k, (const __half2*)kscratch, D, hscale, kspec, H, N, pl, tb, st);
+    }
     const int lg2 = pl.log2L < VALU_KSPEC_MAX_LOG2 ? pl.log2L : VALU_KSPEC_MAX_LOG2;
     const int lgR = pl.log2L - lg2;
     if (lgR == 0) return valu_kspec(k, nullptr, D, kspec, H, N, 0, lg2, pl.order, pl.kscale, tw, st);
@@ -233,14 +247,14 @@ int longconv_kspec_compute(const float* k, const float* D, void* kspec, int64_t 
     if (misaligned(k) || misaligned(kspec) || misaligned(workspace)) return LONGCONV_ERR_ALIGN;
     const Plan pl = make_plan(N, io);
     const WsLayout w = carve(1, H, N, pl, false);
-    const size_t need = w.ws1 - w.kscratch;   // only the producer scratch is used here
+    const size_t need = w.ws1 - w.kscratch;   // producer scratch and per-head scales
     if (need && (!workspace || workspace_bytes < w.kscratch + need)) return LONGCONV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     Tables tb;
     if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
-    const float2* tw = tb.tw;
-    float2* scratch = need ? (float2*)((char*)workspace + w.kscratch) : nullptr;
-    if (note(run_kspec(k, D, (float2*)kspec, scratch, H, N, pl, tw, st), "kspec") != hipSuccess)
+    float2* scratch = (float2*)((char*)workspace + w.kscratch);
+    if (note(run_kspec(k, D, (float2*)kspec, scratch, (float*)((char*)workspace + w.hscale), H, N, pl, tb, st),
+             "kspec") != hipSuccess)
         return LONGCONV_ERR_HIP;
     return LONGCONV_OK;
 }
@@ -259,12 +273,11 @@ int longconv_fwd(const void* u, const float* k, const float* D, const void* kspe
     hipStream_t st = (hipStream_t)stream;
     Tables tb;
     if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
-    const float2* tw = tb.tw;
     char* base = (char*)workspace;
     const float2* ks = (const float2*)kspec;
     if (!ks) {
-        if (note(run_kspec(k, D, (float2*)(base + w.kspec), (float2*)(base + w.kscratch), H, N, pl, tw, st),
-                 "kspec") != hipSuccess)
+        if (note(run_kspec(k, D, (float2*)(base + w.kspec), (float2*)(base + w.kscratch), (float*)(base + w.hscale),
+                           H, N, pl, tb, st), "kspec") != hipSuccess)
             return LONGCONV_ERR_HIP;
         ks = (const float2*)(base + w.kspec);
     }
@@ -331,8 +344,8 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
     if (du) {
         const float2* ks = (const float2*)kspec;
         if (!ks) {
-            if (note(run_kspec(k, D, (float2*)(base + w.kspec), (float2*)(base + w.kscratch), H, N, pl, tw, st),
-                     "kspec") != hipSuccess)
+            if (note(run_kspec(k, D, (float2*)(base + w.kspec), (float2*)(base + w.kscratch),
+                               (float*)(base + w.hscale), H, N, pl, tb, st), "kspec") != hipSuccess)
                 return LONGCONV_ERR_HIP;
             ks = (const float2*)(base + w.kspec);
         }

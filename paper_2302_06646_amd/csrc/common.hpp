@@ -146,6 +146,14 @@ __host__ __device__ inline uint32_t spec_pos(uint32_t f, const SpecOrder& o)
     return pos;
 }
 
+// Power-of-two pre-scale of a head whose largest |k| is m: brings the kernel to magnitude <= 1 before
+// it becomes fp16 matrix-core operands (zero, inf and nan heads are left unscaled).
+__device__ __forceinline__ float head_scale_of(float m)
+{
+    const bool ok = m > 0.f && m < 3.0e38f;
+    return ok ? exp2f(-ceilf(log2f(m))) : 1.f;
+}
+
 enum Engine { ENGINE_VALU = 0, ENGINE_MFMA = 1 };
 
 // Host-side plan: how 2N is factored and which kernels run.

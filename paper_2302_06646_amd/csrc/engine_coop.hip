@@ -130,36 +130,15 @@ __device__ __forceinline__ void make_consts(Consts<LG>& K, const float2* __restr
     }
 }
 
-// ---- phase 1 for the 8 tiles t0..t0+7 of one wave ------------------------------------
-// REAL: rows a, b of I/O elements (zero above N = L/2).  CPLX: chunk of L fp16 complex values.
-template <int LG, class IO, bool CPLX>
-__device__ __forceinline__ void phase1(const typename IO::T* ra, const typename IO::T* rb, bool has_b,
-                                       const __half2* chunk, uint32_t* xb, const uint4* gtab, const uint4* t1f,
-                                       const Consts<LG>& K, int t0, int lane)
+// phase 1 arithmetic on staged operand words of 8 tiles.  CPLX: w[j][tile] fp16 complex;
+// otherwise w[j][0..3] = row a sample pairs, w[j][4..7] = row b sample pairs (fp16).
+template <int LG, bool CPLX>
+__device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t* xb, const uint4* gtab,
+                                            const uint4* t1f, const Consts<LG>& K, int t0, int lane)
 {
     using C = CC<LG>;
     const int c = lane & 15, g = lane >> 4;
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
-    uint32_t w[4][8];       // CPLX: [j][tile] complex words; REAL: [j][0..3] row a pairs, [j][4..7] row b pairs
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
-        if (CPLX) {
-            load_words<4>(chunk + n0, &w[j][0]);
-            load_words<4>(chunk + n0 + 4, &w[j][4]);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) w[j][i] = 0u;
-            if (g < 2) {
-                load_words<4>(ra + n0, &w[j][0]);
-                if (has_b) load_words<4>(rb + n0, &w[j][4]);
-                if (IsBf<IO>::v) {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) w[j][i] = bf2_to_h2(w[j][i]);
-                }
-            }
-        }
-    }
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
 #pragma unroll
     for (int tb = 0; tb < 8; tb += 2) {
@@ -202,6 +181,45 @@ __device__ __forceinline__ void phase1(const typename IO::T* ra, const typename 
             *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
         }
     }
+}
+
+template <int LG>
+__device__ __forceinline__ void phase1_regs(const uint32_t (&w)[4][8], uint32_t* xb, const uint4* gtab,
+                                            const uint4* t1f, const Consts<LG>& K, int t0, int lane)
+{
+    phase1_core<LG, false>(w, xb, gtab, t1f, K, t0, lane);
+}
+
+// ---- phase 1 for the 8 tiles t0..t0+7 of one wave ------------------------------------
+// REAL: rows a, b of I/O elements (zero above N = L/2).  CPLX: chunk of L fp16 complex values.
+template <int LG, class IO, bool CPLX>
+__device__ __forceinline__ void phase1(const typename IO::T* ra, const typename IO::T* rb, bool has_b,
+                                       const __half2* chunk, uint32_t* xb, const uint4* gtab, const uint4* t1f,
+                                       const Consts<LG>& K, int t0, int lane)
+{
+    using C = CC<LG>;
+    const int c = lane & 15, g = lane >> 4;
+    uint32_t w[4][8];       // CPLX: [j][tile] complex words; REAL: [j][0..3] row a pairs, [j][4..7] row b pairs
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
+        if (CPLX) {
+            load_words<4>(chunk + n0, &w[j][0]);
+            load_words<4>(chunk + n0 + 4, &w[j][4]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[j][i] = 0u;
+            if (g < 2) {
+                load_words<4>(ra + n0, &w[j][0]);
+                if (has_b) load_words<4>(rb + n0, &w[j][4]);
+                if (IsBf<IO>::v) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) w[j][i] = bf2_to_h2(w[j][i]);
+                }
+            }
+        }
+    }
+    phase1_core<LG, CPLX>(w, xb, gtab, t1f, K, t0, lane);
 }
 
 // word address of (tile t2, reg 0) for this lane in phase 2; reg j adds j*TE*4 words
@@ -533,6 +551,73 @@ coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __re
     }
 }
 
+// -------------------------------------------------------------------------------------
+// Kernel spectrum on the matrix cores for the chained kernels' lane order.  grid = (H, R).
+//   single pass: the head's kernel k[h,:] * rs[h] (power-of-two pre-scale) as the real row of a
+//                pair whose other row is zero;
+//   multi pass : chunk k1 of the pass-A output of the pre-scaled kernel.
+// Phase 1 and the forward half of phase 2 as in the convolution; value stored =
+// kscale * (FFT([k,0]) + D[h]).
+// -------------------------------------------------------------------------------------
+template <int LG, bool CPLX>
+__global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, const float* __restrict__ D,
+                  const float* __restrict__ rs, float2* __restrict__ kspec, int64_t N, int log2R,
+                  float kscale_over_c, float kscale, const float2* __restrict__ tw,
+                  const unsigned char* __restrict__ ctab)
+{
+    using C = CC<LG>;
+    extern __shared__ uint4 lds4[];
+    uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
+    uint4* t1f = lds4 + C::XWORDS / 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int h = blockIdx.x, k1 = blockIdx.y;
+    const int64_t Ltot = (int64_t)C::L << log2R;
+    const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
+    for (int i = tid; i < C::TC * 8; i += C::NW * 64) t1f[i] = gtab[C::T1F + i];
+    Consts<LG> K;
+    make_consts<LG>(K, tw, lane);
+    __syncthreads();
+    const float r = head_scale_of(rs[h]);
+    const float* kr = k + (size_t)h * N;
+    const __half2* chunk = ws + (size_t)h * Ltot + (size_t)k1 * C::L;
+#pragma unroll
+    for (int gi = 0; gi < C::NG; ++gi) {
+        const int t0 = (gi * C::NW + wave) * 8;
+        if (CPLX) {
+            phase1<LG, IoF16, true>(nullptr, nullptr, false, chunk, xb, gtab, t1f, K, t0, lane);
+        } else {
+            // stage the fp32 kernel row as fp16 in registers, then the common phase 1 on them
+            uint32_t w[4][8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    w[j][i] = 0u; w[j][4 + i] = 0u;
+                    if (g < 2) w[j][i] = pack_h2(kr[n0 + 2 * i] * r, kr[n0 + 2 * i + 1] * r);
+                }
+            }
+            phase1_regs<LG>(w, xb, gtab, t1f, K, t0, lane);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+    const float alpha = kscale_over_c / r, beta = D[h] * kscale;
+    float4* out = reinterpret_cast<float4*>(kspec + (size_t)h * Ltot + (size_t)k1 * C::L);
+#pragma unroll
+    for (int gi = 0; gi < C::NG; ++gi)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t2 = (gi * C::NW + wave) * 8 + i;
+            f4 zr, zi;
+            phase2_fwd<LG>(xb, phase2_base<LG>(t2, lane), K, zr, zi);
+            out[(t2 * 64 + lane) * 2] = make_float4(zr[0] * alpha + beta, zi[0] * alpha, zr[1] * alpha + beta, zi[1] * alpha);
+            out[(t2 * 64 + lane) * 2 + 1] = make_float4(zr[2] * alpha + beta, zi[2] * alpha, zr[3] * alpha + beta, zi[3] * alpha);
+        }
+}
+
 template <int LG>
 size_t coop_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16; }
 
@@ -596,6 +681,32 @@ hipError_t coop_dk_go(const void* dy, const void* u, float* dk, float* dD, const
     return hipGetLastError();
 }
 
+template <int LG>
+hipError_t coop_kspec_go(const float* k, const __half2* ws, const float* D, const float* rs, float2* kspec,
+                         int64_t H, int64_t N, const Plan& pl, const Tables& tb, hipStream_t st)
+{
+    using C = CC<LG>;
+    const size_t lds = coop_lds_bytes<LG>();
+    dim3 grid((unsigned)H, 1u << pl.log2R);
+    const int shift = 6 + (C::te >= 2 ? 1 : 0);
+    const float koc = pl.kscale * (float)(1 << shift);
+    hipError_t e;
+    if (pl.log2R == 0) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_kspec_kernel<LG, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((coop_kspec_kernel<LG, false>), grid, dim3(C::NW * 64), lds, st, k, ws, D, rs, kspec, N,
+                           pl.log2R, koc, pl.kscale, tb.tw, (const unsigned char*)tb.ctab);
+    } else {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_kspec_kernel<LG, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((coop_kspec_kernel<LG, true>), grid, dim3(C::NW * 64), lds, st, k, ws, D, rs, kspec, N,
+                           pl.log2R, koc, pl.kscale, tb.tw, (const unsigned char*)tb.ctab);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
@@ -612,6 +723,15 @@ hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws
         if (pl.log2L2 == 15) GO(15, IoBF16);
     }
 #undef GO
+    return hipErrorInvalidValue;
+}
+
+hipError_t coop_kspec(const float* k, const __half2* ws, const float* D, const float* rs, float2* kspec, int64_t H,
+                      int64_t N, const Plan& pl, const Tables& tb, hipStream_t st)
+{
+    if (pl.log2L2 == 13) return coop_kspec_go<13>(k, ws, D, rs, kspec, H, N, pl, tb, st);
+    if (pl.log2L2 == 14) return coop_kspec_go<14>(k, ws, D, rs, kspec, H, N, pl, tb, st);
+    if (pl.log2L2 == 15) return coop_kspec_go<15>(k, ws, D, rs, kspec, H, N, pl, tb, st);
     return hipErrorInvalidValue;
 }
 

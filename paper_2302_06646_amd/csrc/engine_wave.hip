@@ -640,6 +640,92 @@ hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, const Pro
     }
 }
 
+// -------------------------------------------------------------------------------------
+// Kernel spectrum on the matrix cores (Algorithm 2 lines 1-2) for the wave kernels' lane order.
+// One wave per head: k[h,:] * rs[h] (rs = power of two bringing max|k| to about 1, so the fp16
+// operands keep their relative precision) is transformed as the real row of a pair whose other
+// row is zero; phases 1 and the forward half of phase 2 are those of the convolution kernel.
+// Stored value = kscale * (FFT([k,0]) + D[h]).
+// -------------------------------------------------------------------------------------
+template <int LG, int NWV>
+__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
+wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, const float* __restrict__ rs,
+              float2* __restrict__ kspec, int64_t H, int64_t N, float kscale_over_c, float kscale,
+              const unsigned char* __restrict__ wtab)
+{
+    using C = WC<LG>;
+    extern __shared__ uint4 lds4[];
+    uint32_t* lds = reinterpret_cast<uint32_t*>(lds4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    {
+        const uint4* gt = reinterpret_cast<const uint4*>(wtab + wave_tab_offset(LG));
+        for (int i = tid; i < C::TAB_U4; i += NWV * 64) lds4[i] = gt[i];
+    }
+    __syncthreads();
+    const uint4* tab = lds4;
+    Mats F16, FL;
+    {
+        H8U m;
+        m.u = tab[C::PM + 0 * 64 + lane]; F16.re = m.v;
+        m.u = tab[C::PM + 1 * 64 + lane]; F16.im = m.v;
+        m.u = tab[C::PM + 4 * 64 + lane]; FL.re = m.v;
+        m.u = tab[C::PM + 5 * 64 + lane]; FL.im = m.v;
+    }
+    uint32_t* xb = lds + C::TAB_U4 * 4 + wave * C::PAIR_WORDS;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t h = (int64_t)blockIdx.x * NWV + wave; h < H; h += (int64_t)gridDim.x * NWV) {
+        const float r = head_scale_of(rs[h]);
+        const float* kr = k + (size_t)h * N;
+#pragma unroll
+        for (int tg = 0; tg < C::TC; tg += C::TG) {
+            InRegs<LG, 1> inr;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + tg;
+#pragma unroll
+                for (int i = 0; i < C::NWD; ++i) {
+                    inr.wb[0][j][i] = 0u;
+                    inr.wa[0][j][i] = 0u;
+                    if (g < 2) inr.wa[0][j][i] = pack_h2(kr[n0 + 2 * i] * r, kr[n0 + 2 * i + 1] * r);
+                }
+            }
+            phase1_group<LG, IoF16, 1>(inr, tg, xb, tab, F16, lane);
+        }
+        wave_lds_fence();
+        const float alpha = kscale_over_c / r, beta = D[h] * kscale;
+        float4* out = reinterpret_cast<float4*>(kspec + (size_t)h * C::L);
+#pragma unroll
+        for (int t2 = 0; t2 < C::TC; ++t2) {
+            H8U x;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x.w[j] = xb[phase2_addr<LG>(t2, j, lane)];
+            const f4 yr = MFMA(FL.re, x.v, zero), yi = MFMA(FL.im, x.v, zero);
+            out[(t2 * 64 + lane) * 2] = make_float4(yr[0] * alpha + beta, yi[0] * alpha, yr[1] * alpha + beta, yi[1] * alpha);
+            out[(t2 * 64 + lane) * 2 + 1] = make_float4(yr[2] * alpha + beta, yi[2] * alpha, yr[3] * alpha + beta, yi[3] * alpha);
+        }
+        wave_lds_fence();
+    }
+}
+
+template <int LG>
+hipError_t wkspec_go(const float* k, const float* D, const float* rs, float2* kspec, int64_t H, int64_t N,
+                     const Plan& pl, const Tables& tb, hipStream_t st)
+{
+    using C = WC<LG>;
+    constexpr int NWV = LG == 12 ? 3 : 8;
+    const size_t lds = (size_t)C::TAB_U4 * 16 + (size_t)NWV * C::PAIR_WORDS * 4;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wkspec_kernel<LG, NWV>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    long nblk = (H + NWV - 1) / NWV;
+    if (nblk > 512) nblk = 512;
+    const int shift = 4 + (C::cb == 4 ? 2 : (C::cb >= 2 ? 1 : 0));
+    hipLaunchKernelGGL((wkspec_kernel<LG, NWV>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st, k, D, rs, kspec, H, N,
+                       pl.kscale * (float)(1 << shift), pl.kscale, (const unsigned char*)tb.wtab);
+    return hipGetLastError();
+}
+
 template <int LG, class IO, int PB, int NWV>
 hipError_t wconv_go(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
                     const Tables& tb, hipStream_t st)
@@ -685,6 +771,18 @@ hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, 
     if (pr.io == LONGCONV_F16) return wconv_io<IoF16>(in, kspec, out, conj, pr, pl, tb, st);
     if (pr.io == LONGCONV_BF16) return wconv_io<IoBF16>(in, kspec, out, conj, pr, pl, tb, st);
     return hipErrorInvalidValue;
+}
+
+hipError_t wave_kspec(const float* k, const float* D, const float* rs, float2* kspec, int64_t H, int64_t N,
+                      const Plan& pl, const Tables& tb, hipStream_t st)
+{
+    switch (pl.log2L2) {
+        case 9: return wkspec_go<9>(k, D, rs, kspec, H, N, pl, tb, st);
+        case 10: return wkspec_go<10>(k, D, rs, kspec, H, N, pl, tb, st);
+        case 11: return wkspec_go<11>(k, D, rs, kspec, H, N, pl, tb, st);
+        case 12: return wkspec_go<12>(k, D, rs, kspec, H, N, pl, tb, st);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,

@@ -17,7 +17,9 @@ struct Problem {
 // dD_part != NULL, per-block partial sums of in*in2 are written for the dD reduction.
 hipError_t outer_fwd(const void* in, const void* in2, void* ws, void* ws2, float* dD_part,
                      const Problem& pr, int log2R, int log2L2, float scale, bool ws_f16,
-                     const float2* tw, hipStream_t st);
+                     const float2* tw, hipStream_t st, const float* head_max = nullptr);
+// mx[h] = max_n |k[h,n]|; consumers derive the head's power-of-two pre-scale with head_scale_of().
+hipError_t head_max(const float* k, float* mx, int64_t H, int64_t N, hipStream_t st);
 int outer_fwd_blocks_per_head(const Problem& pr, int log2L2);
 // Pass C: rows of `out` <- scale * sum_{k1} conj(w_R^(n1*k1) w_L^(n2*k1)) ws[...], n1 < R/2 only
 // (truncation to the first N samples); re -> row 2p, im -> row 2p+1.
@@ -58,12 +60,18 @@ hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, 
                      const Plan& pl, const Tables& tb, hipStream_t st);
 hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
                    const Tables& tb, hipStream_t st);
+// Spectrum on the matrix cores; rs[h] = max |k[h,:]| (see head_max()).
+hipError_t wave_kspec(const float* k, const float* D, const float* rs, float2* kspec, int64_t H, int64_t N,
+                      const Plan& pl, const Tables& tb, hipStream_t st);
 
 // ---- cooperative chained matrix-core kernels for 2^13 <= L2 <= 2^15 (engine_coop.hip) --------
 constexpr int COOP_MIN_LOG2 = 13, COOP_MAX_LOG2 = 15;
 hipError_t coop_fill_tables(const void** tab_out, hipStream_t st);
 hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
                      const Plan& pl, const Tables& tb, hipStream_t st);
+// ws: pass-A output of the pre-scaled kernel (multi-pass plans only).
+hipError_t coop_kspec(const float* k, const __half2* ws, const float* D, const float* rs, float2* kspec, int64_t H,
+                      int64_t N, const Plan& pl, const Tables& tb, hipStream_t st);
 // zbuf: H * 2N * 4 bytes of scratch (transform of the current u pair, parked between the two transforms)
 hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
                    __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl, const Tables& tb,

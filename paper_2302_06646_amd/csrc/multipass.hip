@@ -22,7 +22,8 @@ template <class IO, class CW, int LOG2R, bool TWO>
 __global__ void outer_fwd_kernel(const typename IO::T* __restrict__ in, const typename IO::T* __restrict__ in2,
                                  typename CW::T* __restrict__ ws, typename CW::T* __restrict__ ws2,
                                  float* __restrict__ dD_part, int64_t B, int64_t H, int64_t N, int npairs,
-                                 int log2L2, float scale, const float2* __restrict__ tw)
+                                 int log2L2, float scale, const float2* __restrict__ tw,
+                                 const float* __restrict__ head_max)
 {
     constexpr int R = 1 << LOG2R, RH = R / 2;
     __shared__ float red[OB / 64];
@@ -33,6 +34,7 @@ __global__ void outer_fwd_kernel(const typename IO::T* __restrict__ in, const ty
     const int h = pairidx / npairs, p = pairidx % npairs;
     const bool has_b = (2 * p + 1) < B;
     const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
+    if (head_max) scale *= head_scale_of(head_max[h]);
     float2 z[RH], z2[RH];
     float dsum = 0.f;
 #pragma unroll
@@ -108,6 +110,36 @@ __global__ void outer_inv_kernel(const typename CW::T* __restrict__ ws, typename
     }
 }
 
+// per-head max |k| as float bits (non-negative floats order like unsigned integers, so the
+// atomic max is exact and independent of arrival order)
+__global__ void head_max_zero_kernel(unsigned* __restrict__ mx, int64_t H)
+{
+    const int64_t h = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (h < H) mx[h] = 0u;
+}
+__global__ void head_max_kernel(const float* __restrict__ k, unsigned* __restrict__ mx, int64_t N)
+{
+    __shared__ float red[4];
+    const float4* kr = reinterpret_cast<const float4*>(k + (size_t)blockIdx.y * N) + (size_t)blockIdx.x * 1024;
+    float m = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const size_t idx = threadIdx.x + 256 * i;
+        if (((size_t)blockIdx.x * 1024 + idx) * 4 < (size_t)N) {
+            const float4 v = kr[idx];
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_down(m, o, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        if (!(m == m)) m = __uint_as_float(0x7f800000u);   // a NaN in the head: treat as unscalable
+        atomicMax(&mx[blockIdx.y], __float_as_uint(m));
+    }
+}
+
 __global__ void reduce_dD_kernel(const float* __restrict__ part, float* __restrict__ dD, int64_t H, int nblk)
 {
     const int64_t h = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -119,18 +151,18 @@ __global__ void reduce_dD_kernel(const float* __restrict__ part, float* __restri
 
 template <class IO, class CW, int LOG2R>
 hipError_t fwd_launch(const void* in, const void* in2, void* ws, void* ws2, float* dD_part, const Problem& pr,
-                      int log2L2, float scale, const float2* tw, hipStream_t st)
+                      int log2L2, float scale, const float2* tw, hipStream_t st, const float* hs)
 {
     using T = typename IO::T;
     using C = typename CW::T;
     dim3 grid((1u << log2L2) / OB, (unsigned)(pr.npairs * pr.H));
     if (in2)
         hipLaunchKernelGGL((outer_fwd_kernel<IO, CW, LOG2R, true>), grid, dim3(OB), 0, st, (const T*)in,
-                           (const T*)in2, (C*)ws, (C*)ws2, dD_part, pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw);
+                           (const T*)in2, (C*)ws, (C*)ws2, dD_part, pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw, hs);
     else
         hipLaunchKernelGGL((outer_fwd_kernel<IO, CW, LOG2R, false>), grid, dim3(OB), 0, st, (const T*)in,
                            (const T*)nullptr, (C*)ws, (C*)nullptr, (float*)nullptr, pr.B, pr.H, pr.N, pr.npairs,
-                           log2L2, scale, tw);
+                           log2L2, scale, tw, hs);
     return hipGetLastError();
 }
 
@@ -158,9 +190,9 @@ hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, 
 
 template <class IO, class CW>
 hipError_t fwd_r(const void* in, const void* in2, void* ws, void* ws2, float* dD_part, const Problem& pr,
-                 int log2R, int log2L2, float scale, const float2* tw, hipStream_t st)
+                 int log2R, int log2L2, float scale, const float2* tw, hipStream_t st, const float* hs)
 {
-#define CALL(LR) fwd_launch<IO, CW, LR>(in, in2, ws, ws2, dD_part, pr, log2L2, scale, tw, st)
+#define CALL(LR) fwd_launch<IO, CW, LR>(in, in2, ws, ws2, dD_part, pr, log2L2, scale, tw, st, hs)
     LC_R_SWITCH(CALL)
 #undef CALL
 }
@@ -178,10 +210,11 @@ hipError_t inv_r(const void* ws, void* out, const Problem& pr, int log2R, int lo
 int outer_fwd_blocks_per_head(const Problem& pr, int log2L2) { return pr.npairs * ((1 << log2L2) / OB); }
 
 hipError_t outer_fwd(const void* in, const void* in2, void* ws, void* ws2, float* dD_part, const Problem& pr,
-                     int log2R, int log2L2, float scale, bool ws_f16, const float2* tw, hipStream_t st)
+                     int log2R, int log2L2, float scale, bool ws_f16, const float2* tw, hipStream_t st,
+                     const float* head_scale)
 {
     if ((1 << log2L2) < OB) return hipErrorInvalidValue;
-#define GO(IO, CW) return fwd_r<IO, CW>(in, in2, ws, ws2, dD_part, pr, log2R, log2L2, scale, tw, st)
+#define GO(IO, CW) return fwd_r<IO, CW>(in, in2, ws, ws2, dD_part, pr, log2R, log2L2, scale, tw, st, head_scale)
     if (ws_f16) {
         if (pr.io == LONGCONV_F32) GO(IoF32, CwF16);
         if (pr.io == LONGCONV_F16) GO(IoF16, CwF16);
@@ -209,6 +242,14 @@ hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, in
         GO(IoBF16, CwF32);
     }
 #undef GO
+}
+
+hipError_t head_max(const float* k, float* mx, int64_t H, int64_t N, hipStream_t st)
+{
+    hipLaunchKernelGGL(head_max_zero_kernel, dim3((unsigned)((H + 255) / 256)), dim3(256), 0, st, (unsigned*)mx, H);
+    hipLaunchKernelGGL(head_max_kernel, dim3((unsigned)((N + 4095) / 4096), (unsigned)H), dim3(256), 0, st, k,
+                       (unsigned*)mx, N);
+    return hipGetLastError();
 }
 
 hipError_t reduce_dD(const float* part, float* dD, int64_t H, int nblk, hipStream_t st)
