@@ -21,6 +21,8 @@
 
 namespace lc {
 
+constexpr int NTB = 4;   // tiles advanced together per wave (instruction-level parallelism)
+
 template <int LG>
 struct CC {
     static constexpr int cb = LG - 8, TC = 1 << cb, te = cb - 4, TE = 1 << te, L = 1 << LG;
@@ -141,17 +143,17 @@ __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t*
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
 #pragma unroll
-    for (int tb = 0; tb < 8; tb += 2) {
-        H8U tw0[2], tw1[2];
-        f4 yr[2], yi[2], zr[2], zi[2];
+    for (int tb = 0; tb < 8; tb += NTB) {
+        H8U tw0[NTB], tw1[NTB];
+        f4 yr[NTB], yi[NTB], zr[NTB], zi[NTB];
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
+        for (int k = 0; k < NTB; ++k) {
             const int t = t0 + tb + k;
             tw0[k].u = gtab[C::T0F + t * 64 + lane];
             tw1[k].u = t1f[t * 4 + g];
         }
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
+        for (int k = 0; k < NTB; ++k) {
             const int tt = tb + k;
             H8U x;
 #pragma unroll
@@ -164,7 +166,7 @@ __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t*
             yi[k] = MFMA(x.v, K.F16.im, zero);
         }
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
+        for (int k = 0; k < NTB; ++k) {
             H8U u;
 #pragma unroll
             for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][j], yi[k][j], tw0[k].c[j]);
@@ -172,7 +174,7 @@ __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t*
             zi[k] = MFMA(K.F16.im, u.v, zero);
         }
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
+        for (int k = 0; k < NTB; ++k) {
             uint4 o;
             o.x = cmul_pack(zr[k][0], zi[k][0], tw1[k].c[0]);
             o.y = cmul_pack(zr[k][1], zi[k][1], tw1[k].c[1]);
@@ -180,6 +182,7 @@ __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t*
             o.w = cmul_pack(zr[k][3], zi[k][3], tw1[k].c[3]);
             *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
         }
+        __builtin_amdgcn_sched_barrier(0);   // one batch at a time: bounds register pressure
     }
 }
 
@@ -327,6 +330,8 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     make_consts<LG>(K, tw, lane);
     const float csign = conj ? -1.f : 1.f;
     const float4* ks = reinterpret_cast<const float4*>(kspec + (size_t)h * Ltot + (size_t)k1 * C::L);
+    int ng = C::NG;
+    asm volatile("" : "+s"(ng));   // opaque trip count: the group loops stay loops (bounded register pressure)
     __syncthreads();
 
     for (int p = blockIdx.x; p < npairs; p += gridDim.x) {
@@ -336,33 +341,34 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
         const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
         __half2* chunk = ws + ((size_t)h * npairs + p) * Ltot + (size_t)k1 * C::L;
 
-#pragma unroll
-        for (int gi = 0; gi < C::NG; ++gi) {
+#pragma unroll 1
+        for (int gi = 0; gi < ng; ++gi) {
             phase1<LG, IO, CPLX>(in + oa, in + ob, has_b, chunk, xb, gtab, t1f, K, (gi * C::NW + wave) * 8, lane);
             __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds register pressure
         }
         __syncthreads();
+        asm volatile("" : "+s"(ks));      // keep phase 2's spectrum loads below the barrier (register pressure)
 
         // ---- phase 2: two tiles in flight
+#pragma unroll 1
+        for (int gi = 0; gi < ng; ++gi)
 #pragma unroll
-        for (int gi = 0; gi < C::NG; ++gi)
-#pragma unroll
-        for (int tb = 0; tb < 8; tb += 2) {
+        for (int tb = 0; tb < 8; tb += NTB) {
             const int t0 = (gi * C::NW + wave) * 8;
-            int base[2];
-            f4 zr[2], zi[2];
-            float4 k01[2], k23[2];
+            int base[NTB];
+            f4 zr[NTB], zi[NTB];
+            float4 k01[NTB], k23[NTB];
 #pragma unroll
-            for (int k = 0; k < 2; ++k) {
+            for (int k = 0; k < NTB; ++k) {
                 const int t2 = t0 + tb + k;
                 base[k] = phase2_base<LG>(t2, lane);
                 k01[k] = ks[(t2 * 64 + lane) * 2];
                 k23[k] = ks[(t2 * 64 + lane) * 2 + 1];
             }
 #pragma unroll
-            for (int k = 0; k < 2; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
+            for (int k = 0; k < NTB; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
 #pragma unroll
-            for (int k = 0; k < 2; ++k) {
+            for (int k = 0; k < NTB; ++k) {
                 const float2 kk[4] = {make_float2(k01[k].x, k01[k].y * csign), make_float2(k01[k].z, k01[k].w * csign),
                                       make_float2(k23[k].x, k23[k].y * csign), make_float2(k23[k].z, k23[k].w * csign)};
                 H8U m;
@@ -376,10 +382,11 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
             __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
+        asm volatile("" : "+s"(gtab));
 
         // ---- phase 3
-#pragma unroll
-        for (int gi = 0; gi < C::NG; ++gi) {
+#pragma unroll 1
+        for (int gi = 0; gi < ng; ++gi) {
         const int t0 = (gi * C::NW + wave) * 8;
         uint32_t ow[4][8];     // REAL: [j][0..3] row a, [4..7] row b; CPLX: [j][tile]
 #pragma unroll
@@ -399,6 +406,7 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
                     ow[j][4 + (tb >> 1)] = pack_h2(s[0][j], s[1][j]);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
