@@ -173,9 +173,9 @@ static hipError_t run_kspec(const float* k, const float* D, float2* kspec, float
     const float2* tw = tb.tw;
     if (pl.engine == ENGINE_MFMA && (pl.order.wave_lg || pl.order.coop_lg)) {
         // matrix-core route: per-head power-of-two pre-scale, (pass A,) forward half of the fused kernel
+        if (pl.order.wave_lg) return wave_kspec(k, D, kspec, H, N, pl, tb, st);
         hipError_t e = head_max(k, hscale, H, N, st);
         if (e != hipSuccess) return e;
-        if (pl.order.wave_lg) return wave_kspec(k, D, hscale, kspec, H, N, pl, tb, st);
         if (pl.log2R) {
             Problem pk{1, H, N, LONGCONV_F32, 1};
             e = outer_fwd(k, nullptr, kscratch, nullptr, nullptr, pk, pl.log2R, pl.log2L2, 1.0f, true, tw, st, hscale);

@@ -311,7 +311,7 @@ template <int LG, class IO, bool CPLX>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
                  typename IO::T* __restrict__ out, __half2* __restrict__ ws, int conj, int64_t B, int64_t H,
-                 int64_t N, int npairs, int log2R, const float2* __restrict__ tw,
+                 int64_t N, int npairs, int log2R, int gx, const float2* __restrict__ tw,
                  const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
@@ -322,7 +322,14 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     uint4* t1i = t1f + C::TC * 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
-    const int h = blockIdx.y, k1 = blockIdx.z;
+    // Workgroups go to the 8 XCDs round-robin by linear id, each XCD with its own L2.  Renumber so that
+    // consecutive virtual ids share an XCD: the gx workgroups of one (head, slice) then run side by side
+    // on one L2 and its spectrum slice is fetched from HBM once.
+    const unsigned G = gridDim.x;
+    const unsigned vid = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (G >> 3) + (blockIdx.x >> 3);
+    const int p0 = (int)(vid % (unsigned)gx);
+    const int k1 = (int)((vid / (unsigned)gx) & ((1u << log2R) - 1u));
+    const int h = (int)((vid / (unsigned)gx) >> log2R);
     const int64_t Ltot = (int64_t)C::L << log2R;
     const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
     for (int i = tid; i < C::TC * 8; i += C::NW * 64) t1f[i] = gtab[C::T1F + i];
@@ -334,7 +341,7 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     asm volatile("" : "+s"(ng));   // opaque trip count: the group loops stay loops (bounded register pressure)
     __syncthreads();
 
-    for (int p = blockIdx.x; p < npairs; p += gridDim.x) {
+    for (int p = p0; p < npairs; p += gx) {
         // table and spectrum loads stay inside the loop (hoisting them costs more registers than a wave has)
         asm volatile("" : "+s"(gtab), "+s"(ks));
         const bool has_b = (2 * p + 1) < B;
@@ -639,21 +646,21 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
     long gx = (512 + pr.H * R - 1) / (pr.H * R);
     if (gx < 1) gx = 1;
     if (gx > pr.npairs) gx = pr.npairs;
-    dim3 grid((unsigned)gx, (unsigned)pr.H, (unsigned)R);
+    dim3 grid((unsigned)(gx * pr.H * R));
     hipError_t e;
     if (pl.log2R == 0) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, IO, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((coop_conv_kernel<LG, IO, false>), grid, dim3(CC<LG>::NW * 64), lds, st, (const T*)in,
-                           kspec, (T*)out, ws, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, tb.tw,
+                           kspec, (T*)out, ws, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, (int)gx, tb.tw,
                            (const unsigned char*)tb.ctab);
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, IO, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((coop_conv_kernel<LG, IO, true>), grid, dim3(CC<LG>::NW * 64), lds, st, (const T*)in,
-                           kspec, (T*)out, ws, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, tb.tw,
+                           kspec, (T*)out, ws, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, (int)gx, tb.tw,
                            (const unsigned char*)tb.ctab);
     }
     return hipGetLastError();

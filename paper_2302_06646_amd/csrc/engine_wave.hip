@@ -642,15 +642,14 @@ hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, const Pro
 
 // -------------------------------------------------------------------------------------
 // Kernel spectrum on the matrix cores (Algorithm 2 lines 1-2) for the wave kernels' lane order.
-// One wave per head: k[h,:] * rs[h] (rs = power of two bringing max|k| to about 1, so the fp16
-// operands keep their relative precision) is transformed as the real row of a pair whose other
+// One wave per head: k[h,:] * r (r = power of two bringing max|k[h,:]| to about 1, so the fp16
+// operands keep their relative precision whatever the head's magnitude) is transformed as the real row of a pair whose other
 // row is zero; phases 1 and the forward half of phase 2 are those of the convolution kernel.
 // Stored value = kscale * (FFT([k,0]) + D[h]).
 // -------------------------------------------------------------------------------------
 template <int LG, int NWV>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
-wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, const float* __restrict__ rs,
-              float2* __restrict__ kspec, int64_t H, int64_t N, float kscale_over_c, float kscale,
+wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, float2* __restrict__ kspec, int64_t H, int64_t N, float kscale_over_c, float kscale,
               const unsigned char* __restrict__ wtab)
 {
     using C = WC<LG>;
@@ -675,8 +674,15 @@ wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, const fl
     uint32_t* xb = lds + C::TAB_U4 * 4 + wave * C::PAIR_WORDS;
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     for (int64_t h = (int64_t)blockIdx.x * NWV + wave; h < H; h += (int64_t)gridDim.x * NWV) {
-        const float r = head_scale_of(rs[h]);
         const float* kr = k + (size_t)h * N;
+        // max |k[h,:]| over the wave (the row is read again below, from cache)
+        float m = 0.f;
+        for (int n = lane * 4; n < N; n += 256) {
+            const float4 v = *reinterpret_cast<const float4*>(kr + n);
+            m = fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        }
+        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+        const float r = head_scale_of(m);
 #pragma unroll
         for (int tg = 0; tg < C::TC; tg += C::TG) {
             InRegs<LG, 1> inr;
@@ -709,7 +715,7 @@ wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, const fl
 }
 
 template <int LG>
-hipError_t wkspec_go(const float* k, const float* D, const float* rs, float2* kspec, int64_t H, int64_t N,
+hipError_t wkspec_go(const float* k, const float* D, float2* kspec, int64_t H, int64_t N,
                      const Plan& pl, const Tables& tb, hipStream_t st)
 {
     using C = WC<LG>;
@@ -721,7 +727,7 @@ hipError_t wkspec_go(const float* k, const float* D, const float* rs, float2* ks
     long nblk = (H + NWV - 1) / NWV;
     if (nblk > 512) nblk = 512;
     const int shift = 4 + (C::cb == 4 ? 2 : (C::cb >= 2 ? 1 : 0));
-    hipLaunchKernelGGL((wkspec_kernel<LG, NWV>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st, k, D, rs, kspec, H, N,
+    hipLaunchKernelGGL((wkspec_kernel<LG, NWV>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st, k, D, kspec, H, N,
                        pl.kscale * (float)(1 << shift), pl.kscale, (const unsigned char*)tb.wtab);
     return hipGetLastError();
 }
@@ -773,14 +779,14 @@ hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, 
     return hipErrorInvalidValue;
 }
 
-hipError_t wave_kspec(const float* k, const float* D, const float* rs, float2* kspec, int64_t H, int64_t N,
+hipError_t wave_kspec(const float* k, const float* D, float2* kspec, int64_t H, int64_t N,
                       const Plan& pl, const Tables& tb, hipStream_t st)
 {
     switch (pl.log2L2) {
-        case 9: return wkspec_go<9>(k, D, rs, kspec, H, N, pl, tb, st);
-        case 10: return wkspec_go<10>(k, D, rs, kspec, H, N, pl, tb, st);
-        case 11: return wkspec_go<11>(k, D, rs, kspec, H, N, pl, tb, st);
-        case 12: return wkspec_go<12>(k, D, rs, kspec, H, N, pl, tb, st);
+        case 9: return wkspec_go<9>(k, D, kspec, H, N, pl, tb, st);
+        case 10: return wkspec_go<10>(k, D, kspec, H, N, pl, tb, st);
+        case 11: return wkspec_go<11>(k, D, kspec, H, N, pl, tb, st);
+        case 12: return wkspec_go<12>(k, D, kspec, H, N, pl, tb, st);
         default: return hipErrorInvalidValue;
     }
 }

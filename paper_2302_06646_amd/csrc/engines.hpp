@@ -60,8 +60,8 @@ hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, 
                      const Plan& pl, const Tables& tb, hipStream_t st);
 hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
                    const Tables& tb, hipStream_t st);
-// Spectrum on the matrix cores; rs[h] = max |k[h,:]| (see head_max()).
-hipError_t wave_kspec(const float* k, const float* D, const float* rs, float2* kspec, int64_t H, int64_t N,
+// Spectrum on the matrix cores (finds each head's pre-scale itself).
+hipError_t wave_kspec(const float* k, const float* D, float2* kspec, int64_t H, int64_t N,
                       const Plan& pl, const Tables& tb, hipStream_t st);
 
 // ---- cooperative chained matrix-core kernels for 2^13 <= L2 <= 2^15 (engine_coop.hip) --------

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 def _need_gpu_and_clean_env(monkeypatch):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2"):
+    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL"):
         monkeypatch.delenv(v, raising=False)
     yield
 
@@ -64,6 +64,14 @@ def test_forced_multipass_small(monkeypatch, engine, inner):
     monkeypatch.setenv("LONGCONV_INNER_LOG2", str(inner))
     io = wl.F32 if engine == "valu" else wl.F16
     check_full(wl.generate(_w("1", N=2048, dtype=io), B=3, H=3), label=f"{engine} inner=2^{inner}")
+
+
+@pytest.mark.parametrize("key,B,H", [("2", 5, 3), ("3", 2, 2), ("5_4096", 3, 2)])
+def test_staged_matrix_core_kernel(monkeypatch, key, B, H):
+    # the in-place staged kernel (normally only used for 256-point transforms) forced at other lengths
+    from gpu_harness import check_full
+    monkeypatch.setenv("LONGCONV_MFMA_KERNEL", "staged")
+    check_full(wl.generate(wl.WORKLOADS[key], B=B, H=H), label="staged")
 
 
 def test_valu_engine_with_half_io(monkeypatch):
