@@ -134,7 +134,7 @@ __device__ __forceinline__ void make_consts(Consts<LG>& K, const float2* __restr
 
 // phase 1 arithmetic on staged operand words of 8 tiles.  CPLX: w[j][tile] fp16 complex;
 // otherwise w[j][0..3] = row a sample pairs, w[j][4..7] = row b sample pairs (fp16).
-template <int LG, bool CPLX>
+template <int LG, bool CPLX, int NB = NTB>
 __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t* xb, const uint4* gtab,
                                             const uint4* t1f, const Consts<LG>& K, int t0, int lane)
 {
@@ -143,17 +143,17 @@ __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t*
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
 #pragma unroll
-    for (int tb = 0; tb < 8; tb += NTB) {
-        H8U tw0[NTB], tw1[NTB];
-        f4 yr[NTB], yi[NTB], zr[NTB], zi[NTB];
+    for (int tb = 0; tb < 8; tb += NB) {
+        H8U tw0[NB], tw1[NB];
+        f4 yr[NB], yi[NB], zr[NB], zi[NB];
 #pragma unroll
-        for (int k = 0; k < NTB; ++k) {
+        for (int k = 0; k < NB; ++k) {
             const int t = t0 + tb + k;
             tw0[k].u = gtab[C::T0F + t * 64 + lane];
             tw1[k].u = t1f[t * 4 + g];
         }
 #pragma unroll
-        for (int k = 0; k < NTB; ++k) {
+        for (int k = 0; k < NB; ++k) {
             const int tt = tb + k;
             H8U x;
 #pragma unroll
@@ -166,7 +166,7 @@ __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t*
             yi[k] = MFMA(x.v, K.F16.im, zero);
         }
 #pragma unroll
-        for (int k = 0; k < NTB; ++k) {
+        for (int k = 0; k < NB; ++k) {
             H8U u;
 #pragma unroll
             for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][j], yi[k][j], tw0[k].c[j]);
@@ -174,7 +174,7 @@ __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t*
             zi[k] = MFMA(K.F16.im, u.v, zero);
         }
 #pragma unroll
-        for (int k = 0; k < NTB; ++k) {
+        for (int k = 0; k < NB; ++k) {
             uint4 o;
             o.x = cmul_pack(zr[k][0], zi[k][0], tw1[k].c[0]);
             o.y = cmul_pack(zr[k][1], zi[k][1], tw1[k].c[1]);
@@ -195,7 +195,7 @@ __device__ __forceinline__ void phase1_regs(const uint32_t (&w)[4][8], uint32_t*
 
 // ---- phase 1 for the 8 tiles t0..t0+7 of one wave ------------------------------------
 // REAL: rows a, b of I/O elements (zero above N = L/2).  CPLX: chunk of L fp16 complex values.
-template <int LG, class IO, bool CPLX>
+template <int LG, class IO, bool CPLX, int NB = NTB>
 __device__ __forceinline__ void phase1(const typename IO::T* ra, const typename IO::T* rb, bool has_b,
                                        const __half2* chunk, uint32_t* xb, const uint4* gtab, const uint4* t1f,
                                        const Consts<LG>& K, int t0, int lane)
@@ -222,7 +222,7 @@ __device__ __forceinline__ void phase1(const typename IO::T* ra, const typename 
             }
         }
     }
-    phase1_core<LG, CPLX>(w, xb, gtab, t1f, K, t0, lane);
+    phase1_core<LG, CPLX, NB>(w, xb, gtab, t1f, K, t0, lane);
 }
 
 // word address of (tile t2, reg 0) for this lane in phase 2; reg j adds j*TE*4 words
@@ -267,6 +267,20 @@ __device__ __forceinline__ void phase2_inv(uint32_t* xb, int base, const Consts<
     const f4 vr = MFMA(K.I16.re, u.v, zero), vi = MFMA(K.I16.im, u.v, zero);
 #pragma unroll
     for (int j = 0; j < 4; ++j) xb[base + j * C::TE * 4] = pack_h2(vr[j], vi[j]);
+}
+
+// the same, result kept in registers (4 fp16 complex words)
+template <int LG>
+__device__ __forceinline__ void phase2_inv_regs(const Consts<LG>& K, const H8U& m, H8U& out)
+{
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    const f4 yr = MFMA(m.v, K.IL.re, zero), yi = MFMA(m.v, K.IL.im, zero);
+    H8U u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[j], yi[j], K.t2i[j]);
+    const f4 vr = MFMA(K.I16.re, u.v, zero), vi = MFMA(K.I16.im, u.v, zero);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) out.w[j] = pack_h2(vr[j], vi[j]);
 }
 
 // phase 3 on two tiles t, t+1: returns real parts r[k] and imaginary parts s[k] of the time samples
@@ -434,8 +448,14 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
 
 // -------------------------------------------------------------------------------------
 // dk and dD: one workgroup per (head, chunk) loops over all row pairs of the head in order.
-// Z (u pair) is kept as fp16, A += conj(Z) W accumulates in fp32 registers in the lane order
-// of phase 2; then the inverse half of phase 2 and phase 3 give dk (real part).
+// Per pair: Z = transform of the u pair (kept as fp16 in registers), W = transform of the dy
+// pair, A += conj(Z) W in fp32 registers, in the lane order of phase 2; then the inverse half of
+// phase 2 and phase 3 give dk (real part).  A wave holds Z and A for 8 phase-2 tiles at a time.
+// With NG > 1 tile groups per wave (L = 32768) the batch is walked once per group (the second
+// walk finds its rows in cache), and the inverse half-spectrum of every group but the last is
+// parked in the caller's workspace (`zbuf`, written and read once per head) until phase 3:
+// registers for all groups at once do not exist, and parking Z per pair instead costs an order
+// of magnitude more memory traffic than the second walk.
 // -------------------------------------------------------------------------------------
 template <int LG, class IO, bool CPLX>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
@@ -448,6 +468,7 @@ coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __re
 {
     using C = CC<LG>;
     using T = typename IO::T;
+    constexpr int NB = 2;      // phase-1 tiles in flight (the accumulators leave no room for more)
     extern __shared__ uint4 lds4[];
     __shared__ float red[C::NW];
     uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
@@ -462,64 +483,83 @@ coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __re
     Consts<LG> K;
     make_consts<LG>(K, tw, lane);
     __syncthreads();
-    // Z of the current pair is parked in global scratch (lane order, 16 bytes per lane and tile)
     uint4* zb = zbuf + ((size_t)h * gridDim.y + k1) * (C::TC * 64) + lane;
+    int ng = C::NG;
+    asm volatile("" : "+s"(ng));       // opaque trip count: one copy of the loop bodies (register pressure)
+    float dsum = 0.f;
 
-    float2 acc[C::NG * 8][4];
+    for (int gi = 0; gi < ng; ++gi) {
+        const int t2_0 = (gi * C::NW + wave) * 8;      // this wave's 8 phase-2 tiles of the group
+        float2 acc[8][4];
 #pragma unroll
-    for (int i = 0; i < C::NG * 8; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = make_float2(0.f, 0.f);
+            for (int j = 0; j < 4; ++j) acc[i][j] = make_float2(0.f, 0.f);
 
-    for (int p = 0; p < npairs; ++p) {
-        asm volatile("" : "+s"(gtab));
-        const bool has_b = (2 * p + 1) < B;
-        const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
-        const size_t coff = ((size_t)h * npairs + p) * Ltot + (size_t)k1 * C::L;
-#pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
+        for (int p = 0; p < npairs; ++p) {
             asm volatile("" : "+s"(gtab));
-            const T* src = pass == 0 ? u : dy;
-            const __half2* csrc = pass == 0 ? ws_u : ws_dy;
+            const bool has_b = (2 * p + 1) < B;
+            const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
+            const size_t coff = ((size_t)h * npairs + p) * Ltot + (size_t)k1 * C::L;
+            uint32_t z[8][4];
 #pragma unroll
-            for (int gi = 0; gi < C::NG; ++gi) {
-                phase1<LG, IO, CPLX>(src + oa, src + ob, has_b, csrc + coff, xb, gtab, t1f, K,
-                                     (gi * C::NW + wave) * 8, lane);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            __syncthreads();
-#pragma unroll
-            for (int gi = 0; gi < C::NG; ++gi)
+            for (int pass = 0; pass < 2; ++pass) {     // 0: u pair -> Z, 1: dy pair -> W
+                asm volatile("" : "+s"(gtab));
+                const T* src = pass == 0 ? u : dy;
+                const __half2* csrc = pass == 0 ? ws_u : ws_dy;
+#pragma unroll 1
+                for (int g2 = 0; g2 < ng; ++g2) {
+                    phase1<LG, IO, CPLX, NB>(src + oa, src + ob, has_b, csrc + coff, xb, gtab, t1f, K,
+                                             (g2 * C::NW + wave) * 8, lane);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                __syncthreads();
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const int t2 = (gi * C::NW + wave) * 8 + i;
                     f4 zr, zi;
-                    phase2_fwd<LG>(xb, phase2_base<LG>(t2, lane), K, zr, zi);
+                    phase2_fwd<LG>(xb, phase2_base<LG>(t2_0 + i, lane), K, zr, zi);
                     if (pass == 0) {
-                        zb[(size_t)t2 * 64] = make_uint4(pack_h2(zr[0], zi[0]), pack_h2(zr[1], zi[1]),
-                                                         pack_h2(zr[2], zi[2]), pack_h2(zr[3], zi[3]));
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) z[i][j] = pack_h2(zr[j], zi[j]);
                     } else {
-                        H8U z;
-                        z.u = zb[(size_t)t2 * 64];
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            const float a = (float)z.c[j][0], b = (float)z.c[j][1];
-                            acc[gi * 8 + i][j].x += a * zr[j] + b * zi[j];
-                            acc[gi * 8 + i][j].y += a * zi[j] - b * zr[j];
+                            union { uint32_t u; h2 hh; } cv;
+                            cv.u = z[i][j];
+                            const float a = (float)cv.hh[0], b = (float)cv.hh[1];
+                            acc[i][j].x += a * zr[j] + b * zi[j];      // conj(Z) * W
+                            acc[i][j].y += a * zi[j] - b * zr[j];
                         }
                     }
                     if (i & 1) __builtin_amdgcn_sched_barrier(0);
                 }
-            __syncthreads();
+                __syncthreads();
+            }
+        }
+
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dsum += acc[i][j].x;
+        if (dk) {
+            // inverse half of phase 2: the last group goes to the exchange buffer, earlier ones are parked
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                H8U m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(acc[i][j].x, acc[i][j].y);
+                if (gi + 1 < ng) {
+                    H8U v;
+                    phase2_inv_regs<LG>(K, m, v);
+                    zb[(size_t)(t2_0 + i) * 64] = v.u;
+                } else {
+                    phase2_inv<LG>(xb, phase2_base<LG>(t2_0 + i, lane), K, m);
+                }
+            }
         }
     }
 
     if (dD || dD_part) {
-        float dsum = 0.f;
-#pragma unroll
-        for (int i = 0; i < C::NG * 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) dsum += acc[i][j].x;
         for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
         if (lane == 0) red[wave] = dsum;
         __syncthreads();
@@ -532,37 +572,47 @@ coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __re
     }
     if (!dk) return;
 
+    // parked groups back into the exchange buffer (each lane reads what it wrote itself)
+    for (int gi = 0; gi + 1 < ng; ++gi)
 #pragma unroll
-    for (int gi = 0; gi < C::NG; ++gi)
+        for (int i = 0; i < 8; ++i) {
+            const int t2 = (gi * C::NW + wave) * 8 + i;
+            H8U v;
+            v.u = zb[(size_t)t2 * 64];
+            const int base = phase2_base<LG>(t2, lane);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        H8U m;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(acc[gi * 8 + i][j].x, acc[gi * 8 + i][j].y);
-        phase2_inv<LG>(xb, phase2_base<LG>((gi * C::NW + wave) * 8 + i, lane), K, m);
-    }
+            for (int j = 0; j < 4; ++j) xb[base + j * C::TE * 4] = v.w[j];
+        }
     __syncthreads();
     __half2* achunk = ws_A + (size_t)h * Ltot + (size_t)k1 * C::L;
-#pragma unroll
-    for (int gi = 0; gi < C::NG; ++gi)
-#pragma unroll
-    for (int tb = 0; tb < 8; tb += 2) {
+#pragma unroll 1
+    for (int gi = 0; gi < ng; ++gi) {
         const int t0 = (gi * C::NW + wave) * 8;
-        f4 r[2], s[2];
-        phase3_two<LG>(xb, gtab, t1i, K, t0 + tb, lane, r, s);
+        // 8 tiles = 8 consecutive samples per (lane, j): stored as 32-byte runs
+        uint32_t oc[4][8];     // CPLX: fp16 complex words ; otherwise the bits of the scaled real parts
 #pragma unroll
-        for (int k = 0; k < 2; ++k)
+        for (int tb = 0; tb < 8; tb += 2) {
+            f4 r[2], s[2];
+            phase3_two<LG>(xb, gtab, t1i, K, t0 + tb, lane, r, s);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int n = (4 * g + j) * 16 * C::TC + c * C::TC + t0 + tb + k;
-                if (CPLX) {
-                    union { uint32_t u; __half2 hh; } cv;
-                    cv.u = pack_h2(r[k][j], s[k][j]);
-                    achunk[n] = cv.hh;
-                } else if (g < 2) {
-                    dk[(size_t)h * N + n] = r[k][j] * dkscale;
-                }
+            for (int k = 0; k < 2; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    oc[j][tb + k] = CPLX ? pack_h2(r[k][j], s[k][j]) : __float_as_uint(r[k][j] * dkscale);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
+            if (CPLX) {
+                uint4* dst = reinterpret_cast<uint4*>(achunk + n0);
+                dst[0] = make_uint4(oc[j][0], oc[j][1], oc[j][2], oc[j][3]);
+                dst[1] = make_uint4(oc[j][4], oc[j][5], oc[j][6], oc[j][7]);
+            } else if (g < 2) {
+                uint4* dst = reinterpret_cast<uint4*>(dk + (size_t)h * N + n0);
+                dst[0] = make_uint4(oc[j][0], oc[j][1], oc[j][2], oc[j][3]);
+                dst[1] = make_uint4(oc[j][4], oc[j][5], oc[j][6], oc[j][7]);
             }
+        }
     }
 }
 
