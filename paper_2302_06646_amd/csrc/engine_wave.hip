@@ -480,10 +480,21 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
     }
     uint32_t* xall = lds + C::TAB_U4 * 4;                 // NWV exchange buffers, reused for the reduction
     uint32_t* xb = xall + wave * C::PAIR_WORDS;
-    float2* red = reinterpret_cast<float2*>(xall);        // slot s: red[(s*TC*4 + i)*64 + lane]
+    float2* red = reinterpret_cast<float2*>(xall);        // partial sums of A, reusing the exchange buffers
+    __shared__ float dred[NWV];
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
 
+    static_assert(C::TG == C::TC, "one tile group per pair");
+    static_assert(C::TC <= NWV, "one tile per wave in the epilogue");
+    constexpr int TR = C::TC >= 2 ? C::TC / 2 : 1;      // tiles per reduction round (the LDS area holds NWV x TR)
+    auto rows_of = [&](int h, int p, Rows<1>& R) {
+        const int64_t b0 = 2 * (int64_t)p;
+        R.row_a[0] = true;
+        R.row_b[0] = b0 + 1 < B;
+        R.oa[0] = row_off(b0, h, H, N);
+        R.ob[0] = row_off(R.row_b[0] ? b0 + 1 : b0, h, H, N);
+    };
     for (int h = blockIdx.x; h < H; h += gridDim.x) {
         float2 acc[C::TC][4];
 #pragma unroll
@@ -533,75 +544,71 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
             }
         }
 
-        // ---- sum the waves' partial A in a fixed tree through LDS
-        __syncthreads();
+        // ---- sum the waves' partial A through LDS, tile t to wave t, in wave order (bitwise repeatable);
+        //      two rounds of TR tiles (the area holds NWV x TR tiles of fp32 pairs)
+        float2 tot[4];
 #pragma unroll
-        for (int active = NWV; active > 1; active >>= 1) {
-            const int half = active >> 1;
-            if (wave >= half && wave < active) {
-                float2* dst = red + (size_t)(wave - half) * C::TC * 4 * 64;
+        for (int j = 0; j < 4; ++j) tot[j] = make_float2(0.f, 0.f);
 #pragma unroll
-                for (int t = 0; t < C::TC; ++t)
+        for (int r0 = 0; r0 < C::TC; r0 += TR) {
+            __syncthreads();      // exchange buffers (first round) or the previous round's sums are done with
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) dst[(t * 4 + j) * 64 + lane] = acc[t][j];
-            }
+            for (int tt = 0; tt < TR; ++tt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) red[((size_t)(wave * TR + tt) * 4 + j) * 64 + lane] = acc[r0 + tt][j];
             __syncthreads();
-            if (wave < half) {
-                const float2* srcp = red + (size_t)wave * C::TC * 4 * 64;
+            if (wave >= r0 && wave < r0 + TR) {
 #pragma unroll
-                for (int t = 0; t < C::TC; ++t)
+                for (int w = 0; w < NWV; ++w)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const float2 v = srcp[(t * 4 + j) * 64 + lane];
-                        acc[t][j].x += v.x; acc[t][j].y += v.y;
+                        const float2 v = red[((size_t)(w * TR + (wave - r0)) * 4 + j) * 64 + lane];
+                        tot[j].x += v.x; tot[j].y += v.y;
                     }
-            }
-            __syncthreads();
-        }
-        // ---- wave 0: dD, then inverse of phase 2 into exchange buffer 0
-        if (wave == 0) {
-            if (dD) {
-                float dsum = 0.f;
-#pragma unroll
-                for (int t = 0; t < C::TC; ++t)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) dsum += acc[t][j].x;
-                for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
-                if (lane == 0) dD[h] = dsum * dDscale;
-            }
-            if (dk) {
-#pragma unroll
-                for (int t2 = 0; t2 < C::TC; ++t2) {
-                    H8U m;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(acc[t2][j].x, acc[t2][j].y);
-                    const f4 zr = MFMA(IL.re, m.v, zero), zi = MFMA(IL.im, m.v, zero);
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) xall[phase2_addr<LG>(t2, j, lane)] = pack_h2(zr[j], zi[j]);
-                }
             }
         }
         __syncthreads();
-        // ---- phase 3 shared by the waves: tile t -> real part -> dk
-        if (dk) {
-            for (int t = wave; t < C::TC; t += NWV) {
-                H8U w0, gr, gi, x;
-                w0.u = tab[C::T0I + t * 64 + lane];
-                gr.u = tab[C::GI + (t * 2 + 0) * 64 + lane];
-                gi.u = tab[C::GI + (t * 2 + 1) * 64 + lane];
-                x.u = *reinterpret_cast<const uint4*>(&xall[w1 + 4 * t]);
-                const f4 yr = MFMA(x.v, gr.v, zero), yi = MFMA(x.v, gi.v, zero);
-                H8U uu;
+        // ---- wave t < TC: dD share, inverse of phase 2 on tile t into exchange buffer 0
+        if (wave < C::TC) {
+            float dsum = tot[0].x + tot[1].x + tot[2].x + tot[3].x;
+            for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+            if (lane == 0) dred[wave] = dsum;
+            if (dk) {
+                H8U m;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) uu.w[j] = cmul_pack(yr[j], yi[j], w0.c[j]);
-                const f4 r = MFMA(I16.re, uu.v, zero);
-                if (g < 2) {
+                for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(tot[j].x, tot[j].y);
+                const f4 zr = MFMA(IL.re, m.v, zero), zi = MFMA(IL.im, m.v, zero);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        dk[(size_t)h * N + (4 * g + j) * 16 * C::TC + c * C::TC + t] = r[j] * dkscale;
-                }
+                for (int j = 0; j < 4; ++j) xall[phase2_addr<LG>(wave, j, lane)] = pack_h2(zr[j], zi[j]);
             }
         }
+        __syncthreads();
+        if (tid == 0 && dD) {
+            float t = 0.f;
+            for (int w = 0; w < C::TC; ++w) t += dred[w];
+            dD[h] = t * dDscale;
+        }
+        // ---- phase 3: tile t by wave t -> real part -> dk
+        if (dk && wave < C::TC) {
+            const int t = wave;
+            H8U w0, gr, gi, x;
+            w0.u = tab[C::T0I + t * 64 + lane];
+            gr.u = tab[C::GI + (t * 2 + 0) * 64 + lane];
+            gi.u = tab[C::GI + (t * 2 + 1) * 64 + lane];
+            x.u = *reinterpret_cast<const uint4*>(&xall[w1 + 4 * t]);
+            const f4 yr = MFMA(x.v, gr.v, zero), yi = MFMA(x.v, gi.v, zero);
+            H8U uu;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) uu.w[j] = cmul_pack(yr[j], yi[j], w0.c[j]);
+            const f4 r = MFMA(I16.re, uu.v, zero);
+            if (g < 2) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    dk[(size_t)h * N + (4 * g + j) * 16 * C::TC + c * C::TC + t] = r[j] * dkscale;
+            }
+        }
+        // (the next head's first barrier comes after its pair loop, which only touches per-wave buffers
+        //  other than buffer 0; wave 0 waits for the readers of buffer 0 here)
         __syncthreads();
     }
 }
@@ -719,7 +726,7 @@ hipError_t wkspec_go(const float* k, const float* D, float2* kspec, int64_t H, i
                      const Plan& pl, const Tables& tb, hipStream_t st)
 {
     using C = WC<LG>;
-    constexpr int NWV = LG == 12 ? 3 : 8;
+    constexpr int NWV = 3;      // waves (heads) per workgroup: small, so that H heads spread over all CUs
     const size_t lds = (size_t)C::TAB_U4 * 16 + (size_t)NWV * C::PAIR_WORDS * 4;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wkspec_kernel<LG, NWV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
