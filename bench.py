@@ -8,7 +8,10 @@ step would run it (the kernel changes every step, so its spectrum is recomputed)
 
 Inputs are resident in HBM before the timed region.  Each step uses the next of several
 distinct buffer sets (more than the 256 MB last-level cache in total) so that reads come from
-HBM rather than from cache.  Prints ONE JSON line (see README for the fields).
+HBM rather than from cache.  The timed region is exactly K steps between two events on the launch
+stream; the per-call durations (`segments_ms`, `roofline`) come from a second run of the same K
+steps with an event between the four calls (each event costs a few microseconds of GPU time, so
+it stays out of the timed region).  Prints ONE JSON line (see README for the fields).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4a|...] [--no-cpu]
 """
@@ -29,12 +32,19 @@ import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 CACHE_BYTES = 256 << 20        # last-level (Infinity) cache
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy kernel
-# of known size: FETCH_SIZE x 2.0 KiB, WRITE_SIZE x 1.0 KiB); see profiles/.  Workload 2 only.
-MEASURED_TRAFFIC = {"cfg2_B16_H768_N1024_bf16": {"fwd": (20644.9 * 2.0 + 29184.0) * 1024,
-                                                  "bwd_du": (20644.9 * 2.0 + 29184.0) * 1024,
-                                                  "bwd_dk_dD": (25174.5 * 2.0 + 4120.0) * 1024}}
-
+# HBM bytes per launch group measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy kernel
+# of known size: FETCH_SIZE x 2.0 KiB, WRITE_SIZE x 1.0 KiB), summed over the kernels of the group; see
+# profiles/.
+KIB = 1024
+MEASURED_TRAFFIC = {
+    "cfg2_B16_H768_N1024_bf16": {"fwd": (20800.8 * 2 + 29184.0) * KIB, "bwd_du": (20800.8 * 2 + 29184.0) * KIB,
+                                 "bwd_dk_dD": (24903.5 * 2 + 3096.0) * KIB},
+    "cfg3_B8_H256_N16384_fp16": {"fwd": (102687.2 * 2 + 65536.4) * KIB, "bwd_du": (102687.2 * 2 + 65536.4) * KIB,
+                                 "bwd_dk_dD": (146513.2 * 2 + 38408.3) * KIB},
+    "cfg4_B1_H128_N65536_fp16": {"fwd": ((9572.2 + 100636.5 + 34152.8) * 2 + 65536.0 + 65536.7 + 16384.0) * KIB,
+                                 "bwd_du": ((9572.2 + 100636.5 + 34152.8) * 2 + 65536.0 + 65536.7 + 16384.0) * KIB,
+                                 "bwd_dk_dD": ((17770.4 + 165076.6 + 34148.5) * 2 + 131072.0 + 136645.2 + 32768.0) * KIB},
+}
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
