@@ -32,8 +32,13 @@
  *   - Return value: LONGCONV_OK or an error code; argument validation happens
  *     before anything is launched.  No exceptions, no aborts.
  *   - fp16/bf16 I/O computes with fp16 matrix-core operands and fp32 accumulation;
- *     |values| of u, dy and of the transformed data must stay inside fp16 range
- *     (unit-variance activations up to N = 131072 are).  fp32 I/O computes in fp32.
+ *     the data are not rescaled on the way, so u, dy and the transformed data must
+ *     stay inside fp16's normal range: activations and gradients of order one
+ *     (unit variance up to N = 131072 is fine) and |FFT(k) + D| within about
+ *     2^-8 .. 2^8.  Far outside that range precision is lost silently (bf16
+ *     gradients of order 1e-5, say, should be scaled up by the caller and dk, du
+ *     scaled back).  The kernel k itself may have any magnitude: its spectrum is
+ *     computed from a per-head power-of-two rescaling.  fp32 I/O computes in fp32.
  */
 #ifndef LONGCONV_H
 #define LONGCONV_H

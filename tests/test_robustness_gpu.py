@@ -1,0 +1,131 @@
+"""Further GPU cases through the C-ABI binding: every length with both half dtypes and an odd batch,
+kernels of extreme magnitude, launches on a side stream and under HIP graph capture."""
+from __future__ import annotations
+
+import dataclasses
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu_and_clean_env(monkeypatch):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL"):
+        monkeypatch.delenv(v, raising=False)
+    yield
+
+
+def _w(key, **kw):
+    return dataclasses.replace(wl.WORKLOADS[key], **kw)
+
+
+@pytest.mark.parametrize("io", [wl.F16, wl.BF16])
+@pytest.mark.parametrize("N", [256, 512, 1024, 2048, 4096, 8192, 16384])
+def test_every_single_pass_length_half_io_odd_batch(N, io):
+    # one case per kernel family and tile count; B = 3 leaves the last row pair half empty
+    from gpu_harness import check_full
+    check_full(wl.generate(_w("2", N=N, dtype=io), B=3, H=2), label=f"N={N} io={wl.DTYPE_NAMES[io]}")
+
+
+@pytest.mark.parametrize("io", [wl.F16, wl.BF16])
+def test_longest_sequence_half_io(io):
+    from gpu_harness import check_full
+    check_full(wl.generate(_w("4b", dtype=io), B=2, H=1), label=f"N=131072 io={wl.DTYPE_NAMES[io]}")
+
+
+@pytest.mark.parametrize("key,B,H", [("2", 4, 4), ("3", 2, 4), ("4a", 2, 4)])
+def test_kernel_magnitudes_per_head(key, B, H):
+    """Heads of different magnitude in one call, checked head by head (a whole-tensor norm would hide a
+    small head behind a large one), and an all-zero head with D = 0, which must give exact zeros.  The
+    range is what the fp16 intermediates of the matrix-core engine carry without rescaling the data:
+    |FFT(k) + D| within about 2^-8 .. 2^8 for inputs of order one."""
+    from gpu_harness import GpuRun, TOL
+    import oracle
+    inp = wl.generate(wl.WORKLOADS[key], B=B, H=H)
+    scale = np.array([1.0 / 64, 1.0, 64.0, 0.0], dtype=np.float32)[:H]
+    k = (inp.k * scale[:, None]).astype(np.float32)
+    D = (inp.D * scale).astype(np.float32)
+    inp = dataclasses.replace(inp, k=k, D=D)
+    g = GpuRun(inp)
+    y = g.fwd()
+    du, dk, dD = g.bwd()
+    k64, D64 = k.astype(np.float64), D.astype(np.float64)
+    ry = oracle.longconv_fwd(inp.u, k64, D64)
+    rdu, rdk, rdD = oracle.longconv_bwd(inp.dy, inp.u, k64, D64)
+    tol = TOL[inp.w.dtype]
+    for h in range(H):
+        if scale[h] == 0.0:
+            assert np.all(y[:, h] == 0.0) and np.all(du[:, h] == 0.0)
+        else:
+            ey, edu = wl.rel_l2(y[:, h], ry[:, h]), wl.rel_l2(du[:, h], rdu[:, h])
+            print(f"[magnitude] {inp.w.name} head {h} scale {scale[h]:g}: y={ey:.2e} du={edu:.2e}", flush=True)
+            assert ey <= tol and edu <= tol
+        assert wl.rel_l2(dk[h], rdk[h]) <= tol       # dk does not depend on k: same accuracy for every head
+    assert wl.rel_l2(dD, rdD) <= tol                 # (a single head's dD is a sum with heavy cancellation)
+
+
+def test_side_stream_matches_default_stream():
+    import paper_2302_06646_amd as lc
+    from gpu_harness import GpuRun
+    g = GpuRun(wl.generate(wl.WORKLOADS["2"], B=4, H=4))
+    y0 = g.fwd().copy()
+    du0, dk0, dD0 = [a.copy() for a in g.bwd()]
+    for t in (g.y, g.du, g.dk, g.dD):
+        t.zero_()
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):                      # the binding picks up torch's current stream
+        lc.longconv_fwd(g.u, g.k, g.D, g.y, g.ws)
+    lc.longconv_bwd(g.dy, g.u, g.k, g.D, g.du, g.dk, g.dD, g.ws, stream=st)      # and takes an explicit one
+    st.synchronize()
+    from gpu_harness import to_f64
+    assert np.array_equal(to_f64(g.y, g.io), y0)
+    assert np.array_equal(to_f64(g.du, g.io), du0)
+    assert np.array_equal(g.dk.cpu().numpy().astype(np.float64), dk0)
+    assert np.array_equal(g.dD.cpu().numpy().astype(np.float64), dD0)
+
+
+@pytest.mark.parametrize("key,B,H", [("2", 4, 8), ("3", 2, 2), ("4a", 1, 2)])
+def test_step_under_graph_capture_replays_bitwise(key, B, H):
+    """The library allocates nothing and never synchronises, so a whole step (spectrum, forward, both
+    backward calls) can be captured into a HIP graph.  Every replay, with eager work and
+    synchronisations between replays, must reproduce the eager results bit for bit."""
+    import paper_2302_06646_amd as lc
+    from gpu_harness import GpuRun
+    g = GpuRun(wl.generate(wl.WORKLOADS[key], B=B, H=H))
+    ks = lc.new_kspec(g.H, g.N, g.io)
+
+    def step():
+        lc.longconv_kspec_compute(g.k, g.D, ks, g.io, g.ws)
+        lc.longconv_fwd(g.u, g.k, g.D, g.y, g.ws, kspec=ks)
+        lc.longconv_bwd(g.dy, g.u, g.k, g.D, None, g.dk, g.dD, g.ws, kspec=ks)
+        lc.longconv_bwd(g.dy, g.u, g.k, g.D, g.du, None, None, g.ws, kspec=ks)
+
+    outs = (g.y, g.du, g.dk, g.dD)
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs]
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        step()                                      # warm-up on the capture stream (tables, attributes)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=st):
+            step()
+    torch.cuda.synchronize()
+    for r in range(3):
+        for t in outs:
+            t.fill_(float("nan"))                   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, want in zip(outs, ref):
+            assert torch.equal(t.view(torch.uint8), want.view(torch.uint8)), f"replay {r} differs"
