@@ -648,93 +648,197 @@ hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, const Pro
 }
 
 // -------------------------------------------------------------------------------------
-// Kernel spectrum on the matrix cores (Algorithm 2 lines 1-2) for the wave kernels' lane order.
-// One wave per head: k[h,:] * r (r = power of two bringing max|k[h,:]| to about 1, so the fp16
-// operands keep their relative precision whatever the head's magnitude) is transformed as the real row of a pair whose other
-// row is zero; phases 1 and the forward half of phase 2 are those of the convolution kernel.
-// Stored value = kscale * (FFT([k,0]) + D[h]).
+// Helpers of the spectrum kernel: a wave owns TPW of the head's TC tiles and keeps the twiddles
+// and matrices of exactly those tiles in registers (no constant table in LDS, nothing to copy
+// at workgroup start); NWP = TC / TPW waves share one head.
 // -------------------------------------------------------------------------------------
-template <int LG, int NWV>
-__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
-wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, float2* __restrict__ kspec, int64_t H, int64_t N, float kscale_over_c, float kscale,
-              const unsigned char* __restrict__ wtab)
+template <int LG, int TPW>
+struct WK {     // constants of tiles t0 .. t0+TPW-1 and the plain matrices
+    Mats F16, I16, FL, IL;
+    H8U t0f[TPW], t0i[TPW], gfr[TPW], gfi[TPW], gir[TPW], gii[TPW];
+};
+
+template <int LG, int TPW>
+__device__ __forceinline__ void load_consts(WK<LG, TPW>& K, const unsigned char* __restrict__ wtab, int t0, int lane)
 {
     using C = WC<LG>;
-    extern __shared__ uint4 lds4[];
-    uint32_t* lds = reinterpret_cast<uint32_t*>(lds4);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = lane & 15, g = lane >> 4;
-    {
-        const uint4* gt = reinterpret_cast<const uint4*>(wtab + wave_tab_offset(LG));
-        for (int i = tid; i < C::TAB_U4; i += NWV * 64) lds4[i] = gt[i];
-    }
-    __syncthreads();
-    const uint4* tab = lds4;
-    Mats F16, FL;
-    {
-        H8U m;
-        m.u = tab[C::PM + 0 * 64 + lane]; F16.re = m.v;
-        m.u = tab[C::PM + 1 * 64 + lane]; F16.im = m.v;
-        m.u = tab[C::PM + 4 * 64 + lane]; FL.re = m.v;
-        m.u = tab[C::PM + 5 * 64 + lane]; FL.im = m.v;
-    }
-    uint32_t* xb = lds + C::TAB_U4 * 4 + wave * C::PAIR_WORDS;
-    const f4 zero = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t h = (int64_t)blockIdx.x * NWV + wave; h < H; h += (int64_t)gridDim.x * NWV) {
-        const float* kr = k + (size_t)h * N;
-        // max |k[h,:]| over the wave (the row is read again below, from cache)
-        float m = 0.f;
-        for (int n = lane * 4; n < N; n += 256) {
-            const float4 v = *reinterpret_cast<const float4*>(kr + n);
-            m = fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
-        }
-        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-        const float r = head_scale_of(m);
+    const uint4* gt = reinterpret_cast<const uint4*>(wtab + wave_tab_offset(LG));
+    H8U m;
+    m.u = gt[C::PM + 0 * 64 + lane]; K.F16.re = m.v;
+    m.u = gt[C::PM + 1 * 64 + lane]; K.F16.im = m.v;
+    m.u = gt[C::PM + 2 * 64 + lane]; K.I16.re = m.v;
+    m.u = gt[C::PM + 3 * 64 + lane]; K.I16.im = m.v;
+    m.u = gt[C::PM + 4 * 64 + lane]; K.FL.re = m.v;
+    m.u = gt[C::PM + 5 * 64 + lane]; K.FL.im = m.v;
+    m.u = gt[C::PM + 6 * 64 + lane]; K.IL.re = m.v;
+    m.u = gt[C::PM + 7 * 64 + lane]; K.IL.im = m.v;
 #pragma unroll
-        for (int tg = 0; tg < C::TC; tg += C::TG) {
-            InRegs<LG, 1> inr;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + tg;
-#pragma unroll
-                for (int i = 0; i < C::NWD; ++i) {
-                    inr.wb[0][j][i] = 0u;
-                    inr.wa[0][j][i] = 0u;
-                    if (g < 2) inr.wa[0][j][i] = pack_h2(kr[n0 + 2 * i] * r, kr[n0 + 2 * i + 1] * r);
-                }
-            }
-            phase1_group<LG, IoF16, 1>(inr, tg, xb, tab, F16, lane);
-        }
-        wave_lds_fence();
-        const float alpha = kscale_over_c / r, beta = D[h] * kscale;
-        float4* out = reinterpret_cast<float4*>(kspec + (size_t)h * C::L);
-#pragma unroll
-        for (int t2 = 0; t2 < C::TC; ++t2) {
-            H8U x;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) x.w[j] = xb[phase2_addr<LG>(t2, j, lane)];
-            const f4 yr = MFMA(FL.re, x.v, zero), yi = MFMA(FL.im, x.v, zero);
-            out[(t2 * 64 + lane) * 2] = make_float4(yr[0] * alpha + beta, yi[0] * alpha, yr[1] * alpha + beta, yi[1] * alpha);
-            out[(t2 * 64 + lane) * 2 + 1] = make_float4(yr[2] * alpha + beta, yi[2] * alpha, yr[3] * alpha + beta, yi[3] * alpha);
-        }
-        wave_lds_fence();
+    for (int k = 0; k < TPW; ++k) {
+        const int t = t0 + k;
+        K.t0f[k].u = gt[C::T0F + t * 64 + lane];
+        K.t0i[k].u = gt[C::T0I + t * 64 + lane];
+        K.gfr[k].u = gt[C::GF + (t * 2 + 0) * 64 + lane];
+        K.gfi[k].u = gt[C::GF + (t * 2 + 1) * 64 + lane];
+        K.gir[k].u = gt[C::GI + (t * 2 + 0) * 64 + lane];
+        K.gii[k].u = gt[C::GI + (t * 2 + 1) * 64 + lane];
     }
 }
 
-template <int LG>
-hipError_t wkspec_go(const float* k, const float* D, float2* kspec, int64_t H, int64_t N,
-                     const Plan& pl, const Tables& tb, hipStream_t st)
+// waves sharing a pair meet at a workgroup barrier; a lone wave only needs its own LDS order
+template <int NWP>
+__device__ __forceinline__ void pair_sync()
+{
+    if constexpr (NWP == 1) wave_lds_fence();
+    else __syncthreads();
+}
+
+// Raw input words of a wave's TPW tiles: per register j the TPW consecutive samples n0 .. n0+TPW-1
+// of row a and of row b (I/O dtype, two per word), n0 = (4g+j)*16*TC + c*TC + t0.
+template <int TPW>
+struct In {
+    uint32_t wa[4][TPW / 2], wb[4][TPW / 2];
+};
+
+
+// Phase 1 on the wave's TPW tiles, advanced together stage by stage: [A-role F16 over d_a],
+// w_L twiddle, [B-role per-tile matrix over d_b] -> exchange buffer (one 16-byte write per tile).
+template <int LG, class IO, int TPW>
+__device__ __forceinline__ void w_phase1(In<TPW>& r, uint32_t* xb, const WK<LG, TPW>& K, int t0, int lane)
 {
     using C = WC<LG>;
-    constexpr int NWV = 3;      // waves (heads) per workgroup: small, so that H heads spread over all CUs
-    const size_t lds = (size_t)C::TAB_U4 * 16 + (size_t)NWV * C::PAIR_WORDS * 4;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wkspec_kernel<LG, NWV>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    long nblk = (H + NWV - 1) / NWV;
-    if (nblk > 512) nblk = 512;
+    const int c = lane & 15, g = lane >> 4;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+    if (IsBf<IO>::v) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < TPW / 2; ++i) {
+                r.wa[j][i] = bf2_to_h2(r.wa[j][i]);
+                r.wb[j][i] = bf2_to_h2(r.wb[j][i]);
+            }
+    }
+    f4 yr[TPW], yi[TPW], zr[TPW], zi[TPW];
+#pragma unroll
+    for (int k = 0; k < TPW; ++k) {
+        H8U x;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            x.w[j] = (k & 1) ? __builtin_amdgcn_perm(r.wb[j][k >> 1], r.wa[j][k >> 1], 0x07060302u)
+                             : __builtin_amdgcn_perm(r.wb[j][k >> 1], r.wa[j][k >> 1], 0x05040100u);
+        yr[k] = MFMA(x.v, K.F16.re, zero);   // A-role over d_a
+        yi[k] = MFMA(x.v, K.F16.im, zero);
+    }
+#pragma unroll
+    for (int k = 0; k < TPW; ++k) {
+        H8U u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][j], yi[k][j], K.t0f[k].c[j]);
+        zr[k] = MFMA(K.gfr[k].v, u.v, zero);   // B-role over d_b
+        zi[k] = MFMA(K.gfi[k].v, u.v, zero);
+    }
+#pragma unroll
+    for (int k = 0; k < TPW; ++k) {
+        uint4 o;
+        o.x = pack_h2(zr[k][0], zi[k][0]); o.y = pack_h2(zr[k][1], zi[k][1]);
+        o.z = pack_h2(zr[k][2], zi[k][2]); o.w = pack_h2(zr[k][3], zi[k][3]);
+        *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + k)]) = o;
+    }
+}
+
+
+// forward half of phase 2 on the wave's TPW tiles: gather, [F_TC over d_c]
+template <int LG, int TPW>
+__device__ __forceinline__ void w_phase2_fwd(const uint32_t* xb, const WK<LG, TPW>& K, const int (&ad)[TPW][4],
+                                             f4 (&yr)[TPW], f4 (&yi)[TPW])
+{
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < TPW; ++k) {
+        H8U x;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x.w[j] = xb[ad[k][j]];
+        yr[k] = MFMA(K.FL.re, x.v, zero);
+        yi[k] = MFMA(K.FL.im, x.v, zero);
+    }
+}
+
+
+// -------------------------------------------------------------------------------------
+// Kernel spectrum on the matrix cores (Algorithm 2 lines 1-2) for the wave kernels' lane order.
+// One workgroup (NWP waves) per head.  The row is scaled by a power of two r that brings
+// max|k[h,:]| to about 1, so the fp16 operands keep their relative precision whatever the head's
+// magnitude, and transformed as the real row of a pair whose other row is zero: phase 1 and the
+// forward half of phase 2 of the convolution kernel.  Stored value = kscale * (FFT([k,0]) + D[h]).
+// -------------------------------------------------------------------------------------
+template <int LG, int TPW>
+__global__ void __launch_bounds__((WC<LG>::TC / TPW) * 64) __attribute__((amdgpu_waves_per_eu(2)))
+wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, float2* __restrict__ kspec, int64_t N,
+              float kscale_over_c, float kscale, const unsigned char* __restrict__ wtab)
+{
+    using C = WC<LG>;
+    constexpr int NWP = C::TC / TPW;
+    __shared__ uint32_t xb[C::PAIR_WORDS];
+    __shared__ float wmax[NWP];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, t0 = wave * TPW;
+    const int c = lane & 15, g = lane >> 4;
+    const int h = blockIdx.x;
+    const float* kr = k + (size_t)h * N;
+    // this wave's samples (fp32), and the head's max |k| over all waves
+    float v[4][TPW];
+    float m = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            v[j][i] = 0.f;
+            if (g < 2) v[j][i] = kr[(4 * g + j) * 16 * C::TC + c * C::TC + t0 + i];
+            m = fmaxf(m, fabsf(v[j][i]));
+        }
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    if (NWP > 1) {
+        if (lane == 0) wmax[wave] = m;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < NWP; ++w) m = fmaxf(m, wmax[w]);
+    }
+    const float r = head_scale_of(m);
+    WK<LG, TPW> K;
+    load_consts<LG, TPW>(K, wtab, t0, lane);
+    In<TPW> inr;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < TPW / 2; ++i) {
+            inr.wa[j][i] = pack_h2(v[j][2 * i] * r, v[j][2 * i + 1] * r);
+            inr.wb[j][i] = 0u;
+        }
+    w_phase1<LG, IoF16, TPW>(inr, xb, K, t0, lane);
+    pair_sync<NWP>();
+    int ad[TPW][4];
+#pragma unroll
+    for (int kk = 0; kk < TPW; ++kk)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ad[kk][j] = phase2_addr<LG>(t0 + kk, j, lane);
+    f4 yr[TPW], yi[TPW];
+    w_phase2_fwd<LG, TPW>(xb, K, ad, yr, yi);
+    const float alpha = kscale_over_c / r, beta = D[h] * kscale;
+    float4* out = reinterpret_cast<float4*>(kspec + (size_t)h * C::L);
+#pragma unroll
+    for (int kk = 0; kk < TPW; ++kk) {
+        const int t2 = t0 + kk;
+        out[(t2 * 64 + lane) * 2] = make_float4(yr[kk][0] * alpha + beta, yi[kk][0] * alpha, yr[kk][1] * alpha + beta, yi[kk][1] * alpha);
+        out[(t2 * 64 + lane) * 2 + 1] = make_float4(yr[kk][2] * alpha + beta, yi[kk][2] * alpha, yr[kk][3] * alpha + beta, yi[kk][3] * alpha);
+    }
+}
+
+template <int LG, int TPW>
+hipError_t wkspec_go(const float* k, const float* D, float2* kspec, int64_t H, int64_t N, const Plan& pl,
+                     const Tables& tb, hipStream_t st)
+{
+    using C = WC<LG>;
     const int shift = 4 + (C::cb == 4 ? 2 : (C::cb >= 2 ? 1 : 0));
-    hipLaunchKernelGGL((wkspec_kernel<LG, NWV>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st, k, D, kspec, H, N,
+    hipLaunchKernelGGL((wkspec_kernel<LG, TPW>), dim3((unsigned)H), dim3((C::TC / TPW) * 64), 0, st, k, D, kspec, N,
                        pl.kscale * (float)(1 << shift), pl.kscale, (const unsigned char*)tb.wtab);
     return hipGetLastError();
 }
@@ -790,10 +894,10 @@ hipError_t wave_kspec(const float* k, const float* D, float2* kspec, int64_t H, 
                       const Plan& pl, const Tables& tb, hipStream_t st)
 {
     switch (pl.log2L2) {
-        case 9: return wkspec_go<9>(k, D, kspec, H, N, pl, tb, st);
-        case 10: return wkspec_go<10>(k, D, kspec, H, N, pl, tb, st);
-        case 11: return wkspec_go<11>(k, D, kspec, H, N, pl, tb, st);
-        case 12: return wkspec_go<12>(k, D, kspec, H, N, pl, tb, st);
+        case 9: return wkspec_go<9, 2>(k, D, kspec, H, N, pl, tb, st);
+        case 10: return wkspec_go<10, 4>(k, D, kspec, H, N, pl, tb, st);
+        case 11: return wkspec_go<11, 4>(k, D, kspec, H, N, pl, tb, st);
+        case 12: return wkspec_go<12, 4>(k, D, kspec, H, N, pl, tb, st);
         default: return hipErrorInvalidValue;
     }
 }
