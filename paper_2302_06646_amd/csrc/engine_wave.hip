@@ -1,5 +1,6 @@
-// Wave-autonomous fused convolution for 512 <= L = 2N <= 4096: one wavefront owns whole row
-// pairs, the waves of a workgroup only share read-only constant tables held in LDS.
+// Fused kernels for 512 <= L = 2N <= 4096.  Convolution: one wavefront owns whole row pairs, the
+// waves of a workgroup only share read-only constant tables held in LDS.  dk/dD and the kernel
+// spectrum: a few waves share a pair, each with the constants of its own tiles in registers.
 //
 // L = 16 * 16 * TC, TC = 2^cb in {2,4,8,16}.  Time index n = d_a*16*TC + d_b*TC + d_c, frequency
 // f = k_a + 16*k_b + 256*k_c (Section 3.2 "Butterfly Decomposition" applied twice; twiddles as in
@@ -440,217 +441,9 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
 }
 
 // -------------------------------------------------------------------------------------
-// dk and dD for one head per workgroup pass (workgroups loop over heads).  Each wave transforms
-// some of the head's row pairs: Z = transform of the u pair (kept as fp16 in registers), W =
-// transform of the dy pair, A += conj(Z) W in fp32 registers, in the lane order of phase 2.  The
-// waves' partial A are summed through LDS in a fixed binary tree (bitwise repeatable), wave 0
-// runs the inverse of phase 2 on the total, and all waves share phase 3, whose real part is
-// dk (the cross terms between the two rows of a pair are purely imaginary).  dD is the lag-0
-// correlation, sum_f Re(A_f) / L (Parseval), taken from the fp32 total.
-// -------------------------------------------------------------------------------------
-template <int LG, class IO, int NWV>
-__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
-wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u, float* __restrict__ dk,
-           float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs, float dkscale, float dDscale,
-           const unsigned char* __restrict__ wtab)
-{
-    using C = WC<LG>;
-    using T = typename IO::T;
-    extern __shared__ uint4 lds4[];
-    uint32_t* lds = reinterpret_cast<uint32_t*>(lds4);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = lane & 15, g = lane >> 4;
-    {
-        const uint4* gt = reinterpret_cast<const uint4*>(wtab + wave_tab_offset(LG));
-        for (int i = tid; i < C::TAB_U4; i += NWV * 64) lds4[i] = gt[i];
-    }
-    __syncthreads();
-    const uint4* tab = lds4;
-    Mats F16, I16, FL, IL;
-    {
-        H8U m;
-        m.u = tab[C::PM + 0 * 64 + lane]; F16.re = m.v;
-        m.u = tab[C::PM + 1 * 64 + lane]; F16.im = m.v;
-        m.u = tab[C::PM + 2 * 64 + lane]; I16.re = m.v;
-        m.u = tab[C::PM + 3 * 64 + lane]; I16.im = m.v;
-        m.u = tab[C::PM + 4 * 64 + lane]; FL.re = m.v;
-        m.u = tab[C::PM + 5 * 64 + lane]; FL.im = m.v;
-        m.u = tab[C::PM + 6 * 64 + lane]; IL.re = m.v;
-        m.u = tab[C::PM + 7 * 64 + lane]; IL.im = m.v;
-    }
-    uint32_t* xall = lds + C::TAB_U4 * 4;                 // NWV exchange buffers, reused for the reduction
-    uint32_t* xb = xall + wave * C::PAIR_WORDS;
-    float2* red = reinterpret_cast<float2*>(xall);        // partial sums of A, reusing the exchange buffers
-    __shared__ float dred[NWV];
-    const f4 zero = {0.f, 0.f, 0.f, 0.f};
-    const int w1 = (c * C::PITCH + g * C::TC) * 4;
-
-    static_assert(C::TG == C::TC, "one tile group per pair");
-    static_assert(C::TC <= NWV, "one tile per wave in the epilogue");
-    constexpr int TR = C::TC >= 2 ? C::TC / 2 : 1;      // tiles per reduction round (the LDS area holds NWV x TR)
-    auto rows_of = [&](int h, int p, Rows<1>& R) {
-        const int64_t b0 = 2 * (int64_t)p;
-        R.row_a[0] = true;
-        R.row_b[0] = b0 + 1 < B;
-        R.oa[0] = row_off(b0, h, H, N);
-        R.ob[0] = row_off(R.row_b[0] ? b0 + 1 : b0, h, H, N);
-    };
-    for (int h = blockIdx.x; h < H; h += gridDim.x) {
-        float2 acc[C::TC][4];
-#pragma unroll
-        for (int t = 0; t < C::TC; ++t)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[t][j] = make_float2(0.f, 0.f);
-
-        for (int p = wave; p < npairs; p += NWV) {
-            Rows<1> R;
-            const int64_t b0 = 2 * (int64_t)p;
-            R.row_a[0] = true;
-            R.row_b[0] = b0 + 1 < B;
-            R.oa[0] = row_off(b0, h, H, N);
-            R.ob[0] = row_off(R.row_b[0] ? b0 + 1 : b0, h, H, N);
-            uint32_t z[C::TC][4];
-#pragma unroll
-            for (int pass = 0; pass < 2; ++pass) {     // 0: u pair -> Z, 1: dy pair -> W
-                const T* src = pass == 0 ? u : dy;
-                InRegs<LG, 1> inr;
-#pragma unroll
-                for (int tg = 0; tg < C::TC; tg += C::TG) {
-                    load_inputs<LG, IO, 1>(inr, src, R, tg, lane);
-                    phase1_group<LG, IO, 1>(inr, tg, xb, tab, F16, lane);
-                }
-                wave_lds_fence();
-#pragma unroll
-                for (int t2 = 0; t2 < C::TC; ++t2) {
-                    H8U x;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) x.w[j] = xb[phase2_addr<LG>(t2, j, lane)];
-                    const f4 yr = MFMA(FL.re, x.v, zero), yi = MFMA(FL.im, x.v, zero);
-                    if (pass == 0) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) z[t2][j] = pack_h2(yr[j], yi[j]);
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            union { uint32_t u; h2 h; } cv;
-                            cv.u = z[t2][j];
-                            const float zr = (float)cv.h[0], zi = (float)cv.h[1];
-                            acc[t2][j].x += zr * yr[j] + zi * yi[j];      // conj(Z) * W
-                            acc[t2][j].y += zr * yi[j] - zi * yr[j];
-                        }
-                    }
-                }
-                wave_lds_fence();
-            }
-        }
-
-        // ---- sum the waves' partial A through LDS, tile t to wave t, in wave order (bitwise repeatable);
-        //      two rounds of TR tiles (the area holds NWV x TR tiles of fp32 pairs)
-        float2 tot[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) tot[j] = make_float2(0.f, 0.f);
-#pragma unroll
-        for (int r0 = 0; r0 < C::TC; r0 += TR) {
-            __syncthreads();      // exchange buffers (first round) or the previous round's sums are done with
-#pragma unroll
-            for (int tt = 0; tt < TR; ++tt)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) red[((size_t)(wave * TR + tt) * 4 + j) * 64 + lane] = acc[r0 + tt][j];
-            __syncthreads();
-            if (wave >= r0 && wave < r0 + TR) {
-#pragma unroll
-                for (int w = 0; w < NWV; ++w)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float2 v = red[((size_t)(w * TR + (wave - r0)) * 4 + j) * 64 + lane];
-                        tot[j].x += v.x; tot[j].y += v.y;
-                    }
-            }
-        }
-        __syncthreads();
-        // ---- wave t < TC: dD share, inverse of phase 2 on tile t into exchange buffer 0
-        if (wave < C::TC) {
-            float dsum = tot[0].x + tot[1].x + tot[2].x + tot[3].x;
-            for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
-            if (lane == 0) dred[wave] = dsum;
-            if (dk) {
-                H8U m;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(tot[j].x, tot[j].y);
-                const f4 zr = MFMA(IL.re, m.v, zero), zi = MFMA(IL.im, m.v, zero);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) xall[phase2_addr<LG>(wave, j, lane)] = pack_h2(zr[j], zi[j]);
-            }
-        }
-        __syncthreads();
-        if (tid == 0 && dD) {
-            float t = 0.f;
-            for (int w = 0; w < C::TC; ++w) t += dred[w];
-            dD[h] = t * dDscale;
-        }
-        // ---- phase 3: tile t by wave t -> real part -> dk
-        if (dk && wave < C::TC) {
-            const int t = wave;
-            H8U w0, gr, gi, x;
-            w0.u = tab[C::T0I + t * 64 + lane];
-            gr.u = tab[C::GI + (t * 2 + 0) * 64 + lane];
-            gi.u = tab[C::GI + (t * 2 + 1) * 64 + lane];
-            x.u = *reinterpret_cast<const uint4*>(&xall[w1 + 4 * t]);
-            const f4 yr = MFMA(x.v, gr.v, zero), yi = MFMA(x.v, gi.v, zero);
-            H8U uu;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) uu.w[j] = cmul_pack(yr[j], yi[j], w0.c[j]);
-            const f4 r = MFMA(I16.re, uu.v, zero);
-            if (g < 2) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    dk[(size_t)h * N + (4 * g + j) * 16 * C::TC + c * C::TC + t] = r[j] * dkscale;
-            }
-        }
-        // (the next head's first barrier comes after its pair loop, which only touches per-wave buffers
-        //  other than buffer 0; wave 0 waits for the readers of buffer 0 here)
-        __syncthreads();
-    }
-}
-
-template <int LG, class IO, int NWV>
-hipError_t wdk_go(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
-                  const Tables& tb, hipStream_t st)
-{
-    using T = typename IO::T;
-    using C = WC<LG>;
-    const size_t lds = (size_t)C::TAB_U4 * 16 + (size_t)NWV * C::PAIR_WORDS * 4;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wdk_kernel<LG, IO, NWV>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    long fit = (long)(160 * 1024) / (long)lds;
-    fit = fit < 1 ? 1 : (fit > 4 ? 4 : fit);
-    const long nblk = pr.H < 256 * fit ? pr.H : 256 * fit;
-    // forward chains scale by c = 2^-shift each: A carries c^2, dk's inverse chain another c
-    int shift = 4 + (C::cb == 4 ? 2 : (C::cb >= 2 ? 1 : 0));
-    const float dDscale = pl.dkscale / (float)(1 << shift);
-    hipLaunchKernelGGL((wdk_kernel<LG, IO, NWV>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st, (const T*)dy,
-                       (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, pl.dkscale, dDscale,
-                       (const unsigned char*)tb.wtab);
-    return hipGetLastError();
-}
-
-template <class IO>
-hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
-                  const Tables& tb, hipStream_t st)
-{
-    switch (pl.log2L2) {
-        case 9: return wdk_go<9, IO, 8>(dy, u, dk, dD, pr, pl, tb, st);
-        case 10: return wdk_go<10, IO, 8>(dy, u, dk, dD, pr, pl, tb, st);
-        case 11: return wdk_go<11, IO, 8>(dy, u, dk, dD, pr, pl, tb, st);
-        default: return hipErrorInvalidValue;
-    }
-}
-
-// -------------------------------------------------------------------------------------
-// Helpers of the spectrum kernel: a wave owns TPW of the head's TC tiles and keeps the twiddles
-// and matrices of exactly those tiles in registers (no constant table in LDS, nothing to copy
-// at workgroup start); NWP = TC / TPW waves share one head.
+// Helpers of the dk and spectrum kernels: a wave owns TPW of a row pair's TC tiles in every phase and
+// keeps the twiddles and matrices of exactly those tiles in registers (no constant table in LDS,
+// nothing to copy at workgroup start); NWP = TC / TPW waves share one pair.
 // -------------------------------------------------------------------------------------
 template <int LG, int TPW>
 struct WK {     // constants of tiles t0 .. t0+TPW-1 and the plain matrices
@@ -763,6 +556,222 @@ __device__ __forceinline__ void w_phase2_fwd(const uint32_t* xb, const WK<LG, TP
     }
 }
 
+
+// rows of one pair for this wave's tiles, straight into registers
+template <int LG, class IO, int TPW>
+__device__ __forceinline__ void load_rows(In<TPW>& r, const typename IO::T* pa, const typename IO::T* pb, bool has_b,
+                                          int t0, int lane)
+{
+    using C = WC<LG>;
+    const int c = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < TPW / 2; ++i) r.wa[j][i] = r.wb[j][i] = 0u;
+    if (g < 2) {     // samples at and above N are the zero padding
+        const int n0 = (4 * g) * 16 * C::TC + c * C::TC + t0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) load_words<TPW / 2>(pa + n0 + j * 16 * C::TC, r.wa[j]);
+        if (has_b) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) load_words<TPW / 2>(pb + n0 + j * 16 * C::TC, r.wb[j]);
+        }
+    }
+}
+
+// Phase 3 on tile t0+k: [A-role per-tile inverse matrix over k_b], conj w_L twiddle,
+// [B-role F16^-1 over k_a]; r = real part (row a), s = imaginary part (row b).
+template <int LG, int TPW, bool NEED_IM>
+__device__ __forceinline__ void w_phase3_tile(const uint32_t* xb, const WK<LG, TPW>& K, int t0, int k, int lane,
+                                              f4& r, f4& s)
+{
+    using C = WC<LG>;
+    const int c = lane & 15, g = lane >> 4;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+    H8U x, u;
+    x.u = *reinterpret_cast<const uint4*>(&xb[w1 + 4 * (t0 + k)]);
+    const f4 yr = MFMA(x.v, K.gir[k].v, zero), yi = MFMA(x.v, K.gii[k].v, zero);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[j], yi[j], K.t0i[k].c[j]);
+    r = MFMA(K.I16.re, u.v, zero);
+    if (NEED_IM) s = MFMA(K.I16.im, u.v, zero);
+}
+
+// -------------------------------------------------------------------------------------
+// dk and dD, one head per workgroup of NWV waves = NGRP groups of NWP waves (small workgroups, several
+// per CU: a head's work is a chain of load and exchange latencies, which neighbours hide); group `grp` takes the
+// head's row pairs grp, grp + NGRP, ...  Per pair: Z = transform of the u pair (kept as fp16 in
+// registers), W = transform of the dy pair, A += conj(Z) W in fp32 registers, each wave for its
+// own TPW phase-2 tiles.  The groups' partial A are summed through LDS in a fixed order (bitwise
+// repeatable), group 0 runs the inverse of phase 2 on the total, and phase 3 (real part = dk; the
+// cross terms between the two rows of a pair are purely imaginary) is spread over the groups.
+// dD is the lag-0 correlation, sum_f Re(A_f) / L (Parseval), taken from the fp32 total.
+// -------------------------------------------------------------------------------------
+template <int LG, class IO, int TPW, int NWV>
+__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(TPW == 2 ? 3 : 2)))
+wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u, float* __restrict__ dk,
+           float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs, float dkscale, float dDscale,
+           const unsigned char* __restrict__ wtab)
+{
+    using C = WC<LG>;
+    using T = typename IO::T;
+    constexpr int NWP = C::TC / TPW, NGRP = NWV / NWP;
+    static_assert(NWP >= 1 && NWP <= NWV, "tiles per wave");
+    extern __shared__ uint4 lds4[];
+    uint32_t* lds = reinterpret_cast<uint32_t*>(lds4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = wave / NWP, t0 = (wave % NWP) * TPW;
+    const int c = lane & 15, g = lane >> 4;
+    uint32_t* xa = lds + (size_t)(grp * 2 + 0) * C::PAIR_WORDS;      // u pair
+    uint32_t* xd = lds + (size_t)(grp * 2 + 1) * C::PAIR_WORDS;      // dy pair
+    float2* red = reinterpret_cast<float2*>(lds + (size_t)NGRP * 2 * C::PAIR_WORDS);   // [wave][TPW*4][64]
+    float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWP]
+    const int h = blockIdx.x;
+
+    auto load_pair = [&](int p, In<TPW>& iu, In<TPW>& id) {
+        const int64_t b0 = 2 * (int64_t)p;
+        const bool has_b = b0 + 1 < B;
+        const size_t oa = row_off(b0, h, H, N), ob = row_off(has_b ? b0 + 1 : b0, h, H, N);
+        load_rows<LG, IO, TPW>(iu, u + oa, u + ob, has_b, t0, lane);
+        load_rows<LG, IO, TPW>(id, dy + oa, dy + ob, has_b, t0, lane);
+    };
+    In<TPW> inu, ind;
+    if (grp < npairs) load_pair(grp, inu, ind);
+    WK<LG, TPW> K;
+    load_consts<LG, TPW>(K, wtab, t0, lane);
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    int ad[TPW][4];
+#pragma unroll
+    for (int k = 0; k < TPW; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ad[k][j] = phase2_addr<LG>(t0 + k, j, lane);
+    float2 acc[TPW][4];
+#pragma unroll
+    for (int k = 0; k < TPW; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[k][j] = make_float2(0.f, 0.f);
+
+    const int niter = (npairs + NGRP - 1) / NGRP;      // same for every group: barriers stay uniform
+    for (int it = 0; it < niter; ++it) {
+        const bool act = it * NGRP + grp < npairs;
+        if (act) w_phase1<LG, IO, TPW>(inu, xa, K, t0, lane);
+        pair_sync<NWP>();
+        uint32_t z[TPW][4];
+        if (act) {
+            f4 yr[TPW], yi[TPW];
+            w_phase2_fwd<LG, TPW>(xa, K, ad, yr, yi);
+#pragma unroll
+            for (int k = 0; k < TPW; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) z[k][j] = pack_h2(yr[k][j], yi[k][j]);
+            w_phase1<LG, IO, TPW>(ind, xd, K, t0, lane);
+        }
+        if ((it + 1) * NGRP + grp < npairs) load_pair((it + 1) * NGRP + grp, inu, ind);
+        pair_sync<NWP>();
+        if (act) {
+            f4 yr[TPW], yi[TPW];
+            w_phase2_fwd<LG, TPW>(xd, K, ad, yr, yi);
+#pragma unroll
+            for (int k = 0; k < TPW; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    union { uint32_t u; h2 h; } cv;
+                    cv.u = z[k][j];
+                    const float zr = (float)cv.h[0], zi = (float)cv.h[1];
+                    acc[k][j].x += zr * yr[k][j] + zi * yi[k][j];      // conj(Z) * W
+                    acc[k][j].y += zr * yi[k][j] - zi * yr[k][j];
+                }
+        }
+    }
+
+    // ---- every wave publishes its partial A; group 0 adds them in group order
+#pragma unroll
+    for (int k = 0; k < TPW; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) red[((size_t)(wave * TPW + k) * 4 + j) * 64 + lane] = acc[k][j];
+    __syncthreads();
+    if (grp == 0) {
+        float dsum = 0.f;
+#pragma unroll
+        for (int k = 0; k < TPW; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float2 s = acc[k][j];
+#pragma unroll
+                for (int gi = 1; gi < NGRP; ++gi) {
+                    const float2 v = red[((size_t)((gi * NWP + wave) * TPW + k) * 4 + j) * 64 + lane];
+                    s.x += v.x; s.y += v.y;
+                }
+                acc[k][j] = s;
+                dsum += s.x;
+            }
+        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+        if (lane == 0) dred[wave] = dsum;
+        if (dk) {     // inverse of phase 2 into group 0's first exchange buffer
+#pragma unroll
+            for (int k = 0; k < TPW; ++k) {
+                H8U m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(acc[k][j].x, acc[k][j].y);
+                const f4 zr = MFMA(K.IL.re, m.v, zero), zi = MFMA(K.IL.im, m.v, zero);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) lds[ad[k][j]] = pack_h2(zr[j], zi[j]);
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0 && dD) {
+        float t = 0.f;
+        for (int w = 0; w < NWP; ++w) t += dred[w];
+        dD[h] = t * dDscale;
+    }
+    if (dk) {
+#pragma unroll
+        for (int k = 0; k < TPW; ++k) {
+            if ((k % NGRP) != grp) continue;      // tile t0+k: its constants live in every group's wave t0/TPW
+            f4 r, s;
+            w_phase3_tile<LG, TPW, false>(lds, K, t0, k, lane, r, s);
+            if (g < 2) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    dk[(size_t)h * N + (4 * g + j) * 16 * C::TC + c * C::TC + t0 + k] = r[j] * dkscale;
+            }
+        }
+    }
+}
+
+template <int LG, class IO, int TPW, int NWV>
+hipError_t wdk_go(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
+                  const Tables& tb, hipStream_t st)
+{
+    using T = typename IO::T;
+    using C = WC<LG>;
+    constexpr int NWP = C::TC / TPW, NGRP = NWV / NWP;
+    const size_t lds = (size_t)NGRP * 2 * C::PAIR_WORDS * 4 + (size_t)NWV * TPW * 4 * 64 * 8 + 64;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wdk_kernel<LG, IO, TPW, NWV>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    // forward chains scale by c = 2^-shift each: A carries c^2, dk's inverse chain another c
+    int shift = 4 + (C::cb == 4 ? 2 : (C::cb >= 2 ? 1 : 0));
+    const float dDscale = pl.dkscale / (float)(1 << shift);
+    hipLaunchKernelGGL((wdk_kernel<LG, IO, TPW, NWV>), dim3((unsigned)pr.H), dim3(NWV * 64), lds, st, (const T*)dy,
+                       (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, pl.dkscale, dDscale,
+                       (const unsigned char*)tb.wtab);
+    return hipGetLastError();
+}
+
+template <class IO>
+hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
+                  const Tables& tb, hipStream_t st)
+{
+    switch (pl.log2L2) {
+        case 9: return wdk_go<9, IO, 2, 4>(dy, u, dk, dD, pr, pl, tb, st);
+        case 10: return wdk_go<10, IO, 2, 4>(dy, u, dk, dD, pr, pl, tb, st);
+        case 11: return wdk_go<11, IO, 2, 4>(dy, u, dk, dD, pr, pl, tb, st);
+        default: return hipErrorInvalidValue;
+    }
+}
 
 // -------------------------------------------------------------------------------------
 // Kernel spectrum on the matrix cores (Algorithm 2 lines 1-2) for the wave kernels' lane order.
