@@ -72,7 +72,9 @@ int longconv_init(void);
  * (the skip term is a delta kernel of height D[h]), pre-scaled and stored in the
  * permuted order the fused transform produces (Algorithm 2 lines 1-2: the
  * spectrum is computed once and stored already permuted, so no permutation ever
- * touches u).  Layout is private to the library and depends on (N, io). */
+ * touches u).  Layout and element type are private to the library and depend on
+ * (N, io): fp32 complex for fp32 I/O, fp16 complex for fp16/bf16 I/O; the size
+ * returned is an upper bound (8 bytes per bin). */
 size_t longconv_kspec_bytes(int64_t H, int64_t N, int io);
 
 /* Scratch bytes a call needs (0 on bad args).  `backward` = 0 for longconv_fwd,

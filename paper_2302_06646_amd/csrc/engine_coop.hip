@@ -349,8 +349,10 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     for (int i = tid; i < C::TC * 8; i += C::NW * 64) t1f[i] = gtab[C::T1F + i];
     Consts<LG> K;
     make_consts<LG>(K, tw, lane);
-    const float csign = conj ? -1.f : 1.f;
-    const float4* ks = reinterpret_cast<const float4*>(kspec + (size_t)h * Ltot + (size_t)k1 * C::L);
+    const uint32_t cmask = conj ? 0x80000000u : 0u;      // sign of the imaginary (high) half
+    // spectrum: fp16 complex, four bins per lane and tile in one 16-byte load
+    const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)h * Ltot +
+                                                     (size_t)k1 * C::L);
     int ng = C::NG;
     asm volatile("" : "+s"(ng));   // opaque trip count: the group loops stay loops (bounded register pressure)
     __syncthreads();
@@ -378,25 +380,23 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
             const int t0 = (gi * C::NW + wave) * 8;
             int base[NTB];
             f4 zr[NTB], zi[NTB];
-            float4 k01[NTB], k23[NTB];
+            H8U kk[NTB];
 #pragma unroll
             for (int k = 0; k < NTB; ++k) {
                 const int t2 = t0 + tb + k;
                 base[k] = phase2_base<LG>(t2, lane);
-                k01[k] = ks[(t2 * 64 + lane) * 2];
-                k23[k] = ks[(t2 * 64 + lane) * 2 + 1];
+                kk[k].u = ks[t2 * 64 + lane];
             }
 #pragma unroll
             for (int k = 0; k < NTB; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
 #pragma unroll
             for (int k = 0; k < NTB; ++k) {
-                const float2 kk[4] = {make_float2(k01[k].x, k01[k].y * csign), make_float2(k01[k].z, k01[k].w * csign),
-                                      make_float2(k23[k].x, k23[k].y * csign), make_float2(k23[k].z, k23[k].w * csign)};
                 H8U m;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float2 v = cmul(make_float2(zr[k][j], zi[k][j]), kk[j]);
-                    m.w[j] = pack_h2(v.x, v.y);
+                    union { uint32_t u; h2 h; } kw;
+                    kw.u = kk[k].w[j] ^ cmask;                 // conjugate for the correlation (du)
+                    m.w[j] = cmul_pack(zr[k][j], zi[k][j], kw.h);
                 }
                 phase2_inv<LG>(xb, base[k], K, m);
             }
@@ -622,7 +622,7 @@ coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __re
 //                pair whose other row is zero;
 //   multi pass : chunk k1 of the pass-A output of the pre-scaled kernel.
 // Phase 1 and the forward half of phase 2 as in the convolution; value stored =
-// kscale * (FFT([k,0]) + D[h]).
+// kscale * (FFT([k,0]) + D[h]) as fp16 complex (one 32-bit word per bin).
 // -------------------------------------------------------------------------------------
 template <int LG, bool CPLX>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
@@ -670,7 +670,7 @@ coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, c
     }
     __syncthreads();
     const float alpha = kscale_over_c / r, beta = D[h] * kscale;
-    float4* out = reinterpret_cast<float4*>(kspec + (size_t)h * Ltot + (size_t)k1 * C::L);
+    uint4* out = reinterpret_cast<uint4*>(reinterpret_cast<uint32_t*>(kspec) + (size_t)h * Ltot + (size_t)k1 * C::L);
 #pragma unroll
     for (int gi = 0; gi < C::NG; ++gi)
 #pragma unroll
@@ -678,8 +678,8 @@ coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, c
             const int t2 = (gi * C::NW + wave) * 8 + i;
             f4 zr, zi;
             phase2_fwd<LG>(xb, phase2_base<LG>(t2, lane), K, zr, zi);
-            out[(t2 * 64 + lane) * 2] = make_float4(zr[0] * alpha + beta, zi[0] * alpha, zr[1] * alpha + beta, zi[1] * alpha);
-            out[(t2 * 64 + lane) * 2 + 1] = make_float4(zr[2] * alpha + beta, zi[2] * alpha, zr[3] * alpha + beta, zi[3] * alpha);
+            out[t2 * 64 + lane] = make_uint4(pack_h2(zr[0] * alpha + beta, zi[0] * alpha), pack_h2(zr[1] * alpha + beta, zi[1] * alpha),
+                                             pack_h2(zr[2] * alpha + beta, zi[2] * alpha), pack_h2(zr[3] * alpha + beta, zi[3] * alpha));
         }
 }
 

@@ -304,7 +304,7 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
     }
     uint32_t* xb = lds + C::TAB_U4 * 4 + wave * (PB * C::PAIR_WORDS);
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
-    const float csign = conj ? -1.f : 1.f;
+    const uint32_t cmask = conj ? 0x80000000u : 0u;      // sign of the imaginary (high) half
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
 
     for (int gi_ = 0; gi_ < gpw; ++gi_) {
@@ -327,20 +327,21 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
         wave_lds_fence();
 
         // ---------------- phase 2 ----------------
-        const float4* ks = reinterpret_cast<const float4*>(kspec + (size_t)hcur * C::L);
+        // spectrum: fp16 complex, four bins per lane and tile in one 16-byte load
+        const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)hcur * C::L);
 #pragma unroll
         for (int tb = 0; tb < C::TC; tb += NT) {
             int ad[NT][4];
-            float2 kk[NT][4];
+            H8U kk[NT];
             f4 yr[NT][PB], yi[NT][PB];
 #pragma unroll
             for (int k = 0; k < NT; ++k) {
                 const int t2 = tb + k;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) ad[k][j] = phase2_addr<LG>(t2, j, lane);
-                const float4 k01 = ks[(t2 * 64 + lane) * 2], k23 = ks[(t2 * 64 + lane) * 2 + 1];
-                kk[k][0] = make_float2(k01.x, k01.y * csign); kk[k][1] = make_float2(k01.z, k01.w * csign);
-                kk[k][2] = make_float2(k23.x, k23.y * csign); kk[k][3] = make_float2(k23.z, k23.w * csign);
+                kk[k].u = ks[t2 * 64 + lane];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) kk[k].w[j] ^= cmask;        // conjugate for the correlation (du)
             }
 #pragma unroll
             for (int k = 0; k < NT; ++k)
@@ -359,10 +360,7 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
                 for (int q = 0; q < PB; ++q) {
                     H8U m;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float2 v = cmul(make_float2(yr[k][q][j], yi[k][q][j]), kk[k][j]);
-                        m.w[j] = pack_h2(v.x, v.y);
-                    }
+                    for (int j = 0; j < 4; ++j) m.w[j] = cmul_pack(yr[k][q][j], yi[k][q][j], kk[k].c[j]);
                     zr[k][q] = MFMA(IL.re, m.v, zero);
                     zi[k][q] = MFMA(IL.im, m.v, zero);
                 }
@@ -778,7 +776,8 @@ hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, const Pro
 // One workgroup (NWP waves) per head.  The row is scaled by a power of two r that brings
 // max|k[h,:]| to about 1, so the fp16 operands keep their relative precision whatever the head's
 // magnitude, and transformed as the real row of a pair whose other row is zero: phase 1 and the
-// forward half of phase 2 of the convolution kernel.  Stored value = kscale * (FFT([k,0]) + D[h]).
+// forward half of phase 2 of the convolution kernel.  Stored value = kscale * (FFT([k,0]) + D[h]) as
+// fp16 complex (one 32-bit word per bin).
 // -------------------------------------------------------------------------------------
 template <int LG, int TPW>
 __global__ void __launch_bounds__((WC<LG>::TC / TPW) * 64) __attribute__((amdgpu_waves_per_eu(2)))
@@ -832,12 +831,14 @@ wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, float2* 
     f4 yr[TPW], yi[TPW];
     w_phase2_fwd<LG, TPW>(xb, K, ad, yr, yi);
     const float alpha = kscale_over_c / r, beta = D[h] * kscale;
-    float4* out = reinterpret_cast<float4*>(kspec + (size_t)h * C::L);
+    uint4* out = reinterpret_cast<uint4*>(reinterpret_cast<uint32_t*>(kspec) + (size_t)h * C::L);
 #pragma unroll
     for (int kk = 0; kk < TPW; ++kk) {
         const int t2 = t0 + kk;
-        out[(t2 * 64 + lane) * 2] = make_float4(yr[kk][0] * alpha + beta, yi[kk][0] * alpha, yr[kk][1] * alpha + beta, yi[kk][1] * alpha);
-        out[(t2 * 64 + lane) * 2 + 1] = make_float4(yr[kk][2] * alpha + beta, yi[kk][2] * alpha, yr[kk][3] * alpha + beta, yi[kk][3] * alpha);
+        out[t2 * 64 + lane] = make_uint4(pack_h2(yr[kk][0] * alpha + beta, yi[kk][0] * alpha),
+                                         pack_h2(yr[kk][1] * alpha + beta, yi[kk][1] * alpha),
+                                         pack_h2(yr[kk][2] * alpha + beta, yi[kk][2] * alpha),
+                                         pack_h2(yr[kk][3] * alpha + beta, yi[kk][3] * alpha));
     }
 }
 
