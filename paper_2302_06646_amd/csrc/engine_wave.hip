@@ -144,23 +144,22 @@ struct Rows {
     size_t oa[PB], ob[PB];
 };
 
+// Every lane loads: lanes 32..63 (d_a >= 8, the zero padding) re-read the samples of lanes 0..31, and a
+// missing row re-reads an existing one; the first-stage matrix has zero rows for d_a >= 8 and the outputs
+// of missing rows are never stored, so neither needs branches or cleared registers.
 template <int LG, class IO, int PB>
 __device__ __forceinline__ void load_inputs(InRegs<LG, PB>& r, const typename IO::T* in, const Rows<PB>& R, int tg,
                                             int lane)
 {
     using C = WC<LG>;
-    const int c = lane & 15, g = lane >> 4;
+    const int c = lane & 15, g = (lane >> 4) & 1;
 #pragma unroll
     for (int q = 0; q < PB; ++q)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + tg;
-#pragma unroll
-            for (int i = 0; i < C::NWD; ++i) r.wa[q][j][i] = r.wb[q][j][i] = 0u;
-            if (g < 2) {     // samples at and above N are the zero padding
-                if (R.row_a[q]) load_words<C::NWD>(in + R.oa[q] + n0, r.wa[q][j]);
-                if (R.row_b[q]) load_words<C::NWD>(in + R.ob[q] + n0, r.wb[q][j]);
-            }
+            load_words<C::NWD>(in + R.oa[q] + n0, r.wa[q][j]);
+            load_words<C::NWD>(in + R.ob[q] + n0, r.wb[q][j]);
         }
 }
 
@@ -272,7 +271,7 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
             R.row_a[q] = b0 < B;
             R.row_b[q] = b0 + 1 < B;
             R.oa[q] = row_off(R.row_a[q] ? b0 : 0, h, H, N);
-            R.ob[q] = row_off(R.row_b[q] ? b0 + 1 : 0, h, H, N);
+            R.ob[q] = row_off(R.row_b[q] ? b0 + 1 : (R.row_a[q] ? b0 : 0), h, H, N);
         }
     };
     // first group's rows start travelling before anything else
@@ -301,6 +300,10 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
         m.u = tab[C::PM + 5 * 64 + lane]; FL.im = m.v;
         m.u = tab[C::PM + 6 * 64 + lane]; IL.re = m.v;
         m.u = tab[C::PM + 7 * 64 + lane]; IL.im = m.v;
+    }
+    if (g >= 2) {     // F16 only serves the first stage: rows d_a >= 8 meet the zero padding
+        const h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+        F16.re = z; F16.im = z;
     }
     uint32_t* xb = lds + C::TAB_U4 * 4 + wave * (PB * C::PAIR_WORDS);
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
