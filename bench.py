@@ -37,13 +37,13 @@ CACHE_BYTES = 256 << 20        # last-level (Infinity) cache
 # profiles/.
 KIB = 1024
 MEASURED_TRAFFIC = {
-    "cfg2_B16_H768_N1024_bf16": {"fwd": (20576.9 * 2 + 29184.0) * KIB, "bwd_du": (20576.9 * 2 + 29184.0) * KIB,
+    "cfg2_B16_H768_N1024_bf16": {"fwd": (15885.9 * 2 + 24576.0) * KIB, "bwd_du": (15885.9 * 2 + 24576.0) * KIB,
                                  "bwd_dk_dD": (24847.5 * 2 + 3096.0) * KIB},
-    "cfg3_B8_H256_N16384_fp16": {"fwd": (102687.2 * 2 + 65536.4) * KIB, "bwd_du": (102687.2 * 2 + 65536.4) * KIB,
-                                 "bwd_dk_dD": (146513.2 * 2 + 38408.3) * KIB},
-    "cfg4_B1_H128_N65536_fp16": {"fwd": ((9572.2 + 100636.5 + 34152.8) * 2 + 65536.0 + 65536.7 + 16384.0) * KIB,
-                                 "bwd_du": ((9572.2 + 100636.5 + 34152.8) * 2 + 65536.0 + 65536.7 + 16384.0) * KIB,
-                                 "bwd_dk_dD": ((17770.4 + 165076.6 + 34148.5) * 2 + 131072.0 + 136645.2 + 32768.0) * KIB},
+    "cfg3_B8_H256_N16384_fp16": {"fwd": (69922.3 * 2 + 65536.0) * KIB, "bwd_du": (69922.3 * 2 + 65536.0) * KIB,
+                                 "bwd_dk_dD": (146922.4 * 2 + 38413.4) * KIB},
+    "cfg4_B1_H128_N65536_fp16": {"fwd": ((9572.2 + 67866.0 + 34152.4) * 2 + 65536.0 + 65536.0 + 16384.0) * KIB,
+                                 "bwd_du": ((9572.2 + 67866.0 + 34152.4) * 2 + 65536.0 + 65536.0 + 16384.0) * KIB,
+                                 "bwd_dk_dD": ((17770.2 + 165412.0 + 34151.5) * 2 + 131072.0 + 133777.2 + 32768.0) * KIB},
 }
 
 def log(*a):
