@@ -321,8 +321,8 @@ __device__ __forceinline__ void phase3_two(const uint32_t* xb, const uint4* gtab
 // Fused convolution.  grid = (pair slots, H, R); a workgroup loops over the pairs p = blockIdx.x,
 // blockIdx.x + gridDim.x, ... of head h (chunk k1 of each in the multi-pass split).
 // -------------------------------------------------------------------------------------
-template <int LG, class IO, bool CPLX>
-__global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+template <int LG, class IO, bool CPLX, int NWV, int NB>
+__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(NWV >= 16 ? 4 : 2)))
 coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
                  typename IO::T* __restrict__ out, __half2* __restrict__ ws, int conj, int64_t B, int64_t H,
                  int64_t N, int npairs, int log2R, int gx, const float2* __restrict__ tw,
@@ -346,14 +346,14 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     const int h = (int)((vid / (unsigned)gx) >> log2R);
     const int64_t Ltot = (int64_t)C::L << log2R;
     const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
-    for (int i = tid; i < C::TC * 8; i += C::NW * 64) t1f[i] = gtab[C::T1F + i];
+    for (int i = tid; i < C::TC * 8; i += NWV * 64) t1f[i] = gtab[C::T1F + i];
     Consts<LG> K;
     make_consts<LG>(K, tw, lane);
     const uint32_t cmask = conj ? 0x80000000u : 0u;      // sign of the imaginary (high) half
     // spectrum: fp16 complex, four bins per lane and tile in one 16-byte load
     const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)h * Ltot +
                                                      (size_t)k1 * C::L);
-    int ng = C::NG;
+    int ng = C::TC / (8 * NWV);
     asm volatile("" : "+s"(ng));   // opaque trip count: the group loops stay loops (bounded register pressure)
     __syncthreads();
 
@@ -366,7 +366,7 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
 
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi) {
-            phase1<LG, IO, CPLX>(in + oa, in + ob, has_b, chunk, xb, gtab, t1f, K, (gi * C::NW + wave) * 8, lane);
+            phase1<LG, IO, CPLX, NB>(in + oa, in + ob, has_b, chunk, xb, gtab, t1f, K, (gi * NWV + wave) * 8, lane);
             __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds register pressure
         }
         __syncthreads();
@@ -376,21 +376,21 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi)
 #pragma unroll
-        for (int tb = 0; tb < 8; tb += NTB) {
-            const int t0 = (gi * C::NW + wave) * 8;
-            int base[NTB];
-            f4 zr[NTB], zi[NTB];
-            H8U kk[NTB];
+        for (int tb = 0; tb < 8; tb += NB) {
+            const int t0 = (gi * NWV + wave) * 8;
+            int base[NB];
+            f4 zr[NB], zi[NB];
+            H8U kk[NB];
 #pragma unroll
-            for (int k = 0; k < NTB; ++k) {
+            for (int k = 0; k < NB; ++k) {
                 const int t2 = t0 + tb + k;
                 base[k] = phase2_base<LG>(t2, lane);
                 kk[k].u = ks[t2 * 64 + lane];
             }
 #pragma unroll
-            for (int k = 0; k < NTB; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
+            for (int k = 0; k < NB; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
 #pragma unroll
-            for (int k = 0; k < NTB; ++k) {
+            for (int k = 0; k < NB; ++k) {
                 H8U m;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -408,7 +408,7 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
         // ---- phase 3
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi) {
-        const int t0 = (gi * C::NW + wave) * 8;
+        const int t0 = (gi * NWV + wave) * 8;
         uint32_t ow[4][8];     // REAL: [j][0..3] row a, [4..7] row b; CPLX: [j][tile]
 #pragma unroll
         for (int tb = 0; tb < 8; tb += 2) {
@@ -443,6 +443,289 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
         __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// Fused convolution of zero-padded real row pairs (single-pass plan), rows staged through LDS.
+// The phase-1 tile of a wave takes samples a tile count apart, so loading its operands straight
+// from global memory touches 16 bytes of every 256; here the whole workgroup moves the pair
+// between global memory and LDS in unit-stride 16-byte runs instead, into the very slots that
+// phase 1 reads and phase 3 writes: sample n = d_a 16 TC + d_b TC + t of the pair, packed as the
+// fp16 complex word (row a, row b), lives in word (d_b PITCH + (d_a / 4) TC + t) 4 + d_a % 4 -- the
+// slot phase 1 fills with output (k_a, k_b) = (d_b, d_a) of tile t, and phase 3 the other way round,
+// each lane reading and writing only its own 16 bytes.  Slots of the zero padding (d_a >= 8) are
+// cleared at the start and again by phase 3.  The next pair's runs are fetched into registers
+// before phase 3 and stored to LDS by the lane that has just drained the same slots, so global
+// latency is covered by phase 3 and no phase but the second (spectrum) issues global loads:
+// the w_L twiddle of phases 1 and 3 is the product of a per-lane constant w_256^(k_a d_b) and an
+// LDS table w_L^(k_a t).
+// -------------------------------------------------------------------------------------
+__device__ __forceinline__ h2 cmul_hh(h2 a, h2 w)
+{
+    const h2 ax = {a[0], a[0]}, ay = {a[1], a[1]};
+    const h2 ws = {-w[1], w[0]};
+    return __builtin_elementwise_fma(ay, ws, ax * w);
+}
+// (yr + i yi) * conj(w), packed fp16
+__device__ __forceinline__ uint32_t cmul_pack_conj(float yr, float yi, h2 w)
+{
+    const f2 v = {yr, yi};
+    const h2 y = __builtin_convertvector(v, h2);
+    const h2 yx = {y[0], y[0]}, yy = {y[1], y[1]};
+    const h2 wc = {w[0], -w[1]}, ws = {w[1], w[0]};
+    union { h2 h; uint32_t u; } cv;
+    cv.h = __builtin_elementwise_fma(yy, ws, yx * wc);
+    return cv.u;
+}
+
+template <int LG>
+size_t coop_real_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16 + (size_t)CC<LG>::TC * 16 * 4; }
+
+template <int LG, class IO, int NWV, int NB>
+__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
+coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
+                      typename IO::T* __restrict__ out, int conj, int64_t B, int64_t H, int64_t N, int npairs,
+                      int gx, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
+{
+    using C = CC<LG>;
+    constexpr int NT = NWV * 64;
+    constexpr int RPL = (C::L / 16) / NT;            // 16-byte runs (8 samples) of one row per lane
+    static_assert(RPL * NT * 16 == C::L, "runs must tile the row");
+    extern __shared__ uint4 lds4[];
+    uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
+    uint4* t1f = lds4 + C::XWORDS / 4;
+    uint4* t1i = t1f + C::TC * 4;
+    uint32_t* vt = reinterpret_cast<uint32_t*>(t1i + C::TC * 4);      // [TC][16]: w_L^(k_a t)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const unsigned G = gridDim.x;
+    const unsigned vid = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (G >> 3) + (blockIdx.x >> 3);
+    const int p0 = (int)(vid % (unsigned)gx);
+    const int h = (int)(vid / (unsigned)gx);
+    const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
+    for (int i = tid; i < C::TC * 8; i += NT) t1f[i] = gtab[C::T1F + i];
+    for (int i = tid; i < C::TC * 16; i += NT) {
+        const float2 w = tw_full(tw, (uint32_t)(((i & 15) * (i >> 4)) & (C::L - 1)) << (TW_LOG2 - LG));
+        vt[i] = pack_h2(w.x, w.y);
+    }
+    for (int i = tid; i < C::XWORDS / 4; i += NT) lds4[i] = make_uint4(0u, 0u, 0u, 0u);
+    Consts<LG> K;
+    make_consts<LG>(K, tw, lane);
+    h2 cF[4];                                            // w_256^(x (4g+j)), the same in both directions
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 w = tw_full(tw, (uint32_t)((c * (4 * g + j)) & 255) << (TW_LOG2 - 8));
+        cF[j] = h2{(_Float16)w.x, (_Float16)w.y};
+    }
+    const uint32_t cmask = conj ? 0x80000000u : 0u;
+    const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)h * C::L);
+    int ng = C::TC / (8 * NWV);
+    asm volatile("" : "+s"(ng));
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    // run r of the pair -> (d_a, d_b, q): four lanes cover 64 contiguous bytes of a row, the next lane bits
+    // pick d_a % 4 and d_b % 4, so that a wave's 4-byte LDS accesses (word stride 4 along t) spread over
+    // 32 banks while global accesses keep 64-byte segments
+    auto run_n = [&](int i) {
+        constexpr int QB = C::cb - 3;
+        const int r = i * NT + tid;
+        const int q = (r & 3) | (((r >> 6) & ((1 << (QB - 2)) - 1)) << 2);
+        const int da = ((r >> 2) & 3) | ((r >> (QB + 6)) << 2);
+        const int db = ((r >> 4) & 3) | (((r >> (QB + 4)) & 3) << 2);
+        return (da << (C::cb + 4)) + (db << C::cb) + 8 * q;
+    };
+    auto slot = [&](int i) {
+        const int n = run_n(i);
+        const int t = n & (C::TC - 1), db = (n >> C::cb) & 15, da = n >> (C::cb + 4);
+        return (db * C::PITCH + (da >> 2) * C::TC + t) * 4 + (da & 3);
+    };
+    uint4 pa[RPL], pb[RPL];
+    auto fetch = [&](int p) {
+        const bool has_b = (2 * p + 1) < B;
+        const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
+#pragma unroll
+        for (int i = 0; i < RPL; ++i) {
+            const int n = run_n(i);
+            pa[i] = *reinterpret_cast<const uint4*>(in + oa + n);
+            pb[i] = *reinterpret_cast<const uint4*>(in + ob + n);
+            if (!has_b) pb[i] = make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < RPL; ++i) {
+            uint32_t wa[4] = {pa[i].x, pa[i].y, pa[i].z, pa[i].w}, wb[4] = {pb[i].x, pb[i].y, pb[i].z, pb[i].w};
+            if (IsBf<IO>::v) {
+#pragma unroll
+                for (int m = 0; m < 4; ++m) { wa[m] = bf2_to_h2(wa[m]); wb[m] = bf2_to_h2(wb[m]); }
+            }
+            const int a0 = slot(i);
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                xb[a0 + 8 * m] = __builtin_amdgcn_perm(wb[m], wa[m], 0x05040100u);
+                xb[a0 + 8 * m + 4] = __builtin_amdgcn_perm(wb[m], wa[m], 0x07060302u);
+            }
+        }
+    };
+    auto drain = [&](int p) {
+        const bool has_b = (2 * p + 1) < B;
+        const size_t oa = row_off(2 * p, h, H, N), ob = row_off(2 * p + 1, h, H, N);
+#pragma unroll
+        for (int i = 0; i < RPL; ++i) {
+            const int a0 = slot(i), n = run_n(i);
+            uint32_t x[8], wa[4], wb[4];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = xb[a0 + 4 * e];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                wa[m] = __builtin_amdgcn_perm(x[2 * m + 1], x[2 * m], 0x05040100u);
+                wb[m] = __builtin_amdgcn_perm(x[2 * m + 1], x[2 * m], 0x07060302u);
+                if (IsBf<IO>::v) {
+                    union { uint32_t u; h2 h; } a, b;
+                    a.u = wa[m]; b.u = wb[m];
+                    wa[m] = pack_bf2((float)a.h[0], (float)a.h[1]);
+                    wb[m] = pack_bf2((float)b.h[0], (float)b.h[1]);
+                }
+            }
+            store_words<4>(out + oa + n, wa);
+            if (has_b) store_words<4>(out + ob + n, wb);
+        }
+    };
+
+    int p = p0;
+    if (p < npairs) fetch(p);
+    __syncthreads();                 // tables and cleared slots in place
+    if (p < npairs) stage();
+    for (; p < npairs; p += gx) {
+        asm volatile("" : "+s"(ks));
+        __syncthreads();             // staged pair visible
+
+        // ---- phase 1, in place
+#pragma unroll 1
+        for (int gi = 0; gi < ng; ++gi) {
+            const int t0 = (gi * NWV + wave) * 8;
+#pragma unroll
+            for (int tb = 0; tb < 8; tb += NB) {
+                H8U x[NB], tw1[NB];
+                h2 v[NB];
+                f4 yr[NB], yi[NB], zr[NB], zi[NB];
+#pragma unroll
+                for (int k = 0; k < NB; ++k) {
+                    const int t = t0 + tb + k;
+                    x[k].u = *reinterpret_cast<const uint4*>(&xb[w1 + 4 * t]);
+                    tw1[k].u = t1f[t * 4 + g];
+                    union { uint32_t u; h2 h; } cv;
+                    cv.u = vt[t * 16 + c];
+                    v[k] = cv.h;
+                }
+#pragma unroll
+                for (int k = 0; k < NB; ++k) {
+                    yr[k] = MFMA(x[k].v, K.F16.re, zero);
+                    yi[k] = MFMA(x[k].v, K.F16.im, zero);
+                }
+#pragma unroll
+                for (int k = 0; k < NB; ++k) {
+                    H8U u;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][j], yi[k][j], cmul_hh(cF[j], v[k]));
+                    zr[k] = MFMA(K.F16.re, u.v, zero);
+                    zi[k] = MFMA(K.F16.im, u.v, zero);
+                }
+#pragma unroll
+                for (int k = 0; k < NB; ++k) {
+                    uint4 o;
+                    o.x = cmul_pack(zr[k][0], zi[k][0], tw1[k].c[0]);
+                    o.y = cmul_pack(zr[k][1], zi[k][1], tw1[k].c[1]);
+                    o.z = cmul_pack(zr[k][2], zi[k][2], tw1[k].c[2]);
+                    o.w = cmul_pack(zr[k][3], zi[k][3], tw1[k].c[3]);
+                    *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __syncthreads();
+        asm volatile("" : "+s"(ks));
+
+        // ---- phase 2
+#pragma unroll 1
+        for (int gi = 0; gi < ng; ++gi)
+#pragma unroll
+        for (int tb = 0; tb < 8; tb += NB) {
+            const int t0 = (gi * NWV + wave) * 8;
+            int base[NB];
+            f4 zr[NB], zi[NB];
+            H8U kk[NB];
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                const int t2 = t0 + tb + k;
+                base[k] = phase2_base<LG>(t2, lane);
+                kk[k].u = ks[t2 * 64 + lane];
+            }
+#pragma unroll
+            for (int k = 0; k < NB; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                H8U m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    union { uint32_t u; h2 h; } kw;
+                    kw.u = kk[k].w[j] ^ cmask;
+                    m.w[j] = cmul_pack(zr[k][j], zi[k][j], kw.h);
+                }
+                phase2_inv<LG>(xb, base[k], K, m);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+
+        const bool more = p + gx < npairs;
+        if (more) fetch(p + gx);
+
+        // ---- phase 3, in place: word = (row a sample, row b sample); padding slots cleared
+#pragma unroll 1
+        for (int gi = 0; gi < ng; ++gi) {
+            const int t0 = (gi * NWV + wave) * 8;
+#pragma unroll
+            for (int tb = 0; tb < 8; tb += 2) {
+                H8U tw1[2], x[2], vv[2];
+                f4 yr[2], yi[2], r[2], s[2];
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    const int t = t0 + tb + k;
+                    tw1[k].u = t1i[t * 4 + g];
+                    x[k].u = *reinterpret_cast<const uint4*>(&xb[w1 + 4 * t]);
+                    vv[k].u = *reinterpret_cast<const uint4*>(&vt[t * 16 + 4 * g]);
+                }
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) x[k].w[j] = cmul_h2(x[k].w[j], tw1[k].c[j]);
+                    yr[k] = MFMA(x[k].v, K.I16.re, zero);
+                    yi[k] = MFMA(x[k].v, K.I16.im, zero);
+                }
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    H8U u;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack_conj(yr[k][j], yi[k][j], cmul_hh(cF[j], vv[k].c[j]));
+                    r[k] = MFMA(K.I16.re, u.v, zero);
+                    s[k] = MFMA(K.I16.im, u.v, zero);
+                }
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    uint4 o = make_uint4(0u, 0u, 0u, 0u);
+                    if (g < 2) o = make_uint4(pack_h2(r[k][0], s[k][0]), pack_h2(r[k][1], s[k][1]),
+                                              pack_h2(r[k][2], s[k][2]), pack_h2(r[k][3], s[k][3]));
+                    *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __syncthreads();
+        drain(p);
+        if (more) stage();
     }
 }
 
@@ -691,6 +974,11 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
                         const Plan& pl, const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
+#ifndef COOP_CONV_NW
+#define COOP_CONV_NW 8
+#define COOP_CONV_NB 4
+#endif
+    constexpr int NWV = CC<LG>::TC / 8 > COOP_CONV_NW ? COOP_CONV_NW : CC<LG>::TC / 8, NB = COOP_CONV_NB;
     const size_t lds = coop_lds_bytes<LG>();
     const int R = 1 << pl.log2R;
     long gx = (512 + pr.H * R - 1) / (pr.H * R);
@@ -699,17 +987,18 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
     dim3 grid((unsigned)(gx * pr.H * R));
     hipError_t e;
     if (pl.log2R == 0) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, IO, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        const size_t ldsr = coop_real_lds_bytes<LG>();
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_real_kernel<LG, IO, NWV, NB>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsr);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((coop_conv_kernel<LG, IO, false>), grid, dim3(CC<LG>::NW * 64), lds, st, (const T*)in,
-                           kspec, (T*)out, ws, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, (int)gx, tb.tw,
+        hipLaunchKernelGGL((coop_conv_real_kernel<LG, IO, NWV, NB>), grid, dim3(NWV * 64), ldsr, st, (const T*)in,
+                           kspec, (T*)out, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, (int)gx, tb.tw,
                            (const unsigned char*)tb.ctab);
     } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, IO, true>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, IO, true, NWV, NB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((coop_conv_kernel<LG, IO, true>), grid, dim3(CC<LG>::NW * 64), lds, st, (const T*)in,
+        hipLaunchKernelGGL((coop_conv_kernel<LG, IO, true, NWV, NB>), grid, dim3(NWV * 64), lds, st, (const T*)in,
                            kspec, (T*)out, ws, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, (int)gx, tb.tw,
                            (const unsigned char*)tb.ctab);
     }
