@@ -486,7 +486,7 @@ template <int LG, class IO, int NWV, int NB>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
                       typename IO::T* __restrict__ out, int conj, int64_t B, int64_t H, int64_t N, int npairs,
-                      int gx, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
+                      int per, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
     constexpr int NT = NWV * 64;
@@ -501,15 +501,10 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
     const int c = lane & 15, g = lane >> 4;
     const unsigned G = gridDim.x;
     const unsigned vid = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (G >> 3) + (blockIdx.x >> 3);
-    const int p0 = (int)(vid % (unsigned)gx);
-    const int h = (int)(vid / (unsigned)gx);
+    // work items (head, pair), `per` consecutive ones per workgroup (a head's pairs share its spectrum)
+    const int total = (int)H * npairs;
+    const int it0 = (int)vid * per, it1 = it0 + per < total ? it0 + per : total;
     const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
-    for (int i = tid; i < C::TC * 8; i += NT) t1f[i] = gtab[C::T1F + i];
-    for (int i = tid; i < C::TC * 16; i += NT) {
-        const float2 w = tw_full(tw, (uint32_t)(((i & 15) * (i >> 4)) & (C::L - 1)) << (TW_LOG2 - LG));
-        vt[i] = pack_h2(w.x, w.y);
-    }
-    for (int i = tid; i < C::XWORDS / 4; i += NT) lds4[i] = make_uint4(0u, 0u, 0u, 0u);
     Consts<LG> K;
     make_consts<LG>(K, tw, lane);
     h2 cF[4];                                            // w_256^(x (4g+j)), the same in both directions
@@ -519,7 +514,6 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         cF[j] = h2{(_Float16)w.x, (_Float16)w.y};
     }
     const uint32_t cmask = conj ? 0x80000000u : 0u;
-    const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)h * C::L);
     int ng = C::TC / (8 * NWV);
     asm volatile("" : "+s"(ng));
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
@@ -542,7 +536,8 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         return (db * C::PITCH + (da >> 2) * C::TC + t) * 4 + (da & 3);
     };
     uint4 pa[RPL], pb[RPL];
-    auto fetch = [&](int p) {
+    auto fetch = [&](int it) {
+        const int h = it / npairs, p = it - h * npairs;
         const bool has_b = (2 * p + 1) < B;
         const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
 #pragma unroll
@@ -569,7 +564,8 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             }
         }
     };
-    auto drain = [&](int p) {
+    auto drain = [&](int it) {
+        const int h = it / npairs, p = it - h * npairs;
         const bool has_b = (2 * p + 1) < B;
         const size_t oa = row_off(2 * p, h, H, N), ob = row_off(2 * p + 1, h, H, N);
 #pragma unroll
@@ -594,11 +590,18 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         }
     };
 
-    int p = p0;
-    if (p < npairs) fetch(p);
+    if (it0 < it1) fetch(it0);       // first pair on its way while the tables are built
+    for (int i = tid; i < C::TC * 8; i += NT) t1f[i] = gtab[C::T1F + i];
+    for (int i = tid; i < C::TC * 16; i += NT) {
+        const float2 w = tw_full(tw, (uint32_t)(((i & 15) * (i >> 4)) & (C::L - 1)) << (TW_LOG2 - LG));
+        vt[i] = pack_h2(w.x, w.y);
+    }
+    for (int i = tid; i < C::XWORDS / 4; i += NT) lds4[i] = make_uint4(0u, 0u, 0u, 0u);
     __syncthreads();                 // tables and cleared slots in place
-    if (p < npairs) stage();
-    for (; p < npairs; p += gx) {
+    if (it0 < it1) stage();
+    for (int it = it0; it < it1; ++it) {
+        const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) +
+                                                         (size_t)(it / npairs) * C::L);
         asm volatile("" : "+s"(ks));
         __syncthreads();             // staged pair visible
 
@@ -680,8 +683,8 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         }
         __syncthreads();
 
-        const bool more = p + gx < npairs;
-        if (more) fetch(p + gx);
+        const bool more = it + 1 < it1;
+        if (more) fetch(it + 1);
 
         // ---- phase 3, in place: word = (row a sample, row b sample); padding slots cleared
 #pragma unroll 1
@@ -724,7 +727,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             }
         }
         __syncthreads();
-        drain(p);
+        drain(it);
         if (more) stage();
     }
 }
@@ -969,6 +972,21 @@ coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, c
 template <int LG>
 size_t coop_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16; }
 
+// compute units of the current device (asked once)
+int compute_units()
+{
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
+}
+
 template <int LG, class IO>
 hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
                         const Plan& pl, const Tables& tb, hipStream_t st)
@@ -981,7 +999,10 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
     constexpr int NWV = CC<LG>::TC / 8 > COOP_CONV_NW ? COOP_CONV_NW : CC<LG>::TC / 8, NB = COOP_CONV_NB;
     const size_t lds = coop_lds_bytes<LG>();
     const int R = 1 << pl.log2R;
-    long gx = (512 + pr.H * R - 1) / (pr.H * R);
+#ifndef COOP_WGS
+#define COOP_WGS 512
+#endif
+    long gx = (COOP_WGS + pr.H * R - 1) / (pr.H * R);
     if (gx < 1) gx = 1;
     if (gx > pr.npairs) gx = pr.npairs;
     dim3 grid((unsigned)(gx * pr.H * R));
@@ -991,8 +1012,19 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_real_kernel<LG, IO, NWV, NB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsr);
         if (e != hipSuccess) return e;
+        // as many workgroups as the device holds at once, each with a run of consecutive pairs
+        static int resident = 0;
+        if (resident == 0) {
+            int nb = 0;
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, coop_conv_real_kernel<LG, IO, NWV, NB>, NWV * 64, ldsr);
+            if (e != hipSuccess) return e;
+            resident = (nb > 0 ? nb : 1) * compute_units();
+        }
+        const long total = pr.H * pr.npairs;
+        const int per = (int)((total + resident - 1) / resident);
+        grid = dim3((unsigned)((total + per - 1) / per));
         hipLaunchKernelGGL((coop_conv_real_kernel<LG, IO, NWV, NB>), grid, dim3(NWV * 64), ldsr, st, (const T*)in,
-                           kspec, (T*)out, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, (int)gx, tb.tw,
+                           kspec, (T*)out, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, per, tb.tw,
                            (const unsigned char*)tb.ctab);
     } else {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, IO, true, NWV, NB>),
