@@ -479,6 +479,131 @@ __device__ __forceinline__ uint32_t cmul_pack_conj(float yr, float yi, h2 w)
     return cv.u;
 }
 
+// Phase 1 in place on the staged layout, 8 tiles t0..t0+7 of one wave: each lane reads its own 16 bytes
+// of a tile (samples d_a = 4g..4g+3 of column d_b = c) and writes outputs (k_a, k_b) = (c, 4g..4g+3) there.
+// F1 is the first-stage matrix (rows of the zero padding cleared when those slots hold stale data).
+template <int LG, int NB>
+__device__ __forceinline__ void phase1_inplace(uint32_t* xb, const uint4* t1f, const uint32_t* vt, const Mats& F1,
+                                               const Consts<LG>& K, const h2 (&cF)[4], int t0, int lane)
+{
+    using C = CC<LG>;
+    const int c = lane & 15, g = lane >> 4;
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int tb = 0; tb < 8; tb += NB) {
+        H8U x[NB], tw1[NB];
+        h2 v[NB];
+        f4 yr[NB], yi[NB], zr[NB], zi[NB];
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            const int t = t0 + tb + k;
+            x[k].u = *reinterpret_cast<const uint4*>(&xb[w1 + 4 * t]);
+            tw1[k].u = t1f[t * 4 + g];
+            union { uint32_t u; h2 h; } cv;
+            cv.u = vt[t * 16 + c];
+            v[k] = cv.h;
+        }
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            yr[k] = MFMA(x[k].v, F1.re, zero);
+            yi[k] = MFMA(x[k].v, F1.im, zero);
+        }
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            H8U u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][j], yi[k][j], cmul_hh(cF[j], v[k]));
+            zr[k] = MFMA(K.F16.re, u.v, zero);
+            zi[k] = MFMA(K.F16.im, u.v, zero);
+        }
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            uint4 o;
+            o.x = cmul_pack(zr[k][0], zi[k][0], tw1[k].c[0]);
+            o.y = cmul_pack(zr[k][1], zi[k][1], tw1[k].c[1]);
+            o.z = cmul_pack(zr[k][2], zi[k][2], tw1[k].c[2]);
+            o.w = cmul_pack(zr[k][3], zi[k][3], tw1[k].c[3]);
+            *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Phase 3 on tiles t, t+1 of the staged layout with the factored w_L twiddle: real parts r[k], imaginary
+// parts s[k] of time samples (d_a, d_b) = (4g+j, c) of each tile.
+template <int LG>
+__device__ __forceinline__ void phase3_two_lds(const uint32_t* xb, const uint4* t1i, const uint32_t* vt,
+                                               const Consts<LG>& K, const h2 (&cF)[4], int t, int lane,
+                                               f4 (&r)[2], f4 (&s)[2])
+{
+    using C = CC<LG>;
+    const int c = lane & 15, g = lane >> 4;
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    H8U tw1[2], x[2], vv[2];
+    f4 yr[2], yi[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        tw1[k].u = t1i[(t + k) * 4 + g];
+        x[k].u = *reinterpret_cast<const uint4*>(&xb[w1 + 4 * (t + k)]);
+        vv[k].u = *reinterpret_cast<const uint4*>(&vt[(t + k) * 16 + 4 * g]);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[k].w[j] = cmul_h2(x[k].w[j], tw1[k].c[j]);
+        yr[k] = MFMA(x[k].v, K.I16.re, zero);
+        yi[k] = MFMA(x[k].v, K.I16.im, zero);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        H8U u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack_conj(yr[k][j], yi[k][j], cmul_hh(cF[j], vv[k].c[j]));
+        r[k] = MFMA(K.I16.re, u.v, zero);
+        s[k] = MFMA(K.I16.im, u.v, zero);
+    }
+}
+
+// tables of the staged layout: w_{16TC} (both directions) and w_L^(k_a t); exchange buffer cleared
+template <int LG, int NT>
+__device__ __forceinline__ void staged_tables(uint4* lds4, const uint4* gtab, const float2* __restrict__ tw, int tid,
+                                              int gap)
+{
+    using C = CC<LG>;
+    uint4* t1f = lds4 + C::XWORDS / 4 + gap;             // `gap` 16-byte units between the slots and the tables
+    uint32_t* vt = reinterpret_cast<uint32_t*>(t1f + C::TC * 8);
+    for (int i = tid; i < C::TC * 8; i += NT) t1f[i] = gtab[C::T1F + i];
+    for (int i = tid; i < C::TC * 16; i += NT) {
+        const float2 w = tw_full(tw, (uint32_t)(((i & 15) * (i >> 4)) & (C::L - 1)) << (TW_LOG2 - LG));
+        vt[i] = pack_h2(w.x, w.y);
+    }
+    for (int i = tid; i < C::XWORDS / 4; i += NT) lds4[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+// run r of a row pair -> first sample n: four lanes cover 64 contiguous bytes of a row, the next lane
+// bits pick d_a % 4 and d_b % 4, so that a wave's 4-byte LDS accesses (word stride 4 along t) spread
+// over 32 banks while global accesses keep 64-byte segments
+template <int LG>
+__device__ __forceinline__ int staged_run_n(int r)
+{
+    using C = CC<LG>;
+    constexpr int QB = C::cb - 3;
+    const int q = (r & 3) | (((r >> 6) & ((1 << (QB - 2)) - 1)) << 2);
+    const int da = ((r >> 2) & 3) | ((r >> (QB + 6)) << 2);
+    const int db = ((r >> 4) & 3) | (((r >> (QB + 4)) & 3) << 2);
+    return (da << (C::cb + 4)) + (db << C::cb) + 8 * q;
+}
+// word of sample n of the pair in the exchange buffer (consecutive samples are 4 words apart)
+template <int LG>
+__device__ __forceinline__ int staged_slot(int n)
+{
+    using C = CC<LG>;
+    const int t = n & (C::TC - 1), db = (n >> C::cb) & 15, da = n >> (C::cb + 4);
+    return (db * C::PITCH + (da >> 2) * C::TC + t) * 4 + (da & 3);
+}
+
 template <int LG>
 size_t coop_real_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16 + (size_t)CC<LG>::TC * 16 * 4; }
 
@@ -729,6 +854,306 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         __syncthreads();
         drain(it);
         if (more) stage();
+    }
+}
+
+// wait until at most n of this wave's vector-memory operations are outstanding (n < 16)
+template <int n>
+__device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_waitcnt((n & 15) | (7 << 4) | (15 << 8)); }
+
+// -------------------------------------------------------------------------------------
+// dk and dD of real row pairs (single-pass plan) on the staged layout.  grid = H; the workgroup of a
+// head walks its row pairs: u pair -> phase 1 -> forward half of phase 2 -> Z (fp16 registers); dy
+// pair likewise -> W; A += conj(Z) W in fp32 registers, eight phase-2 tiles per wave.
+// The accumulators leave no registers to hold a prefetched pair, so the next source is copied from
+// global memory straight into a raw LDS area (global_load ... lds: 1 KiB per wave instruction, no
+// registers) while the current one is transformed, and moved from there into the exchange slots.
+//
+// SPLIT: the row length N equals the transform length 2^LG of this instantiation, i.e. the padded
+// length is 2 * 2^LG, twice what the accumulators of one workgroup cover.  The outermost radix-2 step
+// of the padded transform is then taken in time (Section 3.2, one more application of the butterfly
+// decomposition, with the zero half dropped): bins of parity s of the padded row are the 2^LG-point
+// transform of u[n] w_{2N}^(s n).  The batch is walked once per parity with that twist applied while
+// staging; dk[n] = Re(a_0[n] + conj(w_{2N}^n) a_1[n]) / 2 with a_s the inverse transform of parity s,
+// the first term parked in dk itself by the lane that later completes it.
+// -------------------------------------------------------------------------------------
+template <int LG, bool SPLIT>
+size_t coop_dk_real_lds_bytes()
+{
+    using C = CC<LG>;
+    const size_t rown = SPLIT ? C::L : C::L / 2;
+    // slots, raw rows (64 bytes of padding per 2 TC runs), tables, SPLIT: twist of every run start
+    return (size_t)C::XWORDS * 4 + rown * 4 + (2 * rown / 8 / (2 * C::TC)) * 64 + (size_t)C::TC * 8 * 16 +
+           (size_t)C::TC * 16 * 4 + (SPLIT ? rown / 8 * 4 : 0);
+}
+
+template <int LG, class IO, bool SPLIT>
+__global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
+                    float* __restrict__ dk, float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs,
+                    float dkscale, float dDscale, const float2* __restrict__ tw,
+                    const unsigned char* __restrict__ ctab)
+{
+    using C = CC<LG>;
+    using T = typename IO::T;
+    static_assert(C::NG == 1, "one group of eight phase-2 tiles per wave");
+    constexpr int NT = C::NW * 64;
+    constexpr int ROWN = SPLIT ? C::L : C::L / 2;      // samples per row
+    constexpr int RPL = ROWN / 8 / NT;                 // 16-byte runs of one row per lane
+    constexpr int NCP = 2 * ROWN * 2 / 1024 / C::NW;   // 1 KiB copy instructions per wave and source
+    constexpr int NPAR = SPLIT ? 2 : 1;
+    extern __shared__ uint4 lds4[];
+    __shared__ float red[C::NW];
+    uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
+    // raw rows as copied, [2 rows][ROWN] I/O elements in 16-byte runs; run i sits at unit i + 4 (i / 2TC):
+    // the shift spreads the staging reads (lanes 2 TC runs apart) over the banks
+    constexpr int RAWU = 2 * ROWN / 8 + (2 * ROWN / 8 / (2 * C::TC)) * 4;
+    uint4* raw = lds4 + C::XWORDS / 4;
+    uint4* t1f = raw + RAWU;
+    uint4* t1i = t1f + C::TC * 4;
+    uint32_t* vt = reinterpret_cast<uint32_t*>(t1i + C::TC * 4);
+    uint32_t* twr = vt + C::TC * 16;                   // SPLIT: w_{2N}^n at every run start n = 8 i
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int h = blockIdx.x;
+    const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
+    Consts<LG> K;
+    make_consts<LG>(K, tw, lane);
+    h2 cF[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 w = tw_full(tw, (uint32_t)((c * (4 * g + j)) & 255) << (TW_LOG2 - 8));
+        cF[j] = h2{(_Float16)w.x, (_Float16)w.y};
+    }
+    // first-stage matrix: without the split the slots of the zero padding hold stale (finite) values of
+    // the previous source, so their rows are cleared instead
+    Mats F1 = K.F16;
+    if (!SPLIT && g >= 2) {
+        const h8 z8 = {0, 0, 0, 0, 0, 0, 0, 0};
+        F1.re = z8;
+        F1.im = z8;
+    }
+
+    const int nsrc = NPAR * npairs * 2;                  // sources in order: parity, pair, (u, dy)
+    // copy source sidx into the raw area: wave w takes every NW-th KiB (row b after row a; a missing
+    // row b copies row a again and is read as zero)
+    auto copy_in = [&](int sidx) {
+        const int p = (sidx >> 1) % npairs;
+        const char* src = reinterpret_cast<const char*>((sidx & 1) ? dy : u);
+        const bool has_b = (2 * p + 1) < B;
+        const char* pa = src + row_off(2 * p, h, H, N) * sizeof(T);
+        const char* pb = src + row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N) * sizeof(T);
+#pragma unroll
+        for (int q = 0; q < NCP; ++q) {
+            const int kib = q * C::NW + wave;                              // wave-uniform
+            const int row = kib / (ROWN * 2 / 1024), part = kib - row * (ROWN * 2 / 1024);
+            const char* s = (row ? pb : pa) + part * 1024 + lane * 16;
+            uint4* dst = raw + kib * 64 + (kib * 64 / (2 * C::TC)) * 4;
+            const uint32_t lds_off =
+                __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)dst);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(lds_off), "v"(s) : "memory", "m0");
+        }
+    };
+    // raw area -> exchange slots (pair packing, bf16 -> fp16, twist)
+    auto stage = [&](int sidx) {
+        const int p = (sidx >> 1) % npairs;
+        const bool has_b = (2 * p + 1) < B;
+        const bool odd = SPLIT && sidx >= 2 * npairs;
+        int t_ = tid;
+        asm volatile("" : "+v"(t_));                 // addresses are recomputed here, not carried through the walk
+#pragma unroll
+        for (int i = 0; i < RPL; ++i) {
+            const int n = staged_run_n<LG>(i * NT + t_);
+            const int ia = n / 8, ib = (ROWN + n) / 8;
+            const uint4 va = raw[ia + (ia / (2 * C::TC)) * 4], vb = raw[ib + (ib / (2 * C::TC)) * 4];
+            uint32_t wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
+            if (!has_b) {
+#pragma unroll
+                for (int m = 0; m < 4; ++m) wb[m] = 0u;
+            }
+            if (IsBf<IO>::v) {
+#pragma unroll
+                for (int m = 0; m < 4; ++m) { wa[m] = bf2_to_h2(wa[m]); wb[m] = bf2_to_h2(wb[m]); }
+            }
+            uint32_t x[8];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                x[2 * m] = __builtin_amdgcn_perm(wb[m], wa[m], 0x05040100u);
+                x[2 * m + 1] = __builtin_amdgcn_perm(wb[m], wa[m], 0x07060302u);
+            }
+            if (SPLIT && odd) {
+                union { uint32_t u; h2 h; } bw;
+                bw.u = twr[n / 8];
+                const h2 base = bw.h;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float ang = -3.14159265358979323846f * (float)e / (float)ROWN;
+                    const h2 we = {(_Float16)__builtin_cosf(ang), (_Float16)__builtin_sinf(ang)};
+                    x[e] = cmul_h2(x[e], cmul_hh(base, we));
+                }
+            }
+            const int a0 = staged_slot<LG>(n);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xb[a0 + 4 * e] = x[e];
+        }
+    };
+
+    const int t0 = wave * 8;                             // this wave's tiles in every phase
+    float2 acc[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = make_float2(0.f, 0.f);
+    float dsum = 0.f;
+
+    staged_tables<LG, NT>(lds4, gtab, tw, tid, RAWU);
+    if (SPLIT) {
+        for (int i = tid; i < ROWN / 8; i += NT) {
+            const float2 w = tw_full(tw, (uint32_t)(8 * i) << (TW_LOG2 - LG - 1));
+            twr[i] = pack_h2(w.x, w.y);
+        }
+    }
+    __syncthreads();                                     // cleared slots before the first copy lands beside them
+    copy_in(0);
+
+    int sidx = 0;
+#pragma unroll 1
+    for (int par = 0; par < NPAR; ++par) {
+#pragma unroll 1
+        for (int p = 0; p < npairs; ++p) {
+            uint32_t z[8][4];
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass, ++sidx) {
+                int zoff = 0;
+                asm volatile("" : "+v"(zoff));               // table reads stay inside the walk
+                const uint4* t1f_ = t1f + zoff;
+                const uint32_t* vt_ = vt + zoff;
+                wait_vm<0>();                            // this wave's share of the copy has landed
+                __syncthreads();                         // ... and everyone's; the slots are free
+                stage(sidx);
+                __syncthreads();                         // staged source visible, raw area free
+                if (sidx + 1 < nsrc) copy_in(sidx + 1);
+                phase1_inplace<LG, 2>(xb, t1f_, vt_, F1, K, cF, t0, lane);
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    f4 zr, zi;
+                    phase2_fwd<LG>(xb, phase2_base<LG>(t0 + i, lane), K, zr, zi);
+                    if (pass == 0) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) z[i][j] = pack_h2(zr[j], zi[j]);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            union { uint32_t u; h2 hh; } cv;
+                            cv.u = z[i][j];
+                            const float a = (float)cv.hh[0], b = (float)cv.hh[1];
+                            acc[i][j].x += a * zr[j] + b * zi[j];      // conj(Z) * W
+                            acc[i][j].y += a * zi[j] - b * zr[j];
+                        }
+                    }
+                    if (i & 1) __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        // ---- end of a walk: inverse half of phase 2, phase 3, dk
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dsum += acc[i][j].x;
+        if (dk) {
+            // constants of the inverse direction are built here, not kept through the walk; nothing
+            // below is hoisted out of the parity loop
+            const float2* tw2 = tw;
+            int lane2 = lane;
+            asm volatile("" : "+s"(tw2), "+v"(lane2));
+            const int c2 = lane2 & 15, g2 = lane2 >> 4;
+            Consts<LG> Ki;
+            make_consts<LG>(Ki, tw2, lane2);
+            __syncthreads();                             // every wave is done reading the slots
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                H8U m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(acc[i][j].x, acc[i][j].y);
+                phase2_inv<LG>(xb, phase2_base<LG>(t0 + i, lane2), Ki, m);
+            }
+            __syncthreads();
+            // phase 3 leaves the real part (SPLIT, parity 1: of a conj(w_{2N}^n), the twist from the table
+            // of run starts times a constant) as fp32 in the slot word of each sample, in place
+            float2 bw[4];
+            if (SPLIT && par == 1) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    union { uint32_t u; h2 hh; } cv;
+                    cv.u = twr[(((4 * g2 + j) * 16 + c2) * C::TC + t0) >> 3];
+                    bw[j] = make_float2((float)cv.hh[0], (float)cv.hh[1]);
+                }
+            }
+            const int w1 = (c2 * C::PITCH + g2 * C::TC) * 4;
+#pragma unroll
+            for (int tb = 0; tb < 8; tb += 2) {
+                f4 r[2], s2[2];
+                phase3_two_lds<LG>(xb, t1i, vt, Ki, cF, t0 + tb, lane2, r, s2);
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    float v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        v[j] = r[k][j];
+                        if (SPLIT && par == 1) {
+                            const float ang = -3.14159265358979323846f * (float)(tb + k) / (float)ROWN;
+                            const float ex = __builtin_cosf(ang), ey = __builtin_sinf(ang);
+                            const float wx = bw[j].x * ex - bw[j].y * ey, wy = bw[j].x * ey + bw[j].y * ex;
+                            v[j] = r[k][j] * wx + s2[k][j] * wy;             // Re(a conj(w))
+                        }
+                    }
+                    *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) =
+                        make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+                }
+                __builtin_amdgcn_sched_barrier(0);       // one tile pair at a time (register pressure)
+            }
+            __syncthreads();
+            // slots -> dk in unit-stride 32-byte runs
+            int t_ = lane2 + (tid - lane);
+            asm volatile("" : "+v"(t_));
+#pragma unroll
+            for (int i = 0; i < RPL; ++i) {
+                const int n = staged_run_n<LG>(i * NT + t_);
+                const int a0 = staged_slot<LG>(n);
+                float4* dst = reinterpret_cast<float4*>(dk + (size_t)h * N + n);
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = __uint_as_float(xb[a0 + 4 * e]);
+                if (SPLIT && par == 1) {
+                    const float4 l0 = dst[0], h0 = dst[1];                   // parity 0, parked by this lane
+                    v[0] += l0.x; v[1] += l0.y; v[2] += l0.z; v[3] += l0.w;
+                    v[4] += h0.x; v[5] += h0.y; v[6] += h0.z; v[7] += h0.w;
+                }
+                if (!SPLIT || par == 1) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] *= dkscale;
+                }
+                dst[0] = make_float4(v[0], v[1], v[2], v[3]);
+                dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = make_float2(0.f, 0.f);
+    }
+
+    if (dD) {
+        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+        if (lane == 0) red[wave] = dsum;
+        __syncthreads();
+        if (tid == 0) {
+            float t = 0.f;
+            for (int w = 0; w < C::NW; ++w) t += red[w];
+            dD[h] = t * dDscale;
+        }
     }
 }
 
@@ -1067,6 +1492,26 @@ hipError_t coop_dk_go(const void* dy, const void* u, float* dk, float* dD, const
     return hipGetLastError();
 }
 
+template <int LG, class IO, bool SPLIT>
+hipError_t coop_dk_real_go(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Tables& tb,
+                           hipStream_t st)
+{
+    using T = typename IO::T;
+    using C = CC<LG>;
+    const size_t lds = coop_dk_real_lds_bytes<LG, SPLIT>();
+    const int shift = 6 + (C::te >= 2 ? 1 : 0);      // three radix-16 stages (1/4 each) and F_TE
+    // two forward chains and one inverse chain, each scaled by 2^-shift; 1 / padded length
+    const float dkscale = (float)(int64_t(1) << (3 * shift)) / (float)(2 * pr.N);
+    const float dDscale = dkscale / (float)(1 << shift);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_dk_real_kernel<LG, IO, SPLIT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((coop_dk_real_kernel<LG, IO, SPLIT>), dim3((unsigned)pr.H), dim3(C::NW * 64), lds, st,
+                       (const T*)dy, (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, dkscale, dDscale, tb.tw,
+                       (const unsigned char*)tb.ctab);
+    return hipGetLastError();
+}
+
 template <int LG>
 hipError_t coop_kspec_go(const float* k, const __half2* ws, const float* D, const float* rs, float2* kspec,
                          int64_t H, int64_t N, const Plan& pl, const Tables& tb, hipStream_t st)
@@ -1126,6 +1571,16 @@ hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, const __
                    hipStream_t st)
 {
 #define GO(LG, IO) return coop_dk_go<LG, IO>(dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, zbuf, pr, pl, tb, st)
+#define GOR(LG, IO, SPLIT) return coop_dk_real_go<LG, IO, SPLIT>(dy, u, dk, dD, pr, tb, st)
+    if (pl.log2R == 0 && pr.io == LONGCONV_F16) {
+        if (pl.log2L2 == 13) GOR(13, IoF16, false);
+        if (pl.log2L2 == 14) GOR(14, IoF16, false);
+        if (pl.log2L2 == 15) GOR(14, IoF16, true);
+    } else if (pl.log2R == 0 && pr.io == LONGCONV_BF16) {
+        if (pl.log2L2 == 13) GOR(13, IoBF16, false);
+        if (pl.log2L2 == 14) GOR(14, IoBF16, false);
+        if (pl.log2L2 == 15) GOR(14, IoBF16, true);
+    }
     if (pr.io == LONGCONV_F16) {
         if (pl.log2L2 == 13) GO(13, IoF16);
         if (pl.log2L2 == 14) GO(14, IoF16);
@@ -1136,6 +1591,7 @@ hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, const __
         if (pl.log2L2 == 15) GO(15, IoBF16);
     }
 #undef GO
+#undef GOR
     return hipErrorInvalidValue;
 }
 
