@@ -1354,9 +1354,28 @@ coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, c
     for (int i = tid; i < C::TC * 8; i += C::NW * 64) t1f[i] = gtab[C::T1F + i];
     Consts<LG> K;
     make_consts<LG>(K, tw, lane);
-    __syncthreads();
-    const float r = head_scale_of(rs[h]);
     const float* kr = k + (size_t)h * N;
+    // per-head power-of-two pre-scale: from the caller's per-head maxima (multi-pass: pass A used the same
+    // scale), else from a scan of the head's kernel row here
+    float m = 0.f;
+    __shared__ float mred[C::NW];
+    if (!CPLX) {
+        const float4* k4 = reinterpret_cast<const float4*>(kr);
+        for (int i = tid; i < (int)(N / 4); i += C::NW * 64) {
+            const float4 v = k4[i];
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+        if (lane == 0) mred[wave] = m;
+    }
+    __syncthreads();
+    if (!CPLX) {
+        m = mred[0];
+        for (int w = 1; w < C::NW; ++w) m = fmaxf(m, mred[w]);
+    } else {
+        m = rs[h];
+    }
+    const float r = head_scale_of(m);
     const __half2* chunk = ws + (size_t)h * Ltot + (size_t)k1 * C::L;
 #pragma unroll
     for (int gi = 0; gi < C::NG; ++gi) {
