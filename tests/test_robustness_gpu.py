@@ -129,3 +129,27 @@ def test_step_under_graph_capture_replays_bitwise(key, B, H):
         torch.cuda.synchronize()
         for t, want in zip(outs, ref):
             assert torch.equal(t.view(torch.uint8), want.view(torch.uint8)), f"replay {r} differs"
+
+
+@pytest.mark.parametrize("N,B,H,io", [(16384, 6, 129, wl.F16), (4096, 5, 771, wl.BF16), (8192, 3, 300, wl.BF16)])
+def test_persistent_workgroups_ragged_item_count(monkeypatch, N, B, H, io):
+    """More (head, pair) items than resident workgroups, not a multiple of them, odd batch: every item must be
+    processed exactly once.  Sampled heads against the oracle, and every output element against the staged
+    in-place kernel (a different code path with one workgroup per item)."""
+    import paper_2302_06646_amd as lc
+    from gpu_harness import GpuRun, TOL, check_sampled, to_f64
+    inp = wl.generate(_w("3", N=N, dtype=io), B=B, H=H)
+    check_sampled(inp, [0, H // 2, H - 1], label=f"ragged N={N} B={B} H={H}")
+    g = GpuRun(inp)
+    y = g.fwd().copy()
+    du, dk, dD = [a.copy() for a in g.bwd()]
+    monkeypatch.setenv("LONGCONV_MFMA_KERNEL", "staged")
+    g2 = GpuRun(inp)
+    y2 = g2.fwd()
+    du2, dk2, dD2 = g2.bwd()
+    tol = 2 * TOL[io]
+    for h0 in range(0, H, 16):                      # block-wise, so that one missing head cannot hide in the norm
+        sl = slice(h0, min(H, h0 + 16))
+        assert wl.rel_l2(y[:, sl], y2[:, sl]) <= tol and wl.rel_l2(du[:, sl], du2[:, sl]) <= tol, f"heads {sl}"
+        assert wl.rel_l2(dk[sl], dk2[sl]) <= tol, f"dk heads {sl}"
+    assert wl.rel_l2(dD, dD2) <= tol
