@@ -193,36 +193,22 @@ __device__ __forceinline__ void phase1_regs(const uint32_t (&w)[4][8], uint32_t*
     phase1_core<LG, false>(w, xb, gtab, t1f, K, t0, lane);
 }
 
-// ---- phase 1 for the 8 tiles t0..t0+7 of one wave ------------------------------------
-// REAL: rows a, b of I/O elements (zero above N = L/2).  CPLX: chunk of L fp16 complex values.
-template <int LG, class IO, bool CPLX, int NB = NTB>
-__device__ __forceinline__ void phase1(const typename IO::T* ra, const typename IO::T* rb, bool has_b,
-                                       const __half2* chunk, uint32_t* xb, const uint4* gtab, const uint4* t1f,
+// ---- phase 1 for the 8 tiles t0..t0+7 of one wave, operands from a chunk of L fp16 complex values
+// (pass-A output of the multi-pass split) ------------------------------------------------------
+template <int LG, int NB = NTB>
+__device__ __forceinline__ void phase1(const __half2* chunk, uint32_t* xb, const uint4* gtab, const uint4* t1f,
                                        const Consts<LG>& K, int t0, int lane)
 {
     using C = CC<LG>;
     const int c = lane & 15, g = lane >> 4;
-    uint32_t w[4][8];       // CPLX: [j][tile] complex words; REAL: [j][0..3] row a pairs, [j][4..7] row b pairs
+    uint32_t w[4][8];       // [j][tile] complex words
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
-        if (CPLX) {
-            load_words<4>(chunk + n0, &w[j][0]);
-            load_words<4>(chunk + n0 + 4, &w[j][4]);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) w[j][i] = 0u;
-            if (g < 2) {
-                load_words<4>(ra + n0, &w[j][0]);
-                if (has_b) load_words<4>(rb + n0, &w[j][4]);
-                if (IsBf<IO>::v) {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) w[j][i] = bf2_to_h2(w[j][i]);
-                }
-            }
-        }
+        load_words<4>(chunk + n0, &w[j][0]);
+        load_words<4>(chunk + n0 + 4, &w[j][4]);
     }
-    phase1_core<LG, CPLX, NB>(w, xb, gtab, t1f, K, t0, lane);
+    phase1_core<LG, true, NB>(w, xb, gtab, t1f, K, t0, lane);
 }
 
 // word address of (tile t2, reg 0) for this lane in phase 2; reg j adds j*TE*4 words
@@ -318,18 +304,16 @@ __device__ __forceinline__ void phase3_two(const uint32_t* xb, const uint4* gtab
 }
 
 // -------------------------------------------------------------------------------------
-// Fused convolution.  grid = (pair slots, H, R); a workgroup loops over the pairs p = blockIdx.x,
-// blockIdx.x + gridDim.x, ... of head h (chunk k1 of each in the multi-pass split).
+// Inner convolution of the multi-pass split: chunk k1 (L fp16 complex values of pass A's output) of every row
+// pair, in place in the workspace.  grid = pair slots x H x R; a workgroup loops over the pairs p = slot,
+// slot + gx, ... of its (head, chunk).
 // -------------------------------------------------------------------------------------
-template <int LG, class IO, bool CPLX, int NWV, int NB>
-__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(NWV >= 16 ? 4 : 2)))
-coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
-                 typename IO::T* __restrict__ out, __half2* __restrict__ ws, int conj, int64_t B, int64_t H,
-                 int64_t N, int npairs, int log2R, int gx, const float2* __restrict__ tw,
-                 const unsigned char* __restrict__ ctab)
+template <int LG, int NWV, int NB>
+__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
+coop_conv_kernel(const float2* __restrict__ kspec, __half2* __restrict__ ws, int conj, int npairs, int log2R, int gx,
+                 const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
-    using T = typename IO::T;
     extern __shared__ uint4 lds4[];
     uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
     uint4* t1f = lds4 + C::XWORDS / 4;
@@ -360,13 +344,11 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     for (int p = p0; p < npairs; p += gx) {
         // table and spectrum loads stay inside the loop (hoisting them costs more registers than a wave has)
         asm volatile("" : "+s"(gtab), "+s"(ks));
-        const bool has_b = (2 * p + 1) < B;
-        const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
         __half2* chunk = ws + ((size_t)h * npairs + p) * Ltot + (size_t)k1 * C::L;
 
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi) {
-            phase1<LG, IO, CPLX, NB>(in + oa, in + ob, has_b, chunk, xb, gtab, t1f, K, (gi * NWV + wave) * 8, lane);
+            phase1<LG, NB>(chunk, xb, gtab, t1f, K, (gi * NWV + wave) * 8, lane);
             __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds register pressure
         }
         __syncthreads();
@@ -409,36 +391,23 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi) {
         const int t0 = (gi * NWV + wave) * 8;
-        uint32_t ow[4][8];     // REAL: [j][0..3] row a, [4..7] row b; CPLX: [j][tile]
+        uint32_t ow[4][8];     // [j][tile]
 #pragma unroll
         for (int tb = 0; tb < 8; tb += 2) {
             f4 r[2], s[2];
             phase3_two<LG>(xb, gtab, t1i, K, t0 + tb, lane, r, s);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (CPLX) {
-                    ow[j][tb] = pack_h2(r[0][j], s[0][j]);
-                    ow[j][tb + 1] = pack_h2(r[1][j], s[1][j]);
-                } else if (IsBf<IO>::v) {
-                    ow[j][tb >> 1] = pack_bf2(r[0][j], r[1][j]);
-                    ow[j][4 + (tb >> 1)] = pack_bf2(s[0][j], s[1][j]);
-                } else {
-                    ow[j][tb >> 1] = pack_h2(r[0][j], r[1][j]);
-                    ow[j][4 + (tb >> 1)] = pack_h2(s[0][j], s[1][j]);
-                }
+                ow[j][tb] = pack_h2(r[0][j], s[0][j]);
+                ow[j][tb + 1] = pack_h2(r[1][j], s[1][j]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
-            if (CPLX) {
-                store_words<4>(chunk + n0, &ow[j][0]);
-                store_words<4>(chunk + n0 + 4, &ow[j][4]);
-            } else if (g < 2) {
-                store_words<4>(out + oa + n0, &ow[j][0]);
-                if (has_b) store_words<4>(out + ob + n0, &ow[j][4]);
-            }
+            store_words<4>(chunk + n0, &ow[j][0]);
+            store_words<4>(chunk + n0 + 4, &ow[j][4]);
         }
         __builtin_amdgcn_sched_barrier(0);
         }
@@ -1158,27 +1127,23 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
 }
 
 // -------------------------------------------------------------------------------------
-// dk and dD: one workgroup per (head, chunk) loops over all row pairs of the head in order.
-// Per pair: Z = transform of the u pair (kept as fp16 in registers), W = transform of the dy
-// pair, A += conj(Z) W in fp32 registers, in the lane order of phase 2; then the inverse half of
-// phase 2 and phase 3 give dk (real part).  A wave holds Z and A for 8 phase-2 tiles at a time.
+// dk and dD of the multi-pass split: one workgroup per (head, chunk k1) loops over all row pairs of the
+// head in order, reading chunk k1 of pass A's outputs.  Per pair: Z = transform of the u chunk (kept as
+// fp16 in registers), W = transform of the dy chunk, A += conj(Z) W in fp32 registers, in the lane order
+// of phase 2; then the inverse half of phase 2 and phase 3 give the chunk that pass C turns into dk.  A wave holds Z and A for 8 phase-2 tiles at a time.
 // With NG > 1 tile groups per wave (L = 32768) the batch is walked once per group (the second
 // walk finds its rows in cache), and the inverse half-spectrum of every group but the last is
 // parked in the caller's workspace (`zbuf`, written and read once per head) until phase 3:
 // registers for all groups at once do not exist, and parking Z per pair instead costs an order
 // of magnitude more memory traffic than the second walk.
 // -------------------------------------------------------------------------------------
-template <int LG, class IO, bool CPLX>
+template <int LG>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
-coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u, float* __restrict__ dk,
-               float* __restrict__ dD, const __half2* __restrict__ ws_u, const __half2* __restrict__ ws_dy,
-               __half2* __restrict__ ws_A, float* __restrict__ dD_part, uint4* __restrict__ zbuf, int64_t B,
-               int64_t H, int64_t N,
-               int npairs, int log2R, float dkscale, float dDscale, const float2* __restrict__ tw,
-               const unsigned char* __restrict__ ctab)
+coop_dk_kernel(const __half2* __restrict__ ws_u, const __half2* __restrict__ ws_dy, __half2* __restrict__ ws_A,
+               float* __restrict__ dD_part, uint4* __restrict__ zbuf, int npairs, int log2R, float dDscale,
+               const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
-    using T = typename IO::T;
     constexpr int NB = 2;      // phase-1 tiles in flight (the accumulators leave no room for more)
     extern __shared__ uint4 lds4[];
     __shared__ float red[C::NW];
@@ -1209,19 +1174,15 @@ coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __re
 
         for (int p = 0; p < npairs; ++p) {
             asm volatile("" : "+s"(gtab));
-            const bool has_b = (2 * p + 1) < B;
-            const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
             const size_t coff = ((size_t)h * npairs + p) * Ltot + (size_t)k1 * C::L;
             uint32_t z[8][4];
 #pragma unroll
             for (int pass = 0; pass < 2; ++pass) {     // 0: u pair -> Z, 1: dy pair -> W
                 asm volatile("" : "+s"(gtab));
-                const T* src = pass == 0 ? u : dy;
                 const __half2* csrc = pass == 0 ? ws_u : ws_dy;
 #pragma unroll 1
                 for (int g2 = 0; g2 < ng; ++g2) {
-                    phase1<LG, IO, CPLX, NB>(src + oa, src + ob, has_b, csrc + coff, xb, gtab, t1f, K,
-                                             (g2 * C::NW + wave) * 8, lane);
+                    phase1<LG, NB>(csrc + coff, xb, gtab, t1f, K, (g2 * C::NW + wave) * 8, lane);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 __syncthreads();
@@ -1252,7 +1213,7 @@ coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __re
         for (int i = 0; i < 8; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) dsum += acc[i][j].x;
-        if (dk) {
+        if (ws_A) {
             // inverse half of phase 2: the last group goes to the exchange buffer, earlier ones are parked
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -1270,18 +1231,17 @@ coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __re
         }
     }
 
-    if (dD || dD_part) {
+    if (dD_part) {
         for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
         if (lane == 0) red[wave] = dsum;
         __syncthreads();
         if (tid == 0) {
             float t = 0.f;
             for (int w = 0; w < C::NW; ++w) t += red[w];
-            if (log2R == 0) { if (dD) dD[h] = t * dDscale; }
-            else dD_part[(size_t)h * gridDim.y + k1] = t * dDscale;
+            dD_part[(size_t)h * gridDim.y + k1] = t * dDscale;
         }
     }
-    if (!dk) return;
+    if (!ws_A) return;
 
     // parked groups back into the exchange buffer (each lane reads what it wrote itself)
     for (int gi = 0; gi + 1 < ng; ++gi)
@@ -1300,7 +1260,7 @@ coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __re
     for (int gi = 0; gi < ng; ++gi) {
         const int t0 = (gi * C::NW + wave) * 8;
         // 8 tiles = 8 consecutive samples per (lane, j): stored as 32-byte runs
-        uint32_t oc[4][8];     // CPLX: fp16 complex words ; otherwise the bits of the scaled real parts
+        uint32_t oc[4][8];     // fp16 complex words
 #pragma unroll
         for (int tb = 0; tb < 8; tb += 2) {
             f4 r[2], s[2];
@@ -1309,20 +1269,14 @@ coop_dk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __re
             for (int k = 0; k < 2; ++k)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    oc[j][tb + k] = CPLX ? pack_h2(r[k][j], s[k][j]) : __float_as_uint(r[k][j] * dkscale);
+                    oc[j][tb + k] = pack_h2(r[k][j], s[k][j]);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
-            if (CPLX) {
-                uint4* dst = reinterpret_cast<uint4*>(achunk + n0);
-                dst[0] = make_uint4(oc[j][0], oc[j][1], oc[j][2], oc[j][3]);
-                dst[1] = make_uint4(oc[j][4], oc[j][5], oc[j][6], oc[j][7]);
-            } else if (g < 2) {
-                uint4* dst = reinterpret_cast<uint4*>(dk + (size_t)h * N + n0);
-                dst[0] = make_uint4(oc[j][0], oc[j][1], oc[j][2], oc[j][3]);
-                dst[1] = make_uint4(oc[j][4], oc[j][5], oc[j][6], oc[j][7]);
-            }
+            uint4* dst = reinterpret_cast<uint4*>(achunk + n0);
+            dst[0] = make_uint4(oc[j][0], oc[j][1], oc[j][2], oc[j][3]);
+            dst[1] = make_uint4(oc[j][4], oc[j][5], oc[j][6], oc[j][7]);
         }
     }
 }
@@ -1381,7 +1335,7 @@ coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, c
     for (int gi = 0; gi < C::NG; ++gi) {
         const int t0 = (gi * C::NW + wave) * 8;
         if (CPLX) {
-            phase1<LG, IoF16, true>(nullptr, nullptr, false, chunk, xb, gtab, t1f, K, t0, lane);
+            phase1<LG>(chunk, xb, gtab, t1f, K, t0, lane);
         } else {
             // stage the fp32 kernel row as fp16 in registers, then the common phase 1 on them
             uint32_t w[4][8];
@@ -1431,83 +1385,66 @@ int compute_units()
     return n;
 }
 
-template <int LG, class IO>
-hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
-                        const Plan& pl, const Tables& tb, hipStream_t st)
+// work split of the staged convolution kernel: as many workgroups as the device holds at once
+template <int LG, class IO, int NWV, int NB>
+hipError_t coop_conv_real_go(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
+                             const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
-#ifndef COOP_CONV_NW
-#define COOP_CONV_NW 8
-#define COOP_CONV_NB 4
-#endif
-    constexpr int NWV = CC<LG>::TC / 8 > COOP_CONV_NW ? COOP_CONV_NW : CC<LG>::TC / 8, NB = COOP_CONV_NB;
-    const size_t lds = coop_lds_bytes<LG>();
-    const int R = 1 << pl.log2R;
-#ifndef COOP_WGS
-#define COOP_WGS 512
-#endif
-    long gx = (COOP_WGS + pr.H * R - 1) / (pr.H * R);
-    if (gx < 1) gx = 1;
-    if (gx > pr.npairs) gx = pr.npairs;
-    dim3 grid((unsigned)(gx * pr.H * R));
-    hipError_t e;
-    if (pl.log2R == 0) {
-        const size_t ldsr = coop_real_lds_bytes<LG>();
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_real_kernel<LG, IO, NWV, NB>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsr);
+    const size_t lds = coop_real_lds_bytes<LG>();
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_real_kernel<LG, IO, NWV, NB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    static int resident = 0;
+    if (resident == 0) {
+        int nb = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, coop_conv_real_kernel<LG, IO, NWV, NB>, NWV * 64, lds);
         if (e != hipSuccess) return e;
-        // as many workgroups as the device holds at once, each with a run of consecutive pairs
-        static int resident = 0;
-        if (resident == 0) {
-            int nb = 0;
-            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, coop_conv_real_kernel<LG, IO, NWV, NB>, NWV * 64, ldsr);
-            if (e != hipSuccess) return e;
-            resident = (nb > 0 ? nb : 1) * compute_units();
-        }
-        const long total = pr.H * pr.npairs;
-        const int per = (int)((total + resident - 1) / resident);
-        grid = dim3((unsigned)((total + per - 1) / per));
-        hipLaunchKernelGGL((coop_conv_real_kernel<LG, IO, NWV, NB>), grid, dim3(NWV * 64), ldsr, st, (const T*)in,
-                           kspec, (T*)out, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, per, tb.tw,
-                           (const unsigned char*)tb.ctab);
-    } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, IO, true, NWV, NB>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((coop_conv_kernel<LG, IO, true, NWV, NB>), grid, dim3(NWV * 64), lds, st, (const T*)in,
-                           kspec, (T*)out, ws, conj ? 1 : 0, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, (int)gx, tb.tw,
-                           (const unsigned char*)tb.ctab);
+        resident = (nb > 0 ? nb : 1) * compute_units();
     }
+    const long total = pr.H * pr.npairs;                 // (head, pair) items, a run of `per` per workgroup
+    const int per = (int)((total + resident - 1) / resident);
+    hipLaunchKernelGGL((coop_conv_real_kernel<LG, IO, NWV, NB>), dim3((unsigned)((total + per - 1) / per)),
+                       dim3(NWV * 64), lds, st, (const T*)in, kspec, (T*)out, conj ? 1 : 0, pr.B, pr.H, pr.N,
+                       pr.npairs, per, tb.tw, (const unsigned char*)tb.ctab);
     return hipGetLastError();
 }
 
 template <int LG, class IO>
-hipError_t coop_dk_go(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
-                      __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl,
-                      const Tables& tb, hipStream_t st)
+hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
+                        const Plan& pl, const Tables& tb, hipStream_t st)
 {
-    using T = typename IO::T;
+    constexpr int NWV = CC<LG>::NW, NB = NTB;
+    if (pl.log2R == 0) return coop_conv_real_go<LG, IO, NWV, NB>(in, kspec, out, conj, pr, tb, st);
+    // multi-pass: the inner convolution on pass A's workspace; about two workgroups per compute unit in all
+    const size_t lds = coop_lds_bytes<LG>();
+    const long HR = pr.H << pl.log2R;
+    long gx = (2 * compute_units() + HR - 1) / HR;
+    if (gx < 1) gx = 1;
+    if (gx > pr.npairs) gx = pr.npairs;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, NWV, NB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((coop_conv_kernel<LG, NWV, NB>), dim3((unsigned)(gx * HR)), dim3(NWV * 64), lds, st, kspec, ws,
+                       conj ? 1 : 0, pr.npairs, pl.log2R, (int)gx, tb.tw, (const unsigned char*)tb.ctab);
+    return hipGetLastError();
+}
+
+// multi-pass dk: chunks of pass A's outputs in, chunks for pass C and partial dD sums out
+template <int LG>
+hipError_t coop_dk_go(const __half2* ws_u, const __half2* ws_dy, __half2* ws_A, float* dD_part, void* zbuf,
+                      const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
+{
     using C = CC<LG>;
     const size_t lds = coop_lds_bytes<LG>();
     dim3 grid((unsigned)pr.H, 1u << pl.log2R);
     const int shift = 6 + (C::te >= 2 ? 1 : 0);      // three radix-16 stages (1/4 each) and F_TE
     const float dDscale = pl.dkscale / (float)(1 << shift);
-    hipError_t e;
-    if (pl.log2R == 0) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_dk_kernel<LG, IO, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((coop_dk_kernel<LG, IO, false>), grid, dim3(C::NW * 64), lds, st, (const T*)dy, (const T*)u,
-                           dk, dD, ws_u, ws_dy, ws_A, dD_part, (uint4*)zbuf, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, pl.dkscale,
-                           dDscale, tb.tw, (const unsigned char*)tb.ctab);
-    } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_dk_kernel<LG, IO, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((coop_dk_kernel<LG, IO, true>), grid, dim3(C::NW * 64), lds, st, (const T*)dy, (const T*)u,
-                           dk, dD, ws_u, ws_dy, ws_A, dD_part, (uint4*)zbuf, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, pl.dkscale,
-                           dDscale, tb.tw, (const unsigned char*)tb.ctab);
-    }
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_dk_kernel<LG>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((coop_dk_kernel<LG>), grid, dim3(C::NW * 64), lds, st, ws_u, ws_dy, ws_A, dD_part, (uint4*)zbuf,
+                       pr.npairs, pl.log2R, dDscale, tb.tw, (const unsigned char*)tb.ctab);
     return hipGetLastError();
 }
 
@@ -1589,28 +1526,25 @@ hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, const __
                    __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl, const Tables& tb,
                    hipStream_t st)
 {
-#define GO(LG, IO) return coop_dk_go<LG, IO>(dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, zbuf, pr, pl, tb, st)
+    if (pl.log2R == 0) {
+        // single pass: rows straight from the caller's tensors; 32768 points as two walks of 16384
 #define GOR(LG, IO, SPLIT) return coop_dk_real_go<LG, IO, SPLIT>(dy, u, dk, dD, pr, tb, st)
-    if (pl.log2R == 0 && pr.io == LONGCONV_F16) {
-        if (pl.log2L2 == 13) GOR(13, IoF16, false);
-        if (pl.log2L2 == 14) GOR(14, IoF16, false);
-        if (pl.log2L2 == 15) GOR(14, IoF16, true);
-    } else if (pl.log2R == 0 && pr.io == LONGCONV_BF16) {
-        if (pl.log2L2 == 13) GOR(13, IoBF16, false);
-        if (pl.log2L2 == 14) GOR(14, IoBF16, false);
-        if (pl.log2L2 == 15) GOR(14, IoBF16, true);
-    }
-    if (pr.io == LONGCONV_F16) {
-        if (pl.log2L2 == 13) GO(13, IoF16);
-        if (pl.log2L2 == 14) GO(14, IoF16);
-        if (pl.log2L2 == 15) GO(15, IoF16);
-    } else if (pr.io == LONGCONV_BF16) {
-        if (pl.log2L2 == 13) GO(13, IoBF16);
-        if (pl.log2L2 == 14) GO(14, IoBF16);
-        if (pl.log2L2 == 15) GO(15, IoBF16);
-    }
-#undef GO
+        if (pr.io == LONGCONV_F16) {
+            if (pl.log2L2 == 13) GOR(13, IoF16, false);
+            if (pl.log2L2 == 14) GOR(14, IoF16, false);
+            if (pl.log2L2 == 15) GOR(14, IoF16, true);
+        } else if (pr.io == LONGCONV_BF16) {
+            if (pl.log2L2 == 13) GOR(13, IoBF16, false);
+            if (pl.log2L2 == 14) GOR(14, IoBF16, false);
+            if (pl.log2L2 == 15) GOR(14, IoBF16, true);
+        }
 #undef GOR
+        return hipErrorInvalidValue;
+    }
+    // multi-pass: ws_A is null when only dD is wanted
+    if (pl.log2L2 == 13) return coop_dk_go<13>(ws_u, ws_dy, dk ? ws_A : nullptr, dD_part, zbuf, pr, pl, tb, st);
+    if (pl.log2L2 == 14) return coop_dk_go<14>(ws_u, ws_dy, dk ? ws_A : nullptr, dD_part, zbuf, pr, pl, tb, st);
+    if (pl.log2L2 == 15) return coop_dk_go<15>(ws_u, ws_dy, dk ? ws_A : nullptr, dD_part, zbuf, pr, pl, tb, st);
     return hipErrorInvalidValue;
 }
 
