@@ -308,9 +308,9 @@ __device__ __forceinline__ void phase3_two(const uint32_t* xb, const uint4* gtab
 // pair, in place in the workspace.  grid = pair slots x H x R; a workgroup loops over the pairs p = slot,
 // slot + gx, ... of its (head, chunk).
 // -------------------------------------------------------------------------------------
-template <int LG, int NWV, int NB>
+template <int LG, int NWV, int NB, bool CONJ>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
-coop_conv_kernel(const float2* __restrict__ kspec, __half2* __restrict__ ws, int conj, int npairs, int log2R, int gx,
+coop_conv_kernel(const float2* __restrict__ kspec, __half2* __restrict__ ws, int npairs, int log2R, int gx,
                  const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
@@ -333,7 +333,6 @@ coop_conv_kernel(const float2* __restrict__ kspec, __half2* __restrict__ ws, int
     for (int i = tid; i < C::TC * 8; i += NWV * 64) t1f[i] = gtab[C::T1F + i];
     Consts<LG> K;
     make_consts<LG>(K, tw, lane);
-    const uint32_t cmask = conj ? 0x80000000u : 0u;      // sign of the imaginary (high) half
     // spectrum: fp16 complex, four bins per lane and tile in one 16-byte load
     const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)h * Ltot +
                                                      (size_t)k1 * C::L);
@@ -376,9 +375,9 @@ coop_conv_kernel(const float2* __restrict__ kspec, __half2* __restrict__ ws, int
                 H8U m;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    union { uint32_t u; h2 h; } kw;
-                    kw.u = kk[k].w[j] ^ cmask;                 // conjugate for the correlation (du)
-                    m.w[j] = cmul_pack(zr[k][j], zi[k][j], kw.h);
+                    // correlation (du): the conjugate spectrum, a sign inside the multiply
+                    m.w[j] = CONJ ? cmul_pack_conj(zr[k][j], zi[k][j], kk[k].c[j])
+                                  : cmul_pack(zr[k][j], zi[k][j], kk[k].c[j]);
                 }
                 phase2_inv<LG>(xb, base[k], K, m);
             }
@@ -435,17 +434,6 @@ __device__ __forceinline__ h2 cmul_hh(h2 a, h2 w)
     const h2 ax = {a[0], a[0]}, ay = {a[1], a[1]};
     const h2 ws = {-w[1], w[0]};
     return __builtin_elementwise_fma(ay, ws, ax * w);
-}
-// (yr + i yi) * conj(w), packed fp16
-__device__ __forceinline__ uint32_t cmul_pack_conj(float yr, float yi, h2 w)
-{
-    const f2 v = {yr, yi};
-    const h2 y = __builtin_convertvector(v, h2);
-    const h2 yx = {y[0], y[0]}, yy = {y[1], y[1]};
-    const h2 wc = {w[0], -w[1]}, ws = {w[1], w[0]};
-    union { h2 h; uint32_t u; } cv;
-    cv.h = __builtin_elementwise_fma(yy, ws, yx * wc);
-    return cv.u;
 }
 
 // Phase 1 in place on the staged layout, 8 tiles t0..t0+7 of one wave: each lane reads its own 16 bytes
@@ -576,10 +564,10 @@ __device__ __forceinline__ int staged_slot(int n)
 template <int LG>
 size_t coop_real_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16 + (size_t)CC<LG>::TC * 16 * 4; }
 
-template <int LG, class IO, int NWV, int NB>
+template <int LG, class IO, int NWV, int NB, bool CONJ>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
-                      typename IO::T* __restrict__ out, int conj, int64_t B, int64_t H, int64_t N, int npairs,
+                      typename IO::T* __restrict__ out, int64_t B, int64_t H, int64_t N, int npairs,
                       int per, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
@@ -607,7 +595,6 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         const float2 w = tw_full(tw, (uint32_t)((c * (4 * g + j)) & 255) << (TW_LOG2 - 8));
         cF[j] = h2{(_Float16)w.x, (_Float16)w.y};
     }
-    const uint32_t cmask = conj ? 0x80000000u : 0u;
     int ng = C::TC / (8 * NWV);
     asm volatile("" : "+s"(ng));
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
@@ -767,9 +754,9 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
                 H8U m;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    union { uint32_t u; h2 h; } kw;
-                    kw.u = kk[k].w[j] ^ cmask;
-                    m.w[j] = cmul_pack(zr[k][j], zi[k][j], kw.h);
+                    // correlation (du): the conjugate spectrum, a sign inside the multiply
+                    m.w[j] = CONJ ? cmul_pack_conj(zr[k][j], zi[k][j], kk[k].c[j])
+                                  : cmul_pack(zr[k][j], zi[k][j], kk[k].c[j]);
                 }
                 phase2_inv<LG>(xb, base[k], K, m);
             }
@@ -1386,26 +1373,26 @@ int compute_units()
 }
 
 // work split of the staged convolution kernel: as many workgroups as the device holds at once
-template <int LG, class IO, int NWV, int NB>
-hipError_t coop_conv_real_go(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
+template <int LG, class IO, int NWV, int NB, bool CONJ>
+hipError_t coop_conv_real_go(const void* in, const float2* kspec, void* out, const Problem& pr,
                              const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
     const size_t lds = coop_real_lds_bytes<LG>();
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_real_kernel<LG, IO, NWV, NB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_real_kernel<LG, IO, NWV, NB, CONJ>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     static int resident = 0;
     if (resident == 0) {
         int nb = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, coop_conv_real_kernel<LG, IO, NWV, NB>, NWV * 64, lds);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, coop_conv_real_kernel<LG, IO, NWV, NB, CONJ>, NWV * 64, lds);
         if (e != hipSuccess) return e;
         resident = (nb > 0 ? nb : 1) * compute_units();
     }
     const long total = pr.H * pr.npairs;                 // (head, pair) items, a run of `per` per workgroup
     const int per = (int)((total + resident - 1) / resident);
-    hipLaunchKernelGGL((coop_conv_real_kernel<LG, IO, NWV, NB>), dim3((unsigned)((total + per - 1) / per)),
-                       dim3(NWV * 64), lds, st, (const T*)in, kspec, (T*)out, conj ? 1 : 0, pr.B, pr.H, pr.N,
+    hipLaunchKernelGGL((coop_conv_real_kernel<LG, IO, NWV, NB, CONJ>), dim3((unsigned)((total + per - 1) / per)),
+                       dim3(NWV * 64), lds, st, (const T*)in, kspec, (T*)out, pr.B, pr.H, pr.N,
                        pr.npairs, per, tb.tw, (const unsigned char*)tb.ctab);
     return hipGetLastError();
 }
@@ -1415,19 +1402,24 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
                         const Plan& pl, const Tables& tb, hipStream_t st)
 {
     constexpr int NWV = CC<LG>::NW, NB = NTB;
-    if (pl.log2R == 0) return coop_conv_real_go<LG, IO, NWV, NB>(in, kspec, out, conj, pr, tb, st);
+    if (pl.log2R == 0)
+        return conj ? coop_conv_real_go<LG, IO, NWV, NB, true>(in, kspec, out, pr, tb, st)
+                    : coop_conv_real_go<LG, IO, NWV, NB, false>(in, kspec, out, pr, tb, st);
     // multi-pass: the inner convolution on pass A's workspace; about two workgroups per compute unit in all
     const size_t lds = coop_lds_bytes<LG>();
     const long HR = pr.H << pl.log2R;
     long gx = (2 * compute_units() + HR - 1) / HR;
     if (gx < 1) gx = 1;
     if (gx > pr.npairs) gx = pr.npairs;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_kernel<LG, NWV, NB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((coop_conv_kernel<LG, NWV, NB>), dim3((unsigned)(gx * HR)), dim3(NWV * 64), lds, st, kspec, ws,
-                       conj ? 1 : 0, pr.npairs, pl.log2R, (int)gx, tb.tw, (const unsigned char*)tb.ctab);
-    return hipGetLastError();
+    auto launch = [&](auto kern) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3((unsigned)(gx * HR)), dim3(NWV * 64), lds, st, kspec, ws, pr.npairs, pl.log2R,
+                           (int)gx, tb.tw, (const unsigned char*)tb.ctab);
+        return hipGetLastError();
+    };
+    return conj ? launch(coop_conv_kernel<LG, NWV, NB, true>) : launch(coop_conv_kernel<LG, NWV, NB, false>);
 }
 
 // multi-pass dk: chunks of pass A's outputs in, chunks for pass C and partial dD sums out

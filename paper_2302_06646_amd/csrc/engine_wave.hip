@@ -249,10 +249,10 @@ __device__ __forceinline__ int phase2_addr(int t2, int j, int lane)
 // Fused convolution.  Each wave processes `gpw` consecutive groups of PB row pairs (groups are
 // numbered head-major).  block = NWV waves.
 // -------------------------------------------------------------------------------------
-template <int LG, class IO, int PB, int NWV>
+template <int LG, class IO, int PB, int NWV, bool CONJ>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
-             typename IO::T* __restrict__ out, int conj, int64_t B, int64_t H, int64_t N, int gph,
+             typename IO::T* __restrict__ out, int64_t B, int64_t H, int64_t N, int gph,
              int total_groups, int gpw, const unsigned char* __restrict__ wtab)
 {
     using C = WC<LG>;
@@ -307,7 +307,6 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
     }
     uint32_t* xb = lds + C::TAB_U4 * 4 + wave * (PB * C::PAIR_WORDS);
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
-    const uint32_t cmask = conj ? 0x80000000u : 0u;      // sign of the imaginary (high) half
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
 
     for (int gi_ = 0; gi_ < gpw; ++gi_) {
@@ -343,8 +342,6 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
 #pragma unroll
                 for (int j = 0; j < 4; ++j) ad[k][j] = phase2_addr<LG>(t2, j, lane);
                 kk[k].u = ks[t2 * 64 + lane];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) kk[k].w[j] ^= cmask;        // conjugate for the correlation (du)
             }
 #pragma unroll
             for (int k = 0; k < NT; ++k)
@@ -363,7 +360,9 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
                 for (int q = 0; q < PB; ++q) {
                     H8U m;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) m.w[j] = cmul_pack(yr[k][q][j], yi[k][q][j], kk[k].c[j]);
+                    for (int j = 0; j < 4; ++j)       // correlation (du): the conjugate spectrum
+                        m.w[j] = CONJ ? cmul_pack_conj(yr[k][q][j], yi[k][q][j], kk[k].c[j])
+                                      : cmul_pack(yr[k][q][j], yi[k][q][j], kk[k].c[j]);
                     zr[k][q] = MFMA(IL.re, m.v, zero);
                     zi[k][q] = MFMA(IL.im, m.v, zero);
                 }
@@ -856,14 +855,14 @@ hipError_t wkspec_go(const float* k, const float* D, float2* kspec, int64_t H, i
     return hipGetLastError();
 }
 
-template <int LG, class IO, int PB, int NWV>
-hipError_t wconv_go(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
+template <int LG, class IO, int PB, int NWV, bool CONJ>
+hipError_t wconv_run(const void* in, const float2* kspec, void* out, const Problem& pr,
                     const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
     using C = WC<LG>;
     const size_t lds = (size_t)C::TAB_U4 * 16 + (size_t)NWV * PB * C::PAIR_WORDS * 4;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wconv_kernel<LG, IO, PB, NWV>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wconv_kernel<LG, IO, PB, NWV, CONJ>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const int gph = (pr.npairs + PB - 1) / PB;
@@ -874,10 +873,18 @@ hipError_t wconv_go(const void* in, const float2* kspec, void* out, bool conj, c
     long gpw = (total + 256 * fit * NWV - 1) / (256 * fit * NWV);
     if (gpw < 1) gpw = 1;
     const long nblk = (total + gpw * NWV - 1) / (gpw * NWV);
-    hipLaunchKernelGGL((wconv_kernel<LG, IO, PB, NWV>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st,
-                       (const T*)in, kspec, (T*)out, conj ? 1 : 0, pr.B, pr.H, pr.N, gph, (int)total, (int)gpw,
+    hipLaunchKernelGGL((wconv_kernel<LG, IO, PB, NWV, CONJ>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st,
+                       (const T*)in, kspec, (T*)out, pr.B, pr.H, pr.N, gph, (int)total, (int)gpw,
                        (const unsigned char*)tb.wtab);
     return hipGetLastError();
+}
+
+template <int LG, class IO, int PB, int NWV>
+hipError_t wconv_go(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
+                    const Tables& tb, hipStream_t st)
+{
+    return conj ? wconv_run<LG, IO, PB, NWV, true>(in, kspec, out, pr, tb, st)
+                : wconv_run<LG, IO, PB, NWV, false>(in, kspec, out, pr, tb, st);
 }
 
 template <class IO>

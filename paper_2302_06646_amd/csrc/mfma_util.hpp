@@ -51,6 +51,18 @@ __device__ __forceinline__ uint32_t cmul_pack(float yr, float yi, h2 w)
     return cv.u;
 }
 
+// (yr + i yi) * conj(w), packed fp16
+__device__ __forceinline__ uint32_t cmul_pack_conj(float yr, float yi, h2 w)
+{
+    const f2 v = {yr, yi};
+    const h2 y = __builtin_convertvector(v, h2);
+    const h2 yx = {y[0], y[0]}, yy = {y[1], y[1]};
+    const h2 wc = {w[0], -w[1]}, ws = {w[1], w[0]};
+    union { h2 h; uint32_t u; } cv;
+    cv.h = __builtin_elementwise_fma(yy, ws, yx * wc);
+    return cv.u;
+}
+
 #define MFMA(a, b, acc) __builtin_amdgcn_mfma_f32_16x16x32_f16((a), (b), (acc), 0, 0, 0)
 
 // LDS traffic between the lanes of one wave: hardware keeps a wave's LDS operations in order,
