@@ -37,14 +37,14 @@ CACHE_BYTES = 256 << 20        # last-level (Infinity) cache
 # profiles/.
 KIB = 1024
 MEASURED_TRAFFIC = {
-    "cfg2_B16_H768_N1024_bf16": {"fwd": (15879.2 * 2 + 24576.0) * KIB, "bwd_du": (15879.2 * 2 + 24576.0) * KIB,
-                                 "bwd_dk_dD": (24847.5 * 2 + 3096.0) * KIB},
+    "cfg2_B16_H768_N1024_bf16": {"fwd": (15898.8 * 2 + 24576.0) * KIB, "bwd_du": (15886.6 * 2 + 24576.0) * KIB,
+                                 "bwd_dk_dD": (24847.4 * 2 + 3096.0) * KIB},
     # (the forward kernel reads rows in 64-byte requests, which FETCH_SIZE x 2 over-counts: upper bound)
-    "cfg3_B8_H256_N16384_fp16": {"fwd": (98873.3 * 2 + 65536.0) * KIB, "bwd_du": (98873.3 * 2 + 65536.0) * KIB,
-                                 "bwd_dk_dD": (160882.3 * 2 + 54800.5) * KIB},
-    "cfg4_B1_H128_N65536_fp16": {"fwd": ((9572.2 + 67864.0 + 34152.2) * 2 + 65536.0 + 65536.0 + 16384.0) * KIB,
-                                 "bwd_du": ((9572.2 + 67864.0 + 34152.2) * 2 + 65536.0 + 65536.0 + 16384.0) * KIB,
-                                 "bwd_dk_dD": ((17770.2 + 165351.2 + 34175.9) * 2 + 131072.0 + 132405.8 + 32768.0) * KIB},
+    "cfg3_B8_H256_N16384_fp16": {"fwd": (98868.7 * 2 + 65536.0) * KIB, "bwd_du": (98870.0 * 2 + 65536.0) * KIB,
+                                 "bwd_dk_dD": (160923.0 * 2 + 54800.1) * KIB},
+    "cfg4_B1_H128_N65536_fp16": {"fwd": ((9572.2 + 67866.0 + 34152.3) * 2 + 65536.0 + 65536.0 + 16384.0) * KIB,
+                                 "bwd_du": ((9572.2 + 67866.5 + 34152.3) * 2 + 65536.0 + 65536.0 + 16384.0) * KIB,
+                                 "bwd_dk_dD": ((17771.8 + 165354.8 + 34157.0) * 2 + 131072.0 + 137715.5 + 32768.0) * KIB},
 }
 
 def log(*a):
