@@ -1005,8 +1005,9 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                             union { uint32_t u; h2 hh; } cv;
                             cv.u = z[i][j];
                             const float a = (float)cv.hh[0], b = (float)cv.hh[1];
-                            acc[i][j].x += a * zr[j] + b * zi[j];      // conj(Z) * W
-                            acc[i][j].y += a * zi[j] - b * zr[j];
+                            // conj(Z) * W, one fused multiply-add per term
+                            acc[i][j].x = __builtin_fmaf(b, zi[j], __builtin_fmaf(a, zr[j], acc[i][j].x));
+                            acc[i][j].y = __builtin_fmaf(-b, zr[j], __builtin_fmaf(a, zi[j], acc[i][j].y));
                         }
                     }
                     if (i & 1) __builtin_amdgcn_sched_barrier(0);
@@ -1186,8 +1187,9 @@ coop_dk_kernel(const __half2* __restrict__ ws_u, const __half2* __restrict__ ws_
                             union { uint32_t u; h2 hh; } cv;
                             cv.u = z[i][j];
                             const float a = (float)cv.hh[0], b = (float)cv.hh[1];
-                            acc[i][j].x += a * zr[j] + b * zi[j];      // conj(Z) * W
-                            acc[i][j].y += a * zi[j] - b * zr[j];
+                            // conj(Z) * W, one fused multiply-add per term
+                            acc[i][j].x = __builtin_fmaf(b, zi[j], __builtin_fmaf(a, zr[j], acc[i][j].x));
+                            acc[i][j].y = __builtin_fmaf(-b, zr[j], __builtin_fmaf(a, zi[j], acc[i][j].y));
                         }
                     }
                     if (i & 1) __builtin_amdgcn_sched_barrier(0);

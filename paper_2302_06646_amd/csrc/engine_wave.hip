@@ -679,8 +679,9 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
                     union { uint32_t u; h2 h; } cv;
                     cv.u = z[k][j];
                     const float zr = (float)cv.h[0], zi = (float)cv.h[1];
-                    acc[k][j].x += zr * yr[k][j] + zi * yi[k][j];      // conj(Z) * W
-                    acc[k][j].y += zr * yi[k][j] - zi * yr[k][j];
+                    // conj(Z) * W, one fused multiply-add per term (the fp16 -> fp32 converts fold into them)
+                    acc[k][j].x = __builtin_fmaf(zi, yi[k][j], __builtin_fmaf(zr, yr[k][j], acc[k][j].x));
+                    acc[k][j].y = __builtin_fmaf(-zi, yr[k][j], __builtin_fmaf(zr, yi[k][j], acc[k][j].y));
                 }
         }
     }
