@@ -564,17 +564,19 @@ __device__ __forceinline__ void load_rows(In<TPW>& r, const typename IO::T* pa, 
 {
     using C = WC<LG>;
     const int c = lane & 15, g = lane >> 4;
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int i = 0; i < TPW / 2; ++i) r.wa[j][i] = r.wb[j][i] = 0u;
-    if (g < 2) {     // samples at and above N are the zero padding
+    // samples at and above N are the zero padding: lanes g >= 2 keep the zeros the caller put there once
+    if (g < 2) {
         const int n0 = (4 * g) * 16 * C::TC + c * C::TC + t0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) load_words<TPW / 2>(pa + n0 + j * 16 * C::TC, r.wa[j]);
         if (has_b) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) load_words<TPW / 2>(pb + n0 + j * 16 * C::TC, r.wb[j]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < TPW / 2; ++i) r.wb[j][i] = 0u;
         }
     }
 }
@@ -637,6 +639,10 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
         load_rows<LG, IO, TPW>(id, dy + oa, dy + ob, has_b, t0, lane);
     };
     In<TPW> inu, ind;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < TPW / 2; ++i) inu.wa[j][i] = inu.wb[j][i] = ind.wa[j][i] = ind.wb[j][i] = 0u;
     if (grp < npairs) load_pair(grp, inu, ind);
     WK<LG, TPW> K;
     load_consts<LG, TPW>(K, wtab, t0, lane);
