@@ -304,117 +304,6 @@ __device__ __forceinline__ void phase3_two(const uint32_t* xb, const uint4* gtab
 }
 
 // -------------------------------------------------------------------------------------
-// Inner convolution of the multi-pass split: chunk k1 (L fp16 complex values of pass A's output) of every row
-// pair, in place in the workspace.  grid = pair slots x H x R; a workgroup loops over the pairs p = slot,
-// slot + gx, ... of its (head, chunk).
-// -------------------------------------------------------------------------------------
-template <int LG, int NWV, int NB, bool CONJ>
-__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
-coop_conv_kernel(const float2* __restrict__ kspec, __half2* __restrict__ ws, int npairs, int log2R, int gx,
-                 const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
-{
-    using C = CC<LG>;
-    extern __shared__ uint4 lds4[];
-    uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
-    uint4* t1f = lds4 + C::XWORDS / 4;
-    uint4* t1i = t1f + C::TC * 4;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = lane & 15, g = lane >> 4;
-    // Workgroups go to the 8 XCDs round-robin by linear id, each XCD with its own L2.  Renumber so that
-    // consecutive virtual ids share an XCD: the gx workgroups of one (head, slice) then run side by side
-    // on one L2 and its spectrum slice is fetched from HBM once.
-    const unsigned G = gridDim.x;
-    const unsigned vid = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (G >> 3) + (blockIdx.x >> 3);
-    const int p0 = (int)(vid % (unsigned)gx);
-    const int k1 = (int)((vid / (unsigned)gx) & ((1u << log2R) - 1u));
-    const int h = (int)((vid / (unsigned)gx) >> log2R);
-    const int64_t Ltot = (int64_t)C::L << log2R;
-    const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
-    for (int i = tid; i < C::TC * 8; i += NWV * 64) t1f[i] = gtab[C::T1F + i];
-    Consts<LG> K;
-    make_consts<LG>(K, tw, lane);
-    // spectrum: fp16 complex, four bins per lane and tile in one 16-byte load
-    const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)h * Ltot +
-                                                     (size_t)k1 * C::L);
-    int ng = C::TC / (8 * NWV);
-    asm volatile("" : "+s"(ng));   // opaque trip count: the group loops stay loops (bounded register pressure)
-    __syncthreads();
-
-    for (int p = p0; p < npairs; p += gx) {
-        // table and spectrum loads stay inside the loop (hoisting them costs more registers than a wave has)
-        asm volatile("" : "+s"(gtab), "+s"(ks));
-        __half2* chunk = ws + ((size_t)h * npairs + p) * Ltot + (size_t)k1 * C::L;
-
-#pragma unroll 1
-        for (int gi = 0; gi < ng; ++gi) {
-            phase1<LG, NB>(chunk, xb, gtab, t1f, K, (gi * NWV + wave) * 8, lane);
-            __builtin_amdgcn_sched_barrier(0);   // one group at a time: bounds register pressure
-        }
-        __syncthreads();
-        asm volatile("" : "+s"(ks));      // keep phase 2's spectrum loads below the barrier (register pressure)
-
-        // ---- phase 2: two tiles in flight
-#pragma unroll 1
-        for (int gi = 0; gi < ng; ++gi)
-#pragma unroll
-        for (int tb = 0; tb < 8; tb += NB) {
-            const int t0 = (gi * NWV + wave) * 8;
-            int base[NB];
-            f4 zr[NB], zi[NB];
-            H8U kk[NB];
-#pragma unroll
-            for (int k = 0; k < NB; ++k) {
-                const int t2 = t0 + tb + k;
-                base[k] = phase2_base<LG>(t2, lane);
-                kk[k].u = ks[t2 * 64 + lane];
-            }
-#pragma unroll
-            for (int k = 0; k < NB; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
-#pragma unroll
-            for (int k = 0; k < NB; ++k) {
-                H8U m;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    // correlation (du): the conjugate spectrum, a sign inside the multiply
-                    m.w[j] = CONJ ? cmul_pack_conj(zr[k][j], zi[k][j], kk[k].c[j])
-                                  : cmul_pack(zr[k][j], zi[k][j], kk[k].c[j]);
-                }
-                phase2_inv<LG>(xb, base[k], K, m);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        __syncthreads();
-        asm volatile("" : "+s"(gtab));
-
-        // ---- phase 3
-#pragma unroll 1
-        for (int gi = 0; gi < ng; ++gi) {
-        const int t0 = (gi * NWV + wave) * 8;
-        uint32_t ow[4][8];     // [j][tile]
-#pragma unroll
-        for (int tb = 0; tb < 8; tb += 2) {
-            f4 r[2], s[2];
-            phase3_two<LG>(xb, gtab, t1i, K, t0 + tb, lane, r, s);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                ow[j][tb] = pack_h2(r[0][j], s[0][j]);
-                ow[j][tb + 1] = pack_h2(r[1][j], s[1][j]);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
-            store_words<4>(chunk + n0, &ow[j][0]);
-            store_words<4>(chunk + n0 + 4, &ow[j][4]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        }
-        __syncthreads();
-    }
-}
-
-// -------------------------------------------------------------------------------------
 // Fused convolution of zero-padded real row pairs (single-pass plan), rows staged through LDS.
 // The phase-1 tile of a wave takes samples a tile count apart, so loading its operands straight
 // from global memory touches 16 bytes of every 256; here the whole workgroup moves the pair
@@ -810,6 +699,151 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         __syncthreads();
         drain(it);
         if (more) stage();
+    }
+}
+
+// -------------------------------------------------------------------------------------
+// Inner convolution of the multi-pass split on the staged layout: chunk k1 (L fp16 complex values of pass
+// A's output) of every row pair, in place in the workspace.  Work items (head, chunk, pair), consecutive
+// ones (same spectrum slice) per workgroup; a chunk moves between the workspace and the slots in
+// unit-stride 16-byte runs of four values.  Lane bits of a run: two for the position in a 64-byte
+// segment, then d_a % 4 and d_b % 4 (the 4-byte LDS accesses of a wave then hit 64 different banks).
+// -------------------------------------------------------------------------------------
+template <int LG, int NWV, int NB, bool CONJ>
+__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
+coop_conv_kernel(const float2* __restrict__ kspec, __half2* __restrict__ ws, int npairs, int log2R, int total,
+                 int per, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
+{
+    using C = CC<LG>;
+    constexpr int NT = NWV * 64;
+    constexpr int RPL = (C::L / 4) / NT;             // 16-byte runs per lane
+    extern __shared__ uint4 lds4[];
+    uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
+    uint4* t1f = lds4 + C::XWORDS / 4;
+    uint4* t1i = t1f + C::TC * 4;
+    uint32_t* vt = reinterpret_cast<uint32_t*>(t1i + C::TC * 4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const unsigned G = gridDim.x;
+    const unsigned vid = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (G >> 3) + (blockIdx.x >> 3);
+    const int it0 = (int)vid * per, it1 = it0 + per < total ? it0 + per : total;
+    const int64_t Ltot = (int64_t)C::L << log2R;
+    const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
+    Consts<LG> K;
+    make_consts<LG>(K, tw, lane);
+    h2 cF[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 w = tw_full(tw, (uint32_t)((c * (4 * g + j)) & 255) << (TW_LOG2 - 8));
+        cF[j] = h2{(_Float16)w.x, (_Float16)w.y};
+    }
+    int ng = C::TC / (8 * NWV);
+    asm volatile("" : "+s"(ng));
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+
+    auto run_n = [&](int i) {
+        constexpr int QB = C::cb - 2;                // runs per (d_a, d_b) row = TC / 4
+        const int r = i * NT + tid;
+        const int q = (r & 3) | (((r >> 6) & ((1 << (QB - 2)) - 1)) << 2);
+        const int da = ((r >> 2) & 3) | ((r >> (QB + 6)) << 2);
+        const int db = ((r >> 4) & 3) | (((r >> (QB + 4)) & 3) << 2);
+        return (da << (C::cb + 4)) + (db << C::cb) + 4 * q;
+    };
+    auto chunk_of = [&](int it) {
+        const int hk = it / npairs, p = it - hk * npairs;
+        const int h = hk >> log2R, k1 = hk & ((1 << log2R) - 1);
+        return ws + ((size_t)h * npairs + p) * Ltot + (size_t)k1 * C::L;
+    };
+    auto stage = [&](int it) {
+        const uint4* src = reinterpret_cast<const uint4*>(chunk_of(it));
+#pragma unroll
+        for (int i0 = 0; i0 < RPL; i0 += 4) {
+            uint4 v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = src[run_n(i0 + i) / 4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int a0 = staged_slot<LG>(run_n(i0 + i));
+                xb[a0] = v[i].x; xb[a0 + 4] = v[i].y; xb[a0 + 8] = v[i].z; xb[a0 + 12] = v[i].w;
+            }
+        }
+    };
+    auto drain = [&](int it) {
+        uint4* dst = reinterpret_cast<uint4*>(chunk_of(it));
+#pragma unroll
+        for (int i = 0; i < RPL; ++i) {
+            const int n = run_n(i), a0 = staged_slot<LG>(n);
+            dst[n / 4] = make_uint4(xb[a0], xb[a0 + 4], xb[a0 + 8], xb[a0 + 12]);
+        }
+    };
+
+    staged_tables<LG, NT>(lds4, gtab, tw, tid, 0);
+    __syncthreads();
+    if (it0 < it1) stage(it0);
+    for (int it = it0; it < it1; ++it) {
+        const int hk = it / npairs;
+        const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) +
+                                                         (size_t)(hk >> log2R) * Ltot +
+                                                         (size_t)(hk & ((1 << log2R) - 1)) * C::L);
+        asm volatile("" : "+s"(ks));
+        __syncthreads();             // staged chunk visible
+
+        // ---- phase 1, in place
+#pragma unroll 1
+        for (int gi = 0; gi < ng; ++gi)
+            phase1_inplace<LG, NB>(xb, t1f, vt, K.F16, K, cF, (gi * NWV + wave) * 8, lane);
+        __syncthreads();
+        asm volatile("" : "+s"(ks));
+
+        // ---- phase 2
+#pragma unroll 1
+        for (int gi = 0; gi < ng; ++gi)
+#pragma unroll
+        for (int tb = 0; tb < 8; tb += NB) {
+            const int t0 = (gi * NWV + wave) * 8;
+            int base[NB];
+            f4 zr[NB], zi[NB];
+            H8U kk[NB];
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                const int t2 = t0 + tb + k;
+                base[k] = phase2_base<LG>(t2, lane);
+                kk[k].u = ks[t2 * 64 + lane];
+            }
+#pragma unroll
+            for (int k = 0; k < NB; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                H8U m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)      // correlation (du): the conjugate spectrum
+                    m.w[j] = CONJ ? cmul_pack_conj(zr[k][j], zi[k][j], kk[k].c[j])
+                                  : cmul_pack(zr[k][j], zi[k][j], kk[k].c[j]);
+                phase2_inv<LG>(xb, base[k], K, m);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+
+        // ---- phase 3, in place
+#pragma unroll 1
+        for (int gi = 0; gi < ng; ++gi) {
+            const int t0 = (gi * NWV + wave) * 8;
+#pragma unroll
+            for (int tb = 0; tb < 8; tb += 2) {
+                f4 r[2], s2[2];
+                phase3_two_lds<LG>(xb, t1i, vt, K, cF, t0 + tb, lane, r, s2);
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+                    *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) =
+                        make_uint4(pack_h2(r[k][0], s2[k][0]), pack_h2(r[k][1], s2[k][1]),
+                                   pack_h2(r[k][2], s2[k][2]), pack_h2(r[k][3], s2[k][3]));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __syncthreads();
+        drain(it);
+        if (it + 1 < it1) stage(it + 1);
     }
 }
 
@@ -1407,21 +1441,27 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
     if (pl.log2R == 0)
         return conj ? coop_conv_real_go<LG, IO, NWV, NB, true>(in, kspec, out, pr, tb, st)
                     : coop_conv_real_go<LG, IO, NWV, NB, false>(in, kspec, out, pr, tb, st);
-    // multi-pass: the inner convolution on pass A's workspace; about two workgroups per compute unit in all
-    const size_t lds = coop_lds_bytes<LG>();
-    const long HR = pr.H << pl.log2R;
-    long gx = (2 * compute_units() + HR - 1) / HR;
-    if (gx < 1) gx = 1;
-    if (gx > pr.npairs) gx = pr.npairs;
-    auto launch = [&](auto kern) {
+    // multi-pass: the inner convolution on pass A's workspace
+    const size_t lds = coop_real_lds_bytes<LG>();
+    const long total = (pr.H << pl.log2R) * pr.npairs;   // (head, chunk, pair) items
+    auto launch = [&](auto kern, int& resident) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3((unsigned)(gx * HR)), dim3(NWV * 64), lds, st, kspec, ws, pr.npairs, pl.log2R,
-                           (int)gx, tb.tw, (const unsigned char*)tb.ctab);
+        if (resident == 0) {
+            int nb = 0;
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, NWV * 64, lds);
+            if (e != hipSuccess) return e;
+            resident = (nb > 0 ? nb : 1) * compute_units();
+        }
+        const int per = (int)((total + resident - 1) / resident);
+        hipLaunchKernelGGL(kern, dim3((unsigned)((total + per - 1) / per)), dim3(NWV * 64), lds, st, kspec, ws,
+                           pr.npairs, pl.log2R, (int)total, per, tb.tw, (const unsigned char*)tb.ctab);
         return hipGetLastError();
     };
-    return conj ? launch(coop_conv_kernel<LG, NWV, NB, true>) : launch(coop_conv_kernel<LG, NWV, NB, false>);
+    static int res_fwd = 0, res_conj = 0;
+    return conj ? launch(coop_conv_kernel<LG, NWV, NB, true>, res_conj)
+                : launch(coop_conv_kernel<LG, NWV, NB, false>, res_fwd);
 }
 
 // multi-pass dk: chunks of pass A's outputs in, chunks for pass C and partial dD sums out
