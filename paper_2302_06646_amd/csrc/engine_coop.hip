@@ -7,15 +7,19 @@
 // As in the wave-autonomous kernels an "A-role" MFMA (data as A operand) contracts the slot index
 // and transposes the tile, a "B-role" MFMA contracts it in place, so two digits are contracted
 // per trip through registers and the row crosses LDS only twice per transform pair:
-//   phase 1 (tile t = d_c*TE+d_e): global -> [A: F16 over d_a] * w_L^(k_a(d_b TC + t))
+//   phase 1 (tile t = d_c*TE+d_e): [A: F16 over d_a] * w_L^(k_a(d_b TC + t))
 //                                  -> [B: F16 over d_b] * w_{16TC}^(k_b t) -> LDS
 //   phase 2 (tile = (k_a, high bits of k_b)): LDS -> [A: F16 over d_c] * w_TC^(k_c d_e)
 //            -> [B: F_TE over d_e] * spectrum -> [A: F_TE^-1] * conj -> [B: F16^-1 over k_c] -> LDS
 //   phase 3 (tile t): LDS * conj(w_{16TC}) -> [A: F16^-1 over k_b] * conj(w_L) -> [B: F16^-1 over k_a]
-//                                  -> global (first half only when the input was zero padded)
 // Each wave owns groups of 8 consecutive tiles in every phase; workgroup barriers separate
-// the phases.  The w_L twiddles come from a lane-ordered global table (fp16, one 16-byte load per
-// lane and tile), the w_{16TC} ones from a small table in LDS, the w_TC ones are per-lane constants.
+// the phases.  The w_{16TC} twiddles come from a small table in LDS, the w_TC ones are per-lane constants.
+//
+// Two forms of phases 1 and 3.  Direct (multi-pass dk, spectrum): operands straight from global memory
+// in the tile's lane order, w_L twiddles from a lane-ordered global table (16 bytes per lane and tile).
+// Staged (convolutions, single-pass dk): the whole workgroup moves the pair between global memory and
+// LDS in unit-stride runs, phases 1 and 3 run in place on LDS, and the w_L twiddle is a per-lane
+// constant times an LDS table; see coop_conv_real_kernel.
 #include "engines.hpp"
 #include "mfma_util.hpp"
 
@@ -487,24 +491,9 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
     int ng = C::TC / (8 * NWV);
     asm volatile("" : "+s"(ng));
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
-    const f4 zero = {0.f, 0.f, 0.f, 0.f};
 
-    // run r of the pair -> (d_a, d_b, q): four lanes cover 64 contiguous bytes of a row, the next lane bits
-    // pick d_a % 4 and d_b % 4, so that a wave's 4-byte LDS accesses (word stride 4 along t) spread over
-    // 32 banks while global accesses keep 64-byte segments
-    auto run_n = [&](int i) {
-        constexpr int QB = C::cb - 3;
-        const int r = i * NT + tid;
-        const int q = (r & 3) | (((r >> 6) & ((1 << (QB - 2)) - 1)) << 2);
-        const int da = ((r >> 2) & 3) | ((r >> (QB + 6)) << 2);
-        const int db = ((r >> 4) & 3) | (((r >> (QB + 4)) & 3) << 2);
-        return (da << (C::cb + 4)) + (db << C::cb) + 8 * q;
-    };
-    auto slot = [&](int i) {
-        const int n = run_n(i);
-        const int t = n & (C::TC - 1), db = (n >> C::cb) & 15, da = n >> (C::cb + 4);
-        return (db * C::PITCH + (da >> 2) * C::TC + t) * 4 + (da & 3);
-    };
+    auto run_n = [&](int i) { return staged_run_n<LG>(i * NT + tid); };
+    auto slot = [&](int i) { return staged_slot<LG>(run_n(i)); };
     uint4 pa[RPL], pb[RPL];
     auto fetch = [&](int it) {
         const int h = it / npairs, p = it - h * npairs;
@@ -561,12 +550,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
     };
 
     if (it0 < it1) fetch(it0);       // first pair on its way while the tables are built
-    for (int i = tid; i < C::TC * 8; i += NT) t1f[i] = gtab[C::T1F + i];
-    for (int i = tid; i < C::TC * 16; i += NT) {
-        const float2 w = tw_full(tw, (uint32_t)(((i & 15) * (i >> 4)) & (C::L - 1)) << (TW_LOG2 - LG));
-        vt[i] = pack_h2(w.x, w.y);
-    }
-    for (int i = tid; i < C::XWORDS / 4; i += NT) lds4[i] = make_uint4(0u, 0u, 0u, 0u);
+    staged_tables<LG, NT>(lds4, gtab, tw, tid, 0);
     __syncthreads();                 // tables and cleared slots in place
     if (it0 < it1) stage();
     for (int it = it0; it < it1; ++it) {
@@ -577,47 +561,8 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
 
         // ---- phase 1, in place
 #pragma unroll 1
-        for (int gi = 0; gi < ng; ++gi) {
-            const int t0 = (gi * NWV + wave) * 8;
-#pragma unroll
-            for (int tb = 0; tb < 8; tb += NB) {
-                H8U x[NB], tw1[NB];
-                h2 v[NB];
-                f4 yr[NB], yi[NB], zr[NB], zi[NB];
-#pragma unroll
-                for (int k = 0; k < NB; ++k) {
-                    const int t = t0 + tb + k;
-                    x[k].u = *reinterpret_cast<const uint4*>(&xb[w1 + 4 * t]);
-                    tw1[k].u = t1f[t * 4 + g];
-                    union { uint32_t u; h2 h; } cv;
-                    cv.u = vt[t * 16 + c];
-                    v[k] = cv.h;
-                }
-#pragma unroll
-                for (int k = 0; k < NB; ++k) {
-                    yr[k] = MFMA(x[k].v, K.F16.re, zero);
-                    yi[k] = MFMA(x[k].v, K.F16.im, zero);
-                }
-#pragma unroll
-                for (int k = 0; k < NB; ++k) {
-                    H8U u;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][j], yi[k][j], cmul_hh(cF[j], v[k]));
-                    zr[k] = MFMA(K.F16.re, u.v, zero);
-                    zi[k] = MFMA(K.F16.im, u.v, zero);
-                }
-#pragma unroll
-                for (int k = 0; k < NB; ++k) {
-                    uint4 o;
-                    o.x = cmul_pack(zr[k][0], zi[k][0], tw1[k].c[0]);
-                    o.y = cmul_pack(zr[k][1], zi[k][1], tw1[k].c[1]);
-                    o.z = cmul_pack(zr[k][2], zi[k][2], tw1[k].c[2]);
-                    o.w = cmul_pack(zr[k][3], zi[k][3], tw1[k].c[3]);
-                    *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
+        for (int gi = 0; gi < ng; ++gi)
+            phase1_inplace<LG, NB>(xb, t1f, vt, K.F16, K, cF, (gi * NWV + wave) * 8, lane);
         __syncthreads();
         asm volatile("" : "+s"(ks));
 
@@ -662,30 +607,8 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             const int t0 = (gi * NWV + wave) * 8;
 #pragma unroll
             for (int tb = 0; tb < 8; tb += 2) {
-                H8U tw1[2], x[2], vv[2];
-                f4 yr[2], yi[2], r[2], s[2];
-#pragma unroll
-                for (int k = 0; k < 2; ++k) {
-                    const int t = t0 + tb + k;
-                    tw1[k].u = t1i[t * 4 + g];
-                    x[k].u = *reinterpret_cast<const uint4*>(&xb[w1 + 4 * t]);
-                    vv[k].u = *reinterpret_cast<const uint4*>(&vt[t * 16 + 4 * g]);
-                }
-#pragma unroll
-                for (int k = 0; k < 2; ++k) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) x[k].w[j] = cmul_h2(x[k].w[j], tw1[k].c[j]);
-                    yr[k] = MFMA(x[k].v, K.I16.re, zero);
-                    yi[k] = MFMA(x[k].v, K.I16.im, zero);
-                }
-#pragma unroll
-                for (int k = 0; k < 2; ++k) {
-                    H8U u;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack_conj(yr[k][j], yi[k][j], cmul_hh(cF[j], vv[k].c[j]));
-                    r[k] = MFMA(K.I16.re, u.v, zero);
-                    s[k] = MFMA(K.I16.im, u.v, zero);
-                }
+                f4 r[2], s[2];
+                phase3_two_lds<LG>(xb, t1i, vt, K, cF, t0 + tb, lane, r, s);
 #pragma unroll
                 for (int k = 0; k < 2; ++k) {
                     uint4 o = make_uint4(0u, 0u, 0u, 0u);
