@@ -201,14 +201,15 @@ static hipError_t run_conv(const void* in, const float2* kspec, void* out, void*
     hipError_t e;
     const float2* tw = tb.tw;
     const bool f16ws = pl.engine == ENGINE_MFMA;
-    if (pl.log2R && !ws1_ready) {
+    const bool fuse_a = pl.engine == ENGINE_MFMA && pl.fuse_a && !ws1_ready;   // pass A inside the inner kernel
+    if (pl.log2R && !ws1_ready && !fuse_a) {
         e = outer_fwd(in, nullptr, ws1, nullptr, nullptr, pr, pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st);
         if (e != hipSuccess) return e;
     }
     if (pl.engine == ENGINE_VALU)
         e = valu_conv(in, kspec, out, (float2*)ws1, conj, pr, pl, tw, st);
     else
-        e = mfma_conv(in, kspec, out, (__half2*)ws1, conj, pr, pl, tb, st);
+        e = mfma_conv(in, kspec, out, (__half2*)ws1, conj, fuse_a, pr, pl, tb, st);
     if (e != hipSuccess) return e;
     if (pl.log2R) e = outer_inv(ws1, out, pr, pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st);
     return e;

@@ -334,7 +334,7 @@ __device__ __forceinline__ h2 cmul_hh(h2 a, h2 w)
 // F1 is the first-stage matrix (rows of the zero padding cleared when those slots hold stale data).
 template <int LG, int NB>
 __device__ __forceinline__ void phase1_inplace(uint32_t* xb, const uint4* t1f, const uint32_t* vt, const Mats& F1,
-                                               const Consts<LG>& K, const h2 (&cF)[4], int t0, int lane)
+                                               const Mats& F2, const h2 (&cF)[4], int t0, int lane)
 {
     using C = CC<LG>;
     const int c = lane & 15, g = lane >> 4;
@@ -364,8 +364,8 @@ __device__ __forceinline__ void phase1_inplace(uint32_t* xb, const uint4* t1f, c
             H8U u;
 #pragma unroll
             for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][j], yi[k][j], cmul_hh(cF[j], v[k]));
-            zr[k] = MFMA(K.F16.re, u.v, zero);
-            zi[k] = MFMA(K.F16.im, u.v, zero);
+            zr[k] = MFMA(F2.re, u.v, zero);
+            zi[k] = MFMA(F2.im, u.v, zero);
         }
 #pragma unroll
         for (int k = 0; k < NB; ++k) {
@@ -562,7 +562,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         // ---- phase 1, in place
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi)
-            phase1_inplace<LG, NB>(xb, t1f, vt, K.F16, K, cF, (gi * NWV + wave) * 8, lane);
+            phase1_inplace<LG, NB>(xb, t1f, vt, K.F16, K.F16, cF, (gi * NWV + wave) * 8, lane);
         __syncthreads();
         asm volatile("" : "+s"(ks));
 
@@ -631,11 +631,36 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
 // ones (same spectrum slice) per workgroup; a chunk moves between the workspace and the slots in
 // unit-stride 16-byte runs of four values.  Lane bits of a run: two for the position in a 64-byte
 // segment, then d_a % 4 and d_b % 4 (the 4-byte LDS accesses of a wave then hit 64 different banks).
+//
+// FUSEA (outer radix 4 only): pass A is taken here instead of in a kernel of its own.  With the padded half
+// dropped its sum has two terms, s[n2] = z[n2] + (-i)^k1 z[L + n2] (z = row a + i row b), formed while
+// staging straight from the caller's rows; its twist w_{4L}^(k1 n2), n2 = d_a 16 TC + d_b TC + t, costs
+// nothing: the d_a and d_b factors scale the columns of the two phase-1 matrices and the t factor goes
+// into the w_{16TC} table, all three rebuilt per item.
 // -------------------------------------------------------------------------------------
-template <int LG, int NWV, int NB, bool CONJ>
+// (1/4) F16[m][sig] w_{2^lt}^(k1 sig 2^wl) as MFMA operand: the contraction index sig carries the phase
+__device__ __forceinline__ Mats phase_mats(int k1, int wl, int lt, const float2* __restrict__ tw, int lane)
+{
+    const int m = lane & 15, g = lane >> 4;
+    Mats A;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int sig = 4 * g + q;
+        const uint32_t idx = ((uint32_t)((m * sig) & 15) << (TW_LOG2 - 4)) + ((uint32_t)(k1 * sig) << (wl + TW_LOG2 - lt));
+        const float2 w = tw_full(tw, idx & (TW_L - 1));
+        A.re[2 * q] = (_Float16)(w.x * 0.25f);
+        A.re[2 * q + 1] = (_Float16)(-w.y * 0.25f);
+        A.im[2 * q] = (_Float16)(w.y * 0.25f);
+        A.im[2 * q + 1] = (_Float16)(w.x * 0.25f);
+    }
+    return A;
+}
+
+template <int LG, class IO, int NWV, int NB, bool CONJ, bool FUSEA>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
-coop_conv_kernel(const float2* __restrict__ kspec, __half2* __restrict__ ws, int npairs, int log2R, int total,
-                 int per, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
+coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec, __half2* __restrict__ ws,
+                 int64_t B, int64_t H, int64_t N, int npairs, int log2R, int total, int per,
+                 const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
     constexpr int NT = NWV * 64;
@@ -700,23 +725,84 @@ coop_conv_kernel(const float2* __restrict__ kspec, __half2* __restrict__ ws, int
         }
     };
 
+    // FUSEA: rows of the item -> first term + (-i)^k1 second term -> slots; phase-1 operands of the item
+    Mats F1 = K.F16, F2 = K.F16;
+    auto stage_rows = [&](int it) __attribute__((always_inline)) {
+        const int hk = it / npairs, p = it - hk * npairs;
+        const int h = hk >> 2, k1 = hk & 3;
+        F1 = phase_mats(k1, C::cb + 4, LG + 2, tw, lane);
+        F2 = phase_mats(k1, C::cb, LG + 2, tw, lane);
+        for (int i = tid; i < C::TC * 4; i += NT) {      // w_{16TC}^(k_b t) w_{4L}^(k1 t)
+            const float2 w = tw_full(tw, (uint32_t)(k1 * (i >> 2)) << (TW_LOG2 - LG - 2));
+            const h2 tau = {(_Float16)w.x, (_Float16)w.y};
+            H8U e;
+            e.u = gtab[C::T1F + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e.w[j] = cmul_h2(e.w[j], tau);
+            t1f[i] = e.u;
+        }
+        const bool has_b = (2 * p + 1) < B;
+        const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
+        const h2 cr = {(_Float16)((k1 & 1) ? 0.f : (k1 ? -1.f : 1.f)), (_Float16)((k1 & 1) ? (k1 == 1 ? -1.f : 1.f) : 0.f)};
+        const h2 crs = {-cr[1], cr[0]};
+        constexpr int RPA = (C::L / 8) / NT;             // runs of eight samples per lane
+#pragma unroll
+        for (int i0 = 0; i0 < RPA; i0 += 2) {
+            uint4 v[2][4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int n = staged_run_n<LG>((i0 + i) * NT + tid);
+                v[i][0] = *reinterpret_cast<const uint4*>(in + oa + n);
+                v[i][1] = *reinterpret_cast<const uint4*>(in + oa + C::L + n);
+                v[i][2] = *reinterpret_cast<const uint4*>(in + ob + n);
+                v[i][3] = *reinterpret_cast<const uint4*>(in + ob + C::L + n);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                uint32_t w[4][4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    w[r][0] = v[i][r].x; w[r][1] = v[i][r].y; w[r][2] = v[i][r].z; w[r][3] = v[i][r].w;
+                    if (r >= 2 && !has_b) w[r][0] = w[r][1] = w[r][2] = w[r][3] = 0u;
+                    if (IsBf<IO>::v) {
+#pragma unroll
+                        for (int m = 0; m < 4; ++m) w[r][m] = bf2_to_h2(w[r][m]);
+                    }
+                }
+                const int a0 = staged_slot<LG>(staged_run_n<LG>((i0 + i) * NT + tid));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                    union { uint32_t u; h2 h; } z0, z1, o;
+                    z0.u = __builtin_amdgcn_perm(w[2][e >> 1], w[0][e >> 1], sel);
+                    z1.u = __builtin_amdgcn_perm(w[3][e >> 1], w[1][e >> 1], sel);
+                    const h2 x = {z1.h[0], z1.h[0]}, y = {z1.h[1], z1.h[1]};
+                    o.h = __builtin_elementwise_fma(y, crs, __builtin_elementwise_fma(x, cr, z0.h));
+                    xb[a0 + 4 * e] = o.u;
+                }
+            }
+        }
+    };
+    auto stage_item = [&](int it) __attribute__((always_inline)) {
+        if (FUSEA) stage_rows(it);
+        else stage(it);
+    };
+
     staged_tables<LG, NT>(lds4, gtab, tw, tid, 0);
     __syncthreads();
-    if (it0 < it1) stage(it0);
+    if (it0 < it1) stage_item(it0);
     for (int it = it0; it < it1; ++it) {
         const int hk = it / npairs;
         const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) +
                                                          (size_t)(hk >> log2R) * Ltot +
                                                          (size_t)(hk & ((1 << log2R) - 1)) * C::L);
-        asm volatile("" : "+s"(ks));
         __syncthreads();             // staged chunk visible
 
         // ---- phase 1, in place
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi)
-            phase1_inplace<LG, NB>(xb, t1f, vt, K.F16, K, cF, (gi * NWV + wave) * 8, lane);
+            phase1_inplace<LG, NB>(xb, t1f, vt, F1, F2, cF, (gi * NWV + wave) * 8, lane);
         __syncthreads();
-        asm volatile("" : "+s"(ks));
 
         // ---- phase 2
 #pragma unroll 1
@@ -766,7 +852,7 @@ coop_conv_kernel(const float2* __restrict__ kspec, __half2* __restrict__ ws, int
         }
         __syncthreads();
         drain(it);
-        if (it + 1 < it1) stage(it + 1);
+        if (it + 1 < it1) stage_item(it + 1);
     }
 }
 
@@ -947,7 +1033,7 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                 stage(sidx);
                 __syncthreads();                         // staged source visible, raw area free
                 if (sidx + 1 < nsrc) copy_in(sidx + 1);
-                phase1_inplace<LG, 2>(xb, t1f_, vt_, F1, K, cF, t0, lane);
+                phase1_inplace<LG, 2>(xb, t1f_, vt_, F1, K.F16, cF, t0, lane);
                 __syncthreads();
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
@@ -1357,14 +1443,15 @@ hipError_t coop_conv_real_go(const void* in, const float2* kspec, void* out, con
 }
 
 template <int LG, class IO>
-hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
-                        const Plan& pl, const Tables& tb, hipStream_t st)
+hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,
+                        const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
 {
     constexpr int NWV = CC<LG>::NW, NB = NTB;
     if (pl.log2R == 0)
         return conj ? coop_conv_real_go<LG, IO, NWV, NB, true>(in, kspec, out, pr, tb, st)
                     : coop_conv_real_go<LG, IO, NWV, NB, false>(in, kspec, out, pr, tb, st);
-    // multi-pass: the inner convolution on pass A's workspace
+    // multi-pass: the inner convolution on pass A's workspace, or (fuse_a) on the rows themselves
+    using T = typename IO::T;
     const size_t lds = coop_real_lds_bytes<LG>();
     const long total = (pr.H << pl.log2R) * pr.npairs;   // (head, chunk, pair) items
     auto launch = [&](auto kern, int& resident) {
@@ -1378,13 +1465,17 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
             resident = (nb > 0 ? nb : 1) * compute_units();
         }
         const int per = (int)((total + resident - 1) / resident);
-        hipLaunchKernelGGL(kern, dim3((unsigned)((total + per - 1) / per)), dim3(NWV * 64), lds, st, kspec, ws,
-                           pr.npairs, pl.log2R, (int)total, per, tb.tw, (const unsigned char*)tb.ctab);
+        hipLaunchKernelGGL(kern, dim3((unsigned)((total + per - 1) / per)), dim3(NWV * 64), lds, st, (const T*)in, kspec,
+                           ws, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, (int)total, per, tb.tw,
+                           (const unsigned char*)tb.ctab);
         return hipGetLastError();
     };
-    static int res_fwd = 0, res_conj = 0;
-    return conj ? launch(coop_conv_kernel<LG, NWV, NB, true>, res_conj)
-                : launch(coop_conv_kernel<LG, NWV, NB, false>, res_fwd);
+    static int res[4] = {0, 0, 0, 0};
+    if (fuse_a)
+        return conj ? launch(coop_conv_kernel<LG, IO, NWV, NB, true, true>, res[3])
+                    : launch(coop_conv_kernel<LG, IO, NWV, NB, false, true>, res[2]);
+    return conj ? launch(coop_conv_kernel<LG, IO, NWV, NB, true, false>, res[1])
+                : launch(coop_conv_kernel<LG, IO, NWV, NB, false, false>, res[0]);
 }
 
 // multi-pass dk: chunks of pass A's outputs in, chunks for pass C and partial dD sums out
@@ -1453,10 +1544,10 @@ hipError_t coop_kspec_go(const float* k, const __half2* ws, const float* D, cons
 
 }  // namespace
 
-hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
-                     const Plan& pl, const Tables& tb, hipStream_t st)
+hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,
+                     const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
 {
-#define GO(LG, IO) return coop_conv_go<LG, IO>(in, kspec, out, ws, conj, pr, pl, tb, st)
+#define GO(LG, IO) return coop_conv_go<LG, IO>(in, kspec, out, ws, conj, fuse_a, pr, pl, tb, st)
     if (pr.io == LONGCONV_F16) {
         if (pl.log2L2 == 13) GO(13, IoF16);
         if (pl.log2L2 == 14) GO(14, IoF16);

@@ -540,13 +540,17 @@ void mfma_fill_plan(Plan& pl)
     const float c = 1.0f / (float)(1 << total_shift(pl.log2L2));
     pl.kscale = 1.0f / (L * c * c);
     pl.dkscale = 1.0f / (L * c * c * c);
+    // outer radix 4 on the cooperative kernels: the convolutions take pass A in their staging
+    // (LONGCONV_FUSE_PASS_A=0 keeps the separate pass, for comparison)
+    const char* fa = getenv("LONGCONV_FUSE_PASS_A");
+    pl.fuse_a = pl.order.coop_lg && pl.log2R == 2 && !(fa && !strcmp(fa, "0"));
 }
 
-hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
-                     const Plan& pl, const Tables& tb, hipStream_t st)
+hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,
+                     const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
 {
     if (pl.order.wave_lg) return wave_conv(in, kspec, out, conj, pr, pl, tb, st);
-    if (pl.order.coop_lg) return coop_conv(in, kspec, out, ws, conj, pr, pl, tb, st);
+    if (pl.order.coop_lg) return coop_conv(in, kspec, out, ws, conj, fuse_a, pr, pl, tb, st);
     if (pr.io == LONGCONV_F16) { LC_LG_SWITCH(conv_go, IoF16, in, kspec, out, ws, conj, pr, pl, tb, st) }
     if (pr.io == LONGCONV_BF16) { LC_LG_SWITCH(conv_go, IoBF16, in, kspec, out, ws, conj, pr, pl, tb, st) }
     return hipErrorInvalidValue;

@@ -46,7 +46,8 @@ hipError_t valu_dk(const void* dy, const void* u, float* dk, float* dD, const fl
 // ---- fp16 MFMA engine (engine_mfma.hip) ---------------------------------------------
 constexpr int MFMA_INNER_MAX_LOG2 = 15;
 void mfma_fill_plan(Plan& pl);
-hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj,
+// fuse_a (only when pl.fuse_a): pass A has not been run; the inner kernel reads the rows `in` itself.
+hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,
                      const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st);
 // Multi-pass: dD_part[h*R + k1] receives chunk k1's share of dD[h] (sum them with reduce_dD).
 hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u,
@@ -67,8 +68,9 @@ hipError_t wave_kspec(const float* k, const float* D, float2* kspec, int64_t H, 
 // ---- cooperative chained matrix-core kernels for 2^13 <= L2 <= 2^15 (engine_coop.hip) --------
 constexpr int COOP_MIN_LOG2 = 13, COOP_MAX_LOG2 = 15;
 hipError_t coop_fill_tables(const void** tab_out, hipStream_t st);
-hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, const Problem& pr,
-                     const Plan& pl, const Tables& tb, hipStream_t st);
+// fuse_a: multi-pass plans with outer radix 4 only; the kernel then reads the rows `in`, not pass A's output.
+hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,
+                     const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st);
 // ws: pass-A output of the pre-scaled kernel (multi-pass plans only).
 hipError_t coop_kspec(const float* k, const __half2* ws, const float* D, const float* rs, float2* kspec, int64_t H,
                       int64_t N, const Plan& pl, const Tables& tb, hipStream_t st);

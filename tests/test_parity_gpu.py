@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 def _need_gpu_and_clean_env(monkeypatch):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL"):
+    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL", "LONGCONV_FUSE_PASS_A"):
         monkeypatch.delenv(v, raising=False)
     yield
 

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 def _need_gpu_and_clean_env(monkeypatch):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL"):
+    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL", "LONGCONV_FUSE_PASS_A"):
         monkeypatch.delenv(v, raising=False)
     yield
 
@@ -153,3 +153,21 @@ def test_persistent_workgroups_ragged_item_count(monkeypatch, N, B, H, io):
         assert wl.rel_l2(y[:, sl], y2[:, sl]) <= tol and wl.rel_l2(du[:, sl], du2[:, sl]) <= tol, f"heads {sl}"
         assert wl.rel_l2(dk[sl], dk2[sl]) <= tol, f"dk heads {sl}"
     assert wl.rel_l2(dD, dD2) <= tol
+
+
+@pytest.mark.parametrize("io", [wl.F16, wl.BF16])
+def test_outer_radix4_pass_a_inside_the_inner_kernel(monkeypatch, io):
+    """N = 65536 (outer radix 4): the convolutions take pass A while staging their rows.  Odd batch (the last
+    pair has one row), both half dtypes, against the oracle and against the separate pass A."""
+    from gpu_harness import GpuRun, TOL, check_full
+    inp = wl.generate(_w("4a", dtype=io), B=3, H=2)
+    check_full(inp, label=f"pass A fused, io={wl.DTYPE_NAMES[io]}")
+    g = GpuRun(inp)
+    y = g.fwd().copy()
+    du = g.bwd(dk=False, dD=False)[0].copy()
+    monkeypatch.setenv("LONGCONV_FUSE_PASS_A", "0")
+    g2 = GpuRun(inp)
+    y2 = g2.fwd()
+    du2 = g2.bwd(dk=False, dD=False)[0]
+    assert wl.rel_l2(y, y2) <= 2 * TOL[io] and wl.rel_l2(du, du2) <= 2 * TOL[io]
+    assert not np.array_equal(y, y2)          # the two paths round differently: the switch did take effect
