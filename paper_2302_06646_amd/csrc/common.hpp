@@ -165,7 +165,7 @@ struct Plan {
     SpecOrder order; // storage order of the spectrum: outer digit first, then inner digits
     float kscale;    // factor folded into the stored spectrum (includes 1/L)
     float dkscale;   // factor applied to the inverse transform of the dk accumulator
-    int fuse_a;      // multi-pass convolutions take pass A inside the inner kernel (outer radix 4, matrix cores)
+    int fuse_a;      // multi-pass convolutions take pass A inside the inner kernel (outer radix 4 or 8, matrix cores)
 };
 
 Plan make_plan(int64_t N, int io);

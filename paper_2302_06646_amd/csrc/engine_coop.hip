@@ -632,11 +632,11 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
 // unit-stride 16-byte runs of four values.  Lane bits of a run: two for the position in a 64-byte
 // segment, then d_a % 4 and d_b % 4 (the 4-byte LDS accesses of a wave then hit 64 different banks).
 //
-// FUSEA (outer radix 4 only): pass A is taken here instead of in a kernel of its own.  With the padded half
-// dropped its sum has two terms, s[n2] = z[n2] + (-i)^k1 z[L + n2] (z = row a + i row b), formed while
-// staging straight from the caller's rows; its twist w_{4L}^(k1 n2), n2 = d_a 16 TC + d_b TC + t, costs
-// nothing: the d_a and d_b factors scale the columns of the two phase-1 matrices and the t factor goes
-// into the w_{16TC} table, all three rebuilt per item.
+// FUSEA > 0 (= log2 of the outer radix R, 4 or 8): pass A is taken here instead of in a kernel of its own.
+// With the padded half dropped its sum has R/2 terms, s[n2] = sum_{n1 < R/2} w_R^(n1 k1) z[n1 L + n2]
+// (z = row a + i row b), formed while staging straight from the caller's rows; its twist w_{RL}^(k1 n2),
+// n2 = d_a 16 TC + d_b TC + t, costs nothing: the d_a and d_b factors scale the columns of the two
+// phase-1 matrices and the t factor goes into the w_{16TC} table, all three rebuilt per item.
 // -------------------------------------------------------------------------------------
 // (1/4) F16[m][sig] w_{2^lt}^(k1 sig 2^wl) as MFMA operand: the contraction index sig carries the phase
 __device__ __forceinline__ Mats phase_mats(int k1, int wl, int lt, const float2* __restrict__ tw, int lane)
@@ -656,7 +656,7 @@ __device__ __forceinline__ Mats phase_mats(int k1, int wl, int lt, const float2*
     return A;
 }
 
-template <int LG, class IO, int NWV, int NB, bool CONJ, bool FUSEA>
+template <int LG, class IO, int NWV, int NB, bool CONJ, int FUSEA>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec, __half2* __restrict__ ws,
                  int64_t B, int64_t H, int64_t N, int npairs, int log2R, int total, int per,
@@ -725,15 +725,16 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
         }
     };
 
-    // FUSEA: rows of the item -> first term + (-i)^k1 second term -> slots; phase-1 operands of the item
+    // FUSEA: rows of the item -> pass-A sum -> slots; phase-1 operands of the item
     Mats F1 = K.F16, F2 = K.F16;
     auto stage_rows = [&](int it) __attribute__((always_inline)) {
+        constexpr int LR = FUSEA > 0 ? FUSEA : 2, RH = (1 << LR) / 2;
         const int hk = it / npairs, p = it - hk * npairs;
-        const int h = hk >> 2, k1 = hk & 3;
-        F1 = phase_mats(k1, C::cb + 4, LG + 2, tw, lane);
-        F2 = phase_mats(k1, C::cb, LG + 2, tw, lane);
-        for (int i = tid; i < C::TC * 4; i += NT) {      // w_{16TC}^(k_b t) w_{4L}^(k1 t)
-            const float2 w = tw_full(tw, (uint32_t)(k1 * (i >> 2)) << (TW_LOG2 - LG - 2));
+        const int h = hk >> LR, k1 = hk & ((1 << LR) - 1);
+        F1 = phase_mats(k1, C::cb + 4, LG + LR, tw, lane);
+        F2 = phase_mats(k1, C::cb, LG + LR, tw, lane);
+        for (int i = tid; i < C::TC * 4; i += NT) {      // w_{16TC}^(k_b t) w_{RL}^(k1 t)
+            const float2 w = tw_full(tw, (uint32_t)(k1 * (i >> 2)) << (TW_LOG2 - LG - LR));
             const h2 tau = {(_Float16)w.x, (_Float16)w.y};
             H8U e;
             e.u = gtab[C::T1F + i];
@@ -743,42 +744,53 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
         }
         const bool has_b = (2 * p + 1) < B;
         const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
-        const h2 cr = {(_Float16)((k1 & 1) ? 0.f : (k1 ? -1.f : 1.f)), (_Float16)((k1 & 1) ? (k1 == 1 ? -1.f : 1.f) : 0.f)};
-        const h2 crs = {-cr[1], cr[0]};
+        h2 cr[RH], crs[RH];                              // w_R^(n1 k1) and i times it
+#pragma unroll
+        for (int n1 = 1; n1 < RH; ++n1) {
+            const float2 w = tw_full(tw, (uint32_t)((n1 * k1) & ((1 << LR) - 1)) << (TW_LOG2 - LR));
+            cr[n1] = h2{(_Float16)w.x, (_Float16)w.y};
+            crs[n1] = h2{(_Float16)(-w.y), (_Float16)w.x};
+        }
         constexpr int RPA = (C::L / 8) / NT;             // runs of eight samples per lane
+        constexpr int RB = RH <= 2 ? 2 : 1;              // runs in flight
 #pragma unroll
-        for (int i0 = 0; i0 < RPA; i0 += 2) {
-            uint4 v[2][4];
+        for (int i0 = 0; i0 < RPA; i0 += RB) {
+            uint4 va[RB][RH], vb[RB][RH];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < RB; ++i) {
                 const int n = staged_run_n<LG>((i0 + i) * NT + tid);
-                v[i][0] = *reinterpret_cast<const uint4*>(in + oa + n);
-                v[i][1] = *reinterpret_cast<const uint4*>(in + oa + C::L + n);
-                v[i][2] = *reinterpret_cast<const uint4*>(in + ob + n);
-                v[i][3] = *reinterpret_cast<const uint4*>(in + ob + C::L + n);
+#pragma unroll
+                for (int n1 = 0; n1 < RH; ++n1) {
+                    va[i][n1] = *reinterpret_cast<const uint4*>(in + oa + (size_t)n1 * C::L + n);
+                    vb[i][n1] = *reinterpret_cast<const uint4*>(in + ob + (size_t)n1 * C::L + n);
+                }
             }
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                uint32_t w[4][4];
+            for (int i = 0; i < RB; ++i) {
+                uint32_t wa[RH][4], wb[RH][4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    w[r][0] = v[i][r].x; w[r][1] = v[i][r].y; w[r][2] = v[i][r].z; w[r][3] = v[i][r].w;
-                    if (r >= 2 && !has_b) w[r][0] = w[r][1] = w[r][2] = w[r][3] = 0u;
+                for (int n1 = 0; n1 < RH; ++n1) {
+                    wa[n1][0] = va[i][n1].x; wa[n1][1] = va[i][n1].y; wa[n1][2] = va[i][n1].z; wa[n1][3] = va[i][n1].w;
+                    wb[n1][0] = vb[i][n1].x; wb[n1][1] = vb[i][n1].y; wb[n1][2] = vb[i][n1].z; wb[n1][3] = vb[i][n1].w;
+                    if (!has_b) wb[n1][0] = wb[n1][1] = wb[n1][2] = wb[n1][3] = 0u;
                     if (IsBf<IO>::v) {
 #pragma unroll
-                        for (int m = 0; m < 4; ++m) w[r][m] = bf2_to_h2(w[r][m]);
+                        for (int m = 0; m < 4; ++m) { wa[n1][m] = bf2_to_h2(wa[n1][m]); wb[n1][m] = bf2_to_h2(wb[n1][m]); }
                     }
                 }
                 const int a0 = staged_slot<LG>(staged_run_n<LG>((i0 + i) * NT + tid));
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-                    union { uint32_t u; h2 h; } z0, z1, o;
-                    z0.u = __builtin_amdgcn_perm(w[2][e >> 1], w[0][e >> 1], sel);
-                    z1.u = __builtin_amdgcn_perm(w[3][e >> 1], w[1][e >> 1], sel);
-                    const h2 x = {z1.h[0], z1.h[0]}, y = {z1.h[1], z1.h[1]};
-                    o.h = __builtin_elementwise_fma(y, crs, __builtin_elementwise_fma(x, cr, z0.h));
-                    xb[a0 + 4 * e] = o.u;
+                    union { uint32_t u; h2 h; } acc, z;
+                    acc.u = __builtin_amdgcn_perm(wb[0][e >> 1], wa[0][e >> 1], sel);
+#pragma unroll
+                    for (int n1 = 1; n1 < RH; ++n1) {
+                        z.u = __builtin_amdgcn_perm(wb[n1][e >> 1], wa[n1][e >> 1], sel);
+                        const h2 x = {z.h[0], z.h[0]}, y = {z.h[1], z.h[1]};
+                        acc.h = __builtin_elementwise_fma(y, crs[n1], __builtin_elementwise_fma(x, cr[n1], acc.h));
+                    }
+                    xb[a0 + 4 * e] = acc.u;
                 }
             }
         }
@@ -1470,12 +1482,18 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
                            (const unsigned char*)tb.ctab);
         return hipGetLastError();
     };
-    static int res[4] = {0, 0, 0, 0};
-    if (fuse_a)
-        return conj ? launch(coop_conv_kernel<LG, IO, NWV, NB, true, true>, res[3])
-                    : launch(coop_conv_kernel<LG, IO, NWV, NB, false, true>, res[2]);
-    return conj ? launch(coop_conv_kernel<LG, IO, NWV, NB, true, false>, res[1])
-                : launch(coop_conv_kernel<LG, IO, NWV, NB, false, false>, res[0]);
+    static int res[6] = {0, 0, 0, 0, 0, 0};
+    if constexpr (LG == COOP_MAX_LOG2) {
+        if (fuse_a && pl.log2R == 2)
+            return conj ? launch(coop_conv_kernel<LG, IO, NWV, NB, true, 2>, res[2])
+                        : launch(coop_conv_kernel<LG, IO, NWV, NB, false, 2>, res[3]);
+        if (fuse_a && pl.log2R == 3)
+            return conj ? launch(coop_conv_kernel<LG, IO, NWV, NB, true, 3>, res[4])
+                        : launch(coop_conv_kernel<LG, IO, NWV, NB, false, 3>, res[5]);
+    }
+    if (fuse_a) return hipErrorInvalidValue;
+    return conj ? launch(coop_conv_kernel<LG, IO, NWV, NB, true, 0>, res[1])
+                : launch(coop_conv_kernel<LG, IO, NWV, NB, false, 0>, res[0]);
 }
 
 // multi-pass dk: chunks of pass A's outputs in, chunks for pass C and partial dD sums out

@@ -540,10 +540,10 @@ void mfma_fill_plan(Plan& pl)
     const float c = 1.0f / (float)(1 << total_shift(pl.log2L2));
     pl.kscale = 1.0f / (L * c * c);
     pl.dkscale = 1.0f / (L * c * c * c);
-    // outer radix 4 on the cooperative kernels: the convolutions take pass A in their staging
-    // (LONGCONV_FUSE_PASS_A=0 keeps the separate pass, for comparison)
+    // outer radix 4 or 8 around the 32768-point cooperative kernels: the convolutions take pass A in their
+    // staging (LONGCONV_FUSE_PASS_A=0 keeps the separate pass, for comparison)
     const char* fa = getenv("LONGCONV_FUSE_PASS_A");
-    pl.fuse_a = pl.order.coop_lg && pl.log2R == 2 && !(fa && !strcmp(fa, "0"));
+    pl.fuse_a = pl.order.coop_lg == COOP_MAX_LOG2 && (pl.log2R == 2 || pl.log2R == 3) && !(fa && !strcmp(fa, "0"));
 }
 
 hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,

@@ -68,7 +68,7 @@ hipError_t wave_kspec(const float* k, const float* D, float2* kspec, int64_t H, 
 // ---- cooperative chained matrix-core kernels for 2^13 <= L2 <= 2^15 (engine_coop.hip) --------
 constexpr int COOP_MIN_LOG2 = 13, COOP_MAX_LOG2 = 15;
 hipError_t coop_fill_tables(const void** tab_out, hipStream_t st);
-// fuse_a: multi-pass plans with outer radix 4 only; the kernel then reads the rows `in`, not pass A's output.
+// fuse_a (plans with pl.fuse_a only): the kernel reads the rows `in` and takes pass A itself.
 hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,
                      const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st);
 // ws: pass-A output of the pre-scaled kernel (multi-pass plans only).

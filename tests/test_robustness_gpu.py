@@ -156,11 +156,12 @@ def test_persistent_workgroups_ragged_item_count(monkeypatch, N, B, H, io):
 
 
 @pytest.mark.parametrize("io", [wl.F16, wl.BF16])
-def test_outer_radix4_pass_a_inside_the_inner_kernel(monkeypatch, io):
-    """N = 65536 (outer radix 4): the convolutions take pass A while staging their rows.  Odd batch (the last
-    pair has one row), both half dtypes, against the oracle and against the separate pass A."""
+@pytest.mark.parametrize("N", [65536, 131072])
+def test_pass_a_inside_the_inner_kernel(monkeypatch, N, io):
+    """N = 65536, 131072 (outer radix 4, 8): the convolutions take pass A while staging their rows.  Odd batch
+    (the last pair has one row), both half dtypes, against the oracle and against the separate pass A."""
     from gpu_harness import GpuRun, TOL, check_full
-    inp = wl.generate(_w("4a", dtype=io), B=3, H=2)
+    inp = wl.generate(_w("4a", N=N, dtype=io), B=3, H=1 if N > 65536 else 2)
     check_full(inp, label=f"pass A fused, io={wl.DTYPE_NAMES[io]}")
     g = GpuRun(inp)
     y = g.fwd().copy()
