@@ -42,9 +42,9 @@ MEASURED_TRAFFIC = {
     # (the forward kernel reads rows in 64-byte requests, which FETCH_SIZE x 2 over-counts: upper bound)
     "cfg3_B8_H256_N16384_fp16": {"fwd": (98868.7 * 2 + 65536.0) * KIB, "bwd_du": (98870.0 * 2 + 65536.0) * KIB,
                                  "bwd_dk_dD": (160923.0 * 2 + 54800.1) * KIB},
-    "cfg4_B1_H128_N65536_fp16": {"fwd": ((9572.2 + 66103.0 + 34152.3) * 2 + 65536.0 + 66502.0 + 16384.0) * KIB,
-                                 "bwd_du": ((9572.2 + 66103.5 + 34152.3) * 2 + 65536.0 + 66364.8 + 16384.0) * KIB,
-                                 "bwd_dk_dD": ((17771.8 + 165206.0 + 34157.0) * 2 + 131072.0 + 136208.2 + 32768.0) * KIB},
+    "cfg4_B1_H128_N65536_fp16": {"fwd": ((49952.0 + 34152.0) * 2 + 65644.6 + 16384.0) * KIB,
+                                 "bwd_du": ((49955.5 + 34152.0) * 2 + 65621.0 + 16384.0) * KIB,
+                                 "bwd_dk_dD": ((17770.6 + 165351.6 + 34218.3) * 2 + 131072.0 + 132915.0 + 32768.0) * KIB},
 }
 
 def log(*a):
