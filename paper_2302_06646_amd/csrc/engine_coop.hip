@@ -994,15 +994,12 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                 x[2 * m + 1] = __builtin_amdgcn_perm(wb[m], wa[m], 0x07060302u);
             }
             if (SPLIT && odd) {
+                // twist w_{2N}^n, n = d_a 16 TC + d_b TC + t: the (d_a, d_b) part here, one factor per run;
+                // the t part sits in the w_{16TC} table of this walk
                 union { uint32_t u; h2 h; } bw;
-                bw.u = twr[n / 8];
-                const h2 base = bw.h;
+                bw.u = twr[(n & ~(C::TC - 1)) / 8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float ang = -3.14159265358979323846f * (float)e / (float)ROWN;
-                    const h2 we = {(_Float16)__builtin_cosf(ang), (_Float16)__builtin_sinf(ang)};
-                    x[e] = cmul_h2(x[e], cmul_hh(base, we));
-                }
+                for (int e = 0; e < 8; ++e) x[e] = cmul_h2(x[e], bw.h);
             }
             const int a0 = staged_slot<LG>(n);
 #pragma unroll
@@ -1155,6 +1152,19 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
         for (int i = 0; i < 8; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[i][j] = make_float2(0.f, 0.f);
+        if (SPLIT && par == 0) {
+            // second walk: w_{16TC}^(k_b t) w_{2N}^t in the phase-1 table (phase 1 of the first walk is long
+            // over; two barriers follow before the next one reads it)
+            for (int i = tid; i < C::TC * 4; i += NT) {
+                const float2 w = tw_full(tw, (uint32_t)(i >> 2) << (TW_LOG2 - LG - 1));
+                const h2 tau = {(_Float16)w.x, (_Float16)w.y};
+                H8U e;
+                e.u = gtab[C::T1F + i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) e.w[j] = cmul_h2(e.w[j], tau);
+                t1f[i] = e.u;
+            }
+        }
     }
 
     if (dD) {
