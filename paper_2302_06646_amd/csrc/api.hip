@@ -174,7 +174,8 @@ static hipError_t run_kspec(const float* k, const float* D, float2* kspec, float
     if (pl.engine == ENGINE_MFMA && (pl.order.wave_lg || pl.order.coop_lg)) {
         // matrix-core route: per-head power-of-two pre-scale, (pass A,) forward half of the fused kernel
         if (pl.order.wave_lg) return wave_kspec(k, D, kspec, H, N, pl, tb, st);
-        if (!pl.log2R) return coop_kspec(k, nullptr, D, nullptr, kspec, H, N, pl, tb, st);   // finds the maxima itself
+        // single pass, or pass A taken inside the kernel: it reads k itself and finds the maxima
+        if (!pl.log2R || pl.fuse_a) return coop_kspec(k, nullptr, D, nullptr, kspec, H, N, pl, tb, st);
         hipError_t e = head_max(k, hscale, H, N, st);
         if (e != hipSuccess) return e;
         if (pl.log2R) {

@@ -140,7 +140,7 @@ __device__ __forceinline__ void make_consts(Consts<LG>& K, const float2* __restr
 // otherwise w[j][0..3] = row a sample pairs, w[j][4..7] = row b sample pairs (fp16).
 template <int LG, bool CPLX, int NB = NTB>
 __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t* xb, const uint4* gtab,
-                                            const uint4* t1f, const Consts<LG>& K, int t0, int lane)
+                                            const uint4* t1f, const Mats& F1, const Mats& F2, int t0, int lane)
 {
     using C = CC<LG>;
     const int c = lane & 15, g = lane >> 4;
@@ -166,16 +166,16 @@ __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t*
                 else x.w[j] = (tt & 1) ? __builtin_amdgcn_perm(w[j][4 + (tt >> 1)], w[j][tt >> 1], 0x07060302u)
                                        : __builtin_amdgcn_perm(w[j][4 + (tt >> 1)], w[j][tt >> 1], 0x05040100u);
             }
-            yr[k] = MFMA(x.v, K.F16.re, zero);
-            yi[k] = MFMA(x.v, K.F16.im, zero);
+            yr[k] = MFMA(x.v, F1.re, zero);
+            yi[k] = MFMA(x.v, F1.im, zero);
         }
 #pragma unroll
         for (int k = 0; k < NB; ++k) {
             H8U u;
 #pragma unroll
             for (int j = 0; j < 4; ++j) u.w[j] = cmul_pack(yr[k][j], yi[k][j], tw0[k].c[j]);
-            zr[k] = MFMA(K.F16.re, u.v, zero);
-            zi[k] = MFMA(K.F16.im, u.v, zero);
+            zr[k] = MFMA(F2.re, u.v, zero);
+            zi[k] = MFMA(F2.im, u.v, zero);
         }
 #pragma unroll
         for (int k = 0; k < NB; ++k) {
@@ -194,7 +194,7 @@ template <int LG>
 __device__ __forceinline__ void phase1_regs(const uint32_t (&w)[4][8], uint32_t* xb, const uint4* gtab,
                                             const uint4* t1f, const Consts<LG>& K, int t0, int lane)
 {
-    phase1_core<LG, false>(w, xb, gtab, t1f, K, t0, lane);
+    phase1_core<LG, false>(w, xb, gtab, t1f, K.F16, K.F16, t0, lane);
 }
 
 // ---- phase 1 for the 8 tiles t0..t0+7 of one wave, operands from a chunk of L fp16 complex values
@@ -212,7 +212,7 @@ __device__ __forceinline__ void phase1(const __half2* chunk, uint32_t* xb, const
         load_words<4>(chunk + n0, &w[j][0]);
         load_words<4>(chunk + n0 + 4, &w[j][4]);
     }
-    phase1_core<LG, true, NB>(w, xb, gtab, t1f, K, t0, lane);
+    phase1_core<LG, true, NB>(w, xb, gtab, t1f, K.F16, K.F16, t0, lane);
 }
 
 // word address of (tile t2, reg 0) for this lane in phase 2; reg j adds j*TE*4 words
@@ -1343,7 +1343,7 @@ coop_dk_kernel(const __half2* __restrict__ ws_u, const __half2* __restrict__ ws_
 // Phase 1 and the forward half of phase 2 as in the convolution; value stored =
 // kscale * (FFT([k,0]) + D[h]) as fp16 complex (one 32-bit word per bin).
 // -------------------------------------------------------------------------------------
-template <int LG, bool CPLX>
+template <int LG, int MODE>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, const float* __restrict__ D,
                   const float* __restrict__ rs, float2* __restrict__ kspec, int64_t N, int log2R,
@@ -1351,6 +1351,8 @@ coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, c
                   const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
+    constexpr bool CPLX = MODE == 1, FUSE = MODE >= 2;
+    constexpr int LR = FUSE ? MODE : 1, RH = (1 << LR) / 2;      // FUSE: outer radix 2^LR, R/2 non-zero terms
     extern __shared__ uint4 lds4[];
     uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
     uint4* t1f = lds4 + C::XWORDS / 4;
@@ -1359,7 +1361,17 @@ coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, c
     const int h = blockIdx.x, k1 = blockIdx.y;
     const int64_t Ltot = (int64_t)C::L << log2R;
     const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
-    for (int i = tid; i < C::TC * 8; i += C::NW * 64) t1f[i] = gtab[C::T1F + i];
+    for (int i = tid; i < C::TC * 8; i += C::NW * 64) {
+        H8U e;
+        e.u = gtab[C::T1F + i];
+        if (FUSE && i < C::TC * 4) {         // forward table times the tile part of pass A's twist
+            const float2 w = tw_full(tw, (uint32_t)(k1 * (i >> 2)) << (TW_LOG2 - LG - LR));
+            const h2 tau = {(_Float16)w.x, (_Float16)w.y};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e.w[j] = cmul_h2(e.w[j], tau);
+        }
+        t1f[i] = e.u;
+    }
     Consts<LG> K;
     make_consts<LG>(K, tw, lane);
     const float* kr = k + (size_t)h * N;
@@ -1367,7 +1379,7 @@ coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, c
     // scale), else from a scan of the head's kernel row here
     float m = 0.f;
     __shared__ float mred[C::NW];
-    if (!CPLX) {
+    if (!CPLX) {      // (FUSE: every chunk's workgroup scans the whole row)
         const float4* k4 = reinterpret_cast<const float4*>(kr);
         for (int i = tid; i < (int)(N / 4); i += C::NW * 64) {
             const float4 v = k4[i];
@@ -1390,6 +1402,31 @@ coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, c
         const int t0 = (gi * C::NW + wave) * 8;
         if (CPLX) {
             phase1<LG>(chunk, xb, gtab, t1f, K, t0, lane);
+        } else if (FUSE) {
+            // pass A on the fly: s[n2] = sum_{n1 < R/2} w_R^(n1 k1) k[n1 L + n2], its twist folded into the
+            // phase-1 matrices (d_a, d_b parts) and the table above (tile part), as in the convolution
+            const Mats F1 = phase_mats(k1, C::cb + 4, LG + LR, tw, lane), F2 = phase_mats(k1, C::cb, LG + LR, tw, lane);
+            float2 cr[RH];
+#pragma unroll
+            for (int n1 = 0; n1 < RH; ++n1)
+                cr[n1] = tw_full(tw, (uint32_t)((n1 * k1) & ((1 << LR) - 1)) << (TW_LOG2 - LR));
+            uint32_t w[4][8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    float sr = 0.f, si = 0.f;
+#pragma unroll
+                    for (int n1 = 0; n1 < RH; ++n1) {
+                        const float v = kr[(size_t)n1 * C::L + n0 + i] * r;
+                        sr = __builtin_fmaf(cr[n1].x, v, sr);
+                        si = __builtin_fmaf(cr[n1].y, v, si);
+                    }
+                    w[j][i] = pack_h2(sr, si);
+                }
+            }
+            phase1_core<LG, true>(w, xb, gtab, t1f, F1, F2, t0, lane);
         } else {
             // stage the fp32 kernel row as fp16 in registers, then the common phase 1 on them
             uint32_t w[4][8];
@@ -1553,21 +1590,20 @@ hipError_t coop_kspec_go(const float* k, const __half2* ws, const float* D, cons
     dim3 grid((unsigned)H, 1u << pl.log2R);
     const int shift = 6 + (C::te >= 2 ? 1 : 0);
     const float koc = pl.kscale * (float)(1 << shift);
-    hipError_t e;
-    if (pl.log2R == 0) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_kspec_kernel<LG, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    auto launch = [&](auto kern) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((coop_kspec_kernel<LG, false>), grid, dim3(C::NW * 64), lds, st, k, ws, D, rs, kspec, N,
-                           pl.log2R, koc, pl.kscale, tb.tw, (const unsigned char*)tb.ctab);
-    } else {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_kspec_kernel<LG, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((coop_kspec_kernel<LG, true>), grid, dim3(C::NW * 64), lds, st, k, ws, D, rs, kspec, N,
-                           pl.log2R, koc, pl.kscale, tb.tw, (const unsigned char*)tb.ctab);
+        hipLaunchKernelGGL(kern, grid, dim3(C::NW * 64), lds, st, k, ws, D, rs, kspec, N, pl.log2R, koc, pl.kscale,
+                           tb.tw, (const unsigned char*)tb.ctab);
+        return hipGetLastError();
+    };
+    if (pl.log2R == 0) return launch(coop_kspec_kernel<LG, 0>);
+    if constexpr (LG == COOP_MAX_LOG2) {      // pass A inside (ws and rs unused)
+        if (pl.fuse_a && pl.log2R == 2) return launch(coop_kspec_kernel<LG, 2>);
+        if (pl.fuse_a && pl.log2R == 3) return launch(coop_kspec_kernel<LG, 3>);
     }
-    return hipGetLastError();
+    return launch(coop_kspec_kernel<LG, 1>);
 }
 
 }  // namespace
