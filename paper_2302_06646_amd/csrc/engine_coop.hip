@@ -656,6 +656,96 @@ __device__ __forceinline__ Mats phase_mats(int k1, int wl, int lt, const float2*
     return A;
 }
 
+// forward w_{16TC} table times the tile part w_{2^LR L}^(k1 t) of pass A's twist
+template <int LG, int LR, int NT>
+__device__ __forceinline__ void twisted_t1f(uint4* t1f, const uint4* gtab, int k1, const float2* __restrict__ tw, int tid)
+{
+    using C = CC<LG>;
+    for (int i = tid; i < C::TC * 4; i += NT) {
+        const float2 w = tw_full(tw, (uint32_t)(k1 * (i >> 2)) << (TW_LOG2 - LG - LR));
+        const h2 tau = {(_Float16)w.x, (_Float16)w.y};
+        H8U e;
+        e.u = gtab[C::T1F + i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) e.w[j] = cmul_h2(e.w[j], tau);
+        t1f[i] = e.u;
+    }
+}
+
+// Pass A of chunk k1 while staging: rows a, b of one pair (N = 2^(LR-1) L samples each) ->
+// s[n2] = sum_{n1 < R/2} w_R^(n1 k1) z[n1 L + n2], z = a + i b, R = 2^LR, into the exchange slots.  The twist
+// is not applied here (it sits in the phase-1 operands).  One packed fp16 complex multiply-add per term.
+template <int LG, class IO, int LR, int NT>
+__device__ __forceinline__ void stage_rows_pass_a(uint32_t* xb, const typename IO::T* ra, const typename IO::T* rb,
+                                                  bool has_b, int k1, const float2* __restrict__ tw, int tid)
+{
+    using C = CC<LG>;
+    constexpr int RH = (1 << LR) / 2;
+    h2 cr[RH], crs[RH];                              // w_R^(n1 k1) and i times it
+#pragma unroll
+    for (int n1 = 1; n1 < RH; ++n1) {
+        const float2 w = tw_full(tw, (uint32_t)((n1 * k1) & ((1 << LR) - 1)) << (TW_LOG2 - LR));
+        cr[n1] = h2{(_Float16)w.x, (_Float16)w.y};
+        crs[n1] = h2{(_Float16)(-w.y), (_Float16)w.x};
+    }
+    constexpr int RPA = (C::L / 8) / NT;             // runs of eight samples per lane
+    constexpr int RB = RH <= 2 ? 2 : 1;              // runs in flight
+#pragma unroll
+    for (int i0 = 0; i0 < RPA; i0 += RB) {
+        uint4 va[RB][RH], vb[RB][RH];
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+            const int n = staged_run_n<LG>((i0 + i) * NT + tid);
+#pragma unroll
+            for (int n1 = 0; n1 < RH; ++n1) {
+                va[i][n1] = *reinterpret_cast<const uint4*>(ra + (size_t)n1 * C::L + n);
+                vb[i][n1] = *reinterpret_cast<const uint4*>(rb + (size_t)n1 * C::L + n);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+            uint32_t wa[RH][4], wb[RH][4];
+#pragma unroll
+            for (int n1 = 0; n1 < RH; ++n1) {
+                wa[n1][0] = va[i][n1].x; wa[n1][1] = va[i][n1].y; wa[n1][2] = va[i][n1].z; wa[n1][3] = va[i][n1].w;
+                wb[n1][0] = vb[i][n1].x; wb[n1][1] = vb[i][n1].y; wb[n1][2] = vb[i][n1].z; wb[n1][3] = vb[i][n1].w;
+                if (!has_b) wb[n1][0] = wb[n1][1] = wb[n1][2] = wb[n1][3] = 0u;
+                if (IsBf<IO>::v) {
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) { wa[n1][m] = bf2_to_h2(wa[n1][m]); wb[n1][m] = bf2_to_h2(wb[n1][m]); }
+                }
+            }
+            const int a0 = staged_slot<LG>(staged_run_n<LG>((i0 + i) * NT + tid));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                union { uint32_t u; h2 h; } acc, z;
+                acc.u = __builtin_amdgcn_perm(wb[0][e >> 1], wa[0][e >> 1], sel);
+#pragma unroll
+                for (int n1 = 1; n1 < RH; ++n1) {
+                    z.u = __builtin_amdgcn_perm(wb[n1][e >> 1], wa[n1][e >> 1], sel);
+                    const h2 x = {z.h[0], z.h[0]}, y = {z.h[1], z.h[1]};
+                    acc.h = __builtin_elementwise_fma(y, crs[n1], __builtin_elementwise_fma(x, cr[n1], acc.h));
+                }
+                xb[a0 + 4 * e] = acc.u;
+            }
+        }
+    }
+}
+
+// run r of a chunk of complex values (16-byte runs of four) -> first value n; lane bits as for the rows:
+// position in a 64-byte segment, d_a % 4, d_b % 4
+template <int LG>
+__device__ __forceinline__ int chunk_run_n(int r)
+{
+    using C = CC<LG>;
+    constexpr int QB = C::cb - 2;                // runs per (d_a, d_b) row = TC / 4
+    const int q = (r & 3) | (((r >> 6) & ((1 << (QB - 2)) - 1)) << 2);
+    const int da = ((r >> 2) & 3) | ((r >> (QB + 6)) << 2);
+    const int db = ((r >> 4) & 3) | (((r >> (QB + 4)) & 3) << 2);
+    return (da << (C::cb + 4)) + (db << C::cb) + 4 * q;
+}
+
 template <int LG, class IO, int NWV, int NB, bool CONJ, int FUSEA>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec, __half2* __restrict__ ws,
@@ -689,14 +779,7 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     asm volatile("" : "+s"(ng));
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
 
-    auto run_n = [&](int i) {
-        constexpr int QB = C::cb - 2;                // runs per (d_a, d_b) row = TC / 4
-        const int r = i * NT + tid;
-        const int q = (r & 3) | (((r >> 6) & ((1 << (QB - 2)) - 1)) << 2);
-        const int da = ((r >> 2) & 3) | ((r >> (QB + 6)) << 2);
-        const int db = ((r >> 4) & 3) | (((r >> (QB + 4)) & 3) << 2);
-        return (da << (C::cb + 4)) + (db << C::cb) + 4 * q;
-    };
+    auto run_n = [&](int i) { return chunk_run_n<LG>(i * NT + tid); };
     auto chunk_of = [&](int it) {
         const int hk = it / npairs, p = it - hk * npairs;
         const int h = hk >> log2R, k1 = hk & ((1 << log2R) - 1);
@@ -728,72 +811,15 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     // FUSEA: rows of the item -> pass-A sum -> slots; phase-1 operands of the item
     Mats F1 = K.F16, F2 = K.F16;
     auto stage_rows = [&](int it) __attribute__((always_inline)) {
-        constexpr int LR = FUSEA > 0 ? FUSEA : 2, RH = (1 << LR) / 2;
+        constexpr int LR = FUSEA > 0 ? FUSEA : 2;
         const int hk = it / npairs, p = it - hk * npairs;
         const int h = hk >> LR, k1 = hk & ((1 << LR) - 1);
         F1 = phase_mats(k1, C::cb + 4, LG + LR, tw, lane);
         F2 = phase_mats(k1, C::cb, LG + LR, tw, lane);
-        for (int i = tid; i < C::TC * 4; i += NT) {      // w_{16TC}^(k_b t) w_{RL}^(k1 t)
-            const float2 w = tw_full(tw, (uint32_t)(k1 * (i >> 2)) << (TW_LOG2 - LG - LR));
-            const h2 tau = {(_Float16)w.x, (_Float16)w.y};
-            H8U e;
-            e.u = gtab[C::T1F + i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) e.w[j] = cmul_h2(e.w[j], tau);
-            t1f[i] = e.u;
-        }
+        twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);
         const bool has_b = (2 * p + 1) < B;
         const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
-        h2 cr[RH], crs[RH];                              // w_R^(n1 k1) and i times it
-#pragma unroll
-        for (int n1 = 1; n1 < RH; ++n1) {
-            const float2 w = tw_full(tw, (uint32_t)((n1 * k1) & ((1 << LR) - 1)) << (TW_LOG2 - LR));
-            cr[n1] = h2{(_Float16)w.x, (_Float16)w.y};
-            crs[n1] = h2{(_Float16)(-w.y), (_Float16)w.x};
-        }
-        constexpr int RPA = (C::L / 8) / NT;             // runs of eight samples per lane
-        constexpr int RB = RH <= 2 ? 2 : 1;              // runs in flight
-#pragma unroll
-        for (int i0 = 0; i0 < RPA; i0 += RB) {
-            uint4 va[RB][RH], vb[RB][RH];
-#pragma unroll
-            for (int i = 0; i < RB; ++i) {
-                const int n = staged_run_n<LG>((i0 + i) * NT + tid);
-#pragma unroll
-                for (int n1 = 0; n1 < RH; ++n1) {
-                    va[i][n1] = *reinterpret_cast<const uint4*>(in + oa + (size_t)n1 * C::L + n);
-                    vb[i][n1] = *reinterpret_cast<const uint4*>(in + ob + (size_t)n1 * C::L + n);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < RB; ++i) {
-                uint32_t wa[RH][4], wb[RH][4];
-#pragma unroll
-                for (int n1 = 0; n1 < RH; ++n1) {
-                    wa[n1][0] = va[i][n1].x; wa[n1][1] = va[i][n1].y; wa[n1][2] = va[i][n1].z; wa[n1][3] = va[i][n1].w;
-                    wb[n1][0] = vb[i][n1].x; wb[n1][1] = vb[i][n1].y; wb[n1][2] = vb[i][n1].z; wb[n1][3] = vb[i][n1].w;
-                    if (!has_b) wb[n1][0] = wb[n1][1] = wb[n1][2] = wb[n1][3] = 0u;
-                    if (IsBf<IO>::v) {
-#pragma unroll
-                        for (int m = 0; m < 4; ++m) { wa[n1][m] = bf2_to_h2(wa[n1][m]); wb[n1][m] = bf2_to_h2(wb[n1][m]); }
-                    }
-                }
-                const int a0 = staged_slot<LG>(staged_run_n<LG>((i0 + i) * NT + tid));
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-                    union { uint32_t u; h2 h; } acc, z;
-                    acc.u = __builtin_amdgcn_perm(wb[0][e >> 1], wa[0][e >> 1], sel);
-#pragma unroll
-                    for (int n1 = 1; n1 < RH; ++n1) {
-                        z.u = __builtin_amdgcn_perm(wb[n1][e >> 1], wa[n1][e >> 1], sel);
-                        const h2 x = {z.h[0], z.h[0]}, y = {z.h[1], z.h[1]};
-                        acc.h = __builtin_elementwise_fma(y, crs[n1], __builtin_elementwise_fma(x, cr[n1], acc.h));
-                    }
-                    xb[a0 + 4 * e] = acc.u;
-                }
-            }
-        }
+        stage_rows_pass_a<LG, IO, LR, NT>(xb, in + oa, in + ob, has_b, k1, tw, tid);
     };
     auto stage_item = [&](int it) __attribute__((always_inline)) {
         if (FUSEA) stage_rows(it);
