@@ -316,6 +316,8 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
     if (want_dkD) {
         hipError_t e = hipSuccess;
         float* dpart = (float*)(base + w.dpart);
+        int cR = pl.log2R, cL2 = pl.log2L2;        // the split and scale pass C of dk works with
+        float cscale = pl.dkscale;
         if (pl.engine == ENGINE_VALU) {
             if (pl.log2R) {
                 // pass A for u (-> ws2) and dy (-> ws1) in one launch, with the dD partial sums
@@ -327,6 +329,12 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
             if (e == hipSuccess && (dk || !pl.log2R))
                 e = valu_dk(dy, u, dk, dD, (const float2*)(base + w.ws2), (const float2*)(base + w.ws1),
                             (float2*)(base + w.wsA), pr, pl, tw, st);
+        } else if (coop_dk_rows_ok(pl)) {
+            // straight from the rows, as outer radix 8 around 16384-point transforms (no pass A kernel)
+            cR += 1; cL2 -= 1;
+            e = coop_dk_rows(dy, u, dk ? (__half2*)(base + w.wsA) : nullptr, dD ? dpart : nullptr, pr, pl, tb, st,
+                             &cscale);
+            if (e == hipSuccess && dD) e = reduce_dD(dpart, dD, H, 1 << cR, st);
         } else {
             if (pl.log2R) {
                 e = outer_fwd(dy, u, base + w.ws1, base + w.ws2, nullptr, pr, pl.log2R, pl.log2L2, 1.0f, true,
@@ -340,7 +348,7 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
         }
         if (e == hipSuccess && pl.log2R && dk) {
             Problem pk{1, H, N, LONGCONV_F32, 1};   // heads as single rows, real part only
-            e = outer_inv(base + w.wsA, dk, pk, pl.log2R, pl.log2L2, pl.dkscale, f16ws, tw, st);
+            e = outer_inv(base + w.wsA, dk, pk, cR, cL2, cscale, f16ws, tw, st);
         }
         if (note(e, "bwd dk/dD") != hipSuccess) return LONGCONV_ERR_HIP;
     }

@@ -675,9 +675,10 @@ __device__ __forceinline__ void twisted_t1f(uint4* t1f, const uint4* gtab, int k
 // Pass A of chunk k1 while staging: rows a, b of one pair (N = 2^(LR-1) L samples each) ->
 // s[n2] = sum_{n1 < R/2} w_R^(n1 k1) z[n1 L + n2], z = a + i b, R = 2^LR, into the exchange slots.  The twist
 // is not applied here (it sits in the phase-1 operands).  One packed fp16 complex multiply-add per term.
-template <int LG, class IO, int LR, int NT>
-__device__ __forceinline__ void stage_rows_pass_a(uint32_t* xb, const typename IO::T* ra, const typename IO::T* rb,
-                                                  bool has_b, int k1, const float2* __restrict__ tw, int tid)
+// HASB = false: the pair has no row b (odd batch); twice as many runs are then in flight per round trip.
+template <int LG, class IO, int LR, int NT, bool HASB>
+__device__ __forceinline__ void stage_rows_pass_a_impl(uint32_t* xb, const typename IO::T* ra, const typename IO::T* rb,
+                                                       int k1, const float2* __restrict__ tw, int tid)
 {
     using C = CC<LG>;
     constexpr int RH = (1 << LR) / 2;
@@ -689,17 +690,19 @@ __device__ __forceinline__ void stage_rows_pass_a(uint32_t* xb, const typename I
         crs[n1] = h2{(_Float16)(-w.y), (_Float16)w.x};
     }
     constexpr int RPA = (C::L / 8) / NT;             // runs of eight samples per lane
-    constexpr int RB = RH <= 2 ? 2 : 1;              // runs in flight
+    constexpr int RB = (RH <= 2 ? 2 : 1) * (HASB ? 1 : 2);      // runs in flight
+    constexpr int NV = HASB ? 2 : 1;
+    static_assert(RPA % RB == 0, "runs in flight divide the runs of a lane");
 #pragma unroll
     for (int i0 = 0; i0 < RPA; i0 += RB) {
-        uint4 va[RB][RH], vb[RB][RH];
+        uint4 v[RB][NV][RH];
 #pragma unroll
         for (int i = 0; i < RB; ++i) {
             const int n = staged_run_n<LG>((i0 + i) * NT + tid);
 #pragma unroll
             for (int n1 = 0; n1 < RH; ++n1) {
-                va[i][n1] = *reinterpret_cast<const uint4*>(ra + (size_t)n1 * C::L + n);
-                vb[i][n1] = *reinterpret_cast<const uint4*>(rb + (size_t)n1 * C::L + n);
+                v[i][0][n1] = *reinterpret_cast<const uint4*>(ra + (size_t)n1 * C::L + n);
+                if (HASB) v[i][NV - 1][n1] = *reinterpret_cast<const uint4*>(rb + (size_t)n1 * C::L + n);
             }
         }
 #pragma unroll
@@ -707,12 +710,15 @@ __device__ __forceinline__ void stage_rows_pass_a(uint32_t* xb, const typename I
             uint32_t wa[RH][4], wb[RH][4];
 #pragma unroll
             for (int n1 = 0; n1 < RH; ++n1) {
-                wa[n1][0] = va[i][n1].x; wa[n1][1] = va[i][n1].y; wa[n1][2] = va[i][n1].z; wa[n1][3] = va[i][n1].w;
-                wb[n1][0] = vb[i][n1].x; wb[n1][1] = vb[i][n1].y; wb[n1][2] = vb[i][n1].z; wb[n1][3] = vb[i][n1].w;
-                if (!has_b) wb[n1][0] = wb[n1][1] = wb[n1][2] = wb[n1][3] = 0u;
+                const uint4 a4 = v[i][0][n1], b4 = HASB ? v[i][NV - 1][n1] : make_uint4(0u, 0u, 0u, 0u);
+                wa[n1][0] = a4.x; wa[n1][1] = a4.y; wa[n1][2] = a4.z; wa[n1][3] = a4.w;
+                wb[n1][0] = b4.x; wb[n1][1] = b4.y; wb[n1][2] = b4.z; wb[n1][3] = b4.w;
                 if (IsBf<IO>::v) {
 #pragma unroll
-                    for (int m = 0; m < 4; ++m) { wa[n1][m] = bf2_to_h2(wa[n1][m]); wb[n1][m] = bf2_to_h2(wb[n1][m]); }
+                    for (int m = 0; m < 4; ++m) {
+                        wa[n1][m] = bf2_to_h2(wa[n1][m]);
+                        if (HASB) wb[n1][m] = bf2_to_h2(wb[n1][m]);
+                    }
                 }
             }
             const int a0 = staged_slot<LG>(staged_run_n<LG>((i0 + i) * NT + tid));
@@ -731,6 +737,14 @@ __device__ __forceinline__ void stage_rows_pass_a(uint32_t* xb, const typename I
             }
         }
     }
+}
+
+template <int LG, class IO, int LR, int NT>
+__device__ __forceinline__ void stage_rows_pass_a(uint32_t* xb, const typename IO::T* ra, const typename IO::T* rb,
+                                                  bool has_b, int k1, const float2* __restrict__ tw, int tid)
+{
+    if (has_b) stage_rows_pass_a_impl<LG, IO, LR, NT, true>(xb, ra, rb, k1, tw, tid);
+    else stage_rows_pass_a_impl<LG, IO, LR, NT, false>(xb, ra, rb, k1, tw, tid);
 }
 
 // run r of a chunk of complex values (16-byte runs of four) -> first value n; lane bits as for the rows:
@@ -1206,6 +1220,145 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
 }
 
 // -------------------------------------------------------------------------------------
+// dk and dD of the multi-pass split straight from the rows (outer radix 2^LR around 2^LG-point transforms,
+// pass A taken while staging as in coop_conv_kernel).  grid = (H, 2^LR); the workgroup of (head, chunk k1)
+// walks the head's row pairs: u pair -> pass A, phase 1, forward half of phase 2 -> Z (fp16 registers);
+// dy pair likewise -> W; A += conj(Z) W in fp32 registers, eight phase-2 tiles per wave.  Then the inverse
+// half of phase 2 and phase 3 give chunk k1 of pass C's input (fp16 complex, unit-stride runs), and the
+// accumulators' real parts this chunk's share of dD.
+// -------------------------------------------------------------------------------------
+template <int LG, class IO, int LR>
+__global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
+                    __half2* __restrict__ ws_A, float* __restrict__ dD_part, int64_t B, int64_t H, int64_t N,
+                    int npairs, float dDscale, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
+{
+    using C = CC<LG>;
+    using T = typename IO::T;
+    static_assert(C::NG == 1, "one group of eight phase-2 tiles per wave");
+    constexpr int NT = C::NW * 64;
+    extern __shared__ uint4 lds4[];
+    __shared__ float red[C::NW];
+    uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
+    uint4* t1f = lds4 + C::XWORDS / 4;
+    uint4* t1i = t1f + C::TC * 4;
+    uint32_t* vt = reinterpret_cast<uint32_t*>(t1i + C::TC * 4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    // the 2^LR workgroups of a head read the same rows: consecutive ids, renumbered so that they share an XCD
+    // (one L2), fetch them from HBM once
+    const unsigned G = gridDim.x;
+    const unsigned vid = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (G >> 3) + (blockIdx.x >> 3);
+    const int h = (int)(vid >> LR), k1 = (int)(vid & ((1u << LR) - 1u));
+    const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
+    Consts<LG> K;
+    make_consts<LG>(K, tw, lane);
+    h2 cF[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 w = tw_full(tw, (uint32_t)((c * (4 * g + j)) & 255) << (TW_LOG2 - 8));
+        cF[j] = h2{(_Float16)w.x, (_Float16)w.y};
+    }
+    // phase-1 operands of this chunk: pass A's twist in the matrix columns and the w_{16TC} table
+    const Mats F1 = phase_mats(k1, C::cb + 4, LG + LR, tw, lane), F2 = phase_mats(k1, C::cb, LG + LR, tw, lane);
+    staged_tables<LG, NT>(lds4, gtab, tw, tid, 0);
+    __syncthreads();
+    twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);
+
+    const int t0 = wave * 8;                             // this wave's tiles in every phase
+    float2 acc[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = make_float2(0.f, 0.f);
+
+#pragma unroll 1
+    for (int p = 0; p < npairs; ++p) {
+        const bool has_b = (2 * p + 1) < B;
+        const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
+        uint32_t z[8][4];
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+            int zoff = 0;
+            asm volatile("" : "+v"(zoff));               // table reads stay inside the walk
+            const uint4* t1f_ = t1f + zoff;
+            const uint32_t* vt_ = vt + zoff;
+            const T* src = pass ? dy : u;
+            __syncthreads();                             // the slots are free (and the tables written)
+            stage_rows_pass_a<LG, IO, LR, NT>(xb, src + oa, src + ob, has_b, k1, tw, tid);
+            __syncthreads();
+            phase1_inplace<LG, 2>(xb, t1f_, vt_, F1, F2, cF, t0, lane);
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                f4 zr, zi;
+                phase2_fwd<LG>(xb, phase2_base<LG>(t0 + i, lane), K, zr, zi);
+                if (pass == 0) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) z[i][j] = pack_h2(zr[j], zi[j]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        union { uint32_t u; h2 hh; } cv;
+                        cv.u = z[i][j];
+                        const float a = (float)cv.hh[0], b = (float)cv.hh[1];
+                        // conj(Z) * W, one fused multiply-add per term
+                        acc[i][j].x = __builtin_fmaf(b, zi[j], __builtin_fmaf(a, zr[j], acc[i][j].x));
+                        acc[i][j].y = __builtin_fmaf(-b, zr[j], __builtin_fmaf(a, zi[j], acc[i][j].y));
+                    }
+                }
+                if (i & 1) __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    float dsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dsum += acc[i][j].x;
+    if (dD_part) {
+        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+        if (lane == 0) red[wave] = dsum;
+    }
+    __syncthreads();                                     // every wave is done reading the slots
+    if (dD_part && tid == 0) {
+        float t = 0.f;
+        for (int w = 0; w < C::NW; ++w) t += red[w];
+        dD_part[((size_t)h << LR) + k1] = t * dDscale;
+    }
+    if (!ws_A) return;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        H8U m;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(acc[i][j].x, acc[i][j].y);
+        phase2_inv<LG>(xb, phase2_base<LG>(t0 + i, lane), K, m);
+    }
+    __syncthreads();
+    const int w1 = (c * C::PITCH + g * C::TC) * 4;
+#pragma unroll
+    for (int tb = 0; tb < 8; tb += 2) {
+        f4 r[2], s2[2];
+        phase3_two_lds<LG>(xb, t1i, vt, K, cF, t0 + tb, lane, r, s2);
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) =
+                make_uint4(pack_h2(r[k][0], s2[k][0]), pack_h2(r[k][1], s2[k][1]), pack_h2(r[k][2], s2[k][2]),
+                           pack_h2(r[k][3], s2[k][3]));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+    uint4* dst = reinterpret_cast<uint4*>(ws_A + ((size_t)h << (LG + LR)) + (size_t)k1 * C::L);
+    constexpr int RPL = (C::L / 4) / NT;
+#pragma unroll
+    for (int i = 0; i < RPL; ++i) {
+        const int n = chunk_run_n<LG>(i * NT + tid), a0 = staged_slot<LG>(n);
+        dst[n / 4] = make_uint4(xb[a0], xb[a0 + 4], xb[a0 + 8], xb[a0 + 12]);
+    }
+}
+
+// -------------------------------------------------------------------------------------
 // dk and dD of the multi-pass split: one workgroup per (head, chunk k1) loops over all row pairs of the
 // head in order, reading chunk k1 of pass A's outputs.  Per pair: Z = transform of the u chunk (kept as
 // fp16 in registers), W = transform of the dy chunk, A += conj(Z) W in fp32 registers, in the lane order
@@ -1384,7 +1537,13 @@ coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, c
     uint4* t1f = lds4 + C::XWORDS / 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
-    const int h = blockIdx.x, k1 = blockIdx.y;
+    int h = blockIdx.x, k1 = blockIdx.y;
+    if (FUSE) {       // 1-D grid, chunk index fastest, renumbered per XCD: the chunks of a head share its row in L2
+        const unsigned G = gridDim.x;
+        const unsigned vid = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (G >> 3) + (blockIdx.x >> 3);
+        h = (int)(vid >> LR);
+        k1 = (int)(vid & ((1u << LR) - 1u));
+    }
     const int64_t Ltot = (int64_t)C::L << log2R;
     const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
     for (int i = tid; i < C::TC * 8; i += C::NW * 64) {
@@ -1607,6 +1766,29 @@ hipError_t coop_dk_real_go(const void* dy, const void* u, float* dk, float* dD, 
     return hipGetLastError();
 }
 
+// Multi-pass dk from the rows: the plan's split (outer radix 2^log2R around 32768 points) is taken as outer
+// radix 2^(log2R+1) around 16384 points, whose accumulators fit one walk.  Returns the scale pass C has to
+// apply (two forward chains and one inverse chain of the 16384-point transform, 1 / padded length).
+template <class IO, int LR>
+hipError_t coop_dk_rows_go(const void* dy, const void* u, __half2* ws_A, float* dD_part, const Problem& pr,
+                           const Tables& tb, hipStream_t st, float* scale_c)
+{
+    constexpr int LG = COOP_MAX_LOG2 - 1;
+    using T = typename IO::T;
+    using C = CC<LG>;
+    const size_t lds = coop_real_lds_bytes<LG>();
+    const int shift = 6 + (C::te >= 2 ? 1 : 0);
+    const float dkscale = (float)(int64_t(1) << (3 * shift)) / (float)(2 * pr.N);
+    *scale_c = dkscale;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_dk_rows_kernel<LG, IO, LR>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((coop_dk_rows_kernel<LG, IO, LR>), dim3((unsigned)(pr.H << LR)), dim3(C::NW * 64), lds, st,
+                       (const T*)dy, (const T*)u, ws_A, dD_part, pr.B, pr.H, pr.N, pr.npairs,
+                       dkscale / (float)(1 << shift), tb.tw, (const unsigned char*)tb.ctab);
+    return hipGetLastError();
+}
+
 template <int LG>
 hipError_t coop_kspec_go(const float* k, const __half2* ws, const float* D, const float* rs, float2* kspec,
                          int64_t H, int64_t N, const Plan& pl, const Tables& tb, hipStream_t st)
@@ -1626,6 +1808,7 @@ hipError_t coop_kspec_go(const float* k, const __half2* ws, const float* D, cons
     };
     if (pl.log2R == 0) return launch(coop_kspec_kernel<LG, 0>);
     if constexpr (LG == COOP_MAX_LOG2) {      // pass A inside (ws and rs unused)
+        if (pl.fuse_a) grid = dim3((unsigned)(H << pl.log2R));
         if (pl.fuse_a && pl.log2R == 2) return launch(coop_kspec_kernel<LG, 2>);
         if (pl.fuse_a && pl.log2R == 3) return launch(coop_kspec_kernel<LG, 3>);
     }
@@ -1683,6 +1866,15 @@ hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, const __
     if (pl.log2L2 == 13) return coop_dk_go<13>(ws_u, ws_dy, dk ? ws_A : nullptr, dD_part, zbuf, pr, pl, tb, st);
     if (pl.log2L2 == 14) return coop_dk_go<14>(ws_u, ws_dy, dk ? ws_A : nullptr, dD_part, zbuf, pr, pl, tb, st);
     if (pl.log2L2 == 15) return coop_dk_go<15>(ws_u, ws_dy, dk ? ws_A : nullptr, dD_part, zbuf, pr, pl, tb, st);
+    return hipErrorInvalidValue;
+}
+
+hipError_t coop_dk_rows(const void* dy, const void* u, __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl,
+                        const Tables& tb, hipStream_t st, float* scale_c)
+{
+    if (!coop_dk_rows_ok(pl)) return hipErrorInvalidValue;
+    if (pr.io == LONGCONV_F16) return coop_dk_rows_go<IoF16, 3>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
+    if (pr.io == LONGCONV_BF16) return coop_dk_rows_go<IoBF16, 3>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
     return hipErrorInvalidValue;
 }
 
