@@ -136,9 +136,8 @@ __device__ __forceinline__ void make_consts(Consts<LG>& K, const float2* __restr
     }
 }
 
-// phase 1 arithmetic on staged operand words of 8 tiles.  CPLX: w[j][tile] fp16 complex;
-// otherwise w[j][0..3] = row a sample pairs, w[j][4..7] = row b sample pairs (fp16).
-template <int LG, bool CPLX, int NB = NTB>
+// phase 1 arithmetic on the operand words of 8 tiles, w[j][tile] fp16 complex
+template <int LG, int NB = NTB>
 __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t* xb, const uint4* gtab,
                                             const uint4* t1f, const Mats& F1, const Mats& F2, int t0, int lane)
 {
@@ -161,11 +160,7 @@ __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t*
             const int tt = tb + k;
             H8U x;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (CPLX) x.w[j] = w[j][tt];
-                else x.w[j] = (tt & 1) ? __builtin_amdgcn_perm(w[j][4 + (tt >> 1)], w[j][tt >> 1], 0x07060302u)
-                                       : __builtin_amdgcn_perm(w[j][4 + (tt >> 1)], w[j][tt >> 1], 0x05040100u);
-            }
+            for (int j = 0; j < 4; ++j) x.w[j] = w[j][tt];
             yr[k] = MFMA(x.v, F1.re, zero);
             yi[k] = MFMA(x.v, F1.im, zero);
         }
@@ -190,13 +185,6 @@ __device__ __forceinline__ void phase1_core(const uint32_t (&w)[4][8], uint32_t*
     }
 }
 
-template <int LG>
-__device__ __forceinline__ void phase1_regs(const uint32_t (&w)[4][8], uint32_t* xb, const uint4* gtab,
-                                            const uint4* t1f, const Consts<LG>& K, int t0, int lane)
-{
-    phase1_core<LG, false>(w, xb, gtab, t1f, K.F16, K.F16, t0, lane);
-}
-
 // ---- phase 1 for the 8 tiles t0..t0+7 of one wave, operands from a chunk of L fp16 complex values
 // (pass-A output of the multi-pass split) ------------------------------------------------------
 template <int LG, int NB = NTB>
@@ -212,7 +200,7 @@ __device__ __forceinline__ void phase1(const __half2* chunk, uint32_t* xb, const
         load_words<4>(chunk + n0, &w[j][0]);
         load_words<4>(chunk + n0 + 4, &w[j][4]);
     }
-    phase1_core<LG, true, NB>(w, xb, gtab, t1f, K.F16, K.F16, t0, lane);
+    phase1_core<LG, NB>(w, xb, gtab, t1f, K.F16, K.F16, t0, lane);
 }
 
 // word address of (tile t2, reg 0) for this lane in phase 2; reg j adds j*TE*4 words
@@ -1515,123 +1503,179 @@ coop_dk_kernel(const __half2* __restrict__ ws_u, const __half2* __restrict__ ws_
 }
 
 // -------------------------------------------------------------------------------------
-// Kernel spectrum on the matrix cores for the chained kernels' lane order.  grid = (H, R).
-//   single pass: the head's kernel k[h,:] * rs[h] (power-of-two pre-scale) as the real row of a
-//                pair whose other row is zero;
-//   multi pass : chunk k1 of the pass-A output of the pre-scaled kernel.
-// Phase 1 and the forward half of phase 2 as in the convolution; value stored =
-// kscale * (FFT([k,0]) + D[h]) as fp16 complex (one 32-bit word per bin).
+// Kernel spectrum of a multi-pass split from a pass-A workspace, for the chained kernels' lane order.
+// grid = (H, R): chunk k1 of the pass-A output of the kernel pre-scaled by a power of two from rs[h] (the
+// head's maximum; pass A used the same scale).  Phase 1 and the forward half of phase 2 as in the
+// convolution; value stored = kscale * (FFT([k,0]) + D[h]) as fp16 complex (one 32-bit word per bin).
+// (coop_kspec_rows_kernel below reads k itself: single pass, and pass A inside where the plan allows.)
 // -------------------------------------------------------------------------------------
-template <int LG, int MODE>
+template <int LG>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
-coop_kspec_kernel(const float* __restrict__ k, const __half2* __restrict__ ws, const float* __restrict__ D,
-                  const float* __restrict__ rs, float2* __restrict__ kspec, int64_t N, int log2R,
-                  float kscale_over_c, float kscale, const float2* __restrict__ tw,
-                  const unsigned char* __restrict__ ctab)
+coop_kspec_kernel(const __half2* __restrict__ ws, const float* __restrict__ D, const float* __restrict__ rs,
+                  float2* __restrict__ kspec, int log2R, float kscale_over_c, float kscale,
+                  const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
-    constexpr bool CPLX = MODE == 1, FUSE = MODE >= 2;
-    constexpr int LR = FUSE ? MODE : 1, RH = (1 << LR) / 2;      // FUSE: outer radix 2^LR, R/2 non-zero terms
     extern __shared__ uint4 lds4[];
     uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
     uint4* t1f = lds4 + C::XWORDS / 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = lane & 15, g = lane >> 4;
-    int h = blockIdx.x, k1 = blockIdx.y;
-    if (FUSE) {       // 1-D grid, chunk index fastest, renumbered per XCD: the chunks of a head share its row in L2
-        const unsigned G = gridDim.x;
-        const unsigned vid = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (G >> 3) + (blockIdx.x >> 3);
-        h = (int)(vid >> LR);
-        k1 = (int)(vid & ((1u << LR) - 1u));
-    }
+    const int h = blockIdx.x, k1 = blockIdx.y;
     const int64_t Ltot = (int64_t)C::L << log2R;
     const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
-    for (int i = tid; i < C::TC * 8; i += C::NW * 64) {
-        H8U e;
-        e.u = gtab[C::T1F + i];
-        if (FUSE && i < C::TC * 4) {         // forward table times the tile part of pass A's twist
-            const float2 w = tw_full(tw, (uint32_t)(k1 * (i >> 2)) << (TW_LOG2 - LG - LR));
-            const h2 tau = {(_Float16)w.x, (_Float16)w.y};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) e.w[j] = cmul_h2(e.w[j], tau);
-        }
-        t1f[i] = e.u;
-    }
+    for (int i = tid; i < C::TC * 8; i += C::NW * 64) t1f[i] = gtab[C::T1F + i];
     Consts<LG> K;
     make_consts<LG>(K, tw, lane);
-    const float* kr = k + (size_t)h * N;
-    // per-head power-of-two pre-scale: from the caller's per-head maxima (multi-pass: pass A used the same
-    // scale), else from a scan of the head's kernel row here
-    float m = 0.f;
-    __shared__ float mred[C::NW];
-    if (!CPLX) {      // (FUSE: every chunk's workgroup scans the whole row)
-        const float4* k4 = reinterpret_cast<const float4*>(kr);
-        for (int i = tid; i < (int)(N / 4); i += C::NW * 64) {
-            const float4 v = k4[i];
-            m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-        }
-        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-        if (lane == 0) mred[wave] = m;
-    }
-    __syncthreads();
-    if (!CPLX) {
-        m = mred[0];
-        for (int w = 1; w < C::NW; ++w) m = fmaxf(m, mred[w]);
-    } else {
-        m = rs[h];
-    }
-    const float r = head_scale_of(m);
+    const float r = head_scale_of(rs[h]);
     const __half2* chunk = ws + (size_t)h * Ltot + (size_t)k1 * C::L;
+    __syncthreads();
 #pragma unroll
     for (int gi = 0; gi < C::NG; ++gi) {
-        const int t0 = (gi * C::NW + wave) * 8;
-        if (CPLX) {
-            phase1<LG>(chunk, xb, gtab, t1f, K, t0, lane);
-        } else if (FUSE) {
-            // pass A on the fly: s[n2] = sum_{n1 < R/2} w_R^(n1 k1) k[n1 L + n2], its twist folded into the
-            // phase-1 matrices (d_a, d_b parts) and the table above (tile part), as in the convolution
-            const Mats F1 = phase_mats(k1, C::cb + 4, LG + LR, tw, lane), F2 = phase_mats(k1, C::cb, LG + LR, tw, lane);
-            float2 cr[RH];
-#pragma unroll
-            for (int n1 = 0; n1 < RH; ++n1)
-                cr[n1] = tw_full(tw, (uint32_t)((n1 * k1) & ((1 << LR) - 1)) << (TW_LOG2 - LR));
-            uint32_t w[4][8];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    float sr = 0.f, si = 0.f;
-#pragma unroll
-                    for (int n1 = 0; n1 < RH; ++n1) {
-                        const float v = kr[(size_t)n1 * C::L + n0 + i] * r;
-                        sr = __builtin_fmaf(cr[n1].x, v, sr);
-                        si = __builtin_fmaf(cr[n1].y, v, si);
-                    }
-                    w[j][i] = pack_h2(sr, si);
-                }
-            }
-            phase1_core<LG, true>(w, xb, gtab, t1f, F1, F2, t0, lane);
-        } else {
-            // stage the fp32 kernel row as fp16 in registers, then the common phase 1 on them
-            uint32_t w[4][8];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    w[j][i] = 0u; w[j][4 + i] = 0u;
-                    if (g < 2) w[j][i] = pack_h2(kr[n0 + 2 * i] * r, kr[n0 + 2 * i + 1] * r);
-                }
-            }
-            phase1_regs<LG>(w, xb, gtab, t1f, K, t0, lane);
-        }
+        phase1<LG>(chunk, xb, gtab, t1f, K, (gi * C::NW + wave) * 8, lane);
         __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
     const float alpha = kscale_over_c / r, beta = D[h] * kscale;
     uint4* out = reinterpret_cast<uint4*>(reinterpret_cast<uint32_t*>(kspec) + (size_t)h * Ltot + (size_t)k1 * C::L);
 #pragma unroll
+    for (int gi = 0; gi < C::NG; ++gi)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t2 = (gi * C::NW + wave) * 8 + i;
+            f4 zr, zi;
+            phase2_fwd<LG>(xb, phase2_base<LG>(t2, lane), K, zr, zi);
+            out[t2 * 64 + lane] = make_uint4(pack_h2(zr[0] * alpha + beta, zi[0] * alpha), pack_h2(zr[1] * alpha + beta, zi[1] * alpha),
+                                             pack_h2(zr[2] * alpha + beta, zi[2] * alpha), pack_h2(zr[3] * alpha + beta, zi[3] * alpha));
+        }
+}
+
+// Kernel spectrum, staged form.  LR = 0: single pass, the head's row k[h, :] zero-padded to 2^LG points.
+// LR > 0: chunk k1 of the multi-pass split with pass A inside (outer radix 2^LR around 2^LG points); grid =
+// H 2^LR, chunk index fastest and renumbered per XCD, so that the chunks of a head share its row in one L2.
+// Every chunk needs the whole row (pass A sums its R/2 pieces); the workgroup reads it in unit-stride 32-byte
+// runs.  R <= 4: the row stays in registers between the search of the head's maximum (power-of-two pre-scale)
+// and the conversion, one round trip to memory; R = 8: the row is read twice.
+// Then s[n2] = sum_{n1 < R/2} w_R^(n1 k1) k[n1 L + n2] goes to the exchange slots as fp16 complex, phase 1 runs
+// in place with the twist in its operands, the forward half of phase 2 writes kscale (FFT + D[h]).
+template <int LG, int LR>
+__global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D, float2* __restrict__ kspec,
+                       float kscale_over_c, float kscale, const float2* __restrict__ tw,
+                       const unsigned char* __restrict__ ctab)
+{
+    using C = CC<LG>;
+    constexpr int NT = C::NW * 64, RH = LR ? (1 << LR) / 2 : 1;
+    constexpr int NROW = LR ? RH * C::L : C::L / 2;      // samples of a row
+    constexpr int RPA = (C::L / 8) / NT;                 // runs of eight samples per lane
+    extern __shared__ uint4 lds4[];
+    __shared__ float mred[C::NW];
+    uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
+    uint4* t1f = lds4 + C::XWORDS / 4;
+    uint4* t1i = t1f + C::TC * 4;
+    uint32_t* vt = reinterpret_cast<uint32_t*>(t1i + C::TC * 4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const unsigned G = gridDim.x;
+    const unsigned vid = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (G >> 3) + (blockIdx.x >> 3);
+    const int h = (int)(vid >> LR), k1 = (int)(vid & ((1u << LR) - 1u));
+    const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
+    const float* kr = k + (size_t)h * NROW;
+    staged_tables<LG, NT>(lds4, gtab, tw, tid, 0);
+
+    float2 cr[RH];
+#pragma unroll
+    for (int n1 = 0; n1 < RH; ++n1)
+        cr[n1] = LR ? tw_full(tw, (uint32_t)((n1 * k1) & ((1 << LR) - 1)) << (TW_LOG2 - LR)) : make_float2(1.f, 0.f);
+    auto load_run = [&](float4 (&v)[RH][2], int i) __attribute__((always_inline)) {
+        const int n = staged_run_n<LG>(i * NT + tid);
+#pragma unroll
+        for (int n1 = 0; n1 < RH; ++n1) {
+            const float4* src = reinterpret_cast<const float4*>(kr + (size_t)n1 * C::L + n);
+            const bool pad = LR == 0 && n >= NROW;       // the zero half of a single-pass transform
+            v[n1][0] = pad ? make_float4(0.f, 0.f, 0.f, 0.f) : src[0];
+            v[n1][1] = pad ? make_float4(0.f, 0.f, 0.f, 0.f) : src[1];
+        }
+    };
+    auto max_run = [&](const float4 (&v)[RH][2], float m) __attribute__((always_inline)) {
+#pragma unroll
+        for (int n1 = 0; n1 < RH; ++n1)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                m = fmaxf(m, fmaxf(fmaxf(fabsf(v[n1][q].x), fabsf(v[n1][q].y)), fmaxf(fabsf(v[n1][q].z), fabsf(v[n1][q].w))));
+        return m;
+    };
+    auto head_max = [&](float m) __attribute__((always_inline)) {     // over the workgroup; ends behind a barrier
+        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+        if (lane == 0) mred[wave] = m;
+        __syncthreads();
+        m = mred[0];
+        for (int w = 1; w < C::NW; ++w) m = fmaxf(m, mred[w]);
+        return m;
+    };
+    auto put_run = [&](const float4 (&v)[RH][2], int i, float r) __attribute__((always_inline)) {
+        const int a0 = staged_slot<LG>(staged_run_n<LG>(i * NT + tid));
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float sr = 0.f, si = 0.f;
+#pragma unroll
+            for (int n1 = 0; n1 < RH; ++n1) {
+                const float4 q = v[n1][e >> 2];
+                const float x = ((e & 3) == 0 ? q.x : (e & 3) == 1 ? q.y : (e & 3) == 2 ? q.z : q.w) * r;
+                sr = __builtin_fmaf(cr[n1].x, x, sr);
+                si = __builtin_fmaf(cr[n1].y, x, si);
+            }
+            xb[a0 + 4 * e] = pack_h2(sr, si);
+        }
+    };
+
+    float r;
+    if constexpr (RH <= 2) {
+        float4 v[RPA][RH][2];
+#pragma unroll
+        for (int i = 0; i < RPA; ++i) load_run(v[i], i);
+        float m = 0.f;
+#pragma unroll
+        for (int i = 0; i < RPA; ++i) m = max_run(v[i], m);
+        r = head_scale_of(head_max(m));                  // (the barrier also covers the tables)
+        if (LR) twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);
+#pragma unroll
+        for (int i = 0; i < RPA; ++i) put_run(v[i], i, r);
+    } else {
+        float m = 0.f;
+        const float4* k4 = reinterpret_cast<const float4*>(kr);
+        for (int i = tid; i < RH * (C::L / 4); i += NT) {
+            const float4 q = k4[i];
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(q.x), fabsf(q.y)), fmaxf(fabsf(q.z), fabsf(q.w))));
+        }
+        r = head_scale_of(head_max(m));
+        twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);
+#pragma unroll
+        for (int i0 = 0; i0 < RPA; i0 += 2) {
+            float4 v[2][RH][2];
+            load_run(v[0], i0);
+            load_run(v[1], i0 + 1);
+            put_run(v[0], i0, r);
+            put_run(v[1], i0 + 1, r);
+        }
+    }
+
+    Consts<LG> K;
+    make_consts<LG>(K, tw, lane);
+    h2 cF[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 w = tw_full(tw, (uint32_t)((c * (4 * g + j)) & 255) << (TW_LOG2 - 8));
+        cF[j] = h2{(_Float16)w.x, (_Float16)w.y};
+    }
+    const Mats F1 = LR ? phase_mats(k1, C::cb + 4, LG + LR, tw, lane) : K.F16;
+    const Mats F2 = LR ? phase_mats(k1, C::cb, LG + LR, tw, lane) : K.F16;
+    __syncthreads();
+#pragma unroll 1
+    for (int gi = 0; gi < C::NG; ++gi) phase1_inplace<LG, 2>(xb, t1f, vt, F1, F2, cF, (gi * C::NW + wave) * 8, lane);
+    __syncthreads();
+    const float alpha = kscale_over_c / r, beta = D[h] * kscale;
+    uint4* out = reinterpret_cast<uint4*>(reinterpret_cast<uint32_t*>(kspec) + (((size_t)h << LR) + k1) * C::L);
+#pragma unroll 1
     for (int gi = 0; gi < C::NG; ++gi)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -1798,21 +1842,26 @@ hipError_t coop_kspec_go(const float* k, const __half2* ws, const float* D, cons
     dim3 grid((unsigned)H, 1u << pl.log2R);
     const int shift = 6 + (C::te >= 2 ? 1 : 0);
     const float koc = pl.kscale * (float)(1 << shift);
-    auto launch = [&](auto kern) {
+    auto launch_rows = [&](auto kern) {      // staged form (ws and rs unused)
+        const size_t lds_rows = coop_real_lds_bytes<LG>();
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_rows);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, grid, dim3(C::NW * 64), lds, st, k, ws, D, rs, kspec, N, pl.log2R, koc, pl.kscale,
-                           tb.tw, (const unsigned char*)tb.ctab);
+        hipLaunchKernelGGL(kern, dim3((unsigned)(H << pl.log2R)), dim3(C::NW * 64), lds_rows, st, k, D, kspec, koc,
+                           pl.kscale, tb.tw, (const unsigned char*)tb.ctab);
         return hipGetLastError();
     };
-    if (pl.log2R == 0) return launch(coop_kspec_kernel<LG, 0>);
-    if constexpr (LG == COOP_MAX_LOG2) {      // pass A inside (ws and rs unused)
-        if (pl.fuse_a) grid = dim3((unsigned)(H << pl.log2R));
-        if (pl.fuse_a && pl.log2R == 2) return launch(coop_kspec_kernel<LG, 2>);
-        if (pl.fuse_a && pl.log2R == 3) return launch(coop_kspec_kernel<LG, 3>);
+    if (pl.log2R == 0) return launch_rows(coop_kspec_rows_kernel<LG, 0>);
+    if constexpr (LG == COOP_MAX_LOG2) {      // pass A inside
+        if (pl.fuse_a && pl.log2R == 2) return launch_rows(coop_kspec_rows_kernel<LG, 2>);
+        if (pl.fuse_a && pl.log2R == 3) return launch_rows(coop_kspec_rows_kernel<LG, 3>);
     }
-    return launch(coop_kspec_kernel<LG, 1>);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_kspec_kernel<LG>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(coop_kspec_kernel<LG>, grid, dim3(C::NW * 64), lds, st, ws, D, rs, kspec, pl.log2R, koc,
+                       pl.kscale, tb.tw, (const unsigned char*)tb.ctab);
+    return hipGetLastError();
 }
 
 }  // namespace

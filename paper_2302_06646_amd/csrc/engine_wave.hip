@@ -617,7 +617,6 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
            const unsigned char* __restrict__ wtab)
 {
     using C = WC<LG>;
-    using T = typename IO::T;
     constexpr int NWP = C::TC / TPW, NGRP = NWV / NWP;
     static_assert(NWP >= 1 && NWP <= NWV, "tiles per wave");
     extern __shared__ uint4 lds4[];
