@@ -443,7 +443,7 @@ __device__ __forceinline__ int staged_slot(int n)
 }
 
 template <int LG>
-size_t coop_real_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16 + (size_t)CC<LG>::TC * 16 * 4; }
+__host__ __device__ constexpr size_t coop_real_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16 + (size_t)CC<LG>::TC * 16 * 4; }
 
 template <int LG, class IO, int NWV, int NB, bool CONJ>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
@@ -1231,6 +1231,7 @@ coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
     uint4* t1f = lds4 + C::XWORDS / 4;
     uint4* t1i = t1f + C::TC * 4;
     uint32_t* vt = reinterpret_cast<uint32_t*>(t1i + C::TC * 4);
+    uint4* zl = lds4 + coop_real_lds_bytes<LG>() / 16;   // Z of the pair in flight: eight 16-byte words per lane
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
     // the 2^LR workgroups of a head read the same rows: consecutive ids, renumbered so that they share an XCD
@@ -1264,7 +1265,6 @@ coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
     for (int p = 0; p < npairs; ++p) {
         const bool has_b = (2 * p + 1) < B;
         const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
-        uint32_t z[8][4];
 #pragma unroll
         for (int pass = 0; pass < 2; ++pass) {
             int zoff = 0;
@@ -1282,13 +1282,15 @@ coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                 f4 zr, zi;
                 phase2_fwd<LG>(xb, phase2_base<LG>(t0 + i, lane), K, zr, zi);
                 if (pass == 0) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) z[i][j] = pack_h2(zr[j], zi[j]);
+                    zl[i * NT + tid] = make_uint4(pack_h2(zr[0], zi[0]), pack_h2(zr[1], zi[1]), pack_h2(zr[2], zi[2]),
+                                                  pack_h2(zr[3], zi[3]));
                 } else {
+                    const uint4 zq = zl[i * NT + tid];   // (written by this lane: no barrier)
+                    const uint32_t z[4] = {zq.x, zq.y, zq.z, zq.w};
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         union { uint32_t u; h2 hh; } cv;
-                        cv.u = z[i][j];
+                        cv.u = z[j];
                         const float a = (float)cv.hh[0], b = (float)cv.hh[1];
                         // conj(Z) * W, one fused multiply-add per term
                         acc[i][j].x = __builtin_fmaf(b, zi[j], __builtin_fmaf(a, zr[j], acc[i][j].x));
@@ -1820,7 +1822,7 @@ hipError_t coop_dk_rows_go(const void* dy, const void* u, __half2* ws_A, float* 
     constexpr int LG = COOP_MAX_LOG2 - 1;
     using T = typename IO::T;
     using C = CC<LG>;
-    const size_t lds = coop_real_lds_bytes<LG>();
+    const size_t lds = coop_real_lds_bytes<LG>() + (size_t)C::NW * 64 * 8 * 16;      // slots, tables, Z
     const int shift = 6 + (C::te >= 2 ? 1 : 0);
     const float dkscale = (float)(int64_t(1) << (3 * shift)) / (float)(2 * pr.N);
     *scale_c = dkscale;
