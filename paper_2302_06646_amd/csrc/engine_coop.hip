@@ -976,6 +976,10 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
     const int nsrc = NPAR * npairs * 2;                  // sources in order: parity, pair, (u, dy)
     // copy source sidx into the raw area: wave w takes every NW-th KiB (row b after row a; a missing
     // row b copies row a again and is read as zero)
+    // (everything about a copy is wave-uniform and kept in scalar registers: the wave's index, the row pointers,
+    // the LDS byte address; a lane only adds its 16 bytes)
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t raw_lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)raw);
     auto copy_in = [&](int sidx) {
         const int p = (sidx >> 1) % npairs;
         const char* src = reinterpret_cast<const char*>((sidx & 1) ? dy : u);
@@ -984,14 +988,18 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
         const char* pb = src + row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N) * sizeof(T);
 #pragma unroll
         for (int q = 0; q < NCP; ++q) {
-            const int kib = q * C::NW + wave;                              // wave-uniform
+            const int kib = q * C::NW + wave_s;
             const int row = kib / (ROWN * 2 / 1024), part = kib - row * (ROWN * 2 / 1024);
-            const char* s = (row ? pb : pa) + part * 1024 + lane * 16;
-            uint4* dst = raw + kib * 64 + (kib * 64 / (2 * C::TC)) * 4;
+            const uint64_t sa = reinterpret_cast<uint64_t>((row ? pb : pa) + part * 1024);
+            // (readfirstlane returns a signed int: both halves go through uint32_t, or bit 31 of the low word
+            // would smear over the high word)
+            const uint32_t sa_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)sa);
+            const uint32_t sa_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(sa >> 32));
+            const uint64_t sbase = ((uint64_t)sa_hi << 32) | (uint64_t)sa_lo;
             const uint32_t lds_off =
-                __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)dst);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :: "s"(lds_off), "v"(s) : "memory", "m0");
+                __builtin_amdgcn_readfirstlane(raw_lds + (uint32_t)(kib * 64 + (kib * 64 / (2 * C::TC)) * 4) * 16u);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(lds_off), "v"(lane * 16), "s"(sbase) : "memory", "m0");
         }
     };
     // raw area -> exchange slots (pair packing, bf16 -> fp16, twist)
