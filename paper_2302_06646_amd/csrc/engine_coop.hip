@@ -892,7 +892,10 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
         }
         __syncthreads();
         drain(it);
-        if (it + 1 < it1) stage_item(it + 1);
+        if (it + 1 < it1) {
+            if (FUSEA) __syncthreads();      // rows are staged by other lanes than those that drained the slots
+            stage_item(it + 1);
+        }
     }
 }
 
