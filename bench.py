@@ -37,14 +37,15 @@ CACHE_BYTES = 256 << 20        # last-level (Infinity) cache
 # profiles/.
 KIB = 1024
 MEASURED_TRAFFIC = {
-    "cfg2_B16_H768_N1024_bf16": {"fwd": (15898.8 * 2 + 24576.0) * KIB, "bwd_du": (15886.6 * 2 + 24576.0) * KIB,
-                                 "bwd_dk_dD": (24847.4 * 2 + 3096.0) * KIB},
+    "cfg2_B16_H768_N1024_bf16": {"fwd": (15891.0 * 2 + 24576.0) * KIB, "bwd_du": (15875.8 * 2 + 24576.0) * KIB,
+                                 "bwd_dk_dD": (24842.0 * 2 + 3096.0) * KIB},
     # (the forward kernel reads rows in 64-byte requests, which FETCH_SIZE x 2 over-counts: upper bound)
-    "cfg3_B8_H256_N16384_fp16": {"fwd": (98868.7 * 2 + 65536.0) * KIB, "bwd_du": (98870.0 * 2 + 65536.0) * KIB,
-                                 "bwd_dk_dD": (160923.0 * 2 + 54800.1) * KIB},
-    "cfg4_B1_H128_N65536_fp16": {"fwd": ((49952.0 + 34152.0) * 2 + 65644.6 + 16384.0) * KIB,
-                                 "bwd_du": ((49955.5 + 34152.0) * 2 + 65621.0 + 16384.0) * KIB,
-                                 "bwd_dk_dD": ((17770.6 + 165351.6 + 34218.3) * 2 + 131072.0 + 132915.0 + 32768.0) * KIB},
+    "cfg3_B8_H256_N16384_fp16": {"fwd": (98875.7 * 2 + 65536.0) * KIB, "bwd_du": (98870.0 * 2 + 65536.0) * KIB,
+                                 "bwd_dk_dD": (141672.5 * 2 + 35911.8) * KIB},
+    # (inner convolution with pass A inside + pass C; dk: rows kernel + pass C + dD reduction)
+    "cfg4_B1_H128_N65536_fp16": {"fwd": ((49954.9 + 33050.9) * 2 + 65577.8 + 16384.0) * KIB,
+                                 "bwd_du": ((49963.5 + 33050.9) * 2 + 65563.6 + 16384.0) * KIB,
+                                 "bwd_dk_dD": ((18854.9 + 32938.6 + 3.2) * 2 + 77826.8 + 32768.0 + 0.5) * KIB},
 }
 
 def log(*a):
