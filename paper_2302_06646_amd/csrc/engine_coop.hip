@@ -1703,21 +1703,6 @@ coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D,
 template <int LG>
 size_t coop_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16; }
 
-// compute units of the current device (asked once)
-int compute_units()
-{
-    static int n = 0;
-    if (n == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            n = v;
-        else
-            n = 256;
-    }
-    return n;
-}
-
 // work split of the staged convolution kernel: as many workgroups as the device holds at once
 template <int LG, class IO, int NWV, int NB, bool CONJ>
 hipError_t coop_conv_real_go(const void* in, const float2* kspec, void* out, const Problem& pr,

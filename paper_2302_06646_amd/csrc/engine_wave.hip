@@ -873,10 +873,16 @@ hipError_t wconv_run(const void* in, const float2* kspec, void* out, const Probl
     if (e != hipSuccess) return e;
     const int gph = (pr.npairs + PB - 1) / PB;
     const long total = (long)gph * pr.H;
-    // persistent workgroups: as many as fit on the 256 compute units at once, equal shares
-    long fit = (long)(160 * 1024) / (long)lds;
-    fit = fit < 1 ? 1 : (fit > 4 ? 4 : fit);
-    long gpw = (total + 256 * fit * NWV - 1) / (256 * fit * NWV);
+    // persistent workgroups: as many as the device holds at once (at most four per compute unit), equal shares
+    static int fit_cached = 0;
+    if (fit_cached == 0) {
+        int nb = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, wconv_kernel<LG, IO, PB, NWV, CONJ>, NWV * 64, lds);
+        if (e != hipSuccess) return e;
+        fit_cached = nb < 1 ? 1 : (nb > 4 ? 4 : nb);
+    }
+    const long fit = fit_cached, cus = compute_units();
+    long gpw = (total + cus * fit * NWV - 1) / (cus * fit * NWV);
     if (gpw < 1) gpw = 1;
     const long nblk = (total + gpw * NWV - 1) / (gpw * NWV);
     hipLaunchKernelGGL((wconv_kernel<LG, IO, PB, NWV, CONJ>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st,

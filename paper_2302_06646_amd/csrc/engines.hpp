@@ -4,6 +4,22 @@
 
 namespace lc {
 
+// compute units of the current device (asked once per translation unit; 256 if the query fails)
+inline int compute_units()
+{
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
+}
+
+
 struct Problem {
     int64_t B, H, N;
     int io;          // longconv_dtype_t of u, y, dy, du

@@ -158,17 +158,22 @@ def test_persistent_workgroups_ragged_item_count(monkeypatch, N, B, H, io):
 @pytest.mark.parametrize("io", [wl.F16, wl.BF16])
 @pytest.mark.parametrize("N", [65536, 131072])
 def test_pass_a_inside_the_inner_kernel(monkeypatch, N, io):
-    """N = 65536, 131072 (outer radix 4, 8): the convolutions take pass A while staging their rows.  Odd batch
-    (the last pair has one row), both half dtypes, against the oracle and against the separate pass A."""
+    """N = 65536, 131072 (outer radix 4, 8): the convolutions, the spectrum and (N = 65536) dk take pass A while
+    staging their rows.  Odd batch (the last pair has one row), both half dtypes, against the oracle and against
+    the separate pass A."""
     from gpu_harness import GpuRun, TOL, check_full
     inp = wl.generate(_w("4a", N=N, dtype=io), B=3, H=1 if N > 65536 else 2)
     check_full(inp, label=f"pass A fused, io={wl.DTYPE_NAMES[io]}")
     g = GpuRun(inp)
     y = g.fwd().copy()
-    du = g.bwd(dk=False, dD=False)[0].copy()
+    du, dk, dD = (a.copy() for a in g.bwd())
     monkeypatch.setenv("LONGCONV_FUSE_PASS_A", "0")
     g2 = GpuRun(inp)
     y2 = g2.fwd()
-    du2 = g2.bwd(dk=False, dD=False)[0]
-    assert wl.rel_l2(y, y2) <= 2 * TOL[io] and wl.rel_l2(du, du2) <= 2 * TOL[io]
+    du2, dk2, dD2 = g2.bwd()
+    tol = 2 * TOL[io]
+    assert wl.rel_l2(y, y2) <= tol and wl.rel_l2(du, du2) <= tol
+    assert wl.rel_l2(dk, dk2) <= tol and wl.rel_l2(dD, dD2) <= tol
     assert not np.array_equal(y, y2)          # the two paths round differently: the switch did take effect
+    if N == 65536:
+        assert not np.array_equal(dk, dk2)    # dk: outer radix 8 from the rows against radix 4 from a workspace
