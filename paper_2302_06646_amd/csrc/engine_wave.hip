@@ -630,19 +630,23 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
     float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWP]
     const int h = blockIdx.x;
 
-    auto load_pair = [&](int p, In<TPW>& iu, In<TPW>& id) {
+    // rows of pair p of one source; each source's registers are refilled right after its phase 1 has read them,
+    // so the next pair's rows travel during two thirds of an iteration
+    auto load_src = [&](int p, const typename IO::T* src, In<TPW>& in) {
         const int64_t b0 = 2 * (int64_t)p;
         const bool has_b = b0 + 1 < B;
         const size_t oa = row_off(b0, h, H, N), ob = row_off(has_b ? b0 + 1 : b0, h, H, N);
-        load_rows<LG, IO, TPW>(iu, u + oa, u + ob, has_b, t0, lane);
-        load_rows<LG, IO, TPW>(id, dy + oa, dy + ob, has_b, t0, lane);
+        load_rows<LG, IO, TPW>(in, src + oa, src + ob, has_b, t0, lane);
     };
     In<TPW> inu, ind;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int i = 0; i < TPW / 2; ++i) inu.wa[j][i] = inu.wb[j][i] = ind.wa[j][i] = ind.wb[j][i] = 0u;
-    if (grp < npairs) load_pair(grp, inu, ind);
+    if (grp < npairs) {
+        load_src(grp, u, inu);
+        load_src(grp, dy, ind);
+    }
     WK<LG, TPW> K;
     load_consts<LG, TPW>(K, wtab, t0, lane);
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -660,7 +664,9 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
     const int niter = (npairs + NGRP - 1) / NGRP;      // same for every group: barriers stay uniform
     for (int it = 0; it < niter; ++it) {
         const bool act = it * NGRP + grp < npairs;
+        const int pnext = (it + 1) * NGRP + grp;
         if (act) w_phase1<LG, IO, TPW>(inu, xa, K, t0, lane);
+        if (pnext < npairs) load_src(pnext, u, inu);
         pair_sync<NWP>();
         uint32_t z[TPW][4];
         if (act) {
@@ -672,7 +678,7 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
                 for (int j = 0; j < 4; ++j) z[k][j] = pack_h2(yr[k][j], yi[k][j]);
             w_phase1<LG, IO, TPW>(ind, xd, K, t0, lane);
         }
-        if ((it + 1) * NGRP + grp < npairs) load_pair((it + 1) * NGRP + grp, inu, ind);
+        if (pnext < npairs) load_src(pnext, dy, ind);
         pair_sync<NWP>();
         if (act) {
             f4 yr[TPW], yi[TPW];
