@@ -4,13 +4,13 @@
 One "step" = one pass of the whole path over one batch of synthetic input, as a training
 step would run it (the kernel changes every step, so its spectrum is recomputed):
 
-    kernel-spectrum precompute  ->  forward  ->  backward (dk, dD)  ->  backward (du)
+    kernel-spectrum precompute  ->  forward  ->  backward (du, dk, dD in one call)
 
 Inputs are resident in HBM before the timed region.  Each step uses the next of several
 distinct buffer sets (more than the 256 MB last-level cache in total) so that reads come from
 HBM rather than from cache.  The timed region is exactly K steps between two events on the launch
 stream; the per-call durations (`segments_ms`, `roofline`) come from a second run of the same K
-steps with an event between the four calls (each event costs a few microseconds of GPU time, so
+steps with an event between the three calls (each event costs a few microseconds of GPU time, so
 it stays out of the timed region).  Prints ONE JSON line (see README for the fields).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4a|...] [--no-cpu]
@@ -37,15 +37,17 @@ CACHE_BYTES = 256 << 20        # last-level (Infinity) cache
 # profiles/.
 KIB = 1024
 MEASURED_TRAFFIC = {
-    "cfg2_B16_H768_N1024_bf16": {"fwd": (15891.0 * 2 + 24576.0) * KIB, "bwd_du": (15875.8 * 2 + 24576.0) * KIB,
-                                 "bwd_dk_dD": (24842.0 * 2 + 3096.0) * KIB},
-    # (the forward kernel reads rows in 64-byte requests, which FETCH_SIZE x 2 over-counts: upper bound)
-    "cfg3_B8_H256_N16384_fp16": {"fwd": (98875.7 * 2 + 65536.0) * KIB, "bwd_du": (98870.0 * 2 + 65536.0) * KIB,
-                                 "bwd_dk_dD": (141672.5 * 2 + 35911.8) * KIB},
-    # (inner convolution with pass A inside + pass C; dk: rows kernel + pass C + dD reduction)
+    # (backward: one kernel for du, dk and dD)
+    "cfg2_B16_H768_N1024_bf16": {"fwd": (15891.0 * 2 + 24576.0) * KIB, "bwd": None},
+    # (the convolution kernels read rows in 64-byte requests, which FETCH_SIZE x 2 over-counts: upper bound;
+    # backward: the dk kernel, then the convolution kernel with the conjugate spectrum)
+    "cfg3_B8_H256_N16384_fp16": {"fwd": (98875.7 * 2 + 65536.0) * KIB,
+                                 "bwd": ((141672.5 + 98870.0) * 2 + 35911.8 + 65536.0) * KIB},
+    # (inner convolution with pass A inside + pass C; backward: dk rows kernel + pass C + dD reduction, then
+    # the convolution with the conjugate spectrum + pass C)
     "cfg4_B1_H128_N65536_fp16": {"fwd": ((49954.9 + 33050.9) * 2 + 65577.8 + 16384.0) * KIB,
-                                 "bwd_du": ((49963.5 + 33050.9) * 2 + 65563.6 + 16384.0) * KIB,
-                                 "bwd_dk_dD": ((18854.9 + 32938.6 + 3.2) * 2 + 77826.8 + 32768.0 + 0.5) * KIB},
+                                 "bwd": ((18854.9 + 32938.6 + 3.2 + 49963.5 + 33050.9) * 2 + 77826.8 + 32768.0 + 0.5 +
+                                         65563.6 + 16384.0) * KIB},
 }
 
 def log(*a):
@@ -80,7 +82,7 @@ def run_workload(key, steps, warmup, lc, torch):
     w = wl.WORKLOADS[key]
     S = Sets(w, lc, torch)
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    marks = [[ev() for _ in range(5)] for _ in range(steps)]
+    marks = [[ev() for _ in range(4)] for _ in range(steps)]
 
     def step(i, m=None):
         j = i % S.nsets
@@ -89,10 +91,8 @@ def run_workload(key, steps, warmup, lc, torch):
         if m: m[1].record()
         lc.longconv_fwd(S.u[j], S.k, S.D, S.y[j], S.ws, kspec=S.kspec)
         if m: m[2].record()
-        lc.longconv_bwd(S.dy[j], S.u[j], S.k, S.D, None, S.dk, S.dD, S.ws, kspec=S.kspec)
+        lc.longconv_bwd(S.dy[j], S.u[j], S.k, S.D, S.du[j], S.dk, S.dD, S.ws, kspec=S.kspec)
         if m: m[3].record()
-        lc.longconv_bwd(S.dy[j], S.u[j], S.k, S.D, S.du[j], None, None, S.ws, kspec=S.kspec)
-        if m: m[4].record()
 
     for i in range(warmup):
         step(i)
@@ -107,19 +107,16 @@ def run_workload(key, steps, warmup, lc, torch):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     step_ms = e0.elapsed_time(e1) / steps
-    # instrumented region: the same steps again with an event between the four calls (each event costs a few
+    # instrumented region: the same steps again with an event between the three calls (each event costs a few
     # microseconds of GPU time, which is why it is kept out of the timed region); gives the per-launch durations
     for i in range(steps):
         step(warmup + steps + i, marks[i])
     torch.cuda.synchronize()
-    seg = np.array([[m[a].elapsed_time(m[a + 1]) for a in range(4)] for m in marks])   # ms
+    seg = np.array([[m[a].elapsed_time(m[a + 1]) for a in range(3)] for m in marks])   # ms
     seg_avg = seg.mean(axis=0)
     fwd_b, bwd_b = wl.algorithmic_bytes(w.B, w.H, w.N, w.dtype)
-    s = wl.DTYPE_BYTES[w.dtype]
-    E = w.B * w.H * w.N
-    small = w.H * w.N * 4 + w.H * 4
-    # algorithmic bytes charged to each launch group; they sum to fwd_b + bwd_b
-    seg_bytes = {"kspec": 0, "fwd": fwd_b, "bwd_dk_dD": E * s + small, "bwd_du": 2 * E * s + small}
+    # algorithmic bytes of each call (the spectrum's read of k is already in fwd's figure)
+    seg_bytes = {"kspec": 0, "fwd": fwd_b, "bwd": bwd_b}
     names = list(seg_bytes)
     res = {
         "workload": w.name, "B": w.B, "H": w.H, "N": w.N, "io": wl.DTYPE_NAMES[w.dtype],
@@ -191,7 +188,7 @@ def main():
     res, seg_bytes = run_workload(a.workload, a.steps, a.warmup, lc, torch)
     log(json.dumps(res, indent=1))
     # dominant kernel = the launch group with the largest share of the step
-    dom = max(("fwd", "bwd_dk_dD", "bwd_du"), key=lambda n: res["segments"][n]["ms"])
+    dom = max(("fwd", "bwd"), key=lambda n: res["segments"][n]["ms"])
     dom_gbps = res["segments"][dom]["GBps"]
     out = {
         "metric": "long-conv fwd+bwd ms, effective GB/s and % HBM roofline at BxHxN",
@@ -199,7 +196,7 @@ def main():
         "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": res["workload"], "B": res["B"], "H": res["H"], "N": res["N"], "io": res["io"],
-                   "step": "kspec+fwd+bwd(dk,dD)+bwd(du)", "plan": res["plan"], "buffer_sets": res["buffer_sets"]},
+                   "step": "kspec+fwd+bwd(du,dk,dD)", "plan": res["plan"], "buffer_sets": res["buffer_sets"]},
         "pct_hbm_roofline": 100.0 * res["frac_hbm"],
         "TFLOPs_algorithmic": res["TFLOPs_algorithmic"],
         "segments_ms": {n: v["ms"] for n, v in res["segments"].items()},

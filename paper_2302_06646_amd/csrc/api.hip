@@ -313,6 +313,18 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
     const bool f16ws = pl.engine == ENGINE_MFMA;
     bool dy_ready = false;   // multi-pass: pass A of dy already in ws1
 
+    if (want_dkD && du && pl.engine == ENGINE_MFMA && wave_bwd_ok(pl)) {
+        // everything from one kernel: dy and u are read once, dy is transformed once
+        const float2* ks = (const float2*)kspec;
+        if (!ks) {
+            if (note(run_kspec(k, D, (float2*)(base + w.kspec), (float2*)(base + w.kscratch),
+                               (float*)(base + w.hscale), H, N, pl, tb, st), "kspec") != hipSuccess)
+                return LONGCONV_ERR_HIP;
+            ks = (const float2*)(base + w.kspec);
+        }
+        if (note(wave_bwd(dy, u, ks, du, dk, dD, pr, pl, tb, st), "bwd") != hipSuccess) return LONGCONV_ERR_HIP;
+        return LONGCONV_OK;
+    }
     if (want_dkD) {
         hipError_t e = hipSuccess;
         float* dpart = (float*)(base + w.dpart);

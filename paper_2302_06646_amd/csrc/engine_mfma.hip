@@ -544,6 +544,9 @@ void mfma_fill_plan(Plan& pl)
     // staging (LONGCONV_FUSE_PASS_A=0 keeps the separate pass, for comparison)
     const char* fa = getenv("LONGCONV_FUSE_PASS_A");
     pl.fuse_a = pl.order.coop_lg == COOP_MAX_LOG2 && (pl.log2R == 2 || pl.log2R == 3) && !(fa && !strcmp(fa, "0"));
+    // one backward kernel where a wave group holds a head's accumulators (LONGCONV_FUSE_BWD=0: separate kernels)
+    const char* fb = getenv("LONGCONV_FUSE_BWD");
+    pl.fuse_bwd = pl.order.wave_lg && pl.log2L2 <= 11 && pl.log2R == 0 && !(fb && !strcmp(fb, "0"));
 }
 
 hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,

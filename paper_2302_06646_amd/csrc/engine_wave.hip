@@ -786,6 +786,238 @@ hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, const Pro
 }
 
 // -------------------------------------------------------------------------------------
+// Whole backward pass of one head per workgroup: du, dk and dD from one read of dy and u.  Same split of
+// the work as wdk_kernel (groups of NWP waves, TPW phase-2 tiles per wave).  Per pair: W = transform of the
+// dy pair; du = inverse transform of W conj(K) (the spectrum of the wave's tiles stays in registers for the
+// whole head), stored from phase 3; Z = transform of the u pair; A += conj(Z) W.  Against the two separate
+// kernels this saves one read and one forward transform of dy per pair.  The dy exchange buffer alternates
+// between two copies: a wave that is ahead writes the next pair while the others still run phase 3 of this one.
+// (About 220 registers, two workgroups per SIMD set; capped at 168 for three it spills ~150 bytes per lane.)
+// -------------------------------------------------------------------------------------
+template <int LG, class IO, int TPW, int NWV>
+__global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
+wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
+            const float2* __restrict__ kspec, typename IO::T* __restrict__ du, float* __restrict__ dk,
+            float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs, float dkscale, float dDscale,
+            const unsigned char* __restrict__ wtab)
+{
+    using C = WC<LG>;
+    static_assert(TPW == 2, "du leaves as one word of two samples per lane and register");
+    constexpr int NWP = C::TC / TPW, NGRP = NWV / NWP;
+    static_assert(NWP >= 1 && NWP <= NWV, "tiles per wave");
+    extern __shared__ uint4 lds4[];
+    uint32_t* lds = reinterpret_cast<uint32_t*>(lds4);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int grp = wave / NWP, t0 = (wave % NWP) * TPW;
+    const int c = lane & 15, g = lane >> 4;
+    uint32_t* xa = lds + (size_t)(grp * 3 + 0) * C::PAIR_WORDS;      // u pair
+    uint32_t* xd0 = lds + (size_t)(grp * 3 + 1) * C::PAIR_WORDS;     // dy pair, even and odd iterations
+    uint32_t* xd1 = lds + (size_t)(grp * 3 + 2) * C::PAIR_WORDS;
+    // du of a pair on its way out: [2 rows][N] I/O elements, two copies (even and odd iterations)
+    constexpr int STW = C::L / 2;                                     // words of one copy
+    uint32_t* stg0 = lds + (size_t)NGRP * 3 * C::PAIR_WORDS + (size_t)(grp * 2 + 0) * STW;
+    uint32_t* stg1 = stg0 + STW;
+    float2* red = reinterpret_cast<float2*>(lds + (size_t)NGRP * (3 * C::PAIR_WORDS + 2 * STW));   // [wave][TPW*4][64]
+    float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWP]
+    const int h = blockIdx.x;
+
+    auto load_src = [&](int p, const typename IO::T* src, In<TPW>& in) {
+        const int64_t b0 = 2 * (int64_t)p;
+        const bool has_b = b0 + 1 < B;
+        const size_t oa = row_off(b0, h, H, N), ob = row_off(has_b ? b0 + 1 : b0, h, H, N);
+        load_rows<LG, IO, TPW>(in, src + oa, src + ob, has_b, t0, lane);
+    };
+    In<TPW> inu, ind;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < TPW / 2; ++i) inu.wa[j][i] = inu.wb[j][i] = ind.wa[j][i] = ind.wb[j][i] = 0u;
+    if (grp < npairs) {
+        load_src(grp, dy, ind);
+        load_src(grp, u, inu);
+    }
+    WK<LG, TPW> K;
+    load_consts<LG, TPW>(K, wtab, t0, lane);
+    // spectrum of this wave's phase-2 tiles: fp16 complex, four bins per lane and tile
+    H8U kk[TPW];
+    {
+        const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)h * C::L);
+#pragma unroll
+        for (int k = 0; k < TPW; ++k) kk[k].u = ks[(t0 + k) * 64 + lane];
+    }
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    int ad[TPW][4];
+#pragma unroll
+    for (int k = 0; k < TPW; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ad[k][j] = phase2_addr<LG>(t0 + k, j, lane);
+    float2 acc[TPW][4];
+#pragma unroll
+    for (int k = 0; k < TPW; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[k][j] = make_float2(0.f, 0.f);
+
+    // du of iteration itf leaves one barrier after phase 3 put it into the staging copy: every lane of the group
+    // stores 16 contiguous bytes (4-byte stores straight from phase 3, a quarter of every 16 bytes per wave, made
+    // the memory side write most lines twice and read them back in between)
+    auto flush_du = [&](int itf) {
+        const int p = itf * NGRP + grp;
+        if (p >= npairs) return;
+        const int gl = (wave % NWP) * 64 + lane;                       // lane of the group, 4 words each
+        const int row = (4 * gl) / (STW / 2), n = ((4 * gl) % (STW / 2)) * 2;
+        const int64_t b0 = 2 * (int64_t)p + row;
+        if (b0 >= B) return;
+        const uint4 v = *reinterpret_cast<const uint4*>(((itf & 1) ? stg1 : stg0) + 4 * gl);
+        *reinterpret_cast<uint4*>(du + row_off(b0, h, H, N) + n) = v;
+    };
+    const int niter = (npairs + NGRP - 1) / NGRP;      // same for every group: barriers stay uniform
+    for (int it = 0; it < niter; ++it) {
+        const int p = it * NGRP + grp, pnext = p + NGRP;
+        const bool act = p < npairs;
+        uint32_t* xd = (it & 1) ? xd1 : xd0;
+        if (act) w_phase1<LG, IO, TPW>(ind, xd, K, t0, lane);
+        if (pnext < npairs) load_src(pnext, dy, ind);
+        pair_sync<NWP>();
+        if (it > 0) flush_du(it - 1);
+        uint32_t w[TPW][4];
+        if (act) {
+            f4 yr[TPW], yi[TPW];
+            w_phase2_fwd<LG, TPW>(xd, K, ad, yr, yi);
+#pragma unroll
+            for (int k = 0; k < TPW; ++k) {
+                H8U m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    w[k][j] = pack_h2(yr[k][j], yi[k][j]);
+                    m.w[j] = cmul_pack_conj(yr[k][j], yi[k][j], kk[k].c[j]);     // correlation with the kernel
+                }
+                const f4 zr = MFMA(K.IL.re, m.v, zero), zi = MFMA(K.IL.im, m.v, zero);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xd[ad[k][j]] = pack_h2(zr[j], zi[j]);
+            }
+            w_phase1<LG, IO, TPW>(inu, xa, K, t0, lane);
+        }
+        if (pnext < npairs) load_src(pnext, u, inu);
+        pair_sync<NWP>();
+        if (act) {
+            // du of this pair: phase 3 of the wave's two tiles = two neighbouring samples per register
+            f4 r[TPW], s[TPW];
+#pragma unroll
+            for (int k = 0; k < TPW; ++k) w_phase3_tile<LG, TPW, true>(xd, K, t0, k, lane, r[k], s[k]);
+            if (g < 2) {     // n_a < 8: the first N samples
+                uint32_t* stg = (it & 1) ? stg1 : stg0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
+                    stg[n0 / 2] = IsBf<IO>::v ? pack_bf2(r[0][j], r[1][j]) : pack_h2(r[0][j], r[1][j]);
+                    stg[STW / 2 + n0 / 2] = IsBf<IO>::v ? pack_bf2(s[0][j], s[1][j]) : pack_h2(s[0][j], s[1][j]);
+                }
+            }
+            f4 yr[TPW], yi[TPW];
+            w_phase2_fwd<LG, TPW>(xa, K, ad, yr, yi);
+#pragma unroll
+            for (int k = 0; k < TPW; ++k)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    union { uint32_t u; h2 h; } cv;
+                    cv.u = w[k][j];
+                    const float wr = (float)cv.h[0], wi = (float)cv.h[1];
+                    // conj(Z) * W, one fused multiply-add per term
+                    acc[k][j].x = __builtin_fmaf(yi[k][j], wi, __builtin_fmaf(yr[k][j], wr, acc[k][j].x));
+                    acc[k][j].y = __builtin_fmaf(-yi[k][j], wr, __builtin_fmaf(yr[k][j], wi, acc[k][j].y));
+                }
+        }
+    }
+
+    // ---- every wave publishes its partial A; group 0 adds them in group order (as in wdk_kernel)
+#pragma unroll
+    for (int k = 0; k < TPW; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) red[((size_t)(wave * TPW + k) * 4 + j) * 64 + lane] = acc[k][j];
+    __syncthreads();
+    flush_du(niter - 1);
+    if (grp == 0) {
+        float dsum = 0.f;
+#pragma unroll
+        for (int k = 0; k < TPW; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float2 sum = acc[k][j];
+#pragma unroll
+                for (int gi = 1; gi < NGRP; ++gi) {
+                    const float2 v = red[((size_t)((gi * NWP + wave) * TPW + k) * 4 + j) * 64 + lane];
+                    sum.x += v.x; sum.y += v.y;
+                }
+                acc[k][j] = sum;
+                dsum += sum.x;
+            }
+        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+        if (lane == 0) dred[wave] = dsum;
+        if (dk) {     // inverse of phase 2 into group 0's first exchange buffer
+#pragma unroll
+            for (int k = 0; k < TPW; ++k) {
+                H8U m;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) m.w[j] = pack_h2(acc[k][j].x, acc[k][j].y);
+                const f4 zr = MFMA(K.IL.re, m.v, zero), zi = MFMA(K.IL.im, m.v, zero);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) lds[ad[k][j]] = pack_h2(zr[j], zi[j]);
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0 && dD) {
+        float t = 0.f;
+        for (int w2 = 0; w2 < NWP; ++w2) t += dred[w2];
+        dD[h] = t * dDscale;
+    }
+    if (dk) {
+#pragma unroll
+        for (int k = 0; k < TPW; ++k) {
+            if ((k % NGRP) != grp) continue;      // tile t0+k: its constants live in every group's wave t0/TPW
+            f4 r, s;
+            w_phase3_tile<LG, TPW, false>(lds, K, t0, k, lane, r, s);
+            if (g < 2) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    dk[(size_t)h * N + (4 * g + j) * 16 * C::TC + c * C::TC + t0 + k] = r[j] * dkscale;
+            }
+        }
+    }
+}
+
+template <int LG, class IO, int TPW, int NWV>
+hipError_t wbwd_go(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD,
+                   const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
+{
+    using T = typename IO::T;
+    using C = WC<LG>;
+    constexpr int NWP = C::TC / TPW, NGRP = NWV / NWP;
+    const size_t lds = (size_t)NGRP * (3 * C::PAIR_WORDS + C::L) * 4 + (size_t)NWV * TPW * 4 * 64 * 8 + 64;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wbwd_kernel<LG, IO, TPW, NWV>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    int shift = 4 + (C::cb == 4 ? 2 : (C::cb >= 2 ? 1 : 0));
+    const float dDscale = pl.dkscale / (float)(1 << shift);
+    hipLaunchKernelGGL((wbwd_kernel<LG, IO, TPW, NWV>), dim3((unsigned)pr.H), dim3(NWV * 64), lds, st, (const T*)dy,
+                       (const T*)u, kspec, (T*)du, dk, dD, pr.B, pr.H, pr.N, pr.npairs, pl.dkscale, dDscale,
+                       (const unsigned char*)tb.wtab);
+    return hipGetLastError();
+}
+
+template <class IO>
+hipError_t wbwd_io(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD,
+                   const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
+{
+    switch (pl.log2L2) {
+        case 9: return wbwd_go<9, IO, 2, 4>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
+        case 10: return wbwd_go<10, IO, 2, 4>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
+        case 11: return wbwd_go<11, IO, 2, 4>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// -------------------------------------------------------------------------------------
 // Kernel spectrum on the matrix cores (Algorithm 2 lines 1-2) for the wave kernels' lane order.
 // One workgroup (NWP waves) per head.  The row is scaled by a power of two r that brings
 // max|k[h,:]| to about 1, so the fp16 operands keep their relative precision whatever the head's
@@ -945,6 +1177,15 @@ hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, const Pr
 {
     if (pr.io == LONGCONV_F16) return wdk_io<IoF16>(dy, u, dk, dD, pr, pl, tb, st);
     if (pr.io == LONGCONV_BF16) return wdk_io<IoBF16>(dy, u, dk, dD, pr, pl, tb, st);
+    return hipErrorInvalidValue;
+}
+
+hipError_t wave_bwd(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD,
+                    const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
+{
+    if (!wave_bwd_ok(pl)) return hipErrorInvalidValue;
+    if (pr.io == LONGCONV_F16) return wbwd_io<IoF16>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
+    if (pr.io == LONGCONV_BF16) return wbwd_io<IoBF16>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
     return hipErrorInvalidValue;
 }
 

@@ -16,7 +16,8 @@ pytestmark = pytest.mark.gpu
 def _need_gpu_and_clean_env(monkeypatch):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL", "LONGCONV_FUSE_PASS_A"):
+    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL", "LONGCONV_FUSE_PASS_A",
+              "LONGCONV_FUSE_BWD"):
         monkeypatch.delenv(v, raising=False)
     yield
 
@@ -101,11 +102,20 @@ def test_optional_gradients():
     g = GpuRun(wl.generate(wl.WORKLOADS["2"], B=2, H=2))
     du, dk, dD = [a.copy() for a in g.bwd()]
     g.du.fill_(7.0); g.dk.fill_(7.0); g.dD.fill_(7.0)
+    # (a call for all three runs one fused kernel on this workload, partial calls the separate kernels: the
+    # results agree to rounding, not bitwise)
+    tol = 2 * 3e-3
     du1, dk1, dD1 = g.bwd(du=False)
-    assert np.all(du1 == 7.0) and np.array_equal(dk1, dk) and np.array_equal(dD1, dD)
+    assert np.all(du1 == 7.0) and wl.rel_l2(dk1, dk) <= tol and wl.rel_l2(dD1, dD) <= tol
     g.du.fill_(7.0); g.dk.fill_(7.0); g.dD.fill_(7.0)
     du2, dk2, dD2 = g.bwd(dk=False, dD=False)
-    assert np.array_equal(du2, du) and np.all(dk2 == 7.0) and np.all(dD2 == 7.0)
+    assert wl.rel_l2(du2, du) <= tol and np.all(dk2 == 7.0) and np.all(dD2 == 7.0)
+    g.du.fill_(7.0); g.dk.fill_(7.0); g.dD.fill_(7.0)
+    du3, dk3, dD3 = g.bwd(dk=False)                      # du and dD only: dk stays untouched
+    assert wl.rel_l2(du3, du) <= tol and np.all(dk3 == 7.0) and wl.rel_l2(dD3, dD) <= tol
+    g.du.fill_(7.0); g.dk.fill_(7.0); g.dD.fill_(7.0)
+    du4, dk4, dD4 = g.bwd(dD=False)                      # du and dk only
+    assert np.array_equal(du4, du) and np.array_equal(dk4, dk) and np.all(dD4 == 7.0)
 
 
 def test_delta_and_shifted_delta_on_gpu():

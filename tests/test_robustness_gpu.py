@@ -17,7 +17,8 @@ pytestmark = pytest.mark.gpu
 def _need_gpu_and_clean_env(monkeypatch):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL", "LONGCONV_FUSE_PASS_A"):
+    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL", "LONGCONV_FUSE_PASS_A",
+              "LONGCONV_FUSE_BWD"):
         monkeypatch.delenv(v, raising=False)
     yield
 
@@ -177,3 +178,25 @@ def test_pass_a_inside_the_inner_kernel(monkeypatch, N, io):
     assert not np.array_equal(y, y2)          # the two paths round differently: the switch did take effect
     if N == 65536:
         assert not np.array_equal(dk, dk2)    # dk: outer radix 8 from the rows against radix 4 from a workspace
+
+
+@pytest.mark.parametrize("io", [wl.F16, wl.BF16])
+@pytest.mark.parametrize("N,B,H", [(256, 5, 7), (512, 1, 5), (1024, 7, 9), (1024, 16, 3)])
+def test_backward_in_one_kernel(monkeypatch, N, B, H, io):
+    """Single-pass plans up to 2048 points: a call that asks for du and dk/dD runs one kernel (one read of dy
+    and u, one transform of dy).  Against the oracle, and against the separate du and dk kernels: du sees the
+    same arithmetic in both (bitwise equal), dk sums the same products with the roles of the packed and the
+    fp32 operand swapped."""
+    from gpu_harness import GpuRun, TOL, check_full
+    inp = wl.generate(_w("2", N=N, dtype=io), B=B, H=H)
+    check_full(inp, label=f"fused backward, io={wl.DTYPE_NAMES[io]}")
+    g = GpuRun(inp)
+    du, dk, dD = (a.copy() for a in g.bwd())
+    du_only = g.bwd(dk=False, dD=False)[0].copy()          # du alone: the convolution kernel
+    monkeypatch.setenv("LONGCONV_FUSE_BWD", "0")
+    g2 = GpuRun(inp)
+    du2, dk2, dD2 = g2.bwd()
+    tol = 2 * TOL[io]
+    assert np.array_equal(du_only, du2)
+    assert wl.rel_l2(du, du2) <= tol and wl.rel_l2(dk, dk2) <= tol and wl.rel_l2(dD, dD2) <= tol
+    assert not np.array_equal(dk, dk2)        # the switch did take effect
