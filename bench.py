@@ -38,7 +38,7 @@ CACHE_BYTES = 256 << 20        # last-level (Infinity) cache
 KIB = 1024
 MEASURED_TRAFFIC = {
     # (backward: one kernel for du, dk and dD)
-    "cfg2_B16_H768_N1024_bf16": {"fwd": (15891.0 * 2 + 24576.0) * KIB, "bwd": None},
+    "cfg2_B16_H768_N1024_bf16": {"fwd": (15883.1 * 2 + 24576.0) * KIB, "bwd": (28186.2 * 2 + 27672.0) * KIB},
     # (the convolution kernels read rows in 64-byte requests, which FETCH_SIZE x 2 over-counts: upper bound;
     # backward: the dk kernel, then the convolution kernel with the conjugate spectrum)
     "cfg3_B8_H256_N16384_fp16": {"fwd": (98875.7 * 2 + 65536.0) * KIB,
