@@ -546,7 +546,7 @@ void mfma_fill_plan(Plan& pl)
     pl.fuse_a = pl.order.coop_lg == COOP_MAX_LOG2 && (pl.log2R == 2 || pl.log2R == 3) && !(fa && !strcmp(fa, "0"));
     // one backward kernel where a wave group holds a head's accumulators (LONGCONV_FUSE_BWD=0: separate kernels)
     const char* fb = getenv("LONGCONV_FUSE_BWD");
-    pl.fuse_bwd = pl.order.wave_lg && pl.log2L2 <= 11 && pl.log2R == 0 && !(fb && !strcmp(fb, "0"));
+    pl.fuse_bwd = pl.order.wave_lg && pl.log2R == 0 && !(fb && !strcmp(fb, "0"));
 }
 
 hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,
@@ -563,8 +563,7 @@ hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __
                    __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl, const Tables& tb,
                    hipStream_t st)
 {
-    // L = 4096 keeps the cooperative kernel: its accumulators do not fit one wave's registers
-    if (pl.order.wave_lg && pl.log2L2 <= 11) return wave_dk(dy, u, dk, dD, pr, pl, tb, st);
+    if (pl.order.wave_lg) return wave_dk(dy, u, dk, dD, pr, pl, tb, st);
     if (pl.order.coop_lg) return coop_dk(dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, zbuf, pr, pl, tb, st);
     if (pr.io == LONGCONV_F16) {
         LC_LG_SWITCH(dk_go, IoF16, dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, pr, pl, tb, st)

@@ -781,6 +781,7 @@ hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, const Pro
         case 9: return wdk_go<9, IO, 2, 4>(dy, u, dk, dD, pr, pl, tb, st);
         case 10: return wdk_go<10, IO, 2, 4>(dy, u, dk, dD, pr, pl, tb, st);
         case 11: return wdk_go<11, IO, 2, 4>(dy, u, dk, dD, pr, pl, tb, st);
+        case 12: return wdk_go<12, IO, 2, 8>(dy, u, dk, dD, pr, pl, tb, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -879,18 +880,15 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
         if (pnext < npairs) load_src(pnext, dy, ind);
         pair_sync<NWP>();
         if (it > 0) flush_du(it - 1);
-        uint32_t w[TPW][4];
+        f4 wr[TPW], wi[TPW];                             // W of the wave's tiles, fp32 until it meets Z
         if (act) {
-            f4 yr[TPW], yi[TPW];
-            w_phase2_fwd<LG, TPW>(xd, K, ad, yr, yi);
+            w_phase2_fwd<LG, TPW>(xd, K, ad, wr, wi);
 #pragma unroll
             for (int k = 0; k < TPW; ++k) {
                 H8U m;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    w[k][j] = pack_h2(yr[k][j], yi[k][j]);
-                    m.w[j] = cmul_pack_conj(yr[k][j], yi[k][j], kk[k].c[j]);     // correlation with the kernel
-                }
+                for (int j = 0; j < 4; ++j)
+                    m.w[j] = cmul_pack_conj(wr[k][j], wi[k][j], kk[k].c[j]);     // correlation with the kernel
                 const f4 zr = MFMA(K.IL.re, m.v, zero), zi = MFMA(K.IL.im, m.v, zero);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) xd[ad[k][j]] = pack_h2(zr[j], zi[j]);
@@ -919,12 +917,9 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
             for (int k = 0; k < TPW; ++k)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    union { uint32_t u; h2 h; } cv;
-                    cv.u = w[k][j];
-                    const float wr = (float)cv.h[0], wi = (float)cv.h[1];
                     // conj(Z) * W, one fused multiply-add per term
-                    acc[k][j].x = __builtin_fmaf(yi[k][j], wi, __builtin_fmaf(yr[k][j], wr, acc[k][j].x));
-                    acc[k][j].y = __builtin_fmaf(-yi[k][j], wr, __builtin_fmaf(yr[k][j], wi, acc[k][j].y));
+                    acc[k][j].x = __builtin_fmaf(yi[k][j], wi[k][j], __builtin_fmaf(yr[k][j], wr[k][j], acc[k][j].x));
+                    acc[k][j].y = __builtin_fmaf(-yi[k][j], wr[k][j], __builtin_fmaf(yr[k][j], wi[k][j], acc[k][j].y));
                 }
         }
     }
@@ -1013,6 +1008,7 @@ hipError_t wbwd_io(const void* dy, const void* u, const float2* kspec, void* du,
         case 9: return wbwd_go<9, IO, 2, 4>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
         case 10: return wbwd_go<10, IO, 2, 4>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
         case 11: return wbwd_go<11, IO, 2, 4>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
+        case 12: return wbwd_go<12, IO, 2, 8>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
         default: return hipErrorInvalidValue;
     }
 }
