@@ -99,7 +99,7 @@ int longconv_fwd(const void* u, const float* k, const float* D, const void* kspe
 /* Backward: du, dk, dD as defined above.  Any of the three output pointers may be
  * NULL to skip that gradient.  dk and dD are overwritten (not accumulated) and are
  * summed over b in a fixed order (bitwise repeatable call to call).  Which kernels
- * run depends on which outputs are asked for (for N <= 1024 with fp16/bf16 I/O, du
+ * run depends on which outputs are asked for (for N <= 2048 with fp16/bf16 I/O, du
  * together with dk or dD comes from one kernel, otherwise from separate ones), so a
  * gradient may differ in its last bits between a call for all three and a call for
  * itself alone; both meet the stated accuracy.  kspec as in longconv_fwd (only

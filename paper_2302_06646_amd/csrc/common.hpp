@@ -166,7 +166,7 @@ struct Plan {
     float kscale;    // factor folded into the stored spectrum (includes 1/L)
     float dkscale;   // factor applied to the inverse transform of the dk accumulator
     int fuse_a;      // multi-pass convolutions take pass A inside the inner kernel (outer radix 4 or 8, matrix cores)
-    int fuse_bwd;    // du, dk and dD of one call come from one kernel (single pass up to 2048 points, matrix cores)
+    int fuse_bwd;    // du, dk and dD of one call come from one kernel (single pass up to 4096 points, matrix cores)
 };
 
 Plan make_plan(int64_t N, int io);

@@ -77,7 +77,7 @@ hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, 
                      const Plan& pl, const Tables& tb, hipStream_t st);
 hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
                    const Tables& tb, hipStream_t st);
-// du, dk and dD in one kernel, from one read of dy and u (single-pass plans up to 2048 points; dk and dD may be
+// du, dk and dD in one kernel, from one read of dy and u (single-pass plans up to 4096 points; dk and dD may be
 // null, du not).
 inline bool wave_bwd_ok(const Plan& pl) { return pl.fuse_bwd != 0; }
 hipError_t wave_bwd(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD,

@@ -185,9 +185,9 @@ def test_pass_a_inside_the_inner_kernel(monkeypatch, N, io):
 
 
 @pytest.mark.parametrize("io", [wl.F16, wl.BF16])
-@pytest.mark.parametrize("N,B,H", [(256, 5, 7), (512, 1, 5), (1024, 7, 9), (1024, 16, 3)])
+@pytest.mark.parametrize("N,B,H", [(256, 5, 7), (512, 1, 5), (1024, 7, 9), (1024, 16, 3), (2048, 3, 6)])
 def test_backward_in_one_kernel(monkeypatch, N, B, H, io):
-    """Single-pass plans up to 2048 points: a call that asks for du and dk/dD runs one kernel (one read of dy
+    """Single-pass plans up to 4096 points: a call that asks for du and dk/dD runs one kernel (one read of dy
     and u, one transform of dy).  Against the oracle, and against the separate du and dk kernels: du sees the
     same arithmetic in both (bitwise equal), dk sums the same products with the roles of the packed and the
     fp32 operand swapped."""
