@@ -11,7 +11,7 @@ distinct buffer sets (more than the 256 MB last-level cache in total) so that re
 HBM rather than from cache.  The timed region is exactly K steps between two events on the launch
 stream; the per-call durations (`segments_ms`, `roofline`) come from a second run of the same K
 steps with an event between the three calls (each event costs a few microseconds of GPU time, so
-it stays out of the timed region).  Prints ONE JSON line (see README for the fields).
+it stays out of the timed region).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4a|...] [--no-cpu]
 """

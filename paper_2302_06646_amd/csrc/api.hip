@@ -175,9 +175,11 @@ static hipError_t run_kspec(const float* k, const float* D, float2* kspec, float
         // matrix-core route: per-head power-of-two pre-scale, (pass A,) forward half of the fused kernel
         if (pl.order.wave_lg) return wave_kspec(k, D, kspec, H, N, pl, tb, st);
         // single pass, or pass A taken inside the kernel: it reads k itself and finds the maxima
-        if (!pl.log2R || pl.fuse_a) return coop_kspec(k, nullptr, D, nullptr, kspec, H, N, pl, tb, st);
+        // (outer radix 8: eight chunks per head would each scan 512 KB, so the maxima are found once, in front)
+        if (!pl.log2R || (pl.fuse_a && pl.log2R < 3)) return coop_kspec(k, nullptr, D, nullptr, kspec, H, N, pl, tb, st);
         hipError_t e = head_max(k, hscale, H, N, st);
         if (e != hipSuccess) return e;
+        if (pl.fuse_a) return coop_kspec(k, nullptr, D, hscale, kspec, H, N, pl, tb, st);
         if (pl.log2R) {
             Problem pk{1, H, N, LONGCONV_F32, 1};
             e = outer_fwd(k, nullptr, kscratch, nullptr, nullptr, pk, pl.log2R, pl.log2L2, 1.0f, true, tw, st, hscale);

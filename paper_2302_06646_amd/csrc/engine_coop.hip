@@ -1567,14 +1567,14 @@ coop_kspec_kernel(const __half2* __restrict__ ws, const float* __restrict__ D, c
 // H 2^LR, chunk index fastest and renumbered per XCD, so that the chunks of a head share its row in one L2.
 // Every chunk needs the whole row (pass A sums its R/2 pieces); the workgroup reads it in unit-stride 32-byte
 // runs.  R <= 4: the row stays in registers between the search of the head's maximum (power-of-two pre-scale)
-// and the conversion, one round trip to memory; R = 8: the row is read twice.
+// and the conversion, one round trip to memory; R = 8: the maximum comes from the caller (rs).
 // Then s[n2] = sum_{n1 < R/2} w_R^(n1 k1) k[n1 L + n2] goes to the exchange slots as fp16 complex, phase 1 runs
 // in place with the twist in its operands, the forward half of phase 2 writes kscale (FFT + D[h]).
 template <int LG, int LR>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
-coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D, float2* __restrict__ kspec,
-                       float kscale_over_c, float kscale, const float2* __restrict__ tw,
-                       const unsigned char* __restrict__ ctab)
+coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D, const float* __restrict__ rs,
+                       float2* __restrict__ kspec, float kscale_over_c, float kscale,
+                       const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
     constexpr int NT = C::NW * 64, RH = LR ? (1 << LR) / 2 : 1;
@@ -1654,13 +1654,18 @@ coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D,
 #pragma unroll
         for (int i = 0; i < RPA; ++i) put_run(v[i], i, r);
     } else {
+        // the head's maximum comes from the caller (rs, found by a kernel in front: one read of the row instead
+        // of one per chunk), else from a scan of the whole row here
         float m = 0.f;
-        const float4* k4 = reinterpret_cast<const float4*>(kr);
-        for (int i = tid; i < RH * (C::L / 4); i += NT) {
-            const float4 q = k4[i];
-            m = fmaxf(m, fmaxf(fmaxf(fabsf(q.x), fabsf(q.y)), fmaxf(fabsf(q.z), fabsf(q.w))));
+        if (!rs) {
+            const float4* k4 = reinterpret_cast<const float4*>(kr);
+            for (int i = tid; i < RH * (C::L / 4); i += NT) {
+                const float4 q = k4[i];
+                m = fmaxf(m, fmaxf(fmaxf(fabsf(q.x), fabsf(q.y)), fmaxf(fabsf(q.z), fabsf(q.w))));
+            }
         }
-        r = head_scale_of(head_max(m));
+        m = head_max(m);                                 // (the barrier also covers the tables)
+        r = head_scale_of(rs ? rs[h] : m);
         twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);
 #pragma unroll
         for (int i0 = 0; i0 < RPA; i0 += 2) {
@@ -1840,13 +1845,13 @@ hipError_t coop_kspec_go(const float* k, const __half2* ws, const float* D, cons
     dim3 grid((unsigned)H, 1u << pl.log2R);
     const int shift = 6 + (C::te >= 2 ? 1 : 0);
     const float koc = pl.kscale * (float)(1 << shift);
-    auto launch_rows = [&](auto kern) {      // staged form (ws and rs unused)
+    auto launch_rows = [&](auto kern) {      // staged form (ws unused; rs only at outer radix 8)
         const size_t lds_rows = coop_real_lds_bytes<LG>();
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_rows);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3((unsigned)(H << pl.log2R)), dim3(C::NW * 64), lds_rows, st, k, D, kspec, koc,
-                           pl.kscale, tb.tw, (const unsigned char*)tb.ctab);
+        hipLaunchKernelGGL(kern, dim3((unsigned)(H << pl.log2R)), dim3(C::NW * 64), lds_rows, st, k, D,
+                           pl.log2R == 3 ? rs : nullptr, kspec, koc, pl.kscale, tb.tw, (const unsigned char*)tb.ctab);
         return hipGetLastError();
     };
     if (pl.log2R == 0) return launch_rows(coop_kspec_rows_kernel<LG, 0>);
