@@ -344,7 +344,7 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
                 e = valu_dk(dy, u, dk, dD, (const float2*)(base + w.ws2), (const float2*)(base + w.ws1),
                             (float2*)(base + w.wsA), pr, pl, tw, st);
         } else if (coop_dk_rows_ok(pl)) {
-            // straight from the rows, as outer radix 8 around 16384-point transforms (no pass A kernel)
+            // straight from the rows, as outer radix 8 or 16 around 16384-point transforms (no pass A kernel)
             cR += 1; cL2 -= 1;
             e = coop_dk_rows(dy, u, dk ? (__half2*)(base + w.wsA) : nullptr, dD ? dpart : nullptr, pr, pl, tb, st,
                              &cscale);

@@ -678,9 +678,69 @@ __device__ __forceinline__ void stage_rows_pass_a_impl(uint32_t* xb, const typen
         crs[n1] = h2{(_Float16)(-w.y), (_Float16)w.x};
     }
     constexpr int RPA = (C::L / 8) / NT;             // runs of eight samples per lane
-    constexpr int RB = (RH <= 2 ? 2 : 1) * (HASB ? 1 : 2);      // runs in flight
+    constexpr int RB = RH > 4 ? 1 : (RH <= 2 ? 2 : 1) * (HASB ? 1 : 2);      // runs in flight
     constexpr int NV = HASB ? 2 : 1;
     static_assert(RPA % RB == 0, "runs in flight divide the runs of a lane");
+    if constexpr (RH > 4) {
+        // outer radix 16: the eight pieces of a run come in two halves of four (registers), the sums of the first
+        // half wait as packed fp16
+        constexpr int PH = 4;
+#pragma unroll
+        for (int i0 = 0; i0 < RPA; i0 += RB) {
+            uint32_t sum[RB][8];
+#pragma unroll
+            for (int half = 0; half < RH / PH; ++half) {
+                uint4 v[RB][NV][PH];
+#pragma unroll
+                for (int i = 0; i < RB; ++i) {
+                    const int n = staged_run_n<LG>((i0 + i) * NT + tid);
+#pragma unroll
+                    for (int q = 0; q < PH; ++q) {
+                        v[i][0][q] = *reinterpret_cast<const uint4*>(ra + (size_t)(half * PH + q) * C::L + n);
+                        if (HASB) v[i][NV - 1][q] = *reinterpret_cast<const uint4*>(rb + (size_t)(half * PH + q) * C::L + n);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < RB; ++i) {
+                    uint32_t wa[PH][4], wb[PH][4];
+#pragma unroll
+                    for (int q = 0; q < PH; ++q) {
+                        const uint4 a4 = v[i][0][q], b4 = HASB ? v[i][NV - 1][q] : make_uint4(0u, 0u, 0u, 0u);
+                        wa[q][0] = a4.x; wa[q][1] = a4.y; wa[q][2] = a4.z; wa[q][3] = a4.w;
+                        wb[q][0] = b4.x; wb[q][1] = b4.y; wb[q][2] = b4.z; wb[q][3] = b4.w;
+                        if (IsBf<IO>::v) {
+#pragma unroll
+                            for (int m = 0; m < 4; ++m) {
+                                wa[q][m] = bf2_to_h2(wa[q][m]);
+                                if (HASB) wb[q][m] = bf2_to_h2(wb[q][m]);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+                        union { uint32_t u; h2 h; } acc, z;
+                        acc.u = half ? sum[i][e] : __builtin_amdgcn_perm(wb[0][e >> 1], wa[0][e >> 1], sel);
+#pragma unroll
+                        for (int q = half ? 0 : 1; q < PH; ++q) {
+                            const int n1 = half * PH + q;
+                            z.u = __builtin_amdgcn_perm(wb[q][e >> 1], wa[q][e >> 1], sel);
+                            const h2 x = {z.h[0], z.h[0]}, y = {z.h[1], z.h[1]};
+                            acc.h = __builtin_elementwise_fma(y, crs[n1], __builtin_elementwise_fma(x, cr[n1], acc.h));
+                        }
+                        sum[i][e] = acc.u;
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < RB; ++i) {
+                const int a0 = staged_slot<LG>(staged_run_n<LG>((i0 + i) * NT + tid));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xb[a0 + 4 * e] = sum[i][e];
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i0 = 0; i0 < RPA; i0 += RB) {
         uint4 v[RB][NV][RH];
@@ -1220,11 +1280,13 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
 
 // -------------------------------------------------------------------------------------
 // dk and dD of the multi-pass split straight from the rows (outer radix 2^LR around 2^LG-point transforms,
-// pass A taken while staging as in coop_conv_kernel).  grid = (H, 2^LR); the workgroup of (head, chunk k1)
-// walks the head's row pairs: u pair -> pass A, phase 1, forward half of phase 2 -> Z (fp16 registers);
-// dy pair likewise -> W; A += conj(Z) W in fp32 registers, eight phase-2 tiles per wave.  Then the inverse
-// half of phase 2 and phase 3 give chunk k1 of pass C's input (fp16 complex, unit-stride runs), and the
-// accumulators' real parts this chunk's share of dD.
+// pass A taken while staging as in coop_conv_kernel).  grid = H 2^LR, chunk index fastest and renumbered per XCD;
+// the workgroup of (head, chunk k1) walks the head's row pairs: u pair -> pass A, phase 1, forward half of
+// phase 2 -> Z (fp16, parked in LDS beside the slots); dy pair likewise -> W; A += conj(Z) W in fp32
+// registers, eight phase-2 tiles per wave.  Then the inverse half of phase 2 and phase 3 give chunk k1 of pass
+// C's input (fp16 complex, unit-stride runs), and the accumulators' real parts this chunk's share of dD.
+// Every chunk's workgroup reads the whole rows: 2^LR reads of u and dy through L2 (LR = 4: 1 GB per launch at
+// N = 131072, B = 1, which is what bounds that case).
 // -------------------------------------------------------------------------------------
 template <int LG, class IO, int LR>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
@@ -1813,8 +1875,8 @@ hipError_t coop_dk_real_go(const void* dy, const void* u, float* dk, float* dD, 
     return hipGetLastError();
 }
 
-// Multi-pass dk from the rows: the plan's split (outer radix 2^log2R around 32768 points) is taken as outer
-// radix 2^(log2R+1) around 16384 points, whose accumulators fit one walk.  Returns the scale pass C has to
+// Multi-pass dk from the rows: the plan's split (outer radix 2^log2R around 32768 points, log2R = 2 or 3) is taken
+// as outer radix 2^(log2R+1) around 16384 points, whose accumulators fit one walk.  Returns the scale pass C has to
 // apply (two forward chains and one inverse chain of the 16384-point transform, 1 / padded length).
 template <class IO, int LR>
 hipError_t coop_dk_rows_go(const void* dy, const void* u, __half2* ws_A, float* dD_part, const Problem& pr,
@@ -1925,8 +1987,13 @@ hipError_t coop_dk_rows(const void* dy, const void* u, __half2* ws_A, float* dD_
                         const Tables& tb, hipStream_t st, float* scale_c)
 {
     if (!coop_dk_rows_ok(pl)) return hipErrorInvalidValue;
-    if (pr.io == LONGCONV_F16) return coop_dk_rows_go<IoF16, 3>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
-    if (pr.io == LONGCONV_BF16) return coop_dk_rows_go<IoBF16, 3>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
+    if (pl.log2R == 2) {
+        if (pr.io == LONGCONV_F16) return coop_dk_rows_go<IoF16, 3>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
+        if (pr.io == LONGCONV_BF16) return coop_dk_rows_go<IoBF16, 3>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
+    } else {
+        if (pr.io == LONGCONV_F16) return coop_dk_rows_go<IoF16, 4>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
+        if (pr.io == LONGCONV_BF16) return coop_dk_rows_go<IoBF16, 4>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
+    }
     return hipErrorInvalidValue;
 }
 

@@ -92,10 +92,13 @@ hipError_t coop_fill_tables(const void** tab_out, hipStream_t st);
 // fuse_a (plans with pl.fuse_a only): the kernel reads the rows `in` and takes pass A itself.
 hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,
                      const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st);
-// Multi-pass dk straight from the rows, for plans of outer radix 4 around 32768 points with pl.fuse_a: run as outer
-// radix 8 around 16384 points.  ws_A (null: dD only) receives pass C's input for that split (log2R + 1,
-// log2L2 - 1), dD_part[h * 8 + k1] the chunks' shares of dD, *scale_c the factor pass C applies.
-inline bool coop_dk_rows_ok(const Plan& pl) { return pl.fuse_a && pl.log2R == 2 && pl.log2L2 == COOP_MAX_LOG2; }
+// Multi-pass dk straight from the rows, for plans of outer radix 4 or 8 around 32768 points with pl.fuse_a: run as
+// outer radix 8 or 16 around 16384 points.  ws_A (null: dD only) receives pass C's input for that split (log2R + 1,
+// log2L2 - 1), dD_part[h * 2R + k1] the chunks' shares of dD, *scale_c the factor pass C applies.
+inline bool coop_dk_rows_ok(const Plan& pl)
+{
+    return pl.fuse_a && (pl.log2R == 2 || pl.log2R == 3) && pl.log2L2 == COOP_MAX_LOG2;
+}
 hipError_t coop_dk_rows(const void* dy, const void* u, __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl,
                         const Tables& tb, hipStream_t st, float* scale_c);
 // ws: pass-A output of the pre-scaled kernel (multi-pass plans only).

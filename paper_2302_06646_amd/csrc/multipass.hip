@@ -113,36 +113,41 @@ __global__ void outer_inv_kernel(const typename CW::T* __restrict__ ws, typename
     }
 }
 
-// v * e^(+2 pi i m / 8), m a compile-time constant after unrolling: quarter turns, then one eighth
-__device__ __forceinline__ float2 rot8(float2 v, int m)
+// v * e^(+2 pi i m / 16), m a compile-time constant after unrolling: quarter turns, then up to three sixteenths
+__device__ __forceinline__ float2 rot16(float2 v, int m)
 {
-    const int q = (m >> 1) & 3;
-    float2 r = q == 0 ? v : q == 1 ? make_float2(-v.y, v.x) : q == 2 ? make_float2(-v.x, -v.y) : make_float2(v.y, -v.x);
-    if (m & 1) r = make_float2((r.x - r.y) * 0.70710678118654752f, (r.x + r.y) * 0.70710678118654752f);
-    return r;
+    const int q = (m >> 2) & 3, r = m & 3;
+    const float2 t = q == 0 ? v : q == 1 ? make_float2(-v.y, v.x) : q == 2 ? make_float2(-v.x, -v.y) : make_float2(v.y, -v.x);
+    constexpr float C1 = 0.92387953251128674f, S1 = 0.38268343236508977f, H = 0.70710678118654752f;
+    if (r == 1) return make_float2(t.x * C1 - t.y * S1, t.x * S1 + t.y * C1);
+    if (r == 2) return make_float2((t.x - t.y) * H, (t.x + t.y) * H);
+    if (r == 3) return make_float2(t.x * S1 - t.y * C1, t.x * C1 + t.y * S1);
+    return t;
 }
 
-template <class IO>
-__device__ __forceinline__ void store_four(typename IO::T* p, float a, float b, float c, float d);
-template <>
-__device__ __forceinline__ void store_four<IoF32>(float* p, float a, float b, float c, float d)
+// columns per thread of outer_inv4_kernel
+__host__ __device__ constexpr int inv4_columns(int log2R) { return log2R <= 3 ? 4 : 2; }
+
+// V (2 or 4) neighbouring samples of a row as one store
+template <class IO, int V>
+__device__ __forceinline__ void store_cols(typename IO::T* p, const float (&x)[V])
 {
-    *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
-}
-template <>
-__device__ __forceinline__ void store_four<IoF16>(__half* p, float a, float b, float c, float d)
-{
-    *reinterpret_cast<uint2*>(p) = make_uint2(mu::pack_h2(a, b), mu::pack_h2(c, d));
-}
-template <>
-__device__ __forceinline__ void store_four<IoBF16>(uint16_t* p, float a, float b, float c, float d)
-{
-    *reinterpret_cast<uint2*>(p) = make_uint2(mu::pack_bf2(a, b), mu::pack_bf2(c, d));
+    static_assert(V == 2 || V == 4, "two or four columns");
+    if constexpr (std::is_same<IO, IoF32>::value) {
+        if constexpr (V == 4) *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+        else *reinterpret_cast<float2*>(p) = make_float2(x[0], x[1]);
+    } else {
+        uint32_t w[V / 2];
+#pragma unroll
+        for (int i = 0; i < V / 2; ++i)
+            w[i] = std::is_same<IO, IoBF16>::value ? mu::pack_bf2(x[2 * i], x[2 * i + 1]) : mu::pack_h2(x[2 * i], x[2 * i + 1]);
+        mu::store_words<V / 2>(p, w);
+    }
 }
 
-// Pass C for an fp16 workspace and outer radix up to 8: four neighbouring columns n2 per thread, so that the
+// Pass C for an fp16 workspace and outer radix up to 16: four (radix 16: two) neighbouring columns n2 per thread, so that the
 // chunks are read in 16-byte pieces and the rows written in 8- or 16-byte pieces; the twist of chunk k1 is the
-// k1-th power of one table entry per column, the radix-R inverse butterfly uses the eighth roots of unity as
+// k1-th power of one table entry per column, the radix-R inverse butterfly uses the sixteenth roots of unity as
 // constants.
 template <class IO, int LOG2R>
 __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restrict__ ws,
@@ -150,25 +155,26 @@ __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restric
                                                         int64_t N, int npairs, int log2L2, float scale,
                                                         const float2* __restrict__ tw)
 {
-    static_assert(LOG2R >= 1 && LOG2R <= 3, "the roots of unity of rot8");
+    static_assert(LOG2R >= 1 && LOG2R <= 4, "the roots of unity of rot16");
     constexpr int R = 1 << LOG2R, RH = R / 2;
+    constexpr int VEC = inv4_columns(LOG2R);             // columns per thread (radix 16: two, for the registers)
     const int L2 = 1 << log2L2;
     const int log2L = log2L2 + LOG2R;
-    const int n2 = (blockIdx.x * OB + threadIdx.x) * 4;
+    const int n2 = (blockIdx.x * OB + threadIdx.x) * VEC;
     const int pairidx = blockIdx.y;
     const int h = pairidx / npairs, p = pairidx % npairs;
     const bool has_b = (2 * p + 1) < B;
     const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
     const __half2* src = ws + ((size_t)pairidx << log2L) + n2;
-    float2 w1[4], pw[4], v[R][4];
+    float2 w1[VEC], pw[VEC], v[R][VEC];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w1[j] = tw_full(tw, (uint32_t)(n2 + j) << (TW_LOG2 - log2L));
+    for (int j = 0; j < VEC; ++j) w1[j] = tw_full(tw, (uint32_t)(n2 + j) << (TW_LOG2 - log2L));
 #pragma unroll
     for (int k1 = 0; k1 < R; ++k1) {
-        const uint4 q = *reinterpret_cast<const uint4*>(src + (size_t)k1 * L2);
-        const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+        uint32_t qw[4];
+        mu::load_words<VEC>(src + (size_t)k1 * L2, qw);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < VEC; ++j) {
             union { uint32_t u; __half2 hh; } cv;
             cv.u = qw[j];
             const float2 x = __half22float2(cv.hh);
@@ -178,16 +184,19 @@ __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restric
     }
 #pragma unroll
     for (int n1 = 0; n1 < RH; ++n1) {
-        float2 t[4];
+        float2 t[VEC];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < VEC; ++j) {
             t[j] = v[0][j];
 #pragma unroll
-            for (int k1 = 1; k1 < R; ++k1) t[j] = cadd(t[j], rot8(v[k1][j], ((n1 * k1) & (R - 1)) * (8 / R)));
+            for (int k1 = 1; k1 < R; ++k1) t[j] = cadd(t[j], rot16(v[k1][j], ((n1 * k1) & (R - 1)) * (16 / R)));
         }
         const size_t n = (size_t)n1 * L2 + n2;
-        store_four<IO>(out + oa + n, t[0].x * scale, t[1].x * scale, t[2].x * scale, t[3].x * scale);
-        if (has_b) store_four<IO>(out + ob + n, t[0].y * scale, t[1].y * scale, t[2].y * scale, t[3].y * scale);
+        float a[VEC], b[VEC];
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) { a[j] = t[j].x * scale; b[j] = t[j].y * scale; }
+        store_cols<IO, VEC>(out + oa + n, a);
+        if (has_b) store_cols<IO, VEC>(out + ob + n, b);
     }
 }
 
@@ -253,9 +262,10 @@ hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, 
 {
     using T = typename IO::T;
     using C = typename CW::T;
-    if constexpr (std::is_same<CW, CwF16>::value && LOG2R <= 3) {
-        if ((1 << log2L2) >= 4 * OB) {
-            dim3 grid4((1u << log2L2) / (4 * OB), (unsigned)(pr.npairs * pr.H));
+    if constexpr (std::is_same<CW, CwF16>::value && LOG2R <= 4) {
+        constexpr int VEC = inv4_columns(LOG2R);
+        if ((1 << log2L2) >= VEC * OB) {
+            dim3 grid4((1u << log2L2) / (VEC * OB), (unsigned)(pr.npairs * pr.H));
             hipLaunchKernelGGL((outer_inv4_kernel<IO, LOG2R>), grid4, dim3(OB), 0, st, (const __half2*)ws, (T*)out,
                                pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw);
             return hipGetLastError();
