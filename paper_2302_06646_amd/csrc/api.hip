@@ -332,6 +332,7 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
         float* dpart = (float*)(base + w.dpart);
         int cR = pl.log2R, cL2 = pl.log2L2;        // the split and scale pass C of dk works with
         float cscale = pl.dkscale;
+        bool rider = false;
         if (pl.engine == ENGINE_VALU) {
             if (pl.log2R) {
                 // pass A for u (-> ws2) and dy (-> ws1) in one launch, with the dD partial sums
@@ -348,7 +349,8 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
             cR += 1; cL2 -= 1;
             e = coop_dk_rows(dy, u, dk ? (__half2*)(base + w.wsA) : nullptr, dD ? dpart : nullptr, pr, pl, tb, st,
                              &cscale);
-            if (e == hipSuccess && dD) e = reduce_dD(dpart, dD, H, 1 << cR, st);
+            if (e == hipSuccess && dD && !dk) e = reduce_dD(dpart, dD, H, 1 << cR, st);
+            rider = dD && dk;       // the sum of the partials rides along with pass C
         } else {
             if (pl.log2R) {
                 e = outer_fwd(dy, u, base + w.ws1, base + w.ws2, nullptr, pr, pl.log2R, pl.log2L2, 1.0f, true,
@@ -362,7 +364,7 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
         }
         if (e == hipSuccess && pl.log2R && dk) {
             Problem pk{1, H, N, LONGCONV_F32, 1};   // heads as single rows, real part only
-            e = outer_inv(base + w.wsA, dk, pk, cR, cL2, cscale, f16ws, tw, st);
+            e = outer_inv(base + w.wsA, dk, pk, cR, cL2, cscale, f16ws, tw, st, rider ? dpart : nullptr, dD, 1 << cR);
         }
         if (note(e, "bwd dk/dD") != hipSuccess) return LONGCONV_ERR_HIP;
     }

@@ -39,8 +39,11 @@ hipError_t head_max(const float* k, float* mx, int64_t H, int64_t N, hipStream_t
 int outer_fwd_blocks_per_head(const Problem& pr, int log2L2);
 // Pass C: rows of `out` <- scale * sum_{k1} conj(w_R^(n1*k1) w_L^(n2*k1)) ws[...], n1 < R/2 only
 // (truncation to the first N samples); re -> row 2p, im -> row 2p+1.
+// dD_part (optional, only with pr.npairs == 1, i.e. rows = heads): dD[h] = sum of dD_part[h * npart + i] is
+// taken along in the same launch.
 hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
-                     bool ws_f16, const float2* tw, hipStream_t st);
+                     bool ws_f16, const float2* tw, hipStream_t st, const float* dD_part = nullptr,
+                     float* dD = nullptr, int npart = 0);
 // dD[h] = sum of the per-block partials written by outer_fwd.
 hipError_t reduce_dD(const float* part, float* dD, int64_t H, int nblk, hipStream_t st);
 

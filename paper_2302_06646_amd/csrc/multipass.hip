@@ -153,9 +153,18 @@ template <class IO, int LOG2R>
 __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restrict__ ws,
                                                         typename IO::T* __restrict__ out, int64_t B, int64_t H,
                                                         int64_t N, int npairs, int log2L2, float scale,
-                                                        const float2* __restrict__ tw)
+                                                        const float2* __restrict__ tw,
+                                                        const float* __restrict__ dD_part, float* __restrict__ dD,
+                                                        int npart)
 {
     static_assert(LOG2R >= 1 && LOG2R <= 4, "the roots of unity of rot16");
+    // rider for the dk path (rows = heads): one lane per head also adds up the head's dD partials, in index
+    // order, which saves a launch of a few microseconds
+    if (dD_part && blockIdx.x == 0 && threadIdx.x == 0) {
+        float t = 0.f;
+        for (int i = 0; i < npart; ++i) t += dD_part[(size_t)blockIdx.y * npart + i];
+        dD[blockIdx.y] = t;
+    }
     constexpr int R = 1 << LOG2R, RH = R / 2;
     constexpr int VEC = inv4_columns(LOG2R);             // columns per thread (radix 16: two, for the registers)
     const int L2 = 1 << log2L2;
@@ -258,7 +267,7 @@ hipError_t fwd_launch(const void* in, const void* in2, void* ws, void* ws2, floa
 
 template <class IO, class CW, int LOG2R>
 hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, float scale, const float2* tw,
-                      hipStream_t st)
+                      hipStream_t st, const float* dD_part, float* dD, int npart)
 {
     using T = typename IO::T;
     using C = typename CW::T;
@@ -267,10 +276,13 @@ hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, 
         if ((1 << log2L2) >= VEC * OB) {
             dim3 grid4((1u << log2L2) / (VEC * OB), (unsigned)(pr.npairs * pr.H));
             hipLaunchKernelGGL((outer_inv4_kernel<IO, LOG2R>), grid4, dim3(OB), 0, st, (const __half2*)ws, (T*)out,
-                               pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw);
+                               pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw, dD_part, dD, npart);
             return hipGetLastError();
         }
     }
+    if (dD_part)     // the plain kernel has no rider
+        hipLaunchKernelGGL(reduce_dD_kernel, dim3((unsigned)((pr.H + 127) / 128)), dim3(128), 0, st, dD_part, dD, pr.H,
+                           npart);
     dim3 grid((1u << log2L2) / OB, (unsigned)(pr.npairs * pr.H));
     hipLaunchKernelGGL((outer_inv_kernel<IO, CW, LOG2R>), grid, dim3(OB), 0, st, (const C*)ws, (T*)out, pr.B,
                        pr.H, pr.N, pr.npairs, log2L2, scale, tw);
@@ -297,9 +309,9 @@ hipError_t fwd_r(const void* in, const void* in2, void* ws, void* ws2, float* dD
 }
 template <class IO, class CW>
 hipError_t inv_r(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
-                 const float2* tw, hipStream_t st)
+                 const float2* tw, hipStream_t st, const float* dD_part, float* dD, int npart)
 {
-#define CALL(LR) inv_launch<IO, CW, LR>(ws, out, pr, log2L2, scale, tw, st)
+#define CALL(LR) inv_launch<IO, CW, LR>(ws, out, pr, log2L2, scale, tw, st, dD_part, dD, npart)
     LC_R_SWITCH(CALL)
 #undef CALL
 }
@@ -327,10 +339,11 @@ hipError_t outer_fwd(const void* in, const void* in2, void* ws, void* ws2, float
 }
 
 hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
-                     bool ws_f16, const float2* tw, hipStream_t st)
+                     bool ws_f16, const float2* tw, hipStream_t st, const float* dD_part, float* dD, int npart)
 {
     if ((1 << log2L2) < OB) return hipErrorInvalidValue;
-#define GO(IO, CW) return inv_r<IO, CW>(ws, out, pr, log2R, log2L2, scale, tw, st)
+    if (dD_part && pr.npairs != 1) return hipErrorInvalidValue;     // the rider takes rows for heads
+#define GO(IO, CW) return inv_r<IO, CW>(ws, out, pr, log2R, log2L2, scale, tw, st, dD_part, dD, npart)
     if (ws_f16) {
         if (pr.io == LONGCONV_F32) GO(IoF32, CwF16);
         if (pr.io == LONGCONV_F16) GO(IoF16, CwF16);
