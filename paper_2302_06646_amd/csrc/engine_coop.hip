@@ -1655,7 +1655,6 @@ coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D,
     const int h = (int)(vid >> LR), k1 = (int)(vid & ((1u << LR) - 1u));
     const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
     const float* kr = k + (size_t)h * NROW;
-    staged_tables<LG, NT>(lds4, gtab, tw, tid, 0);
 
     float2 cr[RH];
 #pragma unroll
@@ -1703,19 +1702,40 @@ coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D,
         }
     };
 
+    // constants of the transform (table look-ups in global memory)
+    Consts<LG> K;
+    h2 cF[4];
+    Mats F1, F2;
+    auto make_operands = [&]() __attribute__((always_inline)) {
+        make_consts<LG>(K, tw, lane);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float2 w = tw_full(tw, (uint32_t)((c * (4 * g + j)) & 255) << (TW_LOG2 - 8));
+            cF[j] = h2{(_Float16)w.x, (_Float16)w.y};
+        }
+        F1 = LR ? phase_mats(k1, C::cb + 4, LG + LR, tw, lane) : K.F16;
+        F2 = LR ? phase_mats(k1, C::cb, LG + LR, tw, lane) : K.F16;
+    };
+
     float r;
     if constexpr (RH <= 2) {
+        // the row starts travelling first; tables and operands are built behind it (their loads return after
+        // the row's, so one round trip to memory covers everything)
         float4 v[RPA][RH][2];
 #pragma unroll
         for (int i = 0; i < RPA; ++i) load_run(v[i], i);
+        staged_tables<LG, NT>(lds4, gtab, tw, tid, 0);
+        if (LR) twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);     // (a lane rewrites the entries it wrote itself)
+        make_operands();
         float m = 0.f;
 #pragma unroll
         for (int i = 0; i < RPA; ++i) m = max_run(v[i], m);
-        r = head_scale_of(head_max(m));                  // (the barrier also covers the tables)
-        if (LR) twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);
+        r = head_scale_of(head_max(m));                  // (the barrier also covers the cleared slots)
 #pragma unroll
         for (int i = 0; i < RPA; ++i) put_run(v[i], i, r);
     } else {
+        staged_tables<LG, NT>(lds4, gtab, tw, tid, 0);
+        make_operands();
         // the head's maximum comes from the caller (rs, found by a kernel in front: one read of the row instead
         // of one per chunk), else from a scan of the whole row here
         float m = 0.f;
@@ -1739,16 +1759,6 @@ coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D,
         }
     }
 
-    Consts<LG> K;
-    make_consts<LG>(K, tw, lane);
-    h2 cF[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float2 w = tw_full(tw, (uint32_t)((c * (4 * g + j)) & 255) << (TW_LOG2 - 8));
-        cF[j] = h2{(_Float16)w.x, (_Float16)w.y};
-    }
-    const Mats F1 = LR ? phase_mats(k1, C::cb + 4, LG + LR, tw, lane) : K.F16;
-    const Mats F2 = LR ? phase_mats(k1, C::cb, LG + LR, tw, lane) : K.F16;
     __syncthreads();
 #pragma unroll 1
     for (int gi = 0; gi < C::NG; ++gi) phase1_inplace<LG, 2>(xb, t1f, vt, F1, F2, cF, (gi * C::NW + wave) * 8, lane);
