@@ -162,6 +162,7 @@ static int check_shape(int64_t B, int64_t H, int64_t N, int io)
     if (io != LONGCONV_F32 && io != LONGCONV_F16 && io != LONGCONV_BF16) return LONGCONV_ERR_DTYPE;
     if (B < 1 || H < 1 || !pow2(N) || N < 256 || N > 131072) return LONGCONV_ERR_SHAPE;
     if (B > (int64_t(1) << 24) || H > 65535) return LONGCONV_ERR_SHAPE;
+    if (((B + 1) / 2) * H > (int64_t(1) << 22)) return LONGCONV_ERR_SHAPE;   // (head, pair) items index 1-D grids
     return LONGCONV_OK;
 }
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -332,7 +333,6 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
         float* dpart = (float*)(base + w.dpart);
         int cR = pl.log2R, cL2 = pl.log2L2;        // the split and scale pass C of dk works with
         float cscale = pl.dkscale;
-        bool rider = false;
         if (pl.engine == ENGINE_VALU) {
             if (pl.log2R) {
                 // pass A for u (-> ws2) and dy (-> ws1) in one launch, with the dD partial sums
@@ -345,26 +345,26 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
                 e = valu_dk(dy, u, dk, dD, (const float2*)(base + w.ws2), (const float2*)(base + w.ws1),
                             (float2*)(base + w.wsA), pr, pl, tw, st);
         } else if (coop_dk_rows_ok(pl)) {
-            // straight from the rows, as outer radix 8 or 16 around 16384-point transforms (no pass A kernel)
+            // straight from the rows, as outer radix 8 or 16 around 16384-point transforms (no pass A kernel);
+            // dD is the rows' dot product, taken by the workgroup of each head's first chunk
             cR += 1; cL2 -= 1;
-            e = coop_dk_rows(dy, u, dk ? (__half2*)(base + w.wsA) : nullptr, dD ? dpart : nullptr, pr, pl, tb, st,
-                             &cscale);
-            if (e == hipSuccess && dD && !dk) e = reduce_dD(dpart, dD, H, 1 << cR, st);
-            rider = dD && dk;       // the sum of the partials rides along with pass C
+            e = coop_dk_rows(dy, u, dk ? (__half2*)(base + w.wsA) : nullptr, dD, pr, pl, tb, st, &cscale);
         } else {
             if (pl.log2R) {
-                e = outer_fwd(dy, u, base + w.ws1, base + w.ws2, nullptr, pr, pl.log2R, pl.log2L2, 1.0f, true,
-                              tw, st);
+                // pass A for u and dy in one launch; its blocks also leave dD's partial dot products
+                e = outer_fwd(dy, u, base + w.ws1, base + w.ws2, dD ? dpart : nullptr, pr, pl.log2R, pl.log2L2, 1.0f,
+                              true, tw, st);
                 dy_ready = true;
+                if (e == hipSuccess && dD) e = reduce_dD(dpart, dD, H, w.nblk, st);
             }
-            if (e == hipSuccess)
-                e = mfma_dk(dy, u, dk, dD, (const __half2*)(base + w.ws2), (const __half2*)(base + w.ws1),
-                            (__half2*)(base + w.wsA), dD ? dpart : nullptr, base + w.zbuf, pr, pl, tb, st);
-            if (e == hipSuccess && pl.log2R && dD) e = reduce_dD(dpart, dD, H, 1 << pl.log2R, st);
+            if (e == hipSuccess && (dk || !pl.log2R))
+                e = mfma_dk(dy, u, dk, pl.log2R ? nullptr : dD, (const __half2*)(base + w.ws2),
+                            (const __half2*)(base + w.ws1), (__half2*)(base + w.wsA), nullptr, base + w.zbuf, pr, pl,
+                            tb, st);
         }
         if (e == hipSuccess && pl.log2R && dk) {
             Problem pk{1, H, N, LONGCONV_F32, 1};   // heads as single rows, real part only
-            e = outer_inv(base + w.wsA, dk, pk, cR, cL2, cscale, f16ws, tw, st, rider ? dpart : nullptr, dD, 1 << cR);
+            e = outer_inv(base + w.wsA, dk, pk, cR, cL2, cscale, f16ws, tw, st);
         }
         if (note(e, "bwd dk/dD") != hipSuccess) return LONGCONV_ERR_HIP;
     }

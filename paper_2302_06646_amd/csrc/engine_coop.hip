@@ -959,6 +959,20 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     }
 }
 
+// s + dot product of two runs of eight raw samples (I/O dtype, two per word): exact products, fp32 sum
+template <class IO>
+__device__ __forceinline__ float run_dot(const uint4& a, const uint4& b, float s)
+{
+    const uint32_t wa[4] = {a.x, a.y, a.z, a.w}, wb[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        union { uint32_t u; h2 h; bf2 b; } x, y;
+        x.u = wa[m]; y.u = wb[m];
+        s = IsBf<IO>::v ? __builtin_amdgcn_fdot2_f32_bf16(x.b, y.b, s, false) : __builtin_amdgcn_fdot2(x.h, y.h, s, false);
+    }
+    return s;
+}
+
 // wait until at most n of this wave's vector-memory operations are outstanding (n < 16)
 template <int n>
 __device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_waitcnt((n & 15) | (7 << 4) | (15 << 8)); }
@@ -993,7 +1007,7 @@ template <int LG, class IO, bool SPLIT>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
                     float* __restrict__ dk, float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs,
-                    float dkscale, float dDscale, const float2* __restrict__ tw,
+                    float dkscale, const float2* __restrict__ tw,
                     const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
@@ -1138,6 +1152,35 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                 const uint32_t* vt_ = vt + zoff;
                 wait_vm<0>();                            // this wave's share of the copy has landed
                 __syncthreads();                         // ... and everyone's; the slots are free
+                // dD = sum of dy u over the raw rows, in fp32 (first walk only): the dy pair sits in the raw area;
+                // the same runs of the u pair, which went through this CU's caches one source earlier, are read
+                // again from global memory, DG runs at a time (registers)
+                if (pass == 1 && par == 0 && dD != nullptr) {
+                    constexpr int DG = RPL < 2 ? RPL : 2;
+                    const bool dot_b = (2 * p + 1) < B;
+                    const T* qa = u + row_off(2 * p, h, H, N);
+                    const T* qb = u + row_off(dot_b ? 2 * p + 1 : 2 * p, h, H, N);
+                    int t_ = tid;
+                    asm volatile("" : "+v"(t_));
+#pragma unroll
+                    for (int i0 = 0; i0 < RPL; i0 += DG) {
+                        uint4 ua[DG], ub[DG];
+#pragma unroll
+                        for (int i = 0; i < DG; ++i) {
+                            const int n = staged_run_n<LG>((i0 + i) * NT + t_);
+                            ua[i] = *reinterpret_cast<const uint4*>(qa + n);
+                            ub[i] = *reinterpret_cast<const uint4*>(qb + n);
+                        }
+#pragma unroll
+                        for (int i = 0; i < DG; ++i) {
+                            const int n = staged_run_n<LG>((i0 + i) * NT + t_);
+                            const int ia = n / 8, ib = (ROWN + n) / 8;
+                            dsum = run_dot<IO>(ua[i], raw[ia + (ia / (2 * C::TC)) * 4], dsum);
+                            if (dot_b) dsum = run_dot<IO>(ub[i], raw[ib + (ib / (2 * C::TC)) * 4], dsum);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
                 stage(sidx);
                 __syncthreads();                         // staged source visible, raw area free
                 if (sidx + 1 < nsrc) copy_in(sidx + 1);
@@ -1166,10 +1209,6 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
             }
         }
         // ---- end of a walk: inverse half of phase 2, phase 3, dk
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) dsum += acc[i][j].x;
         if (dk) {
             // constants of the inverse direction are built here, not kept through the walk; nothing
             // below is hoisted out of the parity loop
@@ -1273,7 +1312,7 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
         if (tid == 0) {
             float t = 0.f;
             for (int w = 0; w < C::NW; ++w) t += red[w];
-            dD[h] = t * dDscale;
+            dD[h] = t;
         }
     }
 }
@@ -1284,15 +1323,15 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
 // the workgroup of (head, chunk k1) walks the head's row pairs: u pair -> pass A, phase 1, forward half of
 // phase 2 -> Z (fp16, parked in LDS beside the slots); dy pair likewise -> W; A += conj(Z) W in fp32
 // registers, eight phase-2 tiles per wave.  Then the inverse half of phase 2 and phase 3 give chunk k1 of pass
-// C's input (fp16 complex, unit-stride runs), and the accumulators' real parts this chunk's share of dD.
+// C's input (fp16 complex, unit-stride runs).  dD is the plain fp32 dot product of the rows (chunk 0's workgroup).
 // Every chunk's workgroup reads the whole rows: 2^LR reads of u and dy through L2 (LR = 4: 1 GB per launch at
 // N = 131072, B = 1, which is what bounds that case).
 // -------------------------------------------------------------------------------------
 template <int LG, class IO, int LR>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
-                    __half2* __restrict__ ws_A, float* __restrict__ dD_part, int64_t B, int64_t H, int64_t N,
-                    int npairs, float dDscale, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
+                    __half2* __restrict__ ws_A, float* __restrict__ dD, int64_t B, int64_t H, int64_t N,
+                    int npairs, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
     using T = typename IO::T;
@@ -1326,6 +1365,36 @@ coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
     staged_tables<LG, NT>(lds4, gtab, tw, tid, 0);
     __syncthreads();
     twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);
+
+    // dD[h] = sum over the head's rows of dy u, in fp32, by the workgroup of chunk 0 (its siblings pull the same
+    // rows through this XCD's L2): unit-stride runs of eight samples, exact products, fixed summation order
+    if (dD && k1 == 0) {
+        float dsum = 0.f;
+        const int64_t nrun = N / 8;
+        for (int64_t b = 0; b < B; ++b) {
+            const uint4* qu = reinterpret_cast<const uint4*>(u + row_off(b, h, H, N));
+            const uint4* qd = reinterpret_cast<const uint4*>(dy + row_off(b, h, H, N));
+            for (int64_t i0 = tid; i0 < nrun; i0 += 4 * NT) {
+                uint4 a[4], d[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t i = i0 + q * NT;
+                    if (i < nrun) { a[q] = qu[i]; d[q] = qd[i]; }
+                    else { a[q] = make_uint4(0u, 0u, 0u, 0u); d[q] = a[q]; }
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) dsum = run_dot<IO>(a[q], d[q], dsum);
+            }
+        }
+        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+        if (lane == 0) red[wave] = dsum;
+        __syncthreads();
+        if (tid == 0) {
+            float t = 0.f;
+            for (int w = 0; w < C::NW; ++w) t += red[w];
+            dD[h] = t;
+        }
+    }
 
     const int t0 = wave * 8;                             // this wave's tiles in every phase
     float2 acc[8][4];
@@ -1375,21 +1444,7 @@ coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
         }
     }
 
-    float dsum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) dsum += acc[i][j].x;
-    if (dD_part) {
-        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
-        if (lane == 0) red[wave] = dsum;
-    }
     __syncthreads();                                     // every wave is done reading the slots
-    if (dD_part && tid == 0) {
-        float t = 0.f;
-        for (int w = 0; w < C::NW; ++w) t += red[w];
-        dD_part[((size_t)h << LR) + k1] = t * dDscale;
-    }
     if (!ws_A) return;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -1875,12 +1930,11 @@ hipError_t coop_dk_real_go(const void* dy, const void* u, float* dk, float* dD, 
     const int shift = 6 + (C::te >= 2 ? 1 : 0);      // three radix-16 stages (1/4 each) and F_TE
     // two forward chains and one inverse chain, each scaled by 2^-shift; 1 / padded length
     const float dkscale = (float)(int64_t(1) << (3 * shift)) / (float)(2 * pr.N);
-    const float dDscale = dkscale / (float)(1 << shift);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_dk_real_kernel<LG, IO, SPLIT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((coop_dk_real_kernel<LG, IO, SPLIT>), dim3((unsigned)pr.H), dim3(C::NW * 64), lds, st,
-                       (const T*)dy, (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, dkscale, dDscale, tb.tw,
+                       (const T*)dy, (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, dkscale, tb.tw,
                        (const unsigned char*)tb.ctab);
     return hipGetLastError();
 }
@@ -1889,7 +1943,7 @@ hipError_t coop_dk_real_go(const void* dy, const void* u, float* dk, float* dD, 
 // as outer radix 2^(log2R+1) around 16384 points, whose accumulators fit one walk.  Returns the scale pass C has to
 // apply (two forward chains and one inverse chain of the 16384-point transform, 1 / padded length).
 template <class IO, int LR>
-hipError_t coop_dk_rows_go(const void* dy, const void* u, __half2* ws_A, float* dD_part, const Problem& pr,
+hipError_t coop_dk_rows_go(const void* dy, const void* u, __half2* ws_A, float* dD, const Problem& pr,
                            const Tables& tb, hipStream_t st, float* scale_c)
 {
     constexpr int LG = COOP_MAX_LOG2 - 1;
@@ -1903,8 +1957,8 @@ hipError_t coop_dk_rows_go(const void* dy, const void* u, __half2* ws_A, float* 
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((coop_dk_rows_kernel<LG, IO, LR>), dim3((unsigned)(pr.H << LR)), dim3(C::NW * 64), lds, st,
-                       (const T*)dy, (const T*)u, ws_A, dD_part, pr.B, pr.H, pr.N, pr.npairs,
-                       dkscale / (float)(1 << shift), tb.tw, (const unsigned char*)tb.ctab);
+                       (const T*)dy, (const T*)u, ws_A, dD, pr.B, pr.H, pr.N, pr.npairs, tb.tw,
+                       (const unsigned char*)tb.ctab);
     return hipGetLastError();
 }
 
@@ -1993,16 +2047,16 @@ hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, const __
     return hipErrorInvalidValue;
 }
 
-hipError_t coop_dk_rows(const void* dy, const void* u, __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl,
+hipError_t coop_dk_rows(const void* dy, const void* u, __half2* ws_A, float* dD, const Problem& pr, const Plan& pl,
                         const Tables& tb, hipStream_t st, float* scale_c)
 {
     if (!coop_dk_rows_ok(pl)) return hipErrorInvalidValue;
     if (pl.log2R == 2) {
-        if (pr.io == LONGCONV_F16) return coop_dk_rows_go<IoF16, 3>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
-        if (pr.io == LONGCONV_BF16) return coop_dk_rows_go<IoBF16, 3>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
+        if (pr.io == LONGCONV_F16) return coop_dk_rows_go<IoF16, 3>(dy, u, ws_A, dD, pr, tb, st, scale_c);
+        if (pr.io == LONGCONV_BF16) return coop_dk_rows_go<IoBF16, 3>(dy, u, ws_A, dD, pr, tb, st, scale_c);
     } else {
-        if (pr.io == LONGCONV_F16) return coop_dk_rows_go<IoF16, 4>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
-        if (pr.io == LONGCONV_BF16) return coop_dk_rows_go<IoBF16, 4>(dy, u, ws_A, dD_part, pr, tb, st, scale_c);
+        if (pr.io == LONGCONV_F16) return coop_dk_rows_go<IoF16, 4>(dy, u, ws_A, dD, pr, tb, st, scale_c);
+        if (pr.io == LONGCONV_BF16) return coop_dk_rows_go<IoBF16, 4>(dy, u, ws_A, dD, pr, tb, st, scale_c);
     }
     return hipErrorInvalidValue;
 }

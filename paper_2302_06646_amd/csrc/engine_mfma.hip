@@ -565,6 +565,12 @@ hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __
 {
     if (pl.order.wave_lg) return wave_dk(dy, u, dk, dD, pr, pl, tb, st);
     if (pl.order.coop_lg) return coop_dk(dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, zbuf, pr, pl, tb, st);
+    if (pl.log2R == 0 && dD) {
+        // single pass of the in-place staged kernel: dD as the plain dot product of the rows
+        hipError_t e = head_dot(dy, u, dD, pr, st);
+        if (e != hipSuccess || !dk) return e;
+        dD = nullptr;
+    }
     if (pr.io == LONGCONV_F16) {
         LC_LG_SWITCH(dk_go, IoF16, dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, pr, pl, tb, st)
     }

@@ -492,6 +492,29 @@ struct In {
     uint32_t wa[4][TPW / 2], wb[4][TPW / 2];
 };
 
+// s + dot product of the raw words of two register sets (I/O dtype, two samples per word): exact fp16 / bf16
+// products, fp32 sum (v_dot2c_f32_f16 / v_dot2c_f32_bf16).  This is dD's definition in the time domain.
+template <class IO, int TPW>
+__device__ __forceinline__ float raw_dot(const In<TPW>& a, const In<TPW>& b, float s)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < TPW / 2; ++i) {
+            union { uint32_t u; h2 h; bf2 b; } xa, xb, ya, yb;
+            xa.u = a.wa[j][i]; ya.u = b.wa[j][i];
+            xb.u = a.wb[j][i]; yb.u = b.wb[j][i];
+            if (IsBf<IO>::v) {
+                s = __builtin_amdgcn_fdot2_f32_bf16(xa.b, ya.b, s, false);
+                s = __builtin_amdgcn_fdot2_f32_bf16(xb.b, yb.b, s, false);
+            } else {
+                s = __builtin_amdgcn_fdot2(xa.h, ya.h, s, false);
+                s = __builtin_amdgcn_fdot2(xb.h, yb.h, s, false);
+            }
+        }
+    return s;
+}
+
 
 // Phase 1 on the wave's TPW tiles, advanced together stage by stage: [A-role F16 over d_a],
 // w_L twiddle, [B-role per-tile matrix over d_b] -> exchange buffer (one 16-byte write per tile).
@@ -608,12 +631,13 @@ __device__ __forceinline__ void w_phase3_tile(const uint32_t* xb, const WK<LG, T
 // own TPW phase-2 tiles.  The groups' partial A are summed through LDS in a fixed order (bitwise
 // repeatable), group 0 runs the inverse of phase 2 on the total, and phase 3 (real part = dk; the
 // cross terms between the two rows of a pair are purely imaginary) is spread over the groups.
-// dD is the lag-0 correlation, sum_f Re(A_f) / L (Parseval), taken from the fp32 total.
+// dD is the plain dot product of the raw rows (fp32 sum of exact products), taken while both rows of a pair
+// sit in registers; the waves' partial sums are added in wave order (bitwise repeatable).
 // -------------------------------------------------------------------------------------
 template <int LG, class IO, int TPW, int NWV>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(TPW == 2 ? 3 : 2)))
 wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u, float* __restrict__ dk,
-           float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs, float dkscale, float dDscale,
+           float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs, float dkscale,
            const unsigned char* __restrict__ wtab)
 {
     using C = WC<LG>;
@@ -627,7 +651,7 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
     uint32_t* xa = lds + (size_t)(grp * 2 + 0) * C::PAIR_WORDS;      // u pair
     uint32_t* xd = lds + (size_t)(grp * 2 + 1) * C::PAIR_WORDS;      // dy pair
     float2* red = reinterpret_cast<float2*>(lds + (size_t)NGRP * 2 * C::PAIR_WORDS);   // [wave][TPW*4][64]
-    float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWP]
+    float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWV]
     const int h = blockIdx.x;
 
     // rows of pair p of one source; each source's registers are refilled right after its phase 1 has read them,
@@ -661,10 +685,12 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[k][j] = make_float2(0.f, 0.f);
 
+    float dsum = 0.f;
     const int niter = (npairs + NGRP - 1) / NGRP;      // same for every group: barriers stay uniform
     for (int it = 0; it < niter; ++it) {
         const bool act = it * NGRP + grp < npairs;
         const int pnext = (it + 1) * NGRP + grp;
+        if (act) dsum = raw_dot<IO, TPW>(inu, ind, dsum);    // both raw rows of the pair are in registers here
         if (act) w_phase1<LG, IO, TPW>(inu, xa, K, t0, lane);
         if (pnext < npairs) load_src(pnext, u, inu);
         pair_sync<NWP>();
@@ -702,9 +728,10 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
     for (int k = 0; k < TPW; ++k)
 #pragma unroll
         for (int j = 0; j < 4; ++j) red[((size_t)(wave * TPW + k) * 4 + j) * 64 + lane] = acc[k][j];
+    for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+    if (lane == 0) dred[wave] = dsum;
     __syncthreads();
     if (grp == 0) {
-        float dsum = 0.f;
 #pragma unroll
         for (int k = 0; k < TPW; ++k)
 #pragma unroll
@@ -716,10 +743,7 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
                     s.x += v.x; s.y += v.y;
                 }
                 acc[k][j] = s;
-                dsum += s.x;
             }
-        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
-        if (lane == 0) dred[wave] = dsum;
         if (dk) {     // inverse of phase 2 into group 0's first exchange buffer
 #pragma unroll
             for (int k = 0; k < TPW; ++k) {
@@ -735,8 +759,8 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
     __syncthreads();
     if (tid == 0 && dD) {
         float t = 0.f;
-        for (int w = 0; w < NWP; ++w) t += dred[w];
-        dD[h] = t * dDscale;
+        for (int w = 0; w < NWV; ++w) t += dred[w];
+        dD[h] = t;
     }
     if (dk) {
 #pragma unroll
@@ -764,11 +788,8 @@ hipError_t wdk_go(const void* dy, const void* u, float* dk, float* dD, const Pro
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wdk_kernel<LG, IO, TPW, NWV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    // forward chains scale by c = 2^-shift each: A carries c^2, dk's inverse chain another c
-    int shift = 4 + (C::cb == 4 ? 2 : (C::cb >= 2 ? 1 : 0));
-    const float dDscale = pl.dkscale / (float)(1 << shift);
     hipLaunchKernelGGL((wdk_kernel<LG, IO, TPW, NWV>), dim3((unsigned)pr.H), dim3(NWV * 64), lds, st, (const T*)dy,
-                       (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, pl.dkscale, dDscale,
+                       (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, pl.dkscale,
                        (const unsigned char*)tb.wtab);
     return hipGetLastError();
 }
@@ -799,7 +820,7 @@ template <int LG, class IO, int TPW, int NWV>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
             const float2* __restrict__ kspec, typename IO::T* __restrict__ du, float* __restrict__ dk,
-            float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs, float dkscale, float dDscale,
+            float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs, float dkscale,
             const unsigned char* __restrict__ wtab)
 {
     using C = WC<LG>;
@@ -819,7 +840,7 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
     uint32_t* stg0 = lds + (size_t)NGRP * 3 * C::PAIR_WORDS + (size_t)(grp * 2 + 0) * STW;
     uint32_t* stg1 = stg0 + STW;
     float2* red = reinterpret_cast<float2*>(lds + (size_t)NGRP * (3 * C::PAIR_WORDS + 2 * STW));   // [wave][TPW*4][64]
-    float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWP]
+    float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWV]
     const int h = blockIdx.x;
 
     auto load_src = [&](int p, const typename IO::T* src, In<TPW>& in) {
@@ -871,11 +892,13 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
         const uint4 v = *reinterpret_cast<const uint4*>(((itf & 1) ? stg1 : stg0) + 4 * gl);
         *reinterpret_cast<uint4*>(du + row_off(b0, h, H, N) + n) = v;
     };
+    float dsum = 0.f;                                  // dD: dot product of the raw rows, fp32
     const int niter = (npairs + NGRP - 1) / NGRP;      // same for every group: barriers stay uniform
     for (int it = 0; it < niter; ++it) {
         const int p = it * NGRP + grp, pnext = p + NGRP;
         const bool act = p < npairs;
         uint32_t* xd = (it & 1) ? xd1 : xd0;
+        if (act) dsum = raw_dot<IO, TPW>(inu, ind, dsum);    // both raw rows of the pair are in registers here
         if (act) w_phase1<LG, IO, TPW>(ind, xd, K, t0, lane);
         if (pnext < npairs) load_src(pnext, dy, ind);
         pair_sync<NWP>();
@@ -929,10 +952,11 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
     for (int k = 0; k < TPW; ++k)
 #pragma unroll
         for (int j = 0; j < 4; ++j) red[((size_t)(wave * TPW + k) * 4 + j) * 64 + lane] = acc[k][j];
+    for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
+    if (lane == 0) dred[wave] = dsum;
     __syncthreads();
     flush_du(niter - 1);
     if (grp == 0) {
-        float dsum = 0.f;
 #pragma unroll
         for (int k = 0; k < TPW; ++k)
 #pragma unroll
@@ -944,10 +968,7 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
                     sum.x += v.x; sum.y += v.y;
                 }
                 acc[k][j] = sum;
-                dsum += sum.x;
             }
-        for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
-        if (lane == 0) dred[wave] = dsum;
         if (dk) {     // inverse of phase 2 into group 0's first exchange buffer
 #pragma unroll
             for (int k = 0; k < TPW; ++k) {
@@ -963,8 +984,8 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
     __syncthreads();
     if (tid == 0 && dD) {
         float t = 0.f;
-        for (int w2 = 0; w2 < NWP; ++w2) t += dred[w2];
-        dD[h] = t * dDscale;
+        for (int w2 = 0; w2 < NWV; ++w2) t += dred[w2];
+        dD[h] = t;
     }
     if (dk) {
 #pragma unroll
@@ -992,10 +1013,8 @@ hipError_t wbwd_go(const void* dy, const void* u, const float2* kspec, void* du,
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wbwd_kernel<LG, IO, TPW, NWV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    int shift = 4 + (C::cb == 4 ? 2 : (C::cb >= 2 ? 1 : 0));
-    const float dDscale = pl.dkscale / (float)(1 << shift);
     hipLaunchKernelGGL((wbwd_kernel<LG, IO, TPW, NWV>), dim3((unsigned)pr.H), dim3(NWV * 64), lds, st, (const T*)dy,
-                       (const T*)u, kspec, (T*)du, dk, dD, pr.B, pr.H, pr.N, pr.npairs, pl.dkscale, dDscale,
+                       (const T*)u, kspec, (T*)du, dk, dD, pr.B, pr.H, pr.N, pr.npairs, pl.dkscale,
                        (const unsigned char*)tb.wtab);
     return hipGetLastError();
 }

@@ -39,11 +39,10 @@ hipError_t head_max(const float* k, float* mx, int64_t H, int64_t N, hipStream_t
 int outer_fwd_blocks_per_head(const Problem& pr, int log2L2);
 // Pass C: rows of `out` <- scale * sum_{k1} conj(w_R^(n1*k1) w_L^(n2*k1)) ws[...], n1 < R/2 only
 // (truncation to the first N samples); re -> row 2p, im -> row 2p+1.
-// dD_part (optional, only with pr.npairs == 1, i.e. rows = heads): dD[h] = sum of dD_part[h * npart + i] is
-// taken along in the same launch.
 hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
-                     bool ws_f16, const float2* tw, hipStream_t st, const float* dD_part = nullptr,
-                     float* dD = nullptr, int npart = 0);
+                     bool ws_f16, const float2* tw, hipStream_t st);
+// dD[h] = sum_b sum_t dy[b,h,t] u[b,h,t], plain fp32 dot product (one workgroup per head).
+hipError_t head_dot(const void* dy, const void* u, float* dD, const Problem& pr, hipStream_t st);
 // dD[h] = sum of the per-block partials written by outer_fwd.
 hipError_t reduce_dD(const float* part, float* dD, int64_t H, int nblk, hipStream_t st);
 
@@ -97,12 +96,12 @@ hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws
                      const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st);
 // Multi-pass dk straight from the rows, for plans of outer radix 4 or 8 around 32768 points with pl.fuse_a: run as
 // outer radix 8 or 16 around 16384 points.  ws_A (null: dD only) receives pass C's input for that split (log2R + 1,
-// log2L2 - 1), dD_part[h * 2R + k1] the chunks' shares of dD, *scale_c the factor pass C applies.
+// log2L2 - 1), dD (may be null) the heads' dot products, *scale_c the factor pass C applies.
 inline bool coop_dk_rows_ok(const Plan& pl)
 {
     return pl.fuse_a && (pl.log2R == 2 || pl.log2R == 3) && pl.log2L2 == COOP_MAX_LOG2;
 }
-hipError_t coop_dk_rows(const void* dy, const void* u, __half2* ws_A, float* dD_part, const Problem& pr, const Plan& pl,
+hipError_t coop_dk_rows(const void* dy, const void* u, __half2* ws_A, float* dD, const Problem& pr, const Plan& pl,
                         const Tables& tb, hipStream_t st, float* scale_c);
 // ws: pass-A output of the pre-scaled kernel (multi-pass plans only).
 hipError_t coop_kspec(const float* k, const __half2* ws, const float* D, const float* rs, float2* kspec, int64_t H,

@@ -32,8 +32,10 @@ __global__ void outer_fwd_kernel(const typename IO::T* __restrict__ in, const ty
     __shared__ float red[OB / 64];
     const int L2 = 1 << log2L2;
     const int log2L = log2L2 + LOG2R;
-    const int n2 = blockIdx.x * OB + threadIdx.x;
-    const int pairidx = blockIdx.y;
+    // grid.x = (head, pair, block of columns), the column block fastest
+    const int nbx = L2 / OB, bx = blockIdx.x % nbx;
+    const int n2 = bx * OB + threadIdx.x;
+    const int pairidx = blockIdx.x / nbx;
     const int h = pairidx / npairs, p = pairidx % npairs;
     const bool has_b = (2 * p + 1) < B;
     const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
@@ -74,7 +76,7 @@ __global__ void outer_fwd_kernel(const typename IO::T* __restrict__ in, const ty
         if (threadIdx.x == 0) {
             float t = 0.f;
             for (int w = 0; w < OB / 64; ++w) t += red[w];
-            dD_part[(size_t)pairidx * gridDim.x + blockIdx.x] = t;
+            dD_part[blockIdx.x] = t;        // = (pairidx, bx): a head's partials are consecutive
         }
     }
 }
@@ -87,8 +89,9 @@ __global__ void outer_inv_kernel(const typename CW::T* __restrict__ ws, typename
     constexpr int R = 1 << LOG2R, RH = R / 2;
     const int L2 = 1 << log2L2;
     const int log2L = log2L2 + LOG2R;
-    const int n2 = blockIdx.x * OB + threadIdx.x;
-    const int pairidx = blockIdx.y;
+    const int nbx = L2 / OB;
+    const int n2 = (blockIdx.x % nbx) * OB + threadIdx.x;
+    const int pairidx = blockIdx.x / nbx;
     const int h = pairidx / npairs, p = pairidx % npairs;
     const bool has_b = (2 * p + 1) < B;
     const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
@@ -153,24 +156,16 @@ template <class IO, int LOG2R>
 __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restrict__ ws,
                                                         typename IO::T* __restrict__ out, int64_t B, int64_t H,
                                                         int64_t N, int npairs, int log2L2, float scale,
-                                                        const float2* __restrict__ tw,
-                                                        const float* __restrict__ dD_part, float* __restrict__ dD,
-                                                        int npart)
+                                                        const float2* __restrict__ tw)
 {
     static_assert(LOG2R >= 1 && LOG2R <= 4, "the roots of unity of rot16");
-    // rider for the dk path (rows = heads): one lane per head also adds up the head's dD partials, in index
-    // order, which saves a launch of a few microseconds
-    if (dD_part && blockIdx.x == 0 && threadIdx.x == 0) {
-        float t = 0.f;
-        for (int i = 0; i < npart; ++i) t += dD_part[(size_t)blockIdx.y * npart + i];
-        dD[blockIdx.y] = t;
-    }
     constexpr int R = 1 << LOG2R, RH = R / 2;
     constexpr int VEC = inv4_columns(LOG2R);             // columns per thread (radix 16: two, for the registers)
     const int L2 = 1 << log2L2;
     const int log2L = log2L2 + LOG2R;
-    const int n2 = (blockIdx.x * OB + threadIdx.x) * VEC;
-    const int pairidx = blockIdx.y;
+    const int nbx = L2 / (VEC * OB);
+    const int n2 = ((blockIdx.x % nbx) * OB + threadIdx.x) * VEC;
+    const int pairidx = blockIdx.x / nbx;
     const int h = pairidx / npairs, p = pairidx % npairs;
     const bool has_b = (2 * p + 1) < B;
     const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
@@ -248,13 +243,36 @@ __global__ void reduce_dD_kernel(const float* __restrict__ part, float* __restri
     dD[h] = t;
 }
 
+// dD[h] = sum_b sum_t dy[b,h,t] u[b,h,t]: the plain dot product in fp32, one workgroup per head, fixed order.
+template <class IO>
+__global__ void __launch_bounds__(OB) head_dot_kernel(const typename IO::T* __restrict__ dy,
+                                                      const typename IO::T* __restrict__ u, float* __restrict__ dD,
+                                                      int64_t B, int64_t H, int64_t N)
+{
+    __shared__ float red[OB / 64];
+    const int64_t h = blockIdx.x;
+    float s = 0.f;
+    for (int64_t b = 0; b < B; ++b) {
+        const size_t o = row_off(b, h, H, N);
+        for (int64_t t = threadIdx.x; t < N; t += OB) s = __builtin_fmaf(IO::ld(dy, o + t), IO::ld(u, o + t), s);
+    }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int w = 0; w < OB / 64; ++w) t += red[w];
+        dD[h] = t;
+    }
+}
+
 template <class IO, class CW, int LOG2R>
 hipError_t fwd_launch(const void* in, const void* in2, void* ws, void* ws2, float* dD_part, const Problem& pr,
                       int log2L2, float scale, const float2* tw, hipStream_t st, const float* hs)
 {
     using T = typename IO::T;
     using C = typename CW::T;
-    dim3 grid((1u << log2L2) / OB, (unsigned)(pr.npairs * pr.H));
+    dim3 grid((unsigned)(((size_t)1 << log2L2) / OB * (size_t)pr.npairs * (size_t)pr.H));
     if (in2)
         hipLaunchKernelGGL((outer_fwd_kernel<IO, CW, LOG2R, true>), grid, dim3(OB), 0, st, (const T*)in,
                            (const T*)in2, (C*)ws, (C*)ws2, dD_part, pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw, hs);
@@ -267,23 +285,20 @@ hipError_t fwd_launch(const void* in, const void* in2, void* ws, void* ws2, floa
 
 template <class IO, class CW, int LOG2R>
 hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, float scale, const float2* tw,
-                      hipStream_t st, const float* dD_part, float* dD, int npart)
+                      hipStream_t st)
 {
     using T = typename IO::T;
     using C = typename CW::T;
     if constexpr (std::is_same<CW, CwF16>::value && LOG2R <= 4) {
         constexpr int VEC = inv4_columns(LOG2R);
         if ((1 << log2L2) >= VEC * OB) {
-            dim3 grid4((1u << log2L2) / (VEC * OB), (unsigned)(pr.npairs * pr.H));
+            dim3 grid4((unsigned)(((size_t)1 << log2L2) / (VEC * OB) * (size_t)pr.npairs * (size_t)pr.H));
             hipLaunchKernelGGL((outer_inv4_kernel<IO, LOG2R>), grid4, dim3(OB), 0, st, (const __half2*)ws, (T*)out,
-                               pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw, dD_part, dD, npart);
+                               pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw);
             return hipGetLastError();
         }
     }
-    if (dD_part)     // the plain kernel has no rider
-        hipLaunchKernelGGL(reduce_dD_kernel, dim3((unsigned)((pr.H + 127) / 128)), dim3(128), 0, st, dD_part, dD, pr.H,
-                           npart);
-    dim3 grid((1u << log2L2) / OB, (unsigned)(pr.npairs * pr.H));
+    dim3 grid((unsigned)(((size_t)1 << log2L2) / OB * (size_t)pr.npairs * (size_t)pr.H));
     hipLaunchKernelGGL((outer_inv_kernel<IO, CW, LOG2R>), grid, dim3(OB), 0, st, (const C*)ws, (T*)out, pr.B,
                        pr.H, pr.N, pr.npairs, log2L2, scale, tw);
     return hipGetLastError();
@@ -309,9 +324,9 @@ hipError_t fwd_r(const void* in, const void* in2, void* ws, void* ws2, float* dD
 }
 template <class IO, class CW>
 hipError_t inv_r(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
-                 const float2* tw, hipStream_t st, const float* dD_part, float* dD, int npart)
+                 const float2* tw, hipStream_t st)
 {
-#define CALL(LR) inv_launch<IO, CW, LR>(ws, out, pr, log2L2, scale, tw, st, dD_part, dD, npart)
+#define CALL(LR) inv_launch<IO, CW, LR>(ws, out, pr, log2L2, scale, tw, st)
     LC_R_SWITCH(CALL)
 #undef CALL
 }
@@ -339,11 +354,10 @@ hipError_t outer_fwd(const void* in, const void* in2, void* ws, void* ws2, float
 }
 
 hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
-                     bool ws_f16, const float2* tw, hipStream_t st, const float* dD_part, float* dD, int npart)
+                     bool ws_f16, const float2* tw, hipStream_t st)
 {
     if ((1 << log2L2) < OB) return hipErrorInvalidValue;
-    if (dD_part && pr.npairs != 1) return hipErrorInvalidValue;     // the rider takes rows for heads
-#define GO(IO, CW) return inv_r<IO, CW>(ws, out, pr, log2R, log2L2, scale, tw, st, dD_part, dD, npart)
+#define GO(IO, CW) return inv_r<IO, CW>(ws, out, pr, log2R, log2L2, scale, tw, st)
     if (ws_f16) {
         if (pr.io == LONGCONV_F32) GO(IoF32, CwF16);
         if (pr.io == LONGCONV_F16) GO(IoF16, CwF16);
@@ -361,6 +375,18 @@ hipError_t head_max(const float* k, float* mx, int64_t H, int64_t N, hipStream_t
     hipLaunchKernelGGL(head_max_zero_kernel, dim3((unsigned)((H + 255) / 256)), dim3(256), 0, st, (unsigned*)mx, H);
     hipLaunchKernelGGL(head_max_kernel, dim3((unsigned)((N + 4095) / 4096), (unsigned)H), dim3(256), 0, st, k,
                        (unsigned*)mx, N);
+    return hipGetLastError();
+}
+
+hipError_t head_dot(const void* dy, const void* u, float* dD, const Problem& pr, hipStream_t st)
+{
+    const dim3 grid((unsigned)pr.H), blk(OB);
+    if (pr.io == LONGCONV_F32)
+        hipLaunchKernelGGL(head_dot_kernel<IoF32>, grid, blk, 0, st, (const float*)dy, (const float*)u, dD, pr.B, pr.H, pr.N);
+    else if (pr.io == LONGCONV_F16)
+        hipLaunchKernelGGL(head_dot_kernel<IoF16>, grid, blk, 0, st, (const __half*)dy, (const __half*)u, dD, pr.B, pr.H, pr.N);
+    else
+        hipLaunchKernelGGL(head_dot_kernel<IoBF16>, grid, blk, 0, st, (const uint16_t*)dy, (const uint16_t*)u, dD, pr.B, pr.H, pr.N);
     return hipGetLastError();
 }
 

@@ -30,13 +30,11 @@ def _w(key, **kw):
 @pytest.mark.parametrize("io", [wl.F16, wl.BF16])
 @pytest.mark.parametrize("N", [256, 512, 1024, 2048, 4096, 8192, 16384])
 def test_every_single_pass_length_half_io_odd_batch(N, io):
-    # one case per kernel family and tile count; B = 3 leaves the last row pair half empty.  dD has one number
-    # per head, each a sum of B N products of random sign: with two heads its relative L2 error is the luck of
-    # two magnitudes (absolute error 0.04 against |dD| of 76 rms but sometimes below 10 at N = 2048, measured
-    # over 64 heads: 5.6e-4 relative for the whole vector), so the short lengths use twelve heads
+    # one case per kernel family and tile count; B = 3 leaves the last row pair half empty; two heads only, so
+    # that dD (one number per head, a sum of B N products of random sign that can come out small) is held to
+    # its definition: the fp32 dot product of the raw rows, not a by-product of the rounded transforms
     from gpu_harness import check_full
-    check_full(wl.generate(_w("2", N=N, dtype=io), B=3, H=12 if N <= 4096 else 2),
-               label=f"N={N} io={wl.DTYPE_NAMES[io]}")
+    check_full(wl.generate(_w("2", N=N, dtype=io), B=3, H=2), label=f"N={N} io={wl.DTYPE_NAMES[io]}")
 
 
 @pytest.mark.parametrize("io", [wl.F16, wl.BF16])
@@ -73,7 +71,7 @@ def test_kernel_magnitudes_per_head(key, B, H):
             print(f"[magnitude] {inp.w.name} head {h} scale {scale[h]:g}: y={ey:.2e} du={edu:.2e}", flush=True)
             assert ey <= tol and edu <= tol
         assert wl.rel_l2(dk[h], rdk[h]) <= tol       # dk does not depend on k: same accuracy for every head
-    assert wl.rel_l2(dD, rdD) <= tol                 # (a single head's dD is a sum with heavy cancellation)
+    assert wl.rel_l2(dD, rdD) <= 1e-5                # dD: fp32 dot product of the rows on every path
 
 
 def test_side_stream_matches_default_stream():
