@@ -2,18 +2,26 @@
 """Benchmark of the long-convolution hot path on one MI355X.
 
 One "step" = one pass of the whole path over one batch of synthetic input, as a training
-step would run it (the kernel changes every step, so its spectrum is recomputed):
+step runs it (the kernel changes every step, so its spectrum is recomputed: "cold spectrum"):
 
     kernel-spectrum precompute  ->  forward  ->  backward (du, dk, dD in one call)
 
-Inputs are resident in HBM before the timed region.  Each step uses the next of several
-distinct buffer sets (more than the 256 MB last-level cache in total) so that reads come from
-HBM rather than from cache.  The timed region is exactly K steps between two events on the launch
-stream; the per-call durations (`segments_ms`, `roofline`) come from a second run of the same K
-steps with an event between the three calls (each event costs a few microseconds of GPU time, so
-it stays out of the timed region).  Prints ONE JSON line.
+Headline workload: B=8, H=256, N=16384, fp16 I/O (the N=16K target configuration); the N=64K
+target (B=1, H=128) and the language-model-width block (B=16, H=768, N=1024, bf16) follow under
+`targets`, each with its own roofline object.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2|3|4a|...] [--no-cpu]
+Inputs are resident in HBM before the timed region.  Each step uses the next of several distinct
+buffer sets (more than twice the 256 MB last-level cache in total) so that reads come from HBM
+rather than from cache.  The timed region is exactly K steps between two events on the launch
+stream.  Further regions, each again K steps between events on the same stream:
+  * per-call durations: an event between the calls of a step (the backward call split into its
+    dk/dD part and its du part where the plan runs them as separate kernels anyway), median and
+    minimum over the K steps;
+  * warm spectrum: forward + backward with the cached spectrum (inference-like / frozen kernel);
+  * cache-hot: the same buffer set every step (labelled as such; never the headline).
+A plain device copy is timed in the same run (copy bandwidth of the box).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3|4a|2|...] [--also 4a,2] [--no-cpu]
 """
 from __future__ import annotations
 
@@ -31,27 +39,49 @@ sys.path.insert(0, ROOT)
 import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 matrix-core peak, published
 CACHE_BYTES = 256 << 20        # last-level (Infinity) cache
-# HBM bytes per launch group measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy kernel
-# of known size: FETCH_SIZE x 2.0 KiB, WRITE_SIZE x 1.0 KiB), summed over the kernels of the group; see
-# profiles/.
 KIB = 1024
-MEASURED_TRAFFIC = {
-    # (backward: one kernel for du, dk and dD)
-    "cfg2_B16_H768_N1024_bf16": {"fwd": (15883.1 * 2 + 24576.0) * KIB, "bwd": (28186.2 * 2 + 27672.0) * KIB},
-    # (the convolution kernels read rows in 64-byte requests, which FETCH_SIZE x 2 over-counts: upper bound;
-    # backward: the dk kernel, then the convolution kernel with the conjugate spectrum)
-    "cfg3_B8_H256_N16384_fp16": {"fwd": (98875.7 * 2 + 65536.0) * KIB,
-                                 "bwd": ((141672.5 + 98870.0) * 2 + 35911.8 + 65536.0) * KIB},
-    # (inner convolution with pass A inside + pass C; backward: dk rows kernel + pass C + dD reduction, then
-    # the convolution with the conjugate spectrum + pass C)
-    "cfg4_B1_H128_N65536_fp16": {"fwd": ((49954.9 + 33050.9) * 2 + 65577.8 + 16384.0) * KIB,
-                                 "bwd": ((18854.9 + 32938.6 + 3.2 + 49963.5 + 33050.9) * 2 + 77826.8 + 32768.0 + 0.5 +
-                                         65563.6 + 16384.0) * KIB},
-}
+# HBM bytes per launch of the dominant kernel group, measured OFFLINE with `rocprofv3 --pmc FETCH_SIZE` and
+# `--pmc WRITE_SIZE` (KiB per dispatch, scaled by what the same counters read for a plain copy of known size:
+# FETCH_SIZE x 2.0, WRITE_SIZE x 1.0) and copied here from the summaries under profiles/; null where no such
+# run covers the group.  Not measured by this script.
+OFFLINE_TRAFFIC = {}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+# ---------------------------------------------------------------------------------------------
+# byte and flop models
+# ---------------------------------------------------------------------------------------------
+def group_bytes(w: wl.Workload):
+    """Algorithmic bytes (user-visible tensors only) of each launch group taken as a unit."""
+    s = wl.DTYPE_BYTES[w.dtype]
+    E = w.B * w.H * w.N
+    hn = 4 * w.H * w.N + 4 * w.H
+    fwd_b, bwd_b = wl.algorithmic_bytes(w.B, w.H, w.N, w.dtype)
+    return {"kspec": 0,                       # its read of k is charged to fwd
+            "fwd": fwd_b,                     # u in, y out, k and D in
+            "bwd": bwd_b,                     # dy, u in; du out; k in, dk out; D in, dD out
+            "bwd_dk": 2 * E * s + hn,         # dy, u in; dk, dD out
+            "bwd_du": 2 * E * s + hn}         # dy in, du out; k, D in
+
+
+def executed_mfma_flops(w: wl.Workload):
+    """Matrix-core flops the kernels issue for one step (model of the factorisation, dense 16x16x32 blocks,
+    two instructions per 16x16 complex tile and stage, 16384 flop each): per 256-point tile a forward or an
+    inverse half transform costs 8 instructions on the cooperative kernels (four stages), 6 on the
+    wave-autonomous ones (three stages).  Half transforms per row pair: forward 2, backward 3 where one kernel
+    serves du, dk and dD (up to 4096 points) else 4; per head: spectrum 1, dk's inverse 1."""
+    if w.dtype == wl.F32:
+        return 0.0
+    L = 2 * w.N
+    npairs = (w.B + 1) // 2
+    per_half = (6 if L <= 4096 else 8) * 16384 * (L / 256)
+    bwd_halves = 3 if L <= 4096 else 4
+    return w.H * (npairs * (2 + bwd_halves) + 2) * per_half
 
 
 class Sets:
@@ -78,62 +108,123 @@ class Sets:
         self.ws = lc.new_workspace(w.B, w.H, w.N, w.dtype, True)
 
 
+def timed(torch, steps, fn):
+    """ms per step of `steps` calls of fn(i) between two events on the launch stream."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(steps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
 def run_workload(key, steps, warmup, lc, torch):
     w = wl.WORKLOADS[key]
     S = Sets(w, lc, torch)
-    ev = lambda: torch.cuda.Event(enable_timing=True)
-    marks = [[ev() for _ in range(4)] for _ in range(steps)]
+    plan = lc.longconv_plan_string(w.N, w.dtype)
+    one_kernel_bwd = "kernel=wave" in plan            # du, dk, dD of a call come from one kernel
+    gb = group_bytes(w)
+    groups = ["kspec", "fwd"] + (["bwd"] if one_kernel_bwd else ["bwd_dk", "bwd_du"])
 
-    def step(i, m=None):
+    def step(i, cold=True):
         j = i % S.nsets
-        if m: m[0].record()
-        lc.longconv_kspec_compute(S.k, S.D, S.kspec, w.dtype, S.ws)
-        if m: m[1].record()
+        if cold:
+            lc.longconv_kspec_compute(S.k, S.D, S.kspec, w.dtype, S.ws)
         lc.longconv_fwd(S.u[j], S.k, S.D, S.y[j], S.ws, kspec=S.kspec)
-        if m: m[2].record()
         lc.longconv_bwd(S.dy[j], S.u[j], S.k, S.D, S.du[j], S.dk, S.dD, S.ws, kspec=S.kspec)
-        if m: m[3].record()
+
+    def step_marked(i, m):
+        j = i % S.nsets
+        m[0].record()
+        lc.longconv_kspec_compute(S.k, S.D, S.kspec, w.dtype, S.ws)
+        m[1].record()
+        lc.longconv_fwd(S.u[j], S.k, S.D, S.y[j], S.ws, kspec=S.kspec)
+        m[2].record()
+        if one_kernel_bwd:
+            lc.longconv_bwd(S.dy[j], S.u[j], S.k, S.D, S.du[j], S.dk, S.dD, S.ws, kspec=S.kspec)
+            m[3].record()
+        else:       # the same kernels the single call launches, with an event between them
+            lc.longconv_bwd(S.dy[j], S.u[j], S.k, S.D, None, S.dk, S.dD, S.ws, kspec=S.kspec)
+            m[3].record()
+            lc.longconv_bwd(S.dy[j], S.u[j], S.k, S.D, S.du[j], None, None, S.ws, kspec=S.kspec)
+            m[4].record()
 
     for i in range(warmup):
         step(i)
-    # timed region: exactly `steps` steps between two events on the launch stream, nothing in between
-    e0, e1 = ev(), ev()
-    torch.cuda.synchronize()
+    # ---- headline region: exactly `steps` cold-spectrum steps, HBM-cold buffers, nothing in between
     t0 = time.perf_counter()
-    e0.record()
-    for i in range(steps):
-        step(warmup + i)
-    e1.record()
-    torch.cuda.synchronize()
+    step_ms = timed(torch, steps, lambda i: step(warmup + i))
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-    step_ms = e0.elapsed_time(e1) / steps
-    # instrumented region: the same steps again with an event between the three calls (each event costs a few
-    # microseconds of GPU time, which is why it is kept out of the timed region); gives the per-launch durations
+    # ---- per-call durations
+    ng = len(groups)
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(ng + 1)] for _ in range(steps)]
     for i in range(steps):
-        step(warmup + steps + i, marks[i])
+        step_marked(warmup + steps + i, marks[i])
     torch.cuda.synchronize()
-    seg = np.array([[m[a].elapsed_time(m[a + 1]) for a in range(3)] for m in marks])   # ms
-    seg_avg = seg.mean(axis=0)
-    fwd_b, bwd_b = wl.algorithmic_bytes(w.B, w.H, w.N, w.dtype)
-    # algorithmic bytes of each call (the spectrum's read of k is already in fwd's figure)
-    seg_bytes = {"kspec": 0, "fwd": fwd_b, "bwd": bwd_b}
-    names = list(seg_bytes)
-    res = {
-        "workload": w.name, "B": w.B, "H": w.H, "N": w.N, "io": wl.DTYPE_NAMES[w.dtype],
-        "plan": lc.longconv_plan_string(w.N, w.dtype), "buffer_sets": S.nsets,
-        "ms_per_step": float(step_ms), "wall_ms_per_step": wall_ms, "ms_per_step_instrumented": float(seg_avg.sum()),
-        "bytes_per_step": fwd_b + bwd_b,
-        "GBps": (fwd_b + bwd_b) / (step_ms * 1e-3) / 1e9,
-        "segments": {n: {"ms": float(seg_avg[i]), "ms_min": float(seg[:, i].min()),
-                         "GBps": (seg_bytes[n] / (seg_avg[i] * 1e-3) / 1e9) if seg_bytes[n] else None}
-                     for i, n in enumerate(names)},
-    }
+    seg = np.array([[m[a].elapsed_time(m[a + 1]) for a in range(ng)] for m in marks])   # ms
+    # ---- warm spectrum (cached), still HBM-cold buffers
+    warm_ms = timed(torch, steps, lambda i: step(i, cold=False))
+    # ---- cache-hot: one buffer set only
+    S_n = S.nsets
+    S.nsets = 1
+    for i in range(3):
+        step(i)
+    hot_ms = timed(torch, steps, lambda i: step(i))
+    S.nsets = S_n
+
+    fwd_b, bwd_b = gb["fwd"], gb["bwd"]
+    tot_b = fwd_b + bwd_b
     ff, bf = wl.algorithmic_flops(w.B, w.H, w.N)
-    res["TFLOPs_algorithmic"] = (ff + bf) / (step_ms * 1e-3) / 1e12
-    res["frac_hbm"] = res["GBps"] / HBM_PEAK_GBS
+    mf = executed_mfma_flops(w)
+    segments = {n: {"ms_mean": float(seg[:, i].mean()), "ms_median": float(np.median(seg[:, i])),
+                    "ms_min": float(seg[:, i].min()), "algorithmic_bytes": gb[n],
+                    "GBps": (gb[n] / (seg[:, i].mean() * 1e-3) / 1e9) if gb[n] else None}
+                for i, n in enumerate(groups)}
+    dom = max((n for n in groups if gb[n]), key=lambda n: segments[n]["ms_mean"])
+    res = {
+        "workload": w.name, "B": w.B, "H": w.H, "N": w.N, "io": wl.DTYPE_NAMES[w.dtype], "plan": plan,
+        "buffer_sets": S.nsets, "steps": steps,
+        "ms_per_step": float(step_ms), "wall_ms_per_step": wall_ms,
+        "ms_per_step_instrumented_mean": float(seg.sum(axis=1).mean()),
+        "ms_per_step_instrumented_median": float(np.median(seg.sum(axis=1))),
+        "ms_per_step_instrumented_min": float(seg.sum(axis=1).min()),
+        "bytes_per_step": tot_b, "GBps": tot_b / (step_ms * 1e-3) / 1e9,
+        "pct_hbm_roofline": 100.0 * tot_b / (step_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "warm_spectrum": {"ms_per_step": float(warm_ms), "GBps": tot_b / (warm_ms * 1e-3) / 1e9,
+                          "pct_hbm_roofline": 100.0 * tot_b / (warm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "cache_hot_same_buffers": {"ms_per_step": float(hot_ms), "GBps": tot_b / (hot_ms * 1e-3) / 1e9,
+                                   "note": "one buffer set reused every step: data served by the last-level cache, not HBM"},
+        "fwd_ms": segments["fwd"]["ms_mean"],
+        "fwd_pct_hbm_roofline": 100.0 * segments["fwd"]["GBps"] / HBM_PEAK_GBS,
+        "segments": segments,
+        "TFLOPs_algorithmic": (ff + bf) / (step_ms * 1e-3) / 1e12,
+        "mfma_executed": {"TFLOPs": mf / (step_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS,
+                          "pct_of_peak": 100.0 * mf / (step_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                          "flops_per_step_model": mf},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": segments[dom]["GBps"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": segments[dom]["GBps"] / HBM_PEAK_GBS,
+                     "traffic": OFFLINE_TRAFFIC.get(w.name, {}).get(dom),
+                     "traffic_source": "offline rocprofv3 --pmc runs, see profiles/" if OFFLINE_TRAFFIC.get(w.name, {}).get(dom) else None,
+                     "algorithmic_bytes_per_launch": gb[dom],
+                     "avg_launch_ms": segments[dom]["ms_mean"]},
+    }
     del S
     torch.cuda.empty_cache()
-    return res, seg_bytes
+    return res
+
+
+def copy_bandwidth(torch, nbytes=1 << 30, reps=10):
+    """Plain device-to-device copy of 1 GiB, read + written bytes per second."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    ms = timed(torch, reps, lambda i: dst.copy_(src))
+    del src, dst
+    torch.cuda.empty_cache()
+    return 2 * nbytes / (ms * 1e-3) / 1e9
 
 
 def cpu_baseline(key):
@@ -142,7 +233,7 @@ def cpu_baseline(key):
     import oracle
     w = wl.WORKLOADS[key]
     macs_per_head = 3 * w.B * w.N * w.N / 2          # fwd + du + dk
-    budget = 15.0 * 10e9                             # about 15 s at ~10 GMAC/s
+    budget = 15.0 * 50e9                             # about 15 s at ~50 GMAC/s
     heads = int(max(1, min(w.H, budget // macs_per_head)))
     inp = wl.generate(w, H=heads)
     k64, D64 = inp.k.astype(np.float64), inp.D.astype(np.float64)
@@ -162,11 +253,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="2", choices=list(wl.WORKLOADS))
-    ap.add_argument("--also", default="3,4a", help="comma list of further workloads reported under 'targets'")
+    ap.add_argument("--workload", default="3", choices=list(wl.WORKLOADS))
+    ap.add_argument("--also", default="4a,2", help="comma list of further workloads reported under 'targets'")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run three plain 64 MiB device copies (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
@@ -178,41 +267,39 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(1)
     lc.longconv_init()
-    if a.copy_probe:
-        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
+    copy_gbs = copy_bandwidth(torch)
 
-    res, seg_bytes = run_workload(a.workload, a.steps, a.warmup, lc, torch)
+    res = run_workload(a.workload, a.steps, a.warmup, lc, torch)
     log(json.dumps(res, indent=1))
-    # dominant kernel = the launch group with the largest share of the step
-    dom = max(("fwd", "bwd"), key=lambda n: res["segments"][n]["ms"])
-    dom_gbps = res["segments"][dom]["GBps"]
+    w = wl.WORKLOADS[a.workload]
     out = {
         "metric": "long-conv fwd+bwd ms, effective GB/s and % HBM roofline at BxHxN",
         "value": res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
+        # arithmetic type of the transforms: fp16 matrix-core operands with fp32 accumulation for fp16 and bf16
+        # I/O (bf16 inputs are converted on load), fp32 for fp32 I/O; the I/O dtype is config.io
+        "dtype": "f32" if w.dtype == wl.F32 else "f16", "data": "synthetic",
         "config": {"workload": res["workload"], "B": res["B"], "H": res["H"], "N": res["N"], "io": res["io"],
-                   "step": "kspec+fwd+bwd(du,dk,dD)", "plan": res["plan"], "buffer_sets": res["buffer_sets"]},
-        "pct_hbm_roofline": 100.0 * res["frac_hbm"],
-        "TFLOPs_algorithmic": res["TFLOPs_algorithmic"],
-        "segments_ms": {n: v["ms"] for n, v in res["segments"].items()},
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbps, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": dom_gbps / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get(res["workload"], {}).get(dom),
-                     "algorithmic_bytes_per_launch": seg_bytes[dom]},
+                   "step": "kspec+fwd+bwd(du,dk,dD), cold spectrum, HBM-cold buffers", "plan": res["plan"],
+                   "buffer_sets": res["buffer_sets"]},
+        "pct_hbm_roofline": res["pct_hbm_roofline"],
+        "pct_of_copy_bandwidth": 100.0 * res["GBps"] / copy_gbs,
+        "copy_bandwidth_GBps": copy_gbs,
+        "ms_per_step_median_instrumented": res["ms_per_step_instrumented_median"],
+        "ms_per_step_min_instrumented": res["ms_per_step_instrumented_min"],
+        "fwd_ms": res["fwd_ms"], "fwd_pct_hbm_roofline": res["fwd_pct_hbm_roofline"],
+        "warm_spectrum": res["warm_spectrum"], "cache_hot_same_buffers": res["cache_hot_same_buffers"],
+        "TFLOPs_algorithmic": res["TFLOPs_algorithmic"], "mfma_executed": res["mfma_executed"],
+        "segments": res["segments"],
+        "roofline": res["roofline"],
     }
     targets = []
     for key in [k for k in a.also.split(",") if k and k != a.workload]:
-        r, _ = run_workload(key, max(10, a.steps // 2), max(3, a.warmup // 2), lc, torch)
+        r = run_workload(key, max(20, a.steps // 2), max(5, a.warmup // 2), lc, torch)
         log(json.dumps(r, indent=1))
-        targets.append({"workload": r["workload"], "ms_per_step": r["ms_per_step"], "GBps": r["GBps"],
-                        "pct_hbm_roofline": 100 * r["frac_hbm"],
-                        "fwd_ms": r["segments"]["fwd"]["ms"],
-                        "fwd_pct_hbm_roofline": 100 * r["segments"]["fwd"]["GBps"] / HBM_PEAK_GBS})
+        targets.append({k: r[k] for k in ("workload", "plan", "steps", "ms_per_step", "GBps", "pct_hbm_roofline", "fwd_ms",
+                                          "fwd_pct_hbm_roofline", "warm_spectrum", "cache_hot_same_buffers", "mfma_executed",
+                                          "segments", "roofline")})
     out["targets"] = targets
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(a.workload)

@@ -22,7 +22,8 @@
  *     dense, row-major, N fastest: u, y, dy, du are [B,H,N] in the I/O dtype;
  *     k, dk are [H,N] float32; D, dD are [H] float32.  Base pointers must be
  *     16-byte aligned.  Outputs must not alias inputs.
- *   - N must be a power of two with 256 <= N <= 131072; B >= 1; H >= 1.
+ *   - N must be a power of two with 256 <= N <= 131072; 1 <= B <= 2^24; 1 <= H <= 65535;
+ *     ceil(B/2) * H <= 2^22.  Anything else returns LONGCONV_ERR_SHAPE before a launch.
  *   - The caller owns every buffer.  The library allocates no per-call device
  *     memory, frees nothing, never synchronises the stream and enqueues work only
  *     on `stream` (a hipStream_t passed as void*; NULL is the default stream).
@@ -73,8 +74,9 @@ int longconv_init(void);
  * permuted order the fused transform produces (Algorithm 2 lines 1-2: the
  * spectrum is computed once and stored already permuted, so no permutation ever
  * touches u).  Layout and element type are private to the library and depend on
- * (N, io): fp32 complex for fp32 I/O, fp16 complex for fp16/bf16 I/O; the size
- * returned is an upper bound (8 bytes per bin). */
+ * (N, io): fp32 complex (8 bytes per bin) for fp32 I/O, fp16 complex (4 bytes per
+ * bin) for fp16/bf16 I/O; the size returned is exact.  Because the skip term is
+ * part of it, a cached spectrum is valid until k OR D changes. */
 size_t longconv_kspec_bytes(int64_t H, int64_t N, int io);
 
 /* Scratch bytes a call needs (0 on bad args).  `backward` = 0 for longconv_fwd,
@@ -108,6 +110,20 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
                  void* du, float* dk, float* dD,
                  int64_t B, int64_t H, int64_t N, int io,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Debug and test switches (process-wide; not needed in normal use).  Each selects among
+ * kernels that compute the same result: "engine" (0 by dtype, 1 fp32 vector-ALU engine,
+ * 2 fp16 matrix-core engine), "inner_log2" (0, or n: cap the on-chip transform at 2^n
+ * points, which forces the multi-pass split), "staged_kernel" (1: first-generation in-place
+ * matrix-core kernel), "fuse_pass_a" (0: outer pass A as a kernel of its own),
+ * "fuse_bwd" (0: du and dk/dD from separate kernels).  The environment variables
+ * LONGCONV_ENGINE=valu|mfma, LONGCONV_INNER_LOG2, LONGCONV_MFMA_KERNEL=staged,
+ * LONGCONV_FUSE_PASS_A, LONGCONV_FUSE_BWD give the initial values and are read once, at
+ * the first library call.  The private layout of a cached spectrum depends on the
+ * switches: do not change them between longconv_kspec_compute and the calls that consume
+ * its result.  Not thread-safe against concurrent compute calls.  Unknown name or bad
+ * value: LONGCONV_ERR_SHAPE. */
+int longconv_set_option(const char* name, int value);
 
 /* Static text for a status code. */
 const char* longconv_status_string(int status);

@@ -8,7 +8,8 @@ the functions raises.
 
 Functions mirror the C ABI of ``include/longconv.h``:
     longconv_init, longconv_kspec_bytes, longconv_workspace_bytes,
-    longconv_kspec_compute, longconv_fwd, longconv_bwd, longconv_plan_string
+    longconv_kspec_compute, longconv_fwd, longconv_bwd, longconv_plan_string,
+    longconv_set_option
 """
 from __future__ import annotations
 
@@ -27,7 +28,7 @@ _lib = None
 
 EXPORTS = ("longconv_init", "longconv_kspec_bytes", "longconv_workspace_bytes",
            "longconv_kspec_compute", "longconv_fwd", "longconv_bwd", "longconv_status_string",
-           "longconv_last_hip_error", "longconv_plan_string")
+           "longconv_last_hip_error", "longconv_plan_string", "longconv_set_option")
 
 
 class LongconvError(RuntimeError):
@@ -59,6 +60,8 @@ def lib():
         L.longconv_last_hip_error.restype = ctypes.c_char_p
         L.longconv_plan_string.restype = ctypes.c_char_p
         L.longconv_plan_string.argtypes = [i64, ci]
+        L.longconv_set_option.restype = ci
+        L.longconv_set_option.argtypes = [ctypes.c_char_p, ci]
         _lib = L
     return _lib
 
@@ -107,6 +110,14 @@ def longconv_workspace_bytes(B: int, H: int, N: int, io: int, backward: bool) ->
 
 def longconv_plan_string(N: int, io: int) -> str:
     return lib().longconv_plan_string(N, io).decode()
+
+
+OPTION_DEFAULTS = {"engine": 0, "inner_log2": 0, "staged_kernel": 0, "fuse_pass_a": 1, "fuse_bwd": 1}
+
+
+def longconv_set_option(name: str, value: int) -> None:
+    """Debug/test switch of the library (see include/longconv.h)."""
+    _check(lib().longconv_set_option(name.encode(), int(value)), f"longconv_set_option({name})")
 
 
 def new_workspace(B, H, N, io, backward, device="cuda"):

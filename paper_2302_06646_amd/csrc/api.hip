@@ -1,6 +1,8 @@
 // C-ABI layer of liblongconv: argument validation, planning, workspace carving, dispatch.
-// Every step of the path runs in the kernels of engine_valu.hip / engine_mfma.hip /
-// multipass.hip; nothing here computes on the host.
+// Every step of the path runs in the kernels of engine_wave.hip (512..4096 points), engine_coop.hip
+// (8192..32768 points, and the inner transforms of longer ones), multipass.hip (outer passes), engine_valu.hip
+// (fp32 I/O) and engine_mfma.hip (first-generation in-place kernel, kept as a cross-check behind a switch and
+// for 256-point inner transforms); nothing here computes on the host.
 #include <atomic>
 #include <cstdio>
 #include <cstdlib>
@@ -93,21 +95,38 @@ static int env_int(const char* name, int dflt)
     return (v && *v) ? atoi(v) : dflt;
 }
 
+// The switches: defaults, overridden once from the environment, then only by longconv_set_option().
+static Options g_opt = {0, 0, 0, 1, 1};
+static std::once_flag g_opt_once;
+static void load_options_from_env()
+{
+    if (const char* e = getenv("LONGCONV_ENGINE")) {
+        if (!strcmp(e, "valu")) g_opt.engine = 1;
+        if (!strcmp(e, "mfma")) g_opt.engine = 2;
+    }
+    g_opt.inner_log2 = env_int("LONGCONV_INNER_LOG2", 0);
+    if (const char* e = getenv("LONGCONV_MFMA_KERNEL")) g_opt.staged = !strcmp(e, "staged");
+    g_opt.fuse_pass_a = env_int("LONGCONV_FUSE_PASS_A", 1) != 0;
+    g_opt.fuse_bwd = env_int("LONGCONV_FUSE_BWD", 1) != 0;
+}
+const Options& options()
+{
+    std::call_once(g_opt_once, load_options_from_env);
+    return g_opt;
+}
+
 // Plan for (N, io).  fp32 I/O runs the fp32 vector-ALU engine; fp16/bf16 I/O runs the fp16
-// matrix-core engine.  Environment overrides (experiments and tests only):
-//   LONGCONV_ENGINE=valu|mfma      force the engine
-//   LONGCONV_INNER_LOG2=<n>        cap the on-chip transform length at 2^n (forces multi-pass)
+// matrix-core engine, unless the debug switches say otherwise.
 Plan make_plan(int64_t N, int io)
 {
+    const Options& opt = options();
     Plan pl{};
     pl.log2L = ilog2(2 * N);
     pl.engine = (io == LONGCONV_F32) ? ENGINE_VALU : ENGINE_MFMA;
-    if (const char* e = getenv("LONGCONV_ENGINE")) {
-        if (!strcmp(e, "valu")) pl.engine = ENGINE_VALU;
-        if (!strcmp(e, "mfma") && io != LONGCONV_F32) pl.engine = ENGINE_MFMA;
-    }
+    if (opt.engine == 1) pl.engine = ENGINE_VALU;
+    if (opt.engine == 2 && io != LONGCONV_F32) pl.engine = ENGINE_MFMA;
     int cap = pl.engine == ENGINE_VALU ? VALU_INNER_MAX_LOG2 : MFMA_INNER_MAX_LOG2;
-    const int forced = env_int("LONGCONV_INNER_LOG2", 0);
+    const int forced = opt.inner_log2;
     if (forced >= 8 && forced < cap) cap = forced;
     pl.log2L2 = pl.log2L < cap ? pl.log2L : cap;
     pl.log2R = pl.log2L - pl.log2L2;
@@ -129,6 +148,11 @@ Plan make_plan(int64_t N, int io)
 }
 
 static size_t cw_bytes(const Plan& pl) { return pl.engine == ENGINE_VALU ? sizeof(float2) : sizeof(__half2); }
+// bytes per stored spectrum bin: fp16 complex for the wave and cooperative matrix-core kernels, fp32 complex otherwise
+static size_t spec_bytes(const Plan& pl)
+{
+    return (pl.engine == ENGINE_MFMA && (pl.order.wave_lg || pl.order.coop_lg)) ? sizeof(__half2) : sizeof(float2);
+}
 static size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 
 struct WsLayout {
@@ -142,8 +166,11 @@ static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool back
     const size_t L = size_t(1) << pl.log2L;
     const size_t npairs = (size_t)((B + 1) / 2);
     size_t off = 0;
-    w.kspec = off; off += up256((size_t)H * L * sizeof(float2));
-    w.kscratch = off; if (pl.log2L > VALU_KSPEC_MAX_LOG2) off += up256((size_t)H * L * sizeof(float2));
+    w.kspec = off; off += up256((size_t)H * L * spec_bytes(pl));
+    // pass-A output of k, for the spectrum routes that run pass A as a kernel of its own
+    const bool mc = pl.engine == ENGINE_MFMA && (pl.order.wave_lg || pl.order.coop_lg);
+    const bool kscr = mc ? (pl.log2R && !pl.fuse_a) : (pl.log2L > VALU_KSPEC_MAX_LOG2);
+    w.kscratch = off; if (kscr) off += up256((size_t)H * L * sizeof(float2));
     w.hscale = off; off += up256((size_t)H * sizeof(float));
     w.ws1 = off; if (pl.log2R) off += up256((size_t)H * npairs * L * cw_bytes(pl));
     w.ws2 = off; if (pl.log2R && backward) off += up256((size_t)H * npairs * L * cw_bytes(pl));
@@ -234,7 +261,7 @@ int longconv_init(void)
 size_t longconv_kspec_bytes(int64_t H, int64_t N, int io)
 {
     if (check_shape(1, H, N, io) != LONGCONV_OK) return 0;
-    return (size_t)H * (size_t)(2 * N) * sizeof(float2);
+    return (size_t)H * (size_t)(2 * N) * spec_bytes(make_plan(N, io));
 }
 
 size_t longconv_workspace_bytes(int64_t B, int64_t H, int64_t N, int io, int backward)
@@ -379,6 +406,19 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
         if (note(run_conv(dy, ks, du, base + w.ws1, true, pr, pl, tb, st, dy_ready), "bwd du") != hipSuccess)
             return LONGCONV_ERR_HIP;
     }
+    return LONGCONV_OK;
+}
+
+int longconv_set_option(const char* name, int value)
+{
+    if (!name) return LONGCONV_ERR_NULL;
+    options();                                   // the environment is read first, once
+    if (!strcmp(name, "engine")) { if (value < 0 || value > 2) return LONGCONV_ERR_SHAPE; g_opt.engine = value; }
+    else if (!strcmp(name, "inner_log2")) { if (value < 0 || value > 31) return LONGCONV_ERR_SHAPE; g_opt.inner_log2 = value; }
+    else if (!strcmp(name, "staged_kernel")) g_opt.staged = value != 0;
+    else if (!strcmp(name, "fuse_pass_a")) g_opt.fuse_pass_a = value != 0;
+    else if (!strcmp(name, "fuse_bwd")) g_opt.fuse_bwd = value != 0;
+    else return LONGCONV_ERR_SHAPE;
     return LONGCONV_OK;
 }
 

@@ -171,6 +171,19 @@ struct Plan {
 
 Plan make_plan(int64_t N, int io);
 
+// Process-wide debug/test switches, read once from the environment (LONGCONV_ENGINE, LONGCONV_INNER_LOG2,
+// LONGCONV_MFMA_KERNEL, LONGCONV_FUSE_PASS_A, LONGCONV_FUSE_BWD) at the first library call and changed afterwards
+// only through longconv_set_option().  They select among equivalent kernels; the plan, and with it the private
+// layout of a cached spectrum, depends on them.
+struct Options {
+    int engine;       // 0: by dtype (default), 1: fp32 vector-ALU engine, 2: fp16 matrix-core engine (half I/O only)
+    int inner_log2;   // 0: default; otherwise cap the on-chip transform length at 2^n (forces the multi-pass split)
+    int staged;       // 1: the in-place staged matrix-core kernel instead of the wave / cooperative kernels
+    int fuse_pass_a;  // 1 (default): pass A of outer radix 4 and 8 inside the inner kernels
+    int fuse_bwd;     // 1 (default): du, dk, dD of one call from one kernel where a plan has one
+};
+const Options& options();
+
 // Row addressing: element (b,h,n) of a [B,H,N] tensor.
 __device__ __forceinline__ size_t row_off(int64_t b, int64_t h, int64_t H, int64_t N)
 {

@@ -526,8 +526,8 @@ void mfma_fill_plan(Plan& pl)
     pl.order.wave_lg = 0;
     pl.order.coop_lg = 0;
     pl.order.outer_bits = pl.log2R;
-    const char* kv = getenv("LONGCONV_MFMA_KERNEL");   // "staged" forces the in-place staged kernel everywhere
-    const bool staged = kv && !strcmp(kv, "staged");
+    const Options& opt = options();
+    const bool staged = opt.staged != 0;           // the in-place staged kernel everywhere (cross-check)
     if (!staged && pl.log2R == 0 && pl.log2L2 >= WAVE_MIN_LOG2 && pl.log2L2 <= WAVE_MAX_LOG2)
         pl.order.wave_lg = pl.log2L2;
     if (!staged && pl.log2L2 >= COOP_MIN_LOG2 && pl.log2L2 <= COOP_MAX_LOG2) pl.order.coop_lg = pl.log2L2;
@@ -541,12 +541,10 @@ void mfma_fill_plan(Plan& pl)
     pl.kscale = 1.0f / (L * c * c);
     pl.dkscale = 1.0f / (L * c * c * c);
     // outer radix 4 or 8 around the 32768-point cooperative kernels: the convolutions take pass A in their
-    // staging (LONGCONV_FUSE_PASS_A=0 keeps the separate pass, for comparison)
-    const char* fa = getenv("LONGCONV_FUSE_PASS_A");
-    pl.fuse_a = pl.order.coop_lg == COOP_MAX_LOG2 && (pl.log2R == 2 || pl.log2R == 3) && !(fa && !strcmp(fa, "0"));
-    // one backward kernel where a wave group holds a head's accumulators (LONGCONV_FUSE_BWD=0: separate kernels)
-    const char* fb = getenv("LONGCONV_FUSE_BWD");
-    pl.fuse_bwd = pl.order.wave_lg && pl.log2R == 0 && !(fb && !strcmp(fb, "0"));
+    // staging (switch fuse_pass_a = 0 keeps the separate pass, for comparison)
+    pl.fuse_a = pl.order.coop_lg == COOP_MAX_LOG2 && (pl.log2R == 2 || pl.log2R == 3) && opt.fuse_pass_a;
+    // one backward kernel where a wave group holds a head's accumulators (switch fuse_bwd = 0: separate kernels)
+    pl.fuse_bwd = pl.order.wave_lg && pl.log2R == 0 && opt.fuse_bwd;
 }
 
 hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,

@@ -43,6 +43,38 @@ def test_sizes_and_plan():
     assert lc.longconv_plan_string(100, lc.F32) == "invalid"
 
 
+def test_spectrum_size_is_exact_per_dtype():
+    # fp32 I/O stores fp32 complex bins, half I/O fp16 complex bins (matrix-core kernels)
+    assert lc.longconv_kspec_bytes(3, 2048, lc.F32) == 3 * 4096 * 8
+    for io in (lc.F16, lc.BF16):
+        for N in (256, 1024, 16384, 65536):
+            assert lc.longconv_kspec_bytes(3, N, io) == 3 * 2 * N * 4
+
+
+def test_options_switch_plans_and_reject_bad_input():
+    try:
+        assert "kernel=wave" in lc.longconv_plan_string(1024, lc.F16)
+        lc.longconv_set_option("staged_kernel", 1)
+        assert "kernel=" not in lc.longconv_plan_string(1024, lc.F16)
+        assert lc.longconv_kspec_bytes(3, 1024, lc.F16) == 3 * 2048 * 8       # that kernel keeps fp32 bins
+        lc.longconv_set_option("staged_kernel", 0)
+        lc.longconv_set_option("inner_log2", 9)
+        assert "passes=3" in lc.longconv_plan_string(1024, lc.F32)
+        lc.longconv_set_option("inner_log2", 0)
+        lc.longconv_set_option("engine", 1)
+        assert "valu" in lc.longconv_plan_string(1024, lc.F16)
+        lc.longconv_set_option("engine", 2)
+        assert "valu" in lc.longconv_plan_string(1024, lc.F32)                # fp32 I/O never runs on fp16 operands
+        L = lc.lib()
+        assert L.longconv_set_option(b"no_such_switch", 1) == 2
+        assert L.longconv_set_option(b"engine", 5) == 2
+        assert L.longconv_set_option(None, 1) == 1
+    finally:
+        for name, value in lc.OPTION_DEFAULTS.items():
+            lc.longconv_set_option(name, value)
+    assert "kernel=wave" in lc.longconv_plan_string(1024, lc.F16)
+
+
 def test_error_codes_before_any_launch():
     L = lc.lib()
     a = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
@@ -54,6 +86,8 @@ def test_error_codes_before_any_launch():
     assert f(a, None, a, None, a, 2, 4, 1024, 0, ws, big, None) == 1            # no k and no kspec
     assert f(a, a, a, None, a, 0, 4, 1024, 0, ws, big, None) == 2               # B < 1
     assert f(a, a, a, None, a, 2, 4, 1000, 0, ws, big, None) == 2               # N not a power of two
+    assert f(a, a, a, None, a, 2, 70000, 1024, 0, ws, big, None) == 2           # H beyond 65535
+    assert f(a, a, a, None, a, 1 << 12, 1 << 12, 1024, 1, ws, big, None) == 2   # more (head, pair) items than 2^22
     assert f(a, a, a, None, a, 2, 4, 1024, 9, ws, big, None) == 3               # dtype
     assert f(odd, a, a, None, a, 2, 4, 1024, 0, ws, big, None) == 4             # alignment
     assert f(a, a, a, None, a, 2, 4, 1024, 0, ws, 16, None) == 5                # workspace too small

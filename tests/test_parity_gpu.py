@@ -13,13 +13,20 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.fixture(autouse=True)
-def _need_gpu_and_clean_env(monkeypatch):
+def _need_gpu_and_default_options():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL", "LONGCONV_FUSE_PASS_A",
-              "LONGCONV_FUSE_BWD"):
-        monkeypatch.delenv(v, raising=False)
+    import paper_2302_06646_amd as lc
+    for name, value in lc.OPTION_DEFAULTS.items():      # whatever the environment or an earlier test left
+        lc.longconv_set_option(name, value)
     yield
+    for name, value in lc.OPTION_DEFAULTS.items():
+        lc.longconv_set_option(name, value)
+
+
+def _opt(name, value):
+    import paper_2302_06646_amd as lc
+    lc.longconv_set_option(name, value)
 
 
 def _w(key, **kw):
@@ -58,26 +65,26 @@ def test_other_long_sequences(N, io):
 
 @pytest.mark.parametrize("engine", ["valu", "mfma"])
 @pytest.mark.parametrize("inner", [9, 10])
-def test_forced_multipass_small(monkeypatch, engine, inner):
+def test_forced_multipass_small(engine, inner):
     # the multi-pass split exercised at a size the oracle checks in full
     from gpu_harness import check_full
-    monkeypatch.setenv("LONGCONV_ENGINE", engine)
-    monkeypatch.setenv("LONGCONV_INNER_LOG2", str(inner))
+    _opt("engine", {"valu": 1, "mfma": 2}[engine])
+    _opt("inner_log2", inner)
     io = wl.F32 if engine == "valu" else wl.F16
     check_full(wl.generate(_w("1", N=2048, dtype=io), B=3, H=3), label=f"{engine} inner=2^{inner}")
 
 
 @pytest.mark.parametrize("key,B,H", [("2", 5, 3), ("3", 2, 2), ("5_4096", 3, 2)])
-def test_staged_matrix_core_kernel(monkeypatch, key, B, H):
+def test_staged_matrix_core_kernel(key, B, H):
     # the in-place staged kernel (normally only used for 256-point transforms) forced at other lengths
     from gpu_harness import check_full
-    monkeypatch.setenv("LONGCONV_MFMA_KERNEL", "staged")
+    _opt("staged_kernel", 1)
     check_full(wl.generate(wl.WORKLOADS[key], B=B, H=H), label="staged")
 
 
-def test_valu_engine_with_half_io(monkeypatch):
+def test_valu_engine_with_half_io():
     from gpu_harness import check_full
-    monkeypatch.setenv("LONGCONV_ENGINE", "valu")
+    _opt("engine", 1)
     check_full(wl.generate(wl.WORKLOADS["2"], B=3, H=3))
     check_full(wl.generate(wl.WORKLOADS["3"], B=2, H=2))
 
@@ -142,7 +149,7 @@ def test_closed_forms_on_the_matrix_core_kernels(N, io):
     front (a circular implementation wraps), k = 1 gives the prefix sum, D adds D u; the backward of a shifted
     delta shifts dy the other way and dk[s'] of it is the lag-s' correlation.  Error per row relative to the
     row's norm, bound 3e-3."""
-    from gpu_harness import GpuRun, TOL, _row_errs
+    from gpu_harness import GpuRun, TOL
     B, H = 3, 5
     inp = wl.generate(_w("3", N=N, dtype=io), B=B, H=H)
     s1, s2 = 7, N - 3
@@ -166,8 +173,16 @@ def test_closed_forms_on_the_matrix_core_kernels(N, io):
     want_y[:, 2, s2:] = u[:, 2, :N - s2]
     want_y[:, 3] = np.cumsum(u[:, 3], axis=-1) * np.float64(np.float32(c1))
     want_y[:, 4] = (0.5 - 1.25) * u[:, 4]
-    e = _row_errs(y, want_y)
-    print(f"[closed forms] N={N} io={wl.DTYPE_NAMES[io]} y rows: max {e.max():.2e}", flush=True)
+    # head 2 keeps three samples of the shifted row: its error is measured against the norm of the whole shifted
+    # row (what the transform carries), every other row against its own norm
+    def errs(x, want, src):
+        num = np.linalg.norm(x - want, axis=-1)
+        den = np.linalg.norm(want, axis=-1)
+        den[:, 2] = np.linalg.norm(src[:, 2], axis=-1)
+        return num / den
+    e = errs(y, want_y, u)
+    print(f"[closed forms] N={N} io={wl.DTYPE_NAMES[io]} y per head: " + " ".join(f"{v:.2e}" for v in e.max(axis=0)),
+          flush=True)
     assert e.max() <= tol
     assert np.abs(y[:, 1, :s1]).max() <= tol * np.abs(u[:, 1]).max()          # nothing wraps around
     assert np.abs(y[:, 2, :s2]).max() <= tol * np.abs(u[:, 2]).max() * 4
@@ -177,8 +192,8 @@ def test_closed_forms_on_the_matrix_core_kernels(N, io):
     want_du[:, 2, :N - s2] = dy[:, 2, s2:]
     want_du[:, 3] = np.cumsum(dy[:, 3, ::-1], axis=-1)[:, ::-1] * np.float64(np.float32(c1))
     want_du[:, 4] = (0.5 - 1.25) * dy[:, 4]
-    e = _row_errs(du, want_du)
-    print(f"[closed forms] du rows: max {e.max():.2e}", flush=True)
+    e = errs(du, want_du, dy)
+    print(f"[closed forms] du per head: " + " ".join(f"{v:.2e}" for v in e.max(axis=0)), flush=True)
     assert e.max() <= tol
     # dD and the first taps of dk straight from their definitions (float64 on the host)
     want_dD = np.einsum("bhn,bhn->h", dy, u)

@@ -14,13 +14,20 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.fixture(autouse=True)
-def _need_gpu_and_clean_env(monkeypatch):
+def _need_gpu_and_default_options():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for v in ("LONGCONV_ENGINE", "LONGCONV_INNER_LOG2", "LONGCONV_MFMA_KERNEL", "LONGCONV_FUSE_PASS_A",
-              "LONGCONV_FUSE_BWD"):
-        monkeypatch.delenv(v, raising=False)
+    import paper_2302_06646_amd as lc
+    for name, value in lc.OPTION_DEFAULTS.items():      # whatever the environment or an earlier test left
+        lc.longconv_set_option(name, value)
     yield
+    for name, value in lc.OPTION_DEFAULTS.items():
+        lc.longconv_set_option(name, value)
+
+
+def _opt(name, value):
+    import paper_2302_06646_amd as lc
+    lc.longconv_set_option(name, value)
 
 
 def _w(key, **kw):
@@ -135,7 +142,7 @@ def test_step_under_graph_capture_replays_bitwise(key, B, H):
 
 
 @pytest.mark.parametrize("N,B,H,io", [(16384, 6, 129, wl.F16), (4096, 5, 771, wl.BF16), (8192, 3, 300, wl.BF16)])
-def test_persistent_workgroups_ragged_item_count(monkeypatch, N, B, H, io):
+def test_persistent_workgroups_ragged_item_count(N, B, H, io):
     """More (head, pair) items than resident workgroups, not a multiple of them, odd batch: every item must be
     processed exactly once.  Sampled heads against the oracle, and every output element against the staged
     in-place kernel (a different code path with one workgroup per item)."""
@@ -146,7 +153,7 @@ def test_persistent_workgroups_ragged_item_count(monkeypatch, N, B, H, io):
     g = GpuRun(inp)
     y = g.fwd().copy()
     du, dk, dD = [a.copy() for a in g.bwd()]
-    monkeypatch.setenv("LONGCONV_MFMA_KERNEL", "staged")
+    _opt("staged_kernel", 1)
     g2 = GpuRun(inp)
     y2 = g2.fwd()
     du2, dk2, dD2 = g2.bwd()
@@ -160,7 +167,7 @@ def test_persistent_workgroups_ragged_item_count(monkeypatch, N, B, H, io):
 
 @pytest.mark.parametrize("io", [wl.F16, wl.BF16])
 @pytest.mark.parametrize("N", [65536, 131072])
-def test_pass_a_inside_the_inner_kernel(monkeypatch, N, io):
+def test_pass_a_inside_the_inner_kernel(N, io):
     """N = 65536, 131072 (outer radix 4, 8): the convolutions, the spectrum and (N = 65536) dk take pass A while
     staging their rows.  Odd batch (the last pair has one row), both half dtypes, against the oracle and against
     the separate pass A."""
@@ -170,7 +177,7 @@ def test_pass_a_inside_the_inner_kernel(monkeypatch, N, io):
     g = GpuRun(inp)
     y = g.fwd().copy()
     du, dk, dD = (a.copy() for a in g.bwd())
-    monkeypatch.setenv("LONGCONV_FUSE_PASS_A", "0")
+    _opt("fuse_pass_a", 0)
     g2 = GpuRun(inp)
     y2 = g2.fwd()
     du2, dk2, dD2 = g2.bwd()
@@ -184,7 +191,7 @@ def test_pass_a_inside_the_inner_kernel(monkeypatch, N, io):
 
 @pytest.mark.parametrize("io", [wl.F16, wl.BF16])
 @pytest.mark.parametrize("N,B,H", [(256, 5, 7), (512, 1, 5), (1024, 7, 9), (1024, 16, 3), (2048, 3, 6)])
-def test_backward_in_one_kernel(monkeypatch, N, B, H, io):
+def test_backward_in_one_kernel(N, B, H, io):
     """Single-pass plans up to 4096 points: a call that asks for du and dk/dD runs one kernel (one read of dy
     and u, one transform of dy).  Against the oracle, and against the separate du and dk kernels: du sees the
     same arithmetic in both (bitwise equal), dk sums the same products with the roles of the packed and the
@@ -195,7 +202,7 @@ def test_backward_in_one_kernel(monkeypatch, N, B, H, io):
     g = GpuRun(inp)
     du, dk, dD = (a.copy() for a in g.bwd())
     du_only = g.bwd(dk=False, dD=False)[0].copy()          # du alone: the convolution kernel
-    monkeypatch.setenv("LONGCONV_FUSE_BWD", "0")
+    _opt("fuse_bwd", 0)
     g2 = GpuRun(inp)
     du2, dk2, dD2 = g2.bwd()
     tol = 2 * TOL[io]
