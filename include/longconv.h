@@ -98,6 +98,20 @@ int longconv_fwd(const void* u, const float* k, const float* D, const void* kspe
                  int64_t B, int64_t H, int64_t N, int io,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* Forward for callers that cannot allocate device memory or carry a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and
+ * same results as longconv_fwd; the scratch memory (on-the-fly spectrum, multi-pass workspace)
+ * lives in a library-owned static device array of LONGCONV_STATIC_SCRATCH_BYTES, which every
+ * GPU the library runs on holds until the process ends.  The call allocates and frees nothing.
+ * Shapes whose longconv_workspace_bytes(B,H,N,io,0) exceeds that size return
+ * LONGCONV_ERR_WORKSPACE before anything is launched.  All calls on one GPU share the one
+ * array: calls that overlap in time on the same GPU (different streams, different threads)
+ * race; nothing in the array needs clearing between calls.  With kspec == NULL the spectrum
+ * is computed into the array by this call. */
+#define LONGCONV_STATIC_SCRATCH_BYTES (64u << 20)
+int longconv_fwd_noalloc(const void* u, const float* k, const float* D, const void* kspec, void* y,
+                         int64_t B, int64_t H, int64_t N, int io, void* stream);
+
 /* Backward: du, dk, dD as defined above.  Any of the three output pointers may be
  * NULL to skip that gradient.  dk and dD are overwritten (not accumulated) and are
  * summed over b in a fixed order (bitwise repeatable call to call).  Which kernels

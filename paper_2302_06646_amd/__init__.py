@@ -9,7 +9,7 @@ the functions raises.
 Functions mirror the C ABI of ``include/longconv.h``:
     longconv_init, longconv_kspec_bytes, longconv_workspace_bytes,
     longconv_kspec_compute, longconv_fwd, longconv_bwd, longconv_plan_string,
-    longconv_set_option
+    longconv_set_option, longconv_fwd_noalloc
 """
 from __future__ import annotations
 
@@ -28,7 +28,8 @@ _lib = None
 
 EXPORTS = ("longconv_init", "longconv_kspec_bytes", "longconv_workspace_bytes",
            "longconv_kspec_compute", "longconv_fwd", "longconv_bwd", "longconv_status_string",
-           "longconv_last_hip_error", "longconv_plan_string", "longconv_set_option")
+           "longconv_last_hip_error", "longconv_plan_string", "longconv_set_option",
+           "longconv_fwd_noalloc")
 
 
 class LongconvError(RuntimeError):
@@ -53,6 +54,8 @@ def lib():
         L.longconv_kspec_compute.argtypes = [vp, vp, vp, i64, i64, ci, vp, sz, vp]
         L.longconv_fwd.restype = ci
         L.longconv_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, sz, vp]
+        L.longconv_fwd_noalloc.restype = ci
+        L.longconv_fwd_noalloc.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp]
         L.longconv_bwd.restype = ci
         L.longconv_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, sz, vp]
         L.longconv_status_string.restype = ctypes.c_char_p
@@ -151,6 +154,19 @@ def longconv_fwd(u, k, D, y, workspace, kspec=None, stream=None) -> None:
     _need(k, "k", torch.float32, (H, N)); _need(D, "D", torch.float32, (H,))
     _check(lib().longconv_fwd(_ptr(u), _ptr(k), _ptr(D), _ptr(kspec), _ptr(y), B, H, N, io,
                               _ptr(workspace), workspace.numel(), _stream(stream)), "longconv_fwd")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def longconv_fwd_noalloc(u, k, D, y, kspec=None, stream=None) -> None:
+    """longconv_fwd without a workspace argument: scratch is the library's static device array."""
+    B, H, N = u.shape
+    io = dtype_code(u)
+    _need(u, "u", _TORCH_DTYPE[io], (B, H, N)); _need(y, "y", _TORCH_DTYPE[io], (B, H, N))
+    _need(k, "k", torch.float32, (H, N)); _need(D, "D", torch.float32, (H,))
+    _check(lib().longconv_fwd_noalloc(_ptr(u), _ptr(k), _ptr(D), _ptr(kspec), _ptr(y), B, H, N, io,
+                                      _stream(stream)), "longconv_fwd_noalloc")
 
 
 def longconv_bwd(dy, u, k, D, du, dk, dD, workspace, kspec=None, stream=None) -> None:

@@ -51,8 +51,14 @@ constexpr int MAX_DEV = 64;
 static std::mutex g_init_mu;
 static Tables g_tab[MAX_DEV] = {};
 
+// Workspace of longconv_fwd_noalloc: one copy per device in that device's memory, held until the process ends.
+// Host code never uses the array's name as an address: the device address is looked up once per device
+// (hipGetSymbolAddress, in get_tables) and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[LONGCONV_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[MAX_DEV] = {};
+
 // Returns the device's table pointer, filling the table on first use (then syncs `st` once).
-static hipError_t get_tables(Tables* out, hipStream_t st, bool sync_device)
+static hipError_t get_tables(Tables* out, hipStream_t st, bool sync_device, void** scratch_out = nullptr)
 {
     int dev = 0;
     hipError_t e = note(hipGetDevice(&dev), "hipGetDevice");
@@ -73,12 +79,17 @@ static hipError_t get_tables(Tables* out, hipStream_t st, bool sync_device)
         if (e != hipSuccess) return e;
         e = note(coop_fill_tables(&g_tab[dev].ctab, st), "fill coop tables");
         if (e != hipSuccess) return e;
+        void* sp = nullptr;
+        e = note(hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (e != hipSuccess) return e;
         e = note(sync_device ? hipDeviceSynchronize() : hipStreamSynchronize(st), "table sync");
         if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = sp;
         g_tab[dev].stw = q;
         g_tab[dev].tw = p;
     }
     *out = g_tab[dev];
+    if (scratch_out) *scratch_out = g_scratch_ptr[dev];
     return hipSuccess;
 }
 
@@ -292,8 +303,11 @@ int longconv_kspec_compute(const float* k, const float* D, void* kspec, int64_t 
     return LONGCONV_OK;
 }
 
-int longconv_fwd(const void* u, const float* k, const float* D, const void* kspec, void* y, int64_t B,
-                 int64_t H, int64_t N, int io, void* workspace, size_t workspace_bytes, void* stream)
+// Forward pass.  own_scratch: the workspace is the library's static device array (longconv_fwd_noalloc);
+// otherwise the caller's.
+static int fwd_impl(const void* u, const float* k, const float* D, const void* kspec, void* y, int64_t B,
+                    int64_t H, int64_t N, int io, void* workspace, size_t workspace_bytes, void* stream,
+                    bool own_scratch)
 {
     int s = check_shape(B, H, N, io);
     if (s != LONGCONV_OK) return s;
@@ -302,10 +316,14 @@ int longconv_fwd(const void* u, const float* k, const float* D, const void* kspe
         return LONGCONV_ERR_ALIGN;
     const Plan pl = make_plan(N, io);
     const WsLayout w = carve(B, H, N, pl, false);
-    if (!workspace || workspace_bytes < w.total) return LONGCONV_ERR_WORKSPACE;
+    if (own_scratch) {
+        if (w.total > (size_t)LONGCONV_STATIC_SCRATCH_BYTES) return LONGCONV_ERR_WORKSPACE;
+    } else if (!workspace || workspace_bytes < w.total) {
+        return LONGCONV_ERR_WORKSPACE;
+    }
     hipStream_t st = (hipStream_t)stream;
     Tables tb;
-    if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    if (get_tables(&tb, st, false, own_scratch ? &workspace : nullptr) != hipSuccess) return LONGCONV_ERR_HIP;
     char* base = (char*)workspace;
     const float2* ks = (const float2*)kspec;
     if (!ks) {
@@ -318,6 +336,18 @@ int longconv_fwd(const void* u, const float* k, const float* D, const void* kspe
     if (note(run_conv(u, ks, y, base + w.ws1, false, pr, pl, tb, st, false), "fwd") != hipSuccess)
         return LONGCONV_ERR_HIP;
     return LONGCONV_OK;
+}
+
+int longconv_fwd(const void* u, const float* k, const float* D, const void* kspec, void* y, int64_t B,
+                 int64_t H, int64_t N, int io, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return fwd_impl(u, k, D, kspec, y, B, H, N, io, workspace, workspace_bytes, stream, false);
+}
+
+int longconv_fwd_noalloc(const void* u, const float* k, const float* D, const void* kspec, void* y, int64_t B,
+                         int64_t H, int64_t N, int io, void* stream)
+{
+    return fwd_impl(u, k, D, kspec, y, B, H, N, io, nullptr, 0, stream, true);
 }
 
 int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, const void* kspec, void* du,
