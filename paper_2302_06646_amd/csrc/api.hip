@@ -167,9 +167,21 @@ static size_t spec_bytes(const Plan& pl)
 static size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 
 struct WsLayout {
-    size_t kspec, kscratch, hscale, ws1, ws2, wsA, dpart, zbuf, total;
-    int nblk;
+    size_t kspec, kscratch, hscale, ws1, ws2, wsA, dpart, zbuf, dkpart, ddpart, total;
+    int nblk, nsplit;
 };
+
+// Single-pass matrix-core plans: the dk kernels run one workgroup per head; with few heads the pairs of a head are
+// dealt to `nsplit` workgroups (about 384 in all), whose partial dk and dD are then summed in a fixed order.
+static int dk_nsplit(int64_t B, int64_t H, const Plan& pl)
+{
+    if (pl.engine != ENGINE_MFMA || pl.log2R || !(pl.order.wave_lg || pl.order.coop_lg)) return 1;
+    const int64_t npairs = (B + 1) / 2;
+    int64_t s = 384 / H;
+    if (s > npairs) s = npairs;
+    if (s > 64) s = 64;
+    return s < 1 ? 1 : (int)s;
+}
 
 static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool backward)
 {
@@ -190,6 +202,9 @@ static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool back
     const size_t npart = (size_t)w.nblk > (size_t(1) << pl.log2R) ? (size_t)w.nblk : (size_t(1) << pl.log2R);
     w.dpart = off; if (pl.log2R && backward) off += up256((size_t)H * npart * sizeof(float));
     w.zbuf = off; if (backward && pl.order.coop_lg) off += up256((size_t)H * L * sizeof(__half2));
+    w.nsplit = backward ? dk_nsplit(B, H, pl) : 1;
+    w.dkpart = off; if (w.nsplit > 1) off += up256((size_t)w.nsplit * H * (L / 2) * sizeof(float));
+    w.ddpart = off; if (w.nsplit > 1) off += up256((size_t)w.nsplit * H * sizeof(float));
     w.total = off;
     return w;
 }
@@ -382,7 +397,13 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
                 return LONGCONV_ERR_HIP;
             ks = (const float2*)(base + w.kspec);
         }
-        if (note(wave_bwd(dy, u, ks, du, dk, dD, pr, pl, tb, st), "bwd") != hipSuccess) return LONGCONV_ERR_HIP;
+        const int ns = w.nsplit;
+        float* dkp = (float*)(base + w.dkpart);
+        float* ddp = (float*)(base + w.ddpart);
+        hipError_t e = wave_bwd(dy, u, ks, du, ns > 1 ? (dk ? dkp : nullptr) : dk, ns > 1 ? (dD ? ddp : nullptr) : dD, ns,
+                                pr, pl, tb, st);
+        if (e == hipSuccess && ns > 1) e = sum_partials(dkp, dk, (size_t)H * N, ddp, dD, (size_t)H, ns, st);
+        if (note(e, "bwd") != hipSuccess) return LONGCONV_ERR_HIP;
         return LONGCONV_OK;
     }
     if (want_dkD) {
@@ -414,10 +435,16 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
                 dy_ready = true;
                 if (e == hipSuccess && dD) e = reduce_dD(dpart, dD, H, w.nblk, st);
             }
-            if (e == hipSuccess && (dk || !pl.log2R))
-                e = mfma_dk(dy, u, dk, pl.log2R ? nullptr : dD, (const __half2*)(base + w.ws2),
-                            (const __half2*)(base + w.ws1), (__half2*)(base + w.wsA), nullptr, base + w.zbuf, pr, pl,
-                            tb, st);
+            if (e == hipSuccess && (dk || !pl.log2R)) {
+                const int ns = w.nsplit;
+                float* dkp = (float*)(base + w.dkpart);
+                float* ddp = (float*)(base + w.ddpart);
+                float* dD1 = pl.log2R ? nullptr : dD;
+                e = mfma_dk(dy, u, ns > 1 ? (dk ? dkp : nullptr) : dk, ns > 1 ? (dD1 ? ddp : nullptr) : dD1, ns,
+                            (const __half2*)(base + w.ws2), (const __half2*)(base + w.ws1), (__half2*)(base + w.wsA),
+                            nullptr, base + w.zbuf, pr, pl, tb, st);
+                if (e == hipSuccess && ns > 1) e = sum_partials(dkp, dk, (size_t)H * N, ddp, dD1, (size_t)H, ns, st);
+            }
         }
         if (e == hipSuccess && pl.log2R && dk) {
             Problem pk{1, H, N, LONGCONV_F32, 1};   // heads as single rows, real part only

@@ -26,6 +26,16 @@
 namespace lc {
 
 constexpr int NTB = 4;   // tiles advanced together per wave (instruction-level parallelism)
+#ifndef X_NB1
+#define X_NB1 NB
+#endif
+#ifndef X_NB2
+#define X_NB2 NB
+#endif
+#ifndef X_SB
+#define X_SB 1
+#endif
+#define SCHED_BARRIER() do { if (X_SB) __builtin_amdgcn_sched_barrier(0); } while (0)
 
 template <int LG>
 struct CC {
@@ -364,7 +374,7 @@ __device__ __forceinline__ void phase1_inplace(uint32_t* xb, const uint4* t1f, c
             o.w = cmul_pack(zr[k][3], zi[k][3], tw1[k].c[3]);
             *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
         }
-        __builtin_amdgcn_sched_barrier(0);
+        SCHED_BARRIER();
     }
 }
 
@@ -550,7 +560,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         // ---- phase 1, in place
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi)
-            phase1_inplace<LG, NB>(xb, t1f, vt, K.F16, K.F16, cF, (gi * NWV + wave) * 8, lane);
+            phase1_inplace<LG, X_NB1>(xb, t1f, vt, K.F16, K.F16, cF, (gi * NWV + wave) * 8, lane);
         __syncthreads();
         asm volatile("" : "+s"(ks));
 
@@ -558,21 +568,21 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi)
 #pragma unroll
-        for (int tb = 0; tb < 8; tb += NB) {
+        for (int tb = 0; tb < 8; tb += X_NB2) {
             const int t0 = (gi * NWV + wave) * 8;
-            int base[NB];
-            f4 zr[NB], zi[NB];
-            H8U kk[NB];
+            int base[X_NB2];
+            f4 zr[X_NB2], zi[X_NB2];
+            H8U kk[X_NB2];
 #pragma unroll
-            for (int k = 0; k < NB; ++k) {
+            for (int k = 0; k < X_NB2; ++k) {
                 const int t2 = t0 + tb + k;
                 base[k] = phase2_base<LG>(t2, lane);
                 kk[k].u = ks[t2 * 64 + lane];
             }
 #pragma unroll
-            for (int k = 0; k < NB; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
+            for (int k = 0; k < X_NB2; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
 #pragma unroll
-            for (int k = 0; k < NB; ++k) {
+            for (int k = 0; k < X_NB2; ++k) {
                 H8U m;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -582,7 +592,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
                 }
                 phase2_inv<LG>(xb, base[k], K, m);
             }
-            __builtin_amdgcn_sched_barrier(0);
+            SCHED_BARRIER();
         }
         __syncthreads();
 
@@ -604,7 +614,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
                                               pack_h2(r[k][2], s[k][2]), pack_h2(r[k][3], s[k][3]));
                     *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
                 }
-                __builtin_amdgcn_sched_barrier(0);
+                SCHED_BARRIER();
             }
         }
         __syncthreads();
@@ -1006,8 +1016,8 @@ size_t coop_dk_real_lds_bytes()
 template <int LG, class IO, bool SPLIT>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
-                    float* __restrict__ dk, float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs,
-                    float dkscale, const float2* __restrict__ tw,
+                    float* __restrict__ dk, float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs_all,
+                    int nsplit, float dkscale, const float2* __restrict__ tw,
                     const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
@@ -1031,7 +1041,11 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
     uint32_t* twr = vt + C::TC * 16;                   // SPLIT: w_{2N}^n at every run start n = 8 i
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
-    const int h = blockIdx.x;
+    // workgroup (head h, share `split` of nsplit): the head's pairs split, split + nsplit, ...; with nsplit > 1
+    // dk and dD point to partial buffers [nsplit][H][N] and [nsplit][H], summed afterwards in share order
+    const int h = blockIdx.x % (unsigned)H, split = blockIdx.x / (unsigned)H;
+    const int npairs = (npairs_all - split + nsplit - 1) / nsplit;      // pairs of this workgroup
+    const size_t ho = (size_t)split * H + h;
     const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
     Consts<LG> K;
     make_consts<LG>(K, tw, lane);
@@ -1058,7 +1072,7 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t raw_lds = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)raw);
     auto copy_in = [&](int sidx) {
-        const int p = (sidx >> 1) % npairs;
+        const int p = ((sidx >> 1) % npairs) * nsplit + split;
         const char* src = reinterpret_cast<const char*>((sidx & 1) ? dy : u);
         const bool has_b = (2 * p + 1) < B;
         const char* pa = src + row_off(2 * p, h, H, N) * sizeof(T);
@@ -1081,7 +1095,7 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
     };
     // raw area -> exchange slots (pair packing, bf16 -> fp16, twist)
     auto stage = [&](int sidx) {
-        const int p = (sidx >> 1) % npairs;
+        const int p = ((sidx >> 1) % npairs) * nsplit + split;
         const bool has_b = (2 * p + 1) < B;
         const bool odd = SPLIT && sidx >= 2 * npairs;
         int t_ = tid;
@@ -1157,9 +1171,10 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                 // again from global memory, DG runs at a time (registers)
                 if (pass == 1 && par == 0 && dD != nullptr) {
                     constexpr int DG = RPL < 2 ? RPL : 2;
-                    const bool dot_b = (2 * p + 1) < B;
-                    const T* qa = u + row_off(2 * p, h, H, N);
-                    const T* qb = u + row_off(dot_b ? 2 * p + 1 : 2 * p, h, H, N);
+                    const int pg = p * nsplit + split;
+                    const bool dot_b = (2 * pg + 1) < B;
+                    const T* qa = u + row_off(2 * pg, h, H, N);
+                    const T* qb = u + row_off(dot_b ? 2 * pg + 1 : 2 * pg, h, H, N);
                     int t_ = tid;
                     asm volatile("" : "+v"(t_));
 #pragma unroll
@@ -1269,7 +1284,7 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
             for (int i = 0; i < RPL; ++i) {
                 const int n = staged_run_n<LG>(i * NT + t_);
                 const int a0 = staged_slot<LG>(n);
-                float4* dst = reinterpret_cast<float4*>(dk + (size_t)h * N + n);
+                float4* dst = reinterpret_cast<float4*>(dk + ho * N + n);
                 float v[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = __uint_as_float(xb[a0 + 4 * e]);
@@ -1312,7 +1327,7 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
         if (tid == 0) {
             float t = 0.f;
             for (int w = 0; w < C::NW; ++w) t += red[w];
-            dD[h] = t;
+            dD[ho] = t;
         }
     }
 }
@@ -1921,8 +1936,8 @@ hipError_t coop_dk_go(const __half2* ws_u, const __half2* ws_dy, __half2* ws_A, 
 }
 
 template <int LG, class IO, bool SPLIT>
-hipError_t coop_dk_real_go(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Tables& tb,
-                           hipStream_t st)
+hipError_t coop_dk_real_go(const void* dy, const void* u, float* dk, float* dD, int nsplit, const Problem& pr,
+                           const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
     using C = CC<LG>;
@@ -1933,8 +1948,8 @@ hipError_t coop_dk_real_go(const void* dy, const void* u, float* dk, float* dD, 
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_dk_real_kernel<LG, IO, SPLIT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((coop_dk_real_kernel<LG, IO, SPLIT>), dim3((unsigned)pr.H), dim3(C::NW * 64), lds, st,
-                       (const T*)dy, (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, dkscale, tb.tw,
+    hipLaunchKernelGGL((coop_dk_real_kernel<LG, IO, SPLIT>), dim3((unsigned)(pr.H * nsplit)), dim3(C::NW * 64), lds, st,
+                       (const T*)dy, (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, nsplit, dkscale, tb.tw,
                        (const unsigned char*)tb.ctab);
     return hipGetLastError();
 }
@@ -2021,13 +2036,13 @@ hipError_t coop_kspec(const float* k, const __half2* ws, const float* D, const f
     return hipErrorInvalidValue;
 }
 
-hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
-                   __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl, const Tables& tb,
-                   hipStream_t st)
+hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, int nsplit, const __half2* ws_u,
+                   const __half2* ws_dy, __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl,
+                   const Tables& tb, hipStream_t st)
 {
     if (pl.log2R == 0) {
         // single pass: rows straight from the caller's tensors; 32768 points as two walks of 16384
-#define GOR(LG, IO, SPLIT) return coop_dk_real_go<LG, IO, SPLIT>(dy, u, dk, dD, pr, tb, st)
+#define GOR(LG, IO, SPLIT) return coop_dk_real_go<LG, IO, SPLIT>(dy, u, dk, dD, nsplit, pr, tb, st)
         if (pr.io == LONGCONV_F16) {
             if (pl.log2L2 == 13) GOR(13, IoF16, false);
             if (pl.log2L2 == 14) GOR(14, IoF16, false);

@@ -557,12 +557,13 @@ hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws
     return hipErrorInvalidValue;
 }
 
-hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
-                   __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl, const Tables& tb,
-                   hipStream_t st)
+hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, int nsplit, const __half2* ws_u,
+                   const __half2* ws_dy, __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl,
+                   const Tables& tb, hipStream_t st)
 {
-    if (pl.order.wave_lg) return wave_dk(dy, u, dk, dD, pr, pl, tb, st);
-    if (pl.order.coop_lg) return coop_dk(dy, u, dk, dD, ws_u, ws_dy, ws_A, dD_part, zbuf, pr, pl, tb, st);
+    if (pl.order.wave_lg) return wave_dk(dy, u, dk, dD, nsplit, pr, pl, tb, st);
+    if (pl.order.coop_lg) return coop_dk(dy, u, dk, dD, nsplit, ws_u, ws_dy, ws_A, dD_part, zbuf, pr, pl, tb, st);
+    if (nsplit != 1) return hipErrorInvalidValue;
     if (pl.log2R == 0 && dD) {
         // single pass of the in-place staged kernel: dD as the plain dot product of the rows
         hipError_t e = head_dot(dy, u, dD, pr, st);

@@ -637,7 +637,7 @@ __device__ __forceinline__ void w_phase3_tile(const uint32_t* xb, const WK<LG, T
 template <int LG, class IO, int TPW, int NWV>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(TPW == 2 ? 3 : 2)))
 wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u, float* __restrict__ dk,
-           float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs, float dkscale,
+           float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs_all, int nsplit, float dkscale,
            const unsigned char* __restrict__ wtab)
 {
     using C = WC<LG>;
@@ -652,12 +652,16 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
     uint32_t* xd = lds + (size_t)(grp * 2 + 1) * C::PAIR_WORDS;      // dy pair
     float2* red = reinterpret_cast<float2*>(lds + (size_t)NGRP * 2 * C::PAIR_WORDS);   // [wave][TPW*4][64]
     float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWV]
-    const int h = blockIdx.x;
+    // workgroup (head h, share `split` of nsplit): the head's pairs split, split + nsplit, ...; with nsplit > 1
+    // dk and dD point to partial buffers [nsplit][H][N] and [nsplit][H], summed afterwards in share order
+    const int h = blockIdx.x % (unsigned)H, split = blockIdx.x / (unsigned)H;
+    const int npairs = (npairs_all - split + nsplit - 1) / nsplit;      // pairs of this workgroup
+    const size_t ho = (size_t)split * H + h;
 
     // rows of pair p of one source; each source's registers are refilled right after its phase 1 has read them,
     // so the next pair's rows travel during two thirds of an iteration
     auto load_src = [&](int p, const typename IO::T* src, In<TPW>& in) {
-        const int64_t b0 = 2 * (int64_t)p;
+        const int64_t b0 = 2 * ((int64_t)p * nsplit + split);
         const bool has_b = b0 + 1 < B;
         const size_t oa = row_off(b0, h, H, N), ob = row_off(has_b ? b0 + 1 : b0, h, H, N);
         load_rows<LG, IO, TPW>(in, src + oa, src + ob, has_b, t0, lane);
@@ -760,7 +764,7 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
     if (tid == 0 && dD) {
         float t = 0.f;
         for (int w = 0; w < NWV; ++w) t += dred[w];
-        dD[h] = t;
+        dD[ho] = t;
     }
     if (dk) {
 #pragma unroll
@@ -771,14 +775,14 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
             if (g < 2) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    dk[(size_t)h * N + (4 * g + j) * 16 * C::TC + c * C::TC + t0 + k] = r[j] * dkscale;
+                    dk[ho * N + (4 * g + j) * 16 * C::TC + c * C::TC + t0 + k] = r[j] * dkscale;
             }
         }
     }
 }
 
 template <int LG, class IO, int TPW, int NWV>
-hipError_t wdk_go(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
+hipError_t wdk_go(const void* dy, const void* u, float* dk, float* dD, int nsplit, const Problem& pr, const Plan& pl,
                   const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
@@ -788,21 +792,21 @@ hipError_t wdk_go(const void* dy, const void* u, float* dk, float* dD, const Pro
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wdk_kernel<LG, IO, TPW, NWV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((wdk_kernel<LG, IO, TPW, NWV>), dim3((unsigned)pr.H), dim3(NWV * 64), lds, st, (const T*)dy,
-                       (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, pl.dkscale,
+    hipLaunchKernelGGL((wdk_kernel<LG, IO, TPW, NWV>), dim3((unsigned)(pr.H * nsplit)), dim3(NWV * 64), lds, st,
+                       (const T*)dy, (const T*)u, dk, dD, pr.B, pr.H, pr.N, pr.npairs, nsplit, pl.dkscale,
                        (const unsigned char*)tb.wtab);
     return hipGetLastError();
 }
 
 template <class IO>
-hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
+hipError_t wdk_io(const void* dy, const void* u, float* dk, float* dD, int nsplit, const Problem& pr, const Plan& pl,
                   const Tables& tb, hipStream_t st)
 {
     switch (pl.log2L2) {
-        case 9: return wdk_go<9, IO, 2, 4>(dy, u, dk, dD, pr, pl, tb, st);
-        case 10: return wdk_go<10, IO, 2, 4>(dy, u, dk, dD, pr, pl, tb, st);
-        case 11: return wdk_go<11, IO, 2, 4>(dy, u, dk, dD, pr, pl, tb, st);
-        case 12: return wdk_go<12, IO, 2, 8>(dy, u, dk, dD, pr, pl, tb, st);
+        case 9: return wdk_go<9, IO, 2, 4>(dy, u, dk, dD, nsplit, pr, pl, tb, st);
+        case 10: return wdk_go<10, IO, 2, 4>(dy, u, dk, dD, nsplit, pr, pl, tb, st);
+        case 11: return wdk_go<11, IO, 2, 4>(dy, u, dk, dD, nsplit, pr, pl, tb, st);
+        case 12: return wdk_go<12, IO, 2, 8>(dy, u, dk, dD, nsplit, pr, pl, tb, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -820,7 +824,7 @@ template <int LG, class IO, int TPW, int NWV>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
             const float2* __restrict__ kspec, typename IO::T* __restrict__ du, float* __restrict__ dk,
-            float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs, float dkscale,
+            float* __restrict__ dD, int64_t B, int64_t H, int64_t N, int npairs_all, int nsplit, float dkscale,
             const unsigned char* __restrict__ wtab)
 {
     using C = WC<LG>;
@@ -841,10 +845,13 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
     uint32_t* stg1 = stg0 + STW;
     float2* red = reinterpret_cast<float2*>(lds + (size_t)NGRP * (3 * C::PAIR_WORDS + 2 * STW));   // [wave][TPW*4][64]
     float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWV]
-    const int h = blockIdx.x;
+    // workgroup (head h, share `split` of nsplit) as in wdk_kernel
+    const int h = blockIdx.x % (unsigned)H, split = blockIdx.x / (unsigned)H;
+    const int npairs = (npairs_all - split + nsplit - 1) / nsplit;
+    const size_t ho = (size_t)split * H + h;
 
     auto load_src = [&](int p, const typename IO::T* src, In<TPW>& in) {
-        const int64_t b0 = 2 * (int64_t)p;
+        const int64_t b0 = 2 * ((int64_t)p * nsplit + split);
         const bool has_b = b0 + 1 < B;
         const size_t oa = row_off(b0, h, H, N), ob = row_off(has_b ? b0 + 1 : b0, h, H, N);
         load_rows<LG, IO, TPW>(in, src + oa, src + ob, has_b, t0, lane);
@@ -887,7 +894,7 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
         if (p >= npairs) return;
         const int gl = (wave % NWP) * 64 + lane;                       // lane of the group, 4 words each
         const int row = (4 * gl) / (STW / 2), n = ((4 * gl) % (STW / 2)) * 2;
-        const int64_t b0 = 2 * (int64_t)p + row;
+        const int64_t b0 = 2 * ((int64_t)p * nsplit + split) + row;
         if (b0 >= B) return;
         const uint4 v = *reinterpret_cast<const uint4*>(((itf & 1) ? stg1 : stg0) + 4 * gl);
         *reinterpret_cast<uint4*>(du + row_off(b0, h, H, N) + n) = v;
@@ -985,7 +992,7 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
     if (tid == 0 && dD) {
         float t = 0.f;
         for (int w2 = 0; w2 < NWV; ++w2) t += dred[w2];
-        dD[h] = t;
+        dD[ho] = t;
     }
     if (dk) {
 #pragma unroll
@@ -996,14 +1003,14 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
             if (g < 2) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    dk[(size_t)h * N + (4 * g + j) * 16 * C::TC + c * C::TC + t0 + k] = r[j] * dkscale;
+                    dk[ho * N + (4 * g + j) * 16 * C::TC + c * C::TC + t0 + k] = r[j] * dkscale;
             }
         }
     }
 }
 
 template <int LG, class IO, int TPW, int NWV>
-hipError_t wbwd_go(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD,
+hipError_t wbwd_go(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD, int nsplit,
                    const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
@@ -1013,21 +1020,21 @@ hipError_t wbwd_go(const void* dy, const void* u, const float2* kspec, void* du,
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wbwd_kernel<LG, IO, TPW, NWV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((wbwd_kernel<LG, IO, TPW, NWV>), dim3((unsigned)pr.H), dim3(NWV * 64), lds, st, (const T*)dy,
-                       (const T*)u, kspec, (T*)du, dk, dD, pr.B, pr.H, pr.N, pr.npairs, pl.dkscale,
+    hipLaunchKernelGGL((wbwd_kernel<LG, IO, TPW, NWV>), dim3((unsigned)(pr.H * nsplit)), dim3(NWV * 64), lds, st,
+                       (const T*)dy, (const T*)u, kspec, (T*)du, dk, dD, pr.B, pr.H, pr.N, pr.npairs, nsplit, pl.dkscale,
                        (const unsigned char*)tb.wtab);
     return hipGetLastError();
 }
 
 template <class IO>
-hipError_t wbwd_io(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD,
+hipError_t wbwd_io(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD, int nsplit,
                    const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
 {
     switch (pl.log2L2) {
-        case 9: return wbwd_go<9, IO, 2, 4>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
-        case 10: return wbwd_go<10, IO, 2, 4>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
-        case 11: return wbwd_go<11, IO, 2, 4>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
-        case 12: return wbwd_go<12, IO, 2, 8>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
+        case 9: return wbwd_go<9, IO, 2, 4>(dy, u, kspec, du, dk, dD, nsplit, pr, pl, tb, st);
+        case 10: return wbwd_go<10, IO, 2, 4>(dy, u, kspec, du, dk, dD, nsplit, pr, pl, tb, st);
+        case 11: return wbwd_go<11, IO, 2, 4>(dy, u, kspec, du, dk, dD, nsplit, pr, pl, tb, st);
+        case 12: return wbwd_go<12, IO, 2, 8>(dy, u, kspec, du, dk, dD, nsplit, pr, pl, tb, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1187,20 +1194,20 @@ hipError_t wave_kspec(const float* k, const float* D, float2* kspec, int64_t H, 
     }
 }
 
-hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
+hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, int nsplit, const Problem& pr, const Plan& pl,
                    const Tables& tb, hipStream_t st)
 {
-    if (pr.io == LONGCONV_F16) return wdk_io<IoF16>(dy, u, dk, dD, pr, pl, tb, st);
-    if (pr.io == LONGCONV_BF16) return wdk_io<IoBF16>(dy, u, dk, dD, pr, pl, tb, st);
+    if (pr.io == LONGCONV_F16) return wdk_io<IoF16>(dy, u, dk, dD, nsplit, pr, pl, tb, st);
+    if (pr.io == LONGCONV_BF16) return wdk_io<IoBF16>(dy, u, dk, dD, nsplit, pr, pl, tb, st);
     return hipErrorInvalidValue;
 }
 
-hipError_t wave_bwd(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD,
+hipError_t wave_bwd(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD, int nsplit,
                     const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
 {
     if (!wave_bwd_ok(pl)) return hipErrorInvalidValue;
-    if (pr.io == LONGCONV_F16) return wbwd_io<IoF16>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
-    if (pr.io == LONGCONV_BF16) return wbwd_io<IoBF16>(dy, u, kspec, du, dk, dD, pr, pl, tb, st);
+    if (pr.io == LONGCONV_F16) return wbwd_io<IoF16>(dy, u, kspec, du, dk, dD, nsplit, pr, pl, tb, st);
+    if (pr.io == LONGCONV_BF16) return wbwd_io<IoBF16>(dy, u, kspec, du, dk, dD, nsplit, pr, pl, tb, st);
     return hipErrorInvalidValue;
 }
 

@@ -68,21 +68,26 @@ void mfma_fill_plan(Plan& pl);
 hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,
                      const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st);
 // Multi-pass: dD_part[h*R + k1] receives chunk k1's share of dD[h] (sum them with reduce_dD).
-hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u,
+hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, int nsplit, const __half2* ws_u,
                    const __half2* ws_dy, __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr,
                    const Plan& pl, const Tables& tb, hipStream_t st);
+// out[i] = sum_s part[s * n + i], s in share order (bitwise repeatable); dk (n_dk values) and dD (n_dD) in one launch
+hipError_t sum_partials(const float* dk_part, float* dk, size_t n_dk, const float* dD_part, float* dD, size_t n_dD,
+                        int nsplit, hipStream_t st);
 
 // ---- wave-autonomous matrix-core kernels for 512 <= L <= 4096 (engine_wave.hip) ----------
 constexpr int WAVE_MIN_LOG2 = 9, WAVE_MAX_LOG2 = 12;
 hipError_t wave_fill_tables(const void** tab_out, hipStream_t st);
 hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
                      const Plan& pl, const Tables& tb, hipStream_t st);
-hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, const Problem& pr, const Plan& pl,
+// nsplit > 1 (single-pass dk kernels): the pairs of a head are dealt to nsplit workgroups, dk and dD then point to
+// partial buffers [nsplit][H][N] and [nsplit][H] that sum_partials() adds up in share order.
+hipError_t wave_dk(const void* dy, const void* u, float* dk, float* dD, int nsplit, const Problem& pr, const Plan& pl,
                    const Tables& tb, hipStream_t st);
 // du, dk and dD in one kernel, from one read of dy and u (single-pass plans up to 4096 points; dk and dD may be
 // null, du not).
 inline bool wave_bwd_ok(const Plan& pl) { return pl.fuse_bwd != 0; }
-hipError_t wave_bwd(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD,
+hipError_t wave_bwd(const void* dy, const void* u, const float2* kspec, void* du, float* dk, float* dD, int nsplit,
                     const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st);
 // Spectrum on the matrix cores (finds each head's pre-scale itself).
 hipError_t wave_kspec(const float* k, const float* D, float2* kspec, int64_t H, int64_t N,
@@ -107,8 +112,8 @@ hipError_t coop_dk_rows(const void* dy, const void* u, __half2* ws_A, float* dD,
 hipError_t coop_kspec(const float* k, const __half2* ws, const float* D, const float* rs, float2* kspec, int64_t H,
                       int64_t N, const Plan& pl, const Tables& tb, hipStream_t st);
 // zbuf: H * 2N * 4 bytes of scratch (transform of the current u pair, parked between the two transforms)
-hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, const __half2* ws_u, const __half2* ws_dy,
-                   __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl, const Tables& tb,
-                   hipStream_t st);
+hipError_t coop_dk(const void* dy, const void* u, float* dk, float* dD, int nsplit, const __half2* ws_u,
+                   const __half2* ws_dy, __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl,
+                   const Tables& tb, hipStream_t st);
 
 }  // namespace lc

@@ -390,6 +390,34 @@ hipError_t head_dot(const void* dy, const void* u, float* dD, const Problem& pr,
     return hipGetLastError();
 }
 
+__global__ void sum_partials_kernel(const float* __restrict__ dk_part, float* __restrict__ dk, size_t n_dk,
+                                    const float* __restrict__ dD_part, float* __restrict__ dD, size_t n_dD, int nsplit)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_dk) {
+        float t = dk_part[i];
+        for (int s = 1; s < nsplit; ++s) t += dk_part[(size_t)s * n_dk + i];
+        dk[i] = t;
+    } else if (i - n_dk < n_dD) {
+        const size_t j = i - n_dk;
+        float t = dD_part[j];
+        for (int s = 1; s < nsplit; ++s) t += dD_part[(size_t)s * n_dD + j];
+        dD[j] = t;
+    }
+}
+
+hipError_t sum_partials(const float* dk_part, float* dk, size_t n_dk, const float* dD_part, float* dD, size_t n_dD,
+                        int nsplit, hipStream_t st)
+{
+    if (!dk) n_dk = 0;
+    if (!dD) n_dD = 0;
+    const size_t n = n_dk + n_dD;
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dk_part, dk, n_dk,
+                       dD_part, dD, n_dD, nsplit);
+    return hipGetLastError();
+}
+
 hipError_t reduce_dD(const float* part, float* dD, int64_t H, int nblk, hipStream_t st)
 {
     hipLaunchKernelGGL(reduce_dD_kernel, dim3((unsigned)((H + 127) / 128)), dim3(128), 0, st, part, dD, H, nblk);

@@ -209,3 +209,21 @@ def test_backward_in_one_kernel(N, B, H, io):
     assert np.array_equal(du_only, du2)
     assert wl.rel_l2(du, du2) <= tol and wl.rel_l2(dk, dk2) <= tol and wl.rel_l2(dD, dD2) <= tol
     assert not np.array_equal(dk, dk2)        # the switch did take effect
+
+
+@pytest.mark.parametrize("N,B,H,io", [(4096, 128, 32, wl.F16), (1024, 37, 3, wl.BF16), (16384, 12, 5, wl.F16)])
+def test_few_heads_batch_dealt_to_several_workgroups(N, B, H, io):
+    """With few heads the pairs of a head are dealt to several workgroups of the dk kernels and the partial dk and
+    dD summed in a fixed order: against the oracle (whole tensors; the first shape is the one of the paper's
+    block-size table, B = 128, H = 32, N = 4096), and bitwise repeatable call to call."""
+    from gpu_harness import GpuRun, check_full
+    inp = wl.generate(_w("2", N=N, dtype=io), B=B, H=H)
+    check_full(inp, label=f"few heads N={N} B={B} H={H}")
+    g = GpuRun(inp)
+    du0, dk0, dD0 = (a.copy() for a in g.bwd())
+    for _ in range(3):
+        g.dk.fill_(float("nan")); g.dD.fill_(float("nan"))
+        du1, dk1, dD1 = g.bwd()
+        assert np.array_equal(dk1, dk0) and np.array_equal(dD1, dD0) and np.array_equal(du1, du0)
+    dk_only = g.bwd(du=False)[1].copy()              # partial request: the separate dk kernel, also dealt out
+    assert wl.rel_l2(dk_only, dk0) <= 2 * 3e-3
