@@ -26,16 +26,6 @@
 namespace lc {
 
 constexpr int NTB = 4;   // tiles advanced together per wave (instruction-level parallelism)
-#ifndef X_NB1
-#define X_NB1 NB
-#endif
-#ifndef X_NB2
-#define X_NB2 NB
-#endif
-#ifndef X_SB
-#define X_SB 1
-#endif
-#define SCHED_BARRIER() do { if (X_SB) __builtin_amdgcn_sched_barrier(0); } while (0)
 
 template <int LG>
 struct CC {
@@ -374,7 +364,7 @@ __device__ __forceinline__ void phase1_inplace(uint32_t* xb, const uint4* t1f, c
             o.w = cmul_pack(zr[k][3], zi[k][3], tw1[k].c[3]);
             *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
         }
-        SCHED_BARRIER();
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -560,7 +550,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         // ---- phase 1, in place
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi)
-            phase1_inplace<LG, X_NB1>(xb, t1f, vt, K.F16, K.F16, cF, (gi * NWV + wave) * 8, lane);
+            phase1_inplace<LG, NB>(xb, t1f, vt, K.F16, K.F16, cF, (gi * NWV + wave) * 8, lane);
         __syncthreads();
         asm volatile("" : "+s"(ks));
 
@@ -568,21 +558,21 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi)
 #pragma unroll
-        for (int tb = 0; tb < 8; tb += X_NB2) {
+        for (int tb = 0; tb < 8; tb += NB) {
             const int t0 = (gi * NWV + wave) * 8;
-            int base[X_NB2];
-            f4 zr[X_NB2], zi[X_NB2];
-            H8U kk[X_NB2];
+            int base[NB];
+            f4 zr[NB], zi[NB];
+            H8U kk[NB];
 #pragma unroll
-            for (int k = 0; k < X_NB2; ++k) {
+            for (int k = 0; k < NB; ++k) {
                 const int t2 = t0 + tb + k;
                 base[k] = phase2_base<LG>(t2, lane);
                 kk[k].u = ks[t2 * 64 + lane];
             }
 #pragma unroll
-            for (int k = 0; k < X_NB2; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
+            for (int k = 0; k < NB; ++k) phase2_fwd<LG>(xb, base[k], K, zr[k], zi[k]);
 #pragma unroll
-            for (int k = 0; k < X_NB2; ++k) {
+            for (int k = 0; k < NB; ++k) {
                 H8U m;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -592,7 +582,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
                 }
                 phase2_inv<LG>(xb, base[k], K, m);
             }
-            SCHED_BARRIER();
+            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
 
@@ -614,7 +604,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
                                               pack_h2(r[k][2], s[k][2]), pack_h2(r[k][3], s[k][3]));
                     *reinterpret_cast<uint4*>(&xb[w1 + 4 * (t0 + tb + k)]) = o;
                 }
-                SCHED_BARRIER();
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         __syncthreads();

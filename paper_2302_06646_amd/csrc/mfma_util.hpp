@@ -44,9 +44,6 @@ __device__ __forceinline__ uint32_t cmul_pack(float yr, float yi, h2 w)
 {
     const f2 v = {yr, yi};
     const h2 y = __builtin_convertvector(v, h2);
-#ifdef X_NO_TWIDDLE
-    { union { h2 h; uint32_t u; } c0; c0.h = y; return c0.u; }
-#endif
     const h2 yx = {y[0], y[0]}, yy = {y[1], y[1]};
     const h2 ws = {-w[1], w[0]};
     union { h2 h; uint32_t u; } cv;
@@ -66,17 +63,7 @@ __device__ __forceinline__ uint32_t cmul_pack_conj(float yr, float yi, h2 w)
     return cv.u;
 }
 
-#ifdef X_FAKE_MFMA
-typedef _Float16 h4x __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ f4 fake_mfma(h8 a, h8 b, f4 acc)
-{
-    const h4x a4 = {a[0], a[1], a[2], a[3]}, b4 = {b[0], b[1], b[2], b[3]};
-    return __builtin_amdgcn_mfma_f32_4x4x4f16(a4, b4, acc, 0, 0, 0);
-}
-#define MFMA(a, b, acc) fake_mfma((a), (b), (acc))
-#else
 #define MFMA(a, b, acc) __builtin_amdgcn_mfma_f32_16x16x32_f16((a), (b), (acc), 0, 0, 0)
-#endif
 
 // LDS traffic between the lanes of one wave: hardware keeps a wave's LDS operations in order,
 // the fence only stops the compiler from moving accesses across the phase boundary.
