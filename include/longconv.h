@@ -125,6 +125,27 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
                  int64_t B, int64_t H, int64_t N, int io,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* Kernel regularisers in front of the convolution (Algorithm 1 lines 1-3; Section 3.1,
+ * "Regularizing the Kernel"), for the raw parameter K [H,N] f32:
+ *     K1 = drop_mask * K                      dropout; the mask (0 or 1/(1-q) per entry, [H,N] f32)
+ *                                             is drawn by the caller; NULL = no dropout
+ *     K2[n] = sum_{|d|<=p} K1[n+d] / (2p+1)   Smooth: centred window of 2p+1 taps, entries outside
+ *                                             0..N-1 count as zero; p = 0 is the identity; p <= 32
+ *     kbar = sign(K2) * max(|K2| - lambda, 0) Squash; lambda >= 0
+ * (the printed Smooth formula is off-centre by one and has no boundary rule: this is the
+ * reading taken).  kbar [H,N] f32 is what longconv_kspec_compute / longconv_fwd / longconv_bwd
+ * take as k.  kbar must not alias K.  No workspace. */
+int longconv_kreg_fwd(const float* k, const float* drop_mask, float* kbar, int64_t H, int64_t N,
+                      int p, float lambda, void* stream);
+
+/* Chain rule back through the three steps: dkbar [H,N] f32 (the dk of longconv_bwd) ->
+ * dk [H,N] f32, the gradient with respect to the raw K:
+ *     dk = drop_mask * Smooth^T(dkbar * [|K2| > lambda])
+ * with K2 recomputed from K and the same mask, p, lambda (gradient 0 at the kink |K2| = lambda).
+ * dk must not alias any input. */
+int longconv_kreg_bwd(const float* k, const float* drop_mask, const float* dkbar, float* dk,
+                      int64_t H, int64_t N, int p, float lambda, void* stream);
+
 /* Debug and test switches (process-wide; not needed in normal use).  Each selects among
  * kernels that compute the same result: "engine" (0 by dtype, 1 fp32 vector-ALU engine,
  * 2 fp16 matrix-core engine), "inner_log2" (0, or n: cap the on-chip transform at 2^n

@@ -9,7 +9,7 @@ the functions raises.
 Functions mirror the C ABI of ``include/longconv.h``:
     longconv_init, longconv_kspec_bytes, longconv_workspace_bytes,
     longconv_kspec_compute, longconv_fwd, longconv_bwd, longconv_plan_string,
-    longconv_set_option, longconv_fwd_noalloc
+    longconv_set_option, longconv_fwd_noalloc, longconv_kreg_fwd, longconv_kreg_bwd
 """
 from __future__ import annotations
 
@@ -29,7 +29,7 @@ _lib = None
 EXPORTS = ("longconv_init", "longconv_kspec_bytes", "longconv_workspace_bytes",
            "longconv_kspec_compute", "longconv_fwd", "longconv_bwd", "longconv_status_string",
            "longconv_last_hip_error", "longconv_plan_string", "longconv_set_option",
-           "longconv_fwd_noalloc")
+           "longconv_fwd_noalloc", "longconv_kreg_fwd", "longconv_kreg_bwd")
 
 
 class LongconvError(RuntimeError):
@@ -63,6 +63,10 @@ def lib():
         L.longconv_last_hip_error.restype = ctypes.c_char_p
         L.longconv_plan_string.restype = ctypes.c_char_p
         L.longconv_plan_string.argtypes = [i64, ci]
+        L.longconv_kreg_fwd.restype = ci
+        L.longconv_kreg_fwd.argtypes = [vp, vp, vp, i64, i64, ci, ctypes.c_float, vp]
+        L.longconv_kreg_bwd.restype = ci
+        L.longconv_kreg_bwd.argtypes = [vp, vp, vp, vp, i64, i64, ci, ctypes.c_float, vp]
         L.longconv_set_option.restype = ci
         L.longconv_set_option.argtypes = [ctypes.c_char_p, ci]
         _lib = L
@@ -121,6 +125,24 @@ OPTION_DEFAULTS = {"engine": 0, "inner_log2": 0, "staged_kernel": 0, "fuse_pass_
 def longconv_set_option(name: str, value: int) -> None:
     """Debug/test switch of the library (see include/longconv.h)."""
     _check(lib().longconv_set_option(name.encode(), int(value)), f"longconv_set_option({name})")
+
+
+def longconv_kreg_fwd(k, drop_mask, kbar, p: int, lam: float, stream=None) -> None:
+    """kbar <- Squash(Smooth(dropout(k))) (Algorithm 1 lines 1-3); drop_mask may be None."""
+    H, N = k.shape
+    _need(k, "k", torch.float32, (H, N)); _need(drop_mask, "drop_mask", torch.float32, (H, N))
+    _need(kbar, "kbar", torch.float32, (H, N))
+    _check(lib().longconv_kreg_fwd(_ptr(k), _ptr(drop_mask), _ptr(kbar), H, N, int(p), float(lam), _stream(stream)),
+           "longconv_kreg_fwd")
+
+
+def longconv_kreg_bwd(k, drop_mask, dkbar, dk, p: int, lam: float, stream=None) -> None:
+    """dk <- chain rule through dropout, Smooth and Squash applied to dkbar."""
+    H, N = k.shape
+    _need(k, "k", torch.float32, (H, N)); _need(drop_mask, "drop_mask", torch.float32, (H, N))
+    _need(dkbar, "dkbar", torch.float32, (H, N)); _need(dk, "dk", torch.float32, (H, N))
+    _check(lib().longconv_kreg_bwd(_ptr(k), _ptr(drop_mask), _ptr(dkbar), _ptr(dk), H, N, int(p), float(lam),
+                                   _stream(stream)), "longconv_kreg_bwd")
 
 
 def new_workspace(B, H, N, io, backward, device="cuda"):

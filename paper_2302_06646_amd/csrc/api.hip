@@ -466,6 +466,35 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
     return LONGCONV_OK;
 }
 
+static int kreg_check(const float* k, const void* a, const void* b, int64_t H, int64_t N, int p, float lambda)
+{
+    int s = check_shape(1, H, N, LONGCONV_F32);
+    if (s != LONGCONV_OK) return s;
+    if (!k || !a || !b) return LONGCONV_ERR_NULL;
+    if (p < 0 || p > KREG_MAX_P || !(lambda >= 0.f) || !(lambda < 3.0e38f)) return LONGCONV_ERR_SHAPE;
+    return LONGCONV_OK;
+}
+
+int longconv_kreg_fwd(const float* k, const float* drop_mask, float* kbar, int64_t H, int64_t N, int p, float lambda,
+                      void* stream)
+{
+    int s = kreg_check(k, kbar, kbar, H, N, p, lambda);
+    if (s != LONGCONV_OK) return s;
+    if (note(kreg_fwd(k, drop_mask, kbar, H, N, p, lambda, (hipStream_t)stream), "kreg fwd") != hipSuccess)
+        return LONGCONV_ERR_HIP;
+    return LONGCONV_OK;
+}
+
+int longconv_kreg_bwd(const float* k, const float* drop_mask, const float* dkbar, float* dk, int64_t H, int64_t N,
+                      int p, float lambda, void* stream)
+{
+    int s = kreg_check(k, dkbar, dk, H, N, p, lambda);
+    if (s != LONGCONV_OK) return s;
+    if (note(kreg_bwd(k, drop_mask, dkbar, dk, H, N, p, lambda, (hipStream_t)stream), "kreg bwd") != hipSuccess)
+        return LONGCONV_ERR_HIP;
+    return LONGCONV_OK;
+}
+
 int longconv_set_option(const char* name, int value)
 {
     if (!name) return LONGCONV_ERR_NULL;

@@ -46,6 +46,13 @@ hipError_t head_dot(const void* dy, const void* u, float* dD, const Problem& pr,
 // dD[h] = sum of the per-block partials written by outer_fwd.
 hipError_t reduce_dD(const float* part, float* dD, int64_t H, int nblk, hipStream_t st);
 
+// ---- kernel regularisers (kreg.hip): Kbar = Squash(Smooth(dropout(K))) and the chain back to K -----------------
+constexpr int KREG_MAX_P = 32;
+hipError_t kreg_fwd(const float* k, const float* mask, float* kbar, int64_t H, int64_t N, int p, float lam,
+                    hipStream_t st);
+hipError_t kreg_bwd(const float* k, const float* mask, const float* dkbar, float* dk, int64_t H, int64_t N, int p,
+                    float lam, hipStream_t st);
+
 // ---- fp32 VALU engine (engine_valu.hip) --------------------------------------------
 // Spectrum of one head (or of one chunk of the multi-pass split) in fp32, scattered to the
 // consumer's storage order.  Used for every dtype: the spectrum is always computed in fp32.

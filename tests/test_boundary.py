@@ -97,6 +97,16 @@ def test_error_codes_before_any_launch():
     assert b(a, None, a, a, None, a, a, a, 2, 4, 1024, 0, ws, big, None) == 1   # dk wanted, no u
     assert b(a, a, a, a, None, a, a, a, 2, 4, 2048 + 1, 0, ws, big, None) == 2
     assert b(a, a, a, a, None, a, a, a, 2, 4, 1024, 0, ws, 8, None) == 5
+    r = L.longconv_kreg_fwd
+    lam = ctypes.c_float(0.01)
+    assert r(None, None, a, 4, 1024, 1, lam, None) == 1                         # NULL k
+    assert r(a, None, None, 4, 1024, 1, lam, None) == 1                         # NULL output
+    assert r(a, None, a, 4, 1024, 33, lam, None) == 2                           # window too wide
+    assert r(a, None, a, 4, 1024, -1, lam, None) == 2
+    assert r(a, None, a, 4, 1024, 1, ctypes.c_float(-0.5), None) == 2           # negative lambda
+    assert r(a, None, a, 4, 1000, 1, lam, None) == 2
+    assert L.longconv_kreg_bwd(a, None, None, a, 4, 1024, 1, lam, None) == 1    # NULL dkbar
+    assert L.longconv_kreg_bwd(a, None, a, a, 4, 1024, 40, lam, None) == 2
     k = L.longconv_kspec_compute
     assert k(None, a, a, 4, 1024, 0, ws, big, None) == 1
     assert k(a, a, a, 4, 3, 0, ws, big, None) == 2
