@@ -268,7 +268,9 @@ static hipError_t run_conv(const void* in, const float2* kspec, void* out, void*
     else
         e = mfma_conv(in, kspec, out, (__half2*)ws1, conj, fuse_a, pr, pl, tb, st);
     if (e != hipSuccess) return e;
-    if (pl.log2R) e = outer_inv(ws1, out, pr, pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st);
+    if (pl.log2R)
+        e = outer_inv(ws1, out, pr, pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st,
+                      fuse_a && coop_conv_chunks(pr, pl, fuse_a) < (1 << pl.log2R));
     return e;
 }
 
@@ -448,7 +450,9 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
         }
         if (e == hipSuccess && pl.log2R && dk) {
             Problem pk{1, H, N, LONGCONV_F32, 1};   // heads as single rows, real part only
-            e = outer_inv(base + w.wsA, dk, pk, cR, cL2, cscale, f16ws, tw, st);
+            // (dk from the rows of a batch of one: only the chunks up to R/2 were computed)
+            e = outer_inv(base + w.wsA, dk, pk, cR, cL2, cscale, f16ws, tw, st,
+                          pl.engine == ENGINE_MFMA && coop_dk_rows_ok(pl) && B == 1);
         }
         if (note(e, "bwd dk/dD") != hipSuccess) return LONGCONV_ERR_HIP;
     }

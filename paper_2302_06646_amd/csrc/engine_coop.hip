@@ -811,7 +811,7 @@ __device__ __forceinline__ int chunk_run_n(int r)
 template <int LG, class IO, int NWV, int NB, bool CONJ, int FUSEA>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec, __half2* __restrict__ ws,
-                 int64_t B, int64_t H, int64_t N, int npairs, int log2R, int total, int per,
+                 int64_t B, int64_t H, int64_t N, int npairs, int log2R, int nch, int total, int per,
                  const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
@@ -842,9 +842,11 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
 
     auto run_n = [&](int i) { return chunk_run_n<LG>(i * NT + tid); };
+    // items (head, chunk k1 < nch, pair); nch = R, or R/2 + 1 where every pair is a single real row: the chunks
+    // above R/2 are then the complex conjugates of those below (Hermitian spectrum) and pass C fills them in
     auto chunk_of = [&](int it) {
         const int hk = it / npairs, p = it - hk * npairs;
-        const int h = hk >> log2R, k1 = hk & ((1 << log2R) - 1);
+        const int h = hk / nch, k1 = hk - h * nch;
         return ws + ((size_t)h * npairs + p) * Ltot + (size_t)k1 * C::L;
     };
     auto stage = [&](int it) {
@@ -875,7 +877,7 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     auto stage_rows = [&](int it) __attribute__((always_inline)) {
         constexpr int LR = FUSEA > 0 ? FUSEA : 2;
         const int hk = it / npairs, p = it - hk * npairs;
-        const int h = hk >> LR, k1 = hk & ((1 << LR) - 1);
+        const int h = hk / nch, k1 = hk - h * nch;
         F1 = phase_mats(k1, C::cb + 4, LG + LR, tw, lane);
         F2 = phase_mats(k1, C::cb, LG + LR, tw, lane);
         twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);
@@ -892,10 +894,9 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
     __syncthreads();
     if (it0 < it1) stage_item(it0);
     for (int it = it0; it < it1; ++it) {
-        const int hk = it / npairs;
+        const int hk = it / npairs, hh = hk / nch;
         const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) +
-                                                         (size_t)(hk >> log2R) * Ltot +
-                                                         (size_t)(hk & ((1 << log2R) - 1)) * C::L);
+                                                         (size_t)hh * Ltot + (size_t)(hk - hh * nch) * C::L);
         __syncthreads();             // staged chunk visible
 
         // ---- phase 1, in place
@@ -1336,7 +1337,7 @@ template <int LG, class IO, int LR>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
                     __half2* __restrict__ ws_A, float* __restrict__ dD, int64_t B, int64_t H, int64_t N,
-                    int npairs, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
+                    int npairs, int nch, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
     using T = typename IO::T;
@@ -1355,7 +1356,9 @@ coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
     // (one L2), fetch them from HBM once
     const unsigned G = gridDim.x;
     const unsigned vid = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * (G >> 3) + (blockIdx.x >> 3);
-    const int h = (int)(vid >> LR), k1 = (int)(vid & ((1u << LR) - 1u));
+    // nch chunks per head: all 2^LR, or only k1 <= 2^LR / 2 for a batch of one row (the accumulated spectrum of
+    // real rows is Hermitian, pass C takes the other chunks as conjugates)
+    const int h = (int)(vid / (unsigned)nch), k1 = (int)(vid - (unsigned)h * (unsigned)nch);
     const uint4* gtab = reinterpret_cast<const uint4*>(ctab + coop_tab_offset(LG));
     Consts<LG> K;
     make_consts<LG>(K, tw, lane);
@@ -1876,7 +1879,10 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
     // multi-pass: the inner convolution on pass A's workspace, or (fuse_a) on the rows themselves
     using T = typename IO::T;
     const size_t lds = coop_real_lds_bytes<LG>();
-    const long total = (pr.H << pl.log2R) * pr.npairs;   // (head, chunk, pair) items
+    // (head, chunk, pair) items; a batch of one row (every pair a single real row) with pass A inside needs only
+    // the chunks up to R/2 (conv_chunks)
+    const int nch = coop_conv_chunks(pr, pl, fuse_a);
+    const long total = pr.H * nch * pr.npairs;
     auto launch = [&](auto kern, int& resident) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1889,12 +1895,15 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
         }
         const int per = (int)((total + resident - 1) / resident);
         hipLaunchKernelGGL(kern, dim3((unsigned)((total + per - 1) / per)), dim3(NWV * 64), lds, st, (const T*)in, kspec,
-                           ws, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, (int)total, per, tb.tw,
+                           ws, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, nch, (int)total, per, tb.tw,
                            (const unsigned char*)tb.ctab);
         return hipGetLastError();
     };
-    static int res[6] = {0, 0, 0, 0, 0, 0};
+    static int res[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if constexpr (LG == COOP_MAX_LOG2) {
+        if (fuse_a && pl.log2R == 1)
+            return conj ? launch(coop_conv_kernel<LG, IO, NWV, NB, true, 1>, res[6])
+                        : launch(coop_conv_kernel<LG, IO, NWV, NB, false, 1>, res[7]);
         if (fuse_a && pl.log2R == 2)
             return conj ? launch(coop_conv_kernel<LG, IO, NWV, NB, true, 2>, res[2])
                         : launch(coop_conv_kernel<LG, IO, NWV, NB, false, 2>, res[3]);
@@ -1961,8 +1970,9 @@ hipError_t coop_dk_rows_go(const void* dy, const void* u, __half2* ws_A, float* 
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_dk_rows_kernel<LG, IO, LR>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((coop_dk_rows_kernel<LG, IO, LR>), dim3((unsigned)(pr.H << LR)), dim3(C::NW * 64), lds, st,
-                       (const T*)dy, (const T*)u, ws_A, dD, pr.B, pr.H, pr.N, pr.npairs, tb.tw,
+    const int nch = pr.B == 1 ? (1 << LR) / 2 + 1 : (1 << LR);
+    hipLaunchKernelGGL((coop_dk_rows_kernel<LG, IO, LR>), dim3((unsigned)(pr.H * nch)), dim3(C::NW * 64), lds, st,
+                       (const T*)dy, (const T*)u, ws_A, dD, pr.B, pr.H, pr.N, pr.npairs, nch, tb.tw,
                        (const unsigned char*)tb.ctab);
     return hipGetLastError();
 }
@@ -1987,6 +1997,7 @@ hipError_t coop_kspec_go(const float* k, const __half2* ws, const float* D, cons
     };
     if (pl.log2R == 0) return launch_rows(coop_kspec_rows_kernel<LG, 0>);
     if constexpr (LG == COOP_MAX_LOG2) {      // pass A inside
+        if (pl.fuse_a && pl.log2R == 1) return launch_rows(coop_kspec_rows_kernel<LG, 1>);
         if (pl.fuse_a && pl.log2R == 2) return launch_rows(coop_kspec_rows_kernel<LG, 2>);
         if (pl.fuse_a && pl.log2R == 3) return launch_rows(coop_kspec_rows_kernel<LG, 3>);
     }
@@ -2056,7 +2067,10 @@ hipError_t coop_dk_rows(const void* dy, const void* u, __half2* ws_A, float* dD,
                         const Tables& tb, hipStream_t st, float* scale_c)
 {
     if (!coop_dk_rows_ok(pl)) return hipErrorInvalidValue;
-    if (pl.log2R == 2) {
+    if (pl.log2R == 1) {
+        if (pr.io == LONGCONV_F16) return coop_dk_rows_go<IoF16, 2>(dy, u, ws_A, dD, pr, tb, st, scale_c);
+        if (pr.io == LONGCONV_BF16) return coop_dk_rows_go<IoBF16, 2>(dy, u, ws_A, dD, pr, tb, st, scale_c);
+    } else if (pl.log2R == 2) {
         if (pr.io == LONGCONV_F16) return coop_dk_rows_go<IoF16, 3>(dy, u, ws_A, dD, pr, tb, st, scale_c);
         if (pr.io == LONGCONV_BF16) return coop_dk_rows_go<IoBF16, 3>(dy, u, ws_A, dD, pr, tb, st, scale_c);
     } else {

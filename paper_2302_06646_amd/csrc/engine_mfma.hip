@@ -542,7 +542,7 @@ void mfma_fill_plan(Plan& pl)
     pl.dkscale = 1.0f / (L * c * c * c);
     // outer radix 4 or 8 around the 32768-point cooperative kernels: the convolutions take pass A in their
     // staging (switch fuse_pass_a = 0 keeps the separate pass, for comparison)
-    pl.fuse_a = pl.order.coop_lg == COOP_MAX_LOG2 && (pl.log2R == 2 || pl.log2R == 3) && opt.fuse_pass_a;
+    pl.fuse_a = pl.order.coop_lg == COOP_MAX_LOG2 && pl.log2R >= 1 && pl.log2R <= 3 && opt.fuse_pass_a;
     // one backward kernel where a wave group holds a head's accumulators (switch fuse_bwd = 0: separate kernels)
     pl.fuse_bwd = pl.order.wave_lg && pl.log2R == 0 && opt.fuse_bwd;
 }

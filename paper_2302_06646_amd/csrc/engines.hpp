@@ -39,8 +39,10 @@ hipError_t head_max(const float* k, float* mx, int64_t H, int64_t N, hipStream_t
 int outer_fwd_blocks_per_head(const Problem& pr, int log2L2);
 // Pass C: rows of `out` <- scale * sum_{k1} conj(w_R^(n1*k1) w_L^(n2*k1)) ws[...], n1 < R/2 only
 // (truncation to the first N samples); re -> row 2p, im -> row 2p+1.
+// herm: every row is a single real row whose chunks above R/2 were not computed; they are taken as the complex
+// conjugates of chunks R - k1 (Hermitian spectrum of real data).
 hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
-                     bool ws_f16, const float2* tw, hipStream_t st);
+                     bool ws_f16, const float2* tw, hipStream_t st, bool herm = false);
 // dD[h] = sum_b sum_t dy[b,h,t] u[b,h,t], plain fp32 dot product (one workgroup per head).
 hipError_t head_dot(const void* dy, const void* u, float* dD, const Problem& pr, hipStream_t st);
 // dD[h] = sum of the per-block partials written by outer_fwd.
@@ -104,6 +106,14 @@ hipError_t wave_kspec(const float* k, const float* D, float2* kspec, int64_t H, 
 constexpr int COOP_MIN_LOG2 = 13, COOP_MAX_LOG2 = 15;
 hipError_t coop_fill_tables(const void** tab_out, hipStream_t st);
 // fuse_a (plans with pl.fuse_a only): the kernel reads the rows `in` and takes pass A itself.
+// Chunks of the multi-pass split that the inner convolution computes: all R, or, for a batch of one row with pass
+// A inside the kernel, only k1 <= R/2: a real row has a Hermitian spectrum, chunk R - k1 of pass C's input is the
+// complex conjugate of chunk k1, and pass C (outer_inv with herm = true) takes it from there.
+inline int coop_conv_chunks(const Problem& pr, const Plan& pl, bool fuse_a)
+{
+    const int R = 1 << pl.log2R;
+    return (fuse_a && pr.B == 1 && pl.log2R >= 2) ? R / 2 + 1 : R;
+}
 hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws, bool conj, bool fuse_a,
                      const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st);
 // Multi-pass dk straight from the rows, for plans of outer radix 4 or 8 around 32768 points with pl.fuse_a: run as
@@ -111,7 +121,7 @@ hipError_t coop_conv(const void* in, const float2* kspec, void* out, __half2* ws
 // log2L2 - 1), dD (may be null) the heads' dot products, *scale_c the factor pass C applies.
 inline bool coop_dk_rows_ok(const Plan& pl)
 {
-    return pl.fuse_a && (pl.log2R == 2 || pl.log2R == 3) && pl.log2L2 == COOP_MAX_LOG2;
+    return pl.fuse_a && pl.log2R >= 1 && pl.log2R <= 3 && pl.log2L2 == COOP_MAX_LOG2;
 }
 hipError_t coop_dk_rows(const void* dy, const void* u, __half2* ws_A, float* dD, const Problem& pr, const Plan& pl,
                         const Tables& tb, hipStream_t st, float* scale_c);

@@ -84,7 +84,7 @@ __global__ void outer_fwd_kernel(const typename IO::T* __restrict__ in, const ty
 template <class IO, class CW, int LOG2R>
 __global__ void outer_inv_kernel(const typename CW::T* __restrict__ ws, typename IO::T* __restrict__ out,
                                  int64_t B, int64_t H, int64_t N, int npairs, int log2L2, float scale,
-                                 const float2* __restrict__ tw)
+                                 const float2* __restrict__ tw, int herm)
 {
     constexpr int R = 1 << LOG2R, RH = R / 2;
     const int L2 = 1 << log2L2;
@@ -100,7 +100,9 @@ __global__ void outer_inv_kernel(const typename CW::T* __restrict__ ws, typename
 #pragma unroll
     for (int k1 = 0; k1 < R; ++k1) {
         const float2 wl = tw_full(tw, ((uint32_t)n2 * (uint32_t)k1) << (TW_LOG2 - log2L));
-        v[k1] = cmulc(CW::ld(ws, base + (size_t)k1 * L2 + n2), wl);
+        // herm: chunks above R/2 were not computed; untwisted, they are the conjugates of their mirror chunks
+        if (herm && k1 > RH) v[k1] = make_float2(v[R - k1].x, -v[R - k1].y);
+        else v[k1] = cmulc(CW::ld(ws, base + (size_t)k1 * L2 + n2), wl);
     }
 #pragma unroll 1
     for (int n1 = 0; n1 < RH; ++n1) {
@@ -156,7 +158,7 @@ template <class IO, int LOG2R>
 __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restrict__ ws,
                                                         typename IO::T* __restrict__ out, int64_t B, int64_t H,
                                                         int64_t N, int npairs, int log2L2, float scale,
-                                                        const float2* __restrict__ tw)
+                                                        const float2* __restrict__ tw, int herm)
 {
     static_assert(LOG2R >= 1 && LOG2R <= 4, "the roots of unity of rot16");
     constexpr int R = 1 << LOG2R, RH = R / 2;
@@ -175,6 +177,13 @@ __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restric
     for (int j = 0; j < VEC; ++j) w1[j] = tw_full(tw, (uint32_t)(n2 + j) << (TW_LOG2 - log2L));
 #pragma unroll
     for (int k1 = 0; k1 < R; ++k1) {
+        // herm (single real rows): chunks above R/2 were not computed; untwisted, chunk k1 is the complex
+        // conjugate of chunk R - k1 (Hermitian spectrum of real data)
+        if (k1 > RH && herm) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) v[k1][j] = make_float2(v[R - k1][j].x, -v[R - k1][j].y);
+            continue;
+        }
         uint32_t qw[4];
         mu::load_words<VEC>(src + (size_t)k1 * L2, qw);
 #pragma unroll
@@ -285,7 +294,7 @@ hipError_t fwd_launch(const void* in, const void* in2, void* ws, void* ws2, floa
 
 template <class IO, class CW, int LOG2R>
 hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, float scale, const float2* tw,
-                      hipStream_t st)
+                      hipStream_t st, int herm)
 {
     using T = typename IO::T;
     using C = typename CW::T;
@@ -294,13 +303,13 @@ hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, 
         if ((1 << log2L2) >= VEC * OB) {
             dim3 grid4((unsigned)(((size_t)1 << log2L2) / (VEC * OB) * (size_t)pr.npairs * (size_t)pr.H));
             hipLaunchKernelGGL((outer_inv4_kernel<IO, LOG2R>), grid4, dim3(OB), 0, st, (const __half2*)ws, (T*)out,
-                               pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw);
+                               pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm);
             return hipGetLastError();
         }
     }
     dim3 grid((unsigned)(((size_t)1 << log2L2) / OB * (size_t)pr.npairs * (size_t)pr.H));
     hipLaunchKernelGGL((outer_inv_kernel<IO, CW, LOG2R>), grid, dim3(OB), 0, st, (const C*)ws, (T*)out, pr.B,
-                       pr.H, pr.N, pr.npairs, log2L2, scale, tw);
+                       pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm);
     return hipGetLastError();
 }
 
@@ -324,9 +333,9 @@ hipError_t fwd_r(const void* in, const void* in2, void* ws, void* ws2, float* dD
 }
 template <class IO, class CW>
 hipError_t inv_r(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
-                 const float2* tw, hipStream_t st)
+                 const float2* tw, hipStream_t st, int herm)
 {
-#define CALL(LR) inv_launch<IO, CW, LR>(ws, out, pr, log2L2, scale, tw, st)
+#define CALL(LR) inv_launch<IO, CW, LR>(ws, out, pr, log2L2, scale, tw, st, herm)
     LC_R_SWITCH(CALL)
 #undef CALL
 }
@@ -354,10 +363,10 @@ hipError_t outer_fwd(const void* in, const void* in2, void* ws, void* ws2, float
 }
 
 hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, int log2L2, float scale,
-                     bool ws_f16, const float2* tw, hipStream_t st)
+                     bool ws_f16, const float2* tw, hipStream_t st, bool herm)
 {
     if ((1 << log2L2) < OB) return hipErrorInvalidValue;
-#define GO(IO, CW) return inv_r<IO, CW>(ws, out, pr, log2R, log2L2, scale, tw, st)
+#define GO(IO, CW) return inv_r<IO, CW>(ws, out, pr, log2R, log2L2, scale, tw, st, herm ? 1 : 0)
     if (ws_f16) {
         if (pr.io == LONGCONV_F32) GO(IoF32, CwF16);
         if (pr.io == LONGCONV_F16) GO(IoF16, CwF16);

@@ -1,0 +1,138 @@
+"""Length sweep and block-size-table shape on one MI355X: `python -m paper_2302_06646_amd.sweep [--quick]`.
+
+Two measurements that mirror the paper's efficiency experiments (Section 5.4 runtime figure: one layer, batch 32,
+128 heads, N = 1K ... 128K, against the FFT-library convolution; Table of block sizes: N = 4096, B = 128, H = 32),
+on synthetic data:
+
+  * forward time of this library (cached spectrum, and with the spectrum recomputed) against the same
+    convolution through torch.fft (rocFFT: rfft of the padded fp32 copy, multiply, irfft, truncate, skip term),
+    the analogue of the paper's cuFFT baseline.  Context only: the torch.fft route is not the oracle and is
+    never on the product path.
+  * forward, backward and whole-step time at the block-size table's shape, with the factorisation the plan
+    picks (the library runs 16-point blocks on the matrix cores and shorter last blocks as block-diagonal
+    16 x 16 matrices).
+
+Each timing: rotating buffer sets (HBM-cold), `steps` calls between two events on the launch stream.
+Prints a markdown table and one JSON line per row.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+import torch
+
+import paper_2302_06646_amd as lc
+
+F16 = lc.F16
+
+
+def _timed(steps, fn):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(steps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps * 1e3      # microseconds
+
+
+def _sets(B, H, N, want_bytes=640 << 20, backward=False):
+    per = (4 if backward else 2) * B * H * N * 2
+    n = max(2, min(8, -(-want_bytes // per)))
+    g = torch.Generator(device="cuda").manual_seed(N)
+    mk = lambda: torch.randn((B, H, N), generator=g, device="cuda", dtype=torch.float32).to(torch.float16)
+    return n, [mk() for _ in range(n)], [torch.empty((B, H, N), device="cuda", dtype=torch.float16) for _ in range(n)]
+
+
+def fft_conv_time(u_sets, k, D, steps):
+    """The FFT-library convolution: y = irfft(rfft(u, 2N) * rfft(k, 2N))[:N] + D u, fp32 transforms of fp16 data,
+    kernel spectrum precomputed (as for the cached-spectrum column)."""
+    N = k.shape[-1]
+    kf = torch.fft.rfft(k, n=2 * N)
+    outs = [torch.empty_like(u) for u in u_sets]
+
+    def fn(i):
+        j = i % len(u_sets)
+        u = u_sets[j].float()
+        y = torch.fft.irfft(torch.fft.rfft(u, n=2 * N) * kf, n=2 * N)[..., :N] + D[None, :, None] * u
+        outs[j].copy_(y)
+    fn(0)
+    return _timed(steps, fn)
+
+
+def sweep_row(B, H, N, steps):
+    io = F16
+    nsets, us, ys = _sets(B, H, N)
+    k = torch.randn(H, N, device="cuda") / N ** 0.5
+    D = torch.randn(H, device="cuda")
+    ks = lc.new_kspec(H, N, io)
+    ws = lc.new_workspace(B, H, N, io, False)
+    lc.longconv_kspec_compute(k, D, ks, io, ws)
+    warm = lambda i: lc.longconv_fwd(us[i % nsets], k, D, ys[i % nsets], ws, kspec=ks)
+    cold = lambda i: lc.longconv_fwd(us[i % nsets], k, D, ys[i % nsets], ws)
+    for i in range(3):
+        warm(i); cold(i)
+    t_warm, t_cold = _timed(steps, warm), _timed(steps, cold)
+    t_fft = fft_conv_time(us, k, D, max(3, steps // 4))
+    bytes_fwd = 2 * B * H * N * 2 + 4 * H * N + 4 * H
+    return {"B": B, "H": H, "N": N, "plan": lc.longconv_plan_string(N, io), "fwd_cached_spectrum_us": t_warm,
+            "fwd_with_spectrum_us": t_cold, "torch_fft_conv_us": t_fft, "speedup_vs_fft_library": t_fft / t_warm,
+            "fwd_GBps": bytes_fwd / t_warm / 1e3, "pct_hbm_roofline": 100 * bytes_fwd / t_warm / 1e3 / 8000.0}
+
+
+def table_shape(B, H, N, steps):
+    io = F16
+    nsets, us, ys = _sets(B, H, N, backward=True)
+    _, dys, dus = _sets(B, H, N, backward=True)
+    k = torch.randn(H, N, device="cuda") / N ** 0.5
+    D = torch.randn(H, device="cuda")
+    dk, dD = torch.empty_like(k), torch.empty_like(D)
+    ks = lc.new_kspec(H, N, io)
+    ws = lc.new_workspace(B, H, N, io, True)
+    kspec = lambda i: lc.longconv_kspec_compute(k, D, ks, io, ws)
+    fwd = lambda i: lc.longconv_fwd(us[i % nsets], k, D, ys[i % nsets], ws, kspec=ks)
+    bwd = lambda i: lc.longconv_bwd(dys[i % nsets], us[i % nsets], k, D, dus[i % nsets], dk, dD, ws, kspec=ks)
+    for i in range(3):
+        kspec(i); fwd(i); bwd(i)
+    t = {"kspec_us": _timed(steps, kspec), "fwd_us": _timed(steps, fwd), "bwd_us": _timed(steps, bwd)}
+    t_fft = fft_conv_time(us, k, D, max(3, steps // 4))
+    L = 2 * N
+    # executed matrix-core flops of the forward pass: 8 instructions of 16384 flop per 256-point tile and half
+    # transform (four 16-point stages, the last one block-diagonal), two half transforms per row pair
+    mf = H * ((B + 1) // 2) * 2 * 8 * 16384 * (L / 256)
+    return {"B": B, "H": H, "N": N, "plan": lc.longconv_plan_string(N, io), **t, "torch_fft_conv_fwd_us": t_fft,
+            "fwd_executed_mfma_GFLOP": mf / 1e9, "fwd_mfma_TFLOPs": mf / t["fwd_us"] / 1e6,
+            "fwd_mfma_pct_of_peak": 100 * mf / t["fwd_us"] / 1e6 / 2500.0}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--quick", action="store_true", help="fewer steps and lengths")
+    a = ap.parse_args()
+    if not torch.cuda.is_available():
+        print("sweep: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    lc.longconv_init()
+    steps = 10 if a.quick else 30
+    lengths = [1024, 16384, 131072] if a.quick else [1024, 2048, 4096, 8192, 16384, 32768, 65536, 131072]
+    rows = [sweep_row(32, 128, N, steps) for N in lengths]
+    print("| N | plan | fwd, cached spectrum (us) | fwd + spectrum (us) | torch.fft conv (us) | speed-up | GB/s | % of 8 TB/s |")
+    print("|---|---|---|---|---|---|---|---|")
+    for r in rows:
+        print(f"| {r['N']} | {r['plan'].split('digits=')[-1]} | {r['fwd_cached_spectrum_us']:.1f} | {r['fwd_with_spectrum_us']:.1f} | "
+              f"{r['torch_fft_conv_us']:.1f} | {r['speedup_vs_fft_library']:.1f}x | {r['fwd_GBps']:.0f} | {r['pct_hbm_roofline']:.1f} |")
+    t = table_shape(128, 32, 4096, steps)
+    print()
+    print("| shape | plan | kspec (us) | fwd (us) | bwd (us) | torch.fft conv fwd (us) | fwd executed MFMA GFLOP | TFLOP/s | % of 2.5 PFLOP/s |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    print(f"| B=128 H=32 N=4096 fp16 | {t['plan'].split('digits=')[-1]} | {t['kspec_us']:.1f} | {t['fwd_us']:.1f} | {t['bwd_us']:.1f} | "
+          f"{t['torch_fft_conv_fwd_us']:.1f} | {t['fwd_executed_mfma_GFLOP']:.1f} | {t['fwd_mfma_TFLOPs']:.0f} | {t['fwd_mfma_pct_of_peak']:.1f} |")
+    for r in rows + [t]:
+        print(json.dumps(r))
+
+
+if __name__ == "__main__":
+    main()

@@ -227,3 +227,23 @@ def test_few_heads_batch_dealt_to_several_workgroups(N, B, H, io):
         assert np.array_equal(dk1, dk0) and np.array_equal(dD1, dD0) and np.array_equal(du1, du0)
     dk_only = g.bwd(du=False)[1].copy()              # partial request: the separate dk kernel, also dealt out
     assert wl.rel_l2(dk_only, dk0) <= 2 * 3e-3
+
+
+@pytest.mark.parametrize("io", [wl.F16, wl.BF16])
+@pytest.mark.parametrize("N", [32768, 65536, 131072])
+def test_single_row_batch_uses_the_hermitian_symmetry_of_its_chunks(N, io):
+    """B = 1 in the multi-pass split: the row is real, so chunk R - k1 of the outer split is the complex conjugate
+    of chunk k1; the inner kernels compute the chunks up to R/2 only and pass C fills in the rest.  Against the
+    oracle, and against the plan with the separate pass A, which computes every chunk."""
+    from gpu_harness import GpuRun, TOL, check_full
+    inp = wl.generate(_w("4a", N=N, dtype=io), B=1, H=3 if N < 131072 else 2)
+    check_full(inp, label=f"single row N={N} io={wl.DTYPE_NAMES[io]}")
+    g = GpuRun(inp)
+    y = g.fwd().copy()
+    du, dk, dD = (a.copy() for a in g.bwd())
+    _opt("fuse_pass_a", 0)
+    g2 = GpuRun(inp)
+    y2 = g2.fwd()
+    du2, dk2, dD2 = g2.bwd()
+    tol = 2 * TOL[io]
+    assert wl.rel_l2(y, y2) <= tol and wl.rel_l2(du, du2) <= tol and wl.rel_l2(dk, dk2) <= tol
