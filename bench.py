@@ -227,6 +227,20 @@ def copy_bandwidth(torch, nbytes=1 << 30, reps=10):
     return 2 * nbytes / (ms * 1e-3) / 1e9
 
 
+def copy_probe(torch):
+    """Reference dispatches for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters (only with --copy-probe):
+    a contiguous 64 MiB device copy (whole 128-byte lines), and a copy that reads every other 64-byte segment of a
+    64 MiB buffer (32 MiB read in 64-byte requests, 32 MiB written)."""
+    n = (64 << 20) // 4
+    src = torch.zeros(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    half = torch.empty(n // 2, dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        dst.copy_(src)
+        half.view(-1, 16).copy_(src.view(-1, 2, 16)[:, 0, :])
+    torch.cuda.synchronize()
+
+
 def cpu_baseline(key):
     """The float64 oracle, as it stands, on the host cores: whole workload if it is a few seconds of
     work, otherwise all batch rows of a subset of heads (cost is linear in heads)."""
@@ -256,6 +270,8 @@ def main():
     ap.add_argument("--workload", default="3", choices=list(wl.WORKLOADS))
     ap.add_argument("--also", default="4a,2", help="comma list of further workloads reported under 'targets'")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run two copies of known size (reference for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
@@ -268,6 +284,8 @@ def main():
         sys.exit(1)
     lc.longconv_init()
     copy_gbs = copy_bandwidth(torch)
+    if a.copy_probe:
+        copy_probe(torch)
 
     res = run_workload(a.workload, a.steps, a.warmup, lc, torch)
     log(json.dumps(res, indent=1))
