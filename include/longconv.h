@@ -32,14 +32,18 @@
  *     which then synchronises `stream` once).
  *   - Return value: LONGCONV_OK or an error code; argument validation happens
  *     before anything is launched.  No exceptions, no aborts.
- *   - fp16/bf16 I/O computes with fp16 matrix-core operands and fp32 accumulation;
- *     the data are not rescaled on the way, so u, dy and the transformed data must
- *     stay inside fp16's normal range: activations and gradients of order one
- *     (unit variance up to N = 131072 is fine) and |FFT(k) + D| within about
- *     2^-8 .. 2^8.  Far outside that range precision is lost silently (bf16
- *     gradients of order 1e-5, say, should be scaled up by the caller and dk, du
- *     scaled back).  The kernel k itself may have any magnitude: its spectrum is
- *     computed from a per-head power-of-two rescaling.  fp32 I/O computes in fp32.
+ *   - fp16/bf16 I/O computes with fp16 matrix-core operands and fp32 accumulation.
+ *     bf16 rows (u, dy) may have any magnitude for N <= 16384: every row whose largest
+ *     sample lies outside 2^-2 .. 2^4 is multiplied by a power of two on its way into the
+ *     transform and by its inverse on the way out, row by row, so gradients of order
+ *     1e-10 or activations of order 1e6 keep the accuracy of data of order one (two rows
+ *     inside that band share one fp16 scale: their error is relative to the larger of the
+ *     two).  Not rescaled, and therefore to be kept inside fp16's normal range by the
+ *     caller: fp16 rows (order one is fine up to N = 131072; the transform grows them by at
+ *     most sqrt(2N)), bf16 rows for N >= 32768, and the spectrum, |FFT(k) + D| within about
+ *     2^-8 .. 2^8.  Far outside those ranges precision is lost silently.  The kernel k
+ *     itself may have any magnitude on its way into the spectrum (per-head power-of-two
+ *     rescaling).  fp32 I/O computes in fp32.
  */
 #ifndef LONGCONV_H
 #define LONGCONV_H

@@ -39,10 +39,32 @@ def build(verbose: bool = True) -> str:
     os.makedirs(objdir, exist_ok=True)
     objs = [os.path.join(objdir, os.path.basename(s)[:-4] + ".o") for s in srcs]
     cflags = [f for f in FLAGS if f != "-shared"]
+    # -save-temps=obj leaves the device assembly of every source next to its object file, for the hazard check
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        list(ex.map(lambda so: _run([HIPCC, *cflags, "-c", so[0], "-o", so[1]], verbose), zip(srcs, objs)))
+        list(ex.map(lambda so: _run([HIPCC, *cflags, "-save-temps=obj", "-c", so[0], "-o", so[1]], verbose),
+                    zip(srcs, objs)))
+    check_assembly(objdir, srcs, verbose)
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], verbose)
     return LIB
+
+
+def check_assembly(objdir: str, srcs, verbose: bool = True) -> None:
+    """Every kernel's assembly must keep the issue distance between an MFMA and the readers of its result
+    (see isa_check.py); a violation is a build error."""
+    from . import isa_check
+    bad, seen = [], 0
+    for s in srcs:
+        stem = os.path.basename(s)[:-4]
+        for asm in glob.glob(os.path.join(objdir, stem + "-hip-amdgcn-amd-amdhsa-gfx950*.s")):
+            seen += 1
+            bad += [(stem,) + b for b in isa_check.check_file(asm)]
+    if seen == 0:
+        raise RuntimeError("no device assembly found in " + objdir + ": the hazard check could not run")
+    if bad:
+        raise RuntimeError("MFMA result read too early in:\n" + "\n".join(
+            f"  {b[0]}: {b[1]}: {b[2]} slots: {b[3]} -> {b[4]}" for b in bad))
+    if verbose:
+        print(f"assembly hazard check ok ({seen} files)", flush=True)
 
 
 if __name__ == "__main__":

@@ -495,13 +495,38 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             if (!has_b) pb[i] = make_uint4(0u, 0u, 0u, 0u);
         }
     };
-    auto stage = [&]() {
+    // bf16 rows outside the band 2^-2 .. 2^4 are scaled by a power of two on the way in and back on the way out.
+    // The pair is staged unscaled first; every wave publishes the band test of the words it fetched (two patterns
+    // and a flag byte), and after the barrier that makes the staged pair visible one LDS read tells all waves
+    // whether any of them saw a row outside the band.  Only then the maxima are combined and the pair is staged
+    // again from the registers, with its scales.
+    __shared__ uint32_t dr_mx[2 * NWV + 2];          // [NWV][2] patterns, then NWV flag bytes
+    auto measure = [&]() {
+        uint32_t m[2] = {0u, 0u};
+#pragma unroll
+        for (int i = 0; i < RPL; ++i) {
+            m[0] = absmax_acc(absmax_acc(absmax_acc(absmax_acc(m[0], pa[i].x), pa[i].y), pa[i].z), pa[i].w);
+            m[1] = absmax_acc(absmax_acc(absmax_acc(absmax_acc(m[1], pb[i].x), pb[i].y), pb[i].z), pb[i].w);
+        }
+        band_or_exact<2>(m);
+        if (lane == 0) {
+            dr_mx[2 * wave] = m[0];
+            dr_mx[2 * wave + 1] = m[1];
+            reinterpret_cast<unsigned char*>(dr_mx + 2 * NWV)[wave] = rows_in_band(m[0], m[1]) ? 0 : 1;
+        }
+    };
+    auto stage = [&](int ea, int eb) {
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             uint32_t wa[4] = {pa[i].x, pa[i].y, pa[i].z, pa[i].w}, wb[4] = {pb[i].x, pb[i].y, pb[i].z, pb[i].w};
             if (IsBf<IO>::v) {
+                if (__builtin_expect((ea | eb) != 0, 0)) {
 #pragma unroll
-                for (int m = 0; m < 4; ++m) { wa[m] = bf2_to_h2(wa[m]); wb[m] = bf2_to_h2(wb[m]); }
+                    for (int m = 0; m < 4; ++m) { wa[m] = bf2_to_h2_scaled(wa[m], ea); wb[m] = bf2_to_h2_scaled(wb[m], eb); }
+                } else {
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) { wa[m] = bf2_to_h2(wa[m]); wb[m] = bf2_to_h2(wb[m]); }
+                }
             }
             const int a0 = slot(i);
 #pragma unroll
@@ -511,7 +536,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             }
         }
     };
-    auto drain = [&](int it) {
+    auto drain = [&](int it, int ea, int eb) {
         const int h = it / npairs, p = it - h * npairs;
         const bool has_b = (2 * p + 1) < B;
         const size_t oa = row_off(2 * p, h, H, N), ob = row_off(2 * p + 1, h, H, N);
@@ -532,6 +557,12 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
                     wb[m] = pack_bf2((float)b.h[0], (float)b.h[1]);
                 }
             }
+            if constexpr (IsBf<IO>::v) {
+                if (__builtin_expect((ea | eb) != 0, 0)) {
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) { wa[m] = bf2_rescaled(wa[m], ea); wb[m] = bf2_rescaled(wb[m], eb); }
+                }
+            }
             store_words<4>(out + oa + n, wa);
             if (has_b) store_words<4>(out + ob + n, wb);
         }
@@ -540,12 +571,33 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
     if (it0 < it1) fetch(it0);       // first pair on its way while the tables are built
     staged_tables<LG, NT>(lds4, gtab, tw, tid, 0);
     __syncthreads();                 // tables and cleared slots in place
-    if (it0 < it1) stage();
+    if (it0 < it1) {
+        if constexpr (IsBf<IO>::v) measure();
+        stage(0, 0);
+    }
     for (int it = it0; it < it1; ++it) {
         const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) +
                                                          (size_t)(it / npairs) * C::L);
         asm volatile("" : "+s"(ks));
         __syncthreads();             // staged pair visible
+        int ea = 0, eb = 0;          // exponents of the two rows of this pair
+        if constexpr (IsBf<IO>::v) {
+            static_assert(NWV == 4 || NWV == 8, "flag bytes are read as one or two words");
+            uint32_t f = dr_mx[2 * NWV];
+            if constexpr (NWV == 8) f |= dr_mx[2 * NWV + 1];
+            if (__builtin_expect(__builtin_amdgcn_readfirstlane((int)f) != 0, 0)) {
+                uint32_t ma = 0u, mb = 0u;
+#pragma unroll
+                for (int w = 0; w < NWV; ++w) { ma = max(ma, dr_mx[2 * w]); mb = max(mb, dr_mx[2 * w + 1]); }
+                ma = (uint32_t)__builtin_amdgcn_readfirstlane((int)ma);
+                mb = (uint32_t)__builtin_amdgcn_readfirstlane((int)mb);
+                if (!rows_in_band(ma, mb)) { ea = row_exponent(ma); eb = row_exponent(mb); }
+                if ((ea | eb) != 0) {
+                    stage(ea, eb);
+                    __syncthreads();
+                }
+            }
+        }
 
         // ---- phase 1, in place
 #pragma unroll 1
@@ -608,8 +660,11 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             }
         }
         __syncthreads();
-        drain(it);
-        if (more) stage();
+        drain(it, ea, eb);
+        if (more) {
+            if constexpr (IsBf<IO>::v) measure();
+            stage(0, 0);
+        }
     }
 }
 
@@ -1084,13 +1139,20 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                          :: "s"(lds_off), "v"(lane * 16), "s"(sbase) : "memory", "m0");
         }
     };
-    // raw area -> exchange slots (pair packing, bf16 -> fp16, twist)
-    auto stage = [&](int sidx) {
+    // bf16 rows outside the band 2^-2 .. 2^4 are scaled by powers of two (see pair_scales): every source is staged
+    // unscaled first while each wave runs the band test on the words it stages (two patterns and a flag byte
+    // into dr_mx); after the barrier that makes the staged source visible one LDS read tells all waves whether
+    // any of them saw a row outside the band, and only then the source is staged again, with its scales, from
+    // the raw area (the next copy waits for that).
+    __shared__ uint32_t dr_mx[2 * C::NW + 2];        // [NW][2] patterns, then NW flag bytes
+    // raw area -> exchange slots (pair packing, bf16 -> fp16 times 2^-ea / 2^-eb, twist)
+    auto stage = [&](int sidx, int ea, int eb, bool measure) {
         const int p = ((sidx >> 1) % npairs) * nsplit + split;
         const bool has_b = (2 * p + 1) < B;
         const bool odd = SPLIT && sidx >= 2 * npairs;
         int t_ = tid;
         asm volatile("" : "+v"(t_));                 // addresses are recomputed here, not carried through the walk
+        uint32_t mx[2] = {0u, 0u};
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             const int n = staged_run_n<LG>(i * NT + t_);
@@ -1102,8 +1164,17 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                 for (int m = 0; m < 4; ++m) wb[m] = 0u;
             }
             if (IsBf<IO>::v) {
+                if (measure) {
 #pragma unroll
-                for (int m = 0; m < 4; ++m) { wa[m] = bf2_to_h2(wa[m]); wb[m] = bf2_to_h2(wb[m]); }
+                    for (int m = 0; m < 4; ++m) { mx[0] = absmax_acc(mx[0], wa[m]); mx[1] = absmax_acc(mx[1], wb[m]); }
+                }
+                if (__builtin_expect((ea | eb) != 0, 0)) {
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) { wa[m] = bf2_to_h2_scaled(wa[m], ea); wb[m] = bf2_to_h2_scaled(wb[m], eb); }
+                } else {
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) { wa[m] = bf2_to_h2(wa[m]); wb[m] = bf2_to_h2(wb[m]); }
+                }
             }
             uint32_t x[8];
 #pragma unroll
@@ -1122,6 +1193,28 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
             const int a0 = staged_slot<LG>(n);
 #pragma unroll
             for (int e = 0; e < 8; ++e) xb[a0 + 4 * e] = x[e];
+        }
+        if (IsBf<IO>::v && measure) {
+            band_or_exact<2>(mx);
+            if (lane == 0) {
+                dr_mx[2 * wave] = mx[0];
+                dr_mx[2 * wave + 1] = mx[1];
+                reinterpret_cast<unsigned char*>(dr_mx + 2 * C::NW)[wave] = rows_in_band(mx[0], mx[1]) ? 0 : 1;
+            }
+        }
+    };
+    // after the barrier behind a measured stage: the pair's two patterns (the stand-in unless a wave flagged)
+    auto staged_patterns = [&](uint32_t& ma, uint32_t& mb) {
+        static_assert(C::NW == 4 || C::NW == 8, "flag bytes are read as one or two words");
+        ma = mb = BAND_LOW;
+        uint32_t f = dr_mx[2 * C::NW];
+        if constexpr (C::NW == 8) f |= dr_mx[2 * C::NW + 1];
+        if (__builtin_expect(__builtin_amdgcn_readfirstlane((int)f) != 0, 0)) {
+            uint32_t a = 0u, b = 0u;
+#pragma unroll
+            for (int w = 0; w < C::NW; ++w) { a = max(a, dr_mx[2 * w]); b = max(b, dr_mx[2 * w + 1]); }
+            ma = (uint32_t)__builtin_amdgcn_readfirstlane((int)a);
+            mb = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
         }
     };
 
@@ -1144,11 +1237,15 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
     copy_in(0);
 
     int sidx = 0;
+    int eref = EXP_NONE;                                 // bf16 rows: the accumulators are in units of 2^eref
 #pragma unroll 1
     for (int par = 0; par < NPAR; ++par) {
+        eref = EXP_NONE;
 #pragma unroll 1
         for (int p = 0; p < npairs; ++p) {
             uint32_t z[8][4];
+            uint32_t mua = BAND_LOW, mub = BAND_LOW;     // patterns of the u rows (first source of the pair)
+            int ep = 0;                                  // conj(Z) W of this pair is in units of 2^ep
 #pragma unroll
             for (int pass = 0; pass < 2; ++pass, ++sidx) {
                 int zoff = 0;
@@ -1187,11 +1284,44 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
-                stage(sidx);
+                stage(sidx, 0, 0, true);
                 __syncthreads();                         // staged source visible, raw area free
+                if constexpr (IsBf<IO>::v) {
+                    int ea = 0, eb = 0;
+                    if (pass == 0) {                     // u rows: normalised one by one
+                        staged_patterns(mua, mub);
+                        if (__builtin_expect(!rows_in_band(mua, mub), 0)) { ea = row_exponent(mua); eb = row_exponent(mub); }
+                    } else {                             // dy rows: what is left of the pair's common exponent
+                        uint32_t mda, mdb;
+                        staged_patterns(mda, mdb);
+                        if (__builtin_expect(!(rows_in_band(mua, mub) && rows_in_band(mda, mdb)), 0)) {
+                            const PairScales ps = pair_scales(mua, mub, mda, mdb);
+                            ea = ps.xa; eb = ps.xb; ep = ps.ep;
+                        }
+                    }
+                    if (__builtin_expect((ea | eb) != 0, 0)) {
+                        stage(sidx, ea, eb, false);
+                        __syncthreads();
+                    }
+                }
                 if (sidx + 1 < nsrc) copy_in(sidx + 1);
                 phase1_inplace<LG, 2>(xb, t1f_, vt_, F1, K.F16, cF, t0, lane);
                 __syncthreads();
+                if (IsBf<IO>::v && pass == 1) {
+                    // this pair's term against the accumulators: times 2^down, applied to the waiting Z (a term that
+                    // much smaller than the sum loses nothing that matters when its small parts underflow)
+                    const int down = dk_term_align<8>(acc, eref, ep);
+                    if (__builtin_expect(down != 0, 0)) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                union { uint32_t u; h2 hh; } cv;
+                                cv.u = z[i][j];
+                                z[i][j] = pack_h2(ldexpf((float)cv.hh[0], down), ldexpf((float)cv.hh[1], down));
+                            }
+                    }
+                }
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     f4 zr, zi;
@@ -1287,6 +1417,10 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                 if (!SPLIT || par == 1) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) v[e] *= dkscale;
+                    if constexpr (IsBf<IO>::v) {         // both walks meet the same pairs: the same eref
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = ldexpf(v[e], eref == EXP_NONE ? 0 : eref);
+                    }
                 }
                 dst[0] = make_float4(v[0], v[1], v[2], v[3]);
                 dst[1] = make_float4(v[4], v[5], v[6], v[7]);

@@ -163,11 +163,26 @@ __device__ __forceinline__ void load_inputs(InRegs<LG, PB>& r, const typename IO
         }
 }
 
+// running maximum of |x| per row (a, b) of every pair over the raw words of one tile group
+template <int LG, int PB>
+__device__ __forceinline__ void rows_absmax(const InRegs<LG, PB>& r, uint32_t (&ma)[PB], uint32_t (&mb)[PB])
+{
+#pragma unroll
+    for (int q = 0; q < PB; ++q)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < WC<LG>::NWD; ++i) {
+                ma[q] = absmax_acc(ma[q], r.wa[q][j][i]);
+                mb[q] = absmax_acc(mb[q], r.wb[q][j][i]);
+            }
+}
+
 // Phase 1 on one tile group: two chained DFT stages -> exchange buffer `xb`.  NT tiles x PB pairs
 // are advanced together, stage by stage, so that independent MFMA / ALU / LDS work overlaps.
 template <int LG, class IO, int PB>
 __device__ __forceinline__ void phase1_group(InRegs<LG, PB>& r, int tg, uint32_t* xb, const uint4* tab,
-                                             const Mats& F16, int lane)
+                                             const Mats& F16, int lane, const int (&ea)[PB], const int (&eb)[PB])
 {
     using C = WC<LG>;
     constexpr int NT = (4 / PB) < C::TG ? (4 / PB) : C::TG;   // tiles advanced together (x PB pairs)
@@ -176,14 +191,25 @@ __device__ __forceinline__ void phase1_group(InRegs<LG, PB>& r, int tg, uint32_t
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
     if (IsBf<IO>::v) {
 #pragma unroll
-        for (int q = 0; q < PB; ++q)
+        for (int q = 0; q < PB; ++q) {
+            if (__builtin_expect((ea[q] | eb[q]) != 0, 0)) {     // a row outside the band: powers of two on the way in (wave-uniform)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int i = 0; i < C::NWD; ++i) {
-                    r.wa[q][j][i] = bf2_to_h2(r.wa[q][j][i]);
-                    r.wb[q][j][i] = bf2_to_h2(r.wb[q][j][i]);
-                }
+                    for (int i = 0; i < C::NWD; ++i) {
+                        r.wa[q][j][i] = bf2_to_h2_scaled(r.wa[q][j][i], ea[q]);
+                        r.wb[q][j][i] = bf2_to_h2_scaled(r.wb[q][j][i], eb[q]);
+                    }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int i = 0; i < C::NWD; ++i) {
+                        r.wa[q][j][i] = bf2_to_h2(r.wa[q][j][i]);
+                        r.wb[q][j][i] = bf2_to_h2(r.wb[q][j][i]);
+                    }
+            }
+        }
     }
 #pragma unroll
     for (int tb = 0; tb < C::TG; tb += NT) {
@@ -315,11 +341,34 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
         const Rows<PB> Rc = R;
         const int hcur = h;
 
+        // bf16 rows: largest magnitude of every row -> power-of-two scales in and out (1 inside the band)
+        int ea[PB], eb[PB];
+#pragma unroll
+        for (int q = 0; q < PB; ++q) ea[q] = eb[q] = 0;
+        if constexpr (IsBf<IO>::v) {
+            uint32_t ma[PB], mb[PB];
+#pragma unroll
+            for (int q = 0; q < PB; ++q) ma[q] = mb[q] = 0u;
+#pragma unroll
+            for (int tg = C::TG; tg < C::TC; tg += C::TG) {     // tile groups that phase 1 loads later: read for the maximum
+                InRegs<LG, PB> peek;
+                load_inputs<LG, IO, PB>(peek, in, Rc, tg, lane);
+                rows_absmax<LG, PB>(peek, ma, mb);
+            }
+            rows_absmax<LG, PB>(inr, ma, mb);
+#pragma unroll
+            for (int q = 0; q < PB; ++q) {
+                uint32_t m2[2] = {ma[q], mb[q]};
+                band_or_exact<2>(m2);
+                if (__builtin_expect(!rows_in_band(m2[0], m2[1]), 0)) { ea[q] = row_exponent(m2[0]); eb[q] = row_exponent(m2[1]); }
+            }
+        }
+
         // ---------------- phase 1 ----------------
 #pragma unroll
         for (int tg = 0; tg < C::TC; tg += C::TG) {
             if (tg > 0) load_inputs<LG, IO, PB>(inr, in, Rc, tg, lane);
-            phase1_group<LG, IO, PB>(inr, tg, xb, tab, F16, lane);
+            phase1_group<LG, IO, PB>(inr, tg, xb, tab, F16, lane, ea, eb);
         }
         // the next group's rows start travelling now and land while phases 2 and 3 run
         if (gi_ + 1 < gpw && group + 1 < total_groups) {
@@ -425,6 +474,19 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
                             }
                         }
             }
+            if constexpr (IsBf<IO>::v) {     // a row outside the band gets its power of two back, on the packed values
+#pragma unroll
+                for (int q = 0; q < PB; ++q)
+                    if (__builtin_expect((ea[q] | eb[q]) != 0, 0)) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+#pragma unroll
+                            for (int i = 0; i < C::NWD; ++i) {
+                                oa[q][j][i] = bf2_rescaled(oa[q][j][i], ea[q]);
+                                ob[q][j][i] = bf2_rescaled(ob[q][j][i], eb[q]);
+                            }
+                    }
+            }
             if (g < 2) {     // n_a < 8: the first N samples
 #pragma unroll
                 for (int q = 0; q < PB; ++q)
@@ -515,24 +577,93 @@ __device__ __forceinline__ float raw_dot(const In<TPW>& a, const In<TPW>& b, flo
     return s;
 }
 
+// Scales of the pair a group of NWP waves is about to transform (bf16 rows).  Both sources' raw words are in
+// registers at the top of an iteration and not earlier (asking sooner would stall on the prefetch), and a
+// barrier right there would cost the slack the waves have between their loads and the first barrier of the
+// iteration.  So the first source's phase 1 runs unscaled on the assumption that all rows are in the band,
+// every wave publishes the patterns of the band test on its own words (four words and a flag byte), and after
+// the iteration's first barrier one LDS read of the flags tells every wave of the workgroup whether any wave
+// saw a row outside the band.  Only then (rare; the same decision in every wave, so the extra barrier is
+// uniform) the group's maxima are combined, the scales computed and the first source's phase 1 repeated with
+// them from rows read again.  With one wave per pair nothing is exchanged and nothing is assumed.
+// top of the iteration: patterns of this wave's words -> LDS (mxs: [NWV][4] words, then NWV flag bytes)
+template <int NWV, int TPW>
+__device__ __forceinline__ void publish_patterns(const In<TPW>& first, const In<TPW>& second, uint32_t* mxs, int wave,
+                                                 int lane, uint4& mine)
+{
+    uint32_t m[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < TPW / 2; ++i) {
+            m[0] = absmax_acc(m[0], first.wa[j][i]);
+            m[1] = absmax_acc(m[1], first.wb[j][i]);
+            m[2] = absmax_acc(m[2], second.wa[j][i]);
+            m[3] = absmax_acc(m[3], second.wb[j][i]);
+        }
+    band_or_exact<4>(m);
+    mine = make_uint4(m[0], m[1], m[2], m[3]);
+    const bool in_band = rows_in_band(mine.x, mine.y) && rows_in_band(mine.z, mine.w);
+    if (lane == 0) {
+        *reinterpret_cast<uint4*>(&mxs[4 * wave]) = mine;
+        reinterpret_cast<unsigned char*>(mxs + 4 * NWV)[wave] = in_band ? 0 : 1;
+    }
+}
+// after the barrier: did any wave of the workgroup see a row outside the band?
+template <int NWV>
+__device__ __forceinline__ bool any_out_of_band(const uint32_t* mxs)
+{
+    static_assert(NWV == 4 || NWV == 8, "flag bytes are read as one or two words");
+    uint32_t f = mxs[4 * NWV];
+    if constexpr (NWV == 8) f |= mxs[4 * NWV + 1];
+    return __builtin_amdgcn_readfirstlane((int)f) != 0;
+}
+// the group's maxima -> scales (slow path)
+template <int NWP>
+__device__ __forceinline__ PairScales group_scales(const uint32_t* mxs, int wave)
+{
+    const int w0 = (wave / NWP) * NWP;
+    uint4 m = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+    for (int w = 0; w < NWP; ++w) {
+        const uint4 v = *reinterpret_cast<const uint4*>(&mxs[4 * (w0 + w)]);
+        m.x = max(m.x, v.x); m.y = max(m.y, v.y); m.z = max(m.z, v.z); m.w = max(m.w, v.w);
+    }
+    const uint32_t mfa = (uint32_t)__builtin_amdgcn_readfirstlane((int)m.x), mfb = (uint32_t)__builtin_amdgcn_readfirstlane((int)m.y);
+    const uint32_t msa = (uint32_t)__builtin_amdgcn_readfirstlane((int)m.z), msb = (uint32_t)__builtin_amdgcn_readfirstlane((int)m.w);
+    PairScales ps = {0, 0, 0, 0, 0};
+    if (!(rows_in_band(mfa, mfb) && rows_in_band(msa, msb))) ps = pair_scales(mfa, mfb, msa, msb);
+    return ps;
+}
 
 // Phase 1 on the wave's TPW tiles, advanced together stage by stage: [A-role F16 over d_a],
 // w_L twiddle, [B-role per-tile matrix over d_b] -> exchange buffer (one 16-byte write per tile).
 template <int LG, class IO, int TPW>
-__device__ __forceinline__ void w_phase1(In<TPW>& r, uint32_t* xb, const WK<LG, TPW>& K, int t0, int lane)
+__device__ __forceinline__ void w_phase1(In<TPW>& r, uint32_t* xb, const WK<LG, TPW>& K, int t0, int lane,
+                                         int ea = 0, int eb = 0)
 {
     using C = WC<LG>;
     const int c = lane & 15, g = lane >> 4;
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     const int w1 = (c * C::PITCH + g * C::TC) * 4;
     if (IsBf<IO>::v) {
+        if (__builtin_expect((ea | eb) != 0, 0)) {     // a row outside the band: powers of two on the way in (uniform over the pair's waves)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int i = 0; i < TPW / 2; ++i) {
-                r.wa[j][i] = bf2_to_h2(r.wa[j][i]);
-                r.wb[j][i] = bf2_to_h2(r.wb[j][i]);
-            }
+                for (int i = 0; i < TPW / 2; ++i) {
+                    r.wa[j][i] = bf2_to_h2_scaled(r.wa[j][i], ea);
+                    r.wb[j][i] = bf2_to_h2_scaled(r.wb[j][i], eb);
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < TPW / 2; ++i) {
+                    r.wa[j][i] = bf2_to_h2(r.wa[j][i]);
+                    r.wb[j][i] = bf2_to_h2(r.wb[j][i]);
+                }
+        }
     }
     f4 yr[TPW], yi[TPW], zr[TPW], zi[TPW];
 #pragma unroll
@@ -652,6 +783,9 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
     uint32_t* xd = lds + (size_t)(grp * 2 + 1) * C::PAIR_WORDS;      // dy pair
     float2* red = reinterpret_cast<float2*>(lds + (size_t)NGRP * 2 * C::PAIR_WORDS);   // [wave][TPW*4][64]
     float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWV]
+    uint32_t* mxs = reinterpret_cast<uint32_t*>(dred + 8);                                 // [NWV][4] row patterns, NWV flag bytes (bf16 rows)
+    int* erefs = reinterpret_cast<int*>(dred + 44);                                        // [NGRP] exponents of the partial A
+    static_assert(NWV <= 8, "layout of the small LDS arrays");
     // workgroup (head h, share `split` of nsplit): the head's pairs split, split + nsplit, ...; with nsplit > 1
     // dk and dD point to partial buffers [nsplit][H][N] and [nsplit][H], summed afterwards in share order
     const int h = blockIdx.x % (unsigned)H, split = blockIdx.x / (unsigned)H;
@@ -690,14 +824,39 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
         for (int j = 0; j < 4; ++j) acc[k][j] = make_float2(0.f, 0.f);
 
     float dsum = 0.f;
+    int eref = EXP_NONE;
     const int niter = (npairs + NGRP - 1) / NGRP;      // same for every group: barriers stay uniform
     for (int it = 0; it < niter; ++it) {
         const bool act = it * NGRP + grp < npairs;
         const int pnext = (it + 1) * NGRP + grp;
+        PairScales ps = {0, 0, 0, 0, 0};      // u rows normalised one by one, dy rows take the rest
+        if constexpr (IsBf<IO>::v) {
+            uint4 mine;
+            publish_patterns<NWV, TPW>(inu, ind, mxs, wave, lane, mine);
+            if constexpr (NWP == 1) {
+                if (__builtin_expect(!(rows_in_band(mine.x, mine.y) && rows_in_band(mine.z, mine.w)), 0))
+                    ps = pair_scales(mine.x, mine.y, mine.z, mine.w);
+            }
+        }
         if (act) dsum = raw_dot<IO, TPW>(inu, ind, dsum);    // both raw rows of the pair are in registers here
-        if (act) w_phase1<LG, IO, TPW>(inu, xa, K, t0, lane);
+        if (act) w_phase1<LG, IO, TPW>(inu, xa, K, t0, lane, ps.efa, ps.efb);
         if (pnext < npairs) load_src(pnext, u, inu);
         pair_sync<NWP>();
+        if constexpr (IsBf<IO>::v && NWP > 1) {
+            if (__builtin_expect(any_out_of_band<NWV>(mxs), 0)) {
+                ps = group_scales<NWP>(mxs, wave);
+                if (act && (ps.efa | ps.efb) != 0) {      // phase 1 of the u pair again, this time with its scales
+                    In<TPW> again;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int i = 0; i < TPW / 2; ++i) again.wa[j][i] = again.wb[j][i] = 0u;
+                    load_src(it * NGRP + grp, u, again);
+                    w_phase1<LG, IO, TPW>(again, xa, K, t0, lane, ps.efa, ps.efb);
+                }
+                __syncthreads();
+            }
+        }
         uint32_t z[TPW][4];
         if (act) {
             f4 yr[TPW], yi[TPW];
@@ -706,24 +865,39 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
             for (int k = 0; k < TPW; ++k)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) z[k][j] = pack_h2(yr[k][j], yi[k][j]);
-            w_phase1<LG, IO, TPW>(ind, xd, K, t0, lane);
+            w_phase1<LG, IO, TPW>(ind, xd, K, t0, lane, ps.xa, ps.xb);
         }
         if (pnext < npairs) load_src(pnext, dy, ind);
         pair_sync<NWP>();
         if (act) {
             f4 yr[TPW], yi[TPW];
             w_phase2_fwd<LG, TPW>(xd, K, ad, yr, yi);
+            int down = 0;
+            if constexpr (IsBf<IO>::v) down = dk_term_align<TPW>(acc, eref, ps.ep);
+            if (__builtin_expect(down != 0, 0)) {
 #pragma unroll
-            for (int k = 0; k < TPW; ++k)
+                for (int k = 0; k < TPW; ++k)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    union { uint32_t u; h2 h; } cv;
-                    cv.u = z[k][j];
-                    const float zr = (float)cv.h[0], zi = (float)cv.h[1];
-                    // conj(Z) * W, one fused multiply-add per term (the fp16 -> fp32 converts fold into them)
-                    acc[k][j].x = __builtin_fmaf(zi, yi[k][j], __builtin_fmaf(zr, yr[k][j], acc[k][j].x));
-                    acc[k][j].y = __builtin_fmaf(-zi, yr[k][j], __builtin_fmaf(zr, yi[k][j], acc[k][j].y));
-                }
+                    for (int j = 0; j < 4; ++j) {
+                        union { uint32_t u; h2 h; } cv;
+                        cv.u = z[k][j];
+                        const float zr = ldexpf((float)cv.h[0], down), zi = ldexpf((float)cv.h[1], down);
+                        acc[k][j].x = __builtin_fmaf(zi, yi[k][j], __builtin_fmaf(zr, yr[k][j], acc[k][j].x));
+                        acc[k][j].y = __builtin_fmaf(-zi, yr[k][j], __builtin_fmaf(zr, yi[k][j], acc[k][j].y));
+                    }
+            } else {
+#pragma unroll
+                for (int k = 0; k < TPW; ++k)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        union { uint32_t u; h2 h; } cv;
+                        cv.u = z[k][j];
+                        const float zr = (float)cv.h[0], zi = (float)cv.h[1];
+                        // conj(Z) * W, one fused multiply-add per term (the fp16 -> fp32 converts fold into them)
+                        acc[k][j].x = __builtin_fmaf(zi, yi[k][j], __builtin_fmaf(zr, yr[k][j], acc[k][j].x));
+                        acc[k][j].y = __builtin_fmaf(-zi, yr[k][j], __builtin_fmaf(zr, yi[k][j], acc[k][j].y));
+                    }
+            }
         }
     }
 
@@ -734,16 +908,26 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
         for (int j = 0; j < 4; ++j) red[((size_t)(wave * TPW + k) * 4 + j) * 64 + lane] = acc[k][j];
     for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
     if (lane == 0) dred[wave] = dsum;
+    if (IsBf<IO>::v && lane == 0 && wave % NWP == 0) erefs[grp] = eref;
     __syncthreads();
+    int etop = 0;                                      // bf16 rows: the partial A come in units of 2^erefs[group]
+    if constexpr (IsBf<IO>::v) {
+        etop = erefs[0];
+#pragma unroll
+        for (int gi = 1; gi < NGRP; ++gi) etop = max(etop, erefs[gi]);
+        etop = __builtin_amdgcn_readfirstlane(etop);
+    }
     if (grp == 0) {
 #pragma unroll
         for (int k = 0; k < TPW; ++k)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 float2 s = acc[k][j];
+                if constexpr (IsBf<IO>::v) { s.x = ldexpf(s.x, eref - etop); s.y = ldexpf(s.y, eref - etop); }
 #pragma unroll
                 for (int gi = 1; gi < NGRP; ++gi) {
-                    const float2 v = red[((size_t)((gi * NWP + wave) * TPW + k) * 4 + j) * 64 + lane];
+                    float2 v = red[((size_t)((gi * NWP + wave) * TPW + k) * 4 + j) * 64 + lane];
+                    if constexpr (IsBf<IO>::v) { v.x = ldexpf(v.x, erefs[gi] - etop); v.y = ldexpf(v.y, erefs[gi] - etop); }
                     s.x += v.x; s.y += v.y;
                 }
                 acc[k][j] = s;
@@ -775,7 +959,7 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
             if (g < 2) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    dk[ho * N + (4 * g + j) * 16 * C::TC + c * C::TC + t0 + k] = r[j] * dkscale;
+                    dk[ho * N + (4 * g + j) * 16 * C::TC + c * C::TC + t0 + k] = ldexpf(r[j] * dkscale, etop);
             }
         }
     }
@@ -788,7 +972,7 @@ hipError_t wdk_go(const void* dy, const void* u, float* dk, float* dD, int nspli
     using T = typename IO::T;
     using C = WC<LG>;
     constexpr int NWP = C::TC / TPW, NGRP = NWV / NWP;
-    const size_t lds = (size_t)NGRP * 2 * C::PAIR_WORDS * 4 + (size_t)NWV * TPW * 4 * 64 * 8 + 64;
+    const size_t lds = (size_t)NGRP * 2 * C::PAIR_WORDS * 4 + (size_t)NWV * TPW * 4 * 64 * 8 + 256;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wdk_kernel<LG, IO, TPW, NWV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -845,6 +1029,9 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
     uint32_t* stg1 = stg0 + STW;
     float2* red = reinterpret_cast<float2*>(lds + (size_t)NGRP * (3 * C::PAIR_WORDS + 2 * STW));   // [wave][TPW*4][64]
     float* dred = reinterpret_cast<float*>(red + (size_t)NWV * TPW * 4 * 64);             // [NWV]
+    uint32_t* mxs = reinterpret_cast<uint32_t*>(dred + 8);                                 // [NWV][4] row patterns, NWV flag bytes (bf16 rows)
+    int* erefs = reinterpret_cast<int*>(dred + 44);                                        // [NGRP] exponents of the partial A
+    static_assert(NWV <= 8, "layout of the small LDS arrays");
     // workgroup (head h, share `split` of nsplit) as in wdk_kernel
     const int h = blockIdx.x % (unsigned)H, split = blockIdx.x / (unsigned)H;
     const int npairs = (npairs_all - split + nsplit - 1) / nsplit;
@@ -900,15 +1087,40 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
         *reinterpret_cast<uint4*>(du + row_off(b0, h, H, N) + n) = v;
     };
     float dsum = 0.f;                                  // dD: dot product of the raw rows, fp32
+    int eref = EXP_NONE;
     const int niter = (npairs + NGRP - 1) / NGRP;      // same for every group: barriers stay uniform
     for (int it = 0; it < niter; ++it) {
         const int p = it * NGRP + grp, pnext = p + NGRP;
         const bool act = p < npairs;
         uint32_t* xd = (it & 1) ? xd1 : xd0;
+        PairScales ps = {0, 0, 0, 0, 0};      // dy rows normalised one by one (du needs that), u rows take the rest
+        if constexpr (IsBf<IO>::v) {
+            uint4 mine;
+            publish_patterns<NWV, TPW>(ind, inu, mxs, wave, lane, mine);
+            if constexpr (NWP == 1) {
+                if (__builtin_expect(!(rows_in_band(mine.x, mine.y) && rows_in_band(mine.z, mine.w)), 0))
+                    ps = pair_scales(mine.x, mine.y, mine.z, mine.w);
+            }
+        }
         if (act) dsum = raw_dot<IO, TPW>(inu, ind, dsum);    // both raw rows of the pair are in registers here
-        if (act) w_phase1<LG, IO, TPW>(ind, xd, K, t0, lane);
+        if (act) w_phase1<LG, IO, TPW>(ind, xd, K, t0, lane, ps.efa, ps.efb);
         if (pnext < npairs) load_src(pnext, dy, ind);
         pair_sync<NWP>();
+        if constexpr (IsBf<IO>::v && NWP > 1) {
+            if (__builtin_expect(any_out_of_band<NWV>(mxs), 0)) {
+                ps = group_scales<NWP>(mxs, wave);
+                if (act && (ps.efa | ps.efb) != 0) {      // phase 1 of the dy pair again, this time with its scales
+                    In<TPW> again;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int i = 0; i < TPW / 2; ++i) again.wa[j][i] = again.wb[j][i] = 0u;
+                    load_src(p, dy, again);
+                    w_phase1<LG, IO, TPW>(again, xd, K, t0, lane, ps.efa, ps.efb);
+                }
+                __syncthreads();
+            }
+        }
         if (it > 0) flush_du(it - 1);
         f4 wr[TPW], wi[TPW];                             // W of the wave's tiles, fp32 until it meets Z
         if (act) {
@@ -923,7 +1135,7 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
 #pragma unroll
                 for (int j = 0; j < 4; ++j) xd[ad[k][j]] = pack_h2(zr[j], zi[j]);
             }
-            w_phase1<LG, IO, TPW>(inu, xa, K, t0, lane);
+            w_phase1<LG, IO, TPW>(inu, xa, K, t0, lane, ps.xa, ps.xb);
         }
         if (pnext < npairs) load_src(pnext, u, inu);
         pair_sync<NWP>();
@@ -932,25 +1144,52 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
             f4 r[TPW], s[TPW];
 #pragma unroll
             for (int k = 0; k < TPW; ++k) w_phase3_tile<LG, TPW, true>(xd, K, t0, k, lane, r[k], s[k]);
+            // the words of the two rows; a row outside the band gets its power of two back on the packed values
+            // (the scales never meet the matrix-core results directly: no register copies at a branch behind an MFMA)
+            uint32_t wa[4], wb[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                wa[j] = IsBf<IO>::v ? pack_bf2(r[0][j], r[1][j]) : pack_h2(r[0][j], r[1][j]);
+                wb[j] = IsBf<IO>::v ? pack_bf2(s[0][j], s[1][j]) : pack_h2(s[0][j], s[1][j]);
+            }
+            if constexpr (IsBf<IO>::v) {
+                if (__builtin_expect((ps.efa | ps.efb) != 0, 0)) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) { wa[j] = bf2_rescaled(wa[j], ps.efa); wb[j] = bf2_rescaled(wb[j], ps.efb); }
+                }
+            }
             if (g < 2) {     // n_a < 8: the first N samples
                 uint32_t* stg = (it & 1) ? stg1 : stg0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int n0 = (4 * g + j) * 16 * C::TC + c * C::TC + t0;
-                    stg[n0 / 2] = IsBf<IO>::v ? pack_bf2(r[0][j], r[1][j]) : pack_h2(r[0][j], r[1][j]);
-                    stg[STW / 2 + n0 / 2] = IsBf<IO>::v ? pack_bf2(s[0][j], s[1][j]) : pack_h2(s[0][j], s[1][j]);
+                    stg[n0 / 2] = wa[j];
+                    stg[STW / 2 + n0 / 2] = wb[j];
                 }
             }
             f4 yr[TPW], yi[TPW];
             w_phase2_fwd<LG, TPW>(xa, K, ad, yr, yi);
+            int down = 0;
+            if constexpr (IsBf<IO>::v) down = dk_term_align<TPW>(acc, eref, ps.ep);
+            if (__builtin_expect(down != 0, 0)) {
 #pragma unroll
-            for (int k = 0; k < TPW; ++k)
+                for (int k = 0; k < TPW; ++k)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    // conj(Z) * W, one fused multiply-add per term
-                    acc[k][j].x = __builtin_fmaf(yi[k][j], wi[k][j], __builtin_fmaf(yr[k][j], wr[k][j], acc[k][j].x));
-                    acc[k][j].y = __builtin_fmaf(-yi[k][j], wr[k][j], __builtin_fmaf(yr[k][j], wi[k][j], acc[k][j].y));
-                }
+                    for (int j = 0; j < 4; ++j) {
+                        const float wrs = ldexpf(wr[k][j], down), wis = ldexpf(wi[k][j], down);
+                        acc[k][j].x = __builtin_fmaf(yi[k][j], wis, __builtin_fmaf(yr[k][j], wrs, acc[k][j].x));
+                        acc[k][j].y = __builtin_fmaf(-yi[k][j], wrs, __builtin_fmaf(yr[k][j], wis, acc[k][j].y));
+                    }
+            } else {
+#pragma unroll
+                for (int k = 0; k < TPW; ++k)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        // conj(Z) * W, one fused multiply-add per term
+                        acc[k][j].x = __builtin_fmaf(yi[k][j], wi[k][j], __builtin_fmaf(yr[k][j], wr[k][j], acc[k][j].x));
+                        acc[k][j].y = __builtin_fmaf(-yi[k][j], wr[k][j], __builtin_fmaf(yr[k][j], wi[k][j], acc[k][j].y));
+                    }
+            }
         }
     }
 
@@ -961,17 +1200,27 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
         for (int j = 0; j < 4; ++j) red[((size_t)(wave * TPW + k) * 4 + j) * 64 + lane] = acc[k][j];
     for (int o = 32; o > 0; o >>= 1) dsum += __shfl_down(dsum, o, 64);
     if (lane == 0) dred[wave] = dsum;
+    if (IsBf<IO>::v && lane == 0 && wave % NWP == 0) erefs[grp] = eref;
     __syncthreads();
     flush_du(niter - 1);
+    int etop = 0;                                      // bf16 rows: the partial A come in units of 2^erefs[group]
+    if constexpr (IsBf<IO>::v) {
+        etop = erefs[0];
+#pragma unroll
+        for (int gi = 1; gi < NGRP; ++gi) etop = max(etop, erefs[gi]);
+        etop = __builtin_amdgcn_readfirstlane(etop);
+    }
     if (grp == 0) {
 #pragma unroll
         for (int k = 0; k < TPW; ++k)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 float2 sum = acc[k][j];
+                if constexpr (IsBf<IO>::v) { sum.x = ldexpf(sum.x, eref - etop); sum.y = ldexpf(sum.y, eref - etop); }
 #pragma unroll
                 for (int gi = 1; gi < NGRP; ++gi) {
-                    const float2 v = red[((size_t)((gi * NWP + wave) * TPW + k) * 4 + j) * 64 + lane];
+                    float2 v = red[((size_t)((gi * NWP + wave) * TPW + k) * 4 + j) * 64 + lane];
+                    if constexpr (IsBf<IO>::v) { v.x = ldexpf(v.x, erefs[gi] - etop); v.y = ldexpf(v.y, erefs[gi] - etop); }
                     sum.x += v.x; sum.y += v.y;
                 }
                 acc[k][j] = sum;
@@ -1003,7 +1252,7 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
             if (g < 2) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    dk[ho * N + (4 * g + j) * 16 * C::TC + c * C::TC + t0 + k] = r[j] * dkscale;
+                    dk[ho * N + (4 * g + j) * 16 * C::TC + c * C::TC + t0 + k] = ldexpf(r[j] * dkscale, etop);
             }
         }
     }
@@ -1016,7 +1265,7 @@ hipError_t wbwd_go(const void* dy, const void* u, const float2* kspec, void* du,
     using T = typename IO::T;
     using C = WC<LG>;
     constexpr int NWP = C::TC / TPW, NGRP = NWV / NWP;
-    const size_t lds = (size_t)NGRP * (3 * C::PAIR_WORDS + C::L) * 4 + (size_t)NWV * TPW * 4 * 64 * 8 + 64;
+    const size_t lds = (size_t)NGRP * (3 * C::PAIR_WORDS + C::L) * 4 + (size_t)NWV * TPW * 4 * 64 * 8 + 256;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wbwd_kernel<LG, IO, TPW, NWV>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -1166,7 +1415,10 @@ hipError_t wconv_io(const void* in, const float2* kspec, void* out, bool conj, c
     switch (pl.log2L2) {
         case 9: return wconv_go<9, IO, 2, 8>(in, kspec, out, conj, pr, tb, st);
         case 10: return wconv_go<10, IO, 2, 8>(in, kspec, out, conj, pr, tb, st);
-        case 11: return wconv_go<11, IO, 1, 12>(in, kspec, out, conj, pr, tb, st);
+        case 11:
+            // bf16: the band test of the rows needs a few registers more than three waves per SIMD leave
+            if (IsBf<IO>::v) return wconv_go<11, IO, 1, 8>(in, kspec, out, conj, pr, tb, st);
+            return wconv_go<11, IO, 1, 12>(in, kspec, out, conj, pr, tb, st);
         case 12: return wconv_go<12, IO, 1, 3>(in, kspec, out, conj, pr, tb, st);
         default: return hipErrorInvalidValue;
     }

@@ -39,6 +39,137 @@ __device__ __forceinline__ uint32_t bf2_to_h2(uint32_t w)
 {
     return pack_h2(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
 }
+// ---------------------------------------------------------------------------------
+// Dynamic range of bf16 rows.  The transforms carry fp16 between their stages, and bf16 data (gradients of
+// order 1e-6, activations of order 1e4) need not fit fp16's exponent range; the two rows that share a complex
+// transform may also differ by many orders of magnitude, and the smaller one would drown in the rounding of
+// the larger.  Every row whose largest magnitude lies outside 2^-2 .. 2^4 is therefore brought to the magnitude
+// of unit-variance data by a power of two on its way into the first stage and taken back on the way out (exact in both
+// directions); rows inside that band are not touched, and a pair of such rows runs the instruction stream
+// without any scaling.
+// ---------------------------------------------------------------------------------
+// Running maximum of |x| over words of two 16-bit floats.  bf16 and fp16 are both sign-magnitude, so the
+// larger magnitude has the larger low 15 bits whichever way the bits are read: the comparison runs as a
+// packed fp16 maximum of (acc, x, -x), one instruction per word (v_pk_maximum3_f16).
+__device__ __forceinline__ uint32_t absmax_acc(uint32_t acc, uint32_t w)
+{
+    union { uint32_t u; h2 h; } a, x;
+    a.u = acc; x.u = w;
+    a.h = __builtin_elementwise_maximum(__builtin_elementwise_maximum(a.h, x.h), -x.h);
+    return a.u;
+}
+// both halves and all 64 lanes -> one 15-bit magnitude pattern, the same in every lane (all lanes active)
+__device__ __forceinline__ uint32_t absmax_wave(uint32_t acc)
+{
+    uint32_t m = max(acc & 0x7fffu, (acc >> 16) & 0x7fffu);
+    m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0xB1, 0xf, 0xf, true));    // quad_perm [1,0,3,2]
+    m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x4E, 0xf, 0xf, true));    // quad_perm [2,3,0,1]
+    m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x141, 0xf, 0xf, true));   // row_half_mirror
+    m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x140, 0xf, 0xf, true));   // row_mirror
+    const uint32_t r0 = __builtin_amdgcn_readlane((int)m, 0), r1 = __builtin_amdgcn_readlane((int)m, 16);
+    const uint32_t r2 = __builtin_amdgcn_readlane((int)m, 32), r3 = __builtin_amdgcn_readlane((int)m, 48);
+    return max(max(r0, r1), max(r2, r3));
+}
+// The band test without the reduction.  m[] = running maxima (two 16-bit patterns per word) of NR rows over the
+// words this wave holds.  If no sample is at or above 2^4 and some lane holds, in the odd samples of every row,
+// a value at or above 2^-2, the wave's part of all rows lies inside the band and the lower band edge stands in
+// for the maxima (a handful of compares: the usual case; the test for "large enough" is sufficient, not
+// necessary, and a row that fails it is merely measured exactly).  Otherwise m[] becomes the exact maxima of
+// the wave's words.  Maxima of several waves combine by max: an exact value outside the band wins over the
+// stand-in exactly when the row's true maximum is outside the band.
+constexpr uint32_t BAND_LOW = 0x3E80u, BAND_HIGH = 0x4180u;      // bf16 patterns of 2^-2 and 2^4
+template <int NR>
+__device__ __forceinline__ void band_or_exact(uint32_t (&m)[NR])
+{
+    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+    union { uint32_t u; us2 v; } hi, lo, x;
+    hi.u = lo.u = m[0];
+#pragma unroll
+    for (int r = 1; r < NR; ++r) {
+        x.u = m[r];
+        hi.v = __builtin_elementwise_max(hi.v, x.v);
+        lo.v = __builtin_elementwise_min(lo.v, x.v);
+    }
+    const bool big = __builtin_amdgcn_ballot_w64(hi.u >= (BAND_HIGH << 16) || (hi.u & 0xffffu) >= BAND_HIGH) != 0;
+    const bool large_enough = __builtin_amdgcn_ballot_w64(lo.u >= (BAND_LOW << 16)) != 0;
+    if (__builtin_expect(big || !large_enough, 0)) {
+#pragma unroll
+        for (int r = 0; r < NR; ++r) m[r] = absmax_wave(m[r]);
+    } else {
+#pragma unroll
+        for (int r = 0; r < NR; ++r) m[r] = BAND_LOW;
+    }
+}
+// after the maxima of all waves holding the row were combined: is the row inside the band?  (Waves publish
+// either the stand-in or an exact value outside the band, so the combined value is the stand-in exactly then.)
+__device__ __forceinline__ bool rows_in_band(uint32_t ma, uint32_t mb) { return ((ma ^ BAND_LOW) | (mb ^ BAND_LOW)) == 0u; }
+// Exponent e of the power of two 2^-e that brings a row whose largest bf16 magnitude pattern is m into
+// [2, 4), where the largest sample of a unit-variance row lies; 0 (no scaling) inside the band
+// 2^-2 <= max < 2^4 and for an all-zero row.
+__device__ __forceinline__ int row_exponent(uint32_t m)
+{
+    const int E = (int)(m >> 7);                     // biased exponent of the largest magnitude
+    if (m == 0u || (E >= 125 && E <= 130)) return 0;
+    return E - 128;
+}
+// word of two bf16 values of one row -> two fp16 values times 2^-e
+__device__ __forceinline__ uint32_t bf2_to_h2_scaled(uint32_t w, int e)
+{
+    return pack_h2(ldexpf(__uint_as_float(w << 16), -e), ldexpf(__uint_as_float(w & 0xffff0000u), -e));
+}
+// word of two bf16 values times 2^e (exact unless it leaves bf16's range)
+__device__ __forceinline__ uint32_t bf2_rescaled(uint32_t w, int e)
+{
+    return pack_bf2(ldexpf(__uint_as_float(w << 16), e), ldexpf(__uint_as_float(w & 0xffff0000u), e));
+}
+constexpr int EXP_NONE = -100000;      // "exponent" of something that is exactly zero
+
+// Scales of the two rows (a, b) of the two sources (u pair, dy pair) in the dk kernels.  dk sums
+// corr(u_a, dy_a) and corr(u_b, dy_b) out of one complex product, so both terms must carry the same power of
+// two: the rows of the source transformed first are normalised one by one (for dy that is what du needs), the
+// rows of the other source take what is left of the common exponent ep, the larger of the two rows' exponent
+// sums.  The term with the smaller sum arrives smaller than one by the difference, which is all the precision
+// it has in the sum anyway.
+struct PairScales {
+    int efa, efb;      // first source: its rows are multiplied by 2^-efa, 2^-efb
+    int xa, xb;        // second source: multiplied by 2^-xa, 2^-xb
+    int ep;            // conj(Z) W of this pair is in units of 2^ep (EXP_NONE: the pair contributes nothing)
+};
+__device__ __forceinline__ PairScales pair_scales(uint32_t mfa, uint32_t mfb, uint32_t msa, uint32_t msb)
+{
+    PairScales p;
+    p.efa = row_exponent(mfa);
+    p.efb = row_exponent(mfb);
+    const int pa = (mfa && msa) ? p.efa + row_exponent(msa) : EXP_NONE;
+    const int pb = (mfb && msb) ? p.efb + row_exponent(msb) : EXP_NONE;
+    p.ep = pa > pb ? pa : pb;
+    const int ec = p.ep == EXP_NONE ? 0 : p.ep;
+    p.xa = ec - p.efa;
+    p.xb = ec - p.efb;
+    return p;
+}
+
+// dk accumulators of pairs with different scales: A is kept in units of 2^eref, eref = the largest exponent sum
+// (u pair + dy pair) met so far.  A pair with a larger sum rescales A first; a pair with a smaller one has its
+// term scaled down by 2^(return value) (0 in the other cases).  Equal exponents, the usual case, cost one scalar
+// compare.  The matrix-core results themselves are not touched here: the caller applies the factor in a loop of
+// its own, so that no register copies sit at a branch right behind an MFMA.
+template <int TPW>
+__device__ __forceinline__ int dk_term_align(float2 (&acc)[TPW][4], int& eref, int ep)
+{
+    if (__builtin_expect(ep == eref, 1)) return 0;
+    if (ep > eref) {
+        const int d = eref - ep;
+#pragma unroll
+        for (int k = 0; k < TPW; ++k)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { acc[k][j].x = ldexpf(acc[k][j].x, d); acc[k][j].y = ldexpf(acc[k][j].y, d); }
+        eref = ep;
+        return 0;
+    }
+    return ep - eref;
+}
+
 // (yr + i yi) * w in packed fp16 (one convert, v_pk_mul_f16, v_pk_fma_f16); result as fp16 complex
 __device__ __forceinline__ uint32_t cmul_pack(float yr, float yi, h2 w)
 {
