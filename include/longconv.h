@@ -83,8 +83,8 @@ int longconv_init(void);
  * part of it, a cached spectrum is valid until k OR D changes. */
 size_t longconv_kspec_bytes(int64_t H, int64_t N, int io);
 
-/* Scratch bytes a call needs (0 on bad args).  `backward` = 0 for longconv_fwd,
- * 1 for longconv_bwd.  The figure includes room for an on-the-fly spectrum, so it
+/* Scratch bytes a call needs (0 on bad args).  `backward` = 0 for longconv_fwd and
+ * longconv_fwd_gated, 1 for longconv_bwd, 2 for longconv_bwd_gated.  The figure includes room for an on-the-fly spectrum, so it
  * is valid whether or not a cached spectrum is passed. */
 size_t longconv_workspace_bytes(int64_t B, int64_t H, int64_t N, int io, int backward);
 
@@ -128,6 +128,26 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
                  void* du, float* dk, float* dD,
                  int64_t B, int64_t H, int64_t N, int io,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Gated layer (Section 4.1: the language-model experiments use the long convolution inside an H3-style layer,
+ * which multiplies the outputs of its two sequence operators element by element as a gating mechanism; the
+ * paper gives no formula, the reading taken is an output gate):
+ *     z = (u * k)[:N] + D u          Eq. 1, as longconv_fwd
+ *     y[b,h,t] = g[b,h,t] * z[b,h,t]      g [B,H,N] in the I/O dtype
+ * Arguments as longconv_fwd plus the gate; y may not alias u or g. */
+int longconv_fwd_gated(const void* u, const float* k, const float* D, const void* kspec, const void* g, void* y,
+                       int64_t B, int64_t H, int64_t N, int io,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of the gated layer, by the product rule: with dz = dy * g,
+ *     du, dk, dD = the gradients of longconv_bwd for dz;      dg[b,h,t] = dy[b,h,t] * z[b,h,t]
+ * (z recomputed from u, k, D).  Any of du, dk, dD, dg may be NULL.  dz is rounded to the I/O dtype on its way
+ * into the backward pass.  Needs longconv_workspace_bytes(B,H,N,io,2) bytes (the backward workspace plus room
+ * for dz). */
+int longconv_bwd_gated(const void* dy, const void* g, const void* u, const float* k, const float* D,
+                       const void* kspec, void* du, float* dk, float* dD, void* dg,
+                       int64_t B, int64_t H, int64_t N, int io,
+                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* Kernel regularisers in front of the convolution (Algorithm 1 lines 1-3; Section 3.1,
  * "Regularizing the Kernel"), for the raw parameter K [H,N] f32:

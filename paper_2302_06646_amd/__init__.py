@@ -9,7 +9,8 @@ the functions raises.
 Functions mirror the C ABI of ``include/longconv.h``:
     longconv_init, longconv_kspec_bytes, longconv_workspace_bytes,
     longconv_kspec_compute, longconv_fwd, longconv_bwd, longconv_plan_string,
-    longconv_set_option, longconv_fwd_noalloc, longconv_kreg_fwd, longconv_kreg_bwd
+    longconv_set_option, longconv_fwd_noalloc, longconv_kreg_fwd, longconv_kreg_bwd,
+    longconv_fwd_gated, longconv_bwd_gated
 """
 from __future__ import annotations
 
@@ -29,7 +30,8 @@ _lib = None
 EXPORTS = ("longconv_init", "longconv_kspec_bytes", "longconv_workspace_bytes",
            "longconv_kspec_compute", "longconv_fwd", "longconv_bwd", "longconv_status_string",
            "longconv_last_hip_error", "longconv_plan_string", "longconv_set_option",
-           "longconv_fwd_noalloc", "longconv_kreg_fwd", "longconv_kreg_bwd")
+           "longconv_fwd_noalloc", "longconv_kreg_fwd", "longconv_kreg_bwd",
+           "longconv_fwd_gated", "longconv_bwd_gated")
 
 
 class LongconvError(RuntimeError):
@@ -67,6 +69,10 @@ def lib():
         L.longconv_kreg_fwd.argtypes = [vp, vp, vp, i64, i64, ci, ctypes.c_float, vp]
         L.longconv_kreg_bwd.restype = ci
         L.longconv_kreg_bwd.argtypes = [vp, vp, vp, vp, i64, i64, ci, ctypes.c_float, vp]
+        L.longconv_fwd_gated.restype = ci
+        L.longconv_fwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, sz, vp]
+        L.longconv_bwd_gated.restype = ci
+        L.longconv_bwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, sz, vp]
         L.longconv_set_option.restype = ci
         L.longconv_set_option.argtypes = [ctypes.c_char_p, ci]
         _lib = L
@@ -111,8 +117,9 @@ def longconv_kspec_bytes(H: int, N: int, io: int) -> int:
     return int(lib().longconv_kspec_bytes(H, N, io))
 
 
-def longconv_workspace_bytes(B: int, H: int, N: int, io: int, backward: bool) -> int:
-    return int(lib().longconv_workspace_bytes(B, H, N, io, 1 if backward else 0))
+def longconv_workspace_bytes(B: int, H: int, N: int, io: int, backward) -> int:
+    """backward: False / 0 forward, True / 1 backward, 2 gated backward."""
+    return int(lib().longconv_workspace_bytes(B, H, N, io, int(backward)))
 
 
 def longconv_plan_string(N: int, io: int) -> str:
@@ -176,6 +183,31 @@ def longconv_fwd(u, k, D, y, workspace, kspec=None, stream=None) -> None:
     _need(k, "k", torch.float32, (H, N)); _need(D, "D", torch.float32, (H,))
     _check(lib().longconv_fwd(_ptr(u), _ptr(k), _ptr(D), _ptr(kspec), _ptr(y), B, H, N, io,
                               _ptr(workspace), workspace.numel(), _stream(stream)), "longconv_fwd")
+
+
+def longconv_fwd_gated(u, k, D, g, y, workspace, kspec=None, stream=None) -> None:
+    """y <- g * ((u * k)[:N] + D u)."""
+    B, H, N = u.shape
+    io = dtype_code(u)
+    _need(u, "u", _TORCH_DTYPE[io], (B, H, N)); _need(y, "y", _TORCH_DTYPE[io], (B, H, N))
+    _need(g, "g", _TORCH_DTYPE[io], (B, H, N))
+    _need(k, "k", torch.float32, (H, N)); _need(D, "D", torch.float32, (H,))
+    _check(lib().longconv_fwd_gated(_ptr(u), _ptr(k), _ptr(D), _ptr(kspec), _ptr(g), _ptr(y), B, H, N, io,
+                                    _ptr(workspace), workspace.numel(), _stream(stream)), "longconv_fwd_gated")
+
+
+def longconv_bwd_gated(dy, g, u, k, D, du, dk, dD, dg, workspace, kspec=None, stream=None) -> None:
+    """du, dk, dD, dg <- gradients of the gated layer (any may be None).  The workspace must hold
+    longconv_workspace_bytes(B, H, N, io, 2) bytes."""
+    B, H, N = dy.shape
+    io = dtype_code(dy)
+    for t, name in ((dy, "dy"), (g, "g"), (u, "u"), (du, "du"), (dg, "dg")):
+        _need(t, name, _TORCH_DTYPE[io], (B, H, N))
+    _need(k, "k", torch.float32, (H, N)); _need(D, "D", torch.float32, (H,))
+    _need(dk, "dk", torch.float32, (H, N)); _need(dD, "dD", torch.float32, (H,))
+    _check(lib().longconv_bwd_gated(_ptr(dy), _ptr(g), _ptr(u), _ptr(k), _ptr(D), _ptr(kspec), _ptr(du), _ptr(dk),
+                                    _ptr(dD), _ptr(dg), B, H, N, io, _ptr(workspace), workspace.numel(),
+                                    _stream(stream)), "longconv_bwd_gated")
 
 
 STATIC_SCRATCH_BYTES = 64 << 20

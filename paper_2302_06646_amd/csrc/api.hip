@@ -209,6 +209,12 @@ static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool back
     return w;
 }
 
+static size_t io_bytes(int io) { return io == LONGCONV_F32 ? 4 : 2; }
+static size_t gated_dz_bytes(int64_t B, int64_t H, int64_t N, int io)
+{
+    return up256((size_t)B * H * N * io_bytes(io));
+}
+
 static bool pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
 static int check_shape(int64_t B, int64_t H, int64_t N, int io)
 {
@@ -296,7 +302,9 @@ size_t longconv_workspace_bytes(int64_t B, int64_t H, int64_t N, int io, int bac
 {
     if (check_shape(B, H, N, io) != LONGCONV_OK) return 0;
     const Plan pl = make_plan(N, io);
-    return carve(B, H, N, pl, backward != 0).total;
+    const size_t base = carve(B, H, N, pl, backward != 0).total;
+    // gated backward: room for dz = dy * g behind the backward pass's own workspace
+    return backward == 2 ? base + gated_dz_bytes(B, H, N, io) : base;
 }
 
 int longconv_kspec_compute(const float* k, const float* D, void* kspec, int64_t H, int64_t N, int io,
@@ -324,7 +332,7 @@ int longconv_kspec_compute(const float* k, const float* D, void* kspec, int64_t 
 // otherwise the caller's.
 static int fwd_impl(const void* u, const float* k, const float* D, const void* kspec, void* y, int64_t B,
                     int64_t H, int64_t N, int io, void* workspace, size_t workspace_bytes, void* stream,
-                    bool own_scratch)
+                    bool own_scratch, const void* gate = nullptr)
 {
     int s = check_shape(B, H, N, io);
     if (s != LONGCONV_OK) return s;
@@ -352,6 +360,8 @@ static int fwd_impl(const void* u, const float* k, const float* D, const void* k
     Problem pr{B, H, N, io, (int)((B + 1) / 2)};
     if (note(run_conv(u, ks, y, base + w.ws1, false, pr, pl, tb, st, false), "fwd") != hipSuccess)
         return LONGCONV_ERR_HIP;
+    // output gate (y = g * z): a pass of its own over y
+    if (gate && note(ew_mul(y, gate, y, (size_t)B * H * N, io, st), "gate") != hipSuccess) return LONGCONV_ERR_HIP;
     return LONGCONV_OK;
 }
 
@@ -365,6 +375,43 @@ int longconv_fwd_noalloc(const void* u, const float* k, const float* D, const vo
                          int64_t H, int64_t N, int io, void* stream)
 {
     return fwd_impl(u, k, D, kspec, y, B, H, N, io, nullptr, 0, stream, true);
+}
+
+int longconv_fwd_gated(const void* u, const float* k, const float* D, const void* kspec, const void* g, void* y,
+                       int64_t B, int64_t H, int64_t N, int io, void* workspace, size_t workspace_bytes,
+                       void* stream)
+{
+    if (!g) return LONGCONV_ERR_NULL;
+    if (misaligned(g)) return LONGCONV_ERR_ALIGN;
+    int s = fwd_impl(u, k, D, kspec, y, B, H, N, io, workspace, workspace_bytes, stream, false, g);
+    return s;
+}
+
+int longconv_bwd_gated(const void* dy, const void* g, const void* u, const float* k, const float* D,
+                       const void* kspec, void* du, float* dk, float* dD, void* dg, int64_t B, int64_t H,
+                       int64_t N, int io, void* workspace, size_t workspace_bytes, void* stream)
+{
+    int s = check_shape(B, H, N, io);
+    if (s != LONGCONV_OK) return s;
+    if (!dy || !g || (dg && (!u || (!kspec && (!k || !D))))) return LONGCONV_ERR_NULL;
+    if (misaligned(dy) || misaligned(g) || misaligned(dg) || misaligned(workspace)) return LONGCONV_ERR_ALIGN;
+    const size_t base = longconv_workspace_bytes(B, H, N, io, 1);
+    if (!workspace || workspace_bytes < base + gated_dz_bytes(B, H, N, io)) return LONGCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t n = (size_t)B * H * N;
+    if (du || dk || dD) {
+        // dz = dy * g is what the convolution's backward pass receives
+        void* dz = (char*)workspace + base;
+        if (note(ew_mul(dy, g, dz, n, io, st), "gate") != hipSuccess) return LONGCONV_ERR_HIP;
+        s = longconv_bwd(dz, u, k, D, kspec, du, dk, dD, B, H, N, io, workspace, base, stream);
+        if (s != LONGCONV_OK) return s;
+    }
+    if (dg) {
+        // dg = dy * z, z the ungated output recomputed: the gated forward with dy in the gate's place
+        s = fwd_impl(u, k, D, kspec, dg, B, H, N, io, workspace, base, stream, false, dy);
+        if (s != LONGCONV_OK) return s;
+    }
+    return LONGCONV_OK;
 }
 
 int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, const void* kspec, void* du,

@@ -50,6 +50,9 @@ hipError_t reduce_dD(const float* part, float* dD, int64_t H, int nblk, hipStrea
 
 // ---- kernel regularisers (kreg.hip): Kbar = Squash(Smooth(dropout(K))) and the chain back to K -----------------
 constexpr int KREG_MAX_P = 32;
+// out = a * b, element by element, n elements of the I/O dtype (n a multiple of 8; out may alias a or b) (gate.hip)
+hipError_t ew_mul(const void* a, const void* b, void* out, size_t n, int io, hipStream_t st);
+
 hipError_t kreg_fwd(const float* k, const float* mask, float* kbar, int64_t H, int64_t N, int p, float lam,
                     hipStream_t st);
 hipError_t kreg_bwd(const float* k, const float* mask, const float* dkbar, float* dk, int64_t H, int64_t N, int p,
