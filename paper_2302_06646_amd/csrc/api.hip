@@ -358,10 +358,14 @@ static int fwd_impl(const void* u, const float* k, const float* D, const void* k
         ks = (const float2*)(base + w.kspec);
     }
     Problem pr{B, H, N, io, (int)((B + 1) / 2)};
+    // output gate (y = g * z): inside the convolution's store where the plan's kernel has that form, otherwise a
+    // pass of its own over y
+    const bool fused_gate = gate && conv_applies_gate(pl, pl.fuse_a);
+    if (fused_gate) pr.gate = gate;
     if (note(run_conv(u, ks, y, base + w.ws1, false, pr, pl, tb, st, false), "fwd") != hipSuccess)
         return LONGCONV_ERR_HIP;
-    // output gate (y = g * z): a pass of its own over y
-    if (gate && note(ew_mul(y, gate, y, (size_t)B * H * N, io, st), "gate") != hipSuccess) return LONGCONV_ERR_HIP;
+    if (gate && !fused_gate && note(ew_mul(y, gate, y, (size_t)B * H * N, io, st), "gate") != hipSuccess)
+        return LONGCONV_ERR_HIP;
     return LONGCONV_OK;
 }
 

@@ -445,11 +445,14 @@ __device__ __forceinline__ int staged_slot(int n)
 template <int LG>
 __host__ __device__ constexpr size_t coop_real_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16 + (size_t)CC<LG>::TC * 16 * 4; }
 
-template <int LG, class IO, int NWV, int NB, bool CONJ>
+// GATE: the output is multiplied element by element by a second tensor of the same shape on its way out (the
+// gated layer: y = g * z).
+template <int LG, class IO, int NWV, int NB, bool CONJ, bool GATE>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
-                      typename IO::T* __restrict__ out, int64_t B, int64_t H, int64_t N, int npairs,
-                      int per, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
+                      typename IO::T* __restrict__ out, const typename IO::T* __restrict__ gate, int64_t B, int64_t H,
+                      int64_t N, int npairs, int per, const float2* __restrict__ tw,
+                      const unsigned char* __restrict__ ctab)
 {
     using C = CC<LG>;
     constexpr int NT = NWV * 64;
@@ -540,6 +543,15 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
         const int h = it / npairs, p = it - h * npairs;
         const bool has_b = (2 * p + 1) < B;
         const size_t oa = row_off(2 * p, h, H, N), ob = row_off(2 * p + 1, h, H, N);
+        uint4 ga[GATE ? RPL : 1], gb[GATE ? RPL : 1];        // gate values of the runs this lane stores
+        if constexpr (GATE) {
+#pragma unroll
+            for (int i = 0; i < RPL; ++i) {
+                const int n = run_n(i);
+                ga[i] = *reinterpret_cast<const uint4*>(gate + oa + n);
+                gb[i] = *reinterpret_cast<const uint4*>(gate + (has_b ? ob : oa) + n);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             const int a0 = slot(i), n = run_n(i);
@@ -550,11 +562,26 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             for (int m = 0; m < 4; ++m) {
                 wa[m] = __builtin_amdgcn_perm(x[2 * m + 1], x[2 * m], 0x05040100u);
                 wb[m] = __builtin_amdgcn_perm(x[2 * m + 1], x[2 * m], 0x07060302u);
+                uint32_t gwa = 0u, gwb = 0u;
+                if constexpr (GATE) {
+                    gwa = m == 0 ? ga[i].x : (m == 1 ? ga[i].y : (m == 2 ? ga[i].z : ga[i].w));
+                    gwb = m == 0 ? gb[i].x : (m == 1 ? gb[i].y : (m == 2 ? gb[i].z : gb[i].w));
+                }
                 if (IsBf<IO>::v) {
                     union { uint32_t u; h2 h; } a, b;
                     a.u = wa[m]; b.u = wb[m];
-                    wa[m] = pack_bf2((float)a.h[0], (float)a.h[1]);
-                    wb[m] = pack_bf2((float)b.h[0], (float)b.h[1]);
+                    float a0f = (float)a.h[0], a1f = (float)a.h[1], b0f = (float)b.h[0], b1f = (float)b.h[1];
+                    if constexpr (GATE) {
+                        a0f *= __uint_as_float(gwa << 16); a1f *= __uint_as_float(gwa & 0xffff0000u);
+                        b0f *= __uint_as_float(gwb << 16); b1f *= __uint_as_float(gwb & 0xffff0000u);
+                    }
+                    wa[m] = pack_bf2(a0f, a1f);
+                    wb[m] = pack_bf2(b0f, b1f);
+                } else if constexpr (GATE) {
+                    union { uint32_t u; h2 h; } a, b, qa, qb;
+                    a.u = wa[m]; b.u = wb[m]; qa.u = gwa; qb.u = gwb;
+                    a.h = a.h * qa.h; b.h = b.h * qb.h;
+                    wa[m] = a.u; wb[m] = b.u;
                 }
             }
             if constexpr (IsBf<IO>::v) {
@@ -1978,26 +2005,26 @@ template <int LG>
 size_t coop_lds_bytes() { return (size_t)CC<LG>::XWORDS * 4 + (size_t)CC<LG>::TC * 8 * 16; }
 
 // work split of the staged convolution kernel: as many workgroups as the device holds at once
-template <int LG, class IO, int NWV, int NB, bool CONJ>
+template <int LG, class IO, int NWV, int NB, bool CONJ, bool GATE>
 hipError_t coop_conv_real_go(const void* in, const float2* kspec, void* out, const Problem& pr,
                              const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
     const size_t lds = coop_real_lds_bytes<LG>();
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_real_kernel<LG, IO, NWV, NB, CONJ>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(coop_conv_real_kernel<LG, IO, NWV, NB, CONJ, GATE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     static int resident = 0;
     if (resident == 0) {
         int nb = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, coop_conv_real_kernel<LG, IO, NWV, NB, CONJ>, NWV * 64, lds);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, coop_conv_real_kernel<LG, IO, NWV, NB, CONJ, GATE>, NWV * 64, lds);
         if (e != hipSuccess) return e;
         resident = (nb > 0 ? nb : 1) * compute_units();
     }
     const long total = pr.H * pr.npairs;                 // (head, pair) items, a run of `per` per workgroup
     const int per = (int)((total + resident - 1) / resident);
-    hipLaunchKernelGGL((coop_conv_real_kernel<LG, IO, NWV, NB, CONJ>), dim3((unsigned)((total + per - 1) / per)),
-                       dim3(NWV * 64), lds, st, (const T*)in, kspec, (T*)out, pr.B, pr.H, pr.N,
+    hipLaunchKernelGGL((coop_conv_real_kernel<LG, IO, NWV, NB, CONJ, GATE>), dim3((unsigned)((total + per - 1) / per)),
+                       dim3(NWV * 64), lds, st, (const T*)in, kspec, (T*)out, (const T*)pr.gate, pr.B, pr.H, pr.N,
                        pr.npairs, per, tb.tw, (const unsigned char*)tb.ctab);
     return hipGetLastError();
 }
@@ -2007,9 +2034,13 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
                         const Problem& pr, const Plan& pl, const Tables& tb, hipStream_t st)
 {
     constexpr int NWV = CC<LG>::NW, NB = NTB;
-    if (pl.log2R == 0)
-        return conj ? coop_conv_real_go<LG, IO, NWV, NB, true>(in, kspec, out, pr, tb, st)
-                    : coop_conv_real_go<LG, IO, NWV, NB, false>(in, kspec, out, pr, tb, st);
+    if (pl.log2R == 0) {
+        if (pr.gate)
+            return conj ? hipErrorInvalidValue
+                        : coop_conv_real_go<LG, IO, NWV, NB, false, true>(in, kspec, out, pr, tb, st);
+        return conj ? coop_conv_real_go<LG, IO, NWV, NB, true, false>(in, kspec, out, pr, tb, st)
+                    : coop_conv_real_go<LG, IO, NWV, NB, false, false>(in, kspec, out, pr, tb, st);
+    }
     // multi-pass: the inner convolution on pass A's workspace, or (fuse_a) on the rows themselves
     using T = typename IO::T;
     const size_t lds = coop_real_lds_bytes<LG>();

@@ -557,6 +557,13 @@ hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws
     return hipErrorInvalidValue;
 }
 
+// the single-pass wave and cooperative convolutions multiply Problem::gate into their own store
+bool conv_applies_gate(const Plan& pl, bool fuse_a)
+{
+    (void)fuse_a;
+    return pl.engine == ENGINE_MFMA && pl.log2R == 0 && (pl.order.wave_lg || pl.order.coop_lg);
+}
+
 hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, int nsplit, const __half2* ws_u,
                    const __half2* ws_dy, __half2* ws_A, float* dD_part, void* zbuf, const Problem& pr, const Plan& pl,
                    const Tables& tb, hipStream_t st)

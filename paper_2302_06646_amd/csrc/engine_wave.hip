@@ -275,11 +275,13 @@ __device__ __forceinline__ int phase2_addr(int t2, int j, int lane)
 // Fused convolution.  Each wave processes `gpw` consecutive groups of PB row pairs (groups are
 // numbered head-major).  block = NWV waves.
 // -------------------------------------------------------------------------------------
-template <int LG, class IO, int PB, int NWV, bool CONJ>
+// GATE: the output is multiplied element by element by a second tensor of the same shape before it is stored
+// (the gated layer: y = g * z), in fp32, so that the product is rounded once.
+template <int LG, class IO, int PB, int NWV, bool CONJ, bool GATE>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec,
-             typename IO::T* __restrict__ out, int64_t B, int64_t H, int64_t N, int gph,
-             int total_groups, int gpw, const unsigned char* __restrict__ wtab)
+             typename IO::T* __restrict__ out, const typename IO::T* __restrict__ gate, int64_t B, int64_t H, int64_t N,
+             int gph, int total_groups, int gpw, const unsigned char* __restrict__ wtab)
 {
     using C = WC<LG>;
     constexpr int NT = (4 / PB) < C::TG ? (4 / PB) : C::TG;   // tiles advanced together (x PB pairs)
@@ -429,6 +431,17 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
 #pragma unroll
         for (int tg = 0; tg < C::TC; tg += C::TG) {
             uint32_t oa[PB][4][C::NWD], ob[PB][4][C::NWD];
+            uint32_t ga[GATE ? PB : 1][4][C::NWD], gb[GATE ? PB : 1][4][C::NWD];      // gate words of the same samples
+            if constexpr (GATE) {
+#pragma unroll
+                for (int q = 0; q < PB; ++q)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int n0 = (4 * (g & 1) + j) * 16 * C::TC + c * C::TC + tg;
+                        load_words<C::NWD>(gate + Rc.oa[q] + n0, ga[q][j]);
+                        load_words<C::NWD>(gate + Rc.ob[q] + n0, gb[q][j]);
+                    }
+            }
 #pragma unroll
             for (int tb = 0; tb < C::TG; tb += NT) {
                 H8U w0[NT], gr[NT], gi[NT];
@@ -459,6 +472,27 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
                         r[k][q] = MFMA(I16.re, u.v, zero);     // B-role over k_a
                         s[k][q] = MFMA(I16.im, u.v, zero);
                     }
+                if constexpr (GATE) {
+#pragma unroll
+                    for (int k = 0; k < NT; k += 2)
+#pragma unroll
+                        for (int q = 0; q < PB; ++q)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const uint32_t wga = ga[q][j][(tb + k) >> 1], wgb = gb[q][j][(tb + k) >> 1];
+                                float a0, a1, b0, b1;
+                                if (IsBf<IO>::v) {
+                                    a0 = __uint_as_float(wga << 16); a1 = __uint_as_float(wga & 0xffff0000u);
+                                    b0 = __uint_as_float(wgb << 16); b1 = __uint_as_float(wgb & 0xffff0000u);
+                                } else {
+                                    union { uint32_t u; h2 h; } xa, xb;
+                                    xa.u = wga; xb.u = wgb;
+                                    a0 = (float)xa.h[0]; a1 = (float)xa.h[1]; b0 = (float)xb.h[0]; b1 = (float)xb.h[1];
+                                }
+                                r[k][q][j] *= a0; r[k + 1][q][j] *= a1;
+                                s[k][q][j] *= b0; s[k + 1][q][j] *= b1;
+                            }
+                }
 #pragma unroll
                 for (int k = 0; k < NT; k += 2)
 #pragma unroll
@@ -1370,14 +1404,14 @@ hipError_t wkspec_go(const float* k, const float* D, float2* kspec, int64_t H, i
     return hipGetLastError();
 }
 
-template <int LG, class IO, int PB, int NWV, bool CONJ>
-hipError_t wconv_run(const void* in, const float2* kspec, void* out, const Problem& pr,
+template <int LG, class IO, int PB, int NWV, bool CONJ, bool GATE>
+hipError_t wconv_run(const void* in, const float2* kspec, void* out, const void* gate, const Problem& pr,
                     const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
     using C = WC<LG>;
     const size_t lds = (size_t)C::TAB_U4 * 16 + (size_t)NWV * PB * C::PAIR_WORDS * 4;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wconv_kernel<LG, IO, PB, NWV, CONJ>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wconv_kernel<LG, IO, PB, NWV, CONJ, GATE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const int gph = (pr.npairs + PB - 1) / PB;
@@ -1386,7 +1420,7 @@ hipError_t wconv_run(const void* in, const float2* kspec, void* out, const Probl
     static int fit_cached = 0;
     if (fit_cached == 0) {
         int nb = 0;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, wconv_kernel<LG, IO, PB, NWV, CONJ>, NWV * 64, lds);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, wconv_kernel<LG, IO, PB, NWV, CONJ, GATE>, NWV * 64, lds);
         if (e != hipSuccess) return e;
         fit_cached = nb < 1 ? 1 : (nb > 4 ? 4 : nb);
     }
@@ -1394,32 +1428,34 @@ hipError_t wconv_run(const void* in, const float2* kspec, void* out, const Probl
     long gpw = (total + cus * fit * NWV - 1) / (cus * fit * NWV);
     if (gpw < 1) gpw = 1;
     const long nblk = (total + gpw * NWV - 1) / (gpw * NWV);
-    hipLaunchKernelGGL((wconv_kernel<LG, IO, PB, NWV, CONJ>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st,
-                       (const T*)in, kspec, (T*)out, pr.B, pr.H, pr.N, gph, (int)total, (int)gpw,
+    hipLaunchKernelGGL((wconv_kernel<LG, IO, PB, NWV, CONJ, GATE>), dim3((unsigned)nblk), dim3(NWV * 64), lds, st,
+                       (const T*)in, kspec, (T*)out, (const T*)gate, pr.B, pr.H, pr.N, gph, (int)total, (int)gpw,
                        (const unsigned char*)tb.wtab);
     return hipGetLastError();
 }
 
 template <int LG, class IO, int PB, int NWV>
-hipError_t wconv_go(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
+hipError_t wconv_go(const void* in, const float2* kspec, void* out, bool conj, const void* gate, const Problem& pr,
                     const Tables& tb, hipStream_t st)
 {
-    return conj ? wconv_run<LG, IO, PB, NWV, true>(in, kspec, out, pr, tb, st)
-                : wconv_run<LG, IO, PB, NWV, false>(in, kspec, out, pr, tb, st);
+    if (gate) return conj ? hipErrorInvalidValue : wconv_run<LG, IO, PB, NWV, false, true>(in, kspec, out, gate, pr, tb, st);
+    return conj ? wconv_run<LG, IO, PB, NWV, true, false>(in, kspec, out, nullptr, pr, tb, st)
+                : wconv_run<LG, IO, PB, NWV, false, false>(in, kspec, out, nullptr, pr, tb, st);
 }
 
 template <class IO>
-hipError_t wconv_io(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr, const Plan& pl,
-                    const Tables& tb, hipStream_t st)
+hipError_t wconv_io(const void* in, const float2* kspec, void* out, bool conj, const void* gate, const Problem& pr,
+                    const Plan& pl, const Tables& tb, hipStream_t st)
 {
     switch (pl.log2L2) {
-        case 9: return wconv_go<9, IO, 2, 8>(in, kspec, out, conj, pr, tb, st);
-        case 10: return wconv_go<10, IO, 2, 8>(in, kspec, out, conj, pr, tb, st);
+        case 9: return wconv_go<9, IO, 2, 8>(in, kspec, out, conj, gate, pr, tb, st);
+        case 10: return wconv_go<10, IO, 2, 8>(in, kspec, out, conj, gate, pr, tb, st);
         case 11:
-            // bf16: the band test of the rows needs a few registers more than three waves per SIMD leave
-            if (IsBf<IO>::v) return wconv_go<11, IO, 1, 8>(in, kspec, out, conj, pr, tb, st);
-            return wconv_go<11, IO, 1, 12>(in, kspec, out, conj, pr, tb, st);
-        case 12: return wconv_go<12, IO, 1, 3>(in, kspec, out, conj, pr, tb, st);
+            // bf16 (the band test of the rows) and the gated form need a few registers more than three waves per
+            // SIMD leave
+            if (IsBf<IO>::v || gate) return wconv_go<11, IO, 1, 8>(in, kspec, out, conj, gate, pr, tb, st);
+            return wconv_go<11, IO, 1, 12>(in, kspec, out, conj, gate, pr, tb, st);
+        case 12: return wconv_go<12, IO, 1, 3>(in, kspec, out, conj, gate, pr, tb, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1429,8 +1465,8 @@ hipError_t wconv_io(const void* in, const float2* kspec, void* out, bool conj, c
 hipError_t wave_conv(const void* in, const float2* kspec, void* out, bool conj, const Problem& pr,
                      const Plan& pl, const Tables& tb, hipStream_t st)
 {
-    if (pr.io == LONGCONV_F16) return wconv_io<IoF16>(in, kspec, out, conj, pr, pl, tb, st);
-    if (pr.io == LONGCONV_BF16) return wconv_io<IoBF16>(in, kspec, out, conj, pr, pl, tb, st);
+    if (pr.io == LONGCONV_F16) return wconv_io<IoF16>(in, kspec, out, conj, pr.gate, pr, pl, tb, st);
+    if (pr.io == LONGCONV_BF16) return wconv_io<IoBF16>(in, kspec, out, conj, pr.gate, pr, pl, tb, st);
     return hipErrorInvalidValue;
 }
 

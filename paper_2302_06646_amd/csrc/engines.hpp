@@ -24,7 +24,10 @@ struct Problem {
     int64_t B, H, N;
     int io;          // longconv_dtype_t of u, y, dy, du
     int npairs;      // ceil(B/2): two batch rows of one head are transformed as re + i*im
+    const void* gate = nullptr;   // convolutions only: [B,H,N] I/O dtype, multiplied into the output before the store
 };
+// which plans apply Problem::gate inside their own store (the others leave it to a pass of its own)
+bool conv_applies_gate(const Plan& pl, bool fuse_a);
 
 // ---- outer passes of the multi-pass split (multipass.hip) ------------------------
 // Pass A: ws[(h*npairs+p)*L + k1*L2 + n2] = scale * w_L^(n2*k1) * sum_{n1<R/2} w_R^(n1*k1) z[n1*L2+n2],
