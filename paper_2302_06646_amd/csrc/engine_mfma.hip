@@ -557,11 +557,15 @@ hipError_t mfma_conv(const void* in, const float2* kspec, void* out, __half2* ws
     return hipErrorInvalidValue;
 }
 
-// the single-pass wave and cooperative convolutions multiply Problem::gate into their own store
+// The single-pass wave and cooperative convolutions multiply Problem::gate into their own store; of the multi-pass
+// plans those whose pass C is the vectorised kernel (fp16 workspace, outer radix up to 16, inner length >= 1024)
+// apply it there.
 bool conv_applies_gate(const Plan& pl, bool fuse_a)
 {
     (void)fuse_a;
-    return pl.engine == ENGINE_MFMA && pl.log2R == 0 && (pl.order.wave_lg || pl.order.coop_lg);
+    if (pl.engine != ENGINE_MFMA) return false;
+    if (pl.log2R == 0) return pl.order.wave_lg || pl.order.coop_lg;
+    return pl.log2R <= 4 && pl.log2L2 >= 10;
 }
 
 hipError_t mfma_dk(const void* dy, const void* u, float* dk, float* dD, int nsplit, const __half2* ws_u,

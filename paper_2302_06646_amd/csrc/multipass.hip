@@ -150,6 +150,33 @@ __device__ __forceinline__ void store_cols(typename IO::T* p, const float (&x)[V
     }
 }
 
+// V neighbouring samples of a row as floats (the reading side of store_cols)
+template <class IO, int V>
+__device__ __forceinline__ void load_cols(const typename IO::T* p, float (&x)[V])
+{
+    static_assert(V == 2 || V == 4, "two or four columns");
+    if constexpr (std::is_same<IO, IoF32>::value) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) x[i] = p[i];
+    } else {
+        uint32_t w[V / 2];
+        mu::load_words<V / 2>(p, w);
+#pragma unroll
+        for (int i = 0; i < V / 2; ++i) {
+            if constexpr (std::is_same<IO, IoBF16>::value) {
+                x[2 * i] = __uint_as_float(w[i] << 16);
+                x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+            } else {
+                union { uint32_t u; __half2 hh; } cv;
+                cv.u = w[i];
+                const float2 f = __half22float2(cv.hh);
+                x[2 * i] = f.x;
+                x[2 * i + 1] = f.y;
+            }
+        }
+    }
+}
+
 // Pass C for an fp16 workspace and outer radix up to 16: four (radix 16: two) neighbouring columns n2 per thread, so that the
 // chunks are read in 16-byte pieces and the rows written in 8- or 16-byte pieces; the twist of chunk k1 is the
 // k1-th power of one table entry per column, the radix-R inverse butterfly uses the sixteenth roots of unity as
@@ -158,8 +185,10 @@ template <class IO, int LOG2R>
 __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restrict__ ws,
                                                         typename IO::T* __restrict__ out, int64_t B, int64_t H,
                                                         int64_t N, int npairs, int log2L2, float scale,
-                                                        const float2* __restrict__ tw, int herm)
+                                                        const float2* __restrict__ tw, int herm,
+                                                        const typename IO::T* __restrict__ gate)
 {
+    // gate != NULL: the rows are multiplied element by element by that tensor before the store (gated layer)
     static_assert(LOG2R >= 1 && LOG2R <= 4, "the roots of unity of rot16");
     constexpr int R = 1 << LOG2R, RH = R / 2;
     constexpr int VEC = inv4_columns(LOG2R);             // columns per thread (radix 16: two, for the registers)
@@ -208,6 +237,13 @@ __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restric
         float a[VEC], b[VEC];
 #pragma unroll
         for (int j = 0; j < VEC; ++j) { a[j] = t[j].x * scale; b[j] = t[j].y * scale; }
+        if (gate) {
+            float ga[VEC], gb[VEC];
+            load_cols<IO, VEC>(gate + oa + n, ga);
+            load_cols<IO, VEC>(gate + ob + n, gb);
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) { a[j] *= ga[j]; b[j] *= gb[j]; }
+        }
         store_cols<IO, VEC>(out + oa + n, a);
         if (has_b) store_cols<IO, VEC>(out + ob + n, b);
     }
@@ -303,10 +339,11 @@ hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, 
         if ((1 << log2L2) >= VEC * OB) {
             dim3 grid4((unsigned)(((size_t)1 << log2L2) / (VEC * OB) * (size_t)pr.npairs * (size_t)pr.H));
             hipLaunchKernelGGL((outer_inv4_kernel<IO, LOG2R>), grid4, dim3(OB), 0, st, (const __half2*)ws, (T*)out,
-                               pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm);
+                               pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm, (const T*)pr.gate);
             return hipGetLastError();
         }
     }
+    if (pr.gate) return hipErrorInvalidValue;      // only the vectorised pass C applies a gate (see conv_applies_gate)
     dim3 grid((unsigned)(((size_t)1 << log2L2) / OB * (size_t)pr.npairs * (size_t)pr.H));
     hipLaunchKernelGGL((outer_inv_kernel<IO, CW, LOG2R>), grid, dim3(OB), 0, st, (const C*)ws, (T*)out, pr.B,
                        pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm);
