@@ -81,7 +81,14 @@ def executed_mfma_flops(w: wl.Workload):
     npairs = (w.B + 1) // 2
     per_half = (6 if L <= 4096 else 8) * 16384 * (L / 256)
     bwd_halves = 3 if L <= 4096 else 4
-    return w.H * (npairs * (2 + bwd_halves) + 2) * per_half
+    fwd_halves, head_halves = 2.0, 2.0
+    if L > 32768 and w.B == 1:
+        # a batch of one row: the multi-pass kernels compute the chunks 0 .. R/2 of R only (Hermitian spectrum);
+        # the convolutions split into R = L / 32768 chunks, dk into 2R chunks of 16384 points
+        R = L // 32768
+        fc, fd = (R / 2 + 1) / R, (R + 1) / (2 * R)
+        fwd_halves, bwd_halves, head_halves = 2 * fc, 2 * fc + 2 * fd, 1 + fd
+    return w.H * (npairs * (fwd_halves + bwd_halves) + head_halves) * per_half
 
 
 class Sets:
