@@ -33,14 +33,16 @@
  *   - Return value: LONGCONV_OK or an error code; argument validation happens
  *     before anything is launched.  No exceptions, no aborts.
  *   - fp16/bf16 I/O computes with fp16 matrix-core operands and fp32 accumulation.
- *     bf16 rows (u, dy) may have any magnitude for N <= 16384: every row whose largest
- *     sample lies outside 2^-2 .. 2^4 is multiplied by a power of two on its way into the
- *     transform and by its inverse on the way out, row by row, so gradients of order
- *     1e-10 or activations of order 1e6 keep the accuracy of data of order one (two rows
- *     inside that band share one fp16 scale: their error is relative to the larger of the
- *     two).  Not rescaled, and therefore to be kept inside fp16's normal range by the
- *     caller: fp16 rows (order one is fine up to N = 131072; the transform grows them by at
- *     most sqrt(2N)), bf16 rows for N >= 32768, and the spectrum, |FFT(k) + D| within about
+ *     bf16 rows (u, dy) may have any magnitude: rows whose largest sample lies outside
+ *     2^-2 .. 2^4 are multiplied by a power of two on their way into the transform and by
+ *     its inverse on the way out, so gradients of order 1e-10 or activations of order 1e6
+ *     keep the accuracy of data of order one.  Up to N = 16384 this is done row by row (two
+ *     rows inside that band share one fp16 scale: their error is relative to the larger of
+ *     the two); from N = 32768 on all rows of a head share one power of two, found by a
+ *     pass over the tensor in front, so rows of one head that differ by many orders of
+ *     magnitude lose the small ones.  Not rescaled, and therefore to be kept inside fp16's
+ *     normal range by the caller: fp16 rows (order one is fine up to N = 131072; the
+ *     transform grows them by at most sqrt(2N)) and the spectrum, |FFT(k) + D| within about
  *     2^-8 .. 2^8.  Far outside those ranges precision is lost silently.  The kernel k
  *     itself may have any magnitude on its way into the spectrum (per-head power-of-two
  *     rescaling).  fp32 I/O computes in fp32.

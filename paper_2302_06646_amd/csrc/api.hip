@@ -167,7 +167,7 @@ static size_t spec_bytes(const Plan& pl)
 static size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
 
 struct WsLayout {
-    size_t kspec, kscratch, hscale, ws1, ws2, wsA, dpart, zbuf, dkpart, ddpart, total;
+    size_t kspec, kscratch, hscale, ws1, ws2, wsA, dpart, zbuf, dkpart, ddpart, rowmx, total;
     int nblk, nsplit;
 };
 
@@ -183,7 +183,13 @@ static int dk_nsplit(int64_t B, int64_t H, const Plan& pl)
     return s < 1 ? 1 : (int)s;
 }
 
-static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool backward)
+// bf16 rows of the multi-pass plans that take pass A inside the inner kernels are scaled per head (see rows_absmax)
+static bool rows_rescaled(const Plan& pl, int io)
+{
+    return io == LONGCONV_BF16 && pl.engine == ENGINE_MFMA && pl.log2R > 0 && pl.fuse_a;
+}
+
+static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool backward, int io)
 {
     WsLayout w{};
     const size_t L = size_t(1) << pl.log2L;
@@ -205,6 +211,8 @@ static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool back
     w.nsplit = backward ? dk_nsplit(B, H, pl) : 1;
     w.dkpart = off; if (w.nsplit > 1) off += up256((size_t)w.nsplit * H * (L / 2) * sizeof(float));
     w.ddpart = off; if (w.nsplit > 1) off += up256((size_t)w.nsplit * H * sizeof(float));
+    // bf16 rows of the multi-pass plans with pass A inside the inner kernels: per-head maxima of u and dy
+    w.rowmx = off; if (rows_rescaled(pl, io)) off += up256((size_t)2 * H * sizeof(uint32_t));
     w.total = off;
     return w;
 }
@@ -302,7 +310,7 @@ size_t longconv_workspace_bytes(int64_t B, int64_t H, int64_t N, int io, int bac
 {
     if (check_shape(B, H, N, io) != LONGCONV_OK) return 0;
     const Plan pl = make_plan(N, io);
-    const size_t base = carve(B, H, N, pl, backward != 0).total;
+    const size_t base = carve(B, H, N, pl, backward != 0, io).total;
     // gated backward: room for dz = dy * g behind the backward pass's own workspace
     return backward == 2 ? base + gated_dz_bytes(B, H, N, io) : base;
 }
@@ -315,7 +323,7 @@ int longconv_kspec_compute(const float* k, const float* D, void* kspec, int64_t 
     if (!k || !D || !kspec) return LONGCONV_ERR_NULL;
     if (misaligned(k) || misaligned(kspec) || misaligned(workspace)) return LONGCONV_ERR_ALIGN;
     const Plan pl = make_plan(N, io);
-    const WsLayout w = carve(1, H, N, pl, false);
+    const WsLayout w = carve(1, H, N, pl, false, io);
     const size_t need = w.ws1 - w.kscratch;   // producer scratch and per-head scales
     if (need && (!workspace || workspace_bytes < w.kscratch + need)) return LONGCONV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
@@ -340,7 +348,7 @@ static int fwd_impl(const void* u, const float* k, const float* D, const void* k
     if (misaligned(u) || misaligned(y) || misaligned(k) || misaligned(kspec) || misaligned(workspace))
         return LONGCONV_ERR_ALIGN;
     const Plan pl = make_plan(N, io);
-    const WsLayout w = carve(B, H, N, pl, false);
+    const WsLayout w = carve(B, H, N, pl, false, io);
     if (own_scratch) {
         if (w.total > (size_t)LONGCONV_STATIC_SCRATCH_BYTES) return LONGCONV_ERR_WORKSPACE;
     } else if (!workspace || workspace_bytes < w.total) {
@@ -358,6 +366,11 @@ static int fwd_impl(const void* u, const float* k, const float* D, const void* k
         ks = (const float2*)(base + w.kspec);
     }
     Problem pr{B, H, N, io, (int)((B + 1) / 2)};
+    if (rows_rescaled(pl, io)) {
+        uint32_t* mx = (uint32_t*)(base + w.rowmx);
+        if (note(rows_absmax(u, mx, pr, st), "rows max") != hipSuccess) return LONGCONV_ERR_HIP;
+        pr.max_a = mx;
+    }
     // output gate (y = g * z): inside the convolution's store where the plan's kernel has that form, otherwise a
     // pass of its own over y
     const bool fused_gate = gate && conv_applies_gate(pl, pl.fuse_a);
@@ -430,7 +443,7 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
         misaligned(dk) || misaligned(workspace))
         return LONGCONV_ERR_ALIGN;
     const Plan pl = make_plan(N, io);
-    const WsLayout w = carve(B, H, N, pl, true);
+    const WsLayout w = carve(B, H, N, pl, true, io);
     if (!workspace || workspace_bytes < w.total) return LONGCONV_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     Tables tb;
@@ -440,6 +453,16 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
     Problem pr{B, H, N, io, (int)((B + 1) / 2)};
     const bool f16ws = pl.engine == ENGINE_MFMA;
     bool dy_ready = false;   // multi-pass: pass A of dy already in ws1
+    uint32_t* mx_u = nullptr;      // bf16 rows of these multi-pass plans: per-head maxima of u and dy
+    uint32_t* mx_dy = nullptr;
+    if (rows_rescaled(pl, io)) {
+        mx_u = (uint32_t*)(base + w.rowmx);
+        mx_dy = mx_u + H;
+        hipError_t e = hipSuccess;
+        if (want_dkD) e = rows_absmax(u, mx_u, pr, st);
+        if (e == hipSuccess) e = rows_absmax(dy, mx_dy, pr, st);
+        if (note(e, "rows max") != hipSuccess) return LONGCONV_ERR_HIP;
+    }
 
     if (want_dkD && du && pl.engine == ENGINE_MFMA && wave_bwd_ok(pl)) {
         // everything from one kernel: dy and u are read once, dy is transformed once
@@ -479,7 +502,10 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
             // straight from the rows, as outer radix 8 or 16 around 16384-point transforms (no pass A kernel);
             // dD is the rows' dot product, taken by the workgroup of each head's first chunk
             cR += 1; cL2 -= 1;
-            e = coop_dk_rows(dy, u, dk ? (__half2*)(base + w.wsA) : nullptr, dD, pr, pl, tb, st, &cscale);
+            Problem prs = pr;
+            prs.max_a = mx_u;
+            prs.max_b = mx_dy;
+            e = coop_dk_rows(dy, u, dk ? (__half2*)(base + w.wsA) : nullptr, dD, prs, pl, tb, st, &cscale);
         } else {
             if (pl.log2R) {
                 // pass A for u and dy in one launch; its blocks also leave dD's partial dot products
@@ -501,6 +527,10 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
         }
         if (e == hipSuccess && pl.log2R && dk) {
             Problem pk{1, H, N, LONGCONV_F32, 1};   // heads as single rows, real part only
+            if (pl.engine == ENGINE_MFMA && coop_dk_rows_ok(pl)) {
+                pk.max_a = mx_u;                     // the powers of two the rows of each head went in with
+                pk.max_b = mx_dy;
+            }
             // (dk from the rows of a batch of one: only the chunks up to R/2 were computed)
             e = outer_inv(base + w.wsA, dk, pk, cR, cL2, cscale, f16ws, tw, st,
                           pl.engine == ENGINE_MFMA && coop_dk_rows_ok(pl) && B == 1);
@@ -515,7 +545,9 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
                 return LONGCONV_ERR_HIP;
             ks = (const float2*)(base + w.kspec);
         }
-        if (note(run_conv(dy, ks, du, base + w.ws1, true, pr, pl, tb, st, dy_ready), "bwd du") != hipSuccess)
+        Problem prd = pr;
+        prd.max_a = dy_ready ? nullptr : mx_dy;
+        if (note(run_conv(dy, ks, du, base + w.ws1, true, prd, pl, tb, st, dy_ready), "bwd du") != hipSuccess)
             return LONGCONV_ERR_HIP;
     }
     return LONGCONV_OK;

@@ -748,8 +748,9 @@ __device__ __forceinline__ void twisted_t1f(uint4* t1f, const uint4* gtab, int k
 // HASB = false: the pair has no row b (odd batch); twice as many runs are then in flight per round trip.
 template <int LG, class IO, int LR, int NT, bool HASB>
 __device__ __forceinline__ void stage_rows_pass_a_impl(uint32_t* xb, const typename IO::T* ra, const typename IO::T* rb,
-                                                       int k1, const float2* __restrict__ tw, int tid)
+                                                       int k1, const float2* __restrict__ tw, int tid, int ex)
 {
+    // ex != 0 (bf16 rows of a head whose largest sample lies outside the band 2^-2 .. 2^4): every sample times 2^-ex
     using C = CC<LG>;
     constexpr int RH = (1 << LR) / 2;
     h2 cr[RH], crs[RH];                              // w_R^(n1 k1) and i times it
@@ -793,8 +794,8 @@ __device__ __forceinline__ void stage_rows_pass_a_impl(uint32_t* xb, const typen
                         if (IsBf<IO>::v) {
 #pragma unroll
                             for (int m = 0; m < 4; ++m) {
-                                wa[q][m] = bf2_to_h2(wa[q][m]);
-                                if (HASB) wb[q][m] = bf2_to_h2(wb[q][m]);
+                                wa[q][m] = ex ? bf2_to_h2_scaled(wa[q][m], ex) : bf2_to_h2(wa[q][m]);
+                                if (HASB) wb[q][m] = ex ? bf2_to_h2_scaled(wb[q][m], ex) : bf2_to_h2(wb[q][m]);
                             }
                         }
                     }
@@ -846,8 +847,8 @@ __device__ __forceinline__ void stage_rows_pass_a_impl(uint32_t* xb, const typen
                 if (IsBf<IO>::v) {
 #pragma unroll
                     for (int m = 0; m < 4; ++m) {
-                        wa[n1][m] = bf2_to_h2(wa[n1][m]);
-                        if (HASB) wb[n1][m] = bf2_to_h2(wb[n1][m]);
+                        wa[n1][m] = ex ? bf2_to_h2_scaled(wa[n1][m], ex) : bf2_to_h2(wa[n1][m]);
+                        if (HASB) wb[n1][m] = ex ? bf2_to_h2_scaled(wb[n1][m], ex) : bf2_to_h2(wb[n1][m]);
                     }
                 }
             }
@@ -871,10 +872,15 @@ __device__ __forceinline__ void stage_rows_pass_a_impl(uint32_t* xb, const typen
 
 template <int LG, class IO, int LR, int NT>
 __device__ __forceinline__ void stage_rows_pass_a(uint32_t* xb, const typename IO::T* ra, const typename IO::T* rb,
-                                                  bool has_b, int k1, const float2* __restrict__ tw, int tid)
+                                                  bool has_b, int k1, const float2* __restrict__ tw, int tid, int ex = 0)
 {
-    if (has_b) stage_rows_pass_a_impl<LG, IO, LR, NT, true>(xb, ra, rb, k1, tw, tid);
-    else stage_rows_pass_a_impl<LG, IO, LR, NT, false>(xb, ra, rb, k1, tw, tid);
+    if (has_b) stage_rows_pass_a_impl<LG, IO, LR, NT, true>(xb, ra, rb, k1, tw, tid, ex);
+    else stage_rows_pass_a_impl<LG, IO, LR, NT, false>(xb, ra, rb, k1, tw, tid, ex);
+}
+// exponent of a head's rows from the pattern of their largest magnitude (NULL: rows are taken as they are)
+__device__ __forceinline__ int head_rows_exponent(const uint32_t* __restrict__ mx, int h)
+{
+    return mx ? __builtin_amdgcn_readfirstlane(row_exponent(mx[h])) : 0;
 }
 
 // run r of a chunk of complex values (16-byte runs of four) -> first value n; lane bits as for the rows:
@@ -894,7 +900,8 @@ template <int LG, class IO, int NWV, int NB, bool CONJ, int FUSEA>
 __global__ void __launch_bounds__(NWV * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ kspec, __half2* __restrict__ ws,
                  int64_t B, int64_t H, int64_t N, int npairs, int log2R, int nch, int total, int per,
-                 const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
+                 const float2* __restrict__ tw, const unsigned char* __restrict__ ctab,
+                 const uint32_t* __restrict__ rows_max)
 {
     using C = CC<LG>;
     constexpr int NT = NWV * 64;
@@ -965,7 +972,7 @@ coop_conv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict
         twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);
         const bool has_b = (2 * p + 1) < B;
         const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
-        stage_rows_pass_a<LG, IO, LR, NT>(xb, in + oa, in + ob, has_b, k1, tw, tid);
+        stage_rows_pass_a<LG, IO, LR, NT>(xb, in + oa, in + ob, has_b, k1, tw, tid, head_rows_exponent(rows_max, h));
     };
     auto stage_item = [&](int it) __attribute__((always_inline)) {
         if (FUSEA) stage_rows(it);
@@ -1498,7 +1505,8 @@ template <int LG, class IO, int LR>
 __global__ void __launch_bounds__(CC<LG>::NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
                     __half2* __restrict__ ws_A, float* __restrict__ dD, int64_t B, int64_t H, int64_t N,
-                    int npairs, int nch, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab)
+                    int npairs, int nch, const float2* __restrict__ tw, const unsigned char* __restrict__ ctab,
+                    const uint32_t* __restrict__ u_max, const uint32_t* __restrict__ dy_max)
 {
     using C = CC<LG>;
     using T = typename IO::T;
@@ -1584,7 +1592,8 @@ coop_dk_rows_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
             const uint32_t* vt_ = vt + zoff;
             const T* src = pass ? dy : u;
             __syncthreads();                             // the slots are free (and the tables written)
-            stage_rows_pass_a<LG, IO, LR, NT>(xb, src + oa, src + ob, has_b, k1, tw, tid);
+            stage_rows_pass_a<LG, IO, LR, NT>(xb, src + oa, src + ob, has_b, k1, tw, tid,
+                                              head_rows_exponent(pass ? dy_max : u_max, h));
             __syncthreads();
             phase1_inplace<LG, 2>(xb, t1f_, vt_, F1, F2, cF, t0, lane);
             __syncthreads();
@@ -2061,7 +2070,7 @@ hipError_t coop_conv_go(const void* in, const float2* kspec, void* out, __half2*
         const int per = (int)((total + resident - 1) / resident);
         hipLaunchKernelGGL(kern, dim3((unsigned)((total + per - 1) / per)), dim3(NWV * 64), lds, st, (const T*)in, kspec,
                            ws, pr.B, pr.H, pr.N, pr.npairs, pl.log2R, nch, (int)total, per, tb.tw,
-                           (const unsigned char*)tb.ctab);
+                           (const unsigned char*)tb.ctab, fuse_a ? pr.max_a : nullptr);
         return hipGetLastError();
     };
     static int res[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -2138,7 +2147,7 @@ hipError_t coop_dk_rows_go(const void* dy, const void* u, __half2* ws_A, float* 
     const int nch = pr.B == 1 ? (1 << LR) / 2 + 1 : (1 << LR);
     hipLaunchKernelGGL((coop_dk_rows_kernel<LG, IO, LR>), dim3((unsigned)(pr.H * nch)), dim3(C::NW * 64), lds, st,
                        (const T*)dy, (const T*)u, ws_A, dD, pr.B, pr.H, pr.N, pr.npairs, nch, tb.tw,
-                       (const unsigned char*)tb.ctab);
+                       (const unsigned char*)tb.ctab, pr.max_a, pr.max_b);
     return hipGetLastError();
 }
 

@@ -25,7 +25,14 @@ struct Problem {
     int io;          // longconv_dtype_t of u, y, dy, du
     int npairs;      // ceil(B/2): two batch rows of one head are transformed as re + i*im
     const void* gate = nullptr;   // convolutions only: [B,H,N] I/O dtype, multiplied into the output before the store
+    // bf16 rows of the multi-pass plans: per head, the bf16 pattern of the largest magnitude of the input rows
+    // (max_a: the convolution's input, or u for dk; max_b: dy for dk).  Heads outside the band are scaled by a
+    // power of two where the rows are converted (pass A inside the inner kernels) and back in pass C.
+    const uint32_t* max_a = nullptr;
+    const uint32_t* max_b = nullptr;
 };
+// mx[h] = bf16 pattern of max |in[b,h,:]| over b (zeroed first); rows of 16-bit floats only
+hipError_t rows_absmax(const void* in, uint32_t* mx, const Problem& pr, hipStream_t st);
 // which plans apply Problem::gate inside their own store (the others leave it to a pass of its own)
 bool conv_applies_gate(const Plan& pl, bool fuse_a);
 

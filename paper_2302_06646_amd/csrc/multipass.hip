@@ -186,8 +186,12 @@ __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restric
                                                         typename IO::T* __restrict__ out, int64_t B, int64_t H,
                                                         int64_t N, int npairs, int log2L2, float scale,
                                                         const float2* __restrict__ tw, int herm,
-                                                        const typename IO::T* __restrict__ gate)
+                                                        const typename IO::T* __restrict__ gate,
+                                                        const uint32_t* __restrict__ max_a,
+                                                        const uint32_t* __restrict__ max_b)
 {
+    // max_a / max_b != NULL: the rows that went into this head were scaled by powers of two on the way in (bf16
+    // rows outside the band); the output gets the product of those powers back
     // gate != NULL: the rows are multiplied element by element by that tensor before the store (gated layer)
     static_assert(LOG2R >= 1 && LOG2R <= 4, "the roots of unity of rot16");
     constexpr int R = 1 << LOG2R, RH = R / 2;
@@ -201,6 +205,7 @@ __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restric
     const bool has_b = (2 * p + 1) < B;
     const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
     const __half2* src = ws + ((size_t)pairidx << log2L) + n2;
+    if (max_a) scale = ldexpf(scale, mu::row_exponent(max_a[h]) + (max_b ? mu::row_exponent(max_b[h]) : 0));
     float2 w1[VEC], pw[VEC], v[R][VEC];
 #pragma unroll
     for (int j = 0; j < VEC; ++j) w1[j] = tw_full(tw, (uint32_t)(n2 + j) << (TW_LOG2 - log2L));
@@ -256,6 +261,35 @@ __global__ void head_max_zero_kernel(unsigned* __restrict__ mx, int64_t H)
     const int64_t h = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (h < H) mx[h] = 0u;
 }
+// Per head, the bit pattern of the largest magnitude over all rows of a [B,H,N] tensor of 16-bit floats (bf16 or
+// fp16: sign-magnitude, so patterns order like magnitudes).  One block per 8192 samples of one row; the
+// patterns are non-negative integers, so the atomic max is exact and independent of arrival order.
+__global__ void __launch_bounds__(OB) rows_absmax_kernel(const uint4* __restrict__ in, unsigned* __restrict__ mx,
+                                                         int64_t H, int64_t N, unsigned per_row)
+{
+    __shared__ uint32_t red[OB / 64];
+    const int64_t row = blockIdx.x / per_row, h = row % H;
+    const unsigned part = blockIdx.x % per_row;
+    const uint4* r = in + (size_t)row * (size_t)(N / 8) + (size_t)part * (4 * OB);
+    const int64_t left = N / 8 - (int64_t)part * (4 * OB);           // 16-byte pieces of this block's part
+    uint32_t m = 0u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t idx = threadIdx.x + OB * i;
+        if (idx < left) {
+            const uint4 v = r[idx];
+            m = mu::absmax_acc(mu::absmax_acc(mu::absmax_acc(mu::absmax_acc(m, v.x), v.y), v.z), v.w);
+        }
+    }
+    m = mu::absmax_wave(m);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < OB / 64; ++w) m = max(m, red[w]);
+        atomicMax(mx + h, m);
+    }
+}
+
 __global__ void head_max_kernel(const float* __restrict__ k, unsigned* __restrict__ mx, int64_t N)
 {
     __shared__ float red[4];
@@ -339,11 +373,13 @@ hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, 
         if ((1 << log2L2) >= VEC * OB) {
             dim3 grid4((unsigned)(((size_t)1 << log2L2) / (VEC * OB) * (size_t)pr.npairs * (size_t)pr.H));
             hipLaunchKernelGGL((outer_inv4_kernel<IO, LOG2R>), grid4, dim3(OB), 0, st, (const __half2*)ws, (T*)out,
-                               pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm, (const T*)pr.gate);
+                               pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm, (const T*)pr.gate, pr.max_a,
+                               pr.max_b);
             return hipGetLastError();
         }
     }
-    if (pr.gate) return hipErrorInvalidValue;      // only the vectorised pass C applies a gate (see conv_applies_gate)
+    // only the vectorised pass C applies a gate (see conv_applies_gate) or undoes row scales
+    if (pr.gate || pr.max_a || pr.max_b) return hipErrorInvalidValue;
     dim3 grid((unsigned)(((size_t)1 << log2L2) / OB * (size_t)pr.npairs * (size_t)pr.H));
     hipLaunchKernelGGL((outer_inv_kernel<IO, CW, LOG2R>), grid, dim3(OB), 0, st, (const C*)ws, (T*)out, pr.B,
                        pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm);
@@ -421,6 +457,16 @@ hipError_t head_max(const float* k, float* mx, int64_t H, int64_t N, hipStream_t
     hipLaunchKernelGGL(head_max_zero_kernel, dim3((unsigned)((H + 255) / 256)), dim3(256), 0, st, (unsigned*)mx, H);
     hipLaunchKernelGGL(head_max_kernel, dim3((unsigned)((N + 4095) / 4096), (unsigned)H), dim3(256), 0, st, k,
                        (unsigned*)mx, N);
+    return hipGetLastError();
+}
+
+hipError_t rows_absmax(const void* in, uint32_t* mx, const Problem& pr, hipStream_t st)
+{
+    if (pr.io != LONGCONV_F16 && pr.io != LONGCONV_BF16) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(head_max_zero_kernel, dim3((unsigned)((pr.H + 255) / 256)), dim3(256), 0, st, (unsigned*)mx, pr.H);
+    const unsigned per_row = (unsigned)((pr.N + 8 * OB * 4 - 1) / (8 * OB * 4));       // blocks of 8192 samples
+    hipLaunchKernelGGL(rows_absmax_kernel, dim3((unsigned)(per_row * pr.B * pr.H)), dim3(OB), 0, st,
+                       (const uint4*)in, (unsigned*)mx, pr.H, pr.N, per_row);
     return hipGetLastError();
 }
 

@@ -49,3 +49,13 @@ def test_rows_of_one_head_at_very_different_magnitudes(N):
     us[0, 0], ds[0, 0] = 1.0, 1.0            # rows inside the band next to the others
     us[3, 1], ds[2, 0] = 1.0, 1.0
     check_full(scaled_inputs(N, B, H, us, ds, seed=1), label=f"mixed magnitudes, N={N}")
+
+
+@pytest.mark.parametrize("N", [32768, 65536])
+def test_multi_pass_lengths_scale_per_head(N):
+    # the multi-pass plans rescale per head (all rows of a head by one power of two): uniform tiny gradients and
+    # large activations, and heads at very different magnitudes
+    check_full(scaled_inputs(N, 3, 2, 1e3, 1e-5), label=f"u 1e3, dy 1e-5, N={N}")
+    us = np.array([[1e-6, 3e4]])
+    ds = np.array([[2e-9, 1.0]])
+    check_full(scaled_inputs(N, 2, 2, us, ds, seed=2), label=f"heads at different magnitudes, N={N}")
