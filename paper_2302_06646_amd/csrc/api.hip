@@ -1,8 +1,9 @@
 // C-ABI layer of liblongconv: argument validation, planning, workspace carving, dispatch.
 // Every step of the path runs in the kernels of engine_wave.hip (512..4096 points), engine_coop.hip
 // (8192..32768 points, and the inner transforms of longer ones), multipass.hip (outer passes), engine_valu.hip
-// (fp32 I/O) and engine_mfma.hip (first-generation in-place kernel, kept as a cross-check behind a switch and
-// for 256-point inner transforms); nothing here computes on the host.
+// (fp32 I/O), engine_mfma.hip (first-generation in-place kernel, kept as a cross-check behind a switch and
+// for 256-point inner transforms), kreg.hip (kernel regularisers) and gate.hip (the gate's streaming pass);
+// nothing here computes on the host.
 #include <atomic>
 #include <cstdio>
 #include <cstdlib>
