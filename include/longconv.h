@@ -144,7 +144,7 @@ int longconv_fwd_gated(const void* u, const float* k, const float* D, const void
 /* Backward of the gated layer, by the product rule: with dz = dy * g,
  *     du, dk, dD = the gradients of longconv_bwd for dz;      dg[b,h,t] = dy[b,h,t] * z[b,h,t]
  * (z recomputed from u, k, D).  Any of du, dk, dD, dg may be NULL.  dz is rounded to the I/O dtype on its way
- * into the backward pass.  Needs longconv_workspace_bytes(B,H,N,io,2) bytes (the backward workspace plus room
+ * into du and dk; dD is the fp32 sum of dy g u taken from the three tensors themselves.  Needs longconv_workspace_bytes(B,H,N,io,2) bytes (the backward workspace plus room
  * for dz). */
 int longconv_bwd_gated(const void* dy, const void* g, const void* u, const float* k, const float* D,
                        const void* kspec, void* du, float* dk, float* dD, void* dg,

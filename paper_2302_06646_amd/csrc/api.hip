@@ -420,9 +420,17 @@ int longconv_bwd_gated(const void* dy, const void* g, const void* u, const float
     if (du || dk || dD) {
         // dz = dy * g is what the convolution's backward pass receives
         void* dz = (char*)workspace + base;
-        if (note(ew_mul(dy, g, dz, n, io, st), "gate") != hipSuccess) return LONGCONV_ERR_HIP;
-        s = longconv_bwd(dz, u, k, D, kspec, du, dk, dD, B, H, N, io, workspace, base, stream);
-        if (s != LONGCONV_OK) return s;
+        if ((du || dk) && note(ew_mul(dy, g, dz, n, io, st), "gate") != hipSuccess) return LONGCONV_ERR_HIP;
+        if (du || dk) {
+            s = longconv_bwd(dz, u, k, D, kspec, du, dk, nullptr, B, H, N, io, workspace, base, stream);
+            if (s != LONGCONV_OK) return s;
+        }
+        if (dD) {
+            // dD = sum dy g u straight from the three tensors: the rounding of dz to the I/O dtype stays out of it
+            if (!u) return LONGCONV_ERR_NULL;
+            Problem pr{B, H, N, io, (int)((B + 1) / 2)};
+            if (note(head_dot3(dy, g, u, dD, pr, st), "gate dD") != hipSuccess) return LONGCONV_ERR_HIP;
+        }
     }
     if (dg) {
         // dg = dy * z, z the ungated output recomputed: the gated forward with dy in the gate's place

@@ -60,6 +60,9 @@ hipError_t reduce_dD(const float* part, float* dD, int64_t H, int nblk, hipStrea
 
 // ---- kernel regularisers (kreg.hip): Kbar = Squash(Smooth(dropout(K))) and the chain back to K -----------------
 constexpr int KREG_MAX_P = 32;
+// dD[h] = sum_b sum_t dy g u in fp32, one workgroup per head, fixed order (gated layer) (multipass.hip)
+hipError_t head_dot3(const void* dy, const void* g, const void* u, float* dD, const Problem& pr, hipStream_t st);
+
 // out = a * b, element by element, n elements of the I/O dtype (n a multiple of 8; out may alias a or b) (gate.hip)
 hipError_t ew_mul(const void* a, const void* b, void* out, size_t n, int io, hipStream_t st);
 

@@ -345,6 +345,32 @@ __global__ void __launch_bounds__(OB) head_dot_kernel(const typename IO::T* __re
     }
 }
 
+// dD[h] = sum_b sum_t dy[b,h,t] g[b,h,t] u[b,h,t] (gated layer: the dot product of u with dz = dy * g, without the
+// rounding of dz to the I/O dtype), fp32, one workgroup per head, fixed order.
+template <class IO>
+__global__ void __launch_bounds__(OB) head_dot3_kernel(const typename IO::T* __restrict__ dy,
+                                                       const typename IO::T* __restrict__ g,
+                                                       const typename IO::T* __restrict__ u, float* __restrict__ dD,
+                                                       int64_t B, int64_t H, int64_t N)
+{
+    __shared__ float red[OB / 64];
+    const int64_t h = blockIdx.x;
+    float s = 0.f;
+    for (int64_t b = 0; b < B; ++b) {
+        const size_t o = row_off(b, h, H, N);
+        for (int64_t t = threadIdx.x; t < N; t += OB)
+            s = __builtin_fmaf(IO::ld(dy, o + t) * IO::ld(g, o + t), IO::ld(u, o + t), s);
+    }
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int w = 0; w < OB / 64; ++w) t += red[w];
+        dD[h] = t;
+    }
+}
+
 template <class IO, class CW, int LOG2R>
 hipError_t fwd_launch(const void* in, const void* in2, void* ws, void* ws2, float* dD_part, const Problem& pr,
                       int log2L2, float scale, const float2* tw, hipStream_t st, const float* hs)
@@ -479,6 +505,21 @@ hipError_t head_dot(const void* dy, const void* u, float* dD, const Problem& pr,
         hipLaunchKernelGGL(head_dot_kernel<IoF16>, grid, blk, 0, st, (const __half*)dy, (const __half*)u, dD, pr.B, pr.H, pr.N);
     else
         hipLaunchKernelGGL(head_dot_kernel<IoBF16>, grid, blk, 0, st, (const uint16_t*)dy, (const uint16_t*)u, dD, pr.B, pr.H, pr.N);
+    return hipGetLastError();
+}
+
+hipError_t head_dot3(const void* dy, const void* g, const void* u, float* dD, const Problem& pr, hipStream_t st)
+{
+    const dim3 grid((unsigned)pr.H), blk(OB);
+    if (pr.io == LONGCONV_F32)
+        hipLaunchKernelGGL(head_dot3_kernel<IoF32>, grid, blk, 0, st, (const float*)dy, (const float*)g, (const float*)u,
+                           dD, pr.B, pr.H, pr.N);
+    else if (pr.io == LONGCONV_F16)
+        hipLaunchKernelGGL(head_dot3_kernel<IoF16>, grid, blk, 0, st, (const __half*)dy, (const __half*)g,
+                           (const __half*)u, dD, pr.B, pr.H, pr.N);
+    else
+        hipLaunchKernelGGL(head_dot3_kernel<IoBF16>, grid, blk, 0, st, (const uint16_t*)dy, (const uint16_t*)g,
+                           (const uint16_t*)u, dD, pr.B, pr.H, pr.N);
     return hipGetLastError();
 }
 
