@@ -41,24 +41,32 @@ def kernels(asm: str):
 
 
 def min_mfma_read_distance(body):
-    """Smallest number of issue slots between an MFMA and the first non-MFMA instruction that reads its result
-    along the fall-through path, and that pair of lines (None if no MFMA result is read that way)."""
-    best, where = None, None
-    for i, line in enumerate(body):
-        if not line.startswith("v_mfma"):
-            continue
-        ops = [t.strip() for t in line.split(None, 1)[1].split(",")]
-        dst = _regs(ops[0])
-        slots = 0
-        for j in range(i + 1, min(i + _LOOKAHEAD, len(body))):
+    """Smallest number of issue slots between an MFMA and the first non-MFMA instruction that reads its result, over
+    the fall-through path and the taken side of every branch met on the way (a few levels deep), and that pair of
+    lines (None if no MFMA result is read within reach)."""
+    labels = {l[:-1]: i for i, l in enumerate(body) if l.endswith(":")}
+    best = [None, None]
+
+    def scan(start, dst, slots, mfma_line, depth):
+        j = start
+        while j < len(body) and j < start + _LOOKAHEAD and slots < 2 * MIN_SLOTS:
             t = body[j]
+            j += 1
             if t.endswith(":"):
                 continue             # a label: the fall-through path continues
             op = t.split()[0]
-            if op in ("s_branch", "s_endpgm", "s_setpc_b64"):
-                break
+            if op in ("s_endpgm", "s_setpc_b64"):
+                return
             if op == "s_nop":
                 slots += int(t.split()[1]) + 1
+                continue
+            if op == "s_branch" or op.startswith("s_cbranch"):
+                target = labels.get(t.split()[-1])
+                if target is not None and depth < 3:
+                    scan(target, dst, slots + 1, mfma_line, depth + 1)
+                if op == "s_branch":
+                    return
+                slots += 1
                 continue
             toks = [x.strip() for x in (t.split(None, 1)[1] if " " in t else "").split(",")]
             is_store = op.startswith(("ds_write", "ds_store", "global_store", "scratch_store", "buffer_store"))
@@ -67,15 +75,21 @@ def min_mfma_read_distance(body):
                 srcs |= _regs(x.split()[0] if x else "")
             if op.startswith("v_mfma"):
                 if _regs(toks[0]) & dst:
-                    break            # overwritten or chained as accumulator: MFMA-to-MFMA is interlocked
+                    return           # overwritten or chained as accumulator: MFMA-to-MFMA is interlocked
             elif srcs & dst:
-                if best is None or slots < best:
-                    best, where = slots, (line, t)
-                break
+                if best[0] is None or slots < best[0]:
+                    best[0], best[1] = slots, (mfma_line, t)
+                return
+            elif not is_store and toks and toks[0] and _regs(toks[0].split()[0]) >= dst:
+                return               # the whole result is overwritten by something else
             slots += 1
-            if slots >= 2 * MIN_SLOTS:
-                break
-    return best, where
+
+    for i, line in enumerate(body):
+        if not line.startswith("v_mfma"):
+            continue
+        ops = [t.strip() for t in line.split(None, 1)[1].split(",")]
+        scan(i + 1, _regs(ops[0]), 0, line, 0)
+    return best[0], best[1]
 
 
 def check_text(asm: str):

@@ -53,3 +53,21 @@ def test_accumulator_chains_are_not_readers_and_stores_count_their_data():
     assert isa_check.check_text(CHAIN) == []
     (_, body), = list(isa_check.kernels(CHAIN))
     assert isa_check.min_mfma_read_distance(body)[0] == 8
+
+TAKEN = """
+_Zkernel_taken:
+	v_mfma_f32_16x16x32_f16 v[10:13], v[2:5], v[6:9], 0
+	s_cbranch_scc1 .LBB3_5
+	s_nop 7
+	v_cvt_pk_f16_f32 v20, v10, v11
+	s_endpgm
+.LBB3_5:
+	v_ldexp_f32 v21, v12, s4
+	s_endpgm
+.Lfunc_end3:
+"""
+
+
+def test_the_taken_side_of_a_branch_is_followed_too():
+    bad = isa_check.check_text(TAKEN)
+    assert len(bad) == 1 and bad[0][1] == 1 and "v_ldexp_f32" in bad[0][3]
