@@ -643,15 +643,18 @@ __device__ __forceinline__ void publish_patterns(const In<TPW>& first, const In<
         reinterpret_cast<unsigned char*>(mxs + 4 * NWV)[wave] = in_band ? 0 : 1;
     }
 }
-// after the barrier: did any wave of the workgroup see a row outside the band?
+// after the barrier: did any wave of the workgroup see a row outside the band?  The flag bytes are read first
+// (flags_issue) and looked at after whatever independent work the caller has (flags_set), so that the LDS
+// latency is not exposed.
 template <int NWV>
-__device__ __forceinline__ bool any_out_of_band(const uint32_t* mxs)
+__device__ __forceinline__ uint32_t flags_issue(const uint32_t* mxs)
 {
     static_assert(NWV == 4 || NWV == 8, "flag bytes are read as one or two words");
     uint32_t f = mxs[4 * NWV];
     if constexpr (NWV == 8) f |= mxs[4 * NWV + 1];
-    return __builtin_amdgcn_readfirstlane((int)f) != 0;
+    return f;
 }
+__device__ __forceinline__ bool flags_set(uint32_t f) { return __builtin_amdgcn_readfirstlane((int)f) != 0; }
 // the group's maxima -> scales (slow path)
 template <int NWP>
 __device__ __forceinline__ PairScales group_scales(const uint32_t* mxs, int wave)
@@ -877,7 +880,7 @@ wdk_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restri
         if (pnext < npairs) load_src(pnext, u, inu);
         pair_sync<NWP>();
         if constexpr (IsBf<IO>::v && NWP > 1) {
-            if (__builtin_expect(any_out_of_band<NWV>(mxs), 0)) {
+            if (__builtin_expect(flags_set(flags_issue<NWV>(mxs)), 0)) {
                 ps = group_scales<NWP>(mxs, wave);
                 if (act && (ps.efa | ps.efb) != 0) {      // phase 1 of the u pair again, this time with its scales
                     In<TPW> again;
@@ -1140,8 +1143,11 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
         if (act) w_phase1<LG, IO, TPW>(ind, xd, K, t0, lane, ps.efa, ps.efb);
         if (pnext < npairs) load_src(pnext, dy, ind);
         pair_sync<NWP>();
+        uint32_t flags = 0u;
+        if constexpr (IsBf<IO>::v && NWP > 1) flags = flags_issue<NWV>(mxs);
+        if (it > 0) flush_du(it - 1);
         if constexpr (IsBf<IO>::v && NWP > 1) {
-            if (__builtin_expect(any_out_of_band<NWV>(mxs), 0)) {
+            if (__builtin_expect(flags_set(flags), 0)) {
                 ps = group_scales<NWP>(mxs, wave);
                 if (act && (ps.efa | ps.efb) != 0) {      // phase 1 of the dy pair again, this time with its scales
                     In<TPW> again;
@@ -1155,7 +1161,6 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
                 __syncthreads();
             }
         }
-        if (it > 0) flush_du(it - 1);
         f4 wr[TPW], wi[TPW];                             // W of the wave's tiles, fp32 until it meets Z
         if (act) {
             w_phase2_fwd<LG, TPW>(xd, K, ad, wr, wi);
