@@ -151,6 +151,29 @@ int longconv_bwd_gated(const void* dy, const void* g, const void* u, const float
                        int64_t B, int64_t H, int64_t N, int io,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* 2-D long convolution (Section 4.1: the image experiments put 2-D long convolution filters in the place of the
+ * S4ND layers; the paper gives no formula, the reading taken is the 2-D counterpart of Eq. 1): one filter of the
+ * size of the image per head, linear (zero padded, not circular) convolution anchored at the origin and truncated
+ * to the image, plus the skip term,
+ *     y[b,h,i,j] = sum_{p<=i} sum_{q<=j} k[h,p,q] u[b,h,i-p,j-q] + D[h] u[b,h,i,j]     0 <= i < N1, 0 <= j < N2
+ * and in the backward pass its exact adjoints du, dk, dD (any of them may be NULL).  u, y, dy, du are
+ * [B,H,N1,N2] in the I/O dtype, N2 fastest; k, dk are [H,N1,N2] float32; D, dD are [H] float32.  N1 and N2 are
+ * powers of two, N2 >= 8, and N = 2 N1 N2 meets the limits of N above (so images up to 256 x 256, or 128 x 512
+ * and so on); B and H as above with that N.  Inside, every row of image and filter is zero padded to 2 N2 columns
+ * in the workspace and the row-major sequence of N samples goes through longconv_fwd / longconv_bwd, which is
+ * exact for this sum and as large as a 2-D transform of the padded image would be; accuracy, dtype rules and
+ * stream behaviour are those of the 1-D call at that N.  The spectrum is always computed on the fly.
+ * longconv2d_workspace_bytes (backward = 0 or 1) includes the padded copies: about 2 (forward) or 3 (backward)
+ * tensors of twice the image's size, plus the 1-D call's own workspace; 0 on bad arguments. */
+size_t longconv2d_workspace_bytes(int64_t B, int64_t H, int64_t N1, int64_t N2, int io, int backward);
+int longconv2d_fwd(const void* u, const float* k, const float* D, void* y,
+                   int64_t B, int64_t H, int64_t N1, int64_t N2, int io,
+                   void* workspace, size_t workspace_bytes, void* stream);
+int longconv2d_bwd(const void* dy, const void* u, const float* k, const float* D,
+                   void* du, float* dk, float* dD,
+                   int64_t B, int64_t H, int64_t N1, int64_t N2, int io,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
 /* Kernel regularisers in front of the convolution (Algorithm 1 lines 1-3; Section 3.1,
  * "Regularizing the Kernel"), for the raw parameter K [H,N] f32:
  *     K1 = drop_mask * K                      dropout; the mask (0 or 1/(1-q) per entry, [H,N] f32)

@@ -10,7 +10,7 @@ Functions mirror the C ABI of ``include/longconv.h``:
     longconv_init, longconv_kspec_bytes, longconv_workspace_bytes,
     longconv_kspec_compute, longconv_fwd, longconv_bwd, longconv_plan_string,
     longconv_set_option, longconv_fwd_noalloc, longconv_kreg_fwd, longconv_kreg_bwd,
-    longconv_fwd_gated, longconv_bwd_gated
+    longconv_fwd_gated, longconv_bwd_gated, longconv2d_workspace_bytes, longconv2d_fwd, longconv2d_bwd
 """
 from __future__ import annotations
 
@@ -31,7 +31,8 @@ EXPORTS = ("longconv_init", "longconv_kspec_bytes", "longconv_workspace_bytes",
            "longconv_kspec_compute", "longconv_fwd", "longconv_bwd", "longconv_status_string",
            "longconv_last_hip_error", "longconv_plan_string", "longconv_set_option",
            "longconv_fwd_noalloc", "longconv_kreg_fwd", "longconv_kreg_bwd",
-           "longconv_fwd_gated", "longconv_bwd_gated")
+           "longconv_fwd_gated", "longconv_bwd_gated",
+           "longconv2d_workspace_bytes", "longconv2d_fwd", "longconv2d_bwd")
 
 
 class LongconvError(RuntimeError):
@@ -73,6 +74,12 @@ def lib():
         L.longconv_fwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, sz, vp]
         L.longconv_bwd_gated.restype = ci
         L.longconv_bwd_gated.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, sz, vp]
+        L.longconv2d_workspace_bytes.restype = sz
+        L.longconv2d_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
+        L.longconv2d_fwd.restype = ci
+        L.longconv2d_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, sz, vp]
+        L.longconv2d_bwd.restype = ci
+        L.longconv2d_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, sz, vp]
         L.longconv_set_option.restype = ci
         L.longconv_set_option.argtypes = [ctypes.c_char_p, ci]
         _lib = L
@@ -208,6 +215,39 @@ def longconv_bwd_gated(dy, g, u, k, D, du, dk, dD, dg, workspace, kspec=None, st
     _check(lib().longconv_bwd_gated(_ptr(dy), _ptr(g), _ptr(u), _ptr(k), _ptr(D), _ptr(kspec), _ptr(du), _ptr(dk),
                                     _ptr(dD), _ptr(dg), B, H, N, io, _ptr(workspace), workspace.numel(),
                                     _stream(stream)), "longconv_bwd_gated")
+
+
+def longconv2d_workspace_bytes(B: int, H: int, N1: int, N2: int, io: int, backward) -> int:
+    return int(lib().longconv2d_workspace_bytes(B, H, N1, N2, io, int(bool(backward))))
+
+
+def new_workspace2d(B, H, N1, N2, io, backward, device="cuda"):
+    n = longconv2d_workspace_bytes(B, H, N1, N2, io, backward)
+    if n == 0:
+        raise LongconvError("bad shape or dtype")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def longconv2d_fwd(u, k, D, y, workspace, stream=None) -> None:
+    """y[b,h] <- the 2-D linear convolution of u[b,h] with k[h], truncated to the image, + D[h] u[b,h]."""
+    B, H, N1, N2 = u.shape
+    io = dtype_code(u)
+    _need(u, "u", _TORCH_DTYPE[io], (B, H, N1, N2)); _need(y, "y", _TORCH_DTYPE[io], (B, H, N1, N2))
+    _need(k, "k", torch.float32, (H, N1, N2)); _need(D, "D", torch.float32, (H,))
+    _check(lib().longconv2d_fwd(_ptr(u), _ptr(k), _ptr(D), _ptr(y), B, H, N1, N2, io, _ptr(workspace),
+                                workspace.numel(), _stream(stream)), "longconv2d_fwd")
+
+
+def longconv2d_bwd(dy, u, k, D, du, dk, dD, workspace, stream=None) -> None:
+    """du, dk, dD <- adjoints of longconv2d_fwd (any of the three may be None)."""
+    B, H, N1, N2 = dy.shape
+    io = dtype_code(dy)
+    for t, name in ((dy, "dy"), (u, "u"), (du, "du")):
+        _need(t, name, _TORCH_DTYPE[io], (B, H, N1, N2))
+    _need(k, "k", torch.float32, (H, N1, N2)); _need(D, "D", torch.float32, (H,))
+    _need(dk, "dk", torch.float32, (H, N1, N2)); _need(dD, "dD", torch.float32, (H,))
+    _check(lib().longconv2d_bwd(_ptr(dy), _ptr(u), _ptr(k), _ptr(D), _ptr(du), _ptr(dk), _ptr(dD), B, H, N1, N2, io,
+                                _ptr(workspace), workspace.numel(), _stream(stream)), "longconv2d_bwd")
 
 
 STATIC_SCRATCH_BYTES = 64 << 20

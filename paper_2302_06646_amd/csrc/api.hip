@@ -2,8 +2,8 @@
 // Every step of the path runs in the kernels of engine_wave.hip (512..4096 points), engine_coop.hip
 // (8192..32768 points, and the inner transforms of longer ones), multipass.hip (outer passes), engine_valu.hip
 // (fp32 I/O), engine_mfma.hip (first-generation in-place kernel, kept as a cross-check behind a switch and
-// for 256-point inner transforms), kreg.hip (kernel regularisers) and gate.hip (the gate's streaming pass);
-// nothing here computes on the host.
+// for 256-point inner transforms), kreg.hip (kernel regularisers), gate.hip (the gate's streaming pass) and
+// conv2d.hip (row padding of the 2-D convolution); nothing here computes on the host.
 #include <atomic>
 #include <cstdio>
 #include <cstdlib>
@@ -559,6 +559,93 @@ int longconv_bwd(const void* dy, const void* u, const float* k, const float* D, 
         if (note(run_conv(dy, ks, du, base + w.ws1, true, prd, pl, tb, st, dy_ready), "bwd du") != hipSuccess)
             return LONGCONV_ERR_HIP;
     }
+    return LONGCONV_OK;
+}
+
+// ---- 2-D long convolution: rows padded to twice their width, then the 1-D path on the row-major sequence -------
+
+struct Ws2d {
+    size_t base, kp, up, yp, dup, dkp, total;     // byte offsets; base = size of the 1-D call's own workspace
+};
+static int check_shape2d(int64_t B, int64_t H, int64_t N1, int64_t N2, int io)
+{
+    if (io != LONGCONV_F32 && io != LONGCONV_F16 && io != LONGCONV_BF16) return LONGCONV_ERR_DTYPE;
+    if (!pow2(N1) || !pow2(N2) || N2 < 8 || N1 > 131072 || N2 > 65536) return LONGCONV_ERR_SHAPE;
+    return check_shape(B, H, 2 * N1 * N2, io);
+}
+static Ws2d carve2d(int64_t B, int64_t H, int64_t N, int io, bool backward)
+{
+    Ws2d w{};
+    const size_t rows = up256((size_t)B * H * N * io_bytes(io)), heads = up256((size_t)H * N * sizeof(float));
+    size_t off = up256(longconv_workspace_bytes(B, H, N, io, backward ? 1 : 0));
+    w.base = off;
+    w.kp = off;  off += heads;
+    w.up = off;  off += rows;
+    w.yp = off;  off += rows;                      // y of the forward pass, dy of the backward pass
+    if (backward) {
+        w.dup = off; off += rows;
+        w.dkp = off; off += heads;
+    }
+    w.total = off;
+    return w;
+}
+
+size_t longconv2d_workspace_bytes(int64_t B, int64_t H, int64_t N1, int64_t N2, int io, int backward)
+{
+    if (check_shape2d(B, H, N1, N2, io) != LONGCONV_OK) return 0;
+    return carve2d(B, H, 2 * N1 * N2, io, backward != 0).total;
+}
+
+int longconv2d_fwd(const void* u, const float* k, const float* D, void* y, int64_t B, int64_t H, int64_t N1,
+                   int64_t N2, int io, void* workspace, size_t workspace_bytes, void* stream)
+{
+    int s = check_shape2d(B, H, N1, N2, io);
+    if (s != LONGCONV_OK) return s;
+    if (!u || !k || !D || !y) return LONGCONV_ERR_NULL;
+    if (misaligned(u) || misaligned(k) || misaligned(y) || misaligned(workspace)) return LONGCONV_ERR_ALIGN;
+    const int64_t N = 2 * N1 * N2;
+    const Ws2d w = carve2d(B, H, N, io, false);
+    if (!workspace || workspace_bytes < w.total) return LONGCONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    if (note(pad_rows(k, ws + w.kp, (size_t)H * N1, (size_t)N2 * sizeof(float), st), "pad k") != hipSuccess ||
+        note(pad_rows(u, ws + w.up, (size_t)B * H * N1, (size_t)N2 * io_bytes(io), st), "pad u") != hipSuccess)
+        return LONGCONV_ERR_HIP;
+    s = longconv_fwd(ws + w.up, (const float*)(ws + w.kp), D, nullptr, ws + w.yp, B, H, N, io, ws, w.base, stream);
+    if (s != LONGCONV_OK) return s;
+    if (note(unpad_rows(ws + w.yp, y, (size_t)B * H * N1, (size_t)N2 * io_bytes(io), st), "unpad y") != hipSuccess)
+        return LONGCONV_ERR_HIP;
+    return LONGCONV_OK;
+}
+
+int longconv2d_bwd(const void* dy, const void* u, const float* k, const float* D, void* du, float* dk, float* dD,
+                   int64_t B, int64_t H, int64_t N1, int64_t N2, int io, void* workspace, size_t workspace_bytes,
+                   void* stream)
+{
+    int s = check_shape2d(B, H, N1, N2, io);
+    if (s != LONGCONV_OK) return s;
+    if (!dy || ((dk || dD) && !u) || (du && (!k || !D))) return LONGCONV_ERR_NULL;
+    if (misaligned(dy) || misaligned(u) || misaligned(k) || misaligned(du) || misaligned(dk) || misaligned(workspace))
+        return LONGCONV_ERR_ALIGN;
+    const int64_t N = 2 * N1 * N2;
+    const Ws2d w = carve2d(B, H, N, io, true);
+    if (!workspace || workspace_bytes < w.total) return LONGCONV_ERR_WORKSPACE;
+    if (!du && !dk && !dD) return LONGCONV_OK;
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    const size_t rows = (size_t)B * H * N1, rb = (size_t)N2 * io_bytes(io);
+    if (note(pad_rows(dy, ws + w.yp, rows, rb, st), "pad dy") != hipSuccess) return LONGCONV_ERR_HIP;
+    if ((dk || dD) && note(pad_rows(u, ws + w.up, rows, rb, st), "pad u") != hipSuccess) return LONGCONV_ERR_HIP;
+    if (du && note(pad_rows(k, ws + w.kp, (size_t)H * N1, (size_t)N2 * sizeof(float), st), "pad k") != hipSuccess)
+        return LONGCONV_ERR_HIP;
+    s = longconv_bwd(ws + w.yp, ws + w.up, (const float*)(ws + w.kp), D, nullptr, du ? ws + w.dup : nullptr,
+                     dk ? (float*)(ws + w.dkp) : nullptr, dD, B, H, N, io, ws, w.base, stream);
+    if (s != LONGCONV_OK) return s;
+    // the gradient with respect to the padding columns of the image and of the filter is dropped: they are
+    // constants of the construction, not parameters
+    if (du && note(unpad_rows(ws + w.dup, du, rows, rb, st), "unpad du") != hipSuccess) return LONGCONV_ERR_HIP;
+    if (dk && note(unpad_rows(ws + w.dkp, dk, (size_t)H * N1, (size_t)N2 * sizeof(float), st), "unpad dk") != hipSuccess)
+        return LONGCONV_ERR_HIP;
     return LONGCONV_OK;
 }
 

@@ -58,14 +58,18 @@ hipError_t head_dot(const void* dy, const void* u, float* dD, const Problem& pr,
 // dD[h] = sum of the per-block partials written by outer_fwd.
 hipError_t reduce_dD(const float* part, float* dD, int64_t H, int nblk, hipStream_t st);
 
-// ---- kernel regularisers (kreg.hip): Kbar = Squash(Smooth(dropout(K))) and the chain back to K -----------------
-constexpr int KREG_MAX_P = 32;
 // dD[h] = sum_b sum_t dy g u in fp32, one workgroup per head, fixed order (gated layer) (multipass.hip)
 hipError_t head_dot3(const void* dy, const void* g, const void* u, float* dD, const Problem& pr, hipStream_t st);
 
 // out = a * b, element by element, n elements of the I/O dtype (n a multiple of 8; out may alias a or b) (gate.hip)
 hipError_t ew_mul(const void* a, const void* b, void* out, size_t n, int io, hipStream_t st);
 
+// 2-D convolution through the 1-D path (conv2d.hip): rows padded to twice their width with zeros, and back
+hipError_t pad_rows(const void* src, void* dst, size_t rows, size_t row_bytes, hipStream_t st);
+hipError_t unpad_rows(const void* src, void* dst, size_t rows, size_t row_bytes, hipStream_t st);
+
+// ---- kernel regularisers (kreg.hip): Kbar = Squash(Smooth(dropout(K))) and the chain back to K -----------------
+constexpr int KREG_MAX_P = 32;
 hipError_t kreg_fwd(const float* k, const float* mask, float* kbar, int64_t H, int64_t N, int p, float lam,
                     hipStream_t st);
 hipError_t kreg_bwd(const float* k, const float* mask, const float* dkbar, float* dk, int64_t H, int64_t N, int p,
