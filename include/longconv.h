@@ -174,6 +174,38 @@ int longconv2d_bwd(const void* dy, const void* u, const float* k, const float* D
                    int64_t B, int64_t H, int64_t N1, int64_t N2, int io,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* Learned Butterfly extension (Section 3.3: the values of the Butterfly blocks of the FFT convolution are learned
+ * per head instead of fixed to the DFT; the paper gives no formula, this is the reading taken).  L = 2N = 2^LG,
+ * three stages over the digits (d_0, d_1, d_2) of a position, d_0 most significant, d_0 and d_1 four bits wide
+ * (block size 16), d_2 the remaining LG - 8 bits (block size r_last = 2N / 256):
+ *     T_A[h]: for s = 0, 1, 2 apply block A[h,s] along digit s, then (s < 2) multiply position p, whose digit s is
+ *             now k_s, by exp(-2 pi i k_s (p mod M_s) / (16 M_s)), M_s the stride of digit s (the twiddle of
+ *             Appendix C.1).  After it, position (k_0, k_1, k_2) holds "frequency" k_0 + 16 k_1 + 256 k_2.
+ *     T_B[h]: the mirror image, s = 2, 1, 0: (s < 2) the conjugate twiddle, then block Bm[h,s]; finally 1 / L.
+ *     y[b,h,t] = Re( T_B[h]( Shat[h] . T_A[h]( [u[b,h,:], 0_N] ) ) )[t]          0 <= t < N
+ * Shat [H, 2N] complex, natural frequency order, is the spectrum the fixed path stores (Algorithm 2 lines 1-2):
+ * FFT_2N([k[h,:], 0_N]) + D[h]; the extension does not touch it.  With A[h,s] = DFT and Bm[h,s] = conj(DFT) the
+ * result is Eq. 1 exactly.
+ *   Af, Ai, dAf, dAi: [H, 3, 16, 16, 2] float32 (row, column, re / im); the last stage reads the leading
+ *       r_last x r_last corner only and its gradient is zero outside it.
+ *   shat, dshat: [H, 2N, 2] float32.  u, y, dy, du: [B,H,N] fp16 or bf16 (LONGCONV_ERR_DTYPE otherwise), values
+ *       within fp16's range (rows are not rescaled here).  N = 256, 512, 1024 or 2048; B, H as above.
+ *   A complex parameter's gradient is dL/dRe + i dL/dIm.  du, dshat, dAf, dAi may each be NULL.
+ * Arithmetic: fp16 matrix-core operands (the blocks are rounded to fp16), fp32 accumulation, fp16 data between
+ * stages; every gradient is summed in a fixed order (bitwise repeatable).  longconv_lbfly_spectrum makes Shat from
+ * (k, D) in fp32 on the device and longconv_lbfly_spectrum_bwd turns dShat into dk (its first N samples of the
+ * conjugate transform) and dD (either may be NULL).  Only the backward pass needs a workspace:
+ * longconv_lbfly_workspace_bytes (0 on bad arguments). */
+size_t longconv_lbfly_workspace_bytes(int64_t B, int64_t H, int64_t N, int io);
+int longconv_lbfly_spectrum(const float* k, const float* D, float* shat, int64_t H, int64_t N, void* stream);
+int longconv_lbfly_spectrum_bwd(const float* dshat, float* dk, float* dD, int64_t H, int64_t N, void* stream);
+int longconv_lbfly_fwd(const void* u, const float* shat, const float* Af, const float* Ai, void* y,
+                       int64_t B, int64_t H, int64_t N, int io, void* stream);
+int longconv_lbfly_bwd(const void* dy, const void* u, const float* shat, const float* Af, const float* Ai,
+                       void* du, float* dshat, float* dAf, float* dAi,
+                       int64_t B, int64_t H, int64_t N, int io,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 /* Kernel regularisers in front of the convolution (Algorithm 1 lines 1-3; Section 3.1,
  * "Regularizing the Kernel"), for the raw parameter K [H,N] f32:
  *     K1 = drop_mask * K                      dropout; the mask (0 or 1/(1-q) per entry, [H,N] f32)

@@ -10,7 +10,9 @@ Functions mirror the C ABI of ``include/longconv.h``:
     longconv_init, longconv_kspec_bytes, longconv_workspace_bytes,
     longconv_kspec_compute, longconv_fwd, longconv_bwd, longconv_plan_string,
     longconv_set_option, longconv_fwd_noalloc, longconv_kreg_fwd, longconv_kreg_bwd,
-    longconv_fwd_gated, longconv_bwd_gated, longconv2d_workspace_bytes, longconv2d_fwd, longconv2d_bwd
+    longconv_fwd_gated, longconv_bwd_gated, longconv2d_workspace_bytes, longconv2d_fwd, longconv2d_bwd,
+    longconv_lbfly_workspace_bytes, longconv_lbfly_spectrum, longconv_lbfly_spectrum_bwd, longconv_lbfly_fwd,
+    longconv_lbfly_bwd
 """
 from __future__ import annotations
 
@@ -32,7 +34,9 @@ EXPORTS = ("longconv_init", "longconv_kspec_bytes", "longconv_workspace_bytes",
            "longconv_last_hip_error", "longconv_plan_string", "longconv_set_option",
            "longconv_fwd_noalloc", "longconv_kreg_fwd", "longconv_kreg_bwd",
            "longconv_fwd_gated", "longconv_bwd_gated",
-           "longconv2d_workspace_bytes", "longconv2d_fwd", "longconv2d_bwd")
+           "longconv2d_workspace_bytes", "longconv2d_fwd", "longconv2d_bwd",
+           "longconv_lbfly_workspace_bytes", "longconv_lbfly_spectrum", "longconv_lbfly_spectrum_bwd",
+           "longconv_lbfly_fwd", "longconv_lbfly_bwd")
 
 
 class LongconvError(RuntimeError):
@@ -80,6 +84,16 @@ def lib():
         L.longconv2d_fwd.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, sz, vp]
         L.longconv2d_bwd.restype = ci
         L.longconv2d_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, vp, sz, vp]
+        L.longconv_lbfly_workspace_bytes.restype = sz
+        L.longconv_lbfly_workspace_bytes.argtypes = [i64, i64, i64, ci]
+        L.longconv_lbfly_spectrum.restype = ci
+        L.longconv_lbfly_spectrum.argtypes = [vp, vp, vp, i64, i64, vp]
+        L.longconv_lbfly_spectrum_bwd.restype = ci
+        L.longconv_lbfly_spectrum_bwd.argtypes = [vp, vp, vp, i64, i64, vp]
+        L.longconv_lbfly_fwd.restype = ci
+        L.longconv_lbfly_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp]
+        L.longconv_lbfly_bwd.restype = ci
+        L.longconv_lbfly_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, sz, vp]
         L.longconv_set_option.restype = ci
         L.longconv_set_option.argtypes = [ctypes.c_char_p, ci]
         _lib = L
@@ -248,6 +262,52 @@ def longconv2d_bwd(dy, u, k, D, du, dk, dD, workspace, stream=None) -> None:
     _need(dk, "dk", torch.float32, (H, N1, N2)); _need(dD, "dD", torch.float32, (H,))
     _check(lib().longconv2d_bwd(_ptr(dy), _ptr(u), _ptr(k), _ptr(D), _ptr(du), _ptr(dk), _ptr(dD), B, H, N1, N2, io,
                                 _ptr(workspace), workspace.numel(), _stream(stream)), "longconv2d_bwd")
+
+
+def longconv_lbfly_workspace_bytes(B: int, H: int, N: int, io: int) -> int:
+    return int(lib().longconv_lbfly_workspace_bytes(B, H, N, io))
+
+
+def longconv_lbfly_spectrum(k, D, shat, stream=None) -> None:
+    """shat [H, 2N, 2] <- FFT([k, 0]) + D in natural frequency order (re, im)."""
+    H, N = k.shape
+    _need(k, "k", torch.float32, (H, N)); _need(D, "D", torch.float32, (H,))
+    _need(shat, "shat", torch.float32, (H, 2 * N, 2))
+    _check(lib().longconv_lbfly_spectrum(_ptr(k), _ptr(D), _ptr(shat), H, N, _stream(stream)), "longconv_lbfly_spectrum")
+
+
+def longconv_lbfly_spectrum_bwd(dshat, dk, dD, stream=None) -> None:
+    """dk [H, N], dD [H] <- the adjoint of longconv_lbfly_spectrum applied to dshat (either may be None)."""
+    H, L, _ = dshat.shape
+    _need(dshat, "dshat", torch.float32, (H, L, 2)); _need(dk, "dk", torch.float32, (H, L // 2))
+    _need(dD, "dD", torch.float32, (H,))
+    _check(lib().longconv_lbfly_spectrum_bwd(_ptr(dshat), _ptr(dk), _ptr(dD), H, L // 2, _stream(stream)),
+           "longconv_lbfly_spectrum_bwd")
+
+
+def longconv_lbfly_fwd(u, shat, Af, Ai, y, stream=None) -> None:
+    """y <- Re(T_B(shat . T_A([u, 0])))[:N] with the per-head blocks Af, Ai [H, 3, 16, 16, 2]."""
+    B, H, N = u.shape
+    io = dtype_code(u)
+    _need(u, "u", _TORCH_DTYPE[io], (B, H, N)); _need(y, "y", _TORCH_DTYPE[io], (B, H, N))
+    _need(shat, "shat", torch.float32, (H, 2 * N, 2))
+    _need(Af, "Af", torch.float32, (H, 3, 16, 16, 2)); _need(Ai, "Ai", torch.float32, (H, 3, 16, 16, 2))
+    _check(lib().longconv_lbfly_fwd(_ptr(u), _ptr(shat), _ptr(Af), _ptr(Ai), _ptr(y), B, H, N, io, _stream(stream)),
+           "longconv_lbfly_fwd")
+
+
+def longconv_lbfly_bwd(dy, u, shat, Af, Ai, du, dshat, dAf, dAi, workspace, stream=None) -> None:
+    """du, dshat, dAf, dAi <- gradients of longconv_lbfly_fwd (any may be None)."""
+    B, H, N = dy.shape
+    io = dtype_code(dy)
+    for t, name in ((dy, "dy"), (u, "u"), (du, "du")):
+        _need(t, name, _TORCH_DTYPE[io], (B, H, N))
+    _need(shat, "shat", torch.float32, (H, 2 * N, 2)); _need(dshat, "dshat", torch.float32, (H, 2 * N, 2))
+    for t, name in ((Af, "Af"), (Ai, "Ai"), (dAf, "dAf"), (dAi, "dAi")):
+        _need(t, name, torch.float32, (H, 3, 16, 16, 2))
+    _check(lib().longconv_lbfly_bwd(_ptr(dy), _ptr(u), _ptr(shat), _ptr(Af), _ptr(Ai), _ptr(du), _ptr(dshat),
+                                    _ptr(dAf), _ptr(dAi), B, H, N, io, _ptr(workspace), workspace.numel(),
+                                    _stream(stream)), "longconv_lbfly_bwd")
 
 
 STATIC_SCRATCH_BYTES = 64 << 20

@@ -3,7 +3,8 @@
 // (8192..32768 points, and the inner transforms of longer ones), multipass.hip (outer passes), engine_valu.hip
 // (fp32 I/O), engine_mfma.hip (first-generation in-place kernel, kept as a cross-check behind a switch and
 // for 256-point inner transforms), kreg.hip (kernel regularisers), gate.hip (the gate's streaming pass) and
-// conv2d.hip (row padding of the 2-D convolution); nothing here computes on the host.
+// conv2d.hip (row padding of the 2-D convolution), lbfly.hip (learned Butterfly extension); nothing here computes
+// on the host.
 #include <atomic>
 #include <cstdio>
 #include <cstdlib>
@@ -647,6 +648,86 @@ int longconv2d_bwd(const void* dy, const void* u, const float* k, const float* D
     if (dk && note(unpad_rows(ws + w.dkp, dk, (size_t)H * N1, (size_t)N2 * sizeof(float), st), "unpad dk") != hipSuccess)
         return LONGCONV_ERR_HIP;
     return LONGCONV_OK;
+}
+
+// ---- learned Butterfly extension -----------------------------------------------------------------------------------
+
+static int check_shape_lb(int64_t B, int64_t H, int64_t N, int io)
+{
+    if (io != LONGCONV_F16 && io != LONGCONV_BF16) return LONGCONV_ERR_DTYPE;
+    if (B < 1 || B > (int64_t(1) << 24) || H < 1 || H > 65535) return LONGCONV_ERR_SHAPE;
+    if (!pow2(N) || N < 256 || N > 2048) return LONGCONV_ERR_SHAPE;
+    return LONGCONV_OK;
+}
+
+size_t longconv_lbfly_workspace_bytes(int64_t B, int64_t H, int64_t N, int io)
+{
+    if (check_shape_lb(B, H, N, io) != LONGCONV_OK) return 0;
+    return up256(lbfly_partial_bytes(B, H, N));
+}
+
+int longconv_lbfly_spectrum(const float* k, const float* D, float* shat, int64_t H, int64_t N, void* stream)
+{
+    int s = check_shape_lb(1, H, N, LONGCONV_F16);
+    if (s != LONGCONV_OK) return s;
+    if (!k || !D || !shat) return LONGCONV_ERR_NULL;
+    if (misaligned(k) || misaligned(shat)) return LONGCONV_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    Tables tb;
+    if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    return note(lbfly_spectrum(k, D, shat, H, N, tb, st), "lbfly spectrum") == hipSuccess ? LONGCONV_OK
+                                                                                          : LONGCONV_ERR_HIP;
+}
+
+int longconv_lbfly_spectrum_bwd(const float* dshat, float* dk, float* dD, int64_t H, int64_t N, void* stream)
+{
+    int s = check_shape_lb(1, H, N, LONGCONV_F16);
+    if (s != LONGCONV_OK) return s;
+    if (!dshat) return LONGCONV_ERR_NULL;
+    if (misaligned(dshat) || misaligned(dk)) return LONGCONV_ERR_ALIGN;
+    if (!dk && !dD) return LONGCONV_OK;
+    hipStream_t st = (hipStream_t)stream;
+    Tables tb;
+    if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    return note(lbfly_spectrum_bwd(dshat, dk, dD, H, N, tb, st), "lbfly spectrum bwd") == hipSuccess
+               ? LONGCONV_OK
+               : LONGCONV_ERR_HIP;
+}
+
+int longconv_lbfly_fwd(const void* u, const float* shat, const float* Af, const float* Ai, void* y, int64_t B,
+                       int64_t H, int64_t N, int io, void* stream)
+{
+    int s = check_shape_lb(B, H, N, io);
+    if (s != LONGCONV_OK) return s;
+    if (!u || !shat || !Af || !Ai || !y) return LONGCONV_ERR_NULL;
+    if (misaligned(u) || misaligned(shat) || misaligned(Af) || misaligned(Ai) || misaligned(y))
+        return LONGCONV_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    Tables tb;
+    if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    return note(lbfly_fwd(u, shat, Af, Ai, y, B, H, N, io, tb, st), "lbfly fwd") == hipSuccess ? LONGCONV_OK
+                                                                                                : LONGCONV_ERR_HIP;
+}
+
+int longconv_lbfly_bwd(const void* dy, const void* u, const float* shat, const float* Af, const float* Ai, void* du,
+                       float* dshat, float* dAf, float* dAi, int64_t B, int64_t H, int64_t N, int io, void* workspace,
+                       size_t workspace_bytes, void* stream)
+{
+    int s = check_shape_lb(B, H, N, io);
+    if (s != LONGCONV_OK) return s;
+    if (!dy || !u || !shat || !Af || !Ai) return LONGCONV_ERR_NULL;
+    if (misaligned(dy) || misaligned(u) || misaligned(shat) || misaligned(Af) || misaligned(Ai) || misaligned(du) ||
+        misaligned(dshat) || misaligned(dAf) || misaligned(dAi) || misaligned(workspace))
+        return LONGCONV_ERR_ALIGN;
+    if (!workspace || workspace_bytes < up256(lbfly_partial_bytes(B, H, N))) return LONGCONV_ERR_WORKSPACE;
+    if (!du && !dshat && !dAf && !dAi) return LONGCONV_OK;
+    hipStream_t st = (hipStream_t)stream;
+    Tables tb;
+    if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    return note(lbfly_bwd(dy, u, shat, Af, Ai, du, dshat, dAf, dAi, workspace, B, H, N, io, tb, st), "lbfly bwd") ==
+                   hipSuccess
+               ? LONGCONV_OK
+               : LONGCONV_ERR_HIP;
 }
 
 static int kreg_check(const float* k, const void* a, const void* b, int64_t H, int64_t N, int p, float lambda)

@@ -68,6 +68,20 @@ hipError_t ew_mul(const void* a, const void* b, void* out, size_t n, int io, hip
 hipError_t pad_rows(const void* src, void* dst, size_t rows, size_t row_bytes, hipStream_t st);
 hipError_t unpad_rows(const void* src, void* dst, size_t rows, size_t row_bytes, hipStream_t st);
 
+// ---- learned Butterfly extension (lbfly.hip): N = 256 .. 2048, fp16 / bf16 rows -----------------------------------
+// rows are split over this many workgroups per head in the backward pass; their partial sums need lbfly_partial_bytes
+int lbfly_nsplit(int64_t B, int64_t H);
+size_t lbfly_partial_bytes(int64_t B, int64_t H, int64_t N);
+hipError_t lbfly_fwd(const void* u, const float* shat, const float* Af, const float* Ai, void* y, int64_t B, int64_t H,
+                     int64_t N, int io, const Tables& tb, hipStream_t st);
+hipError_t lbfly_bwd(const void* dy, const void* u, const float* shat, const float* Af, const float* Ai, void* du,
+                     float* dshat, float* dAf, float* dAi, void* partials, int64_t B, int64_t H, int64_t N, int io,
+                     const Tables& tb, hipStream_t st);
+hipError_t lbfly_spectrum(const float* k, const float* D, float* shat, int64_t H, int64_t N, const Tables& tb,
+                          hipStream_t st);
+hipError_t lbfly_spectrum_bwd(const float* dshat, float* dk, float* dD, int64_t H, int64_t N, const Tables& tb,
+                              hipStream_t st);
+
 // ---- kernel regularisers (kreg.hip): Kbar = Squash(Smooth(dropout(K))) and the chain back to K -----------------
 constexpr int KREG_MAX_P = 32;
 hipError_t kreg_fwd(const float* k, const float* mask, float* kbar, int64_t H, int64_t N, int p, float lam,
