@@ -16,7 +16,7 @@
 // Every block product is one pair of v_mfma_f32_16x16x32_f16 per 16 columns (real form of the complex product, K =
 // 16 slots x (re, im)), data as fp16 complex in LDS between stages, fp32 accumulation; every stage carries a fixed
 // power of two (1/4 per 16-point block) so that DFT-like blocks keep the data at unit magnitude, undone in fp32 at
-// the end.  Backward: the forward chain is run again with the input of every stage kept in LDS (eight buffers of L
+// the end.  Backward: the forward chain is run again with the input of every stage kept in LDS (seven buffers of L
 // complex fp16), then the gradient walks the stages in reverse; the gradient of a block is the 16 x 16 complex
 // matrix sum over columns of (gradient at the block's output) x conj(the block's input), two more MFMAs per 16
 // columns with the columns as the K dimension, accumulated in fp32 registers over the rows a workgroup owns.
@@ -36,7 +36,8 @@ typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 constexpr int NBLK = 256;                       // entries of one 16 x 16 block
 __host__ __device__ constexpr int stage_shift(int b) { return b == 4 ? 2 : (b >= 2 ? 1 : 0); }
 __host__ __device__ constexpr int total_shift(int lg) { return 4 + stage_shift(lg - 8); }
-__host__ __device__ constexpr int lb_waves(int lg) { return lg == 9 ? 2 : 4; }
+__host__ __device__ constexpr int lb_waves(int lg) { return lg == 9 ? 2 : 4; }          // forward kernel
+__host__ __device__ constexpr int lbb_waves(int lg) { return lg == 9 ? 2 : lg == 10 ? 4 : 8; }   // backward kernel
 
 struct Mats {
     h8 re, im;   // A operands producing the real / imaginary part of the output
@@ -97,11 +98,33 @@ __device__ __forceinline__ int tile_pos(int gamma, int sigma, int lgM)
     return ((gamma >> lgM) << (lgM + 4)) | (gamma & ((1 << lgM) - 1)) | (sigma << lgM);
 }
 
+// Physical LDS index of position p: bank bits 2..5 are XORed with position bits 4..7 and 7..10.  Stages read a tile
+// with one slot digit spread over the lanes (strides of 2, 16, 128 ... words), the block gradients read it with the
+// roles of slot and column swapped; unswizzled, that is a five- to six-fold bank conflict on average over the access
+// patterns of this file, with this map about two-fold (bits 0, 1 stay, so runs of four positions remain one aligned
+// 16-byte access).  The map is linear over XOR: phys(a | b) = phys(a) ^ phys(b) for disjoint a, b.
+__host__ __device__ constexpr int phys(int p) { return p ^ ((((p >> 4) ^ (p >> 7)) & 15) << 2); }
+
 // frequency held by position p after the forward chain
 template <int LG>
 __device__ __forceinline__ int freq_of(int p)
 {
     return (p >> (LG - 4)) | (((p >> (LG - 8)) & 15) << 4) | ((p & ((1 << (LG - 8)) - 1)) << 8);
+}
+
+// position that holds frequency f after the forward chain (the inverse of freq_of)
+template <int LG>
+__device__ __forceinline__ int pos_of(int f)
+{
+    return ((f & 15) << (LG - 4)) | (((f >> 4) & 15) << (LG - 8)) | (f >> 8);
+}
+
+// the head's spectrum, natural order in memory, into LDS in position order: the lanes of the middle step then read
+// their four bins as one 32-byte run instead of gathering them from 64 different cache lines per instruction
+template <int LG>
+__device__ __forceinline__ void stage_spectrum(float2* sS, const float2* __restrict__ sh, int tid, int nt)
+{
+    for (int f = tid; f < (1 << LG); f += nt) sS[phys(pos_of<LG>(f))] = sh[f];
 }
 
 // out <- post . (M in) on tile t (16 columns x 16 slots) of the stage with stride 2^lgM.  TWM: 0 no twiddle, 1 the
@@ -111,12 +134,13 @@ __device__ __forceinline__ void stage_tile(const h2* in, h2* out, int t, int lgM
                                            const float2* __restrict__ stw, int lane)
 {
     const int c = lane & 15, g = lane >> 4;
-    int p[4];
+    const int p0 = tile_pos(16 * t + c, 4 * g, lgM), a0 = phys(p0);
+    int a[4];
     H8U x;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        p[j] = tile_pos(16 * t + c, 4 * g + j, lgM);
-        x.c[j] = in[p[j]];
+        a[j] = a0 ^ phys(j << lgM);              // the bits of j are clear in p0
+        x.c[j] = in[a[j]];
     }
     f4 yr, yi;
     blk16(A, x.v, yr, yi);
@@ -124,10 +148,10 @@ __device__ __forceinline__ void stage_tile(const h2* in, h2* out, int t, int lgM
     for (int j = 0; j < 4; ++j) {
         float2 v = make_float2(yr[j], yi[j]);
         if (TWM != 0) {
-            const float2 w = stage_twiddle(stw, p[j], lgT);
+            const float2 w = stage_twiddle(stw, p0 | (j << lgM), lgT);
             v = TWM == 2 ? cmulc(v, w) : cmul(v, w);
         }
-        out[p[j]] = pack(v.x, v.y);
+        out[a[j]] = pack(v.x, v.y);
     }
 }
 
@@ -137,10 +161,11 @@ __device__ __forceinline__ void stage_tile(const h2* in, h2* out, int t, int lgM
 __device__ __forceinline__ void outer_tile(const h2* G, const h2* X, int t, int lgM, f4& qr, f4& qi, int lane)
 {
     const int i = lane & 15, g = lane >> 4;
+    const int a0 = phys(tile_pos(16 * t + 4 * g, i, lgM));
     H8U a, b, bs;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const int p = tile_pos(16 * t + 4 * g + q, i, lgM);
+        const int p = a0 ^ phys(tile_pos(q, 0, lgM));      // column bits of q are clear in the tile's base
         a.c[q] = G[p];
         b.c[q] = X[p];
         bs.c[q] = h2{(_Float16)(-b.c[q][1]), b.c[q][0]};
@@ -203,11 +228,11 @@ __device__ __forceinline__ void load_row(h2* s, const typename IO::T* row, int N
             lo.c[q] = pack(v[q], 0.f);
             hi.c[q] = pack(v[4 + q], 0.f);
         }
-        *reinterpret_cast<uint4*>(&s[8 * i]) = lo.u;
-        *reinterpret_cast<uint4*>(&s[8 * i + 4]) = hi.u;
+        *reinterpret_cast<uint4*>(&s[phys(8 * i)]) = lo.u;
+        *reinterpret_cast<uint4*>(&s[phys(8 * i + 4)]) = hi.u;
         const uint4 z = make_uint4(0, 0, 0, 0);
-        *reinterpret_cast<uint4*>(&s[N + 8 * i]) = z;
-        *reinterpret_cast<uint4*>(&s[N + 8 * i + 4]) = z;
+        *reinterpret_cast<uint4*>(&s[phys(N + 8 * i)]) = z;
+        *reinterpret_cast<uint4*>(&s[phys(N + 8 * i + 4)]) = z;
     }
 }
 
@@ -218,8 +243,8 @@ __device__ __forceinline__ void store_row(const h2* s, typename IO::T* row, int 
     uint4* p = reinterpret_cast<uint4*>(row);
     for (int i = tid; i < N / 8; i += nt) {
         H8U lo, hi;
-        lo.u = *reinterpret_cast<const uint4*>(&s[8 * i]);
-        hi.u = *reinterpret_cast<const uint4*>(&s[8 * i + 4]);
+        lo.u = *reinterpret_cast<const uint4*>(&s[phys(8 * i)]);
+        hi.u = *reinterpret_cast<const uint4*>(&s[phys(8 * i + 4)]);
         float v[8];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -241,8 +266,9 @@ lb_fwd_kernel(const typename IO::T* __restrict__ u, const float2* __restrict__ s
               const float2* __restrict__ stw)
 {
     extern __shared__ uint4 smem_raw[];
-    h2* s = reinterpret_cast<h2*>(smem_raw);
-    constexpr int NW = lb_waves(LG), L = 1 << LG, N = L / 2, T = L / 256, LB = LG - 8;
+    constexpr int NW = lb_waves(LG), L = 1 << LG, N = L / 2, T = L / 256, LB = LG - 8, TPW = T / NW;
+    float2* sS = reinterpret_cast<float2*>(smem_raw);                 // the spectrum in position order
+    h2* s = reinterpret_cast<h2*>(sS + L);
     const int h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float2* af = Af + (size_t)h * 3 * NBLK;
     const float2* ai = Ai + (size_t)h * 3 * NBLK;
@@ -250,28 +276,36 @@ lb_fwd_kernel(const typename IO::T* __restrict__ u, const float2* __restrict__ s
     const Mats A2 = load_mats(af + 2 * NBLK, LB, false, lane);
     const Mats B0 = load_mats(ai, 4, false, lane), B1 = load_mats(ai + NBLK, 4, false, lane);
     const Mats B2 = load_mats(ai + 2 * NBLK, LB, false, lane);
-    const float2* sh = shat + (size_t)h * L;
+    stage_spectrum<LG>(sS, shat + (size_t)h * L, tid, NW * 64);
     const float yscale = exp2f((float)(2 * total_shift(LG) - LG));
     const int64_t b0 = (int64_t)blockIdx.x * rows_per_wg;
     const int64_t b1 = b0 + rows_per_wg < B ? b0 + rows_per_wg : B;
     for (int64_t b = b0; b < b1; ++b) {
         load_row<IO>(s, u + row_off(b, h, H, N), N, tid, NW * 64);
         __syncthreads();
-        for (int t = wave; t < T; t += NW) stage_tile<1>(s, s, t, LG - 4, LG - 4, A0, stw, lane);
+#pragma unroll
+        for (int tt = 0; tt < TPW; ++tt) stage_tile<1>(s, s, wave + tt * NW, LG - 4, LG - 4, A0, stw, lane);
         __syncthreads();
-        for (int t = wave; t < T; t += NW) stage_tile<1>(s, s, t, LG - 8, LG - 8, A1, stw, lane);
+#pragma unroll
+        for (int tt = 0; tt < TPW; ++tt) stage_tile<1>(s, s, wave + tt * NW, LG - 8, LG - 8, A1, stw, lane);
         __syncthreads();
         // last forward block -> product with the spectrum -> first inverse block, in registers
-        for (int t = wave; t < T; t += NW) {
-            const int pb = (16 * t + (lane & 15)) * 16 + 4 * (lane >> 4);
+#pragma unroll
+        for (int tt = 0; tt < TPW; ++tt) {
+            const int t = wave + tt * NW;
+            const int pb = (16 * t + (lane & 15)) * 16 + 4 * (lane >> 4), ab = phys(pb);
             H8U x;
-            x.u = *reinterpret_cast<const uint4*>(&s[pb]);
+            x.u = *reinterpret_cast<const uint4*>(&s[ab]);
             f4 yr, yi;
             blk16(A2, x.v, yr, yi);
+            const float4 s01 = *reinterpret_cast<const float4*>(&sS[ab]);
+            const float4 s23 = *reinterpret_cast<const float4*>(&sS[ab + 2]);
+            const float2 sv[4] = {make_float2(s01.x, s01.y), make_float2(s01.z, s01.w), make_float2(s23.x, s23.y),
+                                  make_float2(s23.z, s23.w)};
             H8U m;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const float2 r = cmul(make_float2(yr[j], yi[j]), sh[freq_of<LG>(pb + j)]);
+                const float2 r = cmul(make_float2(yr[j], yi[j]), sv[j]);
                 m.c[j] = pack(r.x, r.y);
             }
             blk16(B2, m.v, yr, yi);
@@ -281,12 +315,14 @@ lb_fwd_kernel(const typename IO::T* __restrict__ u, const float2* __restrict__ s
                 const float2 r = cmulc(make_float2(yr[j], yi[j]), stage_twiddle(stw, pb + j, LB));
                 o.c[j] = pack(r.x, r.y);
             }
-            *reinterpret_cast<uint4*>(&s[pb]) = o.u;
+            *reinterpret_cast<uint4*>(&s[ab]) = o.u;
         }
         __syncthreads();
-        for (int t = wave; t < T; t += NW) stage_tile<2>(s, s, t, LG - 8, LG - 4, B1, stw, lane);
+#pragma unroll
+        for (int tt = 0; tt < TPW; ++tt) stage_tile<2>(s, s, wave + tt * NW, LG - 8, LG - 4, B1, stw, lane);
         __syncthreads();
-        for (int t = wave; t < T; t += NW) stage_tile<0>(s, s, t, LG - 4, 0, B0, stw, lane);
+#pragma unroll
+        for (int tt = 0; tt < TPW; ++tt) stage_tile<0>(s, s, wave + tt * NW, LG - 4, 0, B0, stw, lane);
         __syncthreads();
         store_row<IO>(s, y + row_off(b, h, H, N), N, yscale, tid, NW * 64);
         __syncthreads();
@@ -296,20 +332,21 @@ lb_fwd_kernel(const typename IO::T* __restrict__ u, const float2* __restrict__ s
 // -------------------------------------------------------------------------------------------------------------------
 // Backward.  grid = (nsplit, H): workgroup (sp, h) owns rows b = sp, sp + nsplit, ... of head h, accumulates the
 // gradients of the head's six blocks and of its spectrum in registers over those rows and writes them as partial
-// results, which lb_reduce_kernel sums in a fixed order.  LDS: X0, X1, X2 (inputs of the forward blocks), U (the
-// transform), W2, W1, W0 (inputs of the inverse blocks), G (the gradient, in place).
+// results, which lb_reduce_kernel sums in a fixed order.  LDS: the spectrum, X0, X1, X2 (inputs of the forward
+// blocks), W2, W1, W0 (inputs of the inverse blocks), G (the gradient, in place).
 // -------------------------------------------------------------------------------------------------------------------
 template <int LG, class IO>
-__global__ void __launch_bounds__(lb_waves(LG) * 64)
+__global__ void __launch_bounds__(lbb_waves(LG) * 64) __attribute__((amdgpu_waves_per_eu(2)))
 lb_bwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restrict__ u,
               const float2* __restrict__ shat, const float2* __restrict__ Af, const float2* __restrict__ Ai,
               typename IO::T* __restrict__ du, float2* __restrict__ part_shat, float2* __restrict__ part_q, int64_t B,
               int64_t H, const float2* __restrict__ stw)
 {
     extern __shared__ uint4 smem_raw[];
-    constexpr int NW = lb_waves(LG), L = 1 << LG, N = L / 2, T = L / 256, LB = LG - 8, TPW = T / NW;
-    h2* bX0 = reinterpret_cast<h2*>(smem_raw);
-    h2 *bX1 = bX0 + L, *bX2 = bX1 + L, *bU = bX2 + L, *bW2 = bU + L, *bW1 = bW2 + L, *bW0 = bW1 + L, *bG = bW0 + L;
+    constexpr int NW = lbb_waves(LG), L = 1 << LG, N = L / 2, T = L / 256, LB = LG - 8, TPW = T / NW;
+    float2* sS = reinterpret_cast<float2*>(smem_raw);                 // the spectrum in position order
+    h2* bX0 = reinterpret_cast<h2*>(sS + L);
+    h2 *bX1 = bX0 + L, *bX2 = bX1 + L, *bW2 = bX2 + L, *bW1 = bW2 + L, *bW0 = bW1 + L, *bG = bW0 + L;
     const int sp = blockIdx.x, nsplit = gridDim.x, h = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float2* af = Af + (size_t)h * 3 * NBLK;
@@ -321,7 +358,7 @@ lb_bwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __res
     const Mats A2H = load_mats(af + 2 * NBLK, LB, true, lane);
     const Mats B0H = load_mats(ai, 4, true, lane), B1H = load_mats(ai + NBLK, 4, true, lane);
     const Mats B2H = load_mats(ai + 2 * NBLK, LB, true, lane);
-    const float2* sh = shat + (size_t)h * L;
+    stage_spectrum<LG>(sS, shat + (size_t)h * L, tid, NW * 64);
     const float yscale = exp2f((float)(2 * total_shift(LG) - LG));
 
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -333,29 +370,37 @@ lb_bwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __res
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc_s[i][j] = make_float2(0.f, 0.f);
 
+    // tile loops stay rolled here (one iteration up to 2048 points; at 4096 points unrolling them costs more in
+    // spilled registers than the hoisted address arithmetic saves)
     for (int64_t b = sp; b < B; b += nsplit) {
         load_row<IO>(bX0, u + row_off(b, h, H, N), N, tid, NW * 64);
         load_row<IO>(bG, dy + row_off(b, h, H, N), N, tid, NW * 64);
         __syncthreads();
-        for (int t = wave; t < T; t += NW) stage_tile<1>(bX0, bX1, t, LG - 4, LG - 4, A0, stw, lane);
+#pragma unroll 1
+        for (int tt = 0; tt < TPW; ++tt) stage_tile<1>(bX0, bX1, wave + tt * NW, LG - 4, LG - 4, A0, stw, lane);
         __syncthreads();
-        for (int t = wave; t < T; t += NW) stage_tile<1>(bX1, bX2, t, LG - 8, LG - 8, A1, stw, lane);
+#pragma unroll 1
+        for (int tt = 0; tt < TPW; ++tt) stage_tile<1>(bX1, bX2, wave + tt * NW, LG - 8, LG - 8, A1, stw, lane);
         __syncthreads();
-        for (int t = wave; t < T; t += NW) {
-            const int pb = (16 * t + (lane & 15)) * 16 + 4 * (lane >> 4);
+#pragma unroll 1
+        for (int tt = 0; tt < TPW; ++tt) {
+            const int t = wave + tt * NW;
+            const int pb = (16 * t + (lane & 15)) * 16 + 4 * (lane >> 4), ab = phys(pb);
             H8U x;
-            x.u = *reinterpret_cast<const uint4*>(&bX2[pb]);
+            x.u = *reinterpret_cast<const uint4*>(&bX2[ab]);
             f4 yr, yi;
             blk16(A2, x.v, yr, yi);
-            H8U uu, m;
+            const float4 s01 = *reinterpret_cast<const float4*>(&sS[ab]);
+            const float4 s23 = *reinterpret_cast<const float4*>(&sS[ab + 2]);
+            const float2 sv[4] = {make_float2(s01.x, s01.y), make_float2(s01.z, s01.w), make_float2(s23.x, s23.y),
+                                  make_float2(s23.z, s23.w)};
+            H8U m;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                uu.c[j] = pack(yr[j], yi[j]);
-                const float2 r = cmul(make_float2(yr[j], yi[j]), sh[freq_of<LG>(pb + j)]);
+                const float2 r = cmul(make_float2(yr[j], yi[j]), sv[j]);
                 m.c[j] = pack(r.x, r.y);
             }
-            *reinterpret_cast<uint4*>(&bU[pb]) = uu.u;
-            *reinterpret_cast<uint4*>(&bW2[pb]) = m.u;
+            *reinterpret_cast<uint4*>(&bW2[ab]) = m.u;
             blk16(B2, m.v, yr, yi);
             H8U o;
 #pragma unroll
@@ -363,19 +408,24 @@ lb_bwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __res
                 const float2 r = cmulc(make_float2(yr[j], yi[j]), stage_twiddle(stw, pb + j, LB));
                 o.c[j] = pack(r.x, r.y);
             }
-            *reinterpret_cast<uint4*>(&bW1[pb]) = o.u;
+            *reinterpret_cast<uint4*>(&bW1[ab]) = o.u;
         }
         __syncthreads();
-        for (int t = wave; t < T; t += NW) stage_tile<2>(bW1, bW0, t, LG - 8, LG - 4, B1, stw, lane);
+#pragma unroll 1
+        for (int tt = 0; tt < TPW; ++tt) stage_tile<2>(bW1, bW0, wave + tt * NW, LG - 8, LG - 4, B1, stw, lane);
         __syncthreads();
 
         // back through the inverse chain: G holds the gradient at the output of B_0 (dy, zero above N)
-        for (int t = wave; t < T; t += NW) {
+#pragma unroll 1
+        for (int tt = 0; tt < TPW; ++tt) {
+            const int t = wave + tt * NW;
             outer_tile(bG, bW0, t, LG - 4, qir[0], qii[0], lane);
             stage_tile<1>(bG, bG, t, LG - 4, LG - 4, B0H, stw, lane);
         }
         __syncthreads();
-        for (int t = wave; t < T; t += NW) {
+#pragma unroll 1
+        for (int tt = 0; tt < TPW; ++tt) {
+            const int t = wave + tt * NW;
             outer_tile(bG, bW1, t, LG - 8, qir[1], qii[1], lane);
             stage_tile<1>(bG, bG, t, LG - 8, LG - 8, B1H, stw, lane);
         }
@@ -384,35 +434,44 @@ lb_bwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __res
 #pragma unroll
         for (int tt = 0; tt < TPW; ++tt) {
             const int t = wave + tt * NW;
-            const int pb = (16 * t + (lane & 15)) * 16 + 4 * (lane >> 4);
+            const int pb = (16 * t + (lane & 15)) * 16 + 4 * (lane >> 4), ab = phys(pb);
             outer_tile(bG, bW2, t, 0, qir[2], qii[2], lane);
-            H8U x, uu;
-            x.u = *reinterpret_cast<const uint4*>(&bG[pb]);
-            uu.u = *reinterpret_cast<const uint4*>(&bU[pb]);
-            f4 yr, yi;
+            H8U x, x2;
+            x.u = *reinterpret_cast<const uint4*>(&bG[ab]);
+            x2.u = *reinterpret_cast<const uint4*>(&bX2[ab]);
+            f4 yr, yi, ur, ui;
             blk16(B2H, x.v, yr, yi);
+            blk16(A2, x2.v, ur, ui);                 // the transform of this tile again, instead of a buffer for it
+            const float4 s01 = *reinterpret_cast<const float4*>(&sS[ab]);
+            const float4 s23 = *reinterpret_cast<const float4*>(&sS[ab + 2]);
+            const float2 sv[4] = {make_float2(s01.x, s01.y), make_float2(s01.z, s01.w), make_float2(s23.x, s23.y),
+                                  make_float2(s23.z, s23.w)};
             H8U o;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float2 gv = make_float2(yr[j], yi[j]);
-                const float2 d = cmulc(gv, make_float2((float)uu.c[j][0], (float)uu.c[j][1]));
+                const float2 d = cmulc(gv, make_float2(ur[j], ui[j]));
                 acc_s[tt][j].x += d.x;
                 acc_s[tt][j].y += d.y;
-                const float2 r = cmulc(gv, sh[freq_of<LG>(pb + j)]);
+                const float2 r = cmulc(gv, sv[j]);
                 o.c[j] = pack(r.x, r.y);
             }
-            *reinterpret_cast<uint4*>(&bG[pb]) = o.u;
+            *reinterpret_cast<uint4*>(&bG[ab]) = o.u;
             // the tile just written is read back with the columns as the K dimension: same wave, LDS keeps the order
             outer_tile(bG, bX2, t, 0, qfr[2], qfi[2], lane);
             stage_tile<2>(bG, bG, t, 0, LG - 8, A2H, stw, lane);
         }
         __syncthreads();
-        for (int t = wave; t < T; t += NW) {
+#pragma unroll 1
+        for (int tt = 0; tt < TPW; ++tt) {
+            const int t = wave + tt * NW;
             outer_tile(bG, bX1, t, LG - 8, qfr[1], qfi[1], lane);
             stage_tile<2>(bG, bG, t, LG - 8, LG - 4, A1H, stw, lane);
         }
         __syncthreads();
-        for (int t = wave; t < T; t += NW) {
+#pragma unroll 1
+        for (int tt = 0; tt < TPW; ++tt) {
+            const int t = wave + tt * NW;
             outer_tile(bG, bX0, t, LG - 4, qfr[0], qfi[0], lane);
             if (du) stage_tile<0>(bG, bG, t, LG - 4, 0, A0H, stw, lane);
         }
@@ -431,24 +490,31 @@ lb_bwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __res
         for (int j = 0; j < 4; ++j)
             ps[freq_of<LG>(pb + j)] = make_float2(acc_s[tt][j].x * yscale, acc_s[tt][j].y * yscale);
     }
-    // gradients of the blocks: the waves' 16 x 16 sums through LDS, added in wave order
-    float2* red = reinterpret_cast<float2*>(smem_raw);          // [NW][6][256]
+    // gradients of the blocks: the waves add their 16 x 16 sums into one LDS copy, one wave after the other
+    float2* red = reinterpret_cast<float2*>(smem_raw);          // [6][256]
+    for (int w = 0; w < NW; ++w) {
+        if (wave == w) {
 #pragma unroll
-    for (int s = 0; s < 3; ++s)
+            for (int s = 0; s < 3; ++s)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int e = (4 * (lane >> 4) + jj) * 16 + (lane & 15);       // entry [i][j]
-            red[(wave * 6 + s) * NBLK + e] = make_float2(qfr[s][jj], qfi[s][jj]);
-            red[(wave * 6 + 3 + s) * NBLK + e] = make_float2(qir[s][jj], qii[s][jj]);
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int e = (4 * (lane >> 4) + jj) * 16 + (lane & 15);       // entry [i][j]
+                    float2 f = make_float2(qfr[s][jj], qfi[s][jj]), i2 = make_float2(qir[s][jj], qii[s][jj]);
+                    if (w > 0) {
+                        f = cadd(f, red[s * NBLK + e]);
+                        i2 = cadd(i2, red[(3 + s) * NBLK + e]);
+                    }
+                    red[s * NBLK + e] = f;
+                    red[(3 + s) * NBLK + e] = i2;
+                }
         }
-    __syncthreads();
+        __syncthreads();
+    }
     float2* pq = part_q + ((size_t)sp * H + h) * 6 * NBLK;
     for (int e = tid; e < 6 * NBLK; e += NW * 64) {
-        float2 a = make_float2(0.f, 0.f);
-        for (int w = 0; w < NW; ++w) a = cadd(a, red[w * 6 * NBLK + e]);
         const int s = (e / NBLK) % 3;
         const float sc = yscale / (float)(1 << stage_shift(s == 2 ? LB : 4));
-        pq[e] = make_float2(a.x * sc, a.y * sc);
+        pq[e] = make_float2(red[e].x * sc, red[e].y * sc);
     }
 }
 
@@ -541,11 +607,11 @@ hipError_t fwd_go(const void* u, const float* shat, const float* Af, const float
 {
     using T = typename IO::T;
     constexpr int NW = lb_waves(LG);
-    const size_t lds = (size_t)(1 << LG) * sizeof(h2);
+    const size_t lds = (size_t)(1 << LG) * (sizeof(h2) + sizeof(float2));
     // enough workgroups to fill the device several times over, each keeping its head's blocks for all its rows
     const int64_t want = (int64_t)compute_units() * 16;
     int64_t rows = (B * H + want - 1) / want;
-    if (rows < 1) rows = 1;
+    if (rows < 4) rows = 4;            // the spectrum is staged once per workgroup: not for fewer rows than this
     if (rows > B) rows = B;
     const unsigned groups = (unsigned)((B + rows - 1) / rows);
     hipError_t e = set_lds(lb_fwd_kernel<LG, IO>, lds);
@@ -560,9 +626,9 @@ hipError_t bwd_go(const void* dy, const void* u, const float* shat, const float*
                   float2* part_shat, float2* part_q, int64_t B, int64_t H, int nsplit, const Tables& tb, hipStream_t st)
 {
     using T = typename IO::T;
-    constexpr int NW = lb_waves(LG);
-    size_t lds = (size_t)8 * (1 << LG) * sizeof(h2);
-    const size_t red = (size_t)NW * 6 * NBLK * sizeof(float2);
+    constexpr int NW = lbb_waves(LG);
+    size_t lds = (size_t)(1 << LG) * (7 * sizeof(h2) + sizeof(float2));
+    const size_t red = (size_t)6 * NBLK * sizeof(float2);
     if (lds < red) lds = red;
     hipError_t e = set_lds(lb_bwd_kernel<LG, IO>, lds);
     if (e != hipSuccess) return e;

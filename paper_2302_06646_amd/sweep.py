@@ -1,4 +1,6 @@
-"""Length sweep and block-size-table shape on one MI355X: `python -m paper_2302_06646_amd.sweep [--quick]`.
+"""Length sweep and block-size-table shape on one MI355X: `python -m paper_2302_06646_amd.sweep [--quick]`;
+`--learned` times the learned Butterfly extension against the fixed path instead (the shape of the paper's table of
+learnable block sizes: block size 16 against the fixed Butterfly, as a speed ratio).
 
 Two measurements that mirror the paper's efficiency experiments (Section 5.4 runtime figure: one layer, batch 32,
 128 heads, N = 1K ... 128K, against the FFT-library convolution; Table of block sizes: N = 4096, B = 128, H = 32),
@@ -108,15 +110,85 @@ def table_shape(B, H, N, steps):
             "fwd_mfma_pct_of_peak": 100 * mf / t["fwd_us"] / 1e6 / 2500.0}
 
 
+def dft_blocks(H, N):
+    """[H, 3, 16, 16, 2] float32 blocks that make the learned path the plain FFT convolution, and their conjugates."""
+    import numpy as np
+    A = np.zeros((H, 3, 16, 16, 2), dtype=np.float32)
+    for s, r in enumerate((16, 16, 2 * N // 256)):
+        F = np.exp(-2j * np.pi * np.outer(np.arange(r), np.arange(r)) / r)
+        A[:, s, :r, :r, 0], A[:, s, :r, :r, 1] = F.real, F.imag
+    Af = torch.from_numpy(A).cuda()
+    Ai = Af.clone()
+    Ai[..., 1] *= -1
+    return Af, Ai
+
+
+def learned_row(B, H, N, steps):
+    """Fixed path against the learned Butterfly extension, bf16 rows, forward and backward (all gradients)."""
+    io, td = lc.BF16, torch.bfloat16
+    nsets = 4
+    g = torch.Generator(device="cuda").manual_seed(N)
+    mk = lambda: torch.randn((B, H, N), generator=g, device="cuda", dtype=torch.float32).to(td)
+    us, dys = [mk() for _ in range(nsets)], [mk() for _ in range(nsets)]
+    y, du = torch.empty_like(us[0]), torch.empty_like(us[0])
+    k = torch.randn(H, N, device="cuda") / N ** 0.5
+    D = torch.randn(H, device="cuda")
+    dk, dD = torch.empty_like(k), torch.empty_like(D)
+    Af, Ai = dft_blocks(H, N)
+    dAf, dAi = torch.empty_like(Af), torch.empty_like(Ai)
+    shat = torch.empty(H, 2 * N, 2, device="cuda")
+    dshat = torch.empty_like(shat)
+    wsl = torch.empty(lc.longconv_lbfly_workspace_bytes(B, H, N, io), dtype=torch.uint8, device="cuda")
+    ws = lc.new_workspace(B, H, N, io, True)
+    fns = {
+        "fixed_fwd_us": lambda i: lc.longconv_fwd(us[i % nsets], k, D, y, ws),
+        "fixed_bwd_us": lambda i: lc.longconv_bwd(dys[i % nsets], us[i % nsets], k, D, du, dk, dD, ws),
+        "learned_spectrum_us": lambda i: lc.longconv_lbfly_spectrum(k, D, shat),
+        "learned_fwd_us": lambda i: lc.longconv_lbfly_fwd(us[i % nsets], shat, Af, Ai, y),
+        "learned_bwd_us": lambda i: lc.longconv_lbfly_bwd(dys[i % nsets], us[i % nsets], shat, Af, Ai, du, dshat, dAf,
+                                                           dAi, wsl),
+        "learned_spectrum_bwd_us": lambda i: lc.longconv_lbfly_spectrum_bwd(dshat, dk, dD),
+    }
+    r = {"B": B, "H": H, "N": N, "dtype": "bf16"}
+    for name, fn in fns.items():
+        for i in range(3):
+            fn(i)
+        r[name] = _timed(steps, fn)
+    fixed = r["fixed_fwd_us"] + r["fixed_bwd_us"]
+    learned = sum(r[n] for n in fns if n.startswith("learned"))
+    r["speed_ratio_learned_over_fixed"] = fixed / learned
+    # bytes of the rows the step has to move: u and y forward, dy, u and du backward
+    r["learned_step_GBps"] = 5 * B * H * N * 2 / learned / 1e3
+    # matrix-core work of the learned step: two instructions of 16384 flop per 256-point tile and block product;
+    # 6 block products forward, 12 + 1 (the transform again) backward, 6 block gradients
+    r["learned_step_mfma_TFLOPs"] = B * H * (2 * N / 256) * (6 + 13 + 6) * 2 * 16384 / learned / 1e6
+    return r
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--quick", action="store_true", help="fewer steps and lengths")
+    ap.add_argument("--learned", action="store_true", help="learned Butterfly extension against the fixed path")
     a = ap.parse_args()
     if not torch.cuda.is_available():
         print("sweep: no GPU visible", file=sys.stderr)
         sys.exit(1)
     lc.longconv_init()
     steps = 10 if a.quick else 30
+    if a.learned:
+        shapes = [(16, 768, 1024)] if a.quick else [(16, 768, 1024), (64, 256, 1024), (64, 1024, 256), (64, 1024, 2048)]
+        rows = [learned_row(B, H, N, steps) for (B, H, N) in shapes]
+        print("| B, H, N | fixed fwd / bwd (us) | learned spectrum / fwd / bwd / spectrum bwd (us) | speed ratio | "
+              "learned step GB/s | MFMA TFLOP/s |")
+        print("|---|---|---|---|---|---|")
+        for r in rows:
+            print(f"| {r['B']}, {r['H']}, {r['N']} | {r['fixed_fwd_us']:.1f} / {r['fixed_bwd_us']:.1f} | "
+                  f"{r['learned_spectrum_us']:.1f} / {r['learned_fwd_us']:.1f} / {r['learned_bwd_us']:.1f} / "
+                  f"{r['learned_spectrum_bwd_us']:.1f} | {r['speed_ratio_learned_over_fixed']:.2f}x | "
+                  f"{r['learned_step_GBps']:.0f} | {r['learned_step_mfma_TFLOPs']:.1f} |")
+        for r in rows:
+            print(json.dumps(r))
+        return
     lengths = [1024, 16384, 131072] if a.quick else [1024, 2048, 4096, 8192, 16384, 32768, 65536, 131072]
     rows = [sweep_row(32, 128, N, steps) for N in lengths]
     print("| N | plan | fwd, cached spectrum (us) | fwd + spectrum (us) | torch.fft conv (us) | speed-up | GB/s | % of 8 TB/s |")
