@@ -189,7 +189,8 @@ int longconv2d_bwd(const void* dy, const void* u, const float* k, const float* D
  *   Af, Ai, dAf, dAi: [H, 3, 16, 16, 2] float32 (row, column, re / im); the last stage reads the leading
  *       r_last x r_last corner only and its gradient is zero outside it.
  *   shat, dshat: [H, 2N, 2] float32.  u, y, dy, du: [B,H,N] fp16 or bf16 (LONGCONV_ERR_DTYPE otherwise), values
- *       within fp16's range (rows are not rescaled here).  N = 256, 512, 1024 or 2048; B, H as above.
+ *       within fp16's range (rows are not rescaled here).  N = 256, 512, 1024 or 2048 (the two spectrum calls: up to
+ *       4096); B, H as above.
  *   A complex parameter's gradient is dL/dRe + i dL/dIm.  du, dshat, dAf, dAi may each be NULL.
  * Arithmetic: fp16 matrix-core operands (the blocks are rounded to fp16), fp32 accumulation, fp16 data between
  * stages; every gradient is summed in a fixed order (bitwise repeatable).  longconv_lbfly_spectrum makes Shat from
@@ -205,6 +206,15 @@ int longconv_lbfly_bwd(const void* dy, const void* u, const float* shat, const f
                        void* du, float* dshat, float* dAf, float* dAi,
                        int64_t B, int64_t H, int64_t N, int io,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Block-size study (Section 3.2, the table of block sizes; Appendix C: on a b x b matrix unit a block of size
+ * r < b costs what a b x b block costs): y = (u * k)[:N] + D u as longconv_fwd computes it, but with every stage of
+ * the transform a dense DFT block of r = 2^log2r points (log2r = 1 .. 4), each run as a 16 x 16 matrix product, so
+ * that ceil(log2(2N) / log2r) stages are executed each way.  A measurement kernel, not a fast path: fp16 rows only
+ * (LONGCONV_ERR_DTYPE otherwise), N = 1024 or 4096, shat [H, 2N, 2] float32 from longconv_lbfly_spectrum (which
+ * serves lengths up to 4096 for this purpose).  Same accuracy bound as longconv_fwd.  No workspace. */
+int longconv_blocksize_fwd(const void* u, const float* shat, void* y,
+                           int64_t B, int64_t H, int64_t N, int io, int log2r, void* stream);
 
 /* Kernel regularisers in front of the convolution (Algorithm 1 lines 1-3; Section 3.1,
  * "Regularizing the Kernel"), for the raw parameter K [H,N] f32:

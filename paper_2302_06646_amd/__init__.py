@@ -12,7 +12,7 @@ Functions mirror the C ABI of ``include/longconv.h``:
     longconv_set_option, longconv_fwd_noalloc, longconv_kreg_fwd, longconv_kreg_bwd,
     longconv_fwd_gated, longconv_bwd_gated, longconv2d_workspace_bytes, longconv2d_fwd, longconv2d_bwd,
     longconv_lbfly_workspace_bytes, longconv_lbfly_spectrum, longconv_lbfly_spectrum_bwd, longconv_lbfly_fwd,
-    longconv_lbfly_bwd
+    longconv_lbfly_bwd, longconv_blocksize_fwd
 """
 from __future__ import annotations
 
@@ -36,7 +36,7 @@ EXPORTS = ("longconv_init", "longconv_kspec_bytes", "longconv_workspace_bytes",
            "longconv_fwd_gated", "longconv_bwd_gated",
            "longconv2d_workspace_bytes", "longconv2d_fwd", "longconv2d_bwd",
            "longconv_lbfly_workspace_bytes", "longconv_lbfly_spectrum", "longconv_lbfly_spectrum_bwd",
-           "longconv_lbfly_fwd", "longconv_lbfly_bwd")
+           "longconv_lbfly_fwd", "longconv_lbfly_bwd", "longconv_blocksize_fwd")
 
 
 class LongconvError(RuntimeError):
@@ -94,6 +94,8 @@ def lib():
         L.longconv_lbfly_fwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp]
         L.longconv_lbfly_bwd.restype = ci
         L.longconv_lbfly_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, sz, vp]
+        L.longconv_blocksize_fwd.restype = ci
+        L.longconv_blocksize_fwd.argtypes = [vp, vp, vp, i64, i64, i64, ci, ci, vp]
         L.longconv_set_option.restype = ci
         L.longconv_set_option.argtypes = [ctypes.c_char_p, ci]
         _lib = L
@@ -308,6 +310,16 @@ def longconv_lbfly_bwd(dy, u, shat, Af, Ai, du, dshat, dAf, dAi, workspace, stre
     _check(lib().longconv_lbfly_bwd(_ptr(dy), _ptr(u), _ptr(shat), _ptr(Af), _ptr(Ai), _ptr(du), _ptr(dshat),
                                     _ptr(dAf), _ptr(dAi), B, H, N, io, _ptr(workspace), workspace.numel(),
                                     _stream(stream)), "longconv_lbfly_bwd")
+
+
+def longconv_blocksize_fwd(u, shat, y, log2r: int, stream=None) -> None:
+    """y <- the convolution computed with DFT blocks of 2**log2r points per stage (block-size study)."""
+    B, H, N = u.shape
+    io = dtype_code(u)
+    _need(u, "u", _TORCH_DTYPE[io], (B, H, N)); _need(y, "y", _TORCH_DTYPE[io], (B, H, N))
+    _need(shat, "shat", torch.float32, (H, 2 * N, 2))
+    _check(lib().longconv_blocksize_fwd(_ptr(u), _ptr(shat), _ptr(y), B, H, N, io, int(log2r), _stream(stream)),
+           "longconv_blocksize_fwd")
 
 
 STATIC_SCRATCH_BYTES = 64 << 20

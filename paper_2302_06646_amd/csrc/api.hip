@@ -3,8 +3,8 @@
 // (8192..32768 points, and the inner transforms of longer ones), multipass.hip (outer passes), engine_valu.hip
 // (fp32 I/O), engine_mfma.hip (first-generation in-place kernel, kept as a cross-check behind a switch and
 // for 256-point inner transforms), kreg.hip (kernel regularisers), gate.hip (the gate's streaming pass) and
-// conv2d.hip (row padding of the 2-D convolution), lbfly.hip (learned Butterfly extension); nothing here computes
-// on the host.
+// conv2d.hip (row padding of the 2-D convolution), lbfly.hip (learned Butterfly extension), bsize.hip (block-size study); nothing here
+// computes on the host.
 #include <atomic>
 #include <cstdio>
 #include <cstdlib>
@@ -666,9 +666,16 @@ size_t longconv_lbfly_workspace_bytes(int64_t B, int64_t H, int64_t N, int io)
     return up256(lbfly_partial_bytes(B, H, N));
 }
 
+// the spectrum helpers also serve the block-size study: up to N = 4096
+static int check_shape_spectrum(int64_t H, int64_t N)
+{
+    if (H < 1 || H > 65535 || !pow2(N) || N < 256 || N > 4096) return LONGCONV_ERR_SHAPE;
+    return LONGCONV_OK;
+}
+
 int longconv_lbfly_spectrum(const float* k, const float* D, float* shat, int64_t H, int64_t N, void* stream)
 {
-    int s = check_shape_lb(1, H, N, LONGCONV_F16);
+    int s = check_shape_spectrum(H, N);
     if (s != LONGCONV_OK) return s;
     if (!k || !D || !shat) return LONGCONV_ERR_NULL;
     if (misaligned(k) || misaligned(shat)) return LONGCONV_ERR_ALIGN;
@@ -681,7 +688,7 @@ int longconv_lbfly_spectrum(const float* k, const float* D, float* shat, int64_t
 
 int longconv_lbfly_spectrum_bwd(const float* dshat, float* dk, float* dD, int64_t H, int64_t N, void* stream)
 {
-    int s = check_shape_lb(1, H, N, LONGCONV_F16);
+    int s = check_shape_spectrum(H, N);
     if (s != LONGCONV_OK) return s;
     if (!dshat) return LONGCONV_ERR_NULL;
     if (misaligned(dshat) || misaligned(dk)) return LONGCONV_ERR_ALIGN;
@@ -728,6 +735,23 @@ int longconv_lbfly_bwd(const void* dy, const void* u, const float* shat, const f
                    hipSuccess
                ? LONGCONV_OK
                : LONGCONV_ERR_HIP;
+}
+
+// ---- block-size study ------------------------------------------------------------------------------------------------
+
+int longconv_blocksize_fwd(const void* u, const float* shat, void* y, int64_t B, int64_t H, int64_t N, int io, int log2r,
+                           void* stream)
+{
+    if (io != LONGCONV_F16) return LONGCONV_ERR_DTYPE;
+    if (B < 1 || B > (int64_t(1) << 24) || H < 1 || H > 65535 || (N != 1024 && N != 4096) || log2r < 1 || log2r > 4)
+        return LONGCONV_ERR_SHAPE;
+    if (!u || !shat || !y) return LONGCONV_ERR_NULL;
+    if (misaligned(u) || misaligned(shat) || misaligned(y)) return LONGCONV_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    Tables tb;
+    if (get_tables(&tb, st, false) != hipSuccess) return LONGCONV_ERR_HIP;
+    return note(blocksize_fwd(u, shat, y, B, H, N, log2r, tb, st), "blocksize fwd") == hipSuccess ? LONGCONV_OK
+                                                                                                   : LONGCONV_ERR_HIP;
 }
 
 static int kreg_check(const float* k, const void* a, const void* b, int64_t H, int64_t N, int p, float lambda)

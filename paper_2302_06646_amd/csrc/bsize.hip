@@ -1,0 +1,261 @@
+// Block-size study (Section 3.2 "Butterfly Decomposition", the table of block sizes, and Appendix C's remark that on a
+// b x b matrix unit a block of size r < b costs what a b x b block costs, so that the executed flops go as
+// N b log N / log r and raising r up to b lowers them): the FFT convolution of Eq. 2 with every stage a dense DFT
+// block of size r = 2, 4, 8 or 16, all of them run on the 16-wide matrix unit (a block smaller than 16 as the
+// matrix I (x) F_r (x) I of size 16).  A measurement kernel: one real row per complex sequence, every stage a trip
+// through LDS, so that the only thing that changes with r is the number of stages, ceil(log2(2N) / log2 r) each way.
+//
+//   L = 2N = 2^LG, digits of BITS bits from the top (the last digit takes what is left), decimation in frequency:
+//   stage s applies F_r along digit s, then the twiddle exp(-2 pi i k_s (p mod M_s) / (r_s M_s)) (Appendix C.1);
+//   frequency k_0 + r_0 k_1 + r_0 r_1 k_2 + ... ends at position (k_0, k_1, ...), where the spectrum (natural order in
+//   memory) is staged in LDS as fp16; the inverse is the mirror image.  y = Re(result)[:N].
+#include "engines.hpp"
+
+namespace lc {
+namespace {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+
+struct Mats {
+    h8 re, im;
+};
+union H8U {
+    h8 v;
+    h2 c[4];
+    uint4 u;
+};
+
+template <int LG, int BITS>
+struct BS {
+    static constexpr int S = (LG + BITS - 1) / BITS;
+    static __host__ __device__ constexpr int bits(int s) { return s < S - 1 ? BITS : LG - BITS * (S - 1); }
+    static __host__ __device__ constexpr int lgM(int s) { return s < S - 1 ? LG - BITS * (s + 1) : 0; }
+    // the 16 slots of a matrix tile are the four position bits from win(s) up; the digit sits off(s) bits into them
+    static __host__ __device__ constexpr int win(int s) { return lgM(s) < LG - 4 ? lgM(s) : LG - 4; }
+    static __host__ __device__ constexpr int off(int s) { return lgM(s) - win(s); }
+    // power of two taken out at stage s: the data keeps unit magnitude (a DFT block of 2^b points grows it by 2^(b/2))
+    static __host__ __device__ constexpr int cum(int s) { return s < S ? BITS * s : LG; }          // bits before stage s
+    static __host__ __device__ constexpr int shift(int s) { return (cum(s) + bits(s)) / 2 - cum(s) / 2; }
+};
+
+// A operands of 2^-sh * (I (x) F_r (x) I): the digit is bits [o, o + b) of the slot index
+__device__ Mats dft_mats(int o, int b, int sh, bool inverse, const float2* __restrict__ tw, int lane)
+{
+    const int r = 1 << b, m = lane & 15, g = lane >> 4, keep = ~((r - 1) << o) & 15;
+    const float sc = 1.0f / (float)(1 << sh);
+    Mats A;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int sig = 4 * g + q;
+        float2 w = make_float2(0.f, 0.f);
+        if (((m ^ sig) & keep) == 0) {
+            const int jk = (((m >> o) & (r - 1)) * ((sig >> o) & (r - 1))) & (r - 1);
+            w = tw_full(tw, (uint32_t)jk << (TW_LOG2 - b));
+            if (inverse) w.y = -w.y;
+        }
+        A.re[2 * q] = (_Float16)(w.x * sc);
+        A.re[2 * q + 1] = (_Float16)(-w.y * sc);
+        A.im[2 * q] = (_Float16)(w.y * sc);
+        A.im[2 * q + 1] = (_Float16)(w.x * sc);
+    }
+    return A;
+}
+
+__device__ __forceinline__ h2 pack(float re, float im)
+{
+    const f2 v = {re, im};
+    return __builtin_convertvector(v, h2);
+}
+
+__device__ __forceinline__ int tile_pos(int gamma, int sigma, int w)
+{
+    return ((gamma >> w) << (w + 4)) | (gamma & ((1 << w) - 1)) | (sigma << w);
+}
+
+// LDS index swizzle (bank bits 2..5 against position bits 4..10; linear over XOR, bits 0-1 kept)
+__host__ __device__ constexpr int phys(int p) { return p ^ ((((p >> 4) ^ (p >> 7)) & 15) << 2); }
+
+// twiddle of stage (lgM, b) at position p: exp(-2 pi i k (p mod M) / (r M)), k the digit's value at p
+__device__ __forceinline__ float2 twiddle(const float2* __restrict__ tw, int p, int lgM, int b)
+{
+    const int k = (p >> lgM) & ((1 << b) - 1), suf = p & ((1 << lgM) - 1);
+    return tw_full(tw, (uint32_t)(k * suf) << (TW_LOG2 - lgM - b));
+}
+
+// one stage over tile t: out = post . (M in), in place.  POST: 0 nothing, 1 twiddle of stage (tM, tb), 2 its
+// conjugate, 3 the spectrum value of the position
+template <int POST>
+__device__ __forceinline__ void stage_tile(h2* s, const h2* sS, int t, int w, const Mats& A, int tM, int tb,
+                                           const float2* __restrict__ tw, int lane)
+{
+    const int c = lane & 15, g = lane >> 4;
+    const int p0 = tile_pos(16 * t + c, 4 * g, w), a0 = phys(p0);
+    int a[4];
+    H8U x;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        a[j] = a0 ^ phys(j << w);
+        x.c[j] = s[a[j]];
+    }
+    const f4 z = {0.f, 0.f, 0.f, 0.f};
+    const f4 yr = __builtin_amdgcn_mfma_f32_16x16x32_f16(A.re, x.v, z, 0, 0, 0);
+    const f4 yi = __builtin_amdgcn_mfma_f32_16x16x32_f16(A.im, x.v, z, 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float2 v = make_float2(yr[j], yi[j]);
+        if (POST == 1) v = cmul(v, twiddle(tw, p0 | (j << w), tM, tb));
+        if (POST == 2) v = cmulc(v, twiddle(tw, p0 | (j << w), tM, tb));
+        if (POST == 3) {
+            const h2 k = sS[a[j]];
+            v = cmul(v, make_float2((float)k[0], (float)k[1]));
+        }
+        s[a[j]] = pack(v.x, v.y);
+    }
+}
+
+template <int LG> __host__ __device__ constexpr int bs_waves() { return LG >= 13 ? 8 : 4; }
+
+// grid = (row groups, H).  LDS: the head's spectrum in position order (fp16 complex), one row (fp16 complex).
+template <int LG, int BITS>
+__global__ void __launch_bounds__(bs_waves<LG>() * 64)
+bs_fwd_kernel(const __half* __restrict__ u, const float2* __restrict__ shat, __half* __restrict__ y, int64_t B,
+              int64_t H, int rows_per_wg, const float2* __restrict__ tw)
+{
+    using C = BS<LG, BITS>;
+    extern __shared__ uint4 smem_raw[];
+    constexpr int NW = bs_waves<LG>(), L = 1 << LG, N = L / 2, T = L / 256, S = C::S;
+    h2* sS = reinterpret_cast<h2*>(smem_raw);
+    h2* s = sS + L;
+    const int h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // distinct matrices: by the digit's offset in the slot window (stages near the top) and by the last digit's width
+    Mats F[5], I[5];
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+        F[o] = dft_mats(o, BITS, 0, false, tw, lane);
+        I[o] = dft_mats(o, BITS, 0, true, tw, lane);
+    }
+    F[4] = dft_mats(0, C::bits(S - 1), 0, false, tw, lane);
+    I[4] = dft_mats(0, C::bits(S - 1), 0, true, tw, lane);
+
+    const float2* sh = shat + (size_t)h * L;
+    for (int f = tid; f < L; f += NW * 64) {
+        int p = 0, rest = f;
+#pragma unroll
+        for (int st = 0; st < S; ++st) {
+            p |= (rest & ((1 << C::bits(st)) - 1)) << C::lgM(st);
+            rest >>= C::bits(st);
+        }
+        const float2 v = sh[f];
+        sS[phys(p)] = pack(v.x, v.y);
+    }
+    // the stages' powers of two are applied to the result as one factor (the matrices themselves are unscaled DFT
+    // blocks times 2^-shift: folded below by scaling the data after each stage)
+    const int64_t b0 = (int64_t)blockIdx.x * rows_per_wg;
+    const int64_t b1 = b0 + rows_per_wg < B ? b0 + rows_per_wg : B;
+    for (int64_t b = b0; b < b1; ++b) {
+        const uint4* src = reinterpret_cast<const uint4*>(u + row_off(b, h, H, N));
+        for (int i = tid; i < N / 8; i += NW * 64) {
+            H8U x, lo, hi;
+            x.u = src[i];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                lo.c[q] = h2{x.v[q], (_Float16)0.f};
+                hi.c[q] = h2{x.v[4 + q], (_Float16)0.f};
+            }
+            *reinterpret_cast<uint4*>(&s[phys(8 * i)]) = lo.u;
+            *reinterpret_cast<uint4*>(&s[phys(8 * i + 4)]) = hi.u;
+            const uint4 z = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4*>(&s[phys(N + 8 * i)]) = z;
+            *reinterpret_cast<uint4*>(&s[phys(N + 8 * i + 4)]) = z;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int st = 0; st < S; ++st) {
+            const int id = st == S - 1 ? 4 : C::off(st);
+            Mats A = F[id];
+            // the stage's power of two: exact in fp16 for these entries (magnitudes 0 .. 1)
+            if (C::shift(st) == 1) { A.re = A.re * (_Float16)0.5f; A.im = A.im * (_Float16)0.5f; }
+            if (C::shift(st) == 2) { A.re = A.re * (_Float16)0.25f; A.im = A.im * (_Float16)0.25f; }
+            for (int t = wave; t < T; t += NW) {
+                if (st < S - 1)
+                    stage_tile<1>(s, sS, t, C::win(st), A, C::lgM(st), C::bits(st), tw, lane);
+                else
+                    stage_tile<3>(s, sS, t, C::win(st), A, 0, 0, tw, lane);
+            }
+            __syncthreads();
+        }
+#pragma unroll
+        for (int st = S - 1; st >= 0; --st) {
+            const int id = st == S - 1 ? 4 : C::off(st);
+            Mats A = I[id];
+            if (C::shift(st) == 1) { A.re = A.re * (_Float16)0.5f; A.im = A.im * (_Float16)0.5f; }
+            if (C::shift(st) == 2) { A.re = A.re * (_Float16)0.25f; A.im = A.im * (_Float16)0.25f; }
+            for (int t = wave; t < T; t += NW) {
+                if (st > 0)
+                    stage_tile<2>(s, sS, t, C::win(st), A, C::lgM(st - 1), C::bits(st - 1), tw, lane);
+                else
+                    stage_tile<0>(s, sS, t, C::win(st), A, 0, 0, tw, lane);
+            }
+            __syncthreads();
+        }
+        // forward and inverse chain each took out 2^-floor(LG/2); 1/L is due
+        const float yscale = (LG & 1) ? 0.5f : 1.0f;
+        uint4* dst = reinterpret_cast<uint4*>(y + row_off(b, h, H, N));
+        for (int i = tid; i < N / 8; i += NW * 64) {
+            H8U lo, hi, o;
+            lo.u = *reinterpret_cast<const uint4*>(&s[phys(8 * i)]);
+            hi.u = *reinterpret_cast<const uint4*>(&s[phys(8 * i + 4)]);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                o.c[q] = pack((float)lo.c[2 * q][0] * yscale, (float)lo.c[2 * q + 1][0] * yscale);
+                o.c[2 + q] = pack((float)hi.c[2 * q][0] * yscale, (float)hi.c[2 * q + 1][0] * yscale);
+            }
+            dst[i] = o.u;
+        }
+        __syncthreads();
+    }
+}
+
+template <int LG, int BITS>
+hipError_t bs_go(const void* u, const float* shat, void* y, int64_t B, int64_t H, const Tables& tb, hipStream_t st)
+{
+    constexpr int NW = bs_waves<LG>();
+    const size_t lds = (size_t)2 * (1 << LG) * sizeof(h2);
+    const int64_t want = (int64_t)compute_units() * 8;
+    int64_t rows = (B * H + want - 1) / want;
+    if (rows < 4) rows = 4;
+    if (rows > B) rows = B;
+    const unsigned groups = (unsigned)((B + rows - 1) / rows);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bs_fwd_kernel<LG, BITS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((bs_fwd_kernel<LG, BITS>), dim3(groups, (unsigned)H), dim3(NW * 64), lds, st, (const __half*)u,
+                       (const float2*)shat, (__half*)y, B, H, (int)rows, tb.tw);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// forward convolution of fp16 rows with DFT blocks of 2^log2r points; N = 1024 or 4096
+hipError_t blocksize_fwd(const void* u, const float* shat, void* y, int64_t B, int64_t H, int64_t N, int log2r,
+                         const Tables& tb, hipStream_t st)
+{
+#define BS_CASE(LGV)                                                  \
+    switch (log2r) {                                                  \
+        case 1: return bs_go<LGV, 1>(u, shat, y, B, H, tb, st);       \
+        case 2: return bs_go<LGV, 2>(u, shat, y, B, H, tb, st);       \
+        case 3: return bs_go<LGV, 3>(u, shat, y, B, H, tb, st);       \
+        case 4: return bs_go<LGV, 4>(u, shat, y, B, H, tb, st);       \
+        default: return hipErrorInvalidValue;                         \
+    }
+    if (N == 1024) { BS_CASE(11) }
+    if (N == 4096) { BS_CASE(13) }
+#undef BS_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace lc

@@ -82,6 +82,10 @@ hipError_t lbfly_spectrum(const float* k, const float* D, float* shat, int64_t H
 hipError_t lbfly_spectrum_bwd(const float* dshat, float* dk, float* dD, int64_t H, int64_t N, const Tables& tb,
                               hipStream_t st);
 
+// ---- block-size study (bsize.hip): forward convolution of fp16 rows with DFT blocks of 2^log2r points, N = 1024, 4096
+hipError_t blocksize_fwd(const void* u, const float* shat, void* y, int64_t B, int64_t H, int64_t N, int log2r,
+                         const Tables& tb, hipStream_t st);
+
 // ---- kernel regularisers (kreg.hip): Kbar = Squash(Smooth(dropout(K))) and the chain back to K -----------------
 constexpr int KREG_MAX_P = 32;
 hipError_t kreg_fwd(const float* k, const float* mask, float* kbar, int64_t H, int64_t N, int p, float lam,

@@ -1,6 +1,7 @@
 """Length sweep and block-size-table shape on one MI355X: `python -m paper_2302_06646_amd.sweep [--quick]`;
 `--learned` times the learned Butterfly extension against the fixed path instead (the shape of the paper's table of
-learnable block sizes: block size 16 against the fixed Butterfly, as a speed ratio).
+learnable block sizes: block size 16 against the fixed Butterfly, as a speed ratio); `--blocks` runs the table of
+block sizes (2, 4, 8, 16 points per block at N = 4096, B = 128, H = 32) with the study kernel.
 
 Two measurements that mirror the paper's efficiency experiments (Section 5.4 runtime figure: one layer, batch 32,
 128 heads, N = 1K ... 128K, against the FFT-library convolution; Table of block sizes: N = 4096, B = 128, H = 32),
@@ -165,16 +166,58 @@ def learned_row(B, H, N, steps):
     return r
 
 
+def block_sizes(B, H, N, steps):
+    """The paper's table of block sizes at its shape (fp16 rows): forward time of the study kernel with DFT blocks of
+    2, 4, 8 and 16 points, every block run as one 16 x 16 matrix product, and the matrix-core work it executes."""
+    td = torch.float16
+    nsets = 4
+    g = torch.Generator(device="cuda").manual_seed(N)
+    us = [torch.randn((B, H, N), generator=g, device="cuda", dtype=torch.float32).to(td) for _ in range(nsets)]
+    y = torch.empty_like(us[0])
+    k = torch.randn(H, N, device="cuda") / N ** 0.5
+    D = torch.randn(H, device="cuda")
+    shat = torch.empty(H, 2 * N, 2, device="cuda")
+    lc.longconv_lbfly_spectrum(k, D, shat)
+    LG = (2 * N).bit_length() - 1
+    rows = []
+    for log2r in (1, 2, 3, 4):
+        fn = lambda i: lc.longconv_blocksize_fwd(us[i % nsets], shat, y, log2r)
+        for i in range(3):
+            fn(i)
+        t = _timed(steps, fn)
+        stages = -(-LG // log2r)
+        # two matrix instructions of 16384 flop per 256-point tile and stage, forward and inverse chain, one complex
+        # sequence per real row
+        gflop = B * H * (2 * N / 256) * 2 * stages * 2 * 16384 / 1e9
+        # what the same stages would cost with blocks of exactly r points: 8 r flop per point and stage
+        nominal = B * H * 2 * N * 2 * stages * 8 * (1 << log2r) / 1e9
+        rows.append({"B": B, "H": H, "N": N, "block": 1 << log2r, "stages_each_way": stages, "fwd_us": t,
+                     "executed_mfma_GFLOP": gflop, "nominal_GFLOP": nominal, "mfma_TFLOPs": gflop / t * 1e3,
+                     "mfma_pct_of_peak": 100 * gflop / t * 1e3 / 2500.0})
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--quick", action="store_true", help="fewer steps and lengths")
     ap.add_argument("--learned", action="store_true", help="learned Butterfly extension against the fixed path")
+    ap.add_argument("--blocks", action="store_true", help="the table of block sizes: 2, 4, 8, 16 at N=4096, B=128, H=32")
     a = ap.parse_args()
     if not torch.cuda.is_available():
         print("sweep: no GPU visible", file=sys.stderr)
         sys.exit(1)
     lc.longconv_init()
     steps = 10 if a.quick else 30
+    if a.blocks:
+        rows = block_sizes(128, 32, 4096, steps)
+        print("| block size | stages each way | fwd (us) | executed MFMA GFLOP | GFLOP at r-point blocks | TFLOP/s | % of 2.5 PFLOP/s |")
+        print("|---|---|---|---|---|---|---|")
+        for r in rows:
+            print(f"| {r['block']} | {r['stages_each_way']} | {r['fwd_us']:.1f} | {r['executed_mfma_GFLOP']:.1f} | "
+                  f"{r['nominal_GFLOP']:.1f} | {r['mfma_TFLOPs']:.0f} | {r['mfma_pct_of_peak']:.1f} |")
+        for r in rows:
+            print(json.dumps(r))
+        return
     if a.learned:
         shapes = [(16, 768, 1024)] if a.quick else [(16, 768, 1024), (64, 256, 1024), (64, 1024, 256), (64, 1024, 2048)]
         rows = [learned_row(B, H, N, steps) for (B, H, N) in shapes]

@@ -1,0 +1,43 @@
+"""Block-size study kernel through the C ABI: with every block size the result is the plain convolution of the
+float64 oracle, to the bound of the fixed path."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2302_06646_amd as lc
+import workloads as wl
+from gpu_harness import TOL, _compare, to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("N", [1024, 4096])
+@pytest.mark.parametrize("log2r", [1, 2, 3, 4])
+def test_every_block_size_gives_the_convolution(N, log2r):
+    B, H = 5, 3
+    print(f"[blocksize] N={N} r={1 << log2r}", flush=True)
+    w = wl.Workload(6, B, H, N, wl.F16, "decay_alpha_squash")
+    inp = wl.generate(w, seed_extra=log2r)
+    u = to_dev(inp.u_store, wl.F16)
+    k, D = torch.from_numpy(inp.k).cuda(), torch.from_numpy(inp.D).cuda()
+    shat = torch.full((H, 2 * N, 2), float("nan"), device="cuda")
+    lc.longconv_lbfly_spectrum(k, D, shat)
+    y = torch.full_like(u, float("nan"))
+    lc.longconv_blocksize_fwd(u, shat, y, log2r)
+    torch.cuda.synchronize()
+    ref = oracle.longconv_fwd(inp.u, inp.k.astype(np.float64), inp.D.astype(np.float64))
+    _compare({"y": to_f64(y, wl.F16)}, {"y": ref}, TOL[wl.F16], f"block size {1 << log2r} N={N}")
+
+
+def test_refused_arguments():
+    u = torch.zeros(2, 2, 1024, device="cuda", dtype=torch.float16)
+    shat = torch.zeros(2, 2048, 2, device="cuda")
+    with pytest.raises(lc.LongconvError, match="shape"):
+        lc.longconv_blocksize_fwd(u, shat, torch.empty_like(u), 5)
+    ub = u.to(torch.bfloat16)
+    with pytest.raises(lc.LongconvError, match="dtype"):
+        lc.longconv_blocksize_fwd(ub, shat, torch.empty_like(ub), 4)
+    u2 = torch.zeros(2, 2, 2048, device="cuda", dtype=torch.float16)
+    with pytest.raises(lc.LongconvError, match="shape"):
+        lc.longconv_blocksize_fwd(u2, torch.zeros(2, 4096, 2, device="cuda"), torch.empty_like(u2), 4)
