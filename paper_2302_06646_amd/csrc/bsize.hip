@@ -2,8 +2,9 @@
 // b x b matrix unit a block of size r < b costs what a b x b block costs, so that the executed flops go as
 // N b log N / log r and raising r up to b lowers them): the FFT convolution of Eq. 2 with every stage a dense DFT
 // block of size r = 2, 4, 8 or 16, all of them run on the 16-wide matrix unit (a block smaller than 16 as the
-// matrix I (x) F_r (x) I of size 16).  A measurement kernel: one real row per complex sequence, every stage a trip
-// through LDS, so that the only thing that changes with r is the number of stages, ceil(log2(2N) / log2 r) each way.
+// matrix I (x) F_r (x) I of size 16), and r = 32 on the 32-wide instruction (further down).  A measurement kernel:
+// one real row per complex sequence, every stage a trip through LDS, so that the only thing that changes with r is
+// the number of stages, ceil(log2(2N) / log2 r) each way.
 //
 //   L = 2N = 2^LG, digits of BITS bits from the top (the last digit takes what is left), decimation in frequency:
 //   stage s applies F_r along digit s, then the twiddle exp(-2 pi i k_s (p mod M_s) / (r_s M_s)) (Appendix C.1);
@@ -220,6 +221,193 @@ bs_fwd_kernel(const __half* __restrict__ u, const float2* __restrict__ shat, __h
     }
 }
 
+// -------------------------------------------------------------------------------------------------------------------
+// Blocks of 32 points: wider than the 16 x 16 x 32 instruction, run on v_mfma_f32_32x32x16_f16.  A tile is 32 slots x
+// 32 columns; the complex product in real form has K = 64 (slot, re / im), four K steps of 16: step s, lane
+// (l % 32, kg = l / 32) holds slots 8s + 4kg .. + 3 as (re, im) pairs.  The result (lane: column l % 32, rows
+// 8 (j / 4) + 4 (l / 32) + j % 4 in register j) lies as the operand of the same slots does, so a stage is in place.
+// -------------------------------------------------------------------------------------------------------------------
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+struct Mats32 {
+    h8 re[4], im[4];
+};
+
+template <int LG>
+struct BS32 {
+    static constexpr int BITS = 5, S = (LG + BITS - 1) / BITS;
+    static __host__ __device__ constexpr int bits(int s) { return s < S - 1 ? BITS : LG - BITS * (S - 1); }
+    static __host__ __device__ constexpr int lgM(int s) { return s < S - 1 ? LG - BITS * (s + 1) : 0; }
+    static __host__ __device__ constexpr int win(int s) { return lgM(s) < LG - 5 ? lgM(s) : LG - 5; }
+    static __host__ __device__ constexpr int off(int s) { return lgM(s) - win(s); }
+    static __host__ __device__ constexpr int cum(int s) { return s < S ? BITS * s : LG; }
+    static __host__ __device__ constexpr int shift(int s) { return (cum(s) + bits(s)) / 2 - cum(s) / 2; }
+};
+
+__device__ Mats32 dft_mats32(int o, int b, int sh, bool inverse, const float2* __restrict__ tw, int lane)
+{
+    const int r = 1 << b, m = lane & 31, kg = lane >> 5, keep = ~((r - 1) << o) & 31;
+    const float sc = 1.0f / (float)(1 << sh);
+    Mats32 A;
+#pragma unroll
+    for (int st = 0; st < 4; ++st)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int sig = 8 * st + 4 * kg + q;
+            float2 w = make_float2(0.f, 0.f);
+            if (((m ^ sig) & keep) == 0) {
+                const int jk = (((m >> o) & (r - 1)) * ((sig >> o) & (r - 1))) & (r - 1);
+                w = tw_full(tw, (uint32_t)jk << (TW_LOG2 - b));
+                if (inverse) w.y = -w.y;
+            }
+            A.re[st][2 * q] = (_Float16)(w.x * sc);
+            A.re[st][2 * q + 1] = (_Float16)(-w.y * sc);
+            A.im[st][2 * q] = (_Float16)(w.y * sc);
+            A.im[st][2 * q + 1] = (_Float16)(w.x * sc);
+        }
+    return A;
+}
+
+__device__ __forceinline__ int tile_pos5(int gamma, int sigma, int w)
+{
+    return ((gamma >> w) << (w + 5)) | (gamma & ((1 << w) - 1)) | (sigma << w);
+}
+
+template <int POST>
+__device__ __forceinline__ void stage_tile32(h2* s, const h2* sS, int t, int w, const Mats32& A, int tM, int tb,
+                                             const float2* __restrict__ tw, int lane)
+{
+    const int c = lane & 31, kg = lane >> 5;
+    const int p0 = tile_pos5(32 * t + c, 4 * kg, w), a0 = phys(p0);
+    int a[16];
+    H8U x[4];
+#pragma unroll
+    for (int st = 0; st < 4; ++st)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            a[4 * st + q] = a0 ^ phys((8 * st + q) << w);        // slot bits 0, 1, 3, 4 are clear in p0
+            x[st].c[q] = s[a[4 * st + q]];
+        }
+    f16v yr, yi;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { yr[j] = 0.f; yi[j] = 0.f; }
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+        yr = __builtin_amdgcn_mfma_f32_32x32x16_f16(A.re[st], x[st].v, yr, 0, 0, 0);
+        yi = __builtin_amdgcn_mfma_f32_32x32x16_f16(A.im[st], x[st].v, yi, 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        float2 v = make_float2(yr[j], yi[j]);
+        const int p = p0 | ((8 * (j >> 2) + (j & 3)) << w);
+        if (POST == 1) v = cmul(v, twiddle(tw, p, tM, tb));
+        if (POST == 2) v = cmulc(v, twiddle(tw, p, tM, tb));
+        if (POST == 3) {
+            const h2 k = sS[a[j]];
+            v = cmul(v, make_float2((float)k[0], (float)k[1]));
+        }
+        s[a[j]] = pack(v.x, v.y);
+    }
+}
+
+template <int LG> __host__ __device__ constexpr int bs32_waves() { return LG >= 13 ? 4 : 2; }   // six 32-wide matrices in registers: no more than 256 lanes
+
+template <int LG>
+__global__ void __launch_bounds__(bs32_waves<LG>() * 64)
+bs32_fwd_kernel(const __half* __restrict__ u, const float2* __restrict__ shat, __half* __restrict__ y, int64_t B,
+                int64_t H, int rows_per_wg, const float2* __restrict__ tw)
+{
+    using C = BS32<LG>;
+    extern __shared__ uint4 smem_raw[];
+    constexpr int NW = bs32_waves<LG>(), L = 1 << LG, N = L / 2, T = L / 1024, S = C::S;
+    h2* sS = reinterpret_cast<h2*>(smem_raw);
+    h2* s = sS + L;
+    const int h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // every stage but the last has its digit at the bottom of the slot window (5 bits wide, as the window) 
+    const Mats32 F5 = dft_mats32(0, 5, C::shift(0), false, tw, lane), I5 = dft_mats32(0, 5, C::shift(0), true, tw, lane);
+    const Mats32 F5b = dft_mats32(0, 5, C::shift(1), false, tw, lane), I5b = dft_mats32(0, 5, C::shift(1), true, tw, lane);
+    const Mats32 FL = dft_mats32(0, C::bits(S - 1), C::shift(S - 1), false, tw, lane);
+    const Mats32 IL = dft_mats32(0, C::bits(S - 1), C::shift(S - 1), true, tw, lane);
+    static_assert(C::off(0) == 0 && C::off(S - 2) == 0, "5-bit digits fill the slot window");
+    static_assert(S == 3, "two 5-bit stages and the rest");
+
+    const float2* sh = shat + (size_t)h * L;
+    for (int f = tid; f < L; f += NW * 64) {
+        int p = 0, rest = f;
+#pragma unroll
+        for (int st = 0; st < S; ++st) {
+            p |= (rest & ((1 << C::bits(st)) - 1)) << C::lgM(st);
+            rest >>= C::bits(st);
+        }
+        const float2 v = sh[f];
+        sS[phys(p)] = pack(v.x, v.y);
+    }
+    const int64_t b0 = (int64_t)blockIdx.x * rows_per_wg;
+    const int64_t b1 = b0 + rows_per_wg < B ? b0 + rows_per_wg : B;
+    for (int64_t b = b0; b < b1; ++b) {
+        const uint4* src = reinterpret_cast<const uint4*>(u + row_off(b, h, H, N));
+        for (int i = tid; i < N / 8; i += NW * 64) {
+            H8U x, lo, hi;
+            x.u = src[i];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                lo.c[q] = h2{x.v[q], (_Float16)0.f};
+                hi.c[q] = h2{x.v[4 + q], (_Float16)0.f};
+            }
+            *reinterpret_cast<uint4*>(&s[phys(8 * i)]) = lo.u;
+            *reinterpret_cast<uint4*>(&s[phys(8 * i + 4)]) = hi.u;
+            const uint4 z = make_uint4(0, 0, 0, 0);
+            *reinterpret_cast<uint4*>(&s[phys(N + 8 * i)]) = z;
+            *reinterpret_cast<uint4*>(&s[phys(N + 8 * i + 4)]) = z;
+        }
+        __syncthreads();
+        for (int t = wave; t < T; t += NW) stage_tile32<1>(s, sS, t, C::win(0), F5, C::lgM(0), 5, tw, lane);
+        __syncthreads();
+        for (int t = wave; t < T; t += NW) stage_tile32<1>(s, sS, t, C::win(1), F5b, C::lgM(1), 5, tw, lane);
+        __syncthreads();
+        for (int t = wave; t < T; t += NW) stage_tile32<3>(s, sS, t, C::win(2), FL, 0, 0, tw, lane);
+        __syncthreads();
+        for (int t = wave; t < T; t += NW) stage_tile32<2>(s, sS, t, C::win(2), IL, C::lgM(1), 5, tw, lane);
+        __syncthreads();
+        for (int t = wave; t < T; t += NW) stage_tile32<2>(s, sS, t, C::win(1), I5b, C::lgM(0), 5, tw, lane);
+        __syncthreads();
+        for (int t = wave; t < T; t += NW) stage_tile32<0>(s, sS, t, C::win(0), I5, 0, 0, tw, lane);
+        __syncthreads();
+        const float yscale = (LG & 1) ? 0.5f : 1.0f;
+        uint4* dst = reinterpret_cast<uint4*>(y + row_off(b, h, H, N));
+        for (int i = tid; i < N / 8; i += NW * 64) {
+            H8U lo, hi, o;
+            lo.u = *reinterpret_cast<const uint4*>(&s[phys(8 * i)]);
+            hi.u = *reinterpret_cast<const uint4*>(&s[phys(8 * i + 4)]);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                o.c[q] = pack((float)lo.c[2 * q][0] * yscale, (float)lo.c[2 * q + 1][0] * yscale);
+                o.c[2 + q] = pack((float)hi.c[2 * q][0] * yscale, (float)hi.c[2 * q + 1][0] * yscale);
+            }
+            dst[i] = o.u;
+        }
+        __syncthreads();
+    }
+}
+
+template <int LG>
+hipError_t bs32_go(const void* u, const float* shat, void* y, int64_t B, int64_t H, const Tables& tb, hipStream_t st)
+{
+    constexpr int NW = bs32_waves<LG>();
+    const size_t lds = (size_t)2 * (1 << LG) * sizeof(h2);
+    const int64_t want = (int64_t)compute_units() * 8;
+    int64_t rows = (B * H + want - 1) / want;
+    if (rows < 4) rows = 4;
+    if (rows > B) rows = B;
+    const unsigned groups = (unsigned)((B + rows - 1) / rows);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(bs32_fwd_kernel<LG>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((bs32_fwd_kernel<LG>), dim3(groups, (unsigned)H), dim3(NW * 64), lds, st, (const __half*)u,
+                       (const float2*)shat, (__half*)y, B, H, (int)rows, tb.tw);
+    return hipGetLastError();
+}
+
 template <int LG, int BITS>
 hipError_t bs_go(const void* u, const float* shat, void* y, int64_t B, int64_t H, const Tables& tb, hipStream_t st)
 {
@@ -240,7 +428,7 @@ hipError_t bs_go(const void* u, const float* shat, void* y, int64_t B, int64_t H
 
 }  // namespace
 
-// forward convolution of fp16 rows with DFT blocks of 2^log2r points; N = 1024 or 4096
+// forward convolution of fp16 rows with DFT blocks of 2^log2r points (log2r = 1 .. 5); N = 1024 or 4096
 hipError_t blocksize_fwd(const void* u, const float* shat, void* y, int64_t B, int64_t H, int64_t N, int log2r,
                          const Tables& tb, hipStream_t st)
 {
@@ -250,6 +438,7 @@ hipError_t blocksize_fwd(const void* u, const float* shat, void* y, int64_t B, i
         case 2: return bs_go<LGV, 2>(u, shat, y, B, H, tb, st);       \
         case 3: return bs_go<LGV, 3>(u, shat, y, B, H, tb, st);       \
         case 4: return bs_go<LGV, 4>(u, shat, y, B, H, tb, st);       \
+        case 5: return bs32_go<LGV>(u, shat, y, B, H, tb, st);        \
         default: return hipErrorInvalidValue;                         \
     }
     if (N == 1024) { BS_CASE(11) }

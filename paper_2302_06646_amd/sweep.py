@@ -1,7 +1,7 @@
 """Length sweep and block-size-table shape on one MI355X: `python -m paper_2302_06646_amd.sweep [--quick]`;
 `--learned` times the learned Butterfly extension against the fixed path instead (the shape of the paper's table of
 learnable block sizes: block size 16 against the fixed Butterfly, as a speed ratio); `--blocks` runs the table of
-block sizes (2, 4, 8, 16 points per block at N = 4096, B = 128, H = 32) with the study kernel.
+block sizes (2 ... 32 points per block at N = 4096, B = 128, H = 32) with the study kernel.
 
 Two measurements that mirror the paper's efficiency experiments (Section 5.4 runtime figure: one layer, batch 32,
 128 heads, N = 1K ... 128K, against the FFT-library convolution; Table of block sizes: N = 4096, B = 128, H = 32),
@@ -168,7 +168,8 @@ def learned_row(B, H, N, steps):
 
 def block_sizes(B, H, N, steps):
     """The paper's table of block sizes at its shape (fp16 rows): forward time of the study kernel with DFT blocks of
-    2, 4, 8 and 16 points, every block run as one 16 x 16 matrix product, and the matrix-core work it executes."""
+    2, 4, 8, 16 points (every block run as one 16 x 16 matrix product) and 32 points (one 32 x 32 product), and the
+    matrix-core work it executes."""
     td = torch.float16
     nsets = 4
     g = torch.Generator(device="cuda").manual_seed(N)
@@ -180,7 +181,7 @@ def block_sizes(B, H, N, steps):
     lc.longconv_lbfly_spectrum(k, D, shat)
     LG = (2 * N).bit_length() - 1
     rows = []
-    for log2r in (1, 2, 3, 4):
+    for log2r in (1, 2, 3, 4, 5):
         fn = lambda i: lc.longconv_blocksize_fwd(us[i % nsets], shat, y, log2r)
         for i in range(3):
             fn(i)
@@ -188,9 +189,11 @@ def block_sizes(B, H, N, steps):
         stages = -(-LG // log2r)
         # two matrix instructions of 16384 flop per 256-point tile and stage, forward and inverse chain, one complex
         # sequence per real row
-        gflop = B * H * (2 * N / 256) * 2 * stages * 2 * 16384 / 1e9
+        # (blocks of 32 points: eight instructions of 32768 flop per 1024-point tile and stage)
+        per_point_stage = 2 * 16384 / 256 if log2r <= 4 else 8 * 32768 / 1024
+        gflop = B * H * 2 * N * 2 * stages * per_point_stage / 1e9
         # what the same stages would cost with blocks of exactly r points: 8 r flop per point and stage
-        nominal = B * H * 2 * N * 2 * stages * 8 * (1 << log2r) / 1e9
+        nominal = B * H * 2 * N * 2 * stages * 8 * (1 << log2r) / 1e9   # (the last, narrower stage counted as a full one)
         rows.append({"B": B, "H": H, "N": N, "block": 1 << log2r, "stages_each_way": stages, "fwd_us": t,
                      "executed_mfma_GFLOP": gflop, "nominal_GFLOP": nominal, "mfma_TFLOPs": gflop / t * 1e3,
                      "mfma_pct_of_peak": 100 * gflop / t * 1e3 / 2500.0})
@@ -201,7 +204,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--quick", action="store_true", help="fewer steps and lengths")
     ap.add_argument("--learned", action="store_true", help="learned Butterfly extension against the fixed path")
-    ap.add_argument("--blocks", action="store_true", help="the table of block sizes: 2, 4, 8, 16 at N=4096, B=128, H=32")
+    ap.add_argument("--blocks", action="store_true", help="the table of block sizes: 2 ... 32 at N=4096, B=128, H=32")
     a = ap.parse_args()
     if not torch.cuda.is_available():
         print("sweep: no GPU visible", file=sys.stderr)
