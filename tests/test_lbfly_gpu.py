@@ -87,8 +87,8 @@ def _check_blocks(got, want, N, tol, label):
     return worst
 
 
-CASES = [(256, wl.F16, 5, 3), (256, wl.BF16, 3, 520), (512, wl.BF16, 5, 3), (1024, wl.F16, 7, 2),
-         (1024, wl.BF16, 4, 3), (2048, wl.F16, 3, 2), (2048, wl.BF16, 5, 2)]
+CASES = [(256, wl.F16, 5, 3), (256, wl.BF16, 3, 520), (512, wl.BF16, 5, 3), (512, wl.F16, 1, 1), (1024, wl.F16, 7, 2),
+         (1024, wl.BF16, 4, 3), (1024, wl.F16, 13, 1), (2048, wl.F16, 3, 2), (2048, wl.BF16, 5, 2)]
 
 
 @pytest.mark.parametrize("N,io,B,H", CASES)
