@@ -153,8 +153,8 @@ bs_fwd_kernel(const __half* __restrict__ u, const float2* __restrict__ shat, __h
         const float2 v = sh[f];
         sS[phys(p)] = pack(v.x, v.y);
     }
-    // the stages' powers of two are applied to the result as one factor (the matrices themselves are unscaled DFT
-    // blocks times 2^-shift: folded below by scaling the data after each stage)
+    // every stage's matrix carries that stage's power of two (applied to the operand copy below); what is left of
+    // 1/L after the 2 floor(LG/2) bits taken out on the way is applied to the result
     const int64_t b0 = (int64_t)blockIdx.x * rows_per_wg;
     const int64_t b1 = b0 + rows_per_wg < B ? b0 + rows_per_wg : B;
     for (int64_t b = b0; b < b1; ++b) {
