@@ -58,6 +58,22 @@ def test_conv2d_against_the_oracle(N1, N2, io, B, H):
              f"conv2d {N1}x{N2} io={wl.DTYPE_NAMES[io]}")
 
 
+def test_full_size_image_batch_on_sampled_heads():
+    """B=64, H=256, 32x32 bf16 images (the shape timed in the design notes), all of it through the library; eight heads
+    (first, last, seeded ones) in full against the oracle."""
+    B, H, N1, N2, io = 64, 256, 32, 32, wl.BF16
+    u_s, u_v, dy_s, dy_v, k, D = _inputs(B, H, N1, N2, io, seed=3)
+    y, du, dk, dD = _run(u_s, dy_s, k, D, io)
+    heads = sorted({0, H - 1, *np.random.default_rng(6).choice(H, size=6, replace=False).tolist()})
+    k64, D64 = k[heads].astype(np.float64), D[heads].astype(np.float64)
+    ry = conv2d.conv2d_fwd(u_v[:, heads], k64, D64)
+    rdu, rdk, rdD = conv2d.conv2d_bwd(dy_v[:, heads], u_v[:, heads], k64, D64)
+    flat = lambda a: a.reshape(a.shape[:-2] + (N1 * N2,))
+    _compare({"y": flat(y[:, heads]), "du": flat(du[:, heads]), "dk": flat(dk[heads]), "dD": dD[heads]},
+             {"y": flat(ry), "du": flat(rdu), "dk": flat(rdk), "dD": rdD}, TOL[io], "conv2d full size")
+    assert np.all(np.isfinite(y)) and np.all(np.isfinite(du)) and np.all(np.isfinite(dk))
+
+
 def test_delta_filter_shifts_the_image_exactly():
     # k = delta at (3, 5), D = 0: y is u moved down 3 and right 5, with zeros (not wrapped samples) coming in
     B, H, N1, N2, io = 2, 2, 32, 32, wl.F32

@@ -125,6 +125,26 @@ def test_dft_blocks_reproduce_the_plain_convolution(N, io):
     assert float(np.max(np.abs(g["dD"] - rdD)) / np.sqrt(np.mean(rdD ** 2))) <= TOL[io]
 
 
+def test_full_size_of_the_timed_shape():
+    """B=16, H=768, N=1024, bf16 rows: the shape `sweep --learned` times, in its launch configuration (rows of a head
+    split over workgroups as there); every output of 24 heads (first, last, seeded ones) against the oracle."""
+    N, io, B, H = 1024, wl.BF16, 16, 768
+    u_s, u_v, dy_s, dy_v, k, D, Af32, Ai32, Af, Ai = _inputs(B, H, N, io, seed=3)
+    g = _run(u_s, dy_s, k, D, Af32, Ai32, io)
+    heads = sorted({0, H - 1, *np.random.default_rng(5).choice(H, size=22, replace=False).tolist()})
+    shat = lbfly.spectrum(k[heads], D[heads])
+    ry = lbfly.lbfly_fwd(u_v[:, heads], shat, Af[heads], Ai[heads])
+    rdu, rdshat, rdAf, rdAi = lbfly.lbfly_bwd(dy_v[:, heads], u_v[:, heads], shat, Af[heads], Ai[heads])
+    rdk, rdD = lbfly.spectrum_bwd(rdshat, N)
+    tol = TOL[io]
+    label = "lbfly full size"
+    _compare({"y": g["y"][:, heads], "du": g["du"][:, heads], "dshat": _ri(g["dshat"][heads]), "dk": g["dk"][heads]},
+             {"y": ry, "du": rdu, "dshat": _ri(rdshat), "dk": rdk}, tol, label)
+    _check_blocks(g["dAf"][heads], rdAf, N, tol, label + " dAf")
+    _check_blocks(g["dAi"][heads], rdAi, N, tol, label + " dAi")
+    assert np.all(np.isfinite(g["y"])) and np.all(np.isfinite(g["dAf"])) and np.all(np.isfinite(g["dshat"]))
+
+
 def test_optional_outputs_repeatability_and_error_codes():
     N, io, B, H = 512, wl.F16, 4, 3
     u_s, u_v, dy_s, dy_v, k, D, Af32, Ai32, Af, Ai = _inputs(B, H, N, io, seed=2)
