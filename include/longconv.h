@@ -210,7 +210,10 @@ int longconv_lbfly_bwd(const void* dy, const void* u, const float* shat, const f
 /* Block-size study (Section 3.2, the table of block sizes; Appendix C: on a b x b matrix unit a block of size
  * r < b costs what a b x b block costs): y = (u * k)[:N] + D u as longconv_fwd computes it, but with every stage of
  * the transform a dense DFT block of r = 2^log2r points (log2r = 1 .. 4: each run as a 16 x 16 matrix product;
- * log2r = 5: as a 32 x 32 one), so that ceil(log2(2N) / log2r) stages are executed each way.  A measurement kernel, not a fast path: fp16 rows only
+ * log2r = 5: as a 32 x 32 one; log2r = 6, and 8 at N = 4096 only: as a dense 2r x 2r real product in 32 x 32 tiles, the
+ * bits of log2(2N) that a whole number of such blocks leaves over as one narrower stage), so that
+ * ceil(log2(2N) / log2r) stages are executed each way; any other log2r is LONGCONV_ERR_SHAPE.  The first call with
+ * log2r = 8 on a device fills a 512 KB table and synchronises the stream once.  A measurement kernel, not a fast path: fp16 rows only
  * (LONGCONV_ERR_DTYPE otherwise), N = 1024 or 4096, shat [H, 2N, 2] float32 from longconv_lbfly_spectrum (which
  * serves lengths up to 4096 for this purpose).  Same accuracy bound as longconv_fwd.  No workspace. */
 int longconv_blocksize_fwd(const void* u, const float* shat, void* y,

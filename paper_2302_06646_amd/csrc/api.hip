@@ -743,7 +743,8 @@ int longconv_blocksize_fwd(const void* u, const float* shat, void* y, int64_t B,
                            void* stream)
 {
     if (io != LONGCONV_F16) return LONGCONV_ERR_DTYPE;
-    if (B < 1 || B > (int64_t(1) << 24) || H < 1 || H > 65535 || (N != 1024 && N != 4096) || log2r < 1 || log2r > 5)
+    if (B < 1 || B > (int64_t(1) << 24) || H < 1 || H > 65535 || (N != 1024 && N != 4096) || log2r < 1 ||
+        (log2r > 6 && !(log2r == 8 && N == 4096)))
         return LONGCONV_ERR_SHAPE;
     if (!u || !shat || !y) return LONGCONV_ERR_NULL;
     if (misaligned(u) || misaligned(shat) || misaligned(y)) return LONGCONV_ERR_ALIGN;

@@ -168,8 +168,9 @@ def learned_row(B, H, N, steps):
 
 def block_sizes(B, H, N, steps):
     """The paper's table of block sizes at its shape (fp16 rows): forward time of the study kernel with DFT blocks of
-    2, 4, 8, 16 points (every block run as one 16 x 16 matrix product) and 32 points (one 32 x 32 product), and the
-    matrix-core work it executes."""
+    2, 4, 8, 16 points (every block run as one 16 x 16 matrix product), 32 points (one 32 x 32 product), 64 and 256
+    points (dense products in 32 x 32 tiles; the bits a whole number of such blocks leaves over run as one narrower
+    stage), and the matrix-core work it executes."""
     td = torch.float16
     nsets = 4
     g = torch.Generator(device="cuda").manual_seed(N)
@@ -180,18 +181,28 @@ def block_sizes(B, H, N, steps):
     shat = torch.empty(H, 2 * N, 2, device="cuda")
     lc.longconv_lbfly_spectrum(k, D, shat)
     LG = (2 * N).bit_length() - 1
+
+    def stage_flop_per_point(bits):
+        # matrix-core flop per point of one stage whose digit has `bits` bits, as the study kernels run it:
+        # up to 4 bits: two instructions of 16384 flop per 256-point tile; 5 bits: eight of 32768 flop per 1024-point
+        # tile; r = 64, 256: the dense 2r x 2r real product, 8 r flop per point
+        if bits <= 4:
+            return 2 * 16384 / 256
+        if bits == 5:
+            return 8 * 32768 / 1024
+        return 8 * (1 << bits)
+
     rows = []
-    for log2r in (1, 2, 3, 4, 5):
+    for log2r in (1, 2, 3, 4, 5, 6, 8):
         fn = lambda i: lc.longconv_blocksize_fwd(us[i % nsets], shat, y, log2r)
         for i in range(3):
             fn(i)
         t = _timed(steps, fn)
         stages = -(-LG // log2r)
-        # two matrix instructions of 16384 flop per 256-point tile and stage, forward and inverse chain, one complex
-        # sequence per real row
-        # (blocks of 32 points: eight instructions of 32768 flop per 1024-point tile and stage)
-        per_point_stage = 2 * 16384 / 256 if log2r <= 4 else 8 * 32768 / 1024
-        gflop = B * H * 2 * N * 2 * stages * per_point_stage / 1e9
+        digits = [log2r] * (stages - 1) + [LG - log2r * (stages - 1)]
+        # forward and inverse chain, one complex sequence per real row
+        # (the 32-point kernel runs its last, narrower digit on the 32-wide tile as well)
+        gflop = B * H * 2 * N * 2 * sum(stage_flop_per_point(5 if log2r == 5 else b) for b in digits) / 1e9
         # what the same stages would cost with blocks of exactly r points: 8 r flop per point and stage
         nominal = B * H * 2 * N * 2 * stages * 8 * (1 << log2r) / 1e9   # (the last, narrower stage counted as a full one)
         rows.append({"B": B, "H": H, "N": N, "block": 1 << log2r, "stages_each_way": stages, "fwd_us": t,
@@ -204,7 +215,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--quick", action="store_true", help="fewer steps and lengths")
     ap.add_argument("--learned", action="store_true", help="learned Butterfly extension against the fixed path")
-    ap.add_argument("--blocks", action="store_true", help="the table of block sizes: 2 ... 32 at N=4096, B=128, H=32")
+    ap.add_argument("--blocks", action="store_true", help="the table of block sizes: 2 ... 64 and 256 at N=4096, B=128, H=32")
     a = ap.parse_args()
     if not torch.cuda.is_available():
         print("sweep: no GPU visible", file=sys.stderr)
