@@ -40,12 +40,14 @@
  *     rows inside that band share one fp16 scale: their error is relative to the larger of
  *     the two); from N = 32768 on all rows of a head share one power of two, found by a
  *     pass over the tensor in front, so rows of one head that differ by many orders of
- *     magnitude lose the small ones.  Not rescaled, and therefore to be kept inside fp16's
- *     normal range by the caller: fp16 rows (order one is fine up to N = 131072; the
- *     transform grows them by at most sqrt(2N)) and the spectrum, |FFT(k) + D| within about
- *     2^-8 .. 2^8.  Far outside those ranges precision is lost silently.  The kernel k
- *     itself may have any magnitude on its way into the spectrum (per-head power-of-two
- *     rescaling).  fp32 I/O computes in fp32.
+ *     magnitude lose the small ones.  The kernel k and the skip term D may have any
+ *     magnitude as well: a head is scaled by a power of two on its way into the spectrum's
+ *     transform, and a head whose spectrum lies outside fp16's comfortable range is stored
+ *     with a further power of two taken out, which the convolutions give back where they
+ *     pack their output (heads of order one take neither path).  Not rescaled, and therefore
+ *     to be kept inside fp16's normal range by the caller: fp16 rows (order one is fine up
+ *     to N = 131072; the transform grows them by at most sqrt(2N)), and of course the outputs
+ *     have to fit the I/O dtype.  fp32 I/O computes in fp32.
  */
 #ifndef LONGCONV_H
 #define LONGCONV_H
@@ -80,9 +82,11 @@ int longconv_init(void);
  * permuted order the fused transform produces (Algorithm 2 lines 1-2: the
  * spectrum is computed once and stored already permuted, so no permutation ever
  * touches u).  Layout and element type are private to the library and depend on
- * (N, io): fp32 complex (8 bytes per bin) for fp32 I/O, fp16 complex (4 bytes per
- * bin) for fp16/bf16 I/O; the size returned is exact.  Because the skip term is
- * part of it, a cached spectrum is valid until k OR D changes. */
+ * (N, io): fp32 complex (8 bytes per bin) for fp32 I/O; fp16 complex (4 bytes per
+ * bin) for fp16/bf16 I/O, followed by one 32-bit exponent per head (the power of
+ * two left out of that head's stored values; the H ints rounded up to 16 bytes).
+ * The size returned is exact.  Because the skip term is part of it, a cached
+ * spectrum is valid until k OR D changes. */
 size_t longconv_kspec_bytes(int64_t H, int64_t N, int io);
 
 /* Scratch bytes a call needs (0 on bad args).  `backward` = 0 for longconv_fwd and

@@ -167,6 +167,16 @@ static size_t spec_bytes(const Plan& pl)
     return (pl.engine == ENGINE_MFMA && (pl.order.wave_lg || pl.order.coop_lg)) ? sizeof(__half2) : sizeof(float2);
 }
 static size_t up256(size_t x) { return (x + 255) & ~size_t(255); }
+// the stored spectrum of H heads: the bins, and for fp16 storage a trailer of H per-head exponents (spec_exponent)
+static bool spec_is_f16(const Plan& pl) { return spec_bytes(pl) == sizeof(__half2); }
+static size_t spec_total_bytes(int64_t H, size_t L, const Plan& pl)
+{
+    return (size_t)H * L * spec_bytes(pl) + (spec_is_f16(pl) ? (((size_t)H * sizeof(int) + 15) & ~size_t(15)) : 0);
+}
+static const int* spec_exp_ptr(const float2* kspec, int64_t H, size_t L, const Plan& pl)
+{
+    return spec_is_f16(pl) ? reinterpret_cast<const int*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)H * L) : nullptr;
+}
 
 struct WsLayout {
     size_t kspec, kscratch, hscale, ws1, ws2, wsA, dpart, zbuf, dkpart, ddpart, rowmx, total;
@@ -197,12 +207,12 @@ static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool back
     const size_t L = size_t(1) << pl.log2L;
     const size_t npairs = (size_t)((B + 1) / 2);
     size_t off = 0;
-    w.kspec = off; off += up256((size_t)H * L * spec_bytes(pl));
+    w.kspec = off; off += up256(spec_total_bytes(H, L, pl));
     // pass-A output of k, for the spectrum routes that run pass A as a kernel of its own
     const bool mc = pl.engine == ENGINE_MFMA && (pl.order.wave_lg || pl.order.coop_lg);
     const bool kscr = mc ? (pl.log2R && !pl.fuse_a) : (pl.log2L > VALU_KSPEC_MAX_LOG2);
     w.kscratch = off; if (kscr) off += up256((size_t)H * L * sizeof(float2));
-    w.hscale = off; off += up256((size_t)H * sizeof(float));
+    w.hscale = off; off += up256((size_t)3 * H * sizeof(float));
     w.ws1 = off; if (pl.log2R) off += up256((size_t)H * npairs * L * cw_bytes(pl));
     w.ws2 = off; if (pl.log2R && backward) off += up256((size_t)H * npairs * L * cw_bytes(pl));
     w.wsA = off; if (pl.log2R && backward) off += up256((size_t)H * L * cw_bytes(pl));
@@ -247,7 +257,7 @@ static hipError_t run_kspec(const float* k, const float* D, float2* kspec, float
         // single pass, or pass A taken inside the kernel: it reads k itself and finds the maxima
         // (outer radix 8: eight chunks per head would each scan 512 KB, so the maxima are found once, in front)
         if (!pl.log2R || (pl.fuse_a && pl.log2R < 3)) return coop_kspec(k, nullptr, D, nullptr, kspec, H, N, pl, tb, st);
-        hipError_t e = head_max(k, hscale, H, N, st);
+        hipError_t e = head_stats(k, D, hscale, H, N, st);
         if (e != hipSuccess) return e;
         if (pl.fuse_a) return coop_kspec(k, nullptr, D, hscale, kspec, H, N, pl, tb, st);
         if (pl.log2R) {
@@ -284,9 +294,12 @@ static hipError_t run_conv(const void* in, const float2* kspec, void* out, void*
     else
         e = mfma_conv(in, kspec, out, (__half2*)ws1, conj, fuse_a, pr, pl, tb, st);
     if (e != hipSuccess) return e;
-    if (pl.log2R)
-        e = outer_inv(ws1, out, pr, pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st,
+    if (pl.log2R) {
+        Problem pc = pr;     // pass C gives the output the power of two that the stored spectrum left out
+        pc.spec_exp = spec_exp_ptr(kspec, pr.H, size_t(1) << pl.log2L, pl);
+        e = outer_inv(ws1, out, pc, pl.log2R, pl.log2L2, 1.0f, f16ws, tw, st,
                       fuse_a && coop_conv_chunks(pr, pl, fuse_a) < (1 << pl.log2R));
+    }
     return e;
 }
 
@@ -305,7 +318,7 @@ int longconv_init(void)
 size_t longconv_kspec_bytes(int64_t H, int64_t N, int io)
 {
     if (check_shape(1, H, N, io) != LONGCONV_OK) return 0;
-    return (size_t)H * (size_t)(2 * N) * spec_bytes(make_plan(N, io));
+    return spec_total_bytes(H, (size_t)(2 * N), make_plan(N, io));
 }
 
 size_t longconv_workspace_bytes(int64_t B, int64_t H, int64_t N, int io, int backward)

@@ -154,6 +154,32 @@ __device__ __forceinline__ float head_scale_of(float m)
     return ok ? exp2f(-ceilf(log2f(m))) : 1.f;
 }
 
+// ---------------------------------------------------------------------------------
+// Range of the stored fp16 spectrum.  Head h's stored values are kscale (FFT([k,0]) + D) 2^-e_h with a per-head
+// exponent e_h, kept in a trailer of H ints behind the spectrum (word H * 2N of the buffer); the convolution
+// kernels give 2^e_h back where they pack their output.  Two bounds on the largest stored magnitude come with
+// the row's maximum search: hi = kscale (|k_0 + D| + sum_{n>0} |k_n|) from above, and lo = kscale max(|k_0 + D|,
+// max_{n>0} |k_n|) from below (the largest bin is at least the root mean square of all bins, which is the
+// 2-norm of that row).  A head whose bounds lie inside 2^-9 .. 2^10 keeps e_h = 0 (heads of order one: nothing
+// changes for them); any other head gets the exponent that puts hi into (2^7, 2^8], so its largest bin lies in
+// 2^8 / N .. 2^8, inside fp16's normal range for every supported N.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ int spec_exponent(float hi, float lo)
+{
+    if (!(hi > 0.f) || !(hi < 3.0e38f)) return 0;        // zero, inf or nan heads are left alone
+    if (hi <= 1024.f && lo >= 1.0f / 512.f) return 0;
+    int e = (int)ceilf(log2f(hi)) - 8;
+    return e < -100 ? -100 : (e > 100 ? 100 : e);
+}
+__device__ __forceinline__ int* spec_exp_of(float2* kspec, int64_t H, int64_t L)
+{
+    return reinterpret_cast<int*>(reinterpret_cast<uint32_t*>(kspec) + (size_t)H * (size_t)L);
+}
+__device__ __forceinline__ const int* spec_exp_of(const float2* kspec, int64_t H, int64_t L)
+{
+    return reinterpret_cast<const int*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)H * (size_t)L);
+}
+
 enum Engine { ENGINE_VALU = 0, ENGINE_MFMA = 1 };
 
 // Host-side plan: how 2N is factored and which kernels run.

@@ -584,10 +584,11 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
                     wa[m] = a.u; wb[m] = b.u;
                 }
             }
-            if constexpr (IsBf<IO>::v) {
-                if (__builtin_expect((ea | eb) != 0, 0)) {
+            if (__builtin_expect((ea | eb) != 0, 0)) {      // exponents of the output rows (drain's arguments)
 #pragma unroll
-                    for (int m = 0; m < 4; ++m) { wa[m] = bf2_rescaled(wa[m], ea); wb[m] = bf2_rescaled(wb[m], eb); }
+                for (int m = 0; m < 4; ++m) {
+                    wa[m] = out_rescaled<IsBf<IO>::v>(wa[m], ea);
+                    wb[m] = out_rescaled<IsBf<IO>::v>(wb[m], eb);
                 }
             }
             store_words<4>(out + oa + n, wa);
@@ -687,7 +688,10 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             }
         }
         __syncthreads();
-        drain(it, ea, eb);
+        {   // output rows: the input rows' powers of two back, and the one the head's stored spectrum left out
+            const int es = __builtin_amdgcn_readfirstlane(spec_exp_of(kspec, H, C::L)[it / npairs]);
+            drain(it, ea + es, eb + es);
+        }
         if (more) {
             if constexpr (IsBf<IO>::v) measure();
             stage(0, 0);
@@ -1843,7 +1847,10 @@ coop_kspec_kernel(const __half2* __restrict__ ws, const float* __restrict__ D, c
         __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
-    const float alpha = kscale_over_c / r, beta = D[h] * kscale;
+    // rs: [0, H) the heads' maxima, [H, 2H) and [2H, 3H) the bounds on their largest spectrum bin
+    const int es = spec_exponent(kscale * rs[gridDim.x + h], kscale * rs[2 * gridDim.x + h]);
+    if (k1 == 0 && tid == 0) spec_exp_of(kspec, gridDim.x, Ltot)[h] = es;
+    const float alpha = ldexpf(kscale_over_c / r, -es), beta = ldexpf(D[h] * kscale, -es);
     uint4* out = reinterpret_cast<uint4*>(reinterpret_cast<uint32_t*>(kspec) + (size_t)h * Ltot + (size_t)k1 * C::L);
 #pragma unroll
     for (int gi = 0; gi < C::NG; ++gi)
@@ -1876,7 +1883,7 @@ coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D,
     constexpr int NROW = LR ? RH * C::L : C::L / 2;      // samples of a row
     constexpr int RPA = (C::L / 8) / NT;                 // runs of eight samples per lane
     extern __shared__ uint4 lds4[];
-    __shared__ float mred[C::NW];
+    __shared__ float mred[3][C::NW];
     uint32_t* xb = reinterpret_cast<uint32_t*>(lds4);
     uint4* t1f = lds4 + C::XWORDS / 4;
     uint4* t1i = t1f + C::TC * 4;
@@ -1903,20 +1910,32 @@ coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D,
             v[n1][1] = pad ? make_float4(0.f, 0.f, 0.f, 0.f) : src[1];
         }
     };
-    auto max_run = [&](const float4 (&v)[RH][2], float m) __attribute__((always_inline)) {
+    // a, mp: sum and maximum of the magnitudes with the skip term counted in the lag-0 tap (`first`: v[0][0].x is
+    // k_0), the two bounds on the head's largest spectrum bin (spec_exponent)
+    const float Dh = D[h];
+    float a = 0.f, mp = 0.f;
+    auto max_run = [&](const float4 (&v)[RH][2], float m, bool first) __attribute__((always_inline)) {
 #pragma unroll
         for (int n1 = 0; n1 < RH; ++n1)
 #pragma unroll
-            for (int q = 0; q < 2; ++q)
+            for (int q = 0; q < 2; ++q) {
                 m = fmaxf(m, fmaxf(fmaxf(fabsf(v[n1][q].x), fabsf(v[n1][q].y)), fmaxf(fabsf(v[n1][q].z), fabsf(v[n1][q].w))));
+                const float x0 = fabsf(v[n1][q].x + ((first && n1 == 0 && q == 0) ? Dh : 0.f));
+                a += (x0 + fabsf(v[n1][q].y)) + (fabsf(v[n1][q].z) + fabsf(v[n1][q].w));
+                mp = fmaxf(mp, fmaxf(fmaxf(x0, fabsf(v[n1][q].y)), fmaxf(fabsf(v[n1][q].z), fabsf(v[n1][q].w))));
+            }
         return m;
     };
     auto head_max = [&](float m) __attribute__((always_inline)) {     // over the workgroup; ends behind a barrier
-        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-        if (lane == 0) mred[wave] = m;
+        for (int o = 32; o > 0; o >>= 1) {
+            m = fmaxf(m, __shfl_xor(m, o, 64));
+            mp = fmaxf(mp, __shfl_xor(mp, o, 64));
+            a += __shfl_xor(a, o, 64);
+        }
+        if (lane == 0) { mred[0][wave] = m; mred[1][wave] = a; mred[2][wave] = mp; }
         __syncthreads();
-        m = mred[0];
-        for (int w = 1; w < C::NW; ++w) m = fmaxf(m, mred[w]);
+        m = mred[0][0]; a = mred[1][0]; mp = mred[2][0];
+        for (int w = 1; w < C::NW; ++w) { m = fmaxf(m, mred[0][w]); a += mred[1][w]; mp = fmaxf(mp, mred[2][w]); }
         return m;
     };
     auto put_run = [&](const float4 (&v)[RH][2], int i, float r) __attribute__((always_inline)) {
@@ -1962,7 +1981,7 @@ coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D,
         make_operands();
         float m = 0.f;
 #pragma unroll
-        for (int i = 0; i < RPA; ++i) m = max_run(v[i], m);
+        for (int i = 0; i < RPA; ++i) m = max_run(v[i], m, i == 0 && tid == 0);     // run 0 of lane 0 starts at k_0
         r = head_scale_of(head_max(m));                  // (the barrier also covers the cleared slots)
 #pragma unroll
         for (int i = 0; i < RPA; ++i) put_run(v[i], i, r);
@@ -1977,10 +1996,18 @@ coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D,
             for (int i = tid; i < RH * (C::L / 4); i += NT) {
                 const float4 q = k4[i];
                 m = fmaxf(m, fmaxf(fmaxf(fabsf(q.x), fabsf(q.y)), fmaxf(fabsf(q.z), fabsf(q.w))));
+                const float x0 = fabsf(q.x + (i == 0 ? Dh : 0.f));
+                a += (x0 + fabsf(q.y)) + (fabsf(q.z) + fabsf(q.w));
+                mp = fmaxf(mp, fmaxf(fmaxf(x0, fabsf(q.y)), fmaxf(fabsf(q.z), fabsf(q.w))));
             }
         }
         m = head_max(m);                                 // (the barrier also covers the tables)
         r = head_scale_of(rs ? rs[h] : m);
+        if (rs) {                                        // [H, 2H) and [2H, 3H) of the caller's statistics
+            const unsigned Hh = G >> LR;
+            a = rs[Hh + h];
+            mp = rs[2 * Hh + h];
+        }
         twisted_t1f<LG, LR, NT>(t1f, gtab, k1, tw, tid);
 #pragma unroll
         for (int i0 = 0; i0 < RPA; i0 += 2) {
@@ -1996,7 +2023,9 @@ coop_kspec_rows_kernel(const float* __restrict__ k, const float* __restrict__ D,
 #pragma unroll 1
     for (int gi = 0; gi < C::NG; ++gi) phase1_inplace<LG, 2>(xb, t1f, vt, F1, F2, cF, (gi * C::NW + wave) * 8, lane);
     __syncthreads();
-    const float alpha = kscale_over_c / r, beta = D[h] * kscale;
+    const int es = spec_exponent(kscale * a, kscale * mp);
+    if (k1 == 0 && tid == 0) spec_exp_of(kspec, G >> LR, (int64_t)C::L << LR)[h] = es;
+    const float alpha = ldexpf(kscale_over_c / r, -es), beta = ldexpf(Dh * kscale, -es);
     uint4* out = reinterpret_cast<uint4*>(reinterpret_cast<uint32_t*>(kspec) + (((size_t)h << LR) + k1) * C::L);
 #pragma unroll 1
     for (int gi = 0; gi < C::NG; ++gi)

@@ -382,6 +382,8 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
         // ---------------- phase 2 ----------------
         // spectrum: fp16 complex, four bins per lane and tile in one 16-byte load
         const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const uint32_t*>(kspec) + (size_t)hcur * C::L);
+        // the head's stored spectrum left out 2^es (0 for heads of order one); the output gets it back below
+        const int es = __builtin_amdgcn_readfirstlane(spec_exp_of(kspec, H, C::L)[hcur]);
 #pragma unroll
         for (int tb = 0; tb < C::TC; tb += NT) {
             int ad[NT][4];
@@ -508,18 +510,21 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
                             }
                         }
             }
-            if constexpr (IsBf<IO>::v) {     // a row outside the band gets its power of two back, on the packed values
+            {   // a bf16 row outside the band gets its power of two back, and every row the power that the head's
+                // stored spectrum left out: on the packed values, in a loop of their own
 #pragma unroll
-                for (int q = 0; q < PB; ++q)
-                    if (__builtin_expect((ea[q] | eb[q]) != 0, 0)) {
+                for (int q = 0; q < PB; ++q) {
+                    const int xa = es + (IsBf<IO>::v ? ea[q] : 0), xb_ = es + (IsBf<IO>::v ? eb[q] : 0);
+                    if (__builtin_expect((xa | xb_) != 0, 0)) {
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
 #pragma unroll
                             for (int i = 0; i < C::NWD; ++i) {
-                                oa[q][j][i] = bf2_rescaled(oa[q][j][i], ea[q]);
-                                ob[q][j][i] = bf2_rescaled(ob[q][j][i], eb[q]);
+                                oa[q][j][i] = out_rescaled<IsBf<IO>::v>(oa[q][j][i], xa);
+                                ob[q][j][i] = out_rescaled<IsBf<IO>::v>(ob[q][j][i], xb_);
                             }
                     }
+                }
             }
             if (g < 2) {     // n_a < 8: the first N samples
 #pragma unroll
@@ -1098,6 +1103,8 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
 #pragma unroll
         for (int k = 0; k < TPW; ++k) kk[k].u = ks[(t0 + k) * 64 + lane];
     }
+    // the head's stored spectrum left out 2^es (0 for heads of order one); du gets it back on its packed words
+    const int es = __builtin_amdgcn_readfirstlane(spec_exp_of(kspec, H, C::L)[h]);
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     int ad[TPW][4];
 #pragma unroll
@@ -1191,10 +1198,14 @@ wbwd_kernel(const typename IO::T* __restrict__ dy, const typename IO::T* __restr
                 wa[j] = IsBf<IO>::v ? pack_bf2(r[0][j], r[1][j]) : pack_h2(r[0][j], r[1][j]);
                 wb[j] = IsBf<IO>::v ? pack_bf2(s[0][j], s[1][j]) : pack_h2(s[0][j], s[1][j]);
             }
-            if constexpr (IsBf<IO>::v) {
-                if (__builtin_expect((ps.efa | ps.efb) != 0, 0)) {
+            {
+                const int xa_ = es + (IsBf<IO>::v ? ps.efa : 0), xb_ = es + (IsBf<IO>::v ? ps.efb : 0);
+                if (__builtin_expect((xa_ | xb_) != 0, 0)) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) { wa[j] = bf2_rescaled(wa[j], ps.efa); wb[j] = bf2_rescaled(wb[j], ps.efb); }
+                    for (int j = 0; j < 4; ++j) {
+                        wa[j] = out_rescaled<IsBf<IO>::v>(wa[j], xa_);
+                        wb[j] = out_rescaled<IsBf<IO>::v>(wb[j], xb_);
+                    }
                 }
             }
             if (g < 2) {     // n_a < 8: the first N samples
@@ -1332,8 +1343,9 @@ hipError_t wbwd_io(const void* dy, const void* u, const float2* kspec, void* du,
 // One workgroup (NWP waves) per head.  The row is scaled by a power of two r that brings
 // max|k[h,:]| to about 1, so the fp16 operands keep their relative precision whatever the head's
 // magnitude, and transformed as the real row of a pair whose other row is zero: phase 1 and the
-// forward half of phase 2 of the convolution kernel.  Stored value = kscale * (FFT([k,0]) + D[h]) as
-// fp16 complex (one 32-bit word per bin).
+// forward half of phase 2 of the convolution kernel.  Stored value = kscale * (FFT([k,0]) + D[h]) 2^-e_h as
+// fp16 complex (one 32-bit word per bin), e_h the head's spectrum exponent (0 for heads of order one), which
+// goes into the trailer behind the spectrum.
 // -------------------------------------------------------------------------------------
 template <int LG, int TPW>
 __global__ void __launch_bounds__((WC<LG>::TC / TPW) * 64) __attribute__((amdgpu_waves_per_eu(2)))
@@ -1343,14 +1355,16 @@ wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, float2* 
     using C = WC<LG>;
     constexpr int NWP = C::TC / TPW;
     __shared__ uint32_t xb[C::PAIR_WORDS];
-    __shared__ float wmax[NWP];
+    __shared__ float wmax[3][NWP];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, t0 = wave * TPW;
     const int c = lane & 15, g = lane >> 4;
     const int h = blockIdx.x;
     const float* kr = k + (size_t)h * N;
-    // this wave's samples (fp32), and the head's max |k| over all waves
+    const float Dh = D[h];
+    // this wave's samples (fp32); over all waves the head's max |k| and the two bounds on its largest spectrum
+    // bin (sum and maximum of the magnitudes, the skip term counted with the lag-0 tap; see spec_exponent)
     float v[4][TPW];
-    float m = 0.f;
+    float m = 0.f, a = 0.f, mp = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -1358,15 +1372,25 @@ wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, float2* 
             v[j][i] = 0.f;
             if (g < 2) v[j][i] = kr[(4 * g + j) * 16 * C::TC + c * C::TC + t0 + i];
             m = fmaxf(m, fabsf(v[j][i]));
+            const float x = fabsf(v[j][i] + ((j == 0 && i == 0 && tid == 0) ? Dh : 0.f));     // tid 0 holds k_0
+            a += x;
+            mp = fmaxf(mp, x);
         }
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    for (int o = 32; o > 0; o >>= 1) {
+        m = fmaxf(m, __shfl_xor(m, o, 64));
+        mp = fmaxf(mp, __shfl_xor(mp, o, 64));
+        a += __shfl_xor(a, o, 64);
+    }
     if (NWP > 1) {
-        if (lane == 0) wmax[wave] = m;
+        if (lane == 0) { wmax[0][wave] = m; wmax[1][wave] = a; wmax[2][wave] = mp; }
         __syncthreads();
+        m = wmax[0][0]; a = wmax[1][0]; mp = wmax[2][0];
 #pragma unroll
-        for (int w = 0; w < NWP; ++w) m = fmaxf(m, wmax[w]);
+        for (int w = 1; w < NWP; ++w) { m = fmaxf(m, wmax[0][w]); a += wmax[1][w]; mp = fmaxf(mp, wmax[2][w]); }
     }
     const float r = head_scale_of(m);
+    const int es = spec_exponent(kscale * a, kscale * mp);
+    if (tid == 0) spec_exp_of(kspec, gridDim.x, C::L)[h] = es;
     WK<LG, TPW> K;
     load_consts<LG, TPW>(K, wtab, t0, lane);
     In<TPW> inr;
@@ -1386,7 +1410,7 @@ wkspec_kernel(const float* __restrict__ k, const float* __restrict__ D, float2* 
         for (int j = 0; j < 4; ++j) ad[kk][j] = phase2_addr<LG>(t0 + kk, j, lane);
     f4 yr[TPW], yi[TPW];
     w_phase2_fwd<LG, TPW>(xb, K, ad, yr, yi);
-    const float alpha = kscale_over_c / r, beta = D[h] * kscale;
+    const float alpha = ldexpf(kscale_over_c / r, -es), beta = ldexpf(Dh * kscale, -es);
     uint4* out = reinterpret_cast<uint4*>(reinterpret_cast<uint32_t*>(kspec) + (size_t)h * C::L);
 #pragma unroll
     for (int kk = 0; kk < TPW; ++kk) {

@@ -30,6 +30,9 @@ struct Problem {
     // power of two where the rows are converted (pass A inside the inner kernels) and back in pass C.
     const uint32_t* max_a = nullptr;
     const uint32_t* max_b = nullptr;
+    // convolutions of the multi-pass plans with an fp16 spectrum: the per-head exponents of the stored spectrum
+    // (spec_exponent), which pass C gives back; NULL = none
+    const int* spec_exp = nullptr;
 };
 // mx[h] = bf16 pattern of max |in[b,h,:]| over b (zeroed first); rows of 16-bit floats only
 hipError_t rows_absmax(const void* in, uint32_t* mx, const Problem& pr, hipStream_t st);
@@ -44,8 +47,9 @@ bool conv_applies_gate(const Plan& pl, bool fuse_a);
 hipError_t outer_fwd(const void* in, const void* in2, void* ws, void* ws2, float* dD_part,
                      const Problem& pr, int log2R, int log2L2, float scale, bool ws_f16,
                      const float2* tw, hipStream_t st, const float* head_max = nullptr);
-// mx[h] = max_n |k[h,n]|; consumers derive the head's power-of-two pre-scale with head_scale_of().
-hipError_t head_max(const float* k, float* mx, int64_t H, int64_t N, hipStream_t st);
+// stats[h] = max_n |k[h,n]| (consumers derive the head's power-of-two pre-scale with head_scale_of()),
+// stats[H + h] and stats[2H + h] = the upper and lower bound statistics of spec_exponent(); 3H floats.
+hipError_t head_stats(const float* k, const float* D, float* stats, int64_t H, int64_t N, hipStream_t st);
 int outer_fwd_blocks_per_head(const Problem& pr, int log2L2);
 // Pass C: rows of `out` <- scale * sum_{k1} conj(w_R^(n1*k1) w_L^(n2*k1)) ws[...], n1 < R/2 only
 // (truncation to the first N samples); re -> row 2p, im -> row 2p+1.

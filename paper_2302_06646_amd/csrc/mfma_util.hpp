@@ -122,6 +122,19 @@ __device__ __forceinline__ uint32_t bf2_rescaled(uint32_t w, int e)
 {
     return pack_bf2(ldexpf(__uint_as_float(w << 16), e), ldexpf(__uint_as_float(w & 0xffff0000u), e));
 }
+// word of two fp16 values times 2^e (through fp32: exact unless it leaves fp16's range)
+__device__ __forceinline__ uint32_t h2_rescaled(uint32_t w, int e)
+{
+    union { uint32_t u; h2 h; } cv;
+    cv.u = w;
+    return pack_h2(ldexpf((float)cv.h[0], e), ldexpf((float)cv.h[1], e));
+}
+// packed output word of either half dtype times 2^e
+template <bool BF>
+__device__ __forceinline__ uint32_t out_rescaled(uint32_t w, int e)
+{
+    return BF ? bf2_rescaled(w, e) : h2_rescaled(w, e);
+}
 constexpr int EXP_NONE = -100000;      // "exponent" of something that is exactly zero
 
 // Scales of the two rows (a, b) of the two sources (u pair, dy pair) in the dk kernels.  dk sums

@@ -84,7 +84,7 @@ __global__ void outer_fwd_kernel(const typename IO::T* __restrict__ in, const ty
 template <class IO, class CW, int LOG2R>
 __global__ void outer_inv_kernel(const typename CW::T* __restrict__ ws, typename IO::T* __restrict__ out,
                                  int64_t B, int64_t H, int64_t N, int npairs, int log2L2, float scale,
-                                 const float2* __restrict__ tw, int herm)
+                                 const float2* __restrict__ tw, int herm, const int* __restrict__ spec_exp)
 {
     constexpr int R = 1 << LOG2R, RH = R / 2;
     const int L2 = 1 << log2L2;
@@ -96,6 +96,7 @@ __global__ void outer_inv_kernel(const typename CW::T* __restrict__ ws, typename
     const bool has_b = (2 * p + 1) < B;
     const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
     const size_t base = (size_t)pairidx << log2L;
+    if (spec_exp) scale = ldexpf(scale, spec_exp[h]);      // the stored spectrum's per-head power of two
     float2 v[R];
 #pragma unroll
     for (int k1 = 0; k1 < R; ++k1) {
@@ -188,7 +189,8 @@ __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restric
                                                         const float2* __restrict__ tw, int herm,
                                                         const typename IO::T* __restrict__ gate,
                                                         const uint32_t* __restrict__ max_a,
-                                                        const uint32_t* __restrict__ max_b)
+                                                        const uint32_t* __restrict__ max_b,
+                                                        const int* __restrict__ spec_exp)
 {
     // max_a / max_b != NULL: the rows that went into this head were scaled by powers of two on the way in (bf16
     // rows outside the band); the output gets the product of those powers back
@@ -206,6 +208,7 @@ __global__ void __launch_bounds__(OB) outer_inv4_kernel(const __half2* __restric
     const size_t oa = row_off(2 * p, h, H, N), ob = row_off(has_b ? 2 * p + 1 : 2 * p, h, H, N);
     const __half2* src = ws + ((size_t)pairidx << log2L) + n2;
     if (max_a) scale = ldexpf(scale, mu::row_exponent(max_a[h]) + (max_b ? mu::row_exponent(max_b[h]) : 0));
+    if (spec_exp) scale = ldexpf(scale, spec_exp[h]);      // the stored spectrum's per-head power of two
     float2 w1[VEC], pw[VEC], v[R][VEC];
 #pragma unroll
     for (int j = 0; j < VEC; ++j) w1[j] = tw_full(tw, (uint32_t)(n2 + j) << (TW_LOG2 - log2L));
@@ -290,26 +293,38 @@ __global__ void __launch_bounds__(OB) rows_absmax_kernel(const uint4* __restrict
     }
 }
 
-__global__ void head_max_kernel(const float* __restrict__ k, unsigned* __restrict__ mx, int64_t N)
+// Per head, in one pass over its row and in a fixed order (one workgroup per head): st[h] = max |k_n| (the
+// transform's pre-scale), st[H + h] = |k_0 + D| + sum_{n>0} |k_n| and st[2H + h] = max(|k_0 + D|, max_{n>0} |k_n|)
+// (the two bounds on the largest spectrum bin, see spec_exponent).
+__global__ void __launch_bounds__(OB) head_stats_kernel(const float* __restrict__ k, const float* __restrict__ D,
+                                                        float* __restrict__ st, int64_t H, int64_t N)
 {
-    __shared__ float red[4];
-    const float4* kr = reinterpret_cast<const float4*>(k + (size_t)blockIdx.y * N) + (size_t)blockIdx.x * 1024;
-    float m = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const size_t idx = threadIdx.x + 256 * i;
-        if (((size_t)blockIdx.x * 1024 + idx) * 4 < (size_t)N) {
-            const float4 v = kr[idx];
-            m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-        }
+    __shared__ float red[3][OB / 64];
+    const int64_t h = blockIdx.x;
+    const float4* kr = reinterpret_cast<const float4*>(k + (size_t)h * N);
+    const float Dh = D[h];
+    float m = 0.f, a = 0.f, mp = 0.f;
+    for (int64_t i = threadIdx.x; i < N / 4; i += OB) {
+        const float4 v = kr[i];
+        const float x0 = fabsf(v.x + (i == 0 ? Dh : 0.f));
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        mp = fmaxf(mp, fmaxf(fmaxf(x0, fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        a += (x0 + fabsf(v.y)) + (fabsf(v.z) + fabsf(v.w));
     }
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_down(m, o, 64));
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    for (int o = 32; o > 0; o >>= 1) {
+        m = fmaxf(m, __shfl_down(m, o, 64));
+        mp = fmaxf(mp, __shfl_down(mp, o, 64));
+        a += __shfl_down(a, o, 64);
+    }
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = m; red[1][threadIdx.x >> 6] = a; red[2][threadIdx.x >> 6] = mp; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        m = red[0][0]; a = red[1][0]; mp = red[2][0];
+        for (int w = 1; w < OB / 64; ++w) { m = fmaxf(m, red[0][w]); a += red[1][w]; mp = fmaxf(mp, red[2][w]); }
         if (!(m == m)) m = __uint_as_float(0x7f800000u);   // a NaN in the head: treat as unscalable
-        atomicMax(&mx[blockIdx.y], __float_as_uint(m));
+        st[h] = m;
+        st[H + h] = a;
+        st[2 * H + h] = mp;
     }
 }
 
@@ -400,7 +415,7 @@ hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, 
             dim3 grid4((unsigned)(((size_t)1 << log2L2) / (VEC * OB) * (size_t)pr.npairs * (size_t)pr.H));
             hipLaunchKernelGGL((outer_inv4_kernel<IO, LOG2R>), grid4, dim3(OB), 0, st, (const __half2*)ws, (T*)out,
                                pr.B, pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm, (const T*)pr.gate, pr.max_a,
-                               pr.max_b);
+                               pr.max_b, pr.spec_exp);
             return hipGetLastError();
         }
     }
@@ -408,7 +423,7 @@ hipError_t inv_launch(const void* ws, void* out, const Problem& pr, int log2L2, 
     if (pr.gate || pr.max_a || pr.max_b) return hipErrorInvalidValue;
     dim3 grid((unsigned)(((size_t)1 << log2L2) / OB * (size_t)pr.npairs * (size_t)pr.H));
     hipLaunchKernelGGL((outer_inv_kernel<IO, CW, LOG2R>), grid, dim3(OB), 0, st, (const C*)ws, (T*)out, pr.B,
-                       pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm);
+                       pr.H, pr.N, pr.npairs, log2L2, scale, tw, herm, pr.spec_exp);
     return hipGetLastError();
 }
 
@@ -478,11 +493,9 @@ hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, in
 #undef GO
 }
 
-hipError_t head_max(const float* k, float* mx, int64_t H, int64_t N, hipStream_t st)
+hipError_t head_stats(const float* k, const float* D, float* stats, int64_t H, int64_t N, hipStream_t st)
 {
-    hipLaunchKernelGGL(head_max_zero_kernel, dim3((unsigned)((H + 255) / 256)), dim3(256), 0, st, (unsigned*)mx, H);
-    hipLaunchKernelGGL(head_max_kernel, dim3((unsigned)((N + 4095) / 4096), (unsigned)H), dim3(256), 0, st, k,
-                       (unsigned*)mx, N);
+    hipLaunchKernelGGL(head_stats_kernel, dim3((unsigned)H), dim3(OB), 0, st, k, D, stats, H, N);
     return hipGetLastError();
 }
 

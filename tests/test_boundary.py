@@ -44,11 +44,13 @@ def test_sizes_and_plan():
 
 
 def test_spectrum_size_is_exact_per_dtype():
-    # fp32 I/O stores fp32 complex bins, half I/O fp16 complex bins (matrix-core kernels)
+    # fp32 I/O stores fp32 complex bins, half I/O fp16 complex bins (matrix-core kernels) and, behind them, one
+    # 32-bit exponent per head (the power of two left out of that head's stored values), rounded up to 16 bytes
     assert lc.longconv_kspec_bytes(3, 2048, lc.F32) == 3 * 4096 * 8
     for io in (lc.F16, lc.BF16):
         for N in (256, 1024, 16384, 65536):
-            assert lc.longconv_kspec_bytes(3, N, io) == 3 * 2 * N * 4
+            assert lc.longconv_kspec_bytes(3, N, io) == 3 * 2 * N * 4 + 16
+        assert lc.longconv_kspec_bytes(8, 1024, io) == 8 * 2048 * 4 + 32
 
 
 def test_options_switch_plans_and_reject_bad_input():

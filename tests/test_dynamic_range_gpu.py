@@ -12,15 +12,16 @@ from gpu_harness import check_full
 pytestmark = pytest.mark.gpu
 
 
-def scaled_inputs(N, B, H, u_scale, dy_scale, k_scale=None, D_scale=None, seed=0):
-    """Workload-2 style bf16 inputs; row (b,h) of u is multiplied by u_scale[b,h] (broadcast), likewise dy; head h
-    of k by k_scale[h] and D[h] by D_scale[h]; u and dy are rounded to bf16 again afterwards."""
-    w = wl.Workload(2, B, H, N, wl.BF16, "squash_pool")
+def scaled_inputs(N, B, H, u_scale, dy_scale, k_scale=None, D_scale=None, seed=0, dtype=wl.BF16):
+    """Workload-2 style inputs (bf16 unless said otherwise); row (b,h) of u is multiplied by u_scale[b,h]
+    (broadcast), likewise dy; head h of k by k_scale[h] and D[h] by D_scale[h]; u and dy are rounded to the I/O
+    dtype again afterwards."""
+    w = wl.Workload(2, B, H, N, dtype, "squash_pool")
     inp = wl.generate(w, seed_extra=seed)
     us = np.broadcast_to(np.asarray(u_scale, dtype=np.float64), (B, H))[:, :, None]
     ds = np.broadcast_to(np.asarray(dy_scale, dtype=np.float64), (B, H))[:, :, None]
-    u_s, u_v = wl.quantize((inp.u * us).astype(np.float32), wl.BF16)
-    dy_s, dy_v = wl.quantize((inp.dy * ds).astype(np.float32), wl.BF16)
+    u_s, u_v = wl.quantize((inp.u * us).astype(np.float32), dtype)
+    dy_s, dy_v = wl.quantize((inp.dy * ds).astype(np.float32), dtype)
     k, D = inp.k, inp.D
     if k_scale is not None:
         k = (k.astype(np.float64) * np.asarray(k_scale, dtype=np.float64)[:, None]).astype(np.float32)
@@ -59,3 +60,29 @@ def test_multi_pass_lengths_scale_per_head(N):
     us = np.array([[1e-6, 3e4]])
     ds = np.array([[2e-9, 1.0]])
     check_full(scaled_inputs(N, 2, 2, us, ds, seed=2), label=f"heads at different magnitudes, N={N}")
+
+
+# The stored spectrum is fp16: a head whose spectrum lies outside fp16's comfortable range is stored with a power of
+# two taken out, which the convolution kernels give back where they pack their output.  One wave length, the
+# cooperative lengths and two multi-pass lengths; every row of every head to the bound of data of order one.
+@pytest.mark.parametrize("N", [256, 1024, 4096, 16384, 65536, 131072])
+def test_kernels_of_any_magnitude_bf16(N):
+    B = 3 if N <= 16384 else 2
+    ks = np.array([2.0 ** -20, 2.0 ** 20, 1.0, 2.0 ** -30, 2.0 ** 12, 1e-3, 3e4])
+    Ds = np.array([2.0 ** -20, 2.0 ** 20, 1.0, 1.0, 2.0 ** -5, 1e3, 3e-4])      # skip term with, above and below the kernel
+    H = len(ks) if N <= 16384 else 4
+    check_full(scaled_inputs(N, B, H, 1.0, 1.0, k_scale=ks[:H], D_scale=Ds[:H], seed=3), label=f"kernel magnitudes, N={N}")
+
+
+@pytest.mark.parametrize("N", [512, 8192, 32768])
+def test_kernels_of_other_magnitudes_fp16(N):
+    # fp16 rows and outputs have to stay inside fp16's own range: heads at 2^-9 and 2^9 with rows of order one
+    ks = np.array([2.0 ** -9, 2.0 ** 9, 1.0, 2.0 ** -6])
+    check_full(scaled_inputs(N, 3, 4, 1.0, 1.0, k_scale=ks, D_scale=ks, seed=4, dtype=wl.F16), label=f"kernel magnitudes fp16, N={N}")
+
+
+def test_kernel_magnitude_with_rows_out_of_band():
+    # both rescalings at once on a single-pass plan: tiny gradients, large activations and kernels far from one
+    ks = np.array([2.0 ** -18, 2.0 ** 15, 1.0])
+    check_full(scaled_inputs(2048, 4, 3, 1e3, 1e-5, k_scale=ks, D_scale=ks, seed=5), label="rows and kernels out of range, N=2048")
+    check_full(scaled_inputs(16384, 3, 3, 1e3, 1e-5, k_scale=ks, D_scale=ks, seed=6), label="rows and kernels out of range, N=16384")

@@ -53,9 +53,8 @@ def test_longest_sequence_half_io(io):
 @pytest.mark.parametrize("key,B,H", [("2", 4, 4), ("3", 2, 4), ("4a", 2, 4)])
 def test_kernel_magnitudes_per_head(key, B, H):
     """Heads of different magnitude in one call, checked head by head (a whole-tensor norm would hide a
-    small head behind a large one), and an all-zero head with D = 0, which must give exact zeros.  The
-    range is what the fp16 intermediates of the matrix-core engine carry without rescaling the data:
-    |FFT(k) + D| within about 2^-8 .. 2^8 for inputs of order one."""
+    small head behind a large one), and an all-zero head with D = 0, which must give exact zeros.  (Heads
+    much further from one: tests/test_dynamic_range_gpu.py.)"""
     from gpu_harness import GpuRun, TOL
     import oracle
     inp = wl.generate(wl.WORKLOADS[key], B=B, H=H)
