@@ -305,8 +305,8 @@ __device__ __forceinline__ void phase3_two(const uint32_t* xb, const uint4* gtab
 // slot phase 1 fills with output (k_a, k_b) = (d_b, d_a) of tile t, and phase 3 the other way round,
 // each lane reading and writing only its own 16 bytes.  Slots of the zero padding (d_a >= 8) are
 // cleared at the start and again by phase 3.  The next pair's runs are fetched into registers
-// before phase 3 and stored to LDS by the lane that has just drained the same slots, so global
-// latency is covered by phase 3 and no phase but the second (spectrum) issues global loads:
+// before phase 1 and stored to LDS by the lane that has just drained the same slots, so global
+// latency is covered by the three phases and no phase but the second (spectrum) issues global loads:
 // the w_L twiddle of phases 1 and 3 is the product of a per-lane constant w_256^(k_a d_b) and an
 // LDS table w_L^(k_a t).
 // -------------------------------------------------------------------------------------
@@ -627,6 +627,11 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             }
         }
 
+        // the next pair's runs start travelling now: they have phases 1 to 3 to land (issued in front of phase 3
+        // only, they arrive in a burst from all compute units at once and part of the transfer is exposed)
+        const bool more = it + 1 < it1;
+        if (more) fetch(it + 1);
+
         // ---- phase 1, in place
 #pragma unroll 1
         for (int gi = 0; gi < ng; ++gi)
@@ -665,9 +670,6 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
-
-        const bool more = it + 1 < it1;
-        if (more) fetch(it + 1);
 
         // ---- phase 3, in place: word = (row a sample, row b sample); padding slots cleared
 #pragma unroll 1
