@@ -42,11 +42,27 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 matrix-core peak, published
 CACHE_BYTES = 256 << 20        # last-level (Infinity) cache
 KIB = 1024
-# HBM bytes per launch of the dominant kernel group, measured OFFLINE with `rocprofv3 --pmc FETCH_SIZE` and
-# `--pmc WRITE_SIZE` (KiB per dispatch, scaled by what the same counters read for a plain copy of known size:
-# FETCH_SIZE x 2.0, WRITE_SIZE x 1.0) and copied here from the summaries under profiles/; null where no such
-# run covers the group.  Not measured by this script.
-OFFLINE_TRAFFIC = {}
+# HBM bytes per launch of each kernel group, measured OFFLINE with `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
+# (KiB per dispatch, scaled by what the same counters read for a plain copy of known size: FETCH_SIZE x 2.0,
+# WRITE_SIZE x 1.0): read from the text summary of those runs under profiles/ (columns: workload, group, bytes,
+# kernels); null where the file or the group is missing.  Not measured by this script.
+TRAFFIC_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_per_launch_group.txt")
+
+
+def load_offline_traffic():
+    table = {}
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                p = line.split()
+                if len(p) >= 3 and not line.startswith("#"):
+                    table.setdefault(p[0], {})[p[1]] = float(p[2])
+    except OSError:
+        pass
+    return table
+
+
+OFFLINE_TRAFFIC = load_offline_traffic()
 
 
 def log(*a):
@@ -213,7 +229,8 @@ def run_workload(key, steps, warmup, lc, torch):
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": segments[dom]["GBps"], "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": segments[dom]["GBps"] / HBM_PEAK_GBS,
                      "traffic": OFFLINE_TRAFFIC.get(w.name, {}).get(dom),
-                     "traffic_source": "offline rocprofv3 --pmc runs, see profiles/" if OFFLINE_TRAFFIC.get(w.name, {}).get(dom) else None,
+                     "traffic_source": ("offline rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, profiles/hbm_traffic_per_launch_group.txt"
+                                        if OFFLINE_TRAFFIC.get(w.name, {}).get(dom) else None),
                      "algorithmic_bytes_per_launch": gb[dom],
                      "avg_launch_ms": segments[dom]["ms_mean"]},
     }
