@@ -121,3 +121,24 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(lc, "LIB_PATH", "/nonexistent/liblongconv.so")
     with pytest.raises(lc.LongconvError):
         lc.lib()
+
+
+def test_bench_reads_the_offline_traffic_table():
+    # roofline.traffic of bench.py comes from the text table written with the rocprofv3 summaries under profiles/:
+    # every launch group of the three profiled workloads has a figure, and it is not below the algorithmic bytes
+    import importlib.util
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    import workloads as wl
+    table = bench.load_offline_traffic()
+    for key in ("2", "3", "4a"):
+        w = wl.WORKLOADS[key]
+        groups = bench.group_bytes(w)
+        assert w.name in table
+        for grp, measured in table[w.name].items():      # the groups this workload's plan launches
+            assert grp in groups, (w.name, grp)
+            assert measured >= 0.95 * groups[grp]
+        assert "fwd" in table[w.name] and ("bwd" in table[w.name] or "bwd_dk" in table[w.name])
