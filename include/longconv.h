@@ -33,14 +33,16 @@
  *   - Return value: LONGCONV_OK or an error code; argument validation happens
  *     before anything is launched.  No exceptions, no aborts.
  *   - fp16/bf16 I/O computes with fp16 matrix-core operands and fp32 accumulation.
- *     bf16 rows (u, dy) may have any magnitude: rows whose largest sample lies outside
- *     2^-2 .. 2^4 are multiplied by a power of two on their way into the transform and by
- *     its inverse on the way out, so gradients of order 1e-10 or activations of order 1e6
- *     keep the accuracy of data of order one.  Up to N = 16384 this is done row by row (two
- *     rows inside that band share one fp16 scale: their error is relative to the larger of
- *     the two); from N = 32768 on all rows of a head share one power of two, found by a
- *     pass over the tensor in front, so rows of one head that differ by many orders of
- *     magnitude lose the small ones.  The kernel k and the skip term D may have any
+ *     bf16 rows (u, dy) may have any magnitude: rows are multiplied by a power of two on
+ *     their way into the transform and by its inverse on the way out where they need it, so
+ *     gradients of order 1e-10 or activations of order 1e6 keep the accuracy of data of
+ *     order one.  Up to N = 16384 this is decided pair by pair (two batch rows of a head
+ *     share one complex transform): a pair whose rows both have their largest sample in
+ *     2^-2 .. 2^4 and within a factor of four of each other runs unscaled, in any other pair
+ *     every row is scaled on its own, so every row meets the bound of data of order one
+ *     whatever its neighbour's size.  From N = 32768 on all rows of a head share one power of
+ *     two, found by a pass over the tensor in front, so rows of one head that differ by many
+ *     orders of magnitude lose the small ones.  The kernel k and the skip term D may have any
  *     magnitude as well: a head is scaled by a power of two on its way into the spectrum's
  *     transform, and a head whose spectrum lies outside fp16's comfortable range is stored
  *     with a further power of two taken out, which the convolutions give back where they

@@ -498,11 +498,11 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
             if (!has_b) pb[i] = make_uint4(0u, 0u, 0u, 0u);
         }
     };
-    // bf16 rows outside the band 2^-2 .. 2^4 are scaled by a power of two on the way in and back on the way out.
-    // The pair is staged unscaled first; every wave publishes the band test of the words it fetched (two patterns
-    // and a flag byte), and after the barrier that makes the staged pair visible one LDS read tells all waves
-    // whether any of them saw a row outside the band.  Only then the maxima are combined and the pair is staged
-    // again from the registers, with its scales.
+    // bf16 rows of a pair that are not both of order one (see band_or_exact, pair_exponents) are scaled by powers
+    // of two on the way in and back on the way out.  The pair is staged unscaled first; every wave publishes the
+    // band test of the words it fetched (two patterns and a flag byte), and after the barrier that makes the staged
+    // pair visible one LDS read tells all waves whether any of them saw a row outside the band.  Only then the
+    // maxima are combined and, if the pair needs it, staged again from the registers, with its scales.
     __shared__ uint32_t dr_mx[2 * NWV + 2];          // [NWV][2] patterns, then NWV flag bytes
     auto measure = [&]() {
         uint32_t m[2] = {0u, 0u};
@@ -619,7 +619,7 @@ coop_conv_real_kernel(const typename IO::T* __restrict__ in, const float2* __res
                 for (int w = 0; w < NWV; ++w) { ma = max(ma, dr_mx[2 * w]); mb = max(mb, dr_mx[2 * w + 1]); }
                 ma = (uint32_t)__builtin_amdgcn_readfirstlane((int)ma);
                 mb = (uint32_t)__builtin_amdgcn_readfirstlane((int)mb);
-                if (!rows_in_band(ma, mb)) { ea = row_exponent(ma); eb = row_exponent(mb); }
+                if (!rows_in_band(ma, mb)) pair_exponents(ma, mb, ea, eb);
                 if ((ea | eb) != 0) {
                     stage(ea, eb);
                     __syncthreads();
@@ -1179,7 +1179,7 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                          :: "s"(lds_off), "v"(lane * 16), "s"(sbase) : "memory", "m0");
         }
     };
-    // bf16 rows outside the band 2^-2 .. 2^4 are scaled by powers of two (see pair_scales): every source is staged
+    // bf16 rows that are not all of order one are scaled by powers of two (see pair_scales): every source is staged
     // unscaled first while each wave runs the band test on the words it stages (two patterns and a flag byte
     // into dr_mx); after the barrier that makes the staged source visible one LDS read tells all waves whether
     // any of them saw a row outside the band, and only then the source is staged again, with its scales, from
@@ -1330,7 +1330,7 @@ coop_dk_real_kernel(const typename IO::T* __restrict__ dy, const typename IO::T*
                     int ea = 0, eb = 0;
                     if (pass == 0) {                     // u rows: normalised one by one
                         staged_patterns(mua, mub);
-                        if (__builtin_expect(!rows_in_band(mua, mub), 0)) { ea = row_exponent(mua); eb = row_exponent(mub); }
+                        if (__builtin_expect(!rows_in_band(mua, mub), 0)) pair_exponents(mua, mub, ea, eb);
                     } else {                             // dy rows: what is left of the pair's common exponent
                         uint32_t mda, mdb;
                         staged_patterns(mda, mdb);

@@ -362,7 +362,7 @@ wconv_kernel(const typename IO::T* __restrict__ in, const float2* __restrict__ k
             for (int q = 0; q < PB; ++q) {
                 uint32_t m2[2] = {ma[q], mb[q]};
                 band_or_exact<2>(m2);
-                if (__builtin_expect(!rows_in_band(m2[0], m2[1]), 0)) { ea[q] = row_exponent(m2[0]); eb[q] = row_exponent(m2[1]); }
+                if (__builtin_expect(!rows_in_band(m2[0], m2[1]), 0)) pair_exponents(m2[0], m2[1], ea[q], eb[q]);
             }
         }
 

@@ -42,11 +42,12 @@ __device__ __forceinline__ uint32_t bf2_to_h2(uint32_t w)
 // ---------------------------------------------------------------------------------
 // Dynamic range of bf16 rows.  The transforms carry fp16 between their stages, and bf16 data (gradients of
 // order 1e-6, activations of order 1e4) need not fit fp16's exponent range; the two rows that share a complex
-// transform may also differ by many orders of magnitude, and the smaller one would drown in the rounding of
-// the larger.  Every row whose largest magnitude lies outside 2^-2 .. 2^4 is therefore brought to the magnitude
-// of unit-variance data by a power of two on its way into the first stage and taken back on the way out (exact in both
-// directions); rows inside that band are not touched, and a pair of such rows runs the instruction stream
-// without any scaling.
+// transform may also differ in magnitude, and the rounding of the larger one is an error of the smaller one.
+// The unit of decision is the pair: if the largest samples of both rows lie in 2 .. 8 (where those of
+// unit-variance rows lie), or, measured exactly, in 2^-2 .. 2^4 and within a factor of four of each other,
+// nothing is scaled and the pair runs the plain instruction stream; otherwise every row of the pair is brought
+// to a largest sample in [2, 4) by a power of two on its way into the first stage and taken back on the way out
+// (exact in both directions).
 // ---------------------------------------------------------------------------------
 // Running maximum of |x| over words of two 16-bit floats.  bf16 and fp16 are both sign-magnitude, so the
 // larger magnitude has the larger low 15 bits whichever way the bits are read: the comparison runs as a
@@ -71,27 +72,31 @@ __device__ __forceinline__ uint32_t absmax_wave(uint32_t acc)
     return max(max(r0, r1), max(r2, r3));
 }
 // The band test without the reduction.  m[] = running maxima (two 16-bit patterns per word) of NR rows over the
-// words this wave holds.  If no sample is at or above 2^4 and some lane holds, in the odd samples of every row,
-// a value at or above 2^-2, the wave's part of all rows lies inside the band and the lower band edge stands in
-// for the maxima (a handful of compares: the usual case; the test for "large enough" is sufficient, not
-// necessary, and a row that fails it is merely measured exactly).  Otherwise m[] becomes the exact maxima of
-// the wave's words.  Maxima of several waves combine by max: an exact value outside the band wins over the
-// stand-in exactly when the row's true maximum is outside the band.
-constexpr uint32_t BAND_LOW = 0x3E80u, BAND_HIGH = 0x4180u;      // bf16 patterns of 2^-2 and 2^4
+// words this wave holds.  If no sample is at or above 8 and every row has, in some lane, a sample at or above 2,
+// the wave's part of all rows lies inside 2 .. 8 as far as this wave can see and the lower edge stands in for
+// the maxima (a few compares and one ballot per row: the usual case; the test is sufficient, not necessary, and
+// rows that fail it are merely measured exactly).  Otherwise m[] becomes the exact maxima of the wave's words.
+// Maxima of several waves combine by max: the result is the stand-in exactly when every wave published it;
+// otherwise it is a largest sample that some wave measured, which lies within a factor of four of the row's true
+// largest sample whenever another wave's stand-in (true value in 2 .. 8) was the larger.
+constexpr uint32_t BAND_LOW = 0x4000u, BAND_HIGH = 0x4100u;      // bf16 patterns of 2 and 8
 template <int NR>
 __device__ __forceinline__ void band_or_exact(uint32_t (&m)[NR])
 {
     typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-    union { uint32_t u; us2 v; } hi, lo, x;
-    hi.u = lo.u = m[0];
+    union { uint32_t u; us2 v; } hi, x;
+    hi.u = m[0];
 #pragma unroll
     for (int r = 1; r < NR; ++r) {
         x.u = m[r];
         hi.v = __builtin_elementwise_max(hi.v, x.v);
-        lo.v = __builtin_elementwise_min(lo.v, x.v);
     }
     const bool big = __builtin_amdgcn_ballot_w64(hi.u >= (BAND_HIGH << 16) || (hi.u & 0xffffu) >= BAND_HIGH) != 0;
-    const bool large_enough = __builtin_amdgcn_ballot_w64(lo.u >= (BAND_LOW << 16)) != 0;
+    bool large_enough = true;
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+        large_enough = large_enough &&
+                       __builtin_amdgcn_ballot_w64(m[r] >= (BAND_LOW << 16) || (m[r] & 0xffffu) >= BAND_LOW) != 0;
     if (__builtin_expect(big || !large_enough, 0)) {
 #pragma unroll
         for (int r = 0; r < NR; ++r) m[r] = absmax_wave(m[r]);
@@ -100,17 +105,29 @@ __device__ __forceinline__ void band_or_exact(uint32_t (&m)[NR])
         for (int r = 0; r < NR; ++r) m[r] = BAND_LOW;
     }
 }
-// after the maxima of all waves holding the row were combined: is the row inside the band?  (Waves publish
-// either the stand-in or an exact value outside the band, so the combined value is the stand-in exactly then.)
+// after the maxima of all waves holding the rows were combined: did every wave publish the stand-in for both?
 __device__ __forceinline__ bool rows_in_band(uint32_t ma, uint32_t mb) { return ((ma ^ BAND_LOW) | (mb ^ BAND_LOW)) == 0u; }
 // Exponent e of the power of two 2^-e that brings a row whose largest bf16 magnitude pattern is m into
-// [2, 4), where the largest sample of a unit-variance row lies; 0 (no scaling) inside the band
-// 2^-2 <= max < 2^4 and for an all-zero row.
+// [2, 4); 0 for an all-zero row.
+__device__ __forceinline__ int tight_exponent(uint32_t m) { return m ? (int)(m >> 7) - 128 : 0; }
+// The same, but 0 (no scaling) inside 2^-2 <= max < 2^4: the per-head scales of the multi-pass plans, where
+// all rows of a head share one power of two.
 __device__ __forceinline__ int row_exponent(uint32_t m)
 {
     const int E = (int)(m >> 7);                     // biased exponent of the largest magnitude
     if (m == 0u || (E >= 125 && E <= 130)) return 0;
     return E - 128;
+}
+// Exponents of the two rows of one pair (patterns measured, or the stand-in): none if both largest samples lie in
+// 2^-2 .. 2^4 and within a factor of four of each other (an all-zero row goes with anything), else each row's own.
+__device__ __forceinline__ void pair_exponents(uint32_t ma, uint32_t mb, int& ea, int& eb)
+{
+    const int Ea = (int)(ma >> 7), Eb = (int)(mb >> 7);
+    const bool oka = ma == 0u || (Ea >= 125 && Ea <= 130), okb = mb == 0u || (Eb >= 125 && Eb <= 130);
+    const bool close_by = ma == 0u || mb == 0u || (Ea - Eb <= 1 && Eb - Ea <= 1);
+    if (oka && okb && close_by) { ea = 0; eb = 0; return; }
+    ea = tight_exponent(ma);
+    eb = tight_exponent(mb);
 }
 // word of two bf16 values of one row -> two fp16 values times 2^-e
 __device__ __forceinline__ uint32_t bf2_to_h2_scaled(uint32_t w, int e)
@@ -139,10 +156,11 @@ constexpr int EXP_NONE = -100000;      // "exponent" of something that is exactl
 
 // Scales of the two rows (a, b) of the two sources (u pair, dy pair) in the dk kernels.  dk sums
 // corr(u_a, dy_a) and corr(u_b, dy_b) out of one complex product, so both terms must carry the same power of
-// two: the rows of the source transformed first are normalised one by one (for dy that is what du needs), the
-// rows of the other source take what is left of the common exponent ep, the larger of the two rows' exponent
-// sums.  The term with the smaller sum arrives smaller than one by the difference, which is all the precision
-// it has in the sum anyway.
+// two: the rows of the source transformed first take the exponents of their own pair (for dy that is what du
+// needs), the rows of the other source take what is left of the common exponent ep, the larger of the two
+// rows' exponent sums: the row of the larger term arrives with its own exponent, the other one smaller than
+// that by the difference of the terms, which is all the precision it has in the sum anyway (and never larger:
+// a row of a negligible term brought up to order one would put its rounding on the term that counts).
 struct PairScales {
     int efa, efb;      // first source: its rows are multiplied by 2^-efa, 2^-efb
     int xa, xb;        // second source: multiplied by 2^-xa, 2^-xb
@@ -151,10 +169,11 @@ struct PairScales {
 __device__ __forceinline__ PairScales pair_scales(uint32_t mfa, uint32_t mfb, uint32_t msa, uint32_t msb)
 {
     PairScales p;
-    p.efa = row_exponent(mfa);
-    p.efb = row_exponent(mfb);
-    const int pa = (mfa && msa) ? p.efa + row_exponent(msa) : EXP_NONE;
-    const int pb = (mfb && msb) ? p.efb + row_exponent(msb) : EXP_NONE;
+    pair_exponents(mfa, mfb, p.efa, p.efb);
+    int sa, sb;
+    pair_exponents(msa, msb, sa, sb);
+    const int pa = (mfa && msa) ? p.efa + sa : EXP_NONE;
+    const int pb = (mfb && msb) ? p.efb + sb : EXP_NONE;
     p.ep = pa > pb ? pa : pb;
     const int ec = p.ep == EXP_NONE ? 0 : p.ep;
     p.xa = ec - p.efa;

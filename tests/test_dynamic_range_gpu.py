@@ -42,8 +42,6 @@ def test_tiny_gradients_and_large_activations(N):
 @pytest.mark.parametrize("N", LENGTHS)
 def test_rows_of_one_head_at_very_different_magnitudes(N):
     B, H = 6, 2
-    # every row either of order one or at least a factor 100 away from it (rows that differ by less than the
-    # width of the unscaled band, 2^6, share one fp16 scale inside a pair: their error is relative to the larger)
     rng = np.random.default_rng(7 + N)
     us = 10.0 ** (rng.choice([-1, 1], size=(B, H)) * rng.uniform(2, 8, size=(B, H)))
     ds = 10.0 ** np.where(rng.random((B, H)) < 0.7, rng.uniform(-12, -3, size=(B, H)), rng.uniform(2, 4, size=(B, H)))
@@ -86,3 +84,18 @@ def test_kernel_magnitude_with_rows_out_of_band():
     ks = np.array([2.0 ** -18, 2.0 ** 15, 1.0])
     check_full(scaled_inputs(2048, 4, 3, 1e3, 1e-5, k_scale=ks, D_scale=ks, seed=5), label="rows and kernels out of range, N=2048")
     check_full(scaled_inputs(16384, 3, 3, 1e3, 1e-5, k_scale=ks, D_scale=ks, seed=6), label="rows and kernels out of range, N=16384")
+
+
+@pytest.mark.parametrize("N", [256, 1024, 2048, 8192, 16384])
+def test_rows_of_a_pair_a_few_times_apart(N):
+    # the two rows of a pair share one complex transform, so the rounding of the larger is an error of the smaller:
+    # rows that differ by a factor of four and more have to be scaled one by one even when both are of "ordinary"
+    # size, and a row of ordinary size next to one that needs scaling anyway is scaled with it
+    B, H = 8, 3
+    us = np.ones((B, H)); ds = np.ones((B, H))
+    us[0:2, 0] = [0.1, 1.0]; us[2:4, 0] = [3.5, 0.09]; us[4:6, 0] = [0.3, 1e4]; us[6:8, 0] = [0.26, 3.9]
+    ds[0:2, 0] = [1.0, 0.08]; ds[2:4, 0] = [0.3, 3e-6]; ds[4:6, 0] = [2.0, 0.5]; ds[6:8, 0] = [0.07, 0.9]
+    rng = np.random.default_rng(11 + N)
+    us[:, 1] = 10.0 ** rng.uniform(-1.2, 1.2, size=B); ds[:, 1] = 10.0 ** rng.uniform(-1.2, 1.2, size=B)
+    us[:, 2] = 10.0 ** rng.uniform(-6, 6, size=B); ds[:, 2] = 10.0 ** rng.uniform(-9, 3, size=B)
+    check_full(scaled_inputs(N, B, H, us, ds, seed=7), label=f"rows a few times apart, N={N}")
