@@ -48,8 +48,10 @@
  *     with a further power of two taken out, which the convolutions give back where they
  *     pack their output (heads of order one take neither path).  Not rescaled, and therefore
  *     to be kept inside fp16's normal range by the caller: fp16 rows (order one is fine up
- *     to N = 131072; the transform grows them by at most sqrt(2N)), and of course the outputs
- *     have to fit the I/O dtype.  fp32 I/O computes in fp32.
+ *     to N = 131072; the transform grows them by at most sqrt(2N); batch rows 2p and 2p+1
+ *     of a head share one complex transform, so the error of an fp16 row is relative to the
+ *     larger of the two: rows of similar size, as a normalised layer produces them, meet the
+ *     bound), and of course the outputs have to fit the I/O dtype.  fp32 I/O computes in fp32.
  */
 #ifndef LONGCONV_H
 #define LONGCONV_H
