@@ -32,6 +32,25 @@ def test_every_block_size_gives_the_convolution(N, log2r):
     _compare({"y": to_f64(y, wl.F16)}, {"y": ref}, TOL[wl.F16], f"block size {1 << log2r} N={N}")
 
 
+@pytest.mark.parametrize("log2r,N,B,H", [(6, 4096, 1, 1), (6, 1024, 3, 2), (6, 1024, 17, 5), (8, 4096, 1, 1), (8, 4096, 7, 40),
+                                         (6, 4096, 9, 33)])
+def test_dense_blocks_on_odd_shapes(log2r, N, B, H):
+    # the dense-block kernels keep several rows resident: row counts that do not fill a group, single rows, more
+    # workgroups than compute units
+    print(f"[blocksize] N={N} r={1 << log2r} B={B} H={H}", flush=True)
+    w = wl.Workload(6, B, H, N, wl.F16, "decay_alpha_squash")
+    inp = wl.generate(w, seed_extra=100 + log2r)
+    u = to_dev(inp.u_store, wl.F16)
+    k, D = torch.from_numpy(inp.k).cuda(), torch.from_numpy(inp.D).cuda()
+    shat = torch.empty((H, 2 * N, 2), device="cuda")
+    lc.longconv_lbfly_spectrum(k, D, shat)
+    y = torch.full_like(u, float("nan"))
+    lc.longconv_blocksize_fwd(u, shat, y, log2r)
+    torch.cuda.synchronize()
+    ref = oracle.longconv_fwd(inp.u, inp.k.astype(np.float64), inp.D.astype(np.float64))
+    _compare({"y": to_f64(y, wl.F16)}, {"y": ref}, TOL[wl.F16], f"block size {1 << log2r} N={N} B={B} H={H}")
+
+
 def test_refused_arguments():
     u = torch.zeros(2, 2, 1024, device="cuda", dtype=torch.float16)
     shat = torch.zeros(2, 2048, 2, device="cuda")
