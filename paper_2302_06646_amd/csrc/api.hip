@@ -212,7 +212,7 @@ static WsLayout carve(int64_t B, int64_t H, int64_t N, const Plan& pl, bool back
     const bool mc = pl.engine == ENGINE_MFMA && (pl.order.wave_lg || pl.order.coop_lg);
     const bool kscr = mc ? (pl.log2R && !pl.fuse_a) : (pl.log2L > VALU_KSPEC_MAX_LOG2);
     w.kscratch = off; if (kscr) off += up256((size_t)H * L * sizeof(float2));
-    w.hscale = off; off += up256((size_t)3 * H * sizeof(float));
+    w.hscale = off; off += up256(head_stats_floats(H, N) * sizeof(float));
     w.ws1 = off; if (pl.log2R) off += up256((size_t)H * npairs * L * cw_bytes(pl));
     w.ws2 = off; if (pl.log2R && backward) off += up256((size_t)H * npairs * L * cw_bytes(pl));
     w.wsA = off; if (pl.log2R && backward) off += up256((size_t)H * L * cw_bytes(pl));

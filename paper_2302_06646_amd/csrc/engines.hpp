@@ -48,7 +48,9 @@ hipError_t outer_fwd(const void* in, const void* in2, void* ws, void* ws2, float
                      const Problem& pr, int log2R, int log2L2, float scale, bool ws_f16,
                      const float2* tw, hipStream_t st, const float* head_max = nullptr);
 // stats[h] = max_n |k[h,n]| (consumers derive the head's power-of-two pre-scale with head_scale_of()),
-// stats[H + h] and stats[2H + h] = the upper and lower bound statistics of spec_exponent(); 3H floats.
+// stats[H + h] and stats[2H + h] = the upper and lower bound statistics of spec_exponent(); the buffer holds
+// head_stats_floats(H, N) floats (the three statistics and the partial results they are summed from).
+size_t head_stats_floats(int64_t H, int64_t N);
 hipError_t head_stats(const float* k, const float* D, float* stats, int64_t H, int64_t N, hipStream_t st);
 int outer_fwd_blocks_per_head(const Problem& pr, int log2L2);
 // Pass C: rows of `out` <- scale * sum_{k1} conj(w_R^(n1*k1) w_L^(n2*k1)) ws[...], n1 < R/2 only

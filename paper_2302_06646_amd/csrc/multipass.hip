@@ -293,23 +293,31 @@ __global__ void __launch_bounds__(OB) rows_absmax_kernel(const uint4* __restrict
     }
 }
 
-// Per head, in one pass over its row and in a fixed order (one workgroup per head): st[h] = max |k_n| (the
-// transform's pre-scale), st[H + h] = |k_0 + D| + sum_{n>0} |k_n| and st[2H + h] = max(|k_0 + D|, max_{n>0} |k_n|)
-// (the two bounds on the largest spectrum bin, see spec_exponent).
-__global__ void __launch_bounds__(OB) head_stats_kernel(const float* __restrict__ k, const float* __restrict__ D,
-                                                        float* __restrict__ st, int64_t H, int64_t N)
+// Per head, in one pass over its row: st[h] = max |k_n| (the transform's pre-scale), st[H + h] = |k_0 + D| +
+// sum_{n>0} |k_n| and st[2H + h] = max(|k_0 + D|, max_{n>0} |k_n|) (the two bounds on the largest spectrum bin, see
+// spec_exponent).  Two steps, both in a fixed order: blocks of 8192 samples write their three partial results
+// behind the statistics ([3H, 3H + 3 H nblk)), then one thread per head combines them block by block.
+constexpr int STAT_BLOCK = 8192;
+__global__ void __launch_bounds__(OB) head_stats_part_kernel(const float* __restrict__ k, const float* __restrict__ D,
+                                                             float* __restrict__ st, int64_t H, int64_t N, int nblk)
 {
     __shared__ float red[3][OB / 64];
-    const int64_t h = blockIdx.x;
-    const float4* kr = reinterpret_cast<const float4*>(k + (size_t)h * N);
+    const int64_t h = blockIdx.y;
+    const int blk = blockIdx.x;
+    const float4* kr = reinterpret_cast<const float4*>(k + (size_t)h * N) + (size_t)blk * (STAT_BLOCK / 4);
+    const int64_t left = N / 4 - (int64_t)blk * (STAT_BLOCK / 4);
     const float Dh = D[h];
     float m = 0.f, a = 0.f, mp = 0.f;
-    for (int64_t i = threadIdx.x; i < N / 4; i += OB) {
-        const float4 v = kr[i];
-        const float x0 = fabsf(v.x + (i == 0 ? Dh : 0.f));
-        m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-        mp = fmaxf(mp, fmaxf(fmaxf(x0, fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-        a += (x0 + fabsf(v.y)) + (fabsf(v.z) + fabsf(v.w));
+#pragma unroll
+    for (int i = 0; i < STAT_BLOCK / 4 / OB; ++i) {
+        const int64_t idx = threadIdx.x + OB * i;
+        if (idx < left) {
+            const float4 v = kr[idx];
+            const float x0 = fabsf(v.x + ((blk == 0 && idx == 0) ? Dh : 0.f));
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+            mp = fmaxf(mp, fmaxf(fmaxf(x0, fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+            a += (x0 + fabsf(v.y)) + (fabsf(v.z) + fabsf(v.w));
+        }
     }
     for (int o = 32; o > 0; o >>= 1) {
         m = fmaxf(m, __shfl_down(m, o, 64));
@@ -321,11 +329,21 @@ __global__ void __launch_bounds__(OB) head_stats_kernel(const float* __restrict_
     if (threadIdx.x == 0) {
         m = red[0][0]; a = red[1][0]; mp = red[2][0];
         for (int w = 1; w < OB / 64; ++w) { m = fmaxf(m, red[0][w]); a += red[1][w]; mp = fmaxf(mp, red[2][w]); }
-        if (!(m == m)) m = __uint_as_float(0x7f800000u);   // a NaN in the head: treat as unscalable
-        st[h] = m;
-        st[H + h] = a;
-        st[2 * H + h] = mp;
+        float* part = st + 3 * H + ((size_t)h * nblk + blk) * 3;
+        part[0] = m; part[1] = a; part[2] = mp;
     }
+}
+__global__ void head_stats_sum_kernel(float* __restrict__ st, int64_t H, int nblk)
+{
+    const int64_t h = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (h >= H) return;
+    const float* part = st + 3 * H + (size_t)h * nblk * 3;
+    float m = 0.f, a = 0.f, mp = 0.f;
+    for (int b = 0; b < nblk; ++b) { m = fmaxf(m, part[3 * b]); a += part[3 * b + 1]; mp = fmaxf(mp, part[3 * b + 2]); }
+    if (!(m == m)) m = __uint_as_float(0x7f800000u);   // a NaN in the head: treat as unscalable
+    st[h] = m;
+    st[H + h] = a;
+    st[2 * H + h] = mp;
 }
 
 __global__ void reduce_dD_kernel(const float* __restrict__ part, float* __restrict__ dD, int64_t H, int nblk)
@@ -493,9 +511,12 @@ hipError_t outer_inv(const void* ws, void* out, const Problem& pr, int log2R, in
 #undef GO
 }
 
+size_t head_stats_floats(int64_t H, int64_t N) { return (size_t)3 * H * (1 + (size_t)((N + STAT_BLOCK - 1) / STAT_BLOCK)); }
 hipError_t head_stats(const float* k, const float* D, float* stats, int64_t H, int64_t N, hipStream_t st)
 {
-    hipLaunchKernelGGL(head_stats_kernel, dim3((unsigned)H), dim3(OB), 0, st, k, D, stats, H, N);
+    const int nblk = (int)((N + STAT_BLOCK - 1) / STAT_BLOCK);
+    hipLaunchKernelGGL(head_stats_part_kernel, dim3((unsigned)nblk, (unsigned)H), dim3(OB), 0, st, k, D, stats, H, N, nblk);
+    hipLaunchKernelGGL(head_stats_sum_kernel, dim3((unsigned)((H + 255) / 256)), dim3(256), 0, st, stats, H, nblk);
     return hipGetLastError();
 }
 
