@@ -99,3 +99,31 @@ def test_rows_of_a_pair_a_few_times_apart(N):
     us[:, 1] = 10.0 ** rng.uniform(-1.2, 1.2, size=B); ds[:, 1] = 10.0 ** rng.uniform(-1.2, 1.2, size=B)
     us[:, 2] = 10.0 ** rng.uniform(-6, 6, size=B); ds[:, 2] = 10.0 ** rng.uniform(-9, 3, size=B)
     check_full(scaled_inputs(N, B, H, us, ds, seed=7), label=f"rows a few times apart, N={N}")
+
+
+def _random_magnitude_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    lengths = [256, 512, 1024, 2048, 4096, 8192, 16384, 32768, 65536]
+    p = np.array([4, 4, 4, 4, 3, 3, 2, 1, 1], dtype=float)
+    cases = []
+    for _ in range(n):
+        N = int(rng.choice(lengths, p=p / p.sum()))
+        B = int(rng.integers(1, 12)) if N <= 4096 else int(rng.integers(1, 5))
+        H = int(rng.integers(1, 7)) if N <= 16384 else int(rng.integers(1, 3))
+        cases.append((N, B, H, int(rng.integers(0, 10000)), bool(rng.integers(0, 2))))
+    return cases
+
+
+@pytest.mark.parametrize("N,B,H,seed,kernels", _random_magnitude_cases(48, 20230213))
+def test_random_magnitudes(N, B, H, seed, kernels):
+    # rows at 10^-6 ... 10^6 (u) and 10^-9 ... 10^3 (dy), drawn row by row up to N = 16384 and head by head beyond (the
+    # multi-pass plans scale per head), kernels and skip terms at 2^-24 ... 2^20 in half of the cases: y, du and dk to
+    # the bound of data of order one, every row and head.  dD is a plain fp32 dot product over all rows of a head:
+    # where rows of wildly different size meet in one sum its relative error reaches a few 1e-5 (1e-7 otherwise).
+    rng = np.random.default_rng(seed)
+    shape = (B, H) if N <= 16384 else (1, H)
+    us = np.broadcast_to(10.0 ** rng.uniform(-6, 6, size=shape), (B, H)).copy()
+    ds = np.broadcast_to(10.0 ** rng.uniform(-9, 3, size=shape), (B, H)).copy()
+    ks = 2.0 ** rng.integers(-24, 20, size=H) if kernels else None
+    Ds = 2.0 ** rng.integers(-24, 20, size=H) if kernels else None
+    check_full(scaled_inputs(N, B, H, us, ds, k_scale=ks, D_scale=Ds, seed=seed), label=f"random magnitudes, N={N}", dd_tol=1e-4)
